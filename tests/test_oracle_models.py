@@ -1,0 +1,148 @@
+"""Whole-model pins: structural facts of the five architectures, the graph
+plumbing of the oracle's model runner (against a library forward pass in fp64
+built from the same description), and the cross-mode / cross-precision bounds.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from workloads import gen, zoo
+
+# (family, nodes, conv, dw, pool, gap, fc, depth, params, MACs/image): architecture tables of the
+# cited networks with BatchNorm's two parameters per channel replaced by one folded bias.
+STRUCT = [
+    ("tiny", 6, 2, 0, 1, 1, 1, 6, 5418, 1622336),
+    ("resnet18", 23, 20, 0, 1, 1, 1, 20, 11689512 - 4800, 1814073344),
+    ("resnet50", 56, 53, 0, 1, 1, 1, 52, 25557032 - 26560, 4089184256),
+    ("mobilenetv2", 54, 35, 17, 0, 1, 1, 54, 3504872 - 17056, 300774272),
+    ("vgg16", 21, 13, 0, 5, 0, 3, 21, 138357544, 15470264320),
+]
+
+
+@pytest.mark.parametrize("row", STRUCT)
+def test_structure(row):
+    fam, nodes, nconv, ndw, npool, ngap, nfc, depth, params, macs = row
+    m = zoo.FAMILIES[fam]()
+    ops = [L.op for L in m.layers]
+    assert len(ops) == nodes
+    assert (ops.count("conv"), ops.count("dwconv"), ops.count("maxpool"), ops.count("gap"), ops.count("fc")) == \
+        (nconv, ndw, npool, ngap, nfc)
+    assert max(m.levels()) == depth
+    assert m.n_params() == params
+    assert m.macs() == macs
+    assert m.layers[m.output].cout == (10 if fam == "tiny" else 1000)
+
+
+def test_stage_shapes():
+    r = zoo.resnet50()
+    sides = [L.out_h for L in r.layers if L.op == "conv"]
+    assert sides[0] == 112 and set(sides) == {112, 56, 28, 14, 7}
+    assert r.layers[1].op == "maxpool" and r.layers[1].out_h == 56
+    v = zoo.vgg16()
+    assert [L.out_h for L in v.layers if L.op == "maxpool"] == [112, 56, 28, 14, 7]
+    assert [L.cin for L in v.layers if L.op == "fc"] == [25088, 4096, 4096]
+    mb = zoo.mobilenetv2()
+    dw = [L for L in mb.layers if L.op == "dwconv"]
+    assert [L.cout for L in dw][:4] == [32, 96, 144, 144] and dw[-1].cout == 960 and dw[-1].out_h == 7
+    assert sum(1 for L in mb.layers if L.residual >= 0) == 10
+    assert sum(1 for L in zoo.resnet50().layers if L.residual >= 0) == 16
+
+
+def _torch_forward(model, blob, x, dtype=torch.float64):
+    """Library forward pass in fp64 from the same description (no oracle code)."""
+    vals = []
+    xt = torch.from_numpy(x).to(dtype)
+    for L in model.layers:
+        inp = xt if L.input == -1 else vals[L.input]
+        if L.op in ("conv", "dwconv", "fc"):
+            nw = {"conv": L.cout * L.cin * L.k * L.k, "dwconv": L.cout * L.k * L.k, "fc": L.cout * L.cin}[L.op]
+            if model.dtype == "f32":
+                w = blob[L.w_off:L.w_off + 4 * nw].view(np.float32)
+            else:
+                w = gen.bf16_to_f32(blob[L.w_off:L.w_off + 2 * nw].view(np.uint16))
+            w = torch.from_numpy(np.array(w)).to(dtype)
+            b = torch.from_numpy(np.array(blob[L.b_off:L.b_off + 4 * L.cout].view(np.float32))).to(dtype)
+        if L.op == "conv":
+            y = F.conv2d(inp, w.reshape(L.cout, L.cin, L.k, L.k), b, stride=L.stride, padding=L.pad)
+        elif L.op == "dwconv":
+            y = F.conv2d(inp, w.reshape(L.cout, 1, L.k, L.k), b, stride=L.stride, padding=L.pad, groups=L.cout)
+        elif L.op == "maxpool":
+            y = F.max_pool2d(inp, L.k, L.stride, L.pad)
+        elif L.op == "gap":
+            y = inp.mean(dim=(2, 3), keepdim=True)
+        elif L.op == "fc":
+            y = F.linear(inp.reshape(inp.shape[0], -1), w.reshape(L.cout, L.cin), b).reshape(-1, L.cout, 1, 1)
+        elif L.op == "softmax":
+            y = torch.softmax(inp.reshape(inp.shape[0], -1), dim=1).reshape(inp.shape)
+        if L.residual >= 0:
+            y = y + vals[L.residual]
+        if L.act == "relu":
+            y = torch.relu(y)
+        elif L.act == "relu6":
+            y = torch.clamp(y, 0.0, 6.0)
+        vals.append(y)
+    return vals[-1].reshape(x.shape[0], -1).numpy()
+
+
+def _rel(a, b):
+    return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
+
+
+@pytest.mark.parametrize("fam,hw", [("tiny", 32), ("resnet18", 64), ("resnet50", 64), ("mobilenetv2", 64), ("vgg16", 32)])
+def test_model_runner_vs_library_forward(fam, hw):
+    m = zoo.tiny_cnn() if fam == "tiny" else zoo.FAMILIES[fam](hw=hw)
+    blob = gen.make_blob(m, 1000 + hw)
+    x = gen.make_input(7, 2, 3, hw, hw, "uniform" if fam == "tiny" else "normal", m.dtype)
+    ref = _torch_forward(m, blob, x)
+    y = oracle.run_model(m, blob, x, round_storage=False)
+    assert y.shape == ref.shape
+    assert _rel(y, ref) < 2e-5
+    # the double-accumulation build bounds the oracle's own rounding
+    y64 = oracle.run_model(m, blob, x, round_storage=False, f64=True)
+    assert _rel(y64, ref) < 2e-6
+    assert _rel(y, y64.astype(np.float64)) < 1e-5
+    # batch independence: image 1 alone gives image 1's row, bit for bit
+    y1 = oracle.run_model(m, blob, x[1:2], round_storage=False)
+    assert np.array_equal(y1[0], y[1])
+
+
+def test_residual_is_added_before_activation():
+    m = zoo.Model("r", "f32", 2, 3, 3)
+    a = m.add(zoo.CONV, -1, cin=2, cout=2, k=1, stride=1, pad=0, act=zoo.NONE)
+    m.add(zoo.CONV, a, cin=2, cout=2, k=1, stride=1, pad=0, act=zoo.RELU, residual=a)
+    m.shapes()
+    size = gen.layout_blob(m)
+    blob = np.zeros(size, np.uint8)
+    eye = np.eye(2, dtype=np.float32).reshape(-1)
+    for L in m.layers:
+        blob[L.w_off:L.w_off + 16] = eye.view(np.uint8)
+    x = np.array([-3.0, 2.0] * 9, dtype=np.float32).reshape(1, 3, 3, 2).transpose(0, 3, 1, 2).copy()
+    y = oracle.run_model(m, blob, x).reshape(1, 2, 3, 3)
+    assert np.all(y[0, 0] == 0.0)  # relu(-3 + -3) = 0, not -3 + relu(-3)
+    assert np.all(y[0, 1] == 4.0)
+
+
+def test_storage_rounding_mode_scale():
+    """Mode S differs from mode F by roughly sqrt(#roundings) * 2^-9 and every stored value is bf16."""
+    m = zoo.resnet18(hw=64)
+    blob = gen.make_blob(m, 1000)
+    x = gen.make_input(7, 1, 3, 64, 64, "normal", "bf16")
+    yf = oracle.run_model(m, blob, x, round_storage=False)
+    ys = oracle.run_model(m, blob, x, round_storage=True)
+    d = _rel(ys, yf.astype(np.float64))
+    assert 1e-4 < d < 1e-2
+    mid = oracle.run_model(m, blob, x, round_storage=True, node=5)
+    assert np.array_equal(mid, oracle.round_bf16(mid))  # an interior node is stored as bf16
+    assert not np.array_equal(ys, oracle.round_bf16(ys))  # logits stay fp32
+
+
+def test_softmax_output_keeps_fp32_logits():
+    m = zoo.tiny_cnn("bf16")
+    blob = gen.make_blob(m, 5, bias_std=0.0)
+    x = gen.make_input(7, 1, 3, 32, 32, "uniform", "bf16")
+    logits = oracle.run_model(m, blob, x, round_storage=True, node=4)
+    p = oracle.run_model(m, blob, x, round_storage=True)
+    assert np.allclose(p, oracle.softmax(logits), atol=1e-7)
+    assert abs(p.sum() - 1.0) < 1e-6

@@ -1,0 +1,225 @@
+"""Layer-graph descriptions of the member models (data only, no arithmetic).
+
+A model is a list of nodes in topological order.  Each node names its operator,
+the node that feeds it (-1 = the model input), an optional residual node that
+is added before the activation, and the operator's integer hyper-parameters.
+This is the per-model graph (nodes u_i, edges {u_i,u_j}, activations phi_i)
+that the paper's Algorithm 1 unions into one DAG.
+
+The five families are the ones the benchmark configurations name: a tiny CNN,
+ResNet-18 / ResNet-50 (BatchNorm folded into the preceding convolution, so each
+convolution carries one bias per output channel), MobileNetV2 (width 1.0) and
+VGG-16.  Shapes follow the published architecture tables; ResNet-50 carries the
+bottleneck stride on its 3x3 convolution.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List
+
+# operator / activation names (strings on purpose: each executor maps them to
+# its own enum, so the two sides share no numeric constants)
+CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX = "conv", "dwconv", "maxpool", "gap", "fc", "softmax"
+NONE, RELU, RELU6 = "none", "relu", "relu6"
+NO_RESIDUAL = -2
+MODEL_INPUT = -1
+
+
+@dataclass
+class Layer:
+    op: str
+    input: int
+    cin: int = 0
+    cout: int = 0
+    k: int = 1
+    stride: int = 1
+    pad: int = 0
+    act: str = NONE
+    residual: int = NO_RESIDUAL
+    # filled by shapes(): logical input / output spatial sizes
+    in_h: int = 0
+    in_w: int = 0
+    out_h: int = 0
+    out_w: int = 0
+    # filled by gen.make_blob(): byte offsets into the canonical weight blob
+    w_off: int = 0
+    b_off: int = 0
+
+
+@dataclass
+class Model:
+    name: str
+    dtype: str  # "f32" | "bf16"
+    in_c: int
+    in_h: int
+    in_w: int
+    layers: List[Layer] = field(default_factory=list)
+
+    @property
+    def output(self) -> int:
+        return len(self.layers) - 1
+
+    def add(self, op, inp, **kw) -> int:
+        self.layers.append(Layer(op=op, input=inp, **kw))
+        return len(self.layers) - 1
+
+    # -- derived facts used by structural pins ------------------------------
+    def shapes(self) -> "Model":
+        """Fill in per-node logical shapes (floor output size everywhere)."""
+        dims = {}
+        for i, L in enumerate(self.layers):
+            c, h, w = (self.in_c, self.in_h, self.in_w) if L.input == MODEL_INPUT else dims[L.input]
+            L.in_h, L.in_w = h, w
+            if L.op in (CONV, DWCONV):
+                ho = (h + 2 * L.pad - L.k) // L.stride + 1
+                wo = (w + 2 * L.pad - L.k) // L.stride + 1
+                dims[i] = (L.cout, ho, wo)
+            elif L.op == MAXPOOL:
+                ho = (h + 2 * L.pad - L.k) // L.stride + 1
+                wo = (w + 2 * L.pad - L.k) // L.stride + 1
+                L.cin = L.cout = c
+                dims[i] = (c, ho, wo)
+            elif L.op == GAP:
+                L.cin = L.cout = c
+                dims[i] = (c, 1, 1)
+            elif L.op == FC:
+                assert L.cin == c * h * w, (self.name, i, L.cin, c, h, w)
+                dims[i] = (L.cout, 1, 1)
+            elif L.op == SOFTMAX:
+                L.cin = L.cout = c
+                dims[i] = (c, 1, 1)
+            else:
+                raise ValueError(L.op)
+            L.out_h, L.out_w = dims[i][1], dims[i][2]
+        return self
+
+    def n_params(self) -> int:
+        n = 0
+        for L in self.layers:
+            if L.op == CONV:
+                n += L.cout * L.cin * L.k * L.k + L.cout
+            elif L.op == DWCONV:
+                n += L.cout * L.k * L.k + L.cout
+            elif L.op == FC:
+                n += L.cout * L.cin + L.cout
+        return n
+
+    def macs(self) -> int:
+        """Multiply-accumulates per image of conv / depthwise / FC nodes."""
+        n = 0
+        for L in self.layers:
+            if L.op == CONV:
+                n += L.out_h * L.out_w * L.cout * L.cin * L.k * L.k
+            elif L.op == DWCONV:
+                n += L.out_h * L.out_w * L.cout * L.k * L.k
+            elif L.op == FC:
+                n += L.cout * L.cin
+        return n
+
+    def levels(self) -> List[int]:
+        """Depth of every node: 1 + max depth of its inputs (model input = 0)."""
+        lv = []
+        for L in self.layers:
+            d = 0 if L.input == MODEL_INPUT else lv[L.input]
+            if L.residual >= 0:
+                d = max(d, lv[L.residual])
+            lv.append(d + 1)
+        return lv
+
+
+def tiny_cnn(dtype: str = "f32", softmax: bool = True) -> Model:
+    m = Model("tiny", dtype, 3, 32, 32)
+    a = m.add(CONV, MODEL_INPUT, cin=3, cout=16, k=3, stride=1, pad=1, act=RELU)
+    a = m.add(MAXPOOL, a, k=2, stride=2, pad=0)
+    a = m.add(CONV, a, cin=16, cout=32, k=3, stride=1, pad=1, act=RELU)
+    a = m.add(GAP, a)
+    a = m.add(FC, a, cin=32, cout=10)
+    if softmax:
+        m.add(SOFTMAX, a)
+    return m.shapes()
+
+
+def _resnet_stem(m: Model) -> int:
+    a = m.add(CONV, MODEL_INPUT, cin=3, cout=64, k=7, stride=2, pad=3, act=RELU)
+    return m.add(MAXPOOL, a, k=3, stride=2, pad=1)
+
+
+def resnet18(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    m = Model("resnet18", dtype, 3, hw, hw)
+    x = _resnet_stem(m)
+    cin = 64
+    for stage, width in enumerate((64, 128, 256, 512)):
+        for blk in range(2):
+            stride = 2 if (stage > 0 and blk == 0) else 1
+            a = m.add(CONV, x, cin=cin, cout=width, k=3, stride=stride, pad=1, act=RELU)
+            if stride != 1 or cin != width:
+                skip = m.add(CONV, x, cin=cin, cout=width, k=1, stride=stride, pad=0, act=NONE)
+            else:
+                skip = x
+            x = m.add(CONV, a, cin=width, cout=width, k=3, stride=1, pad=1, act=RELU, residual=skip)
+            cin = width
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=512, cout=classes)
+    return m.shapes()
+
+
+def resnet50(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    m = Model("resnet50", dtype, 3, hw, hw)
+    x = _resnet_stem(m)
+    cin = 64
+    for stage, (width, reps) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3))):
+        for blk in range(reps):
+            stride = 2 if (stage > 0 and blk == 0) else 1
+            a = m.add(CONV, x, cin=cin, cout=width, k=1, stride=1, pad=0, act=RELU)
+            if blk == 0:
+                skip = m.add(CONV, x, cin=cin, cout=4 * width, k=1, stride=stride, pad=0, act=NONE)
+            else:
+                skip = x
+            a = m.add(CONV, a, cin=width, cout=width, k=3, stride=stride, pad=1, act=RELU)
+            x = m.add(CONV, a, cin=width, cout=4 * width, k=1, stride=1, pad=0, act=RELU, residual=skip)
+            cin = 4 * width
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=2048, cout=classes)
+    return m.shapes()
+
+
+def mobilenetv2(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    m = Model("mobilenetv2", dtype, 3, hw, hw)
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=32, k=3, stride=2, pad=1, act=RELU6)
+    cin = 32
+    for t, c, n, s in ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2),
+                       (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)):
+        for rep in range(n):
+            stride = s if rep == 0 else 1
+            hidden = cin * t
+            a = x
+            if t != 1:
+                a = m.add(CONV, a, cin=cin, cout=hidden, k=1, stride=1, pad=0, act=RELU6)
+            a = m.add(DWCONV, a, cin=hidden, cout=hidden, k=3, stride=stride, pad=1, act=RELU6)
+            skip = x if (stride == 1 and cin == c) else NO_RESIDUAL
+            x = m.add(CONV, a, cin=hidden, cout=c, k=1, stride=1, pad=0, act=NONE, residual=skip)
+            cin = c
+    x = m.add(CONV, x, cin=320, cout=1280, k=1, stride=1, pad=0, act=RELU6)
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=1280, cout=classes)
+    return m.shapes()
+
+
+def vgg16(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    m = Model("vgg16", dtype, 3, hw, hw)
+    x, cin, side = MODEL_INPUT, 3, hw
+    for v in (64, 64, "M", 128, 128, "M", 256, 256, 256, "M", 512, 512, 512, "M", 512, 512, 512, "M"):
+        if v == "M":
+            x = m.add(MAXPOOL, x, k=2, stride=2, pad=0)
+            side //= 2
+        else:
+            x = m.add(CONV, x, cin=cin, cout=v, k=3, stride=1, pad=1, act=RELU)
+            cin = v
+    x = m.add(FC, x, cin=512 * side * side, cout=4096, act=RELU)
+    x = m.add(FC, x, cin=4096, cout=4096, act=RELU)
+    m.add(FC, x, cin=4096, cout=classes)
+    return m.shapes()
+
+
+FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
+            "mobilenetv2": mobilenetv2, "vgg16": vgg16}
