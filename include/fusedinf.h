@@ -1,0 +1,195 @@
+/* fusedinf.h -- C ABI of the fused multi-model CNN inference library (gfx950).
+ *
+ * The library implements the hot path of FusedInf (Section IV "System Design",
+ * Algorithm 1): several independent CNN inference models are compiled into ONE
+ * DAG -- the disjoint union of the members' layer graphs, no edge between members
+ * -- which is then loaded, executed and swapped as a unit.  "Efficient memory
+ * allocation" and "Fewer memory calls" (Section IV-B) become: one device
+ * allocation per load, holding one contiguous weight arena for all members that
+ * is filled by one pinned-host-to-device copy.  The inference loop of Algorithm 1
+ * (every node evaluates phi(sum_j u_j x_j) on tensors of its own model) becomes
+ * one launch schedule in which nodes of different members at the same depth run
+ * as grouped kernels.  Properties C1 / C4 (Section III-A, Section IV-C) are kept:
+ * no operator is merged across members, each member's output is bit-identical to
+ * the member run alone, and no member reads another member's tensors.
+ *
+ * Conventions
+ *  - Every call returns fi_status; on error out-parameters are untouched and
+ *    fi_last_error() holds a thread-local message.  No exception crosses the ABI.
+ *  - "host" / "device" is stated for every pointer.  Specs and host weight blobs
+ *    are BORROWED: the caller keeps them alive until fi_destroy().
+ *  - State machine:  BUILT --fi_load--> LOADED --fi_run*--> LOADED --fi_unload-->
+ *    BUILT --fi_destroy--> gone.  Any other transition returns FI_ESTATE.
+ *  - All members of one DAG share the weight dtype and the input shape, and read
+ *    the same input batch (Algorithm 1's per-model inputs x^m collapse to one
+ *    shared x; per-member inputs are not part of this ABI yet).
+ */
+#ifndef FUSEDINF_H
+#define FUSEDINF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fi_dag fi_dag; /* opaque, owned by the library, one per fi_build_dag */
+
+typedef enum {
+  FI_OK = 0,
+  FI_EINVAL = 1,        /* malformed spec / argument (cycle, dangling index, shape mismatch) */
+  FI_EUNSUPPORTED = 2,  /* well-formed but outside what the kernels cover */
+  FI_ESTATE = 3,        /* call not allowed in the handle's current state */
+  FI_ENOMEM_HOST = 4,   /* host / pinned allocation failed */
+  FI_ENOMEM_DEVICE = 5, /* device allocation failed; handle stays BUILT */
+  FI_EBUDGET = 6,       /* DAG needs more device bytes than fi_build_opts.max_device_bytes */
+  FI_EHIP = 7           /* a HIP runtime call failed */
+} fi_status;
+
+typedef enum { FI_F32 = 0, FI_BF16 = 1 } fi_dtype;
+typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5 } fi_op;
+typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
+
+#define FI_INPUT (-1)       /* fi_layer_spec.input: the model's input tensor */
+#define FI_NO_RESIDUAL (-2) /* fi_layer_spec.residual: nothing is added */
+#define FI_MAX_GROUP 16     /* most problems one grouped launch carries */
+
+/* One node u_i of a member's layer graph (Algorithm 1: node, its in-edge, its
+ * activation phi_i).  Nodes are listed in topological order.
+ *   conv2d / depthwise: y = act(conv(x, w) + b [+ residual]); cross-correlation,
+ *     zero padding, square kernel (kh == kw), floor output size.  The residual
+ *     is added BEFORE the activation.  Depthwise: cin == cout, one filter/channel.
+ *   maxpool2d: max over in-range taps (padding acts as -inf), floor output size.
+ *   global_avgpool: mean over H*W.   softmax: over the channel axis of a 1x1 tensor.
+ *   fc: y = act(x W^T + b); cin = C*H*W of its input, flattened in (c,h,w) order.
+ * w_off / b_off: byte offsets into the member's CANONICAL blob: weights
+ * [cout][cin/groups][kh][kw] (fc: [cout][cin]) in the model dtype, bias [cout] fp32.
+ * cin/cout of pooling, global_avgpool and softmax nodes are ignored (derived). */
+typedef struct {
+  int32_t op;       /* fi_op */
+  int32_t input;    /* node index in this model, or FI_INPUT */
+  int32_t residual; /* node index, or FI_NO_RESIDUAL */
+  int32_t cin, cout, kh, kw, stride, pad;
+  int32_t act;      /* fi_act */
+  uint64_t w_off, b_off;
+} fi_layer_spec;
+
+/* One member model m.  `weights` (host) is either the canonical blob described
+ * above (weights_packed == 0; the library converts it while building) or a blob
+ * already in device layout written by fi_model_pack (weights_packed == 1; the
+ * repository-time form that makes loading a pure copy).
+ * act_dtype: storage precision of this member's intermediate tensors.  FI_BF16
+ * (bf16 weights only) rounds every stored activation to bf16 once per node;
+ * FI_F32 keeps activations in fp32 (mandatory for an FI_F32 model; for a bf16
+ * model it buys fp32-grade accuracy at twice the activation traffic). */
+typedef struct {
+  const char* name;             /* host, borrowed, may be NULL */
+  int32_t dtype;                /* fi_dtype of the weights */
+  int32_t act_dtype;            /* fi_dtype of stored activations */
+  int32_t in_c, in_h, in_w;     /* logical input [batch, in_c, in_h, in_w] */
+  int32_t n_layers;
+  const fi_layer_spec* layers;  /* host, borrowed */
+  int32_t output_node;          /* node whose value is the member's prediction */
+  int32_t weights_packed;       /* 0 canonical, 1 device layout (fi_model_pack) */
+  const void* weights;          /* host, borrowed until fi_destroy */
+  uint64_t weight_bytes;
+} fi_model_spec;
+
+typedef enum {
+  FI_LOAD_ONE_COPY = 0,  /* gather members into one pinned image at build; fi_load = 1 H2D copy */
+  FI_LOAD_PER_MODEL = 1  /* no host gather; fi_load copies each member's packed blob (+1 for the schedule) */
+} fi_load_mode;
+
+/* Allocator callbacks let the caller's memory pool (e.g. a tensor library's
+ * caching allocator) back the library's memory.  NULL = hipMalloc / hipHostMalloc.
+ * A callback returning NULL is reported as FI_ENOMEM_DEVICE / FI_ENOMEM_HOST. */
+typedef struct {
+  int32_t max_batch;         /* largest batch fi_run will be given (>= 1) */
+  int32_t group_levels;      /* 1: same-depth nodes of different members share launches; 0: one launch per node */
+  int32_t load_mode;         /* fi_load_mode */
+  int32_t reserved;
+  uint64_t max_device_bytes; /* 0 = unlimited; else fi_build_dag fails with FI_EBUDGET beyond it */
+  void* (*dev_alloc)(size_t bytes, void* user);
+  void (*dev_free)(void* ptr, void* user);
+  void* (*pin_alloc)(size_t bytes, void* user);
+  void (*pin_free)(void* ptr, void* user);
+  void* user;
+} fi_build_opts;
+
+typedef struct {
+  uint64_t arena_bytes;      /* weight arena: schedule tables + every member's packed weights */
+  uint64_t act_bytes;        /* activation arena at max_batch (liveness-planned) */
+  uint64_t workspace_bytes;  /* kernel scratch */
+  uint64_t device_bytes;     /* the one allocation fi_load makes = sum of the three (aligned) */
+  uint64_t macs_per_image;   /* multiply-accumulates of conv/depthwise/fc nodes, all members */
+  int32_t n_models, n_nodes, n_levels, n_launches;
+  int32_t n_device_allocs;   /* device allocations per fi_load (1) */
+  int32_t n_h2d_copies;      /* host-to-device copies per fi_load (1 in FI_LOAD_ONE_COPY) */
+  int32_t state;             /* 0 BUILT, 1 LOADED */
+  int32_t reserved;
+} fi_dag_info;
+
+/* Introspection of the compiled DAG (tests, reports). */
+typedef struct {
+  int32_t model, index;      /* member and node index inside the member */
+  int32_t op, level, launch; /* depth level (1-based) and the launch that executes it */
+  int32_t out_c, out_h, out_w, out_cp; /* logical shape and padded channel stride of the output */
+  int32_t out_dtype;         /* fi_dtype of the stored output */
+  int32_t is_output;         /* 1: written to the caller's output buffer, not the arena */
+  int32_t first_level, last_level; /* live range of the output tensor in levels */
+  uint64_t out_off, out_bytes;     /* placement in the activation arena (at max_batch) */
+  uint64_t w_off, b_off;           /* placement in the weight arena */
+  uint64_t macs;                   /* per image */
+} fi_node_info;
+
+typedef struct {
+  int32_t level, kind, n_problems, first_node; /* kind: internal kernel family id */
+  uint64_t macs_per_image;   /* dense work of the launch */
+  uint64_t bytes_per_image;  /* compulsory activation bytes (in + out + residual), per image */
+  uint64_t weight_bytes;     /* weight + bias bytes read once per launch */
+  char name[32];             /* kernel family name, e.g. "conv_mfma_128x128" */
+} fi_launch_info;
+
+/* Size / content of a member's device-layout blob (repository time, host only). */
+fi_status fi_model_packed_size(const fi_model_spec* model, uint64_t* bytes);
+/* dst (host, caller-owned, ideally pinned) receives fi_model_packed_size bytes. */
+fi_status fi_model_pack(const fi_model_spec* model, void* dst, uint64_t dst_bytes);
+
+/* Algorithm 1, DAG compilation: union the members' graphs, assign depth levels,
+ * form grouped launches, lay out the weight arena and the activation arena.  Host
+ * only: touches no device.  models: host array of n (1..) specs. */
+fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, fi_dag** out);
+fi_status fi_query(const fi_dag* dag, fi_dag_info* info);
+fi_status fi_node(const fi_dag* dag, int32_t i, fi_node_info* info);     /* i in [0, n_nodes) */
+fi_status fi_launch(const fi_dag* dag, int32_t i, fi_launch_info* info); /* i in [0, n_launches) */
+
+/* Load: one device allocation, one pinned-to-device copy of the weight arena
+ * (asynchronous on hip_stream; hip_stream is a hipStream_t, NULL = default stream). */
+fi_status fi_load(fi_dag* dag, void* hip_stream);
+
+/* Algorithm 1, DAG inference: one pass of the launch schedule, asynchronous on
+ * hip_stream.  d_input: device, [batch, in_h, in_w, in_c] (NHWC) in the DAG's
+ * weight dtype (fp32, or bf16 bit patterns), read-only, shared by all members.
+ * d_outputs: HOST array of n_models DEVICE pointers; member m receives its output
+ * node's value as fp32 [batch, out_h, out_w, out_c] (unpadded NHWC), i.e.
+ * [batch, classes_m] logits for a classifier, or probabilities if the output
+ * node is a softmax.  1 <= batch <= max_batch.  Allocates nothing. */
+fi_status fi_run(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream);
+
+/* Same pass with a HIP event between launches; ms[i] (host, n_launches floats)
+ * receives launch i's elapsed milliseconds.  Synchronises the stream. */
+fi_status fi_profile(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream,
+                     float* ms, int32_t n_ms);
+
+/* Synchronise, release the device allocation; the handle returns to BUILT. */
+fi_status fi_unload(fi_dag* dag);
+void fi_destroy(fi_dag* dag); /* unloads if needed; NULL is allowed */
+
+const char* fi_last_error(void); /* thread-local, valid until the next call on this thread */
+const char* fi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FUSEDINF_H */

@@ -1,0 +1,320 @@
+"""ctypes binding of include/fusedinf.h: argument marshalling only.
+
+The fi_* functions below take and return exactly what the C entry points do.
+`Dag` is a small convenience owner (keeps the borrowed spec memory alive, turns
+a non-zero fi_status into an exception carrying fi_last_error()).  PyTorch is
+used for device memory and streams only: `torch_allocators()` hands the
+library torch-backed dev_alloc / pin_alloc callbacks.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+from . import build as _build
+
+FI_OK, FI_EINVAL, FI_EUNSUPPORTED, FI_ESTATE, FI_ENOMEM_HOST, FI_ENOMEM_DEVICE, FI_EBUDGET, FI_EHIP = range(8)
+FI_F32, FI_BF16 = 0, 1
+FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX = range(6)
+FI_ACT_NONE, FI_ACT_RELU, FI_ACT_RELU6 = range(3)
+FI_INPUT, FI_NO_RESIDUAL = -1, -2
+FI_LOAD_ONE_COPY, FI_LOAD_PER_MODEL = 0, 1
+FI_MAX_GROUP = 16
+STATUS_NAMES = ["FI_OK", "FI_EINVAL", "FI_EUNSUPPORTED", "FI_ESTATE", "FI_ENOMEM_HOST", "FI_ENOMEM_DEVICE",
+                "FI_EBUDGET", "FI_EHIP"]
+
+
+class fi_layer_spec(C.Structure):
+    _fields_ = [("op", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32), ("cin", C.c_int32),
+                ("cout", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32),
+                ("pad", C.c_int32), ("act", C.c_int32), ("w_off", C.c_uint64), ("b_off", C.c_uint64)]
+
+
+class fi_model_spec(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("dtype", C.c_int32), ("act_dtype", C.c_int32), ("in_c", C.c_int32),
+                ("in_h", C.c_int32), ("in_w", C.c_int32), ("n_layers", C.c_int32),
+                ("layers", C.POINTER(fi_layer_spec)), ("output_node", C.c_int32), ("weights_packed", C.c_int32),
+                ("weights", C.c_void_p), ("weight_bytes", C.c_uint64)]
+
+
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
+class fi_build_opts(C.Structure):
+    _fields_ = [("max_batch", C.c_int32), ("group_levels", C.c_int32), ("load_mode", C.c_int32),
+                ("reserved", C.c_int32), ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
+                ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p)]
+
+
+class fi_dag_info(C.Structure):
+    _fields_ = [("arena_bytes", C.c_uint64), ("act_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64),
+                ("device_bytes", C.c_uint64), ("macs_per_image", C.c_uint64), ("n_models", C.c_int32),
+                ("n_nodes", C.c_int32), ("n_levels", C.c_int32), ("n_launches", C.c_int32),
+                ("n_device_allocs", C.c_int32), ("n_h2d_copies", C.c_int32), ("state", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class fi_node_info(C.Structure):
+    _fields_ = [("model", C.c_int32), ("index", C.c_int32), ("op", C.c_int32), ("level", C.c_int32),
+                ("launch", C.c_int32), ("out_c", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32),
+                ("out_cp", C.c_int32), ("out_dtype", C.c_int32), ("is_output", C.c_int32),
+                ("first_level", C.c_int32), ("last_level", C.c_int32), ("out_off", C.c_uint64),
+                ("out_bytes", C.c_uint64), ("w_off", C.c_uint64), ("b_off", C.c_uint64), ("macs", C.c_uint64)]
+
+
+class fi_launch_info(C.Structure):
+    _fields_ = [("level", C.c_int32), ("kind", C.c_int32), ("n_problems", C.c_int32), ("first_node", C.c_int32),
+                ("macs_per_image", C.c_uint64), ("bytes_per_image", C.c_uint64), ("weight_bytes", C.c_uint64),
+                ("name", C.c_char * 32)]
+
+
+LIB_PATH = _build.OUT
+EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_query", "fi_node", "fi_launch", "fi_load",
+           "fi_run", "fi_profile", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
+_lib = None
+
+
+def lib():
+    """Loads the built library; builds it first only when no build exists.  Raises if it cannot be loaded."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            _build.build()
+        L = C.CDLL(LIB_PATH)
+        vp, i32, u64 = C.c_void_p, C.c_int32, C.c_uint64
+        L.fi_model_packed_size.argtypes = [C.POINTER(fi_model_spec), C.POINTER(u64)]
+        L.fi_model_pack.argtypes = [C.POINTER(fi_model_spec), vp, u64]
+        L.fi_build_dag.argtypes = [C.POINTER(fi_model_spec), i32, C.POINTER(fi_build_opts), C.POINTER(vp)]
+        L.fi_query.argtypes = [vp, C.POINTER(fi_dag_info)]
+        L.fi_node.argtypes = [vp, i32, C.POINTER(fi_node_info)]
+        L.fi_launch.argtypes = [vp, i32, C.POINTER(fi_launch_info)]
+        L.fi_load.argtypes = [vp, vp]
+        L.fi_run.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
+        L.fi_profile.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), i32]
+        L.fi_unload.argtypes = [vp]
+        L.fi_destroy.argtypes = [vp]
+        L.fi_destroy.restype = None
+        L.fi_last_error.restype = C.c_char_p
+        L.fi_version.restype = C.c_char_p
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+class FiError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().fi_last_error().decode(errors="replace")
+        super().__init__(f"{where}: {STATUS_NAMES[status] if 0 <= status < 8 else status}: {msg}")
+
+
+def _check(st, where):
+    if st != FI_OK:
+        raise FiError(st, where)
+
+
+# ---- the entry points, same names as the header --------------------------------------------
+def fi_last_error() -> str:
+    return lib().fi_last_error().decode(errors="replace")
+
+
+def fi_version() -> str:
+    return lib().fi_version().decode()
+
+
+def fi_model_packed_size(spec: fi_model_spec) -> int:
+    n = C.c_uint64(0)
+    _check(lib().fi_model_packed_size(C.byref(spec), C.byref(n)), "fi_model_packed_size")
+    return n.value
+
+
+def fi_model_pack(spec: fi_model_spec, dst_ptr: int, dst_bytes: int) -> None:
+    _check(lib().fi_model_pack(C.byref(spec), C.c_void_p(dst_ptr), dst_bytes), "fi_model_pack")
+
+
+def fi_build_dag(specs, opts: fi_build_opts) -> int:
+    arr = (fi_model_spec * len(specs))(*specs)
+    h = C.c_void_p(0)
+    _check(lib().fi_build_dag(arr, len(specs), C.byref(opts), C.byref(h)), "fi_build_dag")
+    return h.value
+
+
+def fi_query(h) -> fi_dag_info:
+    info = fi_dag_info()
+    _check(lib().fi_query(h, C.byref(info)), "fi_query")
+    return info
+
+
+def fi_node(h, i) -> fi_node_info:
+    info = fi_node_info()
+    _check(lib().fi_node(h, i, C.byref(info)), "fi_node")
+    return info
+
+
+def fi_launch(h, i) -> fi_launch_info:
+    info = fi_launch_info()
+    _check(lib().fi_launch(h, i, C.byref(info)), "fi_launch")
+    return info
+
+
+def fi_load(h, stream_ptr=0) -> None:
+    _check(lib().fi_load(h, C.c_void_p(stream_ptr)), "fi_load")
+
+
+def fi_run(h, d_input_ptr, batch, d_output_ptrs, stream_ptr=0) -> None:
+    outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
+    _check(lib().fi_run(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr)), "fi_run")
+
+
+def fi_profile(h, d_input_ptr, batch, d_output_ptrs, stream_ptr, n_launches):
+    outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
+    ms = (C.c_float * n_launches)()
+    _check(lib().fi_profile(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr), ms, n_launches), "fi_profile")
+    return list(ms)
+
+
+def fi_unload(h) -> None:
+    _check(lib().fi_unload(h), "fi_unload")
+
+
+def fi_destroy(h) -> None:
+    lib().fi_destroy(h)
+
+
+# ---- marshalling helpers ---------------------------------------------------------------------
+_OPS = {"conv": FI_CONV2D, "dwconv": FI_DWCONV2D, "maxpool": FI_MAXPOOL2D, "gap": FI_GLOBAL_AVGPOOL,
+        "fc": FI_FC, "softmax": FI_SOFTMAX}
+_ACTS = {"none": FI_ACT_NONE, "relu": FI_ACT_RELU, "relu6": FI_ACT_RELU6}
+_DT = {"f32": FI_F32, "bf16": FI_BF16}
+
+
+def make_spec(model, weights_ptr: int, weight_bytes: int, act_dtype=None, packed=False):
+    """fi_model_spec from a model description (any object with name/dtype/in_c/in_h/in_w/layers whose
+    layers carry op/input/residual/cin/cout/k/stride/pad/act/w_off/b_off).  Returns (spec, keepalive)."""
+    layers = (fi_layer_spec * len(model.layers))()
+    for i, L in enumerate(model.layers):
+        layers[i] = fi_layer_spec(_OPS[L.op], L.input, L.residual, L.cin, L.cout, L.k, L.k, L.stride, L.pad,
+                                  _ACTS[L.act], L.w_off, L.b_off)
+    name = model.name.encode()
+    dt = _DT[model.dtype]
+    spec = fi_model_spec(name, dt, dt if act_dtype is None else _DT.get(act_dtype, act_dtype), model.in_c, model.in_h,
+                         model.in_w, len(model.layers), layers, len(model.layers) - 1, 1 if packed else 0,
+                         C.c_void_p(weights_ptr), weight_bytes)
+    return spec, (layers, name)
+
+
+class HostAllocators:
+    """malloc-backed callbacks (CPU-only tests of the planner; pin_alloc need not be pinned there)."""
+
+    def __init__(self, fail_device=False):
+        self.live = {}
+        self.fail_device = fail_device
+        self.n_dev = self.n_pin = 0
+
+        def pin_alloc(n, _u):
+            buf = C.create_string_buffer(max(1, n))
+            self.live[C.addressof(buf)] = buf
+            self.n_pin += 1
+            return C.addressof(buf)
+
+        def free(p, _u):
+            self.live.pop(p, None)
+
+        def dev_alloc(n, _u):
+            self.n_dev += 1
+            return None
+
+        self.cb = (ALLOC_FN(dev_alloc), FREE_FN(free), ALLOC_FN(pin_alloc), FREE_FN(free))
+
+    def apply(self, opts: fi_build_opts):
+        opts.dev_alloc, opts.dev_free, opts.pin_alloc, opts.pin_free = self.cb
+        return opts
+
+
+class TorchAllocators:
+    """Device and pinned memory from PyTorch's allocators (memory plumbing only)."""
+
+    def __init__(self, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = device
+        self.live = {}
+        self.n_dev = self.n_pin = 0
+        self.dev_bytes_peak = 0
+
+        def dev_alloc(n, _u):
+            try:
+                t = torch.empty(max(1, n), dtype=torch.uint8, device=self.device)
+            except Exception:
+                return None
+            self.live[t.data_ptr()] = t
+            self.n_dev += 1
+            self.dev_bytes_peak = max(self.dev_bytes_peak, sum(v.numel() for v in self.live.values() if v.is_cuda))
+            return t.data_ptr()
+
+        def pin_alloc(n, _u):
+            try:
+                t = torch.empty(max(1, n), dtype=torch.uint8, pin_memory=True)
+            except Exception:
+                return None
+            self.live[t.data_ptr()] = t
+            self.n_pin += 1
+            return t.data_ptr()
+
+        def free(p, _u):
+            self.live.pop(p, None)
+
+        self.cb = (ALLOC_FN(dev_alloc), FREE_FN(free), ALLOC_FN(pin_alloc), FREE_FN(free))
+
+    def apply(self, opts: fi_build_opts):
+        opts.dev_alloc, opts.dev_free, opts.pin_alloc, opts.pin_free = self.cb
+        return opts
+
+
+class Dag:
+    """Owner of one fi_dag handle."""
+
+    def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
+                 max_device_bytes=0, keepalive=None):
+        self.keepalive = (specs, keepalive, allocators)
+        opts = fi_build_opts()
+        opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
+        if allocators is not None:
+            allocators.apply(opts)
+        self.opts = opts
+        self.h = fi_build_dag(specs, opts)
+        self.n_models = len(specs)
+
+    def query(self):
+        return fi_query(self.h)
+
+    def nodes(self):
+        return [fi_node(self.h, i) for i in range(self.query().n_nodes)]
+
+    def launches(self):
+        return [fi_launch(self.h, i) for i in range(self.query().n_launches)]
+
+    def load(self, stream_ptr=0):
+        fi_load(self.h, stream_ptr)
+
+    def run(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
+        fi_run(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr)
+
+    def profile(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
+        return fi_profile(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr, self.query().n_launches)
+
+    def unload(self):
+        fi_unload(self.h)
+
+    def destroy(self):
+        if self.h:
+            fi_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,482 @@
+// C ABI: DAG compilation (Algorithm 1, first loop), arena planning, load / run / unload.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <new>
+#include <thread>
+#include <tuple>
+
+#include "fi_internal.h"
+
+namespace fi {
+const char* last_error();
+
+struct Tensor {           // one stored activation tensor (a node's output, or a staged input)
+  int32_t first, last;    // live range in levels, inclusive
+  uint64_t bytes, off;
+};
+
+struct Member {
+  fi_model_spec spec;     // borrowed pointers inside
+  ModelPlan plan;
+  int32_t node0;          // first global node id
+  uint64_t arena_off;     // placement of the packed blob in the weight arena
+};
+
+}  // namespace fi
+
+struct fi_dag {
+  fi_build_opts opts{};
+  std::vector<fi::Member> members;
+  std::vector<fi::Node> nodes;        // global ids; input/residual are global (or -1/-2)
+  std::vector<fi::Launch> launches;
+  std::vector<fi::Desc> descs;
+  int32_t n_levels = 0;
+  int32_t wdtype = FI_BF16;
+  uint64_t desc_bytes = 0, arena_bytes = 0, act_bytes = 0, workspace_bytes = 0, device_bytes = 0;
+  uint64_t image_bytes = 0;           // bytes of the pinned image (whole arena, or tables only)
+  uint64_t stage_off[2] = {fi::kNone, fi::kNone};  // staged input per activation dtype
+  uint8_t* image = nullptr;           // pinned host image
+  uint8_t* dev = nullptr;             // the one device allocation (LOADED only)
+  int32_t state = 0;
+  uint64_t macs = 0;
+};
+
+using namespace fi;
+
+namespace {
+
+void* pin_alloc(const fi_build_opts& o, size_t n) {
+  if (o.pin_alloc) return o.pin_alloc(n, o.user);
+  void* p = nullptr;
+  if (hipHostMalloc(&p, n, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  return p;
+}
+void pin_free(const fi_build_opts& o, void* p) {
+  if (!p) return;
+  if (o.pin_free) o.pin_free(p, o.user);
+  else if (!o.pin_alloc) (void)hipHostFree(p);
+}
+
+// Copy with a few host threads: one memcpy stream does not saturate host memory bandwidth.
+void parallel_copy(uint8_t* dst, const uint8_t* src, uint64_t n) {
+  const uint64_t kMin = 8ull << 20;
+  unsigned nt = (unsigned)std::min<uint64_t>(8, n / kMin);
+  if (nt <= 1) { std::memcpy(dst, src, (size_t)n); return; }
+  std::vector<std::thread> th;
+  const uint64_t chunk = (n / nt + 4095) & ~4095ull;
+  for (unsigned t = 0; t < nt; ++t) {
+    const uint64_t lo = (uint64_t)t * chunk;
+    if (lo >= n) break;
+    const uint64_t len = std::min(chunk, n - lo);
+    th.emplace_back([=] { std::memcpy(dst + lo, src + lo, (size_t)len); });
+  }
+  for (auto& t : th) t.join();
+}
+
+int pick_tile(const Node& n, int max_batch) {
+  const int64_t M = (int64_t)max_batch * n.Ho * n.Wo;
+  auto blocks = [&](int t) { return ((M + tile_bm(t) - 1) / tile_bm(t)) * ((n.Co + tile_bn(t) - 1) / tile_bn(t)); };
+  if (n.Co > 64 && blocks(T_128x128) >= 512) return T_128x128;
+  if (blocks(T_128x64) >= 512) return T_128x64;
+  return T_64x64;
+}
+
+const char* kind_name(int kind, int tile) {
+  switch (kind) {
+    case K_STAGE: return "stage_input";
+    case K_CONV_DIRECT: return "conv_direct";
+    case K_CONV_MFMA: return tile == T_128x128 ? "conv_mfma_128x128" : tile == T_128x64 ? "conv_mfma_128x64" : "conv_mfma_64x64";
+    case K_DWCONV: return "dwconv";
+    case K_MAXPOOL: return "maxpool";
+    case K_GAP: return "global_avgpool";
+    case K_SOFTMAX: return "softmax";
+  }
+  return "?";
+}
+
+uint64_t esize(int dt) { return dt == FI_BF16 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" {
+
+const char* fi_last_error(void) { return fi::last_error(); }
+const char* fi_version(void) { return "fusedinf-gfx950 0.1"; }
+
+fi_status fi_model_packed_size(const fi_model_spec* model, uint64_t* bytes) {
+  if (!model || !bytes) { set_error("null argument"); return FI_EINVAL; }
+  ModelPlan p;
+  fi_status st = analyze_model(*model, p);
+  if (st != FI_OK) return st;
+  *bytes = p.packed_bytes;
+  return FI_OK;
+}
+
+fi_status fi_model_pack(const fi_model_spec* model, void* dst, uint64_t dst_bytes) {
+  if (!model || !dst) { set_error("null argument"); return FI_EINVAL; }
+  if (model->weights_packed || !model->weights) { set_error("fi_model_pack needs a canonical blob"); return FI_EINVAL; }
+  ModelPlan p;
+  fi_status st = analyze_model(*model, p);
+  if (st != FI_OK) return st;
+  if (dst_bytes < p.packed_bytes) { set_error("destination too small: %llu < %llu", (unsigned long long)dst_bytes, (unsigned long long)p.packed_bytes); return FI_EINVAL; }
+  pack_model(*model, p, static_cast<uint8_t*>(dst));
+  return FI_OK;
+}
+
+fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, fi_dag** out) {
+  if (!models || n < 1 || !opts || !out) { set_error("null argument or no models"); return FI_EINVAL; }
+  if (opts->max_batch < 1) { set_error("max_batch must be >= 1"); return FI_EINVAL; }
+  if (opts->load_mode != FI_LOAD_ONE_COPY && opts->load_mode != FI_LOAD_PER_MODEL) { set_error("bad load_mode"); return FI_EINVAL; }
+  if ((opts->pin_alloc == nullptr) != (opts->pin_free == nullptr) || (opts->dev_alloc == nullptr) != (opts->dev_free == nullptr)) {
+    set_error("allocator callbacks come in alloc/free pairs"); return FI_EINVAL; }
+  std::unique_ptr<fi_dag> g(new (std::nothrow) fi_dag);
+  if (!g) { set_error("out of host memory"); return FI_ENOMEM_HOST; }
+  g->opts = *opts;
+  g->members.resize((size_t)n);
+
+  // ---- per-member analysis; all members share dtype and input shape ----------------
+  for (int32_t m = 0; m < n; ++m) {
+    Member& mb = g->members[(size_t)m];
+    mb.spec = models[m];
+    if (!mb.spec.weights) { set_error("model %d: no weights", m); return FI_EINVAL; }
+    fi_status st = analyze_model(mb.spec, mb.plan);
+    if (st != FI_OK) return st;
+    if (mb.spec.weights_packed && mb.spec.weight_bytes < mb.plan.packed_bytes) {
+      set_error("model %d: packed blob is %llu bytes, layout needs %llu", m, (unsigned long long)mb.spec.weight_bytes, (unsigned long long)mb.plan.packed_bytes);
+      return FI_EINVAL; }
+    if (opts->load_mode == FI_LOAD_PER_MODEL && !mb.spec.weights_packed) {
+      set_error("FI_LOAD_PER_MODEL needs members in device layout (fi_model_pack)"); return FI_EINVAL; }
+    const fi_model_spec& a = models[0];
+    if (mb.spec.dtype != a.dtype || mb.spec.in_c != a.in_c || mb.spec.in_h != a.in_h || mb.spec.in_w != a.in_w) {
+      set_error("model %d: members of one DAG share weight dtype and input shape", m); return FI_EINVAL; }
+  }
+  g->wdtype = models[0].dtype;
+
+  // ---- union of the member graphs (no edge between members) and depth levels --------
+  int32_t total = 0;
+  for (auto& mb : g->members) { mb.node0 = total; total += (int32_t)mb.plan.nodes.size(); }
+  g->nodes.reserve((size_t)total);
+  for (int32_t m = 0; m < n; ++m) {
+    const Member& mb = g->members[(size_t)m];
+    for (const Node& ln : mb.plan.nodes) {
+      Node gn = ln;
+      gn.model = m;
+      if (gn.input >= 0) gn.input += mb.node0;
+      if (gn.residual >= 0) gn.residual += mb.node0;
+      int32_t lv = gn.input >= 0 ? g->nodes[(size_t)gn.input].level : 0;
+      if (gn.residual >= 0) lv = std::max(lv, g->nodes[(size_t)gn.residual].level);
+      gn.level = lv + 1;
+      g->n_levels = std::max(g->n_levels, gn.level);
+      g->macs += gn.macs;
+      g->nodes.push_back(gn);
+    }
+  }
+
+  // ---- kernel family per node ---------------------------------------------------------
+  const int B = opts->max_batch;
+  for (Node& nd : g->nodes) {
+    const int adt = g->members[(size_t)nd.model].spec.act_dtype;
+    nd.tile = 0;
+    switch (nd.op) {
+      case FI_CONV2D:
+      case FI_FC:
+        if (g->wdtype == FI_BF16 && adt == FI_BF16) { nd.kind = K_CONV_MFMA; nd.tile = pick_tile(nd, B); }
+        else nd.kind = K_CONV_DIRECT;
+        break;
+      case FI_DWCONV2D: nd.kind = K_DWCONV; break;
+      case FI_MAXPOOL2D: nd.kind = K_MAXPOOL; break;
+      case FI_GLOBAL_AVGPOOL: nd.kind = K_GAP; break;
+      default: nd.kind = K_SOFTMAX; break;
+    }
+  }
+
+  // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
+  //      share a launch, FI_MAX_GROUP problems at most --------------------------------------
+  bool need_stage[2] = {false, false};
+  for (const Node& nd : g->nodes)
+    if (nd.input == FI_INPUT) need_stage[g->members[(size_t)nd.model].spec.act_dtype] = true;
+  auto new_launch = [&](int level, int kind, int tile, int adt) -> Launch& {
+    Launch L{};
+    L.level = level; L.kind = kind; L.tile = tile; L.wdtype = g->wdtype; L.adtype = adt;
+    L.first_desc = 0; L.n = 0; L.macs = L.act_bytes = L.weight_bytes = 0;
+    L.name = kind_name(kind, tile);
+    g->launches.push_back(L);
+    return g->launches.back();
+  };
+  for (int adt = 0; adt < 2; ++adt)
+    if (need_stage[adt]) new_launch(0, K_STAGE, 0, adt);   // one staged copy per activation dtype
+  for (int32_t lv = 1; lv <= g->n_levels; ++lv) {
+    std::map<std::tuple<int, int, int>, int32_t> open;   // (kind, tile, adtype) -> launch index
+    for (int32_t i = 0; i < total; ++i) {
+      Node& nd = g->nodes[(size_t)i];
+      if (nd.level != lv) continue;
+      const int adt = g->members[(size_t)nd.model].spec.act_dtype;
+      const auto key = std::make_tuple(nd.kind, nd.tile, adt);
+      auto it = open.find(key);
+      if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
+        new_launch(lv, nd.kind, nd.tile, adt);
+        open[key] = (int32_t)g->launches.size() - 1;
+        it = open.find(key);
+      }
+      Launch& L = g->launches[(size_t)it->second];
+      nd.launch = it->second;
+      nd.slot = L.n++;
+      L.nodes.push_back(i);
+    }
+  }
+
+  // ---- activation arena: live range of every stored tensor, then first-fit by size -----
+  std::vector<Tensor> tens((size_t)total + 2);
+  for (int32_t i = 0; i < total; ++i) {
+    Node& nd = g->nodes[(size_t)i];
+    nd.first_level = nd.last_level = nd.level;
+  }
+  int32_t stage_last[2] = {0, 0};
+  for (int32_t i = 0; i < total; ++i) {
+    const Node& nd = g->nodes[(size_t)i];
+    const int adt = g->members[(size_t)nd.model].spec.act_dtype;
+    if (nd.input >= 0) g->nodes[(size_t)nd.input].last_level = std::max(g->nodes[(size_t)nd.input].last_level, nd.level);
+    else stage_last[adt] = std::max(stage_last[adt], nd.level);
+    if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.level);
+  }
+  for (int32_t i = 0; i < total; ++i) {
+    Node& nd = g->nodes[(size_t)i];
+    nd.out_bytes = nd.is_output ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
+    tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.out_bytes, 0};
+  }
+  const Member& m0 = g->members[0];
+  for (int adt = 0; adt < 2; ++adt)
+    tens[(size_t)total + adt] = Tensor{0, stage_last[adt],
+        need_stage[adt] ? align_up((uint64_t)B * m0.spec.in_h * m0.spec.in_w * m0.plan.in_cp * esize(adt)) : 0, 0};
+  {
+    std::vector<int32_t> order;
+    for (int32_t i = 0; i < total + 2; ++i) if (tens[(size_t)i].bytes) order.push_back(i);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return tens[(size_t)a].bytes > tens[(size_t)b].bytes; });
+    std::vector<int32_t> placed;
+    uint64_t top = 0;
+    for (int32_t t : order) {
+      Tensor& T = tens[(size_t)t];
+      // offsets blocked by tensors alive at the same time, scanned in address order
+      std::vector<std::pair<uint64_t, uint64_t>> busy;
+      for (int32_t u : placed) {
+        const Tensor& U = tens[(size_t)u];
+        if (U.first <= T.last && T.first <= U.last) busy.emplace_back(U.off, U.off + U.bytes);
+      }
+      std::sort(busy.begin(), busy.end());
+      uint64_t off = 0;
+      for (auto& b : busy) { if (off + T.bytes <= b.first) break; off = std::max(off, b.second); }
+      T.off = off;
+      top = std::max(top, off + T.bytes);
+      placed.push_back(t);
+    }
+    g->act_bytes = align_up(top ? top : kAlign);
+  }
+  for (int32_t i = 0; i < total; ++i) g->nodes[(size_t)i].out_off = tens[(size_t)i].off;
+  for (int adt = 0; adt < 2; ++adt) if (need_stage[adt]) g->stage_off[adt] = tens[(size_t)total + adt].off;
+
+  // ---- weight arena: [descriptor table][member 0][member 1]... --------------------------
+  size_t n_desc = 0;
+  for (Launch& L : g->launches) { L.first_desc = (int32_t)n_desc; if (L.kind == K_STAGE) L.n = 1; n_desc += (size_t)L.n; }
+  g->descs.assign(n_desc, Desc{});
+  g->desc_bytes = align_up(n_desc * sizeof(Desc));
+  uint64_t off = g->desc_bytes;
+  for (Member& mb : g->members) { mb.arena_off = off; off += mb.plan.packed_bytes; }
+  g->arena_bytes = off;
+  for (Node& nd : g->nodes) {
+    const Member& mb = g->members[(size_t)nd.model];
+    nd.w_off = nd.w_rel == kNone ? kNone : mb.arena_off + nd.w_rel;
+    nd.b_off = nd.b_rel == kNone ? kNone : mb.arena_off + nd.b_rel;
+  }
+  g->workspace_bytes = 0;
+  g->device_bytes = g->arena_bytes + g->act_bytes + g->workspace_bytes;
+  if (opts->max_device_bytes && g->device_bytes > opts->max_device_bytes) {
+    set_error("DAG needs %llu device bytes, budget is %llu", (unsigned long long)g->device_bytes, (unsigned long long)opts->max_device_bytes);
+    return FI_EBUDGET;
+  }
+
+  // ---- descriptors ---------------------------------------------------------------------
+  for (Launch& L : g->launches) {
+    if (L.kind == K_STAGE) {
+      Desc& d = g->descs[(size_t)L.first_desc];
+      d.H = m0.spec.in_h; d.W = m0.spec.in_w; d.C = m0.spec.in_c; d.Cp = m0.plan.in_cp;
+      d.y_off = g->stage_off[L.adtype]; d.r_off = kNone; d.x_off = d.w_off = d.b_off = kNone;
+      L.act_bytes = (uint64_t)d.H * d.W * (d.C * esize(L.wdtype) + d.Cp * esize(L.adtype));
+      continue;
+    }
+    for (int32_t s = 0; s < L.n; ++s) {
+      const Node& nd = g->nodes[(size_t)L.nodes[(size_t)s]];
+      const int adt = g->members[(size_t)nd.model].spec.act_dtype;
+      Desc& d = g->descs[(size_t)(L.first_desc + s)];
+      d.x_off = nd.input >= 0 ? g->nodes[(size_t)nd.input].out_off : g->stage_off[adt];
+      d.y_off = nd.is_output ? kNone : nd.out_off;
+      d.r_off = nd.residual >= 0 ? g->nodes[(size_t)nd.residual].out_off : kNone;
+      d.w_off = nd.w_off; d.b_off = nd.b_off;
+      d.H = nd.H; d.W = nd.W; d.C = nd.C; d.Cp = nd.Cp;
+      d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop;
+      d.k = nd.k; d.stride = nd.stride; d.pad = nd.pad; d.act = nd.act; d.Kp = nd.Kp;
+      if (nd.op == FI_FC) {  // a fully connected node is a 1x1 convolution over the flattened input
+        d.C = d.Cp = nd.H * nd.W * nd.Cp; d.H = d.W = 1; d.k = 1; d.stride = 1; d.pad = 0;
+      }
+      d.ext = nd.is_output;
+      d.out_f32 = (nd.out_dtype == FI_F32 && adt != FI_F32) ? 1 : 0;
+      if (nd.out_dtype == FI_F32 && adt != FI_F32 && !nd.is_output) d.Cop = nd.Cop;  // fp32 rows keep the padded stride
+      d.tiles_n = L.kind == K_CONV_MFMA ? (nd.Co + tile_bn(L.tile) - 1) / tile_bn(L.tile) : 0;
+      L.macs += nd.macs;
+      const uint64_t in_e = esize(nd.input >= 0 ? g->nodes[(size_t)nd.input].out_dtype : adt);
+      L.act_bytes += (uint64_t)nd.H * nd.W * nd.C * in_e + (uint64_t)nd.Ho * nd.Wo * nd.Co * esize(nd.out_dtype) +
+                     (nd.residual >= 0 ? (uint64_t)nd.Ho * nd.Wo * nd.Co * esize(adt) : 0);
+      if (nd.w_rel != kNone)
+        L.weight_bytes += (nd.op == FI_DWCONV2D ? (uint64_t)nd.k * nd.k * nd.C : (uint64_t)nd.Co * nd.k * nd.k * nd.C * (nd.op == FI_FC ? nd.H * nd.W : 1)) * esize(g->wdtype) + (uint64_t)nd.Co * 4;
+    }
+  }
+
+  // ---- pinned image: the bytes fi_load copies ----------------------------------------------
+  g->image_bytes = opts->load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;
+  g->image = static_cast<uint8_t*>(pin_alloc(*opts, (size_t)g->image_bytes));
+  if (!g->image) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)g->image_bytes); return FI_ENOMEM_HOST; }
+  std::memset(g->image, 0, (size_t)g->desc_bytes);
+  std::memcpy(g->image, g->descs.data(), n_desc * sizeof(Desc));
+  if (opts->load_mode == FI_LOAD_ONE_COPY) {
+    for (const Member& mb : g->members) {
+      if (mb.spec.weights_packed) parallel_copy(g->image + mb.arena_off, static_cast<const uint8_t*>(mb.spec.weights), mb.plan.packed_bytes);
+      else pack_model(mb.spec, mb.plan, g->image + mb.arena_off);
+    }
+  }
+  *out = g.release();
+  return FI_OK;
+}
+
+fi_status fi_query(const fi_dag* g, fi_dag_info* info) {
+  if (!g || !info) { set_error("null argument"); return FI_EINVAL; }
+  std::memset(info, 0, sizeof(*info));
+  info->arena_bytes = g->arena_bytes; info->act_bytes = g->act_bytes; info->workspace_bytes = g->workspace_bytes;
+  info->device_bytes = g->device_bytes; info->macs_per_image = g->macs;
+  info->n_models = (int32_t)g->members.size(); info->n_nodes = (int32_t)g->nodes.size();
+  info->n_levels = g->n_levels; info->n_launches = (int32_t)g->launches.size();
+  info->n_device_allocs = 1;
+  info->n_h2d_copies = g->opts.load_mode == FI_LOAD_ONE_COPY ? 1 : 1 + (int32_t)g->members.size();
+  info->state = g->state;
+  return FI_OK;
+}
+
+fi_status fi_node(const fi_dag* g, int32_t i, fi_node_info* o) {
+  if (!g || !o || i < 0 || i >= (int32_t)g->nodes.size()) { set_error("bad node index"); return FI_EINVAL; }
+  const Node& n = g->nodes[(size_t)i];
+  std::memset(o, 0, sizeof(*o));
+  o->model = n.model; o->index = n.index; o->op = n.op; o->level = n.level; o->launch = n.launch;
+  o->out_c = n.Co; o->out_h = n.Ho; o->out_w = n.Wo; o->out_cp = n.Cop; o->out_dtype = n.out_dtype;
+  o->is_output = n.is_output; o->first_level = n.first_level; o->last_level = n.last_level;
+  o->out_off = n.out_off; o->out_bytes = n.out_bytes; o->w_off = n.w_off; o->b_off = n.b_off; o->macs = n.macs;
+  return FI_OK;
+}
+
+fi_status fi_launch(const fi_dag* g, int32_t i, fi_launch_info* o) {
+  if (!g || !o || i < 0 || i >= (int32_t)g->launches.size()) { set_error("bad launch index"); return FI_EINVAL; }
+  const Launch& L = g->launches[(size_t)i];
+  std::memset(o, 0, sizeof(*o));
+  o->level = L.level; o->kind = L.kind; o->n_problems = L.n; o->first_node = L.nodes.empty() ? -1 : L.nodes[0];
+  o->macs_per_image = L.macs; o->bytes_per_image = L.act_bytes; o->weight_bytes = L.weight_bytes;
+  std::snprintf(o->name, sizeof(o->name), "%s", L.name.c_str());
+  return FI_OK;
+}
+
+fi_status fi_load(fi_dag* g, void* stream) {
+  if (!g) { set_error("null handle"); return FI_EINVAL; }
+  if (g->state != 0) { set_error("fi_load: handle is already loaded"); return FI_ESTATE; }
+  uint8_t* d = nullptr;
+  if (g->opts.dev_alloc) d = static_cast<uint8_t*>(g->opts.dev_alloc((size_t)g->device_bytes, g->opts.user));
+  else if (hipMalloc(reinterpret_cast<void**>(&d), (size_t)g->device_bytes) != hipSuccess) { (void)hipGetLastError(); d = nullptr; }
+  if (!d) { set_error("device allocation of %llu bytes failed", (unsigned long long)g->device_bytes); return FI_ENOMEM_DEVICE; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(d, g->image, (size_t)g->image_bytes, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && g->opts.load_mode == FI_LOAD_PER_MODEL)
+    for (const Member& mb : g->members) {
+      e = hipMemcpyAsync(d + mb.arena_off, mb.spec.weights, (size_t)mb.plan.packed_bytes, hipMemcpyHostToDevice, s);
+      if (e != hipSuccess) break;
+    }
+  if (e != hipSuccess) {
+    set_error("hipMemcpyAsync: %s", hipGetErrorString(e));
+    if (g->opts.dev_free) g->opts.dev_free(d, g->opts.user); else (void)hipFree(d);
+    return FI_EHIP;
+  }
+  g->dev = d;
+  g->state = 1;
+  return FI_OK;
+}
+
+static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream,
+                          float* ms, int32_t n_ms) {
+  if (!g || !d_input || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
+  if (g->state != 1) { set_error("fi_run: handle is not loaded"); return FI_ESTATE; }
+  if (batch < 1 || batch > g->opts.max_batch) { set_error("batch %d outside [1, %d]", batch, g->opts.max_batch); return FI_EINVAL; }
+  for (size_t m = 0; m < g->members.size(); ++m)
+    if (!d_outputs[m]) { set_error("output %zu is null", m); return FI_EINVAL; }
+  const size_t nl = g->launches.size();
+  if (ms && n_ms < (int32_t)nl) { set_error("ms holds %d entries, schedule has %zu launches", n_ms, nl); return FI_EINVAL; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<hipEvent_t> ev;
+  if (ms) {
+    ev.resize(nl + 1);
+    for (auto& e : ev) if (hipEventCreate(&e) != hipSuccess) { set_error("hipEventCreate failed"); return FI_EHIP; }
+    (void)hipEventRecord(ev[0], s);
+  }
+  KArgs a{};
+  a.wbase = g->dev;
+  a.abase = g->dev + g->arena_bytes;
+  a.batch = batch;
+  a.ext_in = d_input;
+  fi_status rc = FI_OK;
+  for (size_t i = 0; i < nl; ++i) {
+    const Launch& L = g->launches[i];
+    a.descs = reinterpret_cast<const Desc*>(g->dev) + L.first_desc;
+    a.n = L.n;
+    for (int32_t k = 0; k < L.n && L.kind != K_STAGE; ++k) {
+      const Node& nd = g->nodes[(size_t)L.nodes[(size_t)k]];
+      a.ext_out[k] = nd.is_output ? d_outputs[nd.model] : nullptr;
+    }
+    const int e = launch_kernel(L, a, s, g->descs);
+    if (e != (int)hipSuccess) { set_error("launch %zu (%s): %s", i, L.name.c_str(), hipGetErrorString((hipError_t)e)); rc = FI_EHIP; break; }
+    if (ms) (void)hipEventRecord(ev[i + 1], s);
+  }
+  if (ms) {
+    (void)hipStreamSynchronize(s);
+    if (rc == FI_OK)
+      for (size_t i = 0; i < nl; ++i) (void)hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]);
+    for (auto& e : ev) (void)hipEventDestroy(e);
+  }
+  return rc;
+}
+
+fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream) {
+  return run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0);
+}
+
+fi_status fi_profile(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream, float* ms, int32_t n_ms) {
+  if (!ms) { set_error("null ms"); return FI_EINVAL; }
+  return run_impl(g, d_input, batch, d_outputs, stream, ms, n_ms);
+}
+
+fi_status fi_unload(fi_dag* g) {
+  if (!g) { set_error("null handle"); return FI_EINVAL; }
+  if (g->state != 1) { set_error("fi_unload: handle is not loaded"); return FI_ESTATE; }
+  (void)hipDeviceSynchronize();
+  if (g->opts.dev_free) g->opts.dev_free(g->dev, g->opts.user); else (void)hipFree(g->dev);
+  g->dev = nullptr;
+  g->state = 0;
+  return FI_OK;
+}
+
+void fi_destroy(fi_dag* g) {
+  if (!g) return;
+  if (g->state == 1) (void)fi_unload(g);
+  pin_free(g->opts, g->image);
+  delete g;
+}
+
+}  // extern "C"

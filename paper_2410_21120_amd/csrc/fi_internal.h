@@ -1,0 +1,102 @@
+// Internal structures shared by the host planner, the packer and the kernels.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/fusedinf.h"
+
+namespace fi {
+
+constexpr uint64_t kAlign = 256;       // every arena object starts on a 256-byte boundary
+constexpr uint64_t kNone = ~0ull;
+inline uint64_t align_up(uint64_t v, uint64_t a = kAlign) { return (v + a - 1) / a * a; }
+
+// Kernel families.  A launch runs one family over 1..FI_MAX_GROUP problems.
+enum Kind : int32_t {
+  K_STAGE = 0,        // caller's NHWC input -> channel-padded copy in the activation arena
+  K_CONV_DIRECT = 1,  // one thread per output element (fp32 models, fp32-activation members)
+  K_CONV_MFMA = 2,    // implicit GEMM on the matrix cores (bf16 weights, bf16 activations)
+  K_DWCONV = 3,
+  K_MAXPOOL = 4,
+  K_GAP = 5,
+  K_SOFTMAX = 6,
+  K_NKINDS
+};
+
+// Tile shapes of the MFMA implicit GEMM (rows = output pixels, cols = output channels).
+enum Tile : int32_t { T_128x128 = 0, T_128x64 = 1, T_64x64 = 2, T_NTILES };
+inline int tile_bm(int t) { return t == T_64x64 ? 64 : 128; }
+inline int tile_bn(int t) { return t == T_128x128 ? 128 : 64; }
+
+// Device-visible problem descriptor: one node of the fused DAG, batch independent.
+// Tensor offsets are relative to the activation region, weight offsets to the weight
+// arena, so the table is position independent and travels inside the arena image.
+struct Desc {
+  uint64_t x_off, y_off, r_off;  // input / output / residual (kNone = no residual)
+  uint64_t w_off, b_off;
+  int32_t H, W, C, Cp;           // input: logical dims and padded channel stride
+  int32_t Ho, Wo, Co, Cop;       // output
+  int32_t k, stride, pad, act;
+  int32_t Kp;                    // padded reduction length of a weight row (elements)
+  int32_t ext;                   // 1: output is the caller's fp32 buffer of this problem
+  int32_t out_f32;               // 1: output stored as fp32 whatever the activation dtype
+  int32_t tiles_n;               // MFMA conv: column tiles
+  int32_t rsv[6];
+};
+static_assert(sizeof(Desc) == 128, "Desc is 128 bytes");
+
+struct Node {
+  int32_t model, index;
+  int32_t op, act;
+  int32_t input, residual;       // global node ids (or -1 / -2)
+  int32_t H, W, C, Cp, Ho, Wo, Co, Cop, k, stride, pad;
+  int32_t Kp;
+  int32_t level;
+  int32_t out_dtype;             // FI_F32 / FI_BF16 as stored
+  int32_t is_output;
+  int32_t first_level, last_level;
+  int32_t launch, slot;          // launch index and problem slot inside it
+  int32_t kind, tile;
+  uint64_t w_rel, b_rel;         // offsets inside the member's packed blob
+  uint64_t w_off, b_off;         // offsets in the weight arena
+  uint64_t out_off, out_bytes;   // activation arena placement (bytes at max_batch)
+  uint64_t macs;
+};
+
+struct Launch {
+  int32_t level, kind, tile;
+  int32_t wdtype, adtype;        // weight / activation storage dtype of every problem in it
+  int32_t first_desc, n;         // contiguous range in the descriptor table
+  std::vector<int32_t> nodes;    // global node ids, slot order
+  std::string name;
+  uint64_t macs, act_bytes, weight_bytes;
+};
+
+// Per-member analysis shared by fi_model_packed_size / fi_model_pack / fi_build_dag.
+struct ModelPlan {
+  std::vector<Node> nodes;       // input/residual are LOCAL indices here
+  uint64_t packed_bytes = 0;
+  int32_t cgran = 1;             // channel padding granule (8 for bf16 weights, 1 for fp32)
+  int32_t in_cp = 0;
+};
+
+// Arguments every kernel receives by value.
+struct KArgs {
+  const uint8_t* wbase;          // weight arena (device)
+  uint8_t* abase;                // activation region (device)
+  const Desc* descs;             // first descriptor of this launch (device)
+  int32_t n, batch;
+  const void* ext_in;            // caller's input (K_STAGE only)
+  void* ext_out[FI_MAX_GROUP];   // caller's output per problem slot (when Desc.ext)
+};
+
+void set_error(const char* fmt, ...);
+fi_status analyze_model(const fi_model_spec& m, ModelPlan& out);
+void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst);
+
+// Implemented in fi_kernels.hip.  Returns a hipError_t as int; `stream` is a hipStream_t.
+int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);
+
+}  // namespace fi

@@ -1,0 +1,442 @@
+// HIP kernels of the fused DAG for gfx950 (wave64, MFMA).
+//
+// Every kernel is a GROUPED kernel: one launch carries 1..FI_MAX_GROUP independent
+// problems (nodes of different member models at the same depth).  A workgroup finds its
+// problem by walking the launch's descriptor range and subtracting each problem's
+// workgroup count; it then touches only that problem's input, weights and output, so a
+// member's bits never depend on which other members share the launch (Section III-A,
+// C1 and C4: no operator is merged across models, no tensor is shared between them).
+//
+// Tensors are NHWC with the channel stride padded to Cp; pad channels always hold zero.
+#include <hip/hip_runtime.h>
+
+#include "fi_internal.h"
+
+namespace fi {
+
+// ---------------------------------------------------------------------------------
+// element access
+// ---------------------------------------------------------------------------------
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// round-to-nearest-even; inputs are finite by construction
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float ld(const float* p) { return *p; }
+__device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
+__device__ __forceinline__ void st(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
+
+__device__ __forceinline__ float activate(float v, int act) {
+  if (act == FI_ACT_RELU) return fmaxf(v, 0.0f);
+  if (act == FI_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+  return v;
+}
+
+// Workgroups a problem needs, as a function of the batch (host and device agree on this).
+__host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d, int batch) {
+  switch (kind) {
+    case K_STAGE: return (batch * d.H * d.W + 255) / 256;
+    case K_CONV_DIRECT: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
+    case K_CONV_MFMA: {
+      const int bm = tile == T_64x64 ? 64 : 128;
+      return ((batch * d.Ho * d.Wo + bm - 1) / bm) * d.tiles_n;
+    }
+    case K_DWCONV:
+    case K_MAXPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
+    case K_GAP: return (batch * d.Cop + 255) / 256;
+    case K_SOFTMAX: return batch;
+  }
+  return 0;
+}
+
+// Walks the descriptor range; on return `bid` is the workgroup index inside problem `p`.
+__device__ __forceinline__ bool find_problem(const KArgs& a, int kind, int tile, int& p, int& bid) {
+  bid = blockIdx.x;
+  for (p = 0; p < a.n; ++p) {
+    const int t = problem_blocks(kind, tile, a.descs[p], a.batch);
+    if (bid < t) return true;
+    bid -= t;
+  }
+  return false;
+}
+
+// ---------------------------------------------------------------------------------
+// input staging: caller's [B,H,W,C] (weight dtype) -> [B,H,W,Cp] in the activation dtype
+// ---------------------------------------------------------------------------------
+template <typename TI, typename TA>
+__global__ void __launch_bounds__(256) stage_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_STAGE, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int64_t pix = (int64_t)bid * 256 + threadIdx.x;
+  if (pix >= (int64_t)a.batch * d.H * d.W) return;
+  const TI* x = static_cast<const TI*>(a.ext_in) + pix * d.C;
+  TA* y = reinterpret_cast<TA*>(a.abase + d.y_off) + pix * d.Cp;
+  for (int c = 0; c < d.Cp; ++c) st(y + c, c < d.C ? ld(x + c) : 0.0f);
+}
+
+// ---------------------------------------------------------------------------------
+// direct convolution / FC: one thread per output element.  Used by fp32 models and by
+// bf16 members that keep fp32 activations.
+// ---------------------------------------------------------------------------------
+template <typename TW, typename TA>
+__global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_CONV_DIRECT, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  const int64_t M = (int64_t)a.batch * d.Ho * d.Wo;
+  if (idx >= M * d.Cop) return;
+  const int o = (int)(idx % d.Cop);
+  const int64_t m = idx / d.Cop;
+  float v = 0.0f;
+  if (o < d.Co) {
+    const int q = (int)(m % d.Wo);
+    const int pp = (int)((m / d.Wo) % d.Ho);
+    const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
+    const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
+    const TW* w = reinterpret_cast<const TW*>(a.wbase + d.w_off) + (int64_t)o * d.Kp;
+    float acc = 0.0f;
+    for (int r = 0; r < d.k; ++r) {
+      const int ih = pp * d.stride - d.pad + r;
+      if (ih < 0 || ih >= d.H) continue;
+      for (int s = 0; s < d.k; ++s) {
+        const int iw = q * d.stride - d.pad + s;
+        if (iw < 0 || iw >= d.W) continue;
+        const TA* xr = x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp;
+        const TW* wr = w + (r * d.k + s) * d.Cp;
+        for (int c = 0; c < d.C; ++c) acc += ld(xr + c) * ld(wr + c);
+      }
+    }
+    v = acc + reinterpret_cast<const float*>(a.wbase + d.b_off)[o];
+    if (d.r_off != kNone) v += ld(reinterpret_cast<const TA*>(a.abase + d.r_off) + m * d.Cop + o);
+    v = activate(v, d.act);
+  }
+  if (d.ext) {
+    if (o < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + o] = v;
+  } else if (d.out_f32) {
+    reinterpret_cast<float*>(a.abase + d.y_off)[m * d.Cop + o] = v;
+  } else {
+    st(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + o, v);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// implicit-GEMM convolution / FC on MFMA.
+//   rows  m = (n, p, q) output pixels      M = batch*Ho*Wo
+//   cols  o = output channel               N = Co
+//   red.  kk = (r, s, c), c innermost      K = k*k*Cp, weight rows padded to Kp (x32)
+// A (input patches) and B (weights) tiles of 32 reduction elements are staged through LDS
+// with 16-byte vectors; each of the 4 waves owns a (BM/2)x(BN/2) sub-tile built from
+// 32x32x16 bf16 MFMAs with fp32 accumulation.  Epilogue: + bias (+ residual) -> activation
+// -> one round-to-nearest-even to bf16.
+// ---------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int BK = 32;
+constexpr int LDS_STRIDE = BK + 8;  // elements; 80-byte rows keep 16-byte reads conflict-free
+
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
+  constexpr int TILE = BM == 64 ? T_64x64 : (BN == 128 ? T_128x128 : T_128x64);
+  constexpr int WTM = BM / 2, WTN = BN / 2;  // per-wave sub-tile
+  constexpr int MI = WTM / 32, NI = WTN / 32;
+  constexpr int AR = BM / 64, BR = BN / 64;  // rows each thread stages per tile
+
+  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_STRIDE];
+
+  int p, bid;
+  if (!find_problem(a, K_CONV_MFMA, TILE, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int M = a.batch * d.Ho * d.Wo;
+  const int m0 = (bid / d.tiles_n) * BM;
+  const int n0 = (bid % d.tiles_n) * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const bf16_t* __restrict__ x = reinterpret_cast<const bf16_t*>(a.abase + d.x_off);
+  const bf16_t* __restrict__ w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off);
+
+  // staging assignment: thread -> (row, 8-element k vector)
+  const int srow = tid >> 2, kvec = (tid & 3) * 8;
+  int a_ih0[AR], a_iw0[AR];
+  int64_t a_base[AR];
+  bool a_ok[AR];
+#pragma unroll
+  for (int i = 0; i < AR; ++i) {
+    const int m = m0 + srow + 64 * i;
+    a_ok[i] = m < M;
+    const int mm = a_ok[i] ? m : 0;
+    const int q = mm % d.Wo;
+    const int t = mm / d.Wo;
+    const int pp = t % d.Ho;
+    const int n = t / d.Ho;
+    a_ih0[i] = pp * d.stride - d.pad;
+    a_iw0[i] = q * d.stride - d.pad;
+    a_base[i] = (int64_t)n * d.H * d.W * d.Cp;
+  }
+  const bf16_t* b_ptr[BR];
+#pragma unroll
+  for (int i = 0; i < BR; ++i) {
+    int o = n0 + srow + 64 * i;
+    o = o < d.Co ? o : d.Co - 1;  // clamped rows are computed and discarded
+    b_ptr[i] = w + (int64_t)o * d.Kp + kvec;
+  }
+  // this thread's reduction position (r, s, c), advanced by BK per tile
+  int kr = 0, ks = 0, kc = kvec;
+  while (kc >= d.Cp) { kc -= d.Cp; if (++ks == d.k) { ks = 0; ++kr; } }
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  const int ntiles = d.Kp / BK;
+  for (int kt = 0; kt < ntiles; ++kt) {
+    uint4 av[AR], bv[BR];
+#pragma unroll
+    for (int i = 0; i < AR; ++i) {
+      const int ih = a_ih0[i] + kr, iw = a_iw0[i] + ks;
+      av[i] = make_uint4(0, 0, 0, 0);
+      if (a_ok[i] && kr < d.k && ih >= 0 && ih < d.H && iw >= 0 && iw < d.W)
+        av[i] = *reinterpret_cast<const uint4*>(x + a_base[i] + ((int64_t)ih * d.W + iw) * d.Cp + kc);
+    }
+#pragma unroll
+    for (int i = 0; i < BR; ++i) bv[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + (int64_t)kt * BK);
+    kc += BK;
+    while (kc >= d.Cp) { kc -= d.Cp; if (++ks == d.k) { ks = 0; ++kr; } }
+
+    __syncthreads();  // previous tile fully consumed
+#pragma unroll
+    for (int i = 0; i < AR; ++i) *reinterpret_cast<uint4*>(&As[(srow + 64 * i) * LDS_STRIDE + kvec]) = av[i];
+#pragma unroll
+    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + 64 * i) * LDS_STRIDE + kvec]) = bv[i];
+    __syncthreads();
+
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 af[MI], bfr[NI];
+      const int kof = kk + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * WTM + i * 32 + (lane & 31)) * LDS_STRIDE + kof]);
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * WTN + j * 32 + (lane & 31)) * LDS_STRIDE + kof]);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // epilogue
+  const float* bias = reinterpret_cast<const float*>(a.wbase + d.b_off);
+  const bf16_t* res = d.r_off != kNone ? reinterpret_cast<const bf16_t*>(a.abase + d.r_off) : nullptr;
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int o = n0 + wn * WTN + j * 32 + (lane & 31);
+    if (o >= d.Cop) continue;
+    const bool real = o < d.Co;
+    const float bo = real ? bias[o] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (m >= M) continue;
+        float v = 0.0f;
+        if (real) {
+          v = acc[i][j][e] + bo;
+          if (res) v += bf2f(res[(int64_t)m * d.Cop + o]);
+          v = activate(v, d.act);
+        }
+        if (d.ext) {
+          if (real) static_cast<float*>(a.ext_out[p])[(int64_t)m * d.Co + o] = v;
+        } else if (d.out_f32) {
+          reinterpret_cast<float*>(a.abase + d.y_off)[(int64_t)m * d.Cop + o] = v;
+        } else {
+          reinterpret_cast<bf16_t*>(a.abase + d.y_off)[(int64_t)m * d.Cop + o] = f2bf(v);
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// depthwise convolution: one thread per (pixel, channel), channel fastest (coalesced)
+// ---------------------------------------------------------------------------------
+template <typename TW, typename TA>
+__global__ void __launch_bounds__(256) dwconv_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_DWCONV, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
+  const int c = (int)(idx % d.Cop);
+  const int64_t m = idx / d.Cop;
+  const int q = (int)(m % d.Wo);
+  const int pp = (int)((m / d.Wo) % d.Ho);
+  const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
+  const TW* w = reinterpret_cast<const TW*>(a.wbase + d.w_off);
+  float acc = 0.0f;
+  for (int r = 0; r < d.k; ++r) {
+    const int ih = pp * d.stride - d.pad + r;
+    if (ih < 0 || ih >= d.H) continue;
+    for (int s = 0; s < d.k; ++s) {
+      const int iw = q * d.stride - d.pad + s;
+      if (iw < 0 || iw >= d.W) continue;
+      acc += ld(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp + c) * ld(w + (r * d.k + s) * d.Cp + c);
+    }
+  }
+  float v = 0.0f;
+  if (c < d.Co) {
+    v = acc + reinterpret_cast<const float*>(a.wbase + d.b_off)[c];
+    if (d.r_off != kNone) v += ld(reinterpret_cast<const TA*>(a.abase + d.r_off) + idx);
+    v = activate(v, d.act);
+  }
+  if (d.ext) {
+    if (c < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + c] = v;
+  } else {
+    st(reinterpret_cast<TA*>(a.abase + d.y_off) + idx, v);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// max pooling: out-of-range taps are skipped (padding behaves as -inf)
+// ---------------------------------------------------------------------------------
+template <typename TA>
+__global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_MAXPOOL, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
+  const int c = (int)(idx % d.Cop);
+  const int64_t m = idx / d.Cop;
+  const int q = (int)(m % d.Wo);
+  const int pp = (int)((m / d.Wo) % d.Ho);
+  const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
+  float best = -INFINITY;
+  for (int r = 0; r < d.k; ++r) {
+    const int ih = pp * d.stride - d.pad + r;
+    if (ih < 0 || ih >= d.H) continue;
+    for (int s = 0; s < d.k; ++s) {
+      const int iw = q * d.stride - d.pad + s;
+      if (iw < 0 || iw >= d.W) continue;
+      best = fmaxf(best, ld(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp + c));
+    }
+  }
+  if (d.ext) {
+    if (c < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + c] = best;
+  } else {
+    st(reinterpret_cast<TA*>(a.abase + d.y_off) + idx, best);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// global average pooling: one thread per (image, channel), fp32 sum, divide by H*W
+// ---------------------------------------------------------------------------------
+template <typename TA>
+__global__ void __launch_bounds__(256) gap_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_GAP, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int idx = bid * 256 + threadIdx.x;
+  if (idx >= a.batch * d.Cop) return;
+  const int c = idx % d.Cop, n = idx / d.Cop;
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c;
+  float sum = 0.0f;
+  for (int i = 0; i < d.H * d.W; ++i) sum += ld(x + (int64_t)i * d.Cp);
+  const float v = sum / (float)(d.H * d.W);
+  if (d.ext) {
+    if (c < d.Co) static_cast<float*>(a.ext_out[p])[(int64_t)n * d.Co + c] = v;
+  } else if (d.out_f32) {
+    reinterpret_cast<float*>(a.abase + d.y_off)[idx] = v;
+  } else {
+    st(reinterpret_cast<TA*>(a.abase + d.y_off) + idx, v);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// softmax over the class axis of an fp32 [batch, Cp] tensor: one wave per row
+// ---------------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) softmax_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_SOFTMAX, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const float* z = reinterpret_cast<const float*>(a.abase + d.x_off) + (int64_t)bid * d.Cp;
+  float* y = d.ext ? static_cast<float*>(a.ext_out[p]) + (int64_t)bid * d.Co
+                   : reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)bid * d.Cop;
+  const int lane = threadIdx.x;
+  float m = -INFINITY;
+  for (int c = lane; c < d.C; c += 64) m = fmaxf(m, z[c]);
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  float sum = 0.0f;
+  for (int c = lane; c < d.C; c += 64) sum += expf(z[c] - m);
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+  for (int c = lane; c < d.C; c += 64) y[c] = expf(z[c] - m) / sum;
+  if (!d.ext)
+    for (int c = d.C + lane; c < d.Cop; c += 64) y[c] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------
+// host-side dispatch
+// ---------------------------------------------------------------------------------
+template <typename F>
+static int go(F kernel, int blocks, int threads, const KArgs& a, hipStream_t s) {
+  if (blocks <= 0) return (int)hipSuccess;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3((unsigned)threads), 0, s, a);
+  return (int)hipGetLastError();
+}
+
+int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& hd) {
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int64_t blocks = 0;
+  for (int i = 0; i < L.n; ++i) blocks += problem_blocks(L.kind, L.tile, hd[(size_t)(L.first_desc + i)], a.batch);
+  if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+  const bool wb = L.wdtype == FI_BF16, ab = L.adtype == FI_BF16;
+  const int nb = (int)blocks;
+  switch (L.kind) {
+    case K_STAGE:
+      if (wb && ab) return go(stage_kernel<bf16_t, bf16_t>, nb, 256, a, s);
+      if (wb) return go(stage_kernel<bf16_t, float>, nb, 256, a, s);
+      return go(stage_kernel<float, float>, nb, 256, a, s);
+    case K_CONV_DIRECT:
+      if (wb && ab) return go(conv_direct_kernel<bf16_t, bf16_t>, nb, 256, a, s);
+      if (wb) return go(conv_direct_kernel<bf16_t, float>, nb, 256, a, s);
+      return go(conv_direct_kernel<float, float>, nb, 256, a, s);
+    case K_CONV_MFMA:
+      if (!(wb && ab)) return (int)hipErrorInvalidValue;
+      if (L.tile == T_128x128) return go(conv_mfma_kernel<128, 128>, nb, 256, a, s);
+      if (L.tile == T_128x64) return go(conv_mfma_kernel<128, 64>, nb, 256, a, s);
+      return go(conv_mfma_kernel<64, 64>, nb, 256, a, s);
+    case K_DWCONV:
+      if (wb && ab) return go(dwconv_kernel<bf16_t, bf16_t>, nb, 256, a, s);
+      if (wb) return go(dwconv_kernel<bf16_t, float>, nb, 256, a, s);
+      return go(dwconv_kernel<float, float>, nb, 256, a, s);
+    case K_MAXPOOL:
+      return ab ? go(maxpool_kernel<bf16_t>, nb, 256, a, s) : go(maxpool_kernel<float>, nb, 256, a, s);
+    case K_GAP:
+      return ab ? go(gap_kernel<bf16_t>, nb, 256, a, s) : go(gap_kernel<float>, nb, 256, a, s);
+    case K_SOFTMAX:
+      return go(softmax_kernel, nb, 64, a, s);
+  }
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace fi

@@ -1,0 +1,204 @@
+// Host-side analysis of one member model: validation, shape inference, the
+// device (packed) weight layout, and the canonical -> packed conversion.
+//
+// Packed layout of a member (all offsets 256-byte aligned, node order):
+//   conv       w [cout][kh][kw][Cp]  each row zero-padded to Kp elements, model dtype
+//   depthwise  w [kh][kw][Cp]        (tap-major, channel innermost), model dtype
+//   fc         w [cout][H][W][Cp]    i.e. the input tensor's NHWC storage order, row padded to Kp
+//   bias       fp32 [Cop]
+// Cp rounds channels up to 8 for bf16 weights (16-byte vectors along C) and to 1 for
+// fp32.  Kp rounds the row up to 32 elements for bf16 so a reduction tile never straddles
+// the end of a row; pad weights are zero, so whatever finite activation sits in a padded
+// channel contributes nothing.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "fi_internal.h"
+
+namespace fi {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+const char* last_error() { return g_err; }
+
+static inline int32_t round_up(int32_t v, int32_t g) { return (v + g - 1) / g * g; }
+
+fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
+  const char* nm = m.name ? m.name : "?";
+  if (m.dtype != FI_F32 && m.dtype != FI_BF16) { set_error("model %s: bad dtype %d", nm, m.dtype); return FI_EINVAL; }
+  if (m.act_dtype != FI_F32 && m.act_dtype != FI_BF16) { set_error("model %s: bad act_dtype %d", nm, m.act_dtype); return FI_EINVAL; }
+  if (m.dtype == FI_F32 && m.act_dtype != FI_F32) { set_error("model %s: fp32 weights need fp32 activations", nm); return FI_EINVAL; }
+  if (m.n_layers <= 0 || !m.layers) { set_error("model %s: no layers", nm); return FI_EINVAL; }
+  if (m.in_c <= 0 || m.in_h <= 0 || m.in_w <= 0) { set_error("model %s: bad input shape", nm); return FI_EINVAL; }
+  if (m.output_node < 0 || m.output_node >= m.n_layers) { set_error("model %s: output_node out of range", nm); return FI_EINVAL; }
+  const int32_t g = m.dtype == FI_BF16 ? 8 : 1;
+  const int32_t kg = m.dtype == FI_BF16 ? 32 : 1;
+  const uint64_t wsz = m.dtype == FI_BF16 ? 2 : 4;
+  out.cgran = g;
+  out.in_cp = round_up(m.in_c, g);
+  out.nodes.assign((size_t)m.n_layers, Node{});
+  uint64_t off = 0;
+  for (int32_t i = 0; i < m.n_layers; ++i) {
+    const fi_layer_spec& L = m.layers[i];
+    Node& n = out.nodes[(size_t)i];
+    n.index = i; n.op = L.op; n.act = L.act; n.input = L.input; n.residual = L.residual;
+    if (L.input != FI_INPUT && (L.input < 0 || L.input >= i)) {
+      set_error("model %s node %d: input %d is not an earlier node (cycle or dangling edge)", nm, i, L.input);
+      return FI_EINVAL;
+    }
+    if (L.residual != FI_NO_RESIDUAL && (L.residual < 0 || L.residual >= i)) {
+      set_error("model %s node %d: residual %d is not an earlier node", nm, i, L.residual);
+      return FI_EINVAL;
+    }
+    if (L.act < FI_ACT_NONE || L.act > FI_ACT_RELU6) { set_error("model %s node %d: bad activation", nm, i); return FI_EINVAL; }
+    if (L.input == FI_INPUT) { n.C = m.in_c; n.H = m.in_h; n.W = m.in_w; n.Cp = out.in_cp; }
+    else { const Node& s = out.nodes[(size_t)L.input]; n.C = s.Co; n.H = s.Ho; n.W = s.Wo; n.Cp = s.Cop; }
+    n.k = 1; n.stride = 1; n.pad = 0;
+    switch (L.op) {
+      case FI_CONV2D:
+      case FI_DWCONV2D:
+        if (L.kh != L.kw || L.kh < 1 || L.stride < 1 || L.pad < 0 || L.cout < 1) {
+          set_error("model %s node %d: unsupported kernel geometry", nm, i); return FI_EUNSUPPORTED; }
+        if (L.cin != n.C) { set_error("model %s node %d: cin %d != producer channels %d", nm, i, L.cin, n.C); return FI_EINVAL; }
+        if (L.op == FI_DWCONV2D && L.cout != L.cin) { set_error("model %s node %d: depthwise needs cin == cout", nm, i); return FI_EINVAL; }
+        n.k = L.kh; n.stride = L.stride; n.pad = L.pad; n.Co = L.cout;
+        n.Ho = (n.H + 2 * L.pad - L.kh) / L.stride + 1;
+        n.Wo = (n.W + 2 * L.pad - L.kh) / L.stride + 1;
+        if (n.Ho < 1 || n.Wo < 1 || n.H + 2 * L.pad < L.kh) { set_error("model %s node %d: empty output", nm, i); return FI_EINVAL; }
+        n.macs = (uint64_t)n.Ho * n.Wo * n.Co * (uint64_t)(L.op == FI_CONV2D ? n.C : 1) * L.kh * L.kh;
+        break;
+      case FI_MAXPOOL2D:
+        if (L.kh != L.kw || L.kh < 1 || L.stride < 1 || L.pad < 0 || 2 * L.pad > L.kh) {
+          set_error("model %s node %d: unsupported pooling geometry", nm, i); return FI_EUNSUPPORTED; }
+        n.k = L.kh; n.stride = L.stride; n.pad = L.pad; n.Co = n.C;
+        n.Ho = (n.H + 2 * L.pad - L.kh) / L.stride + 1;
+        n.Wo = (n.W + 2 * L.pad - L.kh) / L.stride + 1;
+        if (n.Ho < 1 || n.Wo < 1 || n.H + 2 * L.pad < L.kh) { set_error("model %s node %d: empty output", nm, i); return FI_EINVAL; }
+        if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: pooling takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
+        break;
+      case FI_GLOBAL_AVGPOOL:
+        n.Co = n.C; n.Ho = 1; n.Wo = 1;
+        if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: pooling takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
+        break;
+      case FI_FC:
+        if (L.cout < 1) { set_error("model %s node %d: bad cout", nm, i); return FI_EINVAL; }
+        if (L.cin != n.C * n.H * n.W) { set_error("model %s node %d: fc cin %d != %d*%d*%d", nm, i, L.cin, n.C, n.H, n.W); return FI_EINVAL; }
+        n.Co = L.cout; n.Ho = 1; n.Wo = 1;
+        n.macs = (uint64_t)L.cout * L.cin;
+        break;
+      case FI_SOFTMAX:
+        if (n.H != 1 || n.W != 1) { set_error("model %s node %d: softmax needs a 1x1 input", nm, i); return FI_EUNSUPPORTED; }
+        if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: softmax takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
+        n.Co = n.C; n.Ho = 1; n.Wo = 1;
+        break;
+      default:
+        set_error("model %s node %d: unknown op %d", nm, i, L.op);
+        return FI_EUNSUPPORTED;
+    }
+    n.Cop = round_up(n.Co, g);
+    if (L.residual != FI_NO_RESIDUAL) {
+      const Node& r = out.nodes[(size_t)L.residual];
+      if (r.Co != n.Co || r.Ho != n.Ho || r.Wo != n.Wo) {
+        set_error("model %s node %d: residual shape mismatch", nm, i); return FI_EINVAL; }
+    }
+    // packed weight placement
+    n.w_rel = n.b_rel = kNone;
+    uint64_t wbytes = 0;
+    if (L.op == FI_CONV2D) { n.Kp = round_up(n.k * n.k * n.Cp, kg); wbytes = (uint64_t)n.Co * n.Kp * wsz; }
+    else if (L.op == FI_FC) { n.Kp = round_up(n.H * n.W * n.Cp, kg); wbytes = (uint64_t)n.Co * n.Kp * wsz; }
+    else if (L.op == FI_DWCONV2D) { n.Kp = n.k * n.k; wbytes = (uint64_t)n.k * n.k * n.Cp * wsz; }
+    if (wbytes) {
+      n.w_rel = off; off = align_up(off + wbytes);
+      n.b_rel = off; off = align_up(off + (uint64_t)n.Cop * 4);
+      // canonical blob bounds
+      const uint64_t cw = (L.op == FI_CONV2D ? (uint64_t)n.Co * n.C * n.k * n.k
+                           : L.op == FI_FC  ? (uint64_t)n.Co * L.cin : (uint64_t)n.Co * n.k * n.k) * wsz;
+      if (!m.weights_packed && m.weights &&
+          (L.w_off + cw > m.weight_bytes || L.b_off + (uint64_t)n.Co * 4 > m.weight_bytes)) {
+        set_error("model %s node %d: weight/bias offsets run past the blob", nm, i); return FI_EINVAL; }
+    }
+  }
+  // stored dtype of every node: fp32 for the output node, softmax nodes and an fc that
+  // feeds only softmax nodes; the member's act_dtype otherwise
+  for (int32_t i = 0; i < m.n_layers; ++i) {
+    Node& n = out.nodes[(size_t)i];
+    n.out_dtype = m.act_dtype;
+    n.is_output = (i == m.output_node);
+    if (n.is_output || n.op == FI_SOFTMAX) n.out_dtype = FI_F32;
+    if (n.op == FI_FC) {
+      bool any = false, all_sm = true;
+      for (int32_t j = i + 1; j < m.n_layers; ++j)
+        if (m.layers[j].input == i || m.layers[j].residual == i) { any = true; if (m.layers[j].op != FI_SOFTMAX) all_sm = false; }
+      if (any && all_sm) n.out_dtype = FI_F32;
+    }
+    if (n.op == FI_SOFTMAX && out.nodes[(size_t)n.input].out_dtype != FI_F32) {
+      set_error("model %s node %d: softmax input must be an fc that feeds only softmax", nm, i); return FI_EUNSUPPORTED; }
+    if (n.out_dtype == FI_F32 && m.act_dtype != FI_F32 && !n.is_output && n.op != FI_SOFTMAX && n.op != FI_FC) {
+      set_error("model %s node %d: internal error (dtype rule)", nm, i); return FI_EINVAL; }
+  }
+  // an fp32-stored fc/softmax value consumed by anything but softmax/nothing is not supported
+  for (int32_t j = 0; j < m.n_layers; ++j) {
+    const fi_layer_spec& L = m.layers[j];
+    for (int32_t src : {L.input, L.residual}) {
+      if (src < 0) continue;
+      const Node& s = out.nodes[(size_t)src];
+      if (s.out_dtype == FI_F32 && m.act_dtype != FI_F32 && L.op != FI_SOFTMAX) {
+        set_error("model %s node %d: consumes the fp32 output node %d", nm, j, src); return FI_EUNSUPPORTED; }
+    }
+  }
+  out.packed_bytes = align_up(off ? off : kAlign);
+  return FI_OK;
+}
+
+static inline float bf16_to_float(uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; std::memcpy(&f, &u, 4); return f; }
+
+// Canonical (OIHW, model dtype) -> packed.  Pure data movement: elements are copied, never
+// converted, and padding is zero-filled.
+void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst) {
+  const size_t wsz = m.dtype == FI_BF16 ? 2 : 4;
+  const uint8_t* src = static_cast<const uint8_t*>(m.weights);
+  std::memset(dst, 0, (size_t)p.packed_bytes);
+  for (int32_t i = 0; i < m.n_layers; ++i) {
+    const Node& n = p.nodes[(size_t)i];
+    if (n.w_rel == kNone) continue;
+    const fi_layer_spec& L = m.layers[i];
+    const uint8_t* w = src + L.w_off;
+    uint8_t* d = dst + n.w_rel;
+    if (n.op == FI_CONV2D) {
+      for (int32_t o = 0; o < n.Co; ++o)
+        for (int32_t c = 0; c < n.C; ++c)
+          for (int32_t r = 0; r < n.k; ++r)
+            for (int32_t s = 0; s < n.k; ++s) {
+              const size_t from = (((size_t)o * n.C + c) * n.k + r) * n.k + s;
+              const size_t to = (size_t)o * n.Kp + ((size_t)r * n.k + s) * n.Cp + c;
+              std::memcpy(d + to * wsz, w + from * wsz, wsz);
+            }
+    } else if (n.op == FI_FC) {
+      // canonical column index runs over (c, h, w); packed over (h, w, c) with stride Cp
+      const int32_t HW = n.H * n.W;
+      for (int32_t o = 0; o < n.Co; ++o) {
+        const uint8_t* wr = w + (size_t)o * n.C * HW * wsz;
+        uint8_t* dr = d + (size_t)o * n.Kp * wsz;
+        if (HW == 1) { std::memcpy(dr, wr, (size_t)n.C * wsz); continue; }
+        for (int32_t c = 0; c < n.C; ++c)
+          for (int32_t q = 0; q < HW; ++q)
+            std::memcpy(dr + ((size_t)q * n.Cp + c) * wsz, wr + ((size_t)c * HW + q) * wsz, wsz);
+      }
+    } else {  // depthwise: [c][0][r][s] -> [r][s][c]
+      for (int32_t c = 0; c < n.C; ++c)
+        for (int32_t t = 0; t < n.k * n.k; ++t)
+          std::memcpy(d + ((size_t)t * n.Cp + c) * wsz, w + ((size_t)c * n.k * n.k + t) * wsz, wsz);
+    }
+    std::memcpy(dst + n.b_rel, src + L.b_off, (size_t)n.Co * 4);
+  }
+  (void)bf16_to_float;
+}
+
+}  // namespace fi

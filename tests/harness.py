@@ -1,0 +1,96 @@
+"""Shared helpers of the GPU parity tests: run member models through the C-ABI
+library on cuda:0 (torch supplies memory and the stream only) and through the
+CPU oracle, on the same seeded inputs."""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+
+import oracle
+import paper_2410_21120_amd as fi
+from workloads import gen
+
+CORES = min(16, os.cpu_count() or 1)
+
+
+def rel_l2(a, ref):
+    a = np.asarray(a, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-30))
+
+
+class GpuDag:
+    """Builds one fused DAG from (model, blob[, act_dtype]) members and runs it."""
+
+    def __init__(self, members, max_batch, group_levels=True, load_mode=fi.FI_LOAD_ONE_COPY, packed=False):
+        import torch
+        self.torch = torch
+        self.alloc = fi.TorchAllocators("cuda:0")
+        self.models = [m[0] for m in members]
+        specs, keep = [], []
+        for mem in members:
+            model, blob = mem[0], mem[1]
+            act = mem[2] if len(mem) > 2 else None
+            spec, k = fi.make_spec(model, blob.ctypes.data, blob.nbytes, act_dtype=act, packed=packed)
+            specs.append(spec)
+            keep.append((k, blob))
+        self.dag = fi.Dag(specs, max_batch, self.alloc, group_levels=group_levels, load_mode=load_mode, keepalive=keep)
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.dag.load(self.stream)
+        self.out_elems = [L.cout * L.out_h * L.out_w for L in (m.layers[m.output] for m in self.models)]
+
+    def run(self, x_nchw, profile=False):
+        """x_nchw: logical fp32 batch (already rounded to the model dtype). Returns per-member fp32 arrays
+        [batch, out_h*out_w*out_c] (NHWC order)."""
+        torch = self.torch
+        dtype = self.models[0].dtype
+        st = gen.to_nhwc_storage(x_nchw, dtype)
+        xin = torch.from_numpy(st.view(np.int16) if dtype == "bf16" else st).cuda()
+        b = x_nchw.shape[0]
+        outs = [torch.full((b, n), float("nan"), dtype=torch.float32, device="cuda:0") for n in self.out_elems]
+        ptrs = [o.data_ptr() for o in outs]
+        if profile:
+            ms = self.dag.profile(xin.data_ptr(), b, ptrs, self.stream)
+        else:
+            self.dag.run(xin.data_ptr(), b, ptrs, self.stream)
+            ms = None
+        torch.cuda.synchronize()
+        res = [o.cpu().numpy() for o in outs]
+        return (res, ms) if profile else res
+
+    def close(self):
+        self.dag.unload()
+        self.dag.destroy()
+
+
+def oracle_nhwc(model, blob, x_nchw, round_storage, node=None):
+    """Oracle output of `node` reordered to the library's [batch, h*w*c] output order."""
+    node = model.output if node is None else node
+    L = model.layers[node]
+    y = oracle.run_model(model, blob, x_nchw, round_storage=round_storage, node=node)
+    b = x_nchw.shape[0]
+    return y.reshape(b, L.cout, L.out_h, L.out_w).transpose(0, 2, 3, 1).reshape(b, -1)
+
+
+def oracle_units(units):
+    """units: (model, blob, x_nchw, round_storage) -> list of [batch, classes] arrays, run on CORES threads."""
+    return oracle.run_models_parallel(units, threads=CORES)
+
+
+def check_top1(z_gpu, z_ref):
+    """Top-1 must agree unless the reference's top-1/top-2 margin is inside the observed error (then the
+    GPU's pick must be one of the reference's two best).  Returns (identical, near_ties)."""
+    ident = ties = 0
+    for g, r in zip(z_gpu, z_ref):
+        tg, tr = int(oracle.top1(g[None])[0]), int(oracle.top1(r[None])[0])
+        if tg == tr:
+            ident += 1
+            continue
+        order = np.argsort(-r, kind="stable")
+        margin = r[order[0]] - r[order[1]]
+        err = np.abs(g - r).max()
+        assert margin < 4 * err and tg in (int(order[0]), int(order[1])), \
+            f"top-1 differs beyond a near tie: gpu {tg}, ref {tr}, margin {margin}, err {err}"
+        ties += 1
+    return ident, ties

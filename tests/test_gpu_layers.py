@@ -1,0 +1,130 @@
+"""Per-kernel GPU parity against the CPU oracle on small seeded shapes that span
+several tiles and ragged tails (odd sizes, stride 2, padding edges, channel
+counts that are not multiples of the tile)."""
+import numpy as np
+import pytest
+
+from workloads import gen, zoo
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = 1e-2   # relative L2 vs the fp32-activation oracle (mode F)
+F32_TOL = 1e-4
+
+
+
+
+def _run_case(model, seed, batch, act_dtype=None, tol=None, bias_std=0.1):
+    from tests import harness
+    model.shapes()
+    blob = gen.make_blob(model, seed, bias_std=bias_std)
+    x = gen.make_input(seed + 1, batch, model.in_c, model.in_h, model.in_w, "normal", model.dtype)
+    g = harness.GpuDag([(model, blob, act_dtype)], batch)
+    try:
+        y = g.run(x)[0]
+    finally:
+        g.close()
+    wide = (model.dtype == "f32") or act_dtype == "f32"
+    ref_f = harness.oracle_nhwc(model, blob, x, False)
+    assert y.shape == ref_f.shape
+    assert np.isfinite(y).all()
+    e = harness.rel_l2(y, ref_f)
+    lim = tol if tol is not None else (F32_TOL if wide else BF16_TOL)
+    assert e <= lim, f"rel L2 {e} > {lim}"
+    if not wide:
+        ref_s = harness.oracle_nhwc(model, blob, x, True)
+        assert harness.rel_l2(y, ref_s) <= 2e-3
+    return e
+
+
+CONV_CASES = [  # cin, cout, k, stride, pad, H, W, batch
+    (3, 16, 3, 1, 1, 32, 32, 1), (3, 64, 7, 2, 3, 37, 41, 2), (16, 24, 1, 1, 0, 17, 19, 3), (24, 144, 1, 1, 0, 28, 28, 2),
+    (64, 64, 3, 1, 1, 14, 14, 2), (32, 160, 3, 2, 1, 15, 15, 3), (128, 256, 3, 2, 1, 9, 9, 2), (72, 40, 3, 1, 0, 11, 13, 1),
+    (256, 512, 1, 2, 0, 14, 14, 2), (8, 8, 3, 1, 1, 5, 5, 1), (320, 1280, 1, 1, 0, 7, 7, 2), (64, 192, 3, 1, 1, 56, 56, 1),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_conv_relu(case, mode):
+    cin, cout, k, s, p, h, w, b = case
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("c", dtype, cin, h, w)
+    m.add(zoo.CONV, -1, cin=cin, cout=cout, k=k, stride=s, pad=p, act=zoo.RELU)
+    _run_case(m, 100 + cin + cout, b, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+@pytest.mark.parametrize("act", [zoo.NONE, zoo.RELU, zoo.RELU6])
+def test_conv_residual_and_activation(mode, act):
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("r", dtype, 16, 13, 13)
+    a = m.add(zoo.CONV, -1, cin=16, cout=40, k=3, stride=1, pad=1, act=zoo.RELU)
+    b = m.add(zoo.CONV, a, cin=40, cout=40, k=1, stride=1, pad=0, act=zoo.NONE)
+    m.add(zoo.CONV, b, cin=40, cout=40, k=3, stride=1, pad=1, act=act, residual=a)
+    _run_case(m, 7, 2, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+@pytest.mark.parametrize("case", [(32, 3, 1, 1, 20, 20, 2), (96, 3, 2, 1, 15, 17, 2), (144, 3, 1, 1, 7, 7, 3), (24, 3, 2, 1, 9, 9, 1)])
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_depthwise(case, mode):
+    c, k, s, p, h, w, b = case
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("d", dtype, c, h, w)
+    m.add(zoo.DWCONV, -1, cin=c, cout=c, k=k, stride=s, pad=p, act=zoo.RELU6)
+    _run_case(m, 200 + c, b, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+@pytest.mark.parametrize("case", [(64, 3, 2, 1, 23, 23, 2), (16, 2, 2, 0, 32, 32, 1), (24, 2, 2, 0, 15, 17, 3)])
+@pytest.mark.parametrize("mode", ["bf16", "f32"])
+def test_maxpool_exact(case, mode):
+    """Pooling moves values without arithmetic: the result is bit-exact."""
+    from tests import harness
+    c, k, s, p, h, w, b = case
+    m = zoo.Model("p", mode, c, h, w)
+    m.add(zoo.MAXPOOL, -1, k=k, stride=s, pad=p)
+    m.shapes()
+    blob = np.zeros(64, np.uint8)
+    x = -np.abs(gen.make_input(3, b, c, h, w, "normal", mode)) - 1.0  # all negative: padding must not win
+    if mode == "bf16":
+        x = gen.bf16_to_f32(gen.bf16_bits(x)).reshape(x.shape)
+    g = harness.GpuDag([(m, blob)], b)
+    try:
+        y = g.run(x)[0]
+    finally:
+        g.close()
+    assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, False))
+
+
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_gap_fc_softmax_chain(mode):
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("g", dtype, 24, 7, 9)
+    a = m.add(zoo.GAP, -1)
+    a = m.add(zoo.FC, a, cin=24, cout=50, act=zoo.RELU)
+    a = m.add(zoo.FC, a, cin=50, cout=10)
+    m.add(zoo.SOFTMAX, a)
+    e = _run_case(m, 31, 5, act_dtype="f32" if mode == "bf16_wide" else None)
+    assert e < 5e-3
+
+
+def test_fc_on_spatial_input_bf16():
+    """FC over a flattened C,H,W tensor (the 25088-input layer shape, scaled down)."""
+    m = zoo.Model("f", "bf16", 40, 7, 7)
+    m.add(zoo.FC, -1, cin=40 * 49, cout=130, act=zoo.RELU)
+    _run_case(m, 5, 8)
+
+
+def test_batch_smaller_than_max_batch():
+    from tests import harness
+    m = zoo.resnet18(hw=64)
+    blob = gen.make_blob(m, 1000)
+    x = gen.make_input(7, 4, 3, 64, 64, "normal", "bf16")
+    g = harness.GpuDag([(m, blob)], 4)
+    try:
+        full = g.run(x)[0]
+        part = g.run(x[:3])[0]
+        one = g.run(x[2:3])[0]
+    finally:
+        g.close()
+    assert np.array_equal(full[:3], part) and np.array_equal(full[2:3], one)
