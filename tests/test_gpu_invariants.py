@@ -1,0 +1,97 @@
+"""Method invariants on the GPU (Section III-A C1/C4, Section IV-C): a member's output in a
+fused DAG equals, bit for bit, the member run alone; changing or removing a co-member changes
+no bit of it; permuting members permutes outputs; grouped and ungrouped schedules agree."""
+import numpy as np
+import pytest
+
+from workloads import gen, zoo
+
+pytestmark = pytest.mark.gpu
+
+
+def _members(hw=64):
+    fams = [("resnet18", None), ("mobilenetv2", None), ("vgg16", None), ("resnet50", None), ("mobilenetv2", "f32")]
+    out = []
+    for i, (f, act) in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=hw)
+        out.append((m, gen.make_blob(m, 1000 + i), act))
+    return out
+
+
+def _run(mem, x, **kw):
+    from tests import harness
+    g = harness.GpuDag(mem, x.shape[0], **kw)
+    try:
+        return g.run(x)
+    finally:
+        g.close()
+
+
+def test_fused_equals_alone_bitwise():
+    mem = _members()
+    x = gen.make_input(7, 3, 3, 64, 64, "normal", "bf16")
+    fused = _run(mem, x)
+    for i, mb in enumerate(mem):
+        alone = _run([mb], x)[0]
+        assert np.array_equal(fused[i], alone), f"member {i} differs from itself alone"
+
+
+def test_isolation_and_permutation():
+    mem = _members()
+    x = gen.make_input(7, 2, 3, 64, 64, "normal", "bf16")
+    base = _run(mem, x)
+    # perturb member 1's weights: nobody else moves
+    m1 = (mem[1][0], gen.make_blob(mem[1][0], 4242), mem[1][2])
+    pert = _run([mem[0], m1] + mem[2:], x)
+    for i in range(len(mem)):
+        if i == 1:
+            assert not np.array_equal(base[i], pert[i])
+        else:
+            assert np.array_equal(base[i], pert[i])
+    # remove member 2
+    less = _run(mem[:2] + mem[3:], x)
+    assert all(np.array_equal(a, b) for a, b in zip(less, base[:2] + base[3:]))
+    # permutation
+    order = [3, 0, 4, 2, 1]
+    perm = _run([mem[i] for i in order], x)
+    for slot, i in enumerate(order):
+        assert np.array_equal(perm[slot], base[i])
+
+
+def test_grouped_equals_ungrouped_and_load_modes():
+    import paper_2410_21120_amd as fi
+    mem = _members()[:3]
+    x = gen.make_input(7, 2, 3, 64, 64, "normal", "bf16")
+    a = _run(mem, x, group_levels=True)
+    b = _run(mem, x, group_levels=False)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    # repository-time packing + per-model copies give the same bits as pack-at-build + one copy
+    import torch
+    packed = []
+    for (m, blob, act) in mem:
+        spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        n = fi.fi_model_packed_size(spec)
+        t = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+        fi.fi_model_pack(spec, t.data_ptr(), n)
+        packed.append((m, t.numpy(), act))
+    for mode in (fi.FI_LOAD_ONE_COPY, fi.FI_LOAD_PER_MODEL):
+        c = _run(packed, x, load_mode=mode, packed=True)
+        assert all(np.array_equal(u, v) for u, v in zip(a, c))
+
+
+def test_launch_counts_and_single_allocation():
+    from tests import harness
+    ms = []
+    for i in range(4):
+        m = zoo.resnet50(hw=64)
+        ms.append((m, gen.make_blob(m, 1000 + i), None))
+    g = harness.GpuDag(ms, 2)
+    try:
+        q = g.dag.query()
+        assert q.n_device_allocs == 1 and q.n_h2d_copies == 1 and q.state == 1
+        assert g.alloc.n_dev == 1 and g.alloc.n_pin == 1
+        assert q.n_nodes == 4 * 56 and q.n_levels == 52
+        # staging + one grouped launch per level (one more where members' shapes pick different tiles)
+        assert 53 <= q.n_launches <= 57
+    finally:
+        g.close()
