@@ -81,6 +81,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             _build.build()
+        # One HIP runtime per process: PyTorch (which owns the device memory and the streams we are
+        # handed) ships its own libamdhip64; import it first so the library binds to that same runtime
+        # instead of pulling a second copy in from the system ROCm.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i32, u64 = C.c_void_p, C.c_int32, C.c_uint64
         L.fi_model_packed_size.argtypes = [C.POINTER(fi_model_spec), C.POINTER(u64)]

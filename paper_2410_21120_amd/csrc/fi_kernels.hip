@@ -131,16 +131,31 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
 //   rows  m = (n, p, q) output pixels      M = batch*Ho*Wo
 //   cols  o = output channel               N = Co
 //   red.  kk = (r, s, c), c innermost      K = k*k*Cp, weight rows padded to Kp (x32)
-// A (input patches) and B (weights) tiles of 32 reduction elements are staged through LDS
-// with 16-byte vectors; each of the 4 waves owns a (BM/2)x(BN/2) sub-tile built from
-// 32x32x16 bf16 MFMAs with fp32 accumulation.  Epilogue: + bias (+ residual) -> activation
-// -> one round-to-nearest-even to bf16.
+// A (input patches) and B (weights) tiles of 32 reduction elements are fetched with 16-byte
+// vectors into registers one tile ahead, parked in a double-buffered LDS stage, and consumed
+// by 32x32x16 bf16 MFMAs with fp32 accumulation; each of the 4 waves owns a (BM/2)x(BN/2)
+// sub-tile.  The epilogue transposes the accumulators through LDS (fp32) so that bias,
+// residual, activation and the single round-to-nearest-even to bf16 run on 8 consecutive
+// channels per thread with 16-byte coalesced residual loads and output stores.
+// Workgroups are renumbered so that each XCD (blockIdx % 8) owns one contiguous run of
+// tiles: neighbouring tiles, which share input rows and a member's weights, meet in one L2.
 // ---------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BK = 32;
 constexpr int LDS_STRIDE = BK + 8;  // elements; 80-byte rows keep 16-byte reads conflict-free
+constexpr int NXCD = 8;
+
+__device__ __forceinline__ int xcd_contiguous(int bid, int total) {
+  const int c = total / NXCD, r = total % NXCD;
+  const int x = bid % NXCD, j = bid / NXCD;
+  return x * c + (x < r ? x : r) + j;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
 
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
@@ -148,12 +163,20 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
   constexpr int WTM = BM / 2, WTN = BN / 2;  // per-wave sub-tile
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int AR = BM / 64, BR = BN / 64;  // rows each thread stages per tile
+  constexpr int STAGE = (BM + BN) * LDS_STRIDE;            // bf16 elements per LDS stage
+  constexpr int EPS = BN + 8;                              // fp32 row stride of the epilogue tile
+  constexpr int SMEM = 2 * STAGE * 2 > 64 * EPS * 4 ? 2 * STAGE * 2 : 64 * EPS * 4;
+  __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
+  bf16_t* const lds = reinterpret_cast<bf16_t*>(smem);
 
-  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_STRIDE];
-
-  int p, bid;
-  if (!find_problem(a, K_CONV_MFMA, TILE, p, bid)) return;
+  // locate the problem and the tile (block-uniform)
+  int p = 0, bid = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
+  for (; p < a.n; ++p) {
+    const int t = problem_blocks(K_CONV_MFMA, TILE, a.descs[p], a.batch);
+    if (bid < t) break;
+    bid -= t;
+  }
+  if (p == a.n) return;
   const Desc d = a.descs[p];
   const int M = a.batch * d.Ho * d.Wo;
   const int m0 = (bid / d.tiles_n) * BM;
@@ -170,17 +193,16 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
   const int srow = tid >> 2, kvec = (tid & 3) * 8;
   int a_ih0[AR], a_iw0[AR];
   int64_t a_base[AR];
-  bool a_ok[AR];
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int m = m0 + srow + 64 * i;
-    a_ok[i] = m < M;
-    const int mm = a_ok[i] ? m : 0;
+    const bool ok = m < M;
+    const int mm = ok ? m : 0;
     const int q = mm % d.Wo;
     const int t = mm / d.Wo;
     const int pp = t % d.Ho;
     const int n = t / d.Ho;
-    a_ih0[i] = pp * d.stride - d.pad;
+    a_ih0[i] = ok ? pp * d.stride - d.pad : -(1 << 20);  // rows past M read as zero
     a_iw0[i] = q * d.stride - d.pad;
     a_base[i] = (int64_t)n * d.H * d.W * d.Cp;
   }
@@ -203,28 +225,38 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  const int ntiles = d.Kp / BK;
-  for (int kt = 0; kt < ntiles; ++kt) {
-    uint4 av[AR], bv[BR];
+  uint4 av[AR], bv[BR];
+  auto fetch = [&](int kt) {
 #pragma unroll
     for (int i = 0; i < AR; ++i) {
       const int ih = a_ih0[i] + kr, iw = a_iw0[i] + ks;
       av[i] = make_uint4(0, 0, 0, 0);
-      if (a_ok[i] && kr < d.k && ih >= 0 && ih < d.H && iw >= 0 && iw < d.W)
+      if (kr < d.k && ih >= 0 && ih < d.H && iw >= 0 && iw < d.W)
         av[i] = *reinterpret_cast<const uint4*>(x + a_base[i] + ((int64_t)ih * d.W + iw) * d.Cp + kc);
     }
 #pragma unroll
     for (int i = 0; i < BR; ++i) bv[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + (int64_t)kt * BK);
     kc += BK;
     while (kc >= d.Cp) { kc -= d.Cp; if (++ks == d.k) { ks = 0; ++kr; } }
-
-    __syncthreads();  // previous tile fully consumed
+  };
+  auto park = [&](int buf) {
+    bf16_t* As = lds + buf * STAGE;
+    bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
     for (int i = 0; i < AR; ++i) *reinterpret_cast<uint4*>(&As[(srow + 64 * i) * LDS_STRIDE + kvec]) = av[i];
 #pragma unroll
     for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + 64 * i) * LDS_STRIDE + kvec]) = bv[i];
-    __syncthreads();
+  };
 
+  const int ntiles = d.Kp / BK;
+  fetch(0);
+  park(0);
+  __syncthreads();
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const bool more = kt + 1 < ntiles;
+    if (more) fetch(kt + 1);  // in flight while this tile is multiplied
+    const bf16_t* As = lds + (kt & 1) * STAGE;
+    const bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 af[MI], bfr[NI];
@@ -241,37 +273,66 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    if (more) park((kt + 1) & 1);
+    __syncthreads();
   }
 
-  // epilogue
+  // ---- epilogue: 64 output rows per pass through an fp32 LDS tile ----------------------
+  float* ep = reinterpret_cast<float*>(smem);
   const float* bias = reinterpret_cast<const float*>(a.wbase + d.b_off);
   const bf16_t* res = d.r_off != kNone ? reinterpret_cast<const bf16_t*>(a.abase + d.r_off) : nullptr;
 #pragma unroll
-  for (int j = 0; j < NI; ++j) {
-    const int o = n0 + wn * WTN + j * 32 + (lane & 31);
-    if (o >= d.Cop) continue;
-    const bool real = o < d.Co;
-    const float bo = real ? bias[o] : 0.0f;
+  for (int pass = 0; pass < BM / 64; ++pass) {
+    if (pass > 0) __syncthreads();
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i) {
+      const int rb = wm * WTM + i * 32;  // first row of this MFMA block inside the tile
+      if (rb / 64 != pass) continue;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (m >= M) continue;
-        float v = 0.0f;
-        if (real) {
-          v = acc[i][j][e] + bo;
-          if (res) v += bf2f(res[(int64_t)m * d.Cop + o]);
-          v = activate(v, d.act);
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int lr = rb - pass * 64 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+          ep[lr * EPS + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
         }
-        if (d.ext) {
-          if (real) static_cast<float*>(a.ext_out[p])[(int64_t)m * d.Co + o] = v;
-        } else if (d.out_f32) {
-          reinterpret_cast<float*>(a.abase + d.y_off)[(int64_t)m * d.Cop + o] = v;
-        } else {
-          reinterpret_cast<bf16_t*>(a.abase + d.y_off)[(int64_t)m * d.Cop + o] = f2bf(v);
-        }
+    }
+    __syncthreads();
+    for (int c = tid; c < 64 * (BN / 8); c += 256) {
+      const int lr = c / (BN / 8), cc = (c % (BN / 8)) * 8;
+      const int m = m0 + pass * 64 + lr, o = n0 + cc;
+      if (m >= M || o >= d.Cop) continue;
+      float v[8];
+      const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
+      const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
+      const float4 b0 = *reinterpret_cast<const float4*>(bias + o);
+      const float4 b1 = *reinterpret_cast<const float4*>(bias + o + 4);
+      v[0] = v0.x + b0.x; v[1] = v0.y + b0.y; v[2] = v0.z + b0.z; v[3] = v0.w + b0.w;
+      v[4] = v1.x + b1.x; v[5] = v1.y + b1.y; v[6] = v1.z + b1.z; v[7] = v1.w + b1.w;
+      if (res) {
+        const uint4 r = *reinterpret_cast<const uint4*>(res + (int64_t)m * d.Cop + o);
+        v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xFFFF0000u);
+        v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xFFFF0000u);
+        v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
+        v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
       }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = (o + i < d.Co) ? activate(v[i], d.act) : 0.0f;  // pad channels hold zero
+      if (d.ext) {
+        float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)m * d.Co + o;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (o + i < d.Co) y[i] = v[i];
+      } else if (d.out_f32) {
+        float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o;
+        *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      } else {
+        uint4 pk;
+        pk.x = pack_bf16x2(v[0], v[1]); pk.y = pack_bf16x2(v[2], v[3]);
+        pk.z = pack_bf16x2(v[4], v[5]); pk.w = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o) = pk;
+      }
+    }
   }
 }
 

@@ -1,0 +1,230 @@
+"""CPU-only tests of the library's host side: the C-ABI loads and exports every declared
+symbol, DAG compilation (union, levels, grouping), the weight-arena and activation-arena
+planners, packing, the state machine and the error paths.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2410_21120_amd as fi
+from workloads import gen, zoo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _build(fams, batch, hw=64, group=True, act=None, seed0=1000, **kw):
+    alloc = fi.HostAllocators()
+    specs, keep, models = [], [], []
+    for i, f in enumerate(fams):
+        m = zoo.tiny_cnn() if f == "tiny" else zoo.FAMILIES[f](hw=hw)
+        blob = gen.make_blob(m, seed0 + i)
+        s, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        specs.append(s)
+        keep.append((k, blob))
+        models.append(m)
+    return fi.Dag(specs, batch, alloc, group_levels=group, keepalive=keep, **kw), models, alloc
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fusedinf.h")).read()
+    declared = set(re.findall(r"\b(fi_[a-z_0-9]+)\s*\(", header))
+    declared -= {"fi_dag"}
+    assert declared == set(fi.EXPORTS)
+    lib = C.CDLL(fi.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert fi.fi_version().startswith("fusedinf")
+
+
+def test_union_levels_and_operator_count():
+    """The DAG is the disjoint union of the members: node count = sum of node counts, per-member
+    levels equal the member's own depth (Algorithm 1, compilation loop; Section IV-C: the DAG holds
+    exactly the members' operators)."""
+    fams = ["resnet50", "mobilenetv2", "vgg16", "resnet18"]
+    d, models, _ = _build(fams, 2)
+    q = d.query()
+    assert q.n_models == 4 and q.n_nodes == sum(len(m.layers) for m in models)
+    assert q.n_levels == max(max(m.levels()) for m in models)
+    assert q.macs_per_image == sum(m.macs() for m in models)
+    nodes = d.nodes()
+    k = 0
+    for mi, m in enumerate(models):
+        lv = m.levels()
+        for i, L in enumerate(m.layers):
+            n = nodes[k]
+            assert (n.model, n.index, n.level) == (mi, i, lv[i])
+            assert (n.out_c, n.out_h, n.out_w) == (L.cout, L.out_h, L.out_w)
+            assert n.is_output == (i == m.output)
+            k += 1
+    # every launch is homogeneous in level and holds at most FI_MAX_GROUP problems from distinct nodes
+    launches = d.launches()
+    seen = set()
+    for li, L in enumerate(launches):
+        assert 1 <= L.n_problems <= fi.FI_MAX_GROUP
+        members = [n for n in nodes if n.launch == li and not (L.level == 0)]
+        if L.level > 0:
+            assert len(members) == L.n_problems and all(n.level == L.level for n in members)
+            for n in members:
+                assert (n.model, n.index) not in seen
+                seen.add((n.model, n.index))
+    assert len(seen) == q.n_nodes
+    assert [L.level for L in launches] == sorted(L.level for L in launches)
+
+
+def test_grouping_reduces_launches_only():
+    fams = ["resnet50"] * 8
+    g, _, _ = _build(fams, 4)
+    u, _, _ = _build(fams, 4, group=False)
+    qg, qu = g.query(), u.query()
+    assert qu.n_launches == 1 + qu.n_nodes
+    assert qg.n_launches <= 1 + qg.n_levels + 8 and qg.n_nodes == qu.n_nodes
+    assert qg.arena_bytes == qu.arena_bytes + (0)  # same weights either way (tables are per node)
+    assert qg.act_bytes == qu.act_bytes
+
+
+def test_activation_arena_liveness_non_overlap():
+    for fams in (["resnet50", "mobilenetv2", "vgg16"], ["resnet18"] * 3, ["tiny", "tiny"]):
+        d, _, _ = _build(fams, 3, hw=64 if fams[0] != "tiny" else 32)
+        q = d.query()
+        nodes = [n for n in d.nodes() if n.out_bytes]
+        for n in nodes:
+            assert n.out_off % 256 == 0 and n.out_off + n.out_bytes <= q.act_bytes
+            assert n.first_level == n.level and n.last_level >= n.level
+        for i, a in enumerate(nodes):
+            for b in nodes[i + 1:]:
+                if a.first_level <= b.last_level and b.first_level <= a.last_level:  # alive together
+                    assert a.out_off + a.out_bytes <= b.out_off or b.out_off + b.out_bytes <= a.out_off
+        # reuse happens: the arena is smaller than the sum of all tensors
+        assert q.act_bytes < sum(n.out_bytes for n in nodes) or len(nodes) < 8
+
+
+def test_consumers_extend_live_ranges():
+    d, models, _ = _build(["resnet18"], 1)
+    nodes = d.nodes()
+    m = models[0]
+    for i, L in enumerate(m.layers):
+        for src in (L.input, L.residual):
+            if src >= 0:
+                assert nodes[src].last_level >= nodes[i].level
+
+
+def test_weight_arena_layout_and_one_copy_accounting():
+    d, models, alloc = _build(["resnet18", "vgg16"], 1, hw=32)
+    q = d.query()
+    assert q.n_device_allocs == 1 and q.n_h2d_copies == 1 and alloc.n_pin == 1
+    assert q.device_bytes == q.arena_bytes + q.act_bytes + q.workspace_bytes
+    spans = sorted((n.w_off, n.b_off) for n in d.nodes() if n.op in (fi.FI_CONV2D, fi.FI_FC, fi.FI_DWCONV2D))
+    flat = [v for s in spans for v in s]
+    assert flat == sorted(flat) and all(v % 256 == 0 and v < q.arena_bytes for v in flat)
+    d2, _, _ = _build(["resnet18", "vgg16"], 1, hw=32)
+    assert d2.query().arena_bytes == q.arena_bytes  # deterministic
+
+
+def test_pack_is_a_permutation_with_zero_padding():
+    m = zoo.mobilenetv2(hw=32)
+    blob = gen.make_blob(m, 5)
+    spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    n = fi.fi_model_packed_size(spec)
+    dst = np.full(n, 0xAB, np.uint8)
+    fi.fi_model_pack(spec, dst.ctypes.data, n)
+    pk = dst.view(np.uint16)
+    # first conv: 3 -> 32, k3: packed rows [o][r][s][c padded to 8], row length 72 -> 96
+    L = m.layers[0]
+    w = blob[L.w_off:L.w_off + 2 * 32 * 27].view(np.uint16).reshape(32, 3, 3, 3)
+    rows = pk[:32 * 96].reshape(32, 96)
+    assert np.array_equal(rows[:, :72].reshape(32, 3, 3, 8)[..., :3], w.transpose(0, 2, 3, 1))
+    assert not rows[:, :72].reshape(32, 3, 3, 8)[..., 3:].any() and not rows[:, 72:].any()
+    # multiset of non-zero weights is preserved over the whole blob
+    canon = np.concatenate([blob[L.w_off:L.w_off + 2 * (L.cout * (L.cin if L.op != "dwconv" else 1) * L.k * L.k)].view(np.uint16)
+                            for L in m.layers if L.op in ("conv", "dwconv", "fc")])
+    with pytest.raises(fi.FiError):
+        fi.fi_model_pack(spec, dst.ctypes.data, n - 1)
+    assert n % 256 == 0 and n >= canon.nbytes
+
+
+def test_packed_and_canonical_members_build_the_same_image():
+    m = zoo.resnet18(hw=32)
+    blob = gen.make_blob(m, 9)
+    spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    n = fi.fi_model_packed_size(spec)
+    packed = np.zeros(n, np.uint8)
+    fi.fi_model_pack(spec, packed.ctypes.data, n)
+    a1, a2 = fi.HostAllocators(), fi.HostAllocators()
+    d1 = fi.Dag([spec], 1, a1, keepalive=keep)
+    spec2, keep2 = fi.make_spec(m, packed.ctypes.data, n, packed=True)
+    d2 = fi.Dag([spec2], 1, a2, keepalive=keep2)
+    i1 = bytes(next(iter(a1.live.values())))[:d1.query().arena_bytes]
+    i2 = bytes(next(iter(a2.live.values())))[:d2.query().arena_bytes]
+    assert i1 == i2
+
+
+def _spec_with(mutator, fam="tiny"):
+    m = zoo.tiny_cnn() if fam == "tiny" else zoo.FAMILIES[fam](hw=32)
+    blob = gen.make_blob(m, 1)
+    spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    mutator(spec)
+    return spec, (keep, blob)
+
+
+@pytest.mark.parametrize("mutate,status", [
+    (lambda s: setattr(s.layers[2], "input", 3), fi.FI_EINVAL),           # edge to a later node (cycle)
+    (lambda s: setattr(s.layers[2], "input", 77), fi.FI_EINVAL),          # dangling edge
+    (lambda s: setattr(s.layers[2], "cin", 17), fi.FI_EINVAL),            # shape mismatch
+    (lambda s: setattr(s.layers[0], "op", 42), fi.FI_EUNSUPPORTED),       # unknown operator
+    (lambda s: setattr(s.layers[0], "kw", 5), fi.FI_EUNSUPPORTED),        # non-square kernel
+    (lambda s: setattr(s.layers[2], "residual", 0), fi.FI_EINVAL),        # residual shape mismatch
+    (lambda s: setattr(s.layers[4], "w_off", 1 << 40), fi.FI_EINVAL),     # weights past the blob
+    (lambda s: setattr(s, "output_node", 99), fi.FI_EINVAL),
+    (lambda s: setattr(s, "act_dtype", fi.FI_BF16), fi.FI_EINVAL),        # fp32 weights need fp32 activations
+    (lambda s: setattr(s, "n_layers", 0), fi.FI_EINVAL),
+])
+def test_malformed_specs_are_refused(mutate, status):
+    spec, keep = _spec_with(mutate)
+    alloc = fi.HostAllocators()
+    with pytest.raises(fi.FiError) as e:
+        fi.Dag([spec], 1, alloc, keepalive=keep)
+    assert e.value.status == status and fi.fi_last_error()
+    assert alloc.n_pin == 0 or not alloc.live  # nothing leaked
+
+
+def test_members_must_share_dtype_and_input_shape():
+    a, ka = _spec_with(lambda s: None)
+    b, kb = _spec_with(lambda s: None, fam="resnet18")
+    with pytest.raises(fi.FiError) as e:
+        fi.Dag([a, b], 1, fi.HostAllocators(), keepalive=(ka, kb))
+    assert e.value.status == fi.FI_EINVAL
+
+
+def test_budget_state_machine_and_device_oom():
+    d, _, alloc = _build(["resnet18"], 1, hw=32)
+    need = d.query().device_bytes
+    with pytest.raises(fi.FiError) as e:
+        _build(["resnet18"], 1, hw=32, max_device_bytes=need - 1)
+    assert e.value.status == fi.FI_EBUDGET
+    _build(["resnet18"], 1, hw=32, max_device_bytes=need)[0].destroy()
+    # not loaded: run / unload are state errors
+    outs = (C.c_void_p * 1)(1)
+    assert fi.lib().fi_run(d.h, C.c_void_p(1), 1, outs, None) == fi.FI_ESTATE
+    assert fi.lib().fi_unload(d.h) == fi.FI_ESTATE
+    # the device allocator refuses: FI_ENOMEM_DEVICE, handle stays BUILT and can be destroyed
+    with pytest.raises(fi.FiError) as e:
+        d.load()
+    assert e.value.status == fi.FI_ENOMEM_DEVICE and alloc.n_dev == 1 and d.query().state == 0
+    d.destroy()
+    assert not alloc.live  # pinned image returned
+    # argument checks
+    assert fi.lib().fi_query(None, None) == fi.FI_EINVAL
+    bad = fi.fi_build_opts()
+    bad.max_batch = 0
+    h = C.c_void_p()
+    s, k = _spec_with(lambda s: None)
+    assert fi.lib().fi_build_dag(C.byref(s), 1, C.byref(bad), C.byref(h)) == fi.FI_EINVAL and not h.value
+    fi.fi_destroy(None)
+
+
+def test_per_model_load_mode_needs_packed_members():
+    with pytest.raises(fi.FiError) as e:
+        _build(["resnet18"], 1, hw=32, load_mode=fi.FI_LOAD_PER_MODEL)
+    assert e.value.status == fi.FI_EINVAL
