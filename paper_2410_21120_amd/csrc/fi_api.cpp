@@ -79,11 +79,18 @@ void parallel_copy(uint8_t* dst, const uint8_t* src, uint64_t n) {
   for (auto& t : th) t.join();
 }
 
-int pick_tile(const Node& n, int max_batch) {
+// Tile of the implicit GEMM for one node; `group` = problems of the same shape that will share
+// its launch.  Larger tiles re-read less and keep the matrix cores busier, but need enough
+// workgroups to cover the 256 compute units.  (Any tile yields the same bits: every output
+// element accumulates its reduction in the same order whatever the tile.)
+int pick_tile(const Node& n, int max_batch, int group) {
   const int64_t M = (int64_t)max_batch * n.Ho * n.Wo;
-  auto blocks = [&](int t) { return ((M + tile_bm(t) - 1) / tile_bm(t)) * ((n.Co + tile_bn(t) - 1) / tile_bn(t)); };
-  if (n.Co > 64 && blocks(T_128x128) >= 512) return T_128x128;
-  if (blocks(T_128x64) >= 512) return T_128x64;
+  auto blocks = [&](int t) { return group * ((M + tile_bm(t) - 1) / tile_bm(t)) * ((n.Co + tile_bn(t) - 1) / tile_bn(t)); };
+  if (n.Co > 64) {
+    if (blocks(T_256x128) >= 256) return T_256x128;
+    if (blocks(T_128x128) >= 256) return T_128x128;
+  }
+  if (blocks(T_128x64) >= 256) return T_128x64;
   return T_64x64;
 }
 
@@ -91,7 +98,7 @@ const char* kind_name(int kind, int tile) {
   switch (kind) {
     case K_STAGE: return "stage_input";
     case K_CONV_DIRECT: return "conv_direct";
-    case K_CONV_MFMA: return tile == T_128x128 ? "conv_mfma_128x128" : tile == T_128x64 ? "conv_mfma_128x64" : "conv_mfma_64x64";
+    case K_CONV_MFMA: return tile == T_256x128 ? "conv_mfma_256x128" : tile == T_128x128 ? "conv_mfma_128x128" : tile == T_128x64 ? "conv_mfma_128x64" : "conv_mfma_64x64";
     case K_DWCONV: return "dwconv";
     case K_MAXPOOL: return "maxpool";
     case K_GAP: return "global_avgpool";
@@ -180,14 +187,26 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
 
   // ---- kernel family per node ---------------------------------------------------------
   const int B = opts->max_batch;
+  std::map<std::tuple<int, int, int, int, int, int>, int> same_shape;  // problems of one shape per level
+  for (const Node& nd : g->nodes)
+    if (nd.op == FI_CONV2D || nd.op == FI_FC) same_shape[std::make_tuple(nd.level, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)]++;
   for (Node& nd : g->nodes) {
     const int adt = g->members[(size_t)nd.model].spec.act_dtype;
     nd.tile = 0;
     switch (nd.op) {
       case FI_CONV2D:
       case FI_FC:
-        if (g->wdtype == FI_BF16 && adt == FI_BF16) { nd.kind = K_CONV_MFMA; nd.tile = pick_tile(nd, B); }
-        else nd.kind = K_CONV_DIRECT;
+        if (g->wdtype == FI_BF16 && adt == FI_BF16) {
+          nd.kind = K_CONV_MFMA;
+          // the kernel addresses its input with 32-bit byte offsets through a buffer resource
+          if ((uint64_t)B * nd.H * nd.W * nd.Cp * 2 >= (1ull << 31)) {
+            set_error("model %d node %d: input tensor of %llu bytes exceeds the 2 GiB a conv kernel addresses",
+                      nd.model, nd.index, (unsigned long long)((uint64_t)B * nd.H * nd.W * nd.Cp * 2));
+            return FI_EUNSUPPORTED;
+          }
+          const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.level, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
+          nd.tile = pick_tile(nd, B, std::min(grp, (int)FI_MAX_GROUP));
+        } else nd.kind = K_CONV_DIRECT;
         break;
       case FI_DWCONV2D: nd.kind = K_DWCONV; break;
       case FI_MAXPOOL2D: nd.kind = K_MAXPOOL; break;
@@ -324,6 +343,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
         d.C = d.Cp = nd.H * nd.W * nd.Cp; d.H = d.W = 1; d.k = 1; d.stride = 1; d.pad = 0;
       }
       d.ext = nd.is_output;
+      d.vec = (adt == FI_BF16 && nd.Cp % 8 == 0 && nd.Cop % 8 == 0 && !nd.is_output && nd.out_dtype == FI_BF16) ? 1 : 0;
       d.out_f32 = (nd.out_dtype == FI_F32 && adt != FI_F32) ? 1 : 0;
       if (nd.out_dtype == FI_F32 && adt != FI_F32 && !nd.is_output) d.Cop = nd.Cop;  // fp32 rows keep the padded stride
       d.tiles_n = L.kind == K_CONV_MFMA ? (nd.Co + tile_bn(L.tile) - 1) / tile_bn(L.tile) : 0;

@@ -26,9 +26,14 @@ enum Kind : int32_t {
 };
 
 // Tile shapes of the MFMA implicit GEMM (rows = output pixels, cols = output channels).
-enum Tile : int32_t { T_128x128 = 0, T_128x64 = 1, T_64x64 = 2, T_NTILES };
-inline int tile_bm(int t) { return t == T_64x64 ? 64 : 128; }
-inline int tile_bn(int t) { return t == T_128x128 ? 128 : 64; }
+enum Tile : int32_t { T_128x128 = 0, T_128x64 = 1, T_64x64 = 2, T_256x128 = 3, T_NTILES };
+#ifdef __HIPCC__
+#define FI_HD __host__ __device__
+#else
+#define FI_HD
+#endif
+FI_HD inline int tile_bm(int t) { return t == T_256x128 ? 256 : t == T_64x64 ? 64 : 128; }
+FI_HD inline int tile_bn(int t) { return (t == T_128x128 || t == T_256x128) ? 128 : 64; }
 
 // Device-visible problem descriptor: one node of the fused DAG, batch independent.
 // Tensor offsets are relative to the activation region, weight offsets to the weight
@@ -43,7 +48,8 @@ struct Desc {
   int32_t ext;                   // 1: output is the caller's fp32 buffer of this problem
   int32_t out_f32;               // 1: output stored as fp32 whatever the activation dtype
   int32_t tiles_n;               // MFMA conv: column tiles
-  int32_t rsv[6];
+  int32_t vec;                   // 1: bf16 tensors with Cp % 8 == 0, kernels work on 8-channel vectors
+  int32_t rsv[5];
 };
 static_assert(sizeof(Desc) == 128, "Desc is 128 bytes");
 

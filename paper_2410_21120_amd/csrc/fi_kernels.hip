@@ -43,11 +43,11 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_STAGE: return (batch * d.H * d.W + 255) / 256;
     case K_CONV_DIRECT: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
     case K_CONV_MFMA: {
-      const int bm = tile == T_64x64 ? 64 : 128;
+      const int bm = tile_bm(tile);
       return ((batch * d.Ho * d.Wo + bm - 1) / bm) * d.tiles_n;
     }
-    case K_DWCONV:
-    case K_MAXPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
+    case K_DWCONV: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
+    case K_MAXPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_GAP: return (batch * d.Cop + 255) / 256;
     case K_SOFTMAX: return batch;
   }
@@ -131,21 +131,24 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
 //   rows  m = (n, p, q) output pixels      M = batch*Ho*Wo
 //   cols  o = output channel               N = Co
 //   red.  kk = (r, s, c), c innermost      K = k*k*Cp, weight rows padded to Kp (x32)
-// A (input patches) and B (weights) tiles of 32 reduction elements are fetched with 16-byte
-// vectors into registers one tile ahead, parked in a double-buffered LDS stage, and consumed
-// by 32x32x16 bf16 MFMAs with fp32 accumulation; each of the 4 waves owns a (BM/2)x(BN/2)
-// sub-tile.  The epilogue transposes the accumulators through LDS (fp32) so that bias,
-// residual, activation and the single round-to-nearest-even to bf16 run on 8 consecutive
-// channels per thread with 16-byte coalesced residual loads and output stores.
+// Per 64-element reduction tile every thread fetches 16-byte vectors of A (input patches,
+// through a buffer resource whose out-of-range reads return zero: that is the padding, the
+// rows past M and the reduction tail) and of B (weights) into registers one tile ahead of
+// the multiply, parks them in LDS, and the 4 waves consume them with 32x32x16 bf16 MFMAs
+// accumulating in fp32.  The epilogue transposes the accumulators through LDS (fp32) so that
+// bias, residual, activation and the single round-to-nearest-even to bf16 run on 8
+// consecutive channels per thread with 16-byte coalesced residual loads and output stores.
 // Workgroups are renumbered so that each XCD (blockIdx % 8) owns one contiguous run of
 // tiles: neighbouring tiles, which share input rows and a member's weights, meet in one L2.
 // ---------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
-constexpr int BK = 32;
-constexpr int LDS_STRIDE = BK + 8;  // elements; 80-byte rows keep 16-byte reads conflict-free
+constexpr int BK = 64;
+constexpr int LDS_STRIDE = BK + 8;  // elements; 144-byte rows keep 16-byte reads conflict-free
 constexpr int NXCD = 8;
+constexpr uint32_t OOB = 0x80000000u;  // byte offset past any tensor: the buffer load returns zero
 
 __device__ __forceinline__ int xcd_contiguous(int bid, int total) {
   const int c = total / NXCD, r = total % NXCD;
@@ -157,17 +160,17 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
 }
 
-template <int BM, int BN>
+template <int TILE, int BM, int BN, int WGM, int WGN>
 __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
-  constexpr int TILE = BM == 64 ? T_64x64 : (BN == 128 ? T_128x128 : T_128x64);
-  constexpr int WTM = BM / 2, WTN = BN / 2;  // per-wave sub-tile
+  static_assert(WGM * WGN == 4, "four waves per workgroup");
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // per-wave sub-tile
   constexpr int MI = WTM / 32, NI = WTN / 32;
-  constexpr int AR = BM / 64, BR = BN / 64;  // rows each thread stages per tile
-  constexpr int STAGE = (BM + BN) * LDS_STRIDE;            // bf16 elements per LDS stage
-  constexpr int EPS = BN + 8;                              // fp32 row stride of the epilogue tile
-  constexpr int SMEM = 2 * STAGE * 2 > 64 * EPS * 4 ? 2 * STAGE * 2 : 64 * EPS * 4;
+  constexpr int AR = BM / 32, BR = BN / 32;  // 16-byte vectors each thread stages per tile
+  constexpr int EPS = BN + 8;                // fp32 row stride of the epilogue tile
+  constexpr int SMEM = (BM + BN) * LDS_STRIDE * 2 > 64 * EPS * 4 ? (BM + BN) * LDS_STRIDE * 2 : 64 * EPS * 4;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
-  bf16_t* const lds = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* const Bs = As + BM * LDS_STRIDE;
 
   // locate the problem and the tile (block-uniform)
   int p = 0, bid = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
@@ -184,18 +187,18 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
-  const bf16_t* __restrict__ x = reinterpret_cast<const bf16_t*>(a.abase + d.x_off);
   const bf16_t* __restrict__ w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off);
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(a.abase + d.x_off), 0, (int)((int64_t)a.batch * d.H * d.W * d.Cp * 2), 0x00020000);
 
-  // staging assignment: thread -> (row, 8-element k vector)
-  const int srow = tid >> 2, kvec = (tid & 3) * 8;
-  int a_ih0[AR], a_iw0[AR];
-  int64_t a_base[AR];
+  // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
+  const int srow = tid >> 3, kvec = (tid & 7) * 8;
+  int a_ih0[AR], a_iw0[AR], a_base[AR];
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
-    const int m = m0 + srow + 64 * i;
+    const int m = m0 + srow + 32 * i;
     const bool ok = m < M;
     const int mm = ok ? m : 0;
     const int q = mm % d.Wo;
@@ -204,18 +207,26 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
     const int n = t / d.Ho;
     a_ih0[i] = ok ? pp * d.stride - d.pad : -(1 << 20);  // rows past M read as zero
     a_iw0[i] = q * d.stride - d.pad;
-    a_base[i] = (int64_t)n * d.H * d.W * d.Cp;
+    a_base[i] = n * d.H * d.W * d.Cp * 2;  // bytes
   }
-  const bf16_t* b_ptr[BR];
+  const uint4* b_ptr[BR];
 #pragma unroll
   for (int i = 0; i < BR; ++i) {
-    int o = n0 + srow + 64 * i;
+    int o = n0 + srow + 32 * i;
     o = o < d.Co ? o : d.Co - 1;  // clamped rows are computed and discarded
-    b_ptr[i] = w + (int64_t)o * d.Kp + kvec;
+    b_ptr[i] = reinterpret_cast<const uint4*>(w + (int64_t)o * d.Kp + kvec);
   }
-  // this thread's reduction position (r, s, c), advanced by BK per tile
+  // this thread's reduction position (r, s, c) for the tile being fetched
   int kr = 0, ks = 0, kc = kvec;
-  while (kc >= d.Cp) { kc -= d.Cp; if (++ks == d.k) { ks = 0; ++kr; } }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const bool wrap = kc >= d.Cp;
+    kc -= wrap ? d.Cp : 0;
+    ks += wrap ? 1 : 0;
+    const bool wrap2 = ks == d.k;
+    ks = wrap2 ? 0 : ks;
+    kr += wrap2 ? 1 : 0;
+  }
 
   f32x16 acc[MI][NI];
 #pragma unroll
@@ -225,38 +236,41 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  uint4 av[AR], bv[BR];
-  auto fetch = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < AR; ++i) {
-      const int ih = a_ih0[i] + kr, iw = a_iw0[i] + ks;
-      av[i] = make_uint4(0, 0, 0, 0);
-      if (kr < d.k && ih >= 0 && ih < d.H && iw >= 0 && iw < d.W)
-        av[i] = *reinterpret_cast<const uint4*>(x + a_base[i] + ((int64_t)ih * d.W + iw) * d.Cp + kc);
-    }
-#pragma unroll
-    for (int i = 0; i < BR; ++i) bv[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + (int64_t)kt * BK);
-    kc += BK;
-    while (kc >= d.Cp) { kc -= d.Cp; if (++ks == d.k) { ks = 0; ++kr; } }
-  };
-  auto park = [&](int buf) {
-    bf16_t* As = lds + buf * STAGE;
-    bf16_t* Bs = As + BM * LDS_STRIDE;
-#pragma unroll
-    for (int i = 0; i < AR; ++i) *reinterpret_cast<uint4*>(&As[(srow + 64 * i) * LDS_STRIDE + kvec]) = av[i];
-#pragma unroll
-    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + 64 * i) * LDS_STRIDE + kvec]) = bv[i];
-  };
+  u32x4 av[AR];
+  uint4 bv[BR];
+  const int ntiles = (d.Kp + BK - 1) / BK;
+  const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
 
-  const int ntiles = d.Kp / BK;
-  fetch(0);
-  park(0);
-  __syncthreads();
+#define FI_FETCH(KT)                                                                              \
+  {                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
+      const int ih = a_ih0[i] + kr, iw = a_iw0[i] + ks;                                           \
+      const bool ok = kr < d.k && (unsigned)ih < (unsigned)d.H && (unsigned)iw < (unsigned)d.W;   \
+      const uint32_t off = ok ? (uint32_t)(a_base[i] + ((ih * d.W + iw) * d.Cp + kc) * 2) : OOB;  \
+      av[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);                             \
+    }                                                                                             \
+    const bool bok = !(b_tail && (KT) == ntiles - 1 && kvec >= 32);                               \
+    _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
+        bv[i] = bok ? b_ptr[i][(KT) * (BK / 8)] : make_uint4(0, 0, 0, 0);                         \
+    kc += BK;                                                                                     \
+    _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                               \
+      const bool wrap = kc >= d.Cp;                                                               \
+      kc -= wrap ? d.Cp : 0;                                                                      \
+      ks += wrap ? 1 : 0;                                                                         \
+      const bool wrap2 = ks == d.k;                                                               \
+      ks = wrap2 ? 0 : ks;                                                                        \
+      kr += wrap2 ? 1 : 0;                                                                        \
+    }                                                                                             \
+  }
+
+  FI_FETCH(0)
   for (int kt = 0; kt < ntiles; ++kt) {
-    const bool more = kt + 1 < ntiles;
-    if (more) fetch(kt + 1);  // in flight while this tile is multiplied
-    const bf16_t* As = lds + (kt & 1) * STAGE;
-    const bf16_t* Bs = As + BM * LDS_STRIDE;
+#pragma unroll
+    for (int i = 0; i < AR; ++i) *reinterpret_cast<u32x4*>(&As[(srow + 32 * i) * LDS_STRIDE + kvec]) = av[i];
+#pragma unroll
+    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + 32 * i) * LDS_STRIDE + kvec]) = bv[i];
+    __syncthreads();
+    if (kt + 1 < ntiles) FI_FETCH(kt + 1)  // in flight while this tile is multiplied
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 af[MI], bfr[NI];
@@ -273,9 +287,9 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (more) park((kt + 1) & 1);
-    __syncthreads();
+    __syncthreads();  // every wave is done with this tile before it is overwritten
   }
+#undef FI_FETCH
 
   // ---- epilogue: 64 output rows per pass through an fp32 LDS tile ----------------------
   float* ep = reinterpret_cast<float*>(smem);
@@ -377,7 +391,9 @@ __global__ void __launch_bounds__(256) dwconv_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
-// max pooling: out-of-range taps are skipped (padding behaves as -inf)
+// max pooling: out-of-range taps are skipped (padding behaves as -inf).  One thread per
+// (pixel, 8 channels) with 16-byte loads and stores when the channel stride allows it
+// (bf16, Cp % 8 == 0); one thread per element otherwise.
 // ---------------------------------------------------------------------------------
 template <typename TA>
 __global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
@@ -385,13 +401,47 @@ __global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
   if (!find_problem(a, K_MAXPOOL, 0, p, bid)) return;
   const Desc d = a.descs[p];
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
+  if (sizeof(TA) == 2 && d.vec) {
+    const int cv = d.Cp / 8;
+    if (idx >= (int64_t)a.batch * d.Ho * d.Wo * cv) return;
+    const int c8 = (int)(idx % cv) * 8;
+    const int64_t m = idx / cv;
+    const int q = (int)(m % d.Wo);
+    const int pp = (int)((m / d.Wo) % d.Ho);
+    const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
+    float best[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) best[i] = -INFINITY;
+    for (int r = 0; r < d.k; ++r) {
+      const int ih = pp * d.stride - d.pad + r;
+      if (ih < 0 || ih >= d.H) continue;
+      for (int s = 0; s < d.k; ++s) {
+        const int iw = q * d.stride - d.pad + s;
+        if (iw < 0 || iw >= d.W) continue;
+        const uint4 v = *reinterpret_cast<const uint4*>(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp + c8);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          best[2 * i] = fmaxf(best[2 * i], __uint_as_float(u[i] << 16));
+          best[2 * i + 1] = fmaxf(best[2 * i + 1], __uint_as_float(u[i] & 0xFFFF0000u));
+        }
+      }
+    }
+    uint4 o;  // the maxima are bf16 values already: packing is exact
+    o.x = (__float_as_uint(best[0]) >> 16) | (__float_as_uint(best[1]) & 0xFFFF0000u);
+    o.y = (__float_as_uint(best[2]) >> 16) | (__float_as_uint(best[3]) & 0xFFFF0000u);
+    o.z = (__float_as_uint(best[4]) >> 16) | (__float_as_uint(best[5]) & 0xFFFF0000u);
+    o.w = (__float_as_uint(best[6]) >> 16) | (__float_as_uint(best[7]) & 0xFFFF0000u);
+    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.Cop + c8) = o;
+    return;
+  }
   if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
   const int c = (int)(idx % d.Cop);
   const int64_t m = idx / d.Cop;
   const int q = (int)(m % d.Wo);
   const int pp = (int)((m / d.Wo) % d.Ho);
   const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
-  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
   float best = -INFINITY;
   for (int r = 0; r < d.k; ++r) {
     const int ih = pp * d.stride - d.pad + r;
@@ -483,9 +533,10 @@ int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vect
       return go(conv_direct_kernel<float, float>, nb, 256, a, s);
     case K_CONV_MFMA:
       if (!(wb && ab)) return (int)hipErrorInvalidValue;
-      if (L.tile == T_128x128) return go(conv_mfma_kernel<128, 128>, nb, 256, a, s);
-      if (L.tile == T_128x64) return go(conv_mfma_kernel<128, 64>, nb, 256, a, s);
-      return go(conv_mfma_kernel<64, 64>, nb, 256, a, s);
+      if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2>, nb, 256, a, s);
+      if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2>, nb, 256, a, s);
+      if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2>, nb, 256, a, s);
+      return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2>, nb, 256, a, s);
     case K_DWCONV:
       if (wb && ab) return go(dwconv_kernel<bf16_t, bf16_t>, nb, 256, a, s);
       if (wb) return go(dwconv_kernel<bf16_t, float>, nb, 256, a, s);
