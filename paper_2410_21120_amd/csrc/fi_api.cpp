@@ -86,11 +86,17 @@ void parallel_copy(uint8_t* dst, const uint8_t* src, uint64_t n) {
 int pick_tile(const Node& n, int max_batch, int group) {
   const int64_t M = (int64_t)max_batch * n.Ho * n.Wo;
   auto blocks = [&](int t) { return group * ((M + tile_bm(t) - 1) / tile_bm(t)) * ((n.Co + tile_bn(t) - 1) / tile_bn(t)); };
-  if (n.Co > 64) {
-    if (blocks(T_256x128) >= 256) return T_256x128;
-    if (blocks(T_128x128) >= 256) return T_128x128;
+  // Short reductions stream activations (bandwidth-bound): medium tiles keep more workgroups
+  // and loads in flight.  Long reductions are matrix-core-bound: the largest tile re-reads least.
+  const int want = n.Kp <= 512 ? T_128x128 : T_256x128;
+  const int order[4] = {T_256x128, T_128x128, T_128x64, T_64x64};
+  bool started = false;
+  for (int t : order) {
+    if (t == want) started = true;
+    if (!started) continue;
+    if (tile_bn(t) == 128 && n.Co <= 64) continue;
+    if (blocks(t) >= 256 || t == T_64x64) return t;
   }
-  if (blocks(T_128x64) >= 256) return T_128x64;
   return T_64x64;
 }
 

@@ -292,11 +292,34 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 #undef FI_FETCH
 
   // ---- epilogue: 64 output rows per pass through an fp32 LDS tile ----------------------
+  // A thread owns one 8-channel column chunk (the same in every pass) and CH rows per pass.
+  // The pass's residual vectors are requested before the accumulators are parked, so their
+  // latency overlaps the LDS round trip instead of serialising behind it.
+  constexpr int CPR = BN / 8;          // 8-channel chunks per tile row
+  constexpr int CH = 64 * CPR / 256;   // chunks per thread per pass
+  constexpr int RSTEP = 256 / CPR;     // row distance between a thread's chunks
   float* ep = reinterpret_cast<float*>(smem);
-  const float* bias = reinterpret_cast<const float*>(a.wbase + d.b_off);
-  const bf16_t* res = d.r_off != kNone ? reinterpret_cast<const bf16_t*>(a.abase + d.r_off) : nullptr;
+  const int cc = (tid % CPR) * 8, lr0 = tid / CPR;
+  const int o = n0 + cc;
+  const bool col_ok = o < d.Cop;
+  float bias8[8];
+  {
+    const float* bias = reinterpret_cast<const float*>(a.wbase + d.b_off);
+    const float4 b0 = col_ok ? *reinterpret_cast<const float4*>(bias + o) : make_float4(0, 0, 0, 0);
+    const float4 b1 = col_ok ? *reinterpret_cast<const float4*>(bias + o + 4) : make_float4(0, 0, 0, 0);
+    bias8[0] = b0.x; bias8[1] = b0.y; bias8[2] = b0.z; bias8[3] = b0.w;
+    bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
+  }
+  const bf16_t* __restrict__ res = d.r_off != kNone ? reinterpret_cast<const bf16_t*>(a.abase + d.r_off) : nullptr;
 #pragma unroll
   for (int pass = 0; pass < BM / 64; ++pass) {
+    uint4 rv[CH];
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+      const int m = m0 + pass * 64 + lr0 + ch * RSTEP;
+      rv[ch] = make_uint4(0, 0, 0, 0);
+      if (res && col_ok && m < M) rv[ch] = *reinterpret_cast<const uint4*>(res + (int64_t)m * d.Cop + o);
+    }
     if (pass > 0) __syncthreads();
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
@@ -311,24 +334,19 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
         }
     }
     __syncthreads();
-    for (int c = tid; c < 64 * (BN / 8); c += 256) {
-      const int lr = c / (BN / 8), cc = (c % (BN / 8)) * 8;
-      const int m = m0 + pass * 64 + lr, o = n0 + cc;
-      if (m >= M || o >= d.Cop) continue;
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+      const int lr = lr0 + ch * RSTEP;
+      const int m = m0 + pass * 64 + lr;
+      if (m >= M || !col_ok) continue;
       float v[8];
       const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
       const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
-      const float4 b0 = *reinterpret_cast<const float4*>(bias + o);
-      const float4 b1 = *reinterpret_cast<const float4*>(bias + o + 4);
-      v[0] = v0.x + b0.x; v[1] = v0.y + b0.y; v[2] = v0.z + b0.z; v[3] = v0.w + b0.w;
-      v[4] = v1.x + b1.x; v[5] = v1.y + b1.y; v[6] = v1.z + b1.z; v[7] = v1.w + b1.w;
-      if (res) {
-        const uint4 r = *reinterpret_cast<const uint4*>(res + (int64_t)m * d.Cop + o);
-        v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xFFFF0000u);
-        v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xFFFF0000u);
-        v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
-        v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
-      }
+      const uint4 r = rv[ch];
+      v[0] = v0.x + bias8[0] + __uint_as_float(r.x << 16); v[1] = v0.y + bias8[1] + __uint_as_float(r.x & 0xFFFF0000u);
+      v[2] = v0.z + bias8[2] + __uint_as_float(r.y << 16); v[3] = v0.w + bias8[3] + __uint_as_float(r.y & 0xFFFF0000u);
+      v[4] = v1.x + bias8[4] + __uint_as_float(r.z << 16); v[5] = v1.y + bias8[5] + __uint_as_float(r.z & 0xFFFF0000u);
+      v[6] = v1.z + bias8[6] + __uint_as_float(r.w << 16); v[7] = v1.w + bias8[7] + __uint_as_float(r.w & 0xFFFF0000u);
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[i] = (o + i < d.Co) ? activate(v[i], d.act) : 0.0f;  // pad channels hold zero
       if (d.ext) {
