@@ -83,12 +83,12 @@ void parallel_copy(uint8_t* dst, const uint8_t* src, uint64_t n) {
 // its launch.  Larger tiles re-read less and keep the matrix cores busier, but need enough
 // workgroups to cover the 256 compute units.  (Any tile yields the same bits: every output
 // element accumulates its reduction in the same order whatever the tile.)
-int pick_tile(const Node& n, int max_batch, int group) {
+int pick_tile(const Node& n, int max_batch, int group, bool wide) {
   const int64_t M = (int64_t)max_batch * n.Ho * n.Wo;
   auto blocks = [&](int t) { return group * ((M + tile_bm(t) - 1) / tile_bm(t)) * ((n.Co + tile_bn(t) - 1) / tile_bn(t)); };
   // Short reductions stream activations (bandwidth-bound): medium tiles keep more workgroups
   // and loads in flight.  Long reductions are matrix-core-bound: the largest tile re-reads least.
-  const int want = n.Kp <= 512 ? T_128x128 : T_256x128;
+  const int want = (n.Kp <= 512 || wide) ? T_128x128 : T_256x128;  // fp32-activation members: no 256-row tile
   const int order[4] = {T_256x128, T_128x128, T_128x64, T_64x64};
   bool started = false;
   for (int t : order) {
@@ -109,6 +109,8 @@ const char* kind_name(int kind, int tile) {
     case K_MAXPOOL: return "maxpool";
     case K_GAP: return "global_avgpool";
     case K_SOFTMAX: return "softmax";
+    case K_FC: return "fc_splitk";
+    case K_FC_REDUCE: return "fc_reduce";
   }
   return "?";
 }
@@ -202,16 +204,21 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
     switch (nd.op) {
       case FI_CONV2D:
       case FI_FC:
-        if (g->wdtype == FI_BF16 && adt == FI_BF16) {
+        if (g->wdtype == FI_BF16 && nd.op == FI_FC && B <= 32 && nd.residual < 0) {
+          // batch <= 32: one 32-wide MFMA column block holds the whole batch; the layer is a weight stream
+          nd.kind = K_FC;
+          const int tiles = (nd.Co + 31) / 32, steps = nd.Kp / 16;
+          nd.splits = std::max(1, std::min(std::min(64, std::max(1, steps / 8)), std::max(1, 2048 / tiles)));
+        } else if (g->wdtype == FI_BF16) {
           nd.kind = K_CONV_MFMA;
           // the kernel addresses its input with 32-bit byte offsets through a buffer resource
-          if ((uint64_t)B * nd.H * nd.W * nd.Cp * 2 >= (1ull << 31)) {
+          if ((uint64_t)B * nd.H * nd.W * nd.Cp * esize(adt) >= (1ull << 31)) {
             set_error("model %d node %d: input tensor of %llu bytes exceeds the 2 GiB a conv kernel addresses",
-                      nd.model, nd.index, (unsigned long long)((uint64_t)B * nd.H * nd.W * nd.Cp * 2));
+                      nd.model, nd.index, (unsigned long long)((uint64_t)B * nd.H * nd.W * nd.Cp * esize(adt)));
             return FI_EUNSUPPORTED;
           }
           const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.level, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
-          nd.tile = pick_tile(nd, B, std::min(grp, (int)FI_MAX_GROUP));
+          nd.tile = pick_tile(nd, B, std::min(grp, (int)FI_MAX_GROUP), adt == FI_F32);
         } else nd.kind = K_CONV_DIRECT;
         break;
       case FI_DWCONV2D: nd.kind = K_DWCONV; break;
@@ -253,6 +260,15 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       nd.launch = it->second;
       nd.slot = L.n++;
       L.nodes.push_back(i);
+    }
+    // every split-K FC launch is followed by the launch that reduces its partials
+    const size_t level_end = g->launches.size();
+    for (size_t li = 0; li < level_end; ++li) {
+      if (g->launches[li].level != lv || g->launches[li].kind != K_FC) continue;
+      const Launch src = g->launches[li];
+      Launch& R = new_launch(lv, K_FC_REDUCE, 0, src.adtype);
+      R.n = src.n;
+      R.nodes = src.nodes;
     }
   }
 
@@ -318,7 +334,18 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
     nd.w_off = nd.w_rel == kNone ? kNone : mb.arena_off + nd.w_rel;
     nd.b_off = nd.b_rel == kNone ? kNone : mb.arena_off + nd.b_rel;
   }
+  // workspace: split-K partials; nodes of one level get disjoint regions, levels reuse them
   g->workspace_bytes = 0;
+  {
+    std::map<int32_t, uint64_t> level_top;
+    for (Node& nd : g->nodes) {
+      if (nd.kind != K_FC) continue;
+      uint64_t& top = level_top[nd.level];
+      nd.ws_off = top;
+      top += align_up((uint64_t)nd.splits * B * nd.Cop * 4);
+      g->workspace_bytes = std::max(g->workspace_bytes, top);
+    }
+  }
   g->device_bytes = g->arena_bytes + g->act_bytes + g->workspace_bytes;
   if (opts->max_device_bytes && g->device_bytes > opts->max_device_bytes) {
     set_error("DAG needs %llu device bytes, budget is %llu", (unsigned long long)g->device_bytes, (unsigned long long)opts->max_device_bytes);
@@ -353,6 +380,15 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       d.out_f32 = (nd.out_dtype == FI_F32 && adt != FI_F32) ? 1 : 0;
       if (nd.out_dtype == FI_F32 && adt != FI_F32 && !nd.is_output) d.Cop = nd.Cop;  // fp32 rows keep the padded stride
       d.tiles_n = L.kind == K_CONV_MFMA ? (nd.Co + tile_bn(L.tile) - 1) / tile_bn(L.tile) : 0;
+      if (L.kind == K_FC || L.kind == K_FC_REDUCE) {
+        d.tiles_n = (nd.Co + 31) / 32;
+        d.splits = nd.splits;
+        d.r_off = g->act_bytes + nd.ws_off;  // the workspace follows the activation arena
+      }
+      if (L.kind == K_FC_REDUCE) {
+        L.act_bytes += (uint64_t)nd.splits * nd.Cop * 4 + (uint64_t)nd.Co * esize(nd.out_dtype);
+        continue;
+      }
       L.macs += nd.macs;
       const uint64_t in_e = esize(nd.input >= 0 ? g->nodes[(size_t)nd.input].out_dtype : adt);
       L.act_bytes += (uint64_t)nd.H * nd.W * nd.C * in_e + (uint64_t)nd.Ho * nd.Wo * nd.Co * esize(nd.out_dtype) +
@@ -360,6 +396,17 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       if (nd.w_rel != kNone)
         L.weight_bytes += (nd.op == FI_DWCONV2D ? (uint64_t)nd.k * nd.k * nd.C : (uint64_t)nd.Co * nd.k * nd.k * nd.C * (nd.op == FI_FC ? nd.H * nd.W : 1)) * esize(g->wdtype) + (uint64_t)nd.Co * 4;
     }
+  }
+
+  // depthwise / global-average launches use the 8-channel vector kernels only when every problem allows it
+  for (Launch& L : g->launches) {
+    if (L.kind != K_DWCONV && L.kind != K_GAP) continue;
+    bool vec = L.kind == K_GAP || g->wdtype == FI_BF16;
+    for (int32_t s = 0; s < L.n; ++s) {
+      const Desc& d = g->descs[(size_t)(L.first_desc + s)];
+      vec = vec && d.Cp % 8 == 0 && d.Cop % 8 == 0;
+    }
+    for (int32_t s = 0; s < L.n; ++s) g->descs[(size_t)(L.first_desc + s)].vec = vec ? 1 : 0;
   }
 
   // ---- pinned image: the bytes fi_load copies ----------------------------------------------

@@ -46,10 +46,12 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
       const int bm = tile_bm(tile);
       return ((batch * d.Ho * d.Wo + bm - 1) / bm) * d.tiles_n;
     }
-    case K_DWCONV: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
+    case K_DWCONV: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_MAXPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
-    case K_GAP: return (batch * d.Cop + 255) / 256;
+    case K_GAP: return (batch * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256;
     case K_SOFTMAX: return batch;
+    case K_FC: return (d.tiles_n * d.splits + 3) / 4;
+    case K_FC_REDUCE: return (batch * (d.Cop / 4) + 255) / 256;
   }
   return 0;
 }
@@ -160,17 +162,24 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
 }
 
-template <int TILE, int BM, int BN, int WGM, int WGN>
+// WIDE: the member keeps fp32 activations.  Each fp32 input is split on the fly into
+// hi = bf16(x) and lo = bf16(x - hi) (two bf16 terms carry 16 mantissa bits), both halves are
+// multiplied by the bf16 weights into the same fp32 accumulator, and outputs / residuals stay
+// fp32: bf16 matrix-core throughput at fp32-grade activation accuracy.
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE>
 __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
   static_assert(WGM * WGN == 4, "four waves per workgroup");
+  constexpr int AE = WIDE ? 4 : 2;       // bytes per stored activation element
+  constexpr int AV = WIDE ? 2 : 1;       // 16-byte loads per 8-element A vector
+  constexpr int AT = WIDE ? 2 : 1;       // A tiles in LDS (hi, lo)
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // per-wave sub-tile
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int AR = BM / 32, BR = BN / 32;  // 16-byte vectors each thread stages per tile
   constexpr int EPS = BN + 8;                // fp32 row stride of the epilogue tile
-  constexpr int SMEM = (BM + BN) * LDS_STRIDE * 2 > 64 * EPS * 4 ? (BM + BN) * LDS_STRIDE * 2 : 64 * EPS * 4;
+  constexpr int SMEM = (AT * BM + BN) * LDS_STRIDE * 2 > 64 * EPS * 4 ? (AT * BM + BN) * LDS_STRIDE * 2 : 64 * EPS * 4;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
-  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* const Bs = As + BM * LDS_STRIDE;
+  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);   // [AT][BM][LDS_STRIDE]
+  bf16_t* const Bs = As + AT * BM * LDS_STRIDE;
 
   // locate the problem and the tile (block-uniform)
   int p = 0, bid = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
@@ -191,7 +200,7 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 
   const bf16_t* __restrict__ w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(a.abase + d.x_off), 0, (int)((int64_t)a.batch * d.H * d.W * d.Cp * 2), 0x00020000);
+      const_cast<uint8_t*>(a.abase + d.x_off), 0, (int)((int64_t)a.batch * d.H * d.W * d.Cp * AE), 0x00020000);
 
   // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
   const int srow = tid >> 3, kvec = (tid & 7) * 8;
@@ -207,7 +216,7 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
     const int n = t / d.Ho;
     a_ih0[i] = ok ? pp * d.stride - d.pad : -(1 << 20);  // rows past M read as zero
     a_iw0[i] = q * d.stride - d.pad;
-    a_base[i] = n * d.H * d.W * d.Cp * 2;  // bytes
+    a_base[i] = n * d.H * d.W * d.Cp * AE;  // bytes
   }
   const uint4* b_ptr[BR];
 #pragma unroll
@@ -236,7 +245,7 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  u32x4 av[AR];
+  u32x4 av[AR][AV];
   uint4 bv[BR];
   const int ntiles = (d.Kp + BK - 1) / BK;
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
@@ -246,8 +255,9 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
     _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
       const int ih = a_ih0[i] + kr, iw = a_iw0[i] + ks;                                           \
       const bool ok = kr < d.k && (unsigned)ih < (unsigned)d.H && (unsigned)iw < (unsigned)d.W;   \
-      const uint32_t off = ok ? (uint32_t)(a_base[i] + ((ih * d.W + iw) * d.Cp + kc) * 2) : OOB;  \
-      av[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);                             \
+      const uint32_t off = ok ? (uint32_t)(a_base[i] + ((ih * d.W + iw) * d.Cp + kc) * AE) : OOB; \
+      _Pragma("unroll") for (int h = 0; h < AV; ++h)                                              \
+          av[i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);             \
     }                                                                                             \
     const bool bok = !(b_tail && (KT) == ntiles - 1 && kvec >= 32);                               \
     _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
@@ -266,26 +276,45 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
   FI_FETCH(0)
   for (int kt = 0; kt < ntiles; ++kt) {
 #pragma unroll
-    for (int i = 0; i < AR; ++i) *reinterpret_cast<u32x4*>(&As[(srow + 32 * i) * LDS_STRIDE + kvec]) = av[i];
+    for (int i = 0; i < AR; ++i) {
+      if constexpr (!WIDE) {
+        *reinterpret_cast<u32x4*>(&As[(srow + 32 * i) * LDS_STRIDE + kvec]) = av[i][0];
+      } else {
+        u32x4 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x0 = __uint_as_float(av[i][e >> 1][(2 * e) & 3]), x1 = __uint_as_float(av[i][e >> 1][(2 * e + 1) & 3]);
+          const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);
+          hi[e] = h0 | (h1 << 16);
+          lo[e] = pack_bf16x2(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h1 << 16));
+        }
+        *reinterpret_cast<u32x4*>(&As[(srow + 32 * i) * LDS_STRIDE + kvec]) = hi;
+        *reinterpret_cast<u32x4*>(&As[(BM + srow + 32 * i) * LDS_STRIDE + kvec]) = lo;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + 32 * i) * LDS_STRIDE + kvec]) = bv[i];
     __syncthreads();
     if (kt + 1 < ntiles) FI_FETCH(kt + 1)  // in flight while this tile is multiplied
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 af[MI], bfr[NI];
+      bf16x8 af[AT][MI], bfr[NI];
       const int kof = kk + (lane >> 5) * 8;
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * WTM + i * 32 + (lane & 31)) * LDS_STRIDE + kof]);
+      for (int h = 0; h < AT; ++h)
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+          af[h][i] = *reinterpret_cast<const bf16x8*>(&As[(h * BM + wm * WTM + i * 32 + (lane & 31)) * LDS_STRIDE + kof]);
 #pragma unroll
       for (int j = 0; j < NI; ++j)
         bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * WTN + j * 32 + (lane & 31)) * LDS_STRIDE + kof]);
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
+      for (int h = AT - 1; h >= 0; --h)  // small (lo) terms first
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();  // every wave is done with this tile before it is overwritten
   }
@@ -310,15 +339,18 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
     bias8[0] = b0.x; bias8[1] = b0.y; bias8[2] = b0.z; bias8[3] = b0.w;
     bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
   }
-  const bf16_t* __restrict__ res = d.r_off != kNone ? reinterpret_cast<const bf16_t*>(a.abase + d.r_off) : nullptr;
+  const uint8_t* __restrict__ res = d.r_off != kNone ? a.abase + d.r_off : nullptr;
 #pragma unroll
   for (int pass = 0; pass < BM / 64; ++pass) {
-    uint4 rv[CH];
+    uint4 rv[CH][AV];
 #pragma unroll
     for (int ch = 0; ch < CH; ++ch) {
       const int m = m0 + pass * 64 + lr0 + ch * RSTEP;
-      rv[ch] = make_uint4(0, 0, 0, 0);
-      if (res && col_ok && m < M) rv[ch] = *reinterpret_cast<const uint4*>(res + (int64_t)m * d.Cop + o);
+#pragma unroll
+      for (int h = 0; h < AV; ++h) {
+        rv[ch][h] = make_uint4(0, 0, 0, 0);
+        if (res && col_ok && m < M) rv[ch][h] = *reinterpret_cast<const uint4*>(res + ((int64_t)m * d.Cop + o) * AE + 16 * h);
+      }
     }
     if (pass > 0) __syncthreads();
 #pragma unroll
@@ -342,11 +374,19 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
       float v[8];
       const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
       const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
-      const uint4 r = rv[ch];
-      v[0] = v0.x + bias8[0] + __uint_as_float(r.x << 16); v[1] = v0.y + bias8[1] + __uint_as_float(r.x & 0xFFFF0000u);
-      v[2] = v0.z + bias8[2] + __uint_as_float(r.y << 16); v[3] = v0.w + bias8[3] + __uint_as_float(r.y & 0xFFFF0000u);
-      v[4] = v1.x + bias8[4] + __uint_as_float(r.z << 16); v[5] = v1.y + bias8[5] + __uint_as_float(r.z & 0xFFFF0000u);
-      v[6] = v1.z + bias8[6] + __uint_as_float(r.w << 16); v[7] = v1.w + bias8[7] + __uint_as_float(r.w & 0xFFFF0000u);
+      v[0] = v0.x + bias8[0]; v[1] = v0.y + bias8[1]; v[2] = v0.z + bias8[2]; v[3] = v0.w + bias8[3];
+      v[4] = v1.x + bias8[4]; v[5] = v1.y + bias8[5]; v[6] = v1.z + bias8[6]; v[7] = v1.w + bias8[7];
+      if constexpr (WIDE) {
+        const uint4 r0 = rv[ch][0], r1 = rv[ch][AV - 1];
+        v[0] += __uint_as_float(r0.x); v[1] += __uint_as_float(r0.y); v[2] += __uint_as_float(r0.z); v[3] += __uint_as_float(r0.w);
+        v[4] += __uint_as_float(r1.x); v[5] += __uint_as_float(r1.y); v[6] += __uint_as_float(r1.z); v[7] += __uint_as_float(r1.w);
+      } else {
+        const uint4 r = rv[ch][0];
+        v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xFFFF0000u);
+        v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xFFFF0000u);
+        v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
+        v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[i] = (o + i < d.Co) ? activate(v[i], d.act) : 0.0f;  // pad channels hold zero
       if (d.ext) {
@@ -354,7 +394,7 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
           if (o + i < d.Co) y[i] = v[i];
-      } else if (d.out_f32) {
+      } else if (WIDE || d.out_f32) {
         float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o;
         *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
         *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
@@ -524,6 +564,240 @@ __global__ void __launch_bounds__(64) softmax_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// 8-channel vector access for the bandwidth-bound kernels
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const bf16_t* p, float* v) {
+  const uint4 u = *reinterpret_cast<const uint4*>(p);
+  v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xFFFF0000u);
+  v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xFFFF0000u);
+  v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ void load8(const float* p, float* v) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float* v) {
+  uint4 u;
+  u.x = pack_bf16x2(v[0], v[1]); u.y = pack_bf16x2(v[2], v[3]); u.z = pack_bf16x2(v[4], v[5]); u.w = pack_bf16x2(v[6], v[7]);
+  *reinterpret_cast<uint4*>(p) = u;
+}
+__device__ __forceinline__ void store8(float* p, const float* v) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+// ---------------------------------------------------------------------------------
+// depthwise convolution, bf16 weights: one thread per (pixel, 8 channels); 16-byte (bf16) or
+// 2x16-byte (fp32) activation vectors, coalesced along the channel axis.
+// ---------------------------------------------------------------------------------
+template <typename TA>
+__global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_DWCONV, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int cv = d.Cop / 8;
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * cv) return;
+  const int c8 = (int)(idx % cv) * 8;
+  const int64_t m = idx / cv;
+  const int q = (int)(m % d.Wo);
+  const int pp = (int)((m / d.Wo) % d.Ho);
+  const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
+  const bf16_t* w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off);
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+  for (int r = 0; r < d.k; ++r) {
+    const int ih = pp * d.stride - d.pad + r;
+    if (ih < 0 || ih >= d.H) continue;
+    for (int s = 0; s < d.k; ++s) {
+      const int iw = q * d.stride - d.pad + s;
+      if (iw < 0 || iw >= d.W) continue;
+      float xv[8], wv[8];
+      load8(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp + c8, xv);
+      load8(w + (r * d.k + s) * d.Cp + c8, wv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += xv[i] * wv[i];
+    }
+  }
+  float bv[8];
+  load8(reinterpret_cast<const float*>(a.wbase + d.b_off) + c8, bv);
+  if (d.r_off != kNone) {
+    float rv[8];
+    load8(reinterpret_cast<const TA*>(a.abase + d.r_off) + m * d.Cop + c8, rv);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bv[i] += rv[i];
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = (c8 + i < d.Co) ? activate(acc[i] + bv[i], d.act) : 0.0f;
+  if (d.ext) {
+    float* y = static_cast<float*>(a.ext_out[p]) + m * d.Co + c8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (c8 + i < d.Co) y[i] = acc[i];
+  } else {
+    store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c8, acc);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// global average pooling, 8 channels per thread
+// ---------------------------------------------------------------------------------
+template <typename TA>
+__global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_GAP, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int cv = d.Cop / 8;
+  const int idx = bid * 256 + threadIdx.x;
+  if (idx >= a.batch * cv) return;
+  const int c8 = (idx % cv) * 8, n = idx / cv;
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c8;
+  float sum[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sum[i] = 0.0f;
+  for (int t = 0; t < d.H * d.W; ++t) {
+    float v[8];
+    load8(x + (int64_t)t * d.Cp, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum[i] += v[i];
+  }
+  const float hw = (float)(d.H * d.W);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sum[i] = sum[i] / hw;
+  if (d.ext) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (c8 + i < d.Co) static_cast<float*>(a.ext_out[p])[(int64_t)n * d.Co + c8 + i] = sum[i];
+  } else if (d.out_f32) {
+    store8(reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)n * d.Cop + c8, sum);
+  } else {
+    store8(reinterpret_cast<TA*>(a.abase + d.y_off) + (int64_t)n * d.Cop + c8, sum);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// small-batch fully connected layer (batch <= 32): y = x W^T is a weight stream, so the
+// reduction is split across waves to put the whole chip on the weight matrix.  One wave owns
+// 32 output features x one slice of K: per 16 reduction elements it loads its 32x16 weight
+// block (each lane walks one weight row, 16 bytes at a time) and the 16x32 slice of x
+// (batch in the MFMA column dimension, rows past the batch are zero), issues one 32x32x16
+// MFMA (two for fp32 activations: hi/lo split), and finally writes its fp32 partial
+// [feature][batch] block to the workspace.  fc_reduce_kernel sums the partials in a fixed
+// order (deterministic), adds the bias, applies the activation and stores.
+// ---------------------------------------------------------------------------------
+template <bool WIDE>
+__global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_FC, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int lane = threadIdx.x & 63;
+  const int unit = bid * 4 + (threadIdx.x >> 6);
+  if (unit >= d.tiles_n * d.splits) return;
+  const int tile = unit % d.tiles_n, split = unit / d.tiles_n;
+  const int steps = d.Kp / 16;
+  const int per = (steps + d.splits - 1) / d.splits;
+  const int s0 = split * per, s1 = min(steps, s0 + per);
+  int f = tile * 32 + (lane & 31);
+  f = f < d.Co ? f : d.Co - 1;  // clamped rows are computed and discarded
+  const int kq = (lane >> 5) * 8;
+  const uint4* wp = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(a.wbase + d.w_off) + (int64_t)f * d.Kp + kq);
+  const int n = lane & 31;
+  const bool nok = n < a.batch;
+  const int K = d.Cp;  // flattened input length (elements), a multiple of 8
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+  constexpr int U = 8;
+  for (int sb = s0; sb < s1; sb += U) {
+    uint4 wv[U];
+    uint4 xv[U][WIDE ? 2 : 1];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int st = sb + u;
+      const bool ok = st < s1;
+      wv[u] = ok ? wp[st * 2] : make_uint4(0, 0, 0, 0);
+      const int k = st * 16 + kq;
+      const bool xok = ok && nok && k < K;
+      if constexpr (WIDE) {
+        const float* xp = reinterpret_cast<const float*>(a.abase + d.x_off) + (int64_t)n * K + k;
+        xv[u][0] = xok ? *reinterpret_cast<const uint4*>(xp) : make_uint4(0, 0, 0, 0);
+        xv[u][1] = xok ? *reinterpret_cast<const uint4*>(xp + 4) : make_uint4(0, 0, 0, 0);
+      } else {
+        const bf16_t* xp = reinterpret_cast<const bf16_t*>(a.abase + d.x_off) + (int64_t)n * K + k;
+        xv[u][0] = xok ? *reinterpret_cast<const uint4*>(xp) : make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bf16x8 wf = __builtin_bit_cast(bf16x8, wv[u]);
+      if constexpr (WIDE) {
+        uint4 hi, lo;
+        const uint32_t* s0p = reinterpret_cast<const uint32_t*>(&xv[u][0]);
+        uint32_t h[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x0 = __uint_as_float(s0p[2 * e]), x1 = __uint_as_float(s0p[2 * e + 1]);
+          const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);
+          h[e] = h0 | (h1 << 16);
+          l[e] = pack_bf16x2(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h1 << 16));
+        }
+        hi = make_uint4(h[0], h[1], h[2], h[3]);
+        lo = make_uint4(l[0], l[1], l[2], l[3]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, lo), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, hi), acc, 0, 0, 0);
+      } else {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, xv[u][0]), acc, 0, 0, 0);
+      }
+    }
+  }
+  // partial block: lane holds batch column n, features 8*g + 4*(lane/32) + t
+  if (nok) {
+    float* ws = reinterpret_cast<float*>(a.abase + d.r_off) + ((int64_t)split * a.batch + n) * d.Cop + tile * 32;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int fo = 8 * g + 4 * (lane >> 5);
+      if (tile * 32 + fo < d.Cop)
+        *reinterpret_cast<float4*>(ws + fo) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+    }
+  }
+}
+
+template <typename TA>
+__global__ void __launch_bounds__(256) fc_reduce_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_FC_REDUCE, 0, p, bid)) return;
+  const Desc d = a.descs[p];
+  const int q4 = d.Cop / 4;
+  const int idx = bid * 256 + threadIdx.x;
+  if (idx >= a.batch * q4) return;
+  const int o = (idx % q4) * 4, n = idx / q4;
+  const float* ws = reinterpret_cast<const float*>(a.abase + d.r_off) + (int64_t)n * d.Cop + o;
+  float4 sum = make_float4(0, 0, 0, 0);
+  for (int s = 0; s < d.splits; ++s) {
+    const float4 v = *reinterpret_cast<const float4*>(ws + (int64_t)s * a.batch * d.Cop);
+    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+  }
+  const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.wbase + d.b_off) + o);
+  float v[4] = {sum.x + b.x, sum.y + b.y, sum.z + b.z, sum.w + b.w};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) v[t] = (o + t < d.Co) ? activate(v[t], d.act) : 0.0f;
+  if (d.ext) {
+    float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)n * d.Co + o;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      if (o + t < d.Co) y[t] = v[t];
+  } else if (sizeof(TA) == 4 || d.out_f32) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) =
+        make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // host-side dispatch
 // ---------------------------------------------------------------------------------
 template <typename F>
@@ -550,19 +824,36 @@ int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vect
       if (wb) return go(conv_direct_kernel<bf16_t, float>, nb, 256, a, s);
       return go(conv_direct_kernel<float, float>, nb, 256, a, s);
     case K_CONV_MFMA:
-      if (!(wb && ab)) return (int)hipErrorInvalidValue;
-      if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2>, nb, 256, a, s);
-      if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2>, nb, 256, a, s);
-      if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2>, nb, 256, a, s);
-      return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2>, nb, 256, a, s);
-    case K_DWCONV:
+      if (!wb) return (int)hipErrorInvalidValue;
+      if (!ab) {  // fp32 activations: split-bf16 inputs
+        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, true>, nb, 256, a, s);
+        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, true>, nb, 256, a, s);
+        if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, true>, nb, 256, a, s);
+        return (int)hipErrorInvalidValue;
+      }
+      if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false>, nb, 256, a, s);
+      if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false>, nb, 256, a, s);
+      if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false>, nb, 256, a, s);
+      return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false>, nb, 256, a, s);
+    case K_DWCONV: {
+      const bool vec = hd[(size_t)L.first_desc].vec != 0;
+      if (vec) return ab ? go(dwconv_vec_kernel<bf16_t>, nb, 256, a, s) : go(dwconv_vec_kernel<float>, nb, 256, a, s);
       if (wb && ab) return go(dwconv_kernel<bf16_t, bf16_t>, nb, 256, a, s);
       if (wb) return go(dwconv_kernel<bf16_t, float>, nb, 256, a, s);
       return go(dwconv_kernel<float, float>, nb, 256, a, s);
+    }
     case K_MAXPOOL:
       return ab ? go(maxpool_kernel<bf16_t>, nb, 256, a, s) : go(maxpool_kernel<float>, nb, 256, a, s);
-    case K_GAP:
+    case K_GAP: {
+      const bool vec = hd[(size_t)L.first_desc].vec != 0;
+      if (vec) return ab ? go(gap_vec_kernel<bf16_t>, nb, 256, a, s) : go(gap_vec_kernel<float>, nb, 256, a, s);
       return ab ? go(gap_kernel<bf16_t>, nb, 256, a, s) : go(gap_kernel<float>, nb, 256, a, s);
+    }
+    case K_FC:
+      if (!wb) return (int)hipErrorInvalidValue;
+      return ab ? go(fc_kernel<false>, nb, 256, a, s) : go(fc_kernel<true>, nb, 256, a, s);
+    case K_FC_REDUCE:
+      return ab ? go(fc_reduce_kernel<bf16_t>, nb, 256, a, s) : go(fc_reduce_kernel<float>, nb, 256, a, s);
     case K_SOFTMAX:
       return go(softmax_kernel, nb, 64, a, s);
   }
