@@ -167,14 +167,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // multiplied by the bf16 weights into the same fp32 accumulator, and outputs / residuals stay
 // fp32: bf16 matrix-core throughput at fp32-grade activation accuracy.
 template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE>
-__global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
-  static_assert(WGM * WGN == 4, "four waves per workgroup");
+__global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
+  constexpr int NT = WGM * WGN * 64;     // threads per workgroup
+  constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
   constexpr int AE = WIDE ? 4 : 2;       // bytes per stored activation element
   constexpr int AV = WIDE ? 2 : 1;       // 16-byte loads per 8-element A vector
   constexpr int AT = WIDE ? 2 : 1;       // A tiles in LDS (hi, lo)
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // per-wave sub-tile
   constexpr int MI = WTM / 32, NI = WTN / 32;
-  constexpr int AR = BM / 32, BR = BN / 32;  // 16-byte vectors each thread stages per tile
+  constexpr int AR = BM / RPP, BR = BN / RPP;  // 8-element vectors each thread stages per tile
   constexpr int EPS = BN + 8;                // fp32 row stride of the epilogue tile
   constexpr int SMEM = (AT * BM + BN) * LDS_STRIDE * 2 > 64 * EPS * 4 ? (AT * BM + BN) * LDS_STRIDE * 2 : 64 * EPS * 4;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
@@ -204,24 +205,31 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 
   // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
   const int srow = tid >> 3, kvec = (tid & 7) * 8;
-  int a_ih0[AR], a_iw0[AR], a_base[AR];
+  // Per row: the byte offset of its window origin (n, p*stride-pad, q*stride-pad, 0) and which
+  // filter rows / columns land inside the image (bit r: row r valid; bit 8+s: column s valid).
+  int a_row[AR], a_rc[AR];
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
-    const int m = m0 + srow + 32 * i;
+    const int m = m0 + srow + RPP * i;
     const bool ok = m < M;
     const int mm = ok ? m : 0;
     const int q = mm % d.Wo;
     const int t = mm / d.Wo;
     const int pp = t % d.Ho;
     const int n = t / d.Ho;
-    a_ih0[i] = ok ? pp * d.stride - d.pad : -(1 << 20);  // rows past M read as zero
-    a_iw0[i] = q * d.stride - d.pad;
-    a_base[i] = n * d.H * d.W * d.Cp * AE;  // bytes
+    const int ih0 = pp * d.stride - d.pad, iw0 = q * d.stride - d.pad;
+    a_row[i] = ((n * d.H + ih0) * d.W + iw0) * d.Cp * AE;
+    int rc = 0;
+    for (int r = 0; r < d.k; ++r) {
+      rc |= ((unsigned)(ih0 + r) < (unsigned)d.H) ? (1 << r) : 0;
+      rc |= ((unsigned)(iw0 + r) < (unsigned)d.W) ? (256 << r) : 0;
+    }
+    a_rc[i] = ok ? rc : 0;  // rows past M read as zero
   }
   const uint4* b_ptr[BR];
 #pragma unroll
   for (int i = 0; i < BR; ++i) {
-    int o = n0 + srow + 32 * i;
+    int o = n0 + srow + RPP * i;
     o = o < d.Co ? o : d.Co - 1;  // clamped rows are computed and discarded
     b_ptr[i] = reinterpret_cast<const uint4*>(w + (int64_t)o * d.Kp + kvec);
   }
@@ -252,10 +260,10 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 
 #define FI_FETCH(KT)                                                                              \
   {                                                                                               \
+    const int tvar = ((kr * d.W + ks) * d.Cp + kc) * AE;                                          \
     _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
-      const int ih = a_ih0[i] + kr, iw = a_iw0[i] + ks;                                           \
-      const bool ok = kr < d.k && (unsigned)ih < (unsigned)d.H && (unsigned)iw < (unsigned)d.W;   \
-      const uint32_t off = ok ? (uint32_t)(a_base[i] + ((ih * d.W + iw) * d.Cp + kc) * AE) : OOB; \
+      const bool ok = ((a_rc[i] >> kr) & (a_rc[i] >> (8 + ks)) & 1) != 0;                         \
+      const uint32_t off = ok ? (uint32_t)(a_row[i] + tvar) : OOB;                                \
       _Pragma("unroll") for (int h = 0; h < AV; ++h)                                              \
           av[i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);             \
     }                                                                                             \
@@ -278,7 +286,7 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
 #pragma unroll
     for (int i = 0; i < AR; ++i) {
       if constexpr (!WIDE) {
-        *reinterpret_cast<u32x4*>(&As[(srow + 32 * i) * LDS_STRIDE + kvec]) = av[i][0];
+        *reinterpret_cast<u32x4*>(&As[(srow + RPP * i) * LDS_STRIDE + kvec]) = av[i][0];
       } else {
         u32x4 hi, lo;
 #pragma unroll
@@ -288,12 +296,12 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
           hi[e] = h0 | (h1 << 16);
           lo[e] = pack_bf16x2(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h1 << 16));
         }
-        *reinterpret_cast<u32x4*>(&As[(srow + 32 * i) * LDS_STRIDE + kvec]) = hi;
-        *reinterpret_cast<u32x4*>(&As[(BM + srow + 32 * i) * LDS_STRIDE + kvec]) = lo;
+        *reinterpret_cast<u32x4*>(&As[(srow + RPP * i) * LDS_STRIDE + kvec]) = hi;
+        *reinterpret_cast<u32x4*>(&As[(BM + srow + RPP * i) * LDS_STRIDE + kvec]) = lo;
       }
     }
 #pragma unroll
-    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + 32 * i) * LDS_STRIDE + kvec]) = bv[i];
+    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + RPP * i) * LDS_STRIDE + kvec]) = bv[i];
     __syncthreads();
     if (kt + 1 < ntiles) FI_FETCH(kt + 1)  // in flight while this tile is multiplied
 #pragma unroll
@@ -325,8 +333,8 @@ __global__ void __launch_bounds__(256) conv_mfma_kernel(KArgs a) {
   // The pass's residual vectors are requested before the accumulators are parked, so their
   // latency overlaps the LDS round trip instead of serialising behind it.
   constexpr int CPR = BN / 8;          // 8-channel chunks per tile row
-  constexpr int CH = 64 * CPR / 256;   // chunks per thread per pass
-  constexpr int RSTEP = 256 / CPR;     // row distance between a thread's chunks
+  constexpr int CH = 64 * CPR / NT;    // chunks per thread per pass
+  constexpr int RSTEP = NT / CPR;      // row distance between a thread's chunks
   float* ep = reinterpret_cast<float*>(smem);
   const int cc = (tid % CPR) * 8, lr0 = tid / CPR;
   const int o = n0 + cc;
