@@ -108,7 +108,7 @@ typedef struct {
   int32_t max_batch;         /* largest batch fi_run will be given (>= 1) */
   int32_t group_levels;      /* 1: same-depth nodes of different members share launches; 0: one launch per node */
   int32_t load_mode;         /* fi_load_mode */
-  int32_t reserved;
+  int32_t use_graph;         /* 1: fi_run replays the schedule as one HIP graph (needs a non-NULL stream) */
   uint64_t max_device_bytes; /* 0 = unlimited; else fi_build_dag fails with FI_EBUDGET beyond it */
   void* (*dev_alloc)(size_t bytes, void* user);
   void (*dev_free)(void* ptr, void* user);

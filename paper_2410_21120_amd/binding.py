@@ -43,7 +43,7 @@ FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
 
 class fi_build_opts(C.Structure):
     _fields_ = [("max_batch", C.c_int32), ("group_levels", C.c_int32), ("load_mode", C.c_int32),
-                ("reserved", C.c_int32), ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
+                ("use_graph", C.c_int32), ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
                 ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p)]
 
 
@@ -281,10 +281,11 @@ class Dag:
     """Owner of one fi_dag handle."""
 
     def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
-                 max_device_bytes=0, keepalive=None):
+                 max_device_bytes=0, keepalive=None, use_graph=False):
         self.keepalive = (specs, keepalive, allocators)
         opts = fi_build_opts()
         opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
+        opts.use_graph = int(use_graph)
         if allocators is not None:
             allocators.apply(opts)
         self.opts = opts

@@ -45,6 +45,11 @@ struct fi_dag {
   uint8_t* dev = nullptr;             // the one device allocation (LOADED only)
   int32_t state = 0;
   uint64_t macs = 0;
+  // captured launch schedule (use_graph): valid for exactly these call arguments
+  hipGraphExec_t gexec = nullptr;
+  int32_t g_batch = 0;
+  const void* g_input = nullptr;
+  std::vector<void*> g_outputs;
 };
 
 using namespace fi;
@@ -110,7 +115,7 @@ const char* kind_name(int kind, int tile) {
     case K_GAP: return "global_avgpool";
     case K_SOFTMAX: return "softmax";
     case K_FC: return "fc_splitk";
-    case K_FC_REDUCE: return "fc_reduce";
+    case K_REDUCE: return "splitk_reduce";
   }
   return "?";
 }
@@ -211,6 +216,15 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
           nd.splits = std::max(1, std::min(std::min(64, std::max(1, steps / 8)), std::max(1, 2048 / tiles)));
         } else if (g->wdtype == FI_BF16) {
           nd.kind = K_CONV_MFMA;
+          {
+            // Small problems cannot cover the chip and walk a long serial reduction: split K.  The split
+            // count depends on the node's own shape only (it fixes the summation order, and a member's bits
+            // must not depend on its co-members).
+            const int64_t M = (int64_t)B * nd.Ho * nd.Wo;
+            const int64_t nb64 = ((M + 63) / 64) * ((nd.Co + 63) / 64);
+            const int ntiles = (nd.Kp + 63) / 64;
+            nd.splits = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, ntiles / 4), 256 / nb64));
+          }
           // the kernel addresses its input with 32-bit byte offsets through a buffer resource
           if ((uint64_t)B * nd.H * nd.W * nd.Cp * esize(adt) >= (1ull << 31)) {
             set_error("model %d node %d: input tensor of %llu bytes exceeds the 2 GiB a conv kernel addresses",
@@ -249,7 +263,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       Node& nd = g->nodes[(size_t)i];
       if (nd.level != lv) continue;
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const auto key = std::make_tuple(nd.kind, nd.tile, adt);
+      const auto key = std::make_tuple(nd.kind, nd.tile, adt * 2 + (nd.kind == K_CONV_MFMA && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
       if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
         new_launch(lv, nd.kind, nd.tile, adt);
@@ -264,9 +278,11 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
     // every split-K FC launch is followed by the launch that reduces its partials
     const size_t level_end = g->launches.size();
     for (size_t li = 0; li < level_end; ++li) {
-      if (g->launches[li].level != lv || g->launches[li].kind != K_FC) continue;
-      const Launch src = g->launches[li];
-      Launch& R = new_launch(lv, K_FC_REDUCE, 0, src.adtype);
+      const Launch& cand = g->launches[li];
+      const bool split_conv = cand.kind == K_CONV_MFMA && !cand.nodes.empty() && g->nodes[(size_t)cand.nodes[0]].splits > 1;
+      if (cand.level != lv || !(cand.kind == K_FC || split_conv)) continue;
+      const Launch src = cand;
+      Launch& R = new_launch(lv, K_REDUCE, 0, src.adtype);
       R.n = src.n;
       R.nodes = src.nodes;
     }
@@ -339,10 +355,10 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   {
     std::map<int32_t, uint64_t> level_top;
     for (Node& nd : g->nodes) {
-      if (nd.kind != K_FC) continue;
+      if (!(nd.kind == K_FC || (nd.kind == K_CONV_MFMA && nd.splits > 1))) continue;
       uint64_t& top = level_top[nd.level];
       nd.ws_off = top;
-      top += align_up((uint64_t)nd.splits * B * nd.Cop * 4);
+      top += align_up((uint64_t)nd.splits * B * nd.Ho * nd.Wo * nd.Cop * 4);
       g->workspace_bytes = std::max(g->workspace_bytes, top);
     }
   }
@@ -380,13 +396,11 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       d.out_f32 = (nd.out_dtype == FI_F32 && adt != FI_F32) ? 1 : 0;
       if (nd.out_dtype == FI_F32 && adt != FI_F32 && !nd.is_output) d.Cop = nd.Cop;  // fp32 rows keep the padded stride
       d.tiles_n = L.kind == K_CONV_MFMA ? (nd.Co + tile_bn(L.tile) - 1) / tile_bn(L.tile) : 0;
-      if (L.kind == K_FC || L.kind == K_FC_REDUCE) {
-        d.tiles_n = (nd.Co + 31) / 32;
-        d.splits = nd.splits;
-        d.r_off = g->act_bytes + nd.ws_off;  // the workspace follows the activation arena
-      }
-      if (L.kind == K_FC_REDUCE) {
-        L.act_bytes += (uint64_t)nd.splits * nd.Cop * 4 + (uint64_t)nd.Co * esize(nd.out_dtype);
+      d.splits = std::max(1, nd.splits);
+      d.ws_off = g->act_bytes + nd.ws_off;  // the workspace follows the activation arena
+      if (L.kind == K_FC) d.tiles_n = (nd.Co + 31) / 32;
+      if (L.kind == K_REDUCE) {
+        L.act_bytes += ((uint64_t)nd.splits * nd.Cop * 4 + (uint64_t)nd.Co * esize(nd.out_dtype)) * nd.Ho * nd.Wo;
         continue;
       }
       L.macs += nd.macs;
@@ -526,8 +540,39 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   return rc;
 }
 
+static void drop_graph(fi_dag* g) {
+  if (g->gexec) { (void)hipGraphExecDestroy(g->gexec); g->gexec = nullptr; }
+}
+
 fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream) {
-  return run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0);
+  if (!g || !g->opts.use_graph || !stream) return run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0);
+  // One HIP graph holds the whole schedule; it is rebuilt when the batch or a buffer changes.
+  if (!d_input || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
+  if (g->state != 1) { set_error("fi_run: handle is not loaded"); return FI_ESTATE; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  bool same = g->gexec && g->g_batch == batch && g->g_input == d_input;
+  for (size_t m = 0; same && m < g->members.size(); ++m) same = g->g_outputs[m] == d_outputs[m];
+  if (!same) {
+    drop_graph(g);
+    hipGraph_t graph = nullptr;
+    if (hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+      (void)hipGetLastError();
+      return run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0);  // this stream cannot capture
+    }
+    const fi_status rc = run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0);
+    const hipError_t e = hipStreamEndCapture(s, &graph);
+    if (rc != FI_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (e != hipSuccess || !graph) { set_error("hipStreamEndCapture: %s", hipGetErrorString(e)); return FI_EHIP; }
+    const hipError_t ei = hipGraphInstantiate(&g->gexec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (ei != hipSuccess) { g->gexec = nullptr; set_error("hipGraphInstantiate: %s", hipGetErrorString(ei)); return FI_EHIP; }
+    g->g_batch = batch;
+    g->g_input = d_input;
+    g->g_outputs.assign(d_outputs, d_outputs + g->members.size());
+  }
+  const hipError_t e = hipGraphLaunch(g->gexec, s);
+  if (e != hipSuccess) { set_error("hipGraphLaunch: %s", hipGetErrorString(e)); return FI_EHIP; }
+  return FI_OK;
 }
 
 fi_status fi_profile(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream, float* ms, int32_t n_ms) {
@@ -539,6 +584,7 @@ fi_status fi_unload(fi_dag* g) {
   if (!g) { set_error("null handle"); return FI_EINVAL; }
   if (g->state != 1) { set_error("fi_unload: handle is not loaded"); return FI_ESTATE; }
   (void)hipDeviceSynchronize();
+  drop_graph(g);
   if (g->opts.dev_free) g->opts.dev_free(g->dev, g->opts.user); else (void)hipFree(g->dev);
   g->dev = nullptr;
   g->state = 0;

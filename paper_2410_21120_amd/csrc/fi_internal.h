@@ -23,7 +23,7 @@ enum Kind : int32_t {
   K_GAP = 5,
   K_SOFTMAX = 6,
   K_FC = 7,           // small-batch fully connected: weight-streaming split-K partial products
-  K_FC_REDUCE = 8,    // sums the partials, adds bias, applies the activation, stores
+  K_REDUCE = 8,       // finishes a split-K node: sums partials, bias, residual, activation, store
   K_NKINDS
 };
 
@@ -51,8 +51,9 @@ struct Desc {
   int32_t out_f32;               // 1: output stored as fp32 whatever the activation dtype
   int32_t tiles_n;               // MFMA conv: column tiles
   int32_t vec;                   // 1: bf16 tensors with Cp % 8 == 0, kernels work on 8-channel vectors
-  int32_t splits;                // K_FC: reduction splits (partials live at r_off, fp32 [splits][batch][Cop])
-  int32_t rsv[4];
+  int32_t splits;                // reduction splits (>1: fp32 partials [splits][rows][Cop] at ws_off)
+  uint64_t ws_off;               // split-K partials, relative to the activation base
+  int32_t rsv[2];
 };
 static_assert(sizeof(Desc) == 128, "Desc is 128 bytes");
 
@@ -68,8 +69,8 @@ struct Node {
   int32_t first_level, last_level;
   int32_t launch, slot;          // launch index and problem slot inside it
   int32_t kind, tile;
-  int32_t splits;                // K_FC only
-  uint64_t ws_off;               // K_FC only: partials, relative to the workspace
+  int32_t splits;                // reduction splits (1 = none)
+  uint64_t ws_off;               // partials of a split node, relative to the workspace
   uint64_t w_rel, b_rel;         // offsets inside the member's packed blob
   uint64_t w_off, b_off;         // offsets in the weight arena
   uint64_t out_off, out_bytes;   // activation arena placement (bytes at max_batch)

@@ -44,14 +44,14 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_CONV_DIRECT: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
     case K_CONV_MFMA: {
       const int bm = tile_bm(tile);
-      return ((batch * d.Ho * d.Wo + bm - 1) / bm) * d.tiles_n;
+      return ((batch * d.Ho * d.Wo + bm - 1) / bm) * d.tiles_n * d.splits;
     }
     case K_DWCONV: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_MAXPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_GAP: return (batch * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256;
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits + 3) / 4;
-    case K_FC_REDUCE: return (batch * (d.Cop / 4) + 255) / 256;
+    case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
   }
   return 0;
 }
@@ -192,6 +192,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   if (p == a.n) return;
   const Desc d = a.descs[p];
   const int M = a.batch * d.Ho * d.Wo;
+  const int tiles_mn = ((M + BM - 1) / BM) * d.tiles_n;
+  const int split = bid / tiles_mn;  // split-K: this workgroup reduces one slice of K into a partial tile
+  bid -= split * tiles_mn;
   const int m0 = (bid / d.tiles_n) * BM;
   const int n0 = (bid % d.tiles_n) * BN;
 
@@ -234,15 +237,17 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     b_ptr[i] = reinterpret_cast<const uint4*>(w + (int64_t)o * d.Kp + kvec);
   }
   // this thread's reduction position (r, s, c) for the tile being fetched
-  int kr = 0, ks = 0, kc = kvec;
-#pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    const bool wrap = kc >= d.Cp;
-    kc -= wrap ? d.Cp : 0;
-    ks += wrap ? 1 : 0;
-    const bool wrap2 = ks == d.k;
-    ks = wrap2 ? 0 : ks;
-    kr += wrap2 ? 1 : 0;
+  const int ntiles_all = (d.Kp + BK - 1) / BK;
+  const int per_split = (ntiles_all + d.splits - 1) / d.splits;
+  const int kt0 = split * per_split;
+  const int ntiles = min(ntiles_all, kt0 + per_split);  // this workgroup multiplies tiles [kt0, ntiles)
+  int kr, ks, kc;
+  {
+    const int k0 = kt0 * BK + kvec;
+    const int rs = k0 / d.Cp;
+    kc = k0 - rs * d.Cp;
+    kr = rs / d.k;
+    ks = rs - kr * d.k;
   }
 
   f32x16 acc[MI][NI];
@@ -255,7 +260,6 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 
   u32x4 av[AR][AV];
   uint4 bv[BR];
-  const int ntiles = (d.Kp + BK - 1) / BK;
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
 
 #define FI_FETCH(KT)                                                                              \
@@ -267,7 +271,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       _Pragma("unroll") for (int h = 0; h < AV; ++h)                                              \
           av[i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);             \
     }                                                                                             \
-    const bool bok = !(b_tail && (KT) == ntiles - 1 && kvec >= 32);                               \
+    const bool bok = !(b_tail && (KT) == ntiles_all - 1 && kvec >= 32);                               \
     _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
         bv[i] = bok ? b_ptr[i][(KT) * (BK / 8)] : make_uint4(0, 0, 0, 0);                         \
     kc += BK;                                                                                     \
@@ -281,8 +285,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     }                                                                                             \
   }
 
-  FI_FETCH(0)
-  for (int kt = 0; kt < ntiles; ++kt) {
+  if (kt0 < ntiles) FI_FETCH(kt0)
+  for (int kt = kt0; kt < ntiles; ++kt) {
 #pragma unroll
     for (int i = 0; i < AR; ++i) {
       if constexpr (!WIDE) {
@@ -357,7 +361,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 #pragma unroll
       for (int h = 0; h < AV; ++h) {
         rv[ch][h] = make_uint4(0, 0, 0, 0);
-        if (res && col_ok && m < M) rv[ch][h] = *reinterpret_cast<const uint4*>(res + ((int64_t)m * d.Cop + o) * AE + 16 * h);
+        if (res && d.splits == 1 && col_ok && m < M) rv[ch][h] = *reinterpret_cast<const uint4*>(res + ((int64_t)m * d.Cop + o) * AE + 16 * h);
       }
     }
     if (pass > 0) __syncthreads();
@@ -382,6 +386,12 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       float v[8];
       const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
       const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
+      if (d.splits > 1) {  // raw partial sums; the reduce launch finishes the node
+        float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
+        *reinterpret_cast<float4*>(ws) = v0;
+        *reinterpret_cast<float4*>(ws + 4) = v1;
+        continue;
+      }
       v[0] = v0.x + bias8[0]; v[1] = v0.y + bias8[1]; v[2] = v0.z + bias8[2]; v[3] = v0.w + bias8[3];
       v[4] = v1.x + bias8[4]; v[5] = v1.y + bias8[5]; v[6] = v1.z + bias8[6]; v[7] = v1.w + bias8[7];
       if constexpr (WIDE) {
@@ -693,7 +703,7 @@ __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
 // block (each lane walks one weight row, 16 bytes at a time) and the 16x32 slice of x
 // (batch in the MFMA column dimension, rows past the batch are zero), issues one 32x32x16
 // MFMA (two for fp32 activations: hi/lo split), and finally writes its fp32 partial
-// [feature][batch] block to the workspace.  fc_reduce_kernel sums the partials in a fixed
+// [feature][batch] block to the workspace.  reduce_kernel sums the partials in a fixed
 // order (deterministic), adds the bias, applies the activation and stores.
 // ---------------------------------------------------------------------------------
 template <bool WIDE>
@@ -763,7 +773,7 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
   }
   // partial block: lane holds batch column n, features 8*g + 4*(lane/32) + t
   if (nok) {
-    float* ws = reinterpret_cast<float*>(a.abase + d.r_off) + ((int64_t)split * a.batch + n) * d.Cop + tile * 32;
+    float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * a.batch + n) * d.Cop + tile * 32;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int fo = 8 * g + 4 * (lane >> 5);
@@ -773,23 +783,31 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
   }
 }
 
+// Finishes a split-K node (small-batch FC or a split convolution): sums the fp32 partials
+// [splits][rows][Cop] in split order, adds bias (and residual), applies the activation, stores.
 template <typename TA>
-__global__ void __launch_bounds__(256) fc_reduce_kernel(KArgs a) {
+__global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
   int p, bid;
-  if (!find_problem(a, K_FC_REDUCE, 0, p, bid)) return;
+  if (!find_problem(a, K_REDUCE, 0, p, bid)) return;
   const Desc d = a.descs[p];
   const int q4 = d.Cop / 4;
+  const int rows = a.batch * d.Ho * d.Wo;
   const int idx = bid * 256 + threadIdx.x;
-  if (idx >= a.batch * q4) return;
+  if (idx >= rows * q4) return;
   const int o = (idx % q4) * 4, n = idx / q4;
-  const float* ws = reinterpret_cast<const float*>(a.abase + d.r_off) + (int64_t)n * d.Cop + o;
+  const float* ws = reinterpret_cast<const float*>(a.abase + d.ws_off) + (int64_t)n * d.Cop + o;
   float4 sum = make_float4(0, 0, 0, 0);
   for (int s = 0; s < d.splits; ++s) {
-    const float4 v = *reinterpret_cast<const float4*>(ws + (int64_t)s * a.batch * d.Cop);
+    const float4 v = *reinterpret_cast<const float4*>(ws + (int64_t)s * rows * d.Cop);
     sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
   }
   const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.wbase + d.b_off) + o);
   float v[4] = {sum.x + b.x, sum.y + b.y, sum.z + b.z, sum.w + b.w};
+  if (d.r_off != kNone) {
+    const TA* r = reinterpret_cast<const TA*>(a.abase + d.r_off) + (int64_t)n * d.Cop + o;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) v[t] += ld(r + t);
+  }
 #pragma unroll
   for (int t = 0; t < 4; ++t) v[t] = (o + t < d.Co) ? activate(v[t], d.act) : 0.0f;
   if (d.ext) {
@@ -860,8 +878,8 @@ int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vect
     case K_FC:
       if (!wb) return (int)hipErrorInvalidValue;
       return ab ? go(fc_kernel<false>, nb, 256, a, s) : go(fc_kernel<true>, nb, 256, a, s);
-    case K_FC_REDUCE:
-      return ab ? go(fc_reduce_kernel<bf16_t>, nb, 256, a, s) : go(fc_reduce_kernel<float>, nb, 256, a, s);
+    case K_REDUCE:
+      return ab ? go(reduce_kernel<bf16_t>, nb, 256, a, s) : go(reduce_kernel<float>, nb, 256, a, s);
     case K_SOFTMAX:
       return go(softmax_kernel, nb, 64, a, s);
   }

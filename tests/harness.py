@@ -23,7 +23,7 @@ def rel_l2(a, ref):
 class GpuDag:
     """Builds one fused DAG from (model, blob[, act_dtype]) members and runs it."""
 
-    def __init__(self, members, max_batch, group_levels=True, load_mode=fi.FI_LOAD_ONE_COPY, packed=False):
+    def __init__(self, members, max_batch, group_levels=True, load_mode=fi.FI_LOAD_ONE_COPY, packed=False, use_graph=False):
         import torch
         self.torch = torch
         self.alloc = fi.TorchAllocators("cuda:0")
@@ -35,8 +35,10 @@ class GpuDag:
             spec, k = fi.make_spec(model, blob.ctypes.data, blob.nbytes, act_dtype=act, packed=packed)
             specs.append(spec)
             keep.append((k, blob))
-        self.dag = fi.Dag(specs, max_batch, self.alloc, group_levels=group_levels, load_mode=load_mode, keepalive=keep)
-        self.stream = torch.cuda.current_stream().cuda_stream
+        self.dag = fi.Dag(specs, max_batch, self.alloc, group_levels=group_levels, load_mode=load_mode, keepalive=keep,
+                          use_graph=use_graph)
+        self.side = torch.cuda.Stream() if use_graph else None  # graph capture needs a non-default stream
+        self.stream = self.side.cuda_stream if use_graph else torch.cuda.current_stream().cuda_stream
         self.dag.load(self.stream)
         self.out_elems = [L.cout * L.out_h * L.out_w for L in (m.layers[m.output] for m in self.models)]
 
@@ -48,8 +50,20 @@ class GpuDag:
         st = gen.to_nhwc_storage(x_nchw, dtype)
         xin = torch.from_numpy(st.view(np.int16) if dtype == "bf16" else st).cuda()
         b = x_nchw.shape[0]
-        outs = [torch.full((b, n), float("nan"), dtype=torch.float32, device="cuda:0") for n in self.out_elems]
+        if getattr(self, "keep_buffers", None) and self.keep_buffers[0] == b:
+            _, kin, kouts = self.keep_buffers  # same device buffers as last time: lets a captured graph replay
+            kin.copy_(xin)
+            xin, outs_reuse = kin, kouts
+        else:
+            outs_reuse = None
+        outs = outs_reuse if outs_reuse is not None else [torch.full((b, n), float("nan"), dtype=torch.float32, device="cuda:0") for n in self.out_elems]
+        if outs_reuse is not None:
+            for o in outs:
+                o.fill_(float("nan"))
+        self.keep_buffers = (b, xin, outs)
         ptrs = [o.data_ptr() for o in outs]
+        if self.side is not None:
+            torch.cuda.synchronize()  # inputs were prepared on torch's current stream
         if profile:
             ms = self.dag.profile(xin.data_ptr(), b, ptrs, self.stream)
         else:

@@ -64,7 +64,7 @@ def test_union_levels_and_operator_count():
     for li, L in enumerate(launches):
         assert 1 <= L.n_problems <= fi.FI_MAX_GROUP
         members = [n for n in nodes if n.launch == li and not (L.level == 0)]
-        if L.level > 0 and L.name != b"fc_reduce":  # the reduce launch re-visits its FC launch's nodes
+        if L.level > 0 and L.name != b"splitk_reduce":  # the reduce launch re-visits its FC launch's nodes
             assert len(members) == L.n_problems and all(n.level == L.level for n in members)
             for n in members:
                 assert (n.model, n.index) not in seen
@@ -78,9 +78,10 @@ def test_grouping_reduces_launches_only():
     g, _, _ = _build(fams, 4)
     u, _, _ = _build(fams, 4, group=False)
     qg, qu = g.query(), u.query()
-    n_fc = sum(1 for n in u.nodes() if n.op == fi.FI_FC)  # each small-batch FC launch has a reduce twin
-    assert qu.n_launches == 1 + qu.n_nodes + n_fc
-    assert qg.n_launches <= 1 + qg.n_levels + 8 + 1 and qg.n_nodes == qu.n_nodes
+    n_red = sum(1 for L in u.launches() if L.name == b"splitk_reduce")  # split-K launches have a reduce twin
+    assert n_red >= sum(1 for n in u.nodes() if n.op == fi.FI_FC)
+    assert qu.n_launches == 1 + qu.n_nodes + n_red
+    assert qg.n_launches <= 2 * (1 + qg.n_levels) + 8 and qg.n_nodes == qu.n_nodes
     assert qg.arena_bytes == qu.arena_bytes + (0)  # same weights either way (tables are per node)
     assert qg.act_bytes == qu.act_bytes
 
