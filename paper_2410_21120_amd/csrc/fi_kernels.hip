@@ -56,15 +56,17 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
   return 0;
 }
 
-// Walks the descriptor range; on return `bid` is the workgroup index inside problem `p`.
-__device__ __forceinline__ bool find_problem(const KArgs& a, int kind, int tile, int& p, int& bid) {
-  bid = blockIdx.x;
-  for (p = 0; p < a.n; ++p) {
-    const int t = problem_blocks(kind, tile, a.descs[p], a.batch);
-    if (bid < t) return true;
-    bid -= t;
-  }
-  return false;
+// Finds the problem a workgroup belongs to from the per-launch table of starting workgroup
+// indices (kernel arguments: no memory round trip); on return `bid` is the index inside problem `p`.
+__device__ __forceinline__ bool find_problem_at(const KArgs& a, int gid, int& p, int& bid) {
+  p = 0;
+#pragma unroll
+  for (int i = 1; i < FI_MAX_GROUP; ++i) p += (i < a.n && gid >= a.first_block[i]) ? 1 : 0;
+  bid = gid - a.first_block[p];
+  return gid < a.first_block[a.n];
+}
+__device__ __forceinline__ bool find_problem(const KArgs& a, int, int, int& p, int& bid) {
+  return find_problem_at(a, (int)blockIdx.x, p, bid);
 }
 
 // ---------------------------------------------------------------------------------
@@ -166,8 +168,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // hi = bf16(x) and lo = bf16(x - hi) (two bf16 terms carry 16 mantissa bits), both halves are
 // multiplied by the bf16 weights into the same fp32 accumulator, and outputs / residuals stay
 // fp32: bf16 matrix-core throughput at fp32-grade activation accuracy.
-template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE>
-__global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, int NS = 1>
+__global__ void __launch_bounds__(WGM * WGN * 64, (BM == 256 && NS == 1) ? 2 : 1) conv_mfma_kernel(KArgs a) {
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
   constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
   constexpr int AE = WIDE ? 4 : 2;       // bytes per stored activation element
@@ -176,20 +178,16 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // per-wave sub-tile
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int AR = BM / RPP, BR = BN / RPP;  // 8-element vectors each thread stages per tile
-  constexpr int EPS = BN + 8;                // fp32 row stride of the epilogue tile
-  constexpr int SMEM = (AT * BM + BN) * LDS_STRIDE * 2 > 64 * EPS * 4 ? (AT * BM + BN) * LDS_STRIDE * 2 : 64 * EPS * 4;
+  constexpr int EPS = BN + 4;                // fp32 row stride of the epilogue tile (16-byte writes spread over all banks)
+  constexpr int STAGE = (AT * BM + BN) * LDS_STRIDE;   // bf16 elements per LDS buffer
+  constexpr int SMEM = NS * STAGE * 2 > 64 * EPS * 4 ? NS * STAGE * 2 : 64 * EPS * 4;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
-  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);   // [AT][BM][LDS_STRIDE]
+  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);   // [NS][AT][BM][LDS_STRIDE] then B
   bf16_t* const Bs = As + AT * BM * LDS_STRIDE;
 
   // locate the problem and the tile (block-uniform)
-  int p = 0, bid = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
-  for (; p < a.n; ++p) {
-    const int t = problem_blocks(K_CONV_MFMA, TILE, a.descs[p], a.batch);
-    if (bid < t) break;
-    bid -= t;
-  }
-  if (p == a.n) return;
+  int p, bid;
+  if (!find_problem_at(a, xcd_contiguous((int)blockIdx.x, (int)gridDim.x), p, bid)) return;
   const Desc d = a.descs[p];
   const int M = a.batch * d.Ho * d.Wo;
   const int tiles_mn = ((M + BM - 1) / BM) * d.tiles_n;
@@ -258,22 +256,25 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  u32x4 av[AR][AV];
-  uint4 bv[BR];
+  // NS register stages feed NS LDS buffers.  NS == 1: fetch one tile ahead, two barriers per
+  // tile.  NS == 2 (DEEP): fetch two tiles ahead and alternate LDS buffers, one barrier per tile;
+  // a tile's loads then have two full multiply phases to land.
+  u32x4 av[NS][AR][AV];
+  uint4 bv[NS][BR];
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
 
-#define FI_FETCH(KT)                                                                              \
+#define FI_FETCH(KT, S)                                                                           \
   {                                                                                               \
     const int tvar = ((kr * d.W + ks) * d.Cp + kc) * AE;                                          \
     _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
       const bool ok = ((a_rc[i] >> kr) & (a_rc[i] >> (8 + ks)) & 1) != 0;                         \
       const uint32_t off = ok ? (uint32_t)(a_row[i] + tvar) : OOB;                                \
       _Pragma("unroll") for (int h = 0; h < AV; ++h)                                              \
-          av[i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);             \
+          av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);          \
     }                                                                                             \
-    const bool bok = !(b_tail && (KT) == ntiles_all - 1 && kvec >= 32);                               \
+    const bool bok = !(b_tail && (KT) == ntiles_all - 1 && kvec >= 32);                           \
     _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
-        bv[i] = bok ? b_ptr[i][(KT) * (BK / 8)] : make_uint4(0, 0, 0, 0);                         \
+        bv[S][i] = bok ? b_ptr[i][(KT) * (BK / 8)] : make_uint4(0, 0, 0, 0);                      \
     kc += BK;                                                                                     \
     _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                               \
       const bool wrap = kc >= d.Cp;                                                               \
@@ -285,52 +286,104 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     }                                                                                             \
   }
 
-  if (kt0 < ntiles) FI_FETCH(kt0)
-  for (int kt = kt0; kt < ntiles; ++kt) {
-#pragma unroll
-    for (int i = 0; i < AR; ++i) {
-      if constexpr (!WIDE) {
-        *reinterpret_cast<u32x4*>(&As[(srow + RPP * i) * LDS_STRIDE + kvec]) = av[i][0];
-      } else {
-        u32x4 hi, lo;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float x0 = __uint_as_float(av[i][e >> 1][(2 * e) & 3]), x1 = __uint_as_float(av[i][e >> 1][(2 * e + 1) & 3]);
-          const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);
-          hi[e] = h0 | (h1 << 16);
-          lo[e] = pack_bf16x2(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h1 << 16));
-        }
-        *reinterpret_cast<u32x4*>(&As[(srow + RPP * i) * LDS_STRIDE + kvec]) = hi;
-        *reinterpret_cast<u32x4*>(&As[(BM + srow + RPP * i) * LDS_STRIDE + kvec]) = lo;
+#define FI_PARK(S)                                                                                \
+  {                                                                                               \
+    bf16_t* const Ap = As + (S) * STAGE;                                                          \
+    bf16_t* const Bp = Bs + (S) * STAGE;                                                          \
+    _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
+      if constexpr (!WIDE) {                                                                      \
+        *reinterpret_cast<u32x4*>(&Ap[(srow + RPP * i) * LDS_STRIDE + kvec]) = av[S][i][0];       \
+      } else {                                                                                    \
+        u32x4 hi, lo;                                                                             \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
+          const float x0 = __uint_as_float(av[S][i][e >> 1][(2 * e) & 3]);                        \
+          const float x1 = __uint_as_float(av[S][i][e >> 1][(2 * e + 1) & 3]);                    \
+          const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);                                            \
+          hi[e] = h0 | (h1 << 16);                                                                \
+          lo[e] = pack_bf16x2(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h1 << 16));    \
+        }                                                                                         \
+        *reinterpret_cast<u32x4*>(&Ap[(srow + RPP * i) * LDS_STRIDE + kvec]) = hi;                \
+        *reinterpret_cast<u32x4*>(&Ap[(BM + srow + RPP * i) * LDS_STRIDE + kvec]) = lo;           \
+      }                                                                                           \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
+        *reinterpret_cast<uint4*>(&Bp[(srow + RPP * i) * LDS_STRIDE + kvec]) = bv[S][i];          \
+  }
+
+  // Fragments of reduction step kk+16 are requested from LDS before the MFMAs of step kk are
+  // issued (two register sets), and scheduling fences keep that order: a wave's matrix pipe
+  // then overlaps its own LDS latency instead of waiting on every operand pair.
+#define FI_LOADFRAGS(Ap, Bp, KK, F)                                                               \
+  {                                                                                               \
+    const int kof = (KK) + (lane >> 5) * 8;                                                       \
+    _Pragma("unroll") for (int h = 0; h < AT; ++h)                                                \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                \
+        af[F][h][i] = *reinterpret_cast<const bf16x8*>(                                           \
+            &Ap[(h * BM + wm * WTM + i * 32 + (lane & 31)) * LDS_STRIDE + kof]);                  \
+    _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                \
+        bfr[F][j] = *reinterpret_cast<const bf16x8*>(&Bp[(wn * WTN + j * 32 + (lane & 31)) * LDS_STRIDE + kof]); \
+  }
+#define FI_MFMAS(F)                                                                               \
+  {                                                                                               \
+    _Pragma("unroll") for (int h = AT - 1; h >= 0; --h) /* small (lo) terms first */              \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                \
+    _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[F][j], af[F][h][i], acc[i][j], 0, 0, 0); \
+  }
+#define FI_MULTIPLY(S)                                                                            \
+  {                                                                                               \
+    const bf16_t* const Ap = As + (S) * STAGE;                                                    \
+    const bf16_t* const Bp = Bs + (S) * STAGE;                                                    \
+    bf16x8 af[2][AT][MI], bfr[2][NI];                                                             \
+    FI_LOADFRAGS(Ap, Bp, 0, 0)                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    FI_LOADFRAGS(Ap, Bp, 16, 1)                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    FI_MFMAS(0)                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    FI_LOADFRAGS(Ap, Bp, 32, 0)                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    FI_MFMAS(1)                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    FI_LOADFRAGS(Ap, Bp, 48, 1)                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    FI_MFMAS(0)                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    FI_MFMAS(1)                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+  }
+
+  if constexpr (NS == 1) {
+    if (kt0 < ntiles) FI_FETCH(kt0, 0)
+    for (int kt = kt0; kt < ntiles; ++kt) {
+      FI_PARK(0)
+      __syncthreads();
+      if (kt + 1 < ntiles) FI_FETCH(kt + 1, 0)  // in flight while this tile is multiplied
+      FI_MULTIPLY(0)
+      __syncthreads();  // every wave is done with this tile before it is overwritten
+    }
+  } else {
+    if (kt0 < ntiles) FI_FETCH(kt0, 0)
+    if (kt0 + 1 < ntiles) FI_FETCH(kt0 + 1, 1)
+    for (int kt = kt0; kt < ntiles; kt += 2) {
+      FI_PARK(0)
+      __syncthreads();  // tile kt is in buffer 0; buffer 1 was last read two steps ago
+      if (kt + 2 < ntiles) FI_FETCH(kt + 2, 0)
+      FI_MULTIPLY(0)
+      if (kt + 1 < ntiles) {
+        FI_PARK(1)
+        __syncthreads();
+        if (kt + 3 < ntiles) FI_FETCH(kt + 3, 1)
+        FI_MULTIPLY(1)
       }
     }
-#pragma unroll
-    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(&Bs[(srow + RPP * i) * LDS_STRIDE + kvec]) = bv[i];
-    __syncthreads();
-    if (kt + 1 < ntiles) FI_FETCH(kt + 1)  // in flight while this tile is multiplied
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 af[AT][MI], bfr[NI];
-      const int kof = kk + (lane >> 5) * 8;
-#pragma unroll
-      for (int h = 0; h < AT; ++h)
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-          af[h][i] = *reinterpret_cast<const bf16x8*>(&As[(h * BM + wm * WTM + i * 32 + (lane & 31)) * LDS_STRIDE + kof]);
-#pragma unroll
-      for (int j = 0; j < NI; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * WTN + j * 32 + (lane & 31)) * LDS_STRIDE + kof]);
-#pragma unroll
-      for (int h = AT - 1; h >= 0; --h)  // small (lo) terms first
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int j = 0; j < NI; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();  // every wave is done with this tile before it is overwritten
+    __syncthreads();  // the epilogue reuses the tile memory
   }
 #undef FI_FETCH
+#undef FI_PARK
+#undef FI_MULTIPLY
+#undef FI_LOADFRAGS
+#undef FI_MFMAS
 
   // ---- epilogue: 64 output rows per pass through an fp32 LDS tile ----------------------
   // A thread owns one 8-channel column chunk (the same in every pass) and CH rows per pass.
@@ -369,13 +422,15 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     for (int i = 0; i < MI; ++i) {
       const int rb = wm * WTM + i * 32;  // first row of this MFMA block inside the tile
       if (rb / 64 != pass) continue;
+      // with the weights as the first MFMA operand a lane holds, for pixel (lane & 31), four runs
+      // of 4 consecutive channels: 16-byte LDS writes
+      const int lr = rb - pass * 64 + (lane & 31);
 #pragma unroll
       for (int j = 0; j < NI; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int lr = rb - pass * 64 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-          ep[lr * EPS + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
-        }
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(&ep[lr * EPS + wn * WTN + j * 32 + 8 * g + 4 * (lane >> 5)]) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
     }
     __syncthreads();
 #pragma unroll
@@ -833,11 +888,15 @@ static int go(F kernel, int blocks, int threads, const KArgs& a, hipStream_t s) 
   return (int)hipGetLastError();
 }
 
-int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& hd) {
+int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::vector<Desc>& hd) {
   hipStream_t s = static_cast<hipStream_t>(stream);
+  KArgs a = args;
   int64_t blocks = 0;
-  for (int i = 0; i < L.n; ++i) blocks += problem_blocks(L.kind, L.tile, hd[(size_t)(L.first_desc + i)], a.batch);
-  if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+  for (int i = 0; i < FI_MAX_GROUP + 1; ++i) {
+    a.first_block[i] = (int32_t)blocks;
+    if (i < L.n) blocks += problem_blocks(L.kind, L.tile, hd[(size_t)(L.first_desc + i)], a.batch);
+    if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+  }
   const bool wb = L.wdtype == FI_BF16, ab = L.adtype == FI_BF16;
   const int nb = (int)blocks;
   switch (L.kind) {
@@ -857,7 +916,7 @@ int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vect
         if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, true>, nb, 256, a, s);
         return (int)hipErrorInvalidValue;
       }
-      if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false>, nb, 256, a, s);
+      if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false, 1>, nb, 256, a, s);
       if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false>, nb, 256, a, s);
       if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false>, nb, 256, a, s);
       return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false>, nb, 256, a, s);
