@@ -169,7 +169,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // multiplied by the bf16 weights into the same fp32 accumulator, and outputs / residuals stay
 // fp32: bf16 matrix-core throughput at fp32-grade activation accuracy.
 template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, int NS = 1>
-__global__ void __launch_bounds__(WGM * WGN * 64, (BM == 256 && NS == 1) ? 2 : 1) conv_mfma_kernel(KArgs a) {
+__global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
   constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
   constexpr int AE = WIDE ? 4 : 2;       // bytes per stored activation element
@@ -310,47 +310,25 @@ __global__ void __launch_bounds__(WGM * WGN * 64, (BM == 256 && NS == 1) ? 2 : 1
         *reinterpret_cast<uint4*>(&Bp[(srow + RPP * i) * LDS_STRIDE + kvec]) = bv[S][i];          \
   }
 
-  // Fragments of reduction step kk+16 are requested from LDS before the MFMAs of step kk are
-  // issued (two register sets), and scheduling fences keep that order: a wave's matrix pipe
-  // then overlaps its own LDS latency instead of waiting on every operand pair.
-#define FI_LOADFRAGS(Ap, Bp, KK, F)                                                               \
-  {                                                                                               \
-    const int kof = (KK) + (lane >> 5) * 8;                                                       \
-    _Pragma("unroll") for (int h = 0; h < AT; ++h)                                                \
-    _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                \
-        af[F][h][i] = *reinterpret_cast<const bf16x8*>(                                           \
-            &Ap[(h * BM + wm * WTM + i * 32 + (lane & 31)) * LDS_STRIDE + kof]);                  \
-    _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                \
-        bfr[F][j] = *reinterpret_cast<const bf16x8*>(&Bp[(wn * WTN + j * 32 + (lane & 31)) * LDS_STRIDE + kof]); \
-  }
-#define FI_MFMAS(F)                                                                               \
-  {                                                                                               \
-    _Pragma("unroll") for (int h = AT - 1; h >= 0; --h) /* small (lo) terms first */              \
-    _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                \
-    _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[F][j], af[F][h][i], acc[i][j], 0, 0, 0); \
-  }
+  // weights are the first MFMA operand: a lane then holds, for ONE pixel, runs of 4 consecutive channels
 #define FI_MULTIPLY(S)                                                                            \
   {                                                                                               \
     const bf16_t* const Ap = As + (S) * STAGE;                                                    \
     const bf16_t* const Bp = Bs + (S) * STAGE;                                                    \
-    bf16x8 af[2][AT][MI], bfr[2][NI];                                                             \
-    FI_LOADFRAGS(Ap, Bp, 0, 0)                                                                    \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    FI_LOADFRAGS(Ap, Bp, 16, 1)                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    FI_MFMAS(0)                                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    FI_LOADFRAGS(Ap, Bp, 32, 0)                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    FI_MFMAS(1)                                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    FI_LOADFRAGS(Ap, Bp, 48, 1)                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    FI_MFMAS(0)                                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    FI_MFMAS(1)                                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
+    _Pragma("unroll") for (int kk = 0; kk < BK; kk += 16) {                                       \
+      bf16x8 af[AT][MI], bfr[NI];                                                                 \
+      const int kof = kk + (lane >> 5) * 8;                                                       \
+      _Pragma("unroll") for (int h = 0; h < AT; ++h)                                              \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                              \
+          af[h][i] = *reinterpret_cast<const bf16x8*>(                                            \
+              &Ap[(h * BM + wm * WTM + i * 32 + (lane & 31)) * LDS_STRIDE + kof]);                \
+      _Pragma("unroll") for (int j = 0; j < NI; ++j)                                              \
+          bfr[j] = *reinterpret_cast<const bf16x8*>(&Bp[(wn * WTN + j * 32 + (lane & 31)) * LDS_STRIDE + kof]); \
+      _Pragma("unroll") for (int h = AT - 1; h >= 0; --h) /* small (lo) terms first */            \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                              \
+      _Pragma("unroll") for (int j = 0; j < NI; ++j)                                              \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[h][i], acc[i][j], 0, 0, 0); \
+    }                                                                                             \
   }
 
   if constexpr (NS == 1) {
@@ -382,8 +360,6 @@ __global__ void __launch_bounds__(WGM * WGN * 64, (BM == 256 && NS == 1) ? 2 : 1
 #undef FI_FETCH
 #undef FI_PARK
 #undef FI_MULTIPLY
-#undef FI_LOADFRAGS
-#undef FI_MFMAS
 
   // ---- epilogue: 64 output rows per pass through an fp32 LDS tile ----------------------
   // A thread owns one 8-channel column chunk (the same in every pass) and CH rows per pass.
@@ -475,7 +451,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64, (BM == 256 && NS == 1) ? 2 : 1
         uint4 pk;
         pk.x = pack_bf16x2(v[0], v[1]); pk.y = pack_bf16x2(v[2], v[3]);
         pk.z = pack_bf16x2(v[4], v[5]); pk.w = pack_bf16x2(v[6], v[7]);
-        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o) = pk;
+        // streamed out: the tensor is far larger than L2 and is next read by another launch
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, pk), reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o));
       }
     }
   }
