@@ -246,11 +246,11 @@ def swap_churn(fi, torch, gen, zoo, alloc, stream, n_req):
 
 def cpu_baseline(member, x, n_members):
     """The CPU oracle as it stands, on this machine's cores: independent (model, image) units of the same
-    single-threaded code, one per thread.  Sample: two rounds of one-image ResNet-50 forward passes."""
+    single-threaded code, one per thread.  Sample: eight rounds of one-image ResNet-50 forward passes (about 15 s)."""
     import oracle
     m, blob, _ = member
     cores = min(16, os.cpu_count() or 1)
-    units = [(m, blob, x[(i % x.shape[0]):(i % x.shape[0]) + 1], False) for i in range(2 * cores)]
+    units = [(m, blob, x[(i % x.shape[0]):(i % x.shape[0]) + 1], False) for i in range(8 * cores)]
     oracle.lib()
     t0 = time.perf_counter()
     oracle.run_models_parallel(units, threads=cores)

@@ -226,6 +226,10 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
             nd.splits = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, ntiles / 4), 256 / nb64));
           }
           // the kernel addresses its input with 32-bit byte offsets through a buffer resource
+          if ((uint64_t)B * nd.Ho * nd.Wo >= (1ull << 24)) {  // row indices are decoded with exact float arithmetic
+            set_error("model %d node %d: more than 2^24 output pixels per launch", nd.model, nd.index);
+            return FI_EUNSUPPORTED;
+          }
           if ((uint64_t)B * nd.H * nd.W * nd.Cp * esize(adt) >= (1ull << 31)) {
             set_error("model %d node %d: input tensor of %llu bytes exceeds the 2 GiB a conv kernel addresses",
                       nd.model, nd.index, (unsigned long long)((uint64_t)B * nd.H * nd.W * nd.Cp * esize(adt)));
@@ -341,7 +345,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   size_t n_desc = 0;
   for (Launch& L : g->launches) { L.first_desc = (int32_t)n_desc; if (L.kind == K_STAGE) L.n = 1; n_desc += (size_t)L.n; }
   g->descs.assign(n_desc, Desc{});
-  g->desc_bytes = align_up(n_desc * sizeof(Desc));
+  g->desc_bytes = kAlign;  // arena header; problem descriptors travel as launch arguments
   uint64_t off = g->desc_bytes;
   for (Member& mb : g->members) { mb.arena_off = off; off += mb.plan.packed_bytes; }
   g->arena_bytes = off;
@@ -428,7 +432,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   g->image = static_cast<uint8_t*>(pin_alloc(*opts, (size_t)g->image_bytes));
   if (!g->image) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)g->image_bytes); return FI_ENOMEM_HOST; }
   std::memset(g->image, 0, (size_t)g->desc_bytes);
-  std::memcpy(g->image, g->descs.data(), n_desc * sizeof(Desc));
+  std::memcpy(g->image, "fusedinf-arena-1", 16);
   if (opts->load_mode == FI_LOAD_ONE_COPY) {
     for (const Member& mb : g->members) {
       if (mb.spec.weights_packed) parallel_copy(g->image + mb.arena_off, static_cast<const uint8_t*>(mb.spec.weights), mb.plan.packed_bytes);
@@ -521,7 +525,6 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   fi_status rc = FI_OK;
   for (size_t i = 0; i < nl; ++i) {
     const Launch& L = g->launches[i];
-    a.descs = reinterpret_cast<const Desc*>(g->dev) + L.first_desc;
     a.n = L.n;
     for (int32_t k = 0; k < L.n && L.kind != K_STAGE; ++k) {
       const Node& nd = g->nodes[(size_t)L.nodes[(size_t)k]];

@@ -37,9 +37,9 @@ enum Tile : int32_t { T_128x128 = 0, T_128x64 = 1, T_64x64 = 2, T_256x128 = 3, T
 FI_HD inline int tile_bm(int t) { return t == T_256x128 ? 256 : t == T_64x64 ? 64 : 128; }
 FI_HD inline int tile_bn(int t) { return (t == T_128x128 || t == T_256x128) ? 128 : 64; }
 
-// Device-visible problem descriptor: one node of the fused DAG, batch independent.
-// Tensor offsets are relative to the activation region, weight offsets to the weight
-// arena, so the table is position independent and travels inside the arena image.
+// Problem descriptor: one node of the fused DAG, batch independent, handed to the kernels
+// as launch arguments.  Tensor offsets are relative to the activation region, weight offsets
+// to the weight arena.
 struct Desc {
   uint64_t x_off, y_off, r_off;  // input / output / residual (kNone = no residual)
   uint64_t w_off, b_off;
@@ -98,11 +98,11 @@ struct ModelPlan {
 struct KArgs {
   const uint8_t* wbase;          // weight arena (device)
   uint8_t* abase;                // activation region (device)
-  const Desc* descs;             // first descriptor of this launch (device)
   int32_t n, batch;
   int32_t first_block[FI_MAX_GROUP + 1];  // workgroup index where each problem starts (filled per launch)
   const void* ext_in;            // caller's input (K_STAGE only)
   void* ext_out[FI_MAX_GROUP];   // caller's output per problem slot (when Desc.ext)
+  Desc d[FI_MAX_GROUP];          // the launch's problems: read through the scalar cache, no memory round trip
 };
 
 void set_error(const char* fmt, ...);

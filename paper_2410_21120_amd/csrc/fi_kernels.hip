@@ -76,7 +76,7 @@ template <typename TI, typename TA>
 __global__ void __launch_bounds__(256) stage_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_STAGE, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int64_t pix = (int64_t)bid * 256 + threadIdx.x;
   if (pix >= (int64_t)a.batch * d.H * d.W) return;
   const TI* x = static_cast<const TI*>(a.ext_in) + pix * d.C;
@@ -92,7 +92,7 @@ template <typename TW, typename TA>
 __global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_CONV_DIRECT, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   const int64_t M = (int64_t)a.batch * d.Ho * d.Wo;
   if (idx >= M * d.Cop) return;
@@ -154,6 +154,15 @@ constexpr int LDS_STRIDE = BK + 8;  // elements; 144-byte rows keep 16-byte read
 constexpr int NXCD = 8;
 constexpr uint32_t OOB = 0x80000000u;  // byte offset past any tensor: the buffer load returns zero
 
+// m / dv for 0 <= m < 2^24 (exact: the float product is off by at most one, then corrected)
+__device__ __forceinline__ int fast_div(int m, int dv, float inv) {
+  int t = (int)((float)m * inv);
+  const int r = m - t * dv;
+  t += (r >= dv) ? 1 : 0;
+  t -= (r < 0) ? 1 : 0;
+  return t;
+}
+
 __device__ __forceinline__ int xcd_contiguous(int bid, int total) {
   const int c = total / NXCD, r = total % NXCD;
   const int x = bid % NXCD, j = bid / NXCD;
@@ -178,9 +187,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // per-wave sub-tile
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int AR = BM / RPP, BR = BN / RPP;  // 8-element vectors each thread stages per tile
-  constexpr int EPS = BN + 4;                // fp32 row stride of the epilogue tile (16-byte writes spread over all banks)
   constexpr int STAGE = (AT * BM + BN) * LDS_STRIDE;   // bf16 elements per LDS buffer
-  constexpr int SMEM = NS * STAGE * 2 > 64 * EPS * 4 ? NS * STAGE * 2 : 64 * EPS * 4;
+  constexpr int SMEM = NS * STAGE * 2;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
   bf16_t* const As = reinterpret_cast<bf16_t*>(smem);   // [NS][AT][BM][LDS_STRIDE] then B
   bf16_t* const Bs = As + AT * BM * LDS_STRIDE;
@@ -188,7 +196,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // locate the problem and the tile (block-uniform)
   int p, bid;
   if (!find_problem_at(a, xcd_contiguous((int)blockIdx.x, (int)gridDim.x), p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int M = a.batch * d.Ho * d.Wo;
   const int tiles_mn = ((M + BM - 1) / BM) * d.tiles_n;
   const int split = bid / tiles_mn;  // split-K: this workgroup reduces one slice of K into a partial tile
@@ -209,15 +217,16 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // Per row: the byte offset of its window origin (n, p*stride-pad, q*stride-pad, 0) and which
   // filter rows / columns land inside the image (bit r: row r valid; bit 8+s: column s valid).
   int a_row[AR], a_rc[AR];
+  const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho;
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int m = m0 + srow + RPP * i;
     const bool ok = m < M;
     const int mm = ok ? m : 0;
-    const int q = mm % d.Wo;
-    const int t = mm / d.Wo;
-    const int pp = t % d.Ho;
-    const int n = t / d.Ho;
+    const int t = fast_div(mm, d.Wo, inv_wo);
+    const int q = mm - t * d.Wo;
+    const int n = fast_div(t, d.Ho, inv_ho);
+    const int pp = t - n * d.Ho;
     const int ih0 = pp * d.stride - d.pad, iw0 = q * d.stride - d.pad;
     a_row[i] = ((n * d.H + ih0) * d.W + iw0) * d.Cp * AE;
     int rc = 0;
@@ -361,98 +370,200 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 #undef FI_PARK
 #undef FI_MULTIPLY
 
-  // ---- epilogue: 64 output rows per pass through an fp32 LDS tile ----------------------
-  // A thread owns one 8-channel column chunk (the same in every pass) and CH rows per pass.
-  // The pass's residual vectors are requested before the accumulators are parked, so their
-  // latency overlaps the LDS round trip instead of serialising behind it.
-  constexpr int CPR = BN / 8;          // 8-channel chunks per tile row
-  constexpr int CH = 64 * CPR / NT;    // chunks per thread per pass
-  constexpr int RSTEP = NT / CPR;      // row distance between a thread's chunks
-  float* ep = reinterpret_cast<float*>(smem);
-  const int cc = (tid % CPR) * 8, lr0 = tid / CPR;
-  const int o = n0 + cc;
-  const bool col_ok = o < d.Cop;
-  float bias8[8];
-  {
-    const float* bias = reinterpret_cast<const float*>(a.wbase + d.b_off);
-    const float4 b0 = col_ok ? *reinterpret_cast<const float4*>(bias + o) : make_float4(0, 0, 0, 0);
-    const float4 b1 = col_ok ? *reinterpret_cast<const float4*>(bias + o + 4) : make_float4(0, 0, 0, 0);
-    bias8[0] = b0.x; bias8[1] = b0.y; bias8[2] = b0.z; bias8[3] = b0.w;
-    bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
-  }
-  const uint8_t* __restrict__ res = d.r_off != kNone ? a.abase + d.r_off : nullptr;
-#pragma unroll
-  for (int pass = 0; pass < BM / 64; ++pass) {
-    uint4 rv[CH][AV];
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-      const int m = m0 + pass * 64 + lr0 + ch * RSTEP;
-#pragma unroll
-      for (int h = 0; h < AV; ++h) {
-        rv[ch][h] = make_uint4(0, 0, 0, 0);
-        if (res && d.splits == 1 && col_ok && m < M) rv[ch][h] = *reinterpret_cast<const uint4*>(res + ((int64_t)m * d.Cop + o) * AE + 16 * h);
-      }
+  // Two epilogues.  Long reductions (the 256-row tile) drain wave by wave without workgroup
+  // barriers; streaming tiles go through one workgroup-wide fp32 tile so that a row of BN
+  // channels leaves as one contiguous run (wider HBM bursts matter more there).
+  if constexpr (BM == 256) {
+    // ---- epilogue: every wave transposes its own sub-tile through a private LDS patch -----------
+    // (no workgroup barrier: waves drain independently, one 32-row MFMA block at a time).  With the
+    // weights as the first MFMA operand a lane holds, for pixel (lane & 31), four runs of 4
+    // consecutive channels, parked with 16-byte LDS writes; it reads back 8 consecutive channels
+    // of one row, so bias + residual + activation + the single rounding to bf16 work on 16-byte
+    // vectors and every output row segment (WTN channels) is one contiguous store run.  The
+    // block's residual vectors are requested before the accumulators are parked.
+    constexpr int EPS = WTN + 4;                 // fp32 row stride of the patch (16-byte writes hit all banks)
+    constexpr int CPR = WTN / 8;                 // 8-channel chunks per patch row
+    constexpr int CH = 32 * CPR / 64;            // chunks per lane per 32-row block
+    constexpr int RSTEP = 64 / CPR;              // row distance between a lane's chunks
+    static_assert(4 * 32 * EPS * 4 <= SMEM, "epilogue patches fit in the tile memory");
+    float* const ep = reinterpret_cast<float*>(smem) + wave * 32 * EPS;
+    const int cc = (lane % CPR) * 8, lr0 = lane / CPR;
+    const int o = n0 + wn * WTN + cc;
+    const bool col_ok = o < d.Cop;
+    float bias8[8];
+    {
+      const float* bias = reinterpret_cast<const float*>(a.wbase + d.b_off);
+      const float4 b0 = col_ok ? *reinterpret_cast<const float4*>(bias + o) : make_float4(0, 0, 0, 0);
+      const float4 b1 = col_ok ? *reinterpret_cast<const float4*>(bias + o + 4) : make_float4(0, 0, 0, 0);
+      bias8[0] = b0.x; bias8[1] = b0.y; bias8[2] = b0.z; bias8[3] = b0.w;
+      bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
     }
-    if (pass > 0) __syncthreads();
-#pragma unroll
+    const uint8_t* __restrict__ res = d.r_off != kNone ? a.abase + d.r_off : nullptr;
+  #pragma unroll
     for (int i = 0; i < MI; ++i) {
-      const int rb = wm * WTM + i * 32;  // first row of this MFMA block inside the tile
-      if (rb / 64 != pass) continue;
-      // with the weights as the first MFMA operand a lane holds, for pixel (lane & 31), four runs
-      // of 4 consecutive channels: 16-byte LDS writes
-      const int lr = rb - pass * 64 + (lane & 31);
-#pragma unroll
+      const int mb = m0 + wm * WTM + i * 32;  // first output row of this MFMA block
+      uint4 rv[CH][AV];
+  #pragma unroll
+      for (int ch = 0; ch < CH; ++ch) {
+        const int m = mb + lr0 + ch * RSTEP;
+  #pragma unroll
+        for (int h = 0; h < AV; ++h) {
+          rv[ch][h] = make_uint4(0, 0, 0, 0);
+          if (res && d.splits == 1 && col_ok && m < M)
+            rv[ch][h] = *reinterpret_cast<const uint4*>(res + ((int64_t)m * d.Cop + o) * AE + 16 * h);
+        }
+      }
+  #pragma unroll
       for (int j = 0; j < NI; ++j)
-#pragma unroll
+  #pragma unroll
         for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<float4*>(&ep[lr * EPS + wn * WTN + j * 32 + 8 * g + 4 * (lane >> 5)]) =
+          *reinterpret_cast<float4*>(&ep[(lane & 31) * EPS + j * 32 + 8 * g + 4 * (lane >> 5)]) =
               make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // the wave's own LDS writes precede its reads
+  #pragma unroll
+      for (int ch = 0; ch < CH; ++ch) {
+        const int lr = lr0 + ch * RSTEP;
+        const int m = mb + lr;
+        float v[8];
+        const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
+        const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
+        if (m >= M || !col_ok) continue;
+        if (d.splits > 1) {  // raw partial sums; the reduce launch finishes the node
+          float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
+          *reinterpret_cast<float4*>(ws) = v0;
+          *reinterpret_cast<float4*>(ws + 4) = v1;
+          continue;
+        }
+        v[0] = v0.x + bias8[0]; v[1] = v0.y + bias8[1]; v[2] = v0.z + bias8[2]; v[3] = v0.w + bias8[3];
+        v[4] = v1.x + bias8[4]; v[5] = v1.y + bias8[5]; v[6] = v1.z + bias8[6]; v[7] = v1.w + bias8[7];
+        if constexpr (WIDE) {
+          const uint4 r0 = rv[ch][0], r1 = rv[ch][AV - 1];
+          v[0] += __uint_as_float(r0.x); v[1] += __uint_as_float(r0.y); v[2] += __uint_as_float(r0.z); v[3] += __uint_as_float(r0.w);
+          v[4] += __uint_as_float(r1.x); v[5] += __uint_as_float(r1.y); v[6] += __uint_as_float(r1.z); v[7] += __uint_as_float(r1.w);
+        } else {
+          const uint4 r = rv[ch][0];
+          v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xFFFF0000u);
+          v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xFFFF0000u);
+          v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
+          v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
+        }
+  #pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = (o + t < d.Co) ? activate(v[t], d.act) : 0.0f;  // pad channels hold zero
+        if (d.ext) {
+          float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)m * d.Co + o;
+  #pragma unroll
+          for (int t = 0; t < 8; ++t)
+            if (o + t < d.Co) y[t] = v[t];
+        } else if (WIDE || d.out_f32) {
+          float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o;
+          *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
+          *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+          // streamed out: the tensor is far larger than L2 and is next read by another launch
+          u32x4 pk;
+          pk[0] = pack_bf16x2(v[0], v[1]); pk[1] = pack_bf16x2(v[2], v[3]);
+          pk[2] = pack_bf16x2(v[4], v[5]); pk[3] = pack_bf16x2(v[6], v[7]);
+          __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o));
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");  // reads done before the next block's writes
     }
-    __syncthreads();
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-      const int lr = lr0 + ch * RSTEP;
-      const int m = m0 + pass * 64 + lr;
-      if (m >= M || !col_ok) continue;
-      float v[8];
-      const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
-      const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
-      if (d.splits > 1) {  // raw partial sums; the reduce launch finishes the node
-        float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
-        *reinterpret_cast<float4*>(ws) = v0;
-        *reinterpret_cast<float4*>(ws + 4) = v1;
-        continue;
+  } else {
+    constexpr int EPS = BN + 4;                // fp32 row stride of the tile (16-byte writes spread over all banks)
+    static_assert(64 * EPS * 4 <= SMEM, "epilogue tile fits in the tile memory");
+    // ---- epilogue: 64 output rows per pass through an fp32 LDS tile ----------------------
+    // A thread owns one 8-channel column chunk (the same in every pass) and CH rows per pass.
+    // The pass's residual vectors are requested before the accumulators are parked, so their
+    // latency overlaps the LDS round trip instead of serialising behind it.
+    constexpr int CPR = BN / 8;          // 8-channel chunks per tile row
+    constexpr int CH = 64 * CPR / NT;    // chunks per thread per pass
+    constexpr int RSTEP = NT / CPR;      // row distance between a thread's chunks
+    float* ep = reinterpret_cast<float*>(smem);
+    const int cc = (tid % CPR) * 8, lr0 = tid / CPR;
+    const int o = n0 + cc;
+    const bool col_ok = o < d.Cop;
+    float bias8[8];
+    {
+      const float* bias = reinterpret_cast<const float*>(a.wbase + d.b_off);
+      const float4 b0 = col_ok ? *reinterpret_cast<const float4*>(bias + o) : make_float4(0, 0, 0, 0);
+      const float4 b1 = col_ok ? *reinterpret_cast<const float4*>(bias + o + 4) : make_float4(0, 0, 0, 0);
+      bias8[0] = b0.x; bias8[1] = b0.y; bias8[2] = b0.z; bias8[3] = b0.w;
+      bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
+    }
+    const uint8_t* __restrict__ res = d.r_off != kNone ? a.abase + d.r_off : nullptr;
+  #pragma unroll
+    for (int pass = 0; pass < BM / 64; ++pass) {
+      uint4 rv[CH][AV];
+  #pragma unroll
+      for (int ch = 0; ch < CH; ++ch) {
+        const int m = m0 + pass * 64 + lr0 + ch * RSTEP;
+  #pragma unroll
+        for (int h = 0; h < AV; ++h) {
+          rv[ch][h] = make_uint4(0, 0, 0, 0);
+          if (res && d.splits == 1 && col_ok && m < M) rv[ch][h] = *reinterpret_cast<const uint4*>(res + ((int64_t)m * d.Cop + o) * AE + 16 * h);
+        }
       }
-      v[0] = v0.x + bias8[0]; v[1] = v0.y + bias8[1]; v[2] = v0.z + bias8[2]; v[3] = v0.w + bias8[3];
-      v[4] = v1.x + bias8[4]; v[5] = v1.y + bias8[5]; v[6] = v1.z + bias8[6]; v[7] = v1.w + bias8[7];
-      if constexpr (WIDE) {
-        const uint4 r0 = rv[ch][0], r1 = rv[ch][AV - 1];
-        v[0] += __uint_as_float(r0.x); v[1] += __uint_as_float(r0.y); v[2] += __uint_as_float(r0.z); v[3] += __uint_as_float(r0.w);
-        v[4] += __uint_as_float(r1.x); v[5] += __uint_as_float(r1.y); v[6] += __uint_as_float(r1.z); v[7] += __uint_as_float(r1.w);
-      } else {
-        const uint4 r = rv[ch][0];
-        v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xFFFF0000u);
-        v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xFFFF0000u);
-        v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
-        v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
+      if (pass > 0) __syncthreads();
+  #pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const int rb = wm * WTM + i * 32;  // first row of this MFMA block inside the tile
+        if (rb / 64 != pass) continue;
+        // with the weights as the first MFMA operand a lane holds, for pixel (lane & 31), four runs
+        // of 4 consecutive channels: 16-byte LDS writes
+        const int lr = rb - pass * 64 + (lane & 31);
+  #pragma unroll
+        for (int j = 0; j < NI; ++j)
+  #pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<float4*>(&ep[lr * EPS + wn * WTN + j * 32 + 8 * g + 4 * (lane >> 5)]) =
+                make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
       }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = (o + i < d.Co) ? activate(v[i], d.act) : 0.0f;  // pad channels hold zero
-      if (d.ext) {
-        float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)m * d.Co + o;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-          if (o + i < d.Co) y[i] = v[i];
-      } else if (WIDE || d.out_f32) {
-        float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o;
-        *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
-        *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
-      } else {
-        uint4 pk;
-        pk.x = pack_bf16x2(v[0], v[1]); pk.y = pack_bf16x2(v[2], v[3]);
-        pk.z = pack_bf16x2(v[4], v[5]); pk.w = pack_bf16x2(v[6], v[7]);
-        // streamed out: the tensor is far larger than L2 and is next read by another launch
-        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, pk), reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o));
+      __syncthreads();
+  #pragma unroll
+      for (int ch = 0; ch < CH; ++ch) {
+        const int lr = lr0 + ch * RSTEP;
+        const int m = m0 + pass * 64 + lr;
+        if (m >= M || !col_ok) continue;
+        float v[8];
+        const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
+        const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
+        if (d.splits > 1) {  // raw partial sums; the reduce launch finishes the node
+          float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
+          *reinterpret_cast<float4*>(ws) = v0;
+          *reinterpret_cast<float4*>(ws + 4) = v1;
+          continue;
+        }
+        v[0] = v0.x + bias8[0]; v[1] = v0.y + bias8[1]; v[2] = v0.z + bias8[2]; v[3] = v0.w + bias8[3];
+        v[4] = v1.x + bias8[4]; v[5] = v1.y + bias8[5]; v[6] = v1.z + bias8[6]; v[7] = v1.w + bias8[7];
+        if constexpr (WIDE) {
+          const uint4 r0 = rv[ch][0], r1 = rv[ch][AV - 1];
+          v[0] += __uint_as_float(r0.x); v[1] += __uint_as_float(r0.y); v[2] += __uint_as_float(r0.z); v[3] += __uint_as_float(r0.w);
+          v[4] += __uint_as_float(r1.x); v[5] += __uint_as_float(r1.y); v[6] += __uint_as_float(r1.z); v[7] += __uint_as_float(r1.w);
+        } else {
+          const uint4 r = rv[ch][0];
+          v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xFFFF0000u);
+          v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xFFFF0000u);
+          v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
+          v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
+        }
+  #pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (o + i < d.Co) ? activate(v[i], d.act) : 0.0f;  // pad channels hold zero
+        if (d.ext) {
+          float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)m * d.Co + o;
+  #pragma unroll
+          for (int i = 0; i < 8; ++i)
+            if (o + i < d.Co) y[i] = v[i];
+        } else if (WIDE || d.out_f32) {
+          float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o;
+          *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
+          *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+          uint4 pk;
+          pk.x = pack_bf16x2(v[0], v[1]); pk.y = pack_bf16x2(v[2], v[3]);
+          pk.z = pack_bf16x2(v[4], v[5]); pk.w = pack_bf16x2(v[6], v[7]);
+          // streamed out: the tensor is far larger than L2 and is next read by another launch
+          __builtin_nontemporal_store(__builtin_bit_cast(u32x4, pk), reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o));
+        }
       }
     }
   }
@@ -465,7 +576,7 @@ template <typename TW, typename TA>
 __global__ void __launch_bounds__(256) dwconv_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_DWCONV, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
   const int c = (int)(idx % d.Cop);
@@ -507,7 +618,7 @@ template <typename TA>
 __global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_MAXPOOL, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
   if (sizeof(TA) == 2 && d.vec) {
@@ -574,7 +685,7 @@ template <typename TA>
 __global__ void __launch_bounds__(256) gap_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_GAP, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int idx = bid * 256 + threadIdx.x;
   if (idx >= a.batch * d.Cop) return;
   const int c = idx % d.Cop, n = idx / d.Cop;
@@ -597,7 +708,7 @@ __global__ void __launch_bounds__(256) gap_kernel(KArgs a) {
 __global__ void __launch_bounds__(64) softmax_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_SOFTMAX, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const float* z = reinterpret_cast<const float*>(a.abase + d.x_off) + (int64_t)bid * d.Cp;
   float* y = d.ext ? static_cast<float*>(a.ext_out[p]) + (int64_t)bid * d.Co
                    : reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)bid * d.Cop;
@@ -645,7 +756,7 @@ template <typename TA>
 __global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_DWCONV, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int cv = d.Cop / 8;
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   if (idx >= (int64_t)a.batch * d.Ho * d.Wo * cv) return;
@@ -699,7 +810,7 @@ template <typename TA>
 __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_GAP, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int cv = d.Cop / 8;
   const int idx = bid * 256 + threadIdx.x;
   if (idx >= a.batch * cv) return;
@@ -742,7 +853,7 @@ template <bool WIDE>
 __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_FC, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int lane = threadIdx.x & 63;
   const int unit = bid * 4 + (threadIdx.x >> 6);
   if (unit >= d.tiles_n * d.splits) return;
@@ -821,7 +932,7 @@ template <typename TA>
 __global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_REDUCE, 0, p, bid)) return;
-  const Desc d = a.descs[p];
+  const Desc d = a.d[p];
   const int q4 = d.Cop / 4;
   const int rows = a.batch * d.Ho * d.Wo;
   const int idx = bid * 256 + threadIdx.x;
@@ -868,6 +979,7 @@ static int go(F kernel, int blocks, int threads, const KArgs& a, hipStream_t s) 
 int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::vector<Desc>& hd) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   KArgs a = args;
+  for (int i = 0; i < L.n; ++i) a.d[i] = hd[(size_t)(L.first_desc + i)];
   int64_t blocks = 0;
   for (int i = 0; i < FI_MAX_GROUP + 1; ++i) {
     a.first_block[i] = (int32_t)blocks;

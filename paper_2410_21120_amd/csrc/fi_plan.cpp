@@ -158,48 +158,52 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
   return FI_OK;
 }
 
-static inline float bf16_to_float(uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; std::memcpy(&f, &u, 4); return f; }
-
 // Canonical (OIHW, model dtype) -> packed.  Pure data movement: elements are copied, never
 // converted, and padding is zero-filled.
-void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst) {
-  const size_t wsz = m.dtype == FI_BF16 ? 2 : 4;
+template <typename T>
+static void pack_typed(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst8) {
   const uint8_t* src = static_cast<const uint8_t*>(m.weights);
-  std::memset(dst, 0, (size_t)p.packed_bytes);
+  std::memset(dst8, 0, (size_t)p.packed_bytes);
   for (int32_t i = 0; i < m.n_layers; ++i) {
     const Node& n = p.nodes[(size_t)i];
     if (n.w_rel == kNone) continue;
     const fi_layer_spec& L = m.layers[i];
-    const uint8_t* w = src + L.w_off;
-    uint8_t* d = dst + n.w_rel;
+    const T* w = reinterpret_cast<const T*>(src + L.w_off);
+    T* d = reinterpret_cast<T*>(dst8 + n.w_rel);
+    const int32_t kk = n.k * n.k;
     if (n.op == FI_CONV2D) {
-      for (int32_t o = 0; o < n.Co; ++o)
-        for (int32_t c = 0; c < n.C; ++c)
-          for (int32_t r = 0; r < n.k; ++r)
-            for (int32_t s = 0; s < n.k; ++s) {
-              const size_t from = (((size_t)o * n.C + c) * n.k + r) * n.k + s;
-              const size_t to = (size_t)o * n.Kp + ((size_t)r * n.k + s) * n.Cp + c;
-              std::memcpy(d + to * wsz, w + from * wsz, wsz);
-            }
+      for (int32_t o = 0; o < n.Co; ++o) {
+        const T* wo = w + (size_t)o * n.C * kk;
+        T* dorow = d + (size_t)o * n.Kp;
+        if (kk == 1) { std::memcpy(dorow, wo, (size_t)n.C * sizeof(T)); continue; }
+        for (int32_t t = 0; t < kk; ++t) {
+          T* dt = dorow + (size_t)t * n.Cp;
+          for (int32_t c = 0; c < n.C; ++c) dt[c] = wo[(size_t)c * kk + t];
+        }
+      }
     } else if (n.op == FI_FC) {
       // canonical column index runs over (c, h, w); packed over (h, w, c) with stride Cp
       const int32_t HW = n.H * n.W;
       for (int32_t o = 0; o < n.Co; ++o) {
-        const uint8_t* wr = w + (size_t)o * n.C * HW * wsz;
-        uint8_t* dr = d + (size_t)o * n.Kp * wsz;
-        if (HW == 1) { std::memcpy(dr, wr, (size_t)n.C * wsz); continue; }
-        for (int32_t c = 0; c < n.C; ++c)
-          for (int32_t q = 0; q < HW; ++q)
-            std::memcpy(dr + ((size_t)q * n.Cp + c) * wsz, wr + ((size_t)c * HW + q) * wsz, wsz);
+        const T* wr = w + (size_t)o * n.C * HW;
+        T* dr = d + (size_t)o * n.Kp;
+        if (HW == 1) { std::memcpy(dr, wr, (size_t)n.C * sizeof(T)); continue; }
+        for (int32_t q = 0; q < HW; ++q) {
+          T* dq = dr + (size_t)q * n.Cp;
+          for (int32_t c = 0; c < n.C; ++c) dq[c] = wr[(size_t)c * HW + q];
+        }
       }
     } else {  // depthwise: [c][0][r][s] -> [r][s][c]
-      for (int32_t c = 0; c < n.C; ++c)
-        for (int32_t t = 0; t < n.k * n.k; ++t)
-          std::memcpy(d + ((size_t)t * n.Cp + c) * wsz, w + ((size_t)c * n.k * n.k + t) * wsz, wsz);
+      for (int32_t t = 0; t < kk; ++t)
+        for (int32_t c = 0; c < n.C; ++c) d[(size_t)t * n.Cp + c] = w[(size_t)c * kk + t];
     }
-    std::memcpy(dst + n.b_rel, src + L.b_off, (size_t)n.Co * 4);
+    std::memcpy(dst8 + n.b_rel, src + L.b_off, (size_t)n.Co * 4);
   }
-  (void)bf16_to_float;
+}
+
+void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst) {
+  if (m.dtype == FI_BF16) pack_typed<uint16_t>(m, p, dst);
+  else pack_typed<uint32_t>(m, p, dst);
 }
 
 }  // namespace fi
