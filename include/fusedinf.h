@@ -9,7 +9,8 @@
  * is filled by one pinned-host-to-device copy.  The inference loop of Algorithm 1
  * (every node evaluates phi(sum_j u_j x_j) on tensors of its own model) becomes
  * one launch schedule in which nodes of different members at the same depth run
- * as grouped kernels.  Properties C1 / C4 (Section III-A, Section IV-C) are kept:
+ * as grouped kernels; members of different architecture, which rarely share a
+ * kernel shape, form separate lanes of that schedule that run concurrently.  Properties C1 / C4 (Section III-A, Section IV-C) are kept:
  * no operator is merged across members, each member's output is bit-identical to
  * the member run alone, and no member reads another member's tensors.
  *
@@ -109,6 +110,8 @@ typedef struct {
   int32_t group_levels;      /* 1: same-depth nodes of different members share launches; 0: one launch per node */
   int32_t load_mode;         /* fi_load_mode */
   int32_t use_graph;         /* 1: fi_run replays the schedule as one HIP graph (needs a non-NULL stream) */
+  int32_t serial_lanes;      /* 0: members of different architecture run concurrently on internal streams; 1: one stream */
+  int32_t reserved;
   uint64_t max_device_bytes; /* 0 = unlimited; else fi_build_dag fails with FI_EBUDGET beyond it */
   void* (*dev_alloc)(size_t bytes, void* user);
   void (*dev_free)(void* ptr, void* user);
@@ -127,7 +130,7 @@ typedef struct {
   int32_t n_device_allocs;   /* device allocations per fi_load (1) */
   int32_t n_h2d_copies;      /* host-to-device copies per fi_load (1 in FI_LOAD_ONE_COPY) */
   int32_t state;             /* 0 BUILT, 1 LOADED */
-  int32_t reserved;
+  int32_t n_lanes;           /* concurrent launch lanes (groups of members with identical architecture) */
 } fi_dag_info;
 
 /* Introspection of the compiled DAG (tests, reports). */
@@ -145,6 +148,7 @@ typedef struct {
 
 typedef struct {
   int32_t level, kind, n_problems, first_node; /* kind: internal kernel family id */
+  int32_t lane, reserved;    /* launch lane (stream) */
   uint64_t macs_per_image;   /* dense work of the launch */
   uint64_t bytes_per_image;  /* compulsory activation bytes (in + out + residual), per image */
   uint64_t weight_bytes;     /* weight + bias bytes read once per launch */

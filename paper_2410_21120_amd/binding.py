@@ -43,7 +43,8 @@ FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
 
 class fi_build_opts(C.Structure):
     _fields_ = [("max_batch", C.c_int32), ("group_levels", C.c_int32), ("load_mode", C.c_int32),
-                ("use_graph", C.c_int32), ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
+                ("use_graph", C.c_int32), ("serial_lanes", C.c_int32), ("reserved", C.c_int32),
+                ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
                 ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p)]
 
 
@@ -52,7 +53,7 @@ class fi_dag_info(C.Structure):
                 ("device_bytes", C.c_uint64), ("macs_per_image", C.c_uint64), ("n_models", C.c_int32),
                 ("n_nodes", C.c_int32), ("n_levels", C.c_int32), ("n_launches", C.c_int32),
                 ("n_device_allocs", C.c_int32), ("n_h2d_copies", C.c_int32), ("state", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("n_lanes", C.c_int32)]
 
 
 class fi_node_info(C.Structure):
@@ -65,7 +66,7 @@ class fi_node_info(C.Structure):
 
 class fi_launch_info(C.Structure):
     _fields_ = [("level", C.c_int32), ("kind", C.c_int32), ("n_problems", C.c_int32), ("first_node", C.c_int32),
-                ("macs_per_image", C.c_uint64), ("bytes_per_image", C.c_uint64), ("weight_bytes", C.c_uint64),
+                ("lane", C.c_int32), ("reserved", C.c_int32), ("macs_per_image", C.c_uint64), ("bytes_per_image", C.c_uint64), ("weight_bytes", C.c_uint64),
                 ("name", C.c_char * 32)]
 
 
@@ -281,11 +282,12 @@ class Dag:
     """Owner of one fi_dag handle."""
 
     def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
-                 max_device_bytes=0, keepalive=None, use_graph=False):
+                 max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False):
         self.keepalive = (specs, keepalive, allocators)
         opts = fi_build_opts()
         opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
         opts.use_graph = int(use_graph)
+        opts.serial_lanes = int(serial_lanes)
         if allocators is not None:
             allocators.apply(opts)
         self.opts = opts

@@ -8,6 +8,7 @@
 #include <map>
 #include <memory>
 #include <new>
+#include <string>
 #include <thread>
 #include <tuple>
 
@@ -18,6 +19,7 @@ const char* last_error();
 
 struct Tensor {           // one stored activation tensor (a node's output, or a staged input)
   int32_t first, last;    // live range in levels, inclusive
+  int32_t lane;           // -1: shared by all lanes (staged input)
   uint64_t bytes, off;
 };
 
@@ -25,6 +27,7 @@ struct Member {
   fi_model_spec spec;     // borrowed pointers inside
   ModelPlan plan;
   int32_t node0;          // first global node id
+  int32_t lane;           // members of identical architecture share a lane
   uint64_t arena_off;     // placement of the packed blob in the weight arena
 };
 
@@ -46,6 +49,9 @@ struct fi_dag {
   int32_t state = 0;
   uint64_t macs = 0;
   // captured launch schedule (use_graph): valid for exactly these call arguments
+  int32_t n_lanes = 1;
+  std::vector<hipStream_t> lane_streams;   // lanes 1.. (lane 0 runs on the caller's stream)
+  std::vector<hipEvent_t> lane_events;     // [0] fork, [l] join of lane l
   hipGraphExec_t gexec = nullptr;
   int32_t g_batch = 0;
   const void* g_input = nullptr;
@@ -198,11 +204,31 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
     }
   }
 
+  // ---- lanes: members whose graphs are identical node for node share launches level by level;
+  //      members of different architecture rarely do, so each architecture gets a lane of its
+  //      own that runs concurrently with the others (no edge joins two members) -----------------
+  {
+    std::map<std::string, int32_t> lane_of;
+    for (Member& mb : g->members) {
+      std::string sig = std::to_string(mb.spec.act_dtype);
+      for (const Node& n : mb.plan.nodes) {
+        char buf[96];
+        std::snprintf(buf, sizeof(buf), "|%d,%d,%d,%d,%d,%d,%d,%d,%d", n.op, n.input, n.residual, n.C, n.Co, n.k, n.stride, n.pad, n.act);
+        sig += buf;
+      }
+      auto it = lane_of.find(sig);
+      if (it == lane_of.end()) it = lane_of.emplace(sig, opts->serial_lanes ? 0 : (int32_t)lane_of.size()).first;
+      mb.lane = it->second;
+    }
+    g->n_lanes = opts->serial_lanes ? 1 : (int32_t)lane_of.size();
+    for (Node& nd : g->nodes) nd.lane = g->members[(size_t)nd.model].lane;
+  }
+
   // ---- kernel family per node ---------------------------------------------------------
   const int B = opts->max_batch;
   std::map<std::tuple<int, int, int, int, int, int>, int> same_shape;  // problems of one shape per level
   for (const Node& nd : g->nodes)
-    if (nd.op == FI_CONV2D || nd.op == FI_FC) same_shape[std::make_tuple(nd.level, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)]++;
+    if (nd.op == FI_CONV2D || nd.op == FI_FC) same_shape[std::make_tuple(nd.level + 1000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)]++;
   for (Node& nd : g->nodes) {
     const int adt = g->members[(size_t)nd.model].spec.act_dtype;
     nd.tile = 0;
@@ -235,7 +261,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
                       nd.model, nd.index, (unsigned long long)((uint64_t)B * nd.H * nd.W * nd.Cp * esize(adt)));
             return FI_EUNSUPPORTED;
           }
-          const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.level, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
+          const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.level + 1000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
           nd.tile = pick_tile(nd, B, std::min(grp, (int)FI_MAX_GROUP), adt == FI_F32);
         } else nd.kind = K_CONV_DIRECT;
         break;
@@ -253,7 +279,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
     if (nd.input == FI_INPUT) need_stage[g->members[(size_t)nd.model].spec.act_dtype] = true;
   auto new_launch = [&](int level, int kind, int tile, int adt) -> Launch& {
     Launch L{};
-    L.level = level; L.kind = kind; L.tile = tile; L.wdtype = g->wdtype; L.adtype = adt;
+    L.level = level; L.kind = kind; L.tile = tile; L.wdtype = g->wdtype; L.adtype = adt; L.lane = 0;
     L.first_desc = 0; L.n = 0; L.macs = L.act_bytes = L.weight_bytes = 0;
     L.name = kind_name(kind, tile);
     g->launches.push_back(L);
@@ -262,15 +288,15 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   for (int adt = 0; adt < 2; ++adt)
     if (need_stage[adt]) new_launch(0, K_STAGE, 0, adt);   // one staged copy per activation dtype
   for (int32_t lv = 1; lv <= g->n_levels; ++lv) {
-    std::map<std::tuple<int, int, int>, int32_t> open;   // (kind, tile, adtype) -> launch index
+    std::map<std::tuple<int, int, int>, int32_t> open;   // (kind, tile, adtype/split/lane) -> launch index
     for (int32_t i = 0; i < total; ++i) {
       Node& nd = g->nodes[(size_t)i];
       if (nd.level != lv) continue;
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const auto key = std::make_tuple(nd.kind, nd.tile, adt * 2 + (nd.kind == K_CONV_MFMA && nd.splits > 1 ? 1 : 0));
+      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 4 + adt * 2 + (nd.kind == K_CONV_MFMA && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
       if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
-        new_launch(lv, nd.kind, nd.tile, adt);
+        new_launch(lv, nd.kind, nd.tile, adt).lane = nd.lane;
         open[key] = (int32_t)g->launches.size() - 1;
         it = open.find(key);
       }
@@ -287,6 +313,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       if (cand.level != lv || !(cand.kind == K_FC || split_conv)) continue;
       const Launch src = cand;
       Launch& R = new_launch(lv, K_REDUCE, 0, src.adtype);
+      R.lane = src.lane;
       R.n = src.n;
       R.nodes = src.nodes;
     }
@@ -309,11 +336,11 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
     nd.out_bytes = nd.is_output ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
-    tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.out_bytes, 0};
+    tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.lane, nd.out_bytes, 0};
   }
   const Member& m0 = g->members[0];
   for (int adt = 0; adt < 2; ++adt)
-    tens[(size_t)total + adt] = Tensor{0, stage_last[adt],
+    tens[(size_t)total + adt] = Tensor{0, stage_last[adt], -1,
         need_stage[adt] ? align_up((uint64_t)B * m0.spec.in_h * m0.spec.in_w * m0.plan.in_cp * esize(adt)) : 0, 0};
   {
     std::vector<int32_t> order;
@@ -327,7 +354,9 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       std::vector<std::pair<uint64_t, uint64_t>> busy;
       for (int32_t u : placed) {
         const Tensor& U = tens[(size_t)u];
-        if (U.first <= T.last && T.first <= U.last) busy.emplace_back(U.off, U.off + U.bytes);
+        // lanes are not level-synchronous with each other: tensors of different lanes never share memory
+        const bool other_lane = g->n_lanes > 1 && (U.lane != T.lane || U.lane < 0);
+        if (other_lane || (U.first <= T.last && T.first <= U.last)) busy.emplace_back(U.off, U.off + U.bytes);
       }
       std::sort(busy.begin(), busy.end());
       uint64_t off = 0;
@@ -357,14 +386,20 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   // workspace: split-K partials; nodes of one level get disjoint regions, levels reuse them
   g->workspace_bytes = 0;
   {
-    std::map<int32_t, uint64_t> level_top;
+    // per lane: nodes of one level get disjoint regions, levels reuse them; lanes never share
+    std::vector<uint64_t> lane_need((size_t)g->n_lanes, 0);
+    std::map<std::pair<int32_t, int32_t>, uint64_t> level_top;
     for (Node& nd : g->nodes) {
       if (!(nd.kind == K_FC || (nd.kind == K_CONV_MFMA && nd.splits > 1))) continue;
-      uint64_t& top = level_top[nd.level];
+      uint64_t& top = level_top[{nd.lane, nd.level}];
       nd.ws_off = top;
       top += align_up((uint64_t)nd.splits * B * nd.Ho * nd.Wo * nd.Cop * 4);
-      g->workspace_bytes = std::max(g->workspace_bytes, top);
+      lane_need[(size_t)nd.lane] = std::max(lane_need[(size_t)nd.lane], top);
     }
+    std::vector<uint64_t> lane_base((size_t)g->n_lanes, 0);
+    for (int32_t l = 0; l < g->n_lanes; ++l) { lane_base[(size_t)l] = g->workspace_bytes; g->workspace_bytes += lane_need[(size_t)l]; }
+    for (Node& nd : g->nodes)
+      if (nd.kind == K_FC || (nd.kind == K_CONV_MFMA && nd.splits > 1)) nd.ws_off += lane_base[(size_t)nd.lane];
   }
   g->device_bytes = g->arena_bytes + g->act_bytes + g->workspace_bytes;
   if (opts->max_device_bytes && g->device_bytes > opts->max_device_bytes) {
@@ -453,6 +488,7 @@ fi_status fi_query(const fi_dag* g, fi_dag_info* info) {
   info->n_device_allocs = 1;
   info->n_h2d_copies = g->opts.load_mode == FI_LOAD_ONE_COPY ? 1 : 1 + (int32_t)g->members.size();
   info->state = g->state;
+  info->n_lanes = g->n_lanes;
   return FI_OK;
 }
 
@@ -471,6 +507,7 @@ fi_status fi_launch(const fi_dag* g, int32_t i, fi_launch_info* o) {
   if (!g || !o || i < 0 || i >= (int32_t)g->launches.size()) { set_error("bad launch index"); return FI_EINVAL; }
   const Launch& L = g->launches[(size_t)i];
   std::memset(o, 0, sizeof(*o));
+  o->lane = L.lane;
   o->level = L.level; o->kind = L.kind; o->n_problems = L.n; o->first_node = L.nodes.empty() ? -1 : L.nodes[0];
   o->macs_per_image = L.macs; o->bytes_per_image = L.act_bytes; o->weight_bytes = L.weight_bytes;
   std::snprintf(o->name, sizeof(o->name), "%s", L.name.c_str());
@@ -496,6 +533,18 @@ fi_status fi_load(fi_dag* g, void* stream) {
     if (g->opts.dev_free) g->opts.dev_free(d, g->opts.user); else (void)hipFree(d);
     return FI_EHIP;
   }
+  // internal streams (default priority) and events for the concurrent lanes
+  for (int32_t l = 1; l < g->n_lanes; ++l) {
+    hipStream_t ls = nullptr;
+    if (hipStreamCreateWithFlags(&ls, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); break; }
+    g->lane_streams.push_back(ls);
+  }
+  if ((int32_t)g->lane_streams.size() == g->n_lanes - 1)
+    for (int32_t l = 0; l < g->n_lanes; ++l) {
+      hipEvent_t ev = nullptr;
+      if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); break; }
+      g->lane_events.push_back(ev);
+    }
   g->dev = d;
   g->state = 1;
   return FI_OK;
@@ -523,17 +572,33 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   a.batch = batch;
   a.ext_in = d_input;
   fi_status rc = FI_OK;
+  // Lanes: after the shared input is staged on the caller's stream the internal streams fork from
+  // it, every launch goes to its lane's stream, and the caller's stream joins them at the end.
+  const bool lanes = !ms && !g->opts.use_graph && g->n_lanes > 1 &&
+                     (int32_t)g->lane_streams.size() == g->n_lanes - 1 && (int32_t)g->lane_events.size() == g->n_lanes;
+  bool forked = false;
   for (size_t i = 0; i < nl; ++i) {
     const Launch& L = g->launches[i];
+    if (lanes && !forked && L.level > 0) {
+      (void)hipEventRecord(g->lane_events[0], s);
+      for (hipStream_t ls : g->lane_streams) (void)hipStreamWaitEvent(ls, g->lane_events[0], 0);
+      forked = true;
+    }
+    hipStream_t ls = (lanes && L.lane > 0) ? g->lane_streams[(size_t)L.lane - 1] : s;
     a.n = L.n;
     for (int32_t k = 0; k < L.n && L.kind != K_STAGE; ++k) {
       const Node& nd = g->nodes[(size_t)L.nodes[(size_t)k]];
       a.ext_out[k] = nd.is_output ? d_outputs[nd.model] : nullptr;
     }
-    const int e = launch_kernel(L, a, s, g->descs);
+    const int e = launch_kernel(L, a, ls, g->descs);
     if (e != (int)hipSuccess) { set_error("launch %zu (%s): %s", i, L.name.c_str(), hipGetErrorString((hipError_t)e)); rc = FI_EHIP; break; }
     if (ms) (void)hipEventRecord(ev[i + 1], s);
   }
+  if (forked)
+    for (int32_t l = 1; l < g->n_lanes; ++l) {
+      (void)hipEventRecord(g->lane_events[(size_t)l], g->lane_streams[(size_t)l - 1]);
+      (void)hipStreamWaitEvent(s, g->lane_events[(size_t)l], 0);
+    }
   if (ms) {
     (void)hipStreamSynchronize(s);
     if (rc == FI_OK)
@@ -588,6 +653,10 @@ fi_status fi_unload(fi_dag* g) {
   if (g->state != 1) { set_error("fi_unload: handle is not loaded"); return FI_ESTATE; }
   (void)hipDeviceSynchronize();
   drop_graph(g);
+  for (hipStream_t ls : g->lane_streams) (void)hipStreamDestroy(ls);
+  for (hipEvent_t ev : g->lane_events) (void)hipEventDestroy(ev);
+  g->lane_streams.clear();
+  g->lane_events.clear();
   if (g->opts.dev_free) g->opts.dev_free(g->dev, g->opts.user); else (void)hipFree(g->dev);
   g->dev = nullptr;
   g->state = 0;

@@ -68,6 +68,7 @@ struct Node {
   int32_t is_output;
   int32_t first_level, last_level;
   int32_t launch, slot;          // launch index and problem slot inside it
+  int32_t lane;                  // lane of the node's member
   int32_t kind, tile;
   int32_t splits;                // reduction splits (1 = none)
   uint64_t ws_off;               // partials of a split node, relative to the workspace
@@ -79,6 +80,7 @@ struct Node {
 
 struct Launch {
   int32_t level, kind, tile;
+  int32_t lane;                  // stream the launch is issued to (0 = the caller's)
   int32_t wdtype, adtype;        // weight / activation storage dtype of every problem in it
   int32_t first_desc, n;         // contiguous range in the descriptor table
   std::vector<int32_t> nodes;    // global node ids, slot order

@@ -127,3 +127,20 @@ def test_hip_graph_replay_matches_eager():
         assert all(np.array_equal(a, b) for a, b in zip(again, eager_small))
     finally:
         g.close()
+
+
+def test_concurrent_lanes_equal_serial_schedule():
+    """Members of different architecture run on concurrent internal streams; the bits are those of the
+    single-stream schedule, run after run."""
+    mem = _members()
+    x = gen.make_input(7, 3, 3, 64, 64, "normal", "bf16")
+    serial = _run(mem, x, serial_lanes=True)
+    from tests import harness
+    g = harness.GpuDag(mem, 3)
+    try:
+        assert g.dag.query().n_lanes == 5
+        for _ in range(3):
+            got = g.run(x)
+            assert all(np.array_equal(a, b) for a, b in zip(got, serial))
+    finally:
+        g.close()

@@ -230,3 +230,26 @@ def test_per_model_load_mode_needs_packed_members():
     with pytest.raises(fi.FiError) as e:
         _build(["resnet18"], 1, hw=32, load_mode=fi.FI_LOAD_PER_MODEL)
     assert e.value.status == fi.FI_EINVAL
+
+
+def test_lanes_group_members_of_identical_architecture():
+    """Members with identical graphs share a lane (and their launches); different architectures get their
+    own lane, whose tensors and split-K scratch never share memory with another lane's."""
+    d, _, _ = _build(["resnet18", "vgg16", "resnet18", "mobilenetv2"], 2)
+    q = d.query()
+    assert q.n_lanes == 3
+    nodes, launches = d.nodes(), d.launches()
+    lane_of_model = {}
+    for n in nodes:
+        lane_of_model.setdefault(n.model, launches[n.launch].lane)
+        assert launches[n.launch].lane == lane_of_model[n.model]
+    assert lane_of_model[0] == lane_of_model[2] and len({lane_of_model[m] for m in (0, 1, 3)}) == 3
+    stored = [n for n in nodes if n.out_bytes]
+    for i, a in enumerate(stored):
+        for b in stored[i + 1:]:
+            if lane_of_model[a.model] != lane_of_model[b.model]:
+                assert a.out_off + a.out_bytes <= b.out_off or b.out_off + b.out_bytes <= a.out_off
+    one, _, _ = _build(["resnet18"] * 3, 2)
+    assert one.query().n_lanes == 1
+    ser, _, _ = _build(["resnet18", "vgg16"], 2, serial_lanes=True)
+    assert ser.query().n_lanes == 1
