@@ -152,6 +152,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 constexpr int BK = 64;
 constexpr int LDS_STRIDE = BK + 8;  // elements; 144-byte rows keep 16-byte reads conflict-free
 constexpr int NXCD = 8;
+#ifndef STREAM_OUT_BYTES
+#define STREAM_OUT_BYTES (48 << 20)
+#endif
 constexpr uint32_t OOB = 0x80000000u;  // byte offset past any tensor: the buffer load returns zero
 
 // m / dv for 0 <= m < 2^24 (exact: the float product is off by at most one, then corrected)
@@ -198,6 +201,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   if (!find_problem_at(a, xcd_contiguous((int)blockIdx.x, (int)gridDim.x), p, bid)) return;
   const Desc d = a.d[p];
   const int M = a.batch * d.Ho * d.Wo;
+  // Outputs far larger than the last-level cache are streamed past it; smaller ones are left to the
+  // cache, which absorbs the store burst of a launch whose workgroups all finish together.
+  const bool stream_out = (int64_t)M * d.Cop * 2 > (int64_t)STREAM_OUT_BYTES;
   const int tiles_mn = ((M + BM - 1) / BM) * d.tiles_n;
   const int split = bid / tiles_mn;  // split-K: this workgroup reduces one slice of K into a partial tile
   bid -= split * tiles_mn;
@@ -459,11 +465,11 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
           *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
           *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
         } else {
-          // streamed out: the tensor is far larger than L2 and is next read by another launch
-          u32x4 pk;
+            u32x4 pk;
           pk[0] = pack_bf16x2(v[0], v[1]); pk[1] = pack_bf16x2(v[2], v[3]);
           pk[2] = pack_bf16x2(v[4], v[5]); pk[3] = pack_bf16x2(v[6], v[7]);
-          __builtin_nontemporal_store(pk, reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o));
+          u32x4* const yp = reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o);
+          if (stream_out) __builtin_nontemporal_store(pk, yp); else *yp = pk;
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");  // reads done before the next block's writes
@@ -561,8 +567,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
           uint4 pk;
           pk.x = pack_bf16x2(v[0], v[1]); pk.y = pack_bf16x2(v[2], v[3]);
           pk.z = pack_bf16x2(v[4], v[5]); pk.w = pack_bf16x2(v[6], v[7]);
-          // streamed out: the tensor is far larger than L2 and is next read by another launch
-          __builtin_nontemporal_store(__builtin_bit_cast(u32x4, pk), reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o));
+            u32x4* const yp = reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o);
+          if (stream_out) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, pk), yp); else *yp = __builtin_bit_cast(u32x4, pk);
         }
       }
     }
