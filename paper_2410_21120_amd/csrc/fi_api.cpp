@@ -99,6 +99,7 @@ int pick_tile(const Node& n, int max_batch, int group, bool wide) {
   auto blocks = [&](int t) { return group * ((M + tile_bm(t) - 1) / tile_bm(t)) * ((n.Co + tile_bn(t) - 1) / tile_bn(t)); };
   // Short reductions stream activations (bandwidth-bound): medium tiles keep more workgroups
   // and loads in flight.  Long reductions are matrix-core-bound: the largest tile re-reads least.
+  if (n.Cp == 4) return n.Co <= 64 ? T_128x64 : T_128x128;  // 4-channel input: the two-tap gather exists for these tiles
   const int want = (n.Kp <= 512 || wide) ? T_128x128 : T_256x128;  // fp32-activation members: no 256-row tile
   const int order[4] = {T_256x128, T_128x128, T_128x64, T_64x64};
   bool started = false;
@@ -249,7 +250,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
             const int64_t M = (int64_t)B * nd.Ho * nd.Wo;
             const int64_t nb64 = ((M + 63) / 64) * ((nd.Co + 63) / 64);
             const int ntiles = (nd.Kp + 63) / 64;
-            nd.splits = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, ntiles / 4), 256 / nb64));
+            nd.splits = nd.Cp == 4 ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, ntiles / 4), 256 / nb64));
           }
           // the kernel addresses its input with 32-bit byte offsets through a buffer resource
           if ((uint64_t)B * nd.Ho * nd.Wo >= (1ull << 24)) {  // row indices are decoded with exact float arithmetic
@@ -293,7 +294,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
       Node& nd = g->nodes[(size_t)i];
       if (nd.level != lv) continue;
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 4 + adt * 2 + (nd.kind == K_CONV_MFMA && nd.splits > 1 ? 1 : 0));
+      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 8 + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 + (nd.kind == K_CONV_MFMA && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
       if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
         new_launch(lv, nd.kind, nd.tile, adt).lane = nd.lane;

@@ -148,6 +148,7 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 constexpr int BK = 64;
 constexpr int LDS_STRIDE = BK + 8;  // elements; 144-byte rows keep 16-byte reads conflict-free
@@ -180,7 +181,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // hi = bf16(x) and lo = bf16(x - hi) (two bf16 terms carry 16 mantissa bits), both halves are
 // multiplied by the bf16 weights into the same fp32 accumulator, and outputs / residuals stay
 // fp32: bf16 matrix-core throughput at fp32-grade activation accuracy.
-template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, int NS = 1>
+// C4: the input has 4 stored channels (an RGB-like model input); an 8-element reduction vector
+// then spans two neighbouring filter taps and is gathered with two half-width loads.
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, int NS = 1, bool C4 = false>
 __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
   constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
@@ -223,7 +226,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // Per row: the byte offset of its window origin (n, p*stride-pad, q*stride-pad, 0) and which
   // filter rows / columns land inside the image (bit r: row r valid; bit 8+s: column s valid).
   int a_row[AR], a_rc[AR];
-  const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho;
+  const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho, inv_k = 1.0f / (float)d.k;
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int m = m0 + srow + RPP * i;
@@ -280,12 +283,35 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 
 #define FI_FETCH(KT, S)                                                                           \
   {                                                                                               \
-    const int tvar = ((kr * d.W + ks) * d.Cp + kc) * AE;                                          \
-    _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
-      const bool ok = ((a_rc[i] >> kr) & (a_rc[i] >> (8 + ks)) & 1) != 0;                         \
-      const uint32_t off = ok ? (uint32_t)(a_row[i] + tvar) : OOB;                                \
-      _Pragma("unroll") for (int h = 0; h < AV; ++h)                                              \
-          av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);          \
+    if constexpr (!C4) {                                                                          \
+      const int tvar = ((kr * d.W + ks) * d.Cp + kc) * AE;                                        \
+      _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                            \
+        const bool ok = ((a_rc[i] >> kr) & (a_rc[i] >> (8 + ks)) & 1) != 0;                       \
+        const uint32_t off = ok ? (uint32_t)(a_row[i] + tvar) : OOB;                              \
+        _Pragma("unroll") for (int h = 0; h < AV; ++h)                                            \
+            av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);        \
+      }                                                                                           \
+    } else {                                                                                      \
+      const int tap0 = ((KT) * BK + kvec) >> 2; /* elements 0-3: tap0, elements 4-7: tap0 + 1 */  \
+      int tr[2], tc[2], tv[2];                                                                    \
+      _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                             \
+        tr[h] = fast_div(tap0 + h, d.k, inv_k);                                                   \
+        tc[h] = tap0 + h - tr[h] * d.k;                                                           \
+        tv[h] = (tr[h] * d.W + tc[h]) * 4 * AE;                                                   \
+      }                                                                                           \
+      _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                            \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                           \
+          const bool ok = tr[h] < d.k && ((a_rc[i] >> tr[h]) & (a_rc[i] >> (8 + tc[h])) & 1) != 0; \
+          const uint32_t off = ok ? (uint32_t)(a_row[i] + tv[h]) : OOB;                           \
+          if constexpr (WIDE) {                                                                   \
+            av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);                 \
+          } else {                                                                                \
+            const u32x2 half = __builtin_amdgcn_raw_buffer_load_b64(xres, off, 0, 0);             \
+            av[S][i][0][2 * h] = half[0];                                                         \
+            av[S][i][0][2 * h + 1] = half[1];                                                     \
+          }                                                                                       \
+        }                                                                                         \
+      }                                                                                           \
     }                                                                                             \
     const bool bok = !(b_tail && (KT) == ntiles_all - 1 && kvec >= 32);                           \
     _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
@@ -1005,6 +1031,16 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       return go(conv_direct_kernel<float, float>, nb, 256, a, s);
     case K_CONV_MFMA:
       if (!wb) return (int)hipErrorInvalidValue;
+      if (hd[(size_t)L.first_desc].Cp == 4) {  // 4-channel model input
+        if (!ab) {
+          if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, true, 1, true>, nb, 256, a, s);
+          if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, true, 1, true>, nb, 256, a, s);
+          return (int)hipErrorInvalidValue;
+        }
+        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false, 1, true>, nb, 256, a, s);
+        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, 1, true>, nb, 256, a, s);
+        return (int)hipErrorInvalidValue;
+      }
       if (!ab) {  // fp32 activations: split-bf16 inputs
         if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, true>, nb, 256, a, s);
         if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, true>, nb, 256, a, s);

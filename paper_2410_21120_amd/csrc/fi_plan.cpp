@@ -43,6 +43,15 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
   const uint64_t wsz = m.dtype == FI_BF16 ? 2 : 4;
   out.cgran = g;
   out.in_cp = round_up(m.in_c, g);
+  if (m.dtype == FI_BF16 && m.in_c <= 4) {
+    // An RGB-like input padded to 8 channels would make five eighths of the first convolution's
+    // reduction zeros; when only convolutions read the input it is staged with 4 channels and the
+    // kernels gather each 8-element vector from two neighbouring filter taps.
+    bool only_convs = true;
+    for (int32_t i = 0; i < m.n_layers; ++i)
+      if (m.layers[i].input == FI_INPUT && m.layers[i].op != FI_CONV2D) only_convs = false;
+    if (only_convs) out.in_cp = 4;
+  }
   out.nodes.assign((size_t)m.n_layers, Node{});
   uint64_t off = 0;
   for (int32_t i = 0; i < m.n_layers; ++i) {

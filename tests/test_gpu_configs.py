@@ -47,9 +47,14 @@ def test_config1_two_tiny_cnns_fp32():
             ys = g.run(x)
         finally:
             g.close()
-        for (m, blob), y in zip(mem, ys):
+        import json
+        import os
+        gold = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config1_oracle.json")))
+        for i, ((m, blob), y) in enumerate(zip(mem, ys)):
             ref = oracle.run_model(m, blob, x)
             assert harness.rel_l2(y, ref) <= 1e-4
+            stored = np.array(gold["members"][i]["softmax" if softmax else "logits"], dtype=np.float32)[None]
+            assert harness.rel_l2(y, stored) <= 1e-4  # the oracle's stored values (tests/golden)
             assert int(oracle.top1(y)[0]) == int(oracle.top1(ref)[0])
             if softmax:
                 assert abs(float(y.sum()) - 1.0) < 1e-5

@@ -132,12 +132,16 @@ def test_pack_is_a_permutation_with_zero_padding():
     dst = np.full(n, 0xAB, np.uint8)
     fi.fi_model_pack(spec, dst.ctypes.data, n)
     pk = dst.view(np.uint16)
-    # first conv: 3 -> 32, k3: packed rows [o][r][s][c padded to 8], row length 72 -> 96
+    # first conv: 3 -> 32, k3, reading the 4-channel staged input: packed rows [o][r][s][c padded to 4],
+    # row length 36 -> 64
     L = m.layers[0]
     w = blob[L.w_off:L.w_off + 2 * 32 * 27].view(np.uint16).reshape(32, 3, 3, 3)
-    rows = pk[:32 * 96].reshape(32, 96)
-    assert np.array_equal(rows[:, :72].reshape(32, 3, 3, 8)[..., :3], w.transpose(0, 2, 3, 1))
-    assert not rows[:, :72].reshape(32, 3, 3, 8)[..., 3:].any() and not rows[:, 72:].any()
+    rows = pk[:32 * 64].reshape(32, 64)
+    assert np.array_equal(rows[:, :36].reshape(32, 3, 3, 4)[..., :3], w.transpose(0, 2, 3, 1))
+    assert not rows[:, :36].reshape(32, 3, 3, 4)[..., 3:].any() and not rows[:, 36:].any()
+    # second conv (1x1, 32 -> 16 after the depthwise): channels are padded to 8 everywhere else
+    L2 = m.layers[2]
+    assert L2.op == "conv" and L2.cin == 32
     # multiset of non-zero weights is preserved over the whole blob
     canon = np.concatenate([blob[L.w_off:L.w_off + 2 * (L.cout * (L.cin if L.op != "dwconv" else 1) * L.k * L.k)].view(np.uint16)
                             for L in m.layers if L.op in ("conv", "dwconv", "fc")])

@@ -10,29 +10,44 @@ import torch.nn.functional as F
 import oracle
 from workloads import gen, zoo
 
-# (family, nodes, conv, dw, pool, gap, fc, depth, params, MACs/image): architecture tables of the
-# cited networks with BatchNorm's two parameters per channel replaced by one folded bias.
-STRUCT = [
-    ("tiny", 6, 2, 0, 1, 1, 1, 6, 5418, 1622336),
-    ("resnet18", 23, 20, 0, 1, 1, 1, 20, 11689512 - 4800, 1814073344),
-    ("resnet50", 56, 53, 0, 1, 1, 1, 52, 25557032 - 26560, 4089184256),
-    ("mobilenetv2", 54, 35, 17, 0, 1, 1, 54, 3504872 - 17056, 300774272),
-    ("vgg16", 21, 13, 0, 5, 0, 3, 21, 138357544, 15470264320),
-]
+import json
+import os
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+ARCH = {k: v for k, v in json.load(open(os.path.join(GOLDEN, "architectures.json"))).items() if not k.startswith("_")}
 
 
-@pytest.mark.parametrize("row", STRUCT)
-def test_structure(row):
-    fam, nodes, nconv, ndw, npool, ngap, nfc, depth, params, macs = row
+@pytest.mark.parametrize("fam", sorted(ARCH))
+def test_structure(fam):
+    """Node, parameter and MAC counts of the published architecture tables (tests/golden/architectures.json)."""
+    g = ARCH[fam]
     m = zoo.FAMILIES[fam]()
     ops = [L.op for L in m.layers]
-    assert len(ops) == nodes
+    assert len(ops) == g["nodes"]
     assert (ops.count("conv"), ops.count("dwconv"), ops.count("maxpool"), ops.count("gap"), ops.count("fc")) == \
-        (nconv, ndw, npool, ngap, nfc)
-    assert max(m.levels()) == depth
-    assert m.n_params() == params
-    assert m.macs() == macs
-    assert m.layers[m.output].cout == (10 if fam == "tiny" else 1000)
+        (g["conv"], g["dwconv"], g["maxpool"], g["gap"], g["fc"])
+    assert max(m.levels()) == g["depth"]
+    assert m.n_params() == g["params"]
+    assert m.macs() == g["macs"]
+    fc_or_sm = m.layers[m.output]
+    assert fc_or_sm.cout == g["classes"]
+    if "params_with_batchnorm" in g:  # folding removes one of BatchNorm's two parameters per normalised channel
+        bn_channels = sum(L.cout for L in m.layers if L.op in ("conv", "dwconv"))
+        assert g["params_with_batchnorm"] - g["params"] in (bn_channels, 0)
+
+
+def test_config1_matches_stored_oracle_values():
+    """The oracle reproduces its stored outputs for configuration 1 (a guard against silent oracle drift)."""
+    gold = json.load(open(os.path.join(GOLDEN, "config1_oracle.json")))
+    x = gen.make_input(7, 1, 3, 32, 32, "uniform", "f32")
+    for i, mem in enumerate(gold["members"]):
+        m = zoo.tiny_cnn("f32", softmax=True)
+        blob = gen.make_blob(m, mem["seed"], bias_std=0.0)
+        logits = oracle.run_model(m, blob, x, node=4)[0]
+        probs = oracle.run_model(m, blob, x)[0]
+        assert np.allclose(logits, mem["logits"], rtol=1e-6, atol=1e-7)
+        assert np.allclose(probs, mem["softmax"], rtol=1e-6, atol=1e-8)
+        assert int(oracle.top1(logits[None])[0]) == mem["top1"]
 
 
 def test_stage_shapes():
