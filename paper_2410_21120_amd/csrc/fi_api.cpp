@@ -27,7 +27,8 @@ struct Member {
   fi_model_spec spec;     // borrowed pointers inside
   ModelPlan plan;
   int32_t node0;          // first global node id
-  int32_t lane;           // members of identical architecture share a lane
+  int32_t lane;           // members of identical architecture share a lane (two lanes when they are many and large)
+  int32_t sibling_lanes;  // lanes that run this member's architecture side by side
   uint64_t arena_off;     // placement of the packed blob in the weight arena
 };
 
@@ -207,21 +208,45 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
 
   // ---- lanes: members whose graphs are identical node for node share launches level by level;
   //      members of different architecture rarely do, so each architecture gets a lane of its
-  //      own that runs concurrently with the others (no edge joins two members) -----------------
+  //      own that runs concurrently with the others (no edge joins two members).  A large family
+  //      of large members is halved into two lanes: every launch of a half still covers the chip,
+  //      and the tail of one lane's launch (workgroups draining, stores in flight, the next launch
+  //      starting up) is filled by the other lane's work instead of idling. --------------------
   {
-    std::map<std::string, int32_t> lane_of;
-    for (Member& mb : g->members) {
+    std::map<std::string, std::vector<int32_t>> family;   // architecture signature -> members, in order
+    std::vector<std::string> order;
+    for (size_t mi = 0; mi < g->members.size(); ++mi) {
+      Member& mb = g->members[mi];
       std::string sig = std::to_string(mb.spec.act_dtype);
       for (const Node& n : mb.plan.nodes) {
         char buf[96];
         std::snprintf(buf, sizeof(buf), "|%d,%d,%d,%d,%d,%d,%d,%d,%d", n.op, n.input, n.residual, n.C, n.Co, n.k, n.stride, n.pad, n.act);
         sig += buf;
       }
-      auto it = lane_of.find(sig);
-      if (it == lane_of.end()) it = lane_of.emplace(sig, opts->serial_lanes ? 0 : (int32_t)lane_of.size()).first;
-      mb.lane = it->second;
+      if (!family.count(sig)) order.push_back(sig);
+      family[sig].push_back((int32_t)mi);
     }
-    g->n_lanes = opts->serial_lanes ? 1 : (int32_t)lane_of.size();
+    int32_t next_lane = 0;
+    for (const std::string& sig : order) {
+      const std::vector<int32_t>& mem = family[sig];
+      const int32_t m = (int32_t)mem.size();
+      // halve when most convolutions of half the family still give every compute unit a 128x128 tile
+      int32_t convs = 0, full = 0;
+      for (const Node& n : g->members[(size_t)mem[0]].plan.nodes) {
+        if (n.op != FI_CONV2D) continue;
+        ++convs;
+        const int64_t tiles = (((int64_t)opts->max_batch * n.Ho * n.Wo + 127) / 128) * ((n.Co + 127) / 128);
+        if (tiles * (m / 2) >= 256) ++full;
+      }
+      const int32_t halves = (!opts->serial_lanes && m >= 4 && convs > 0 && 2 * full >= convs) ? 2 : 1;
+      for (int32_t j = 0; j < m; ++j) {
+        Member& mb = g->members[(size_t)mem[(size_t)j]];
+        mb.lane = opts->serial_lanes ? 0 : next_lane + (halves == 2 && j >= (m + 1) / 2 ? 1 : 0);
+        mb.sibling_lanes = halves;
+      }
+      next_lane += halves;
+    }
+    g->n_lanes = opts->serial_lanes ? 1 : next_lane;
     for (Node& nd : g->nodes) nd.lane = g->members[(size_t)nd.model].lane;
   }
 
@@ -263,7 +288,8 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
             return FI_EUNSUPPORTED;
           }
           const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.level + 1000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
-          nd.tile = pick_tile(nd, B, std::min(grp, (int)FI_MAX_GROUP), adt == FI_F32);
+          // sibling lanes run the same level at about the same time: the chip is shared by all of them
+          nd.tile = pick_tile(nd, B, std::min(grp * g->members[(size_t)nd.model].sibling_lanes, (int)FI_MAX_GROUP), adt == FI_F32);
         } else nd.kind = K_CONV_DIRECT;
         break;
       case FI_DWCONV2D: nd.kind = K_DWCONV; break;

@@ -257,3 +257,20 @@ def test_lanes_group_members_of_identical_architecture():
     assert one.query().n_lanes == 1
     ser, _, _ = _build(["resnet18", "vgg16"], 2, serial_lanes=True)
     assert ser.query().n_lanes == 1
+
+
+def test_large_family_is_halved_into_two_lanes():
+    """Four or more identical members whose convolutions cover the chip even at half the family run as
+    two lanes (first half, second half); the same family at a small batch stays one lane."""
+    big, _, _ = _build(["resnet18"] * 4, 256)
+    assert big.query().n_lanes == 2
+    launches = big.launches()
+    lane_of_model = {}
+    for n in big.nodes():
+        lane_of_model.setdefault(n.model, launches[n.launch].lane)
+        assert launches[n.launch].lane == lane_of_model[n.model]
+    assert [lane_of_model[m] for m in range(4)] == [0, 0, 1, 1]
+    small, _, _ = _build(["resnet18"] * 4, 2)
+    assert small.query().n_lanes == 1
+    ser, _, _ = _build(["resnet18"] * 4, 256, serial_lanes=True)
+    assert ser.query().n_lanes == 1
