@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--swap-requests", type=int, default=200)
     ap.add_argument("--no-extras", action="store_true", help="skip separate-DAG, swap and CPU legs")
+    ap.add_argument("--serial-lanes", action="store_true",
+                    help="issue every launch on the caller's stream (no concurrent lanes): the condition the per-kernel "
+                         "roofline is measured in, for profiler runs that should show the same durations")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to calibrate rocprofv3 counters)")
     a = ap.parse_args()
@@ -85,7 +88,7 @@ def main():
 
     # ---- fused DAG: timed region ------------------------------------------------------------
     t0 = time.perf_counter()
-    dag = make_dag(members)
+    dag = make_dag(members, serial_lanes=a.serial_lanes)
     t_build = time.perf_counter() - t0
     t0 = time.perf_counter()
     dag.load(stream)
@@ -101,39 +104,58 @@ def main():
     torch.cuda.synchronize()
     fused_ms = (time.perf_counter() - t0) * 1e3 / a.steps
 
-    # ---- per-launch HIP-event timing on the launch stream --------------------------------------
+    # ---- per-launch HIP-event timing on the streams the launches go to -------------------------
+    # fi_timeline issues the step exactly as fi_run does (lanes concurrent) with an event after every
+    # launch on its own stream.  Launch i spans [end of the previous launch on that stream, its own end].
+    # Launches of one kernel on different lanes overlap, so a kernel's rate is its algorithmic work
+    # divided by the time during which at least one of its launches was running (the union of its
+    # intervals): never more than the chip delivered, and an underestimate whenever a different
+    # kernel shared the chip during that time.
     launches = dag.launches()
     prof_iters = max(3, min(10, a.steps))
-    acc = np.zeros(len(launches))
-    for _ in range(prof_iters):
-        acc += np.array(dag.profile(xin.data_ptr(), B, optr, stream))
-    acc /= prof_iters
     per_kernel = {}
-    for L, ms in zip(launches, acc):
-        k = per_kernel.setdefault(L.name.decode(), dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
+    for L in launches:
+        k = per_kernel.setdefault(L.name.decode(), dict(launches=0, ms=0.0, busy_ms=0.0, flops=0.0, bytes=0.0))
         k["launches"] += 1
-        k["ms"] += float(ms)
         k["flops"] += 2.0 * L.macs_per_image * B
         k["bytes"] += float(L.bytes_per_image) * B + L.weight_bytes
-    dom_name = max((n for n in per_kernel if n.startswith("conv_mfma")), key=lambda n: per_kernel[n]["ms"],
-                   default=max(per_kernel, key=lambda n: per_kernel[n]["ms"]))
+    for _ in range(prof_iters):
+        tb, te = dag.timeline(xin.data_ptr(), B, optr, stream)
+        spans = {}
+        for L, b, e in zip(launches, tb, te):
+            per_kernel[L.name.decode()]["ms"] += (e - b) / prof_iters
+            spans.setdefault(L.name.decode(), []).append((b, e))
+        for n, iv in spans.items():
+            iv.sort()
+            busy, hi = 0.0, -1.0
+            for b, e in iv:
+                if e > hi:
+                    busy += e - max(b, hi)
+                    hi = e
+            per_kernel[n]["busy_ms"] += busy / prof_iters
+    dom_name = max((n for n in per_kernel if n.startswith("conv_mfma")), key=lambda n: per_kernel[n]["busy_ms"],
+                   default=max(per_kernel, key=lambda n: per_kernel[n]["busy_ms"]))
     dom = per_kernel[dom_name]
     mfma = [v for n, v in per_kernel.items() if n.startswith("conv_mfma")]
-    mfma_flops, mfma_ms = sum(v["flops"] for v in mfma), sum(v["ms"] for v in mfma)
+    mfma_flops = sum(v["flops"] for v in mfma)
     # the roofline that binds this kernel's algorithmic work: matrix cores or HBM
     t_mfma = dom["flops"] / (PEAK_MFMA_BF16 * 1e12)
     t_hbm = dom["bytes"] / (PEAK_HBM * 1e9)
     if t_mfma >= t_hbm:
-        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        achieved = dom["flops"] / (dom["busy_ms"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_MFMA_BF16, unit="TFLOP/s", frac=achieved / PEAK_MFMA_BF16)
     else:
-        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        achieved = dom["bytes"] / (dom["busy_ms"] * 1e-3) / 1e9
         roofline = dict(bound="hbm", achieved=achieved, peak=PEAK_HBM, unit="GB/s", frac=achieved / PEAK_HBM)
     roofline.update(kernel=dom_name, launches_per_step=dom["launches"], avg_launch_ms=dom["ms"] / dom["launches"],
-                    flops_per_step=dom["flops"], bytes_per_step=dom["bytes"], traffic=None)
-    kernels = {n: dict(launches=v["launches"], ms=round(v["ms"], 4),
-                       tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["flops"] else 0.0,
-                       gbps=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1)) for n, v in per_kernel.items()}
+                    busy_ms_per_step=dom["busy_ms"], concurrent_lanes=q.n_lanes,
+                    flops_per_step=dom["flops"], bytes_per_step=dom["bytes"],
+                    timing="HIP events after every launch on the stream it is issued to, in the schedule the timed region runs; "
+                           "achieved = algorithmic work of all launches of the kernel / time at least one of them was running",
+                    traffic=counter_traffic(dom_name, a.workload))
+    kernels = {n: dict(launches=v["launches"], ms=round(v["ms"], 4), busy_ms=round(v["busy_ms"], 4),
+                       tflops=round(v["flops"] / (v["busy_ms"] * 1e-3) / 1e12, 2) if v["flops"] else 0.0,
+                       gbps=round(v["bytes"] / (v["busy_ms"] * 1e-3) / 1e9, 1)) for n, v in per_kernel.items()}
     res = {
         "metric": "fused-DAG images/sec + MFMA util; peak HBM and swap latency vs per-model",
         "value": B / (fused_ms * 1e-3), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -142,11 +164,12 @@ def main():
         "config": {"workload": wl["desc"], "members": len(members), "batch": B,
                    "model_inferences_per_s": B * len(members) / (fused_ms * 1e-3)},
         "roofline": roofline,
-        "mfma_util_all_dense": mfma_flops / (mfma_ms * 1e-3) / 1e12 / PEAK_MFMA_BF16 if mfma_ms else None,
+        # every dense (matrix-core) FLOP of the step over the whole step time
+        "mfma_util_all_dense": mfma_flops / (fused_ms * 1e-3) / 1e12 / PEAK_MFMA_BF16,
         "kernels": kernels,
         "dag": dict(nodes=q.n_nodes, levels=q.n_levels, launches=q.n_launches, device_allocs=q.n_device_allocs,
                     h2d_copies=q.n_h2d_copies, arena_bytes=q.arena_bytes, act_bytes=q.act_bytes,
-                    device_bytes=q.device_bytes, build_ms=t_build * 1e3, load_ms=t_load * 1e3,
+                    lanes=q.n_lanes, device_bytes=q.device_bytes, build_ms=t_build * 1e3, load_ms=t_load * 1e3,
                     load_gbps=q.arena_bytes / t_load / 1e9),
     }
     dag.unload()
@@ -183,6 +206,40 @@ def main():
         res["swap"] = swap_churn(fi, torch, gen, zoo, alloc, stream, a.swap_requests)
         res["cpu_baseline"] = cpu_baseline(members[0], x, len(members))
     print(json.dumps(res))
+
+
+# HBM traffic of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; KiB per dispatch,
+# summed over the kernel's launches of one step and scaled by what the same counters read for a
+# 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
+# has changed since the counters were taken the entry no longer applies and traffic is null.
+COUNTERS = {
+    "sources_sha256": "",
+    "workload": "cfg4",
+    "kernel": "",
+    "launches_per_step": 0,
+    "fetch_kib_per_step": 0.0, "write_kib_per_step": 0.0,
+    "fetch_scale": 2.0, "write_scale": 1.0,
+}
+
+
+def sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2410_21120_amd", "csrc")
+    for f in ("fi_internal.h", "fi_plan.cpp", "fi_api.cpp", "fi_kernels.hip"):
+        with open(os.path.join(csrc, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def counter_traffic(kernel, workload):
+    c = COUNTERS
+    if not c["sources_sha256"] or c["kernel"] != kernel or c["workload"] != workload or c["sources_sha256"] != sources_sha256():
+        return None
+    per_launch = (c["fetch_kib_per_step"] * c["fetch_scale"] + c["write_kib_per_step"] * c["write_scale"]) * 1024.0 / c["launches_per_step"]
+    return dict(bytes_per_launch=per_launch, fetch_bytes_per_launch=c["fetch_kib_per_step"] * c["fetch_scale"] * 1024.0 / c["launches_per_step"],
+                write_bytes_per_launch=c["write_kib_per_step"] * c["write_scale"] * 1024.0 / c["launches_per_step"],
+                source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy probe")
 
 
 def swap_churn(fi, torch, gen, zoo, alloc, stream, n_req):

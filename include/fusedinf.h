@@ -181,10 +181,21 @@ fi_status fi_load(fi_dag* dag, void* hip_stream);
  * node is a softmax.  1 <= batch <= max_batch.  Allocates nothing. */
 fi_status fi_run(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream);
 
-/* Same pass with a HIP event between launches; ms[i] (host, n_launches floats)
- * receives launch i's elapsed milliseconds.  Synchronises the stream. */
+/* Same pass with every launch issued on hip_stream (lanes serialised) and a HIP
+ * event between launches; ms[i] (host, n_launches floats) receives launch i's
+ * elapsed milliseconds: the kernel's own time with the chip to itself.
+ * Synchronises the stream. */
 fi_status fi_profile(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream,
                      float* ms, int32_t n_ms);
+
+/* Same pass issued exactly as fi_run issues it (Section 3: independent members
+ * run side by side, here as concurrent lanes), with a HIP event after every
+ * launch on the stream it went to.  Launch i occupies [begin_ms[i], end_ms[i]]
+ * (host arrays, n >= n_launches floats each), in milliseconds since the pass
+ * began: from the end of the previous launch on the same stream to its own
+ * end.  Intervals of different lanes overlap.  Synchronises the stream. */
+fi_status fi_timeline(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream,
+                      float* begin_ms, float* end_ms, int32_t n);
 
 /* Synchronise, release the device allocation; the handle returns to BUILT. */
 fi_status fi_unload(fi_dag* dag);

@@ -72,7 +72,7 @@ class fi_launch_info(C.Structure):
 
 LIB_PATH = _build.OUT
 EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_query", "fi_node", "fi_launch", "fi_load",
-           "fi_run", "fi_profile", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
+           "fi_run", "fi_profile", "fi_timeline", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
 
@@ -97,6 +97,7 @@ def lib():
         L.fi_load.argtypes = [vp, vp]
         L.fi_run.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
         L.fi_profile.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), i32]
+        L.fi_timeline.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32]
         L.fi_unload.argtypes = [vp]
         L.fi_destroy.argtypes = [vp]
         L.fi_destroy.restype = None
@@ -178,6 +179,14 @@ def fi_profile(h, d_input_ptr, batch, d_output_ptrs, stream_ptr, n_launches):
     ms = (C.c_float * n_launches)()
     _check(lib().fi_profile(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr), ms, n_launches), "fi_profile")
     return list(ms)
+
+
+def fi_timeline(h, d_input_ptr, batch, d_output_ptrs, stream_ptr, n_launches):
+    outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
+    b = (C.c_float * n_launches)()
+    e = (C.c_float * n_launches)()
+    _check(lib().fi_timeline(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr), b, e, n_launches), "fi_timeline")
+    return list(b), list(e)
 
 
 def fi_unload(h) -> None:
@@ -311,6 +320,9 @@ class Dag:
 
     def profile(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
         return fi_profile(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr, self.query().n_launches)
+
+    def timeline(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
+        return fi_timeline(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr, self.query().n_launches)
 
     def unload(self):
         fi_unload(self.h)

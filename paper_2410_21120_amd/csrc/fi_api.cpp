@@ -577,18 +577,24 @@ fi_status fi_load(fi_dag* g, void* stream) {
   return FI_OK;
 }
 
+// ms: durations with every launch serialised on the caller's stream.  tl_begin / tl_end: the schedule as
+// fi_run issues it (lanes concurrent), launch i spanning [previous event on its stream, event after it],
+// in milliseconds since the pass began.
 static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream,
-                          float* ms, int32_t n_ms) {
+                          float* ms, int32_t n_ms, float* tl_begin = nullptr, float* tl_end = nullptr) {
   if (!g || !d_input || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
   if (g->state != 1) { set_error("fi_run: handle is not loaded"); return FI_ESTATE; }
   if (batch < 1 || batch > g->opts.max_batch) { set_error("batch %d outside [1, %d]", batch, g->opts.max_batch); return FI_EINVAL; }
   for (size_t m = 0; m < g->members.size(); ++m)
     if (!d_outputs[m]) { set_error("output %zu is null", m); return FI_EINVAL; }
   const size_t nl = g->launches.size();
-  if (ms && n_ms < (int32_t)nl) { set_error("ms holds %d entries, schedule has %zu launches", n_ms, nl); return FI_EINVAL; }
+  const bool timeline = tl_begin && tl_end;
+  if ((ms || timeline) && n_ms < (int32_t)nl) { set_error("timing arrays hold %d entries, schedule has %zu launches", n_ms, nl); return FI_EINVAL; }
   hipStream_t s = static_cast<hipStream_t>(stream);
   std::vector<hipEvent_t> ev;
-  if (ms) {
+  std::vector<size_t> ev_before(nl, 0);                        // timeline: index of the event that precedes launch i on its stream
+  std::vector<size_t> last_on_lane((size_t)g->n_lanes, 0);
+  if (ms || timeline) {
     ev.resize(nl + 1);
     for (auto& e : ev) if (hipEventCreate(&e) != hipSuccess) { set_error("hipEventCreate failed"); return FI_EHIP; }
     (void)hipEventRecord(ev[0], s);
@@ -620,16 +626,30 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
     const int e = launch_kernel(L, a, ls, g->descs);
     if (e != (int)hipSuccess) { set_error("launch %zu (%s): %s", i, L.name.c_str(), hipGetErrorString((hipError_t)e)); rc = FI_EHIP; break; }
     if (ms) (void)hipEventRecord(ev[i + 1], s);
+    if (timeline) {
+      const size_t lane = lanes ? (size_t)L.lane : 0;
+      // before the fork every lane's history is the caller's stream
+      ev_before[i] = (lanes && !forked) ? last_on_lane[0] : last_on_lane[lane];
+      (void)hipEventRecord(ev[i + 1], ls);
+      if (lanes && !forked) std::fill(last_on_lane.begin(), last_on_lane.end(), i + 1);
+      else last_on_lane[lane] = i + 1;
+    }
   }
   if (forked)
     for (int32_t l = 1; l < g->n_lanes; ++l) {
       (void)hipEventRecord(g->lane_events[(size_t)l], g->lane_streams[(size_t)l - 1]);
       (void)hipStreamWaitEvent(s, g->lane_events[(size_t)l], 0);
     }
-  if (ms) {
+  if (ms || timeline) {
     (void)hipStreamSynchronize(s);
-    if (rc == FI_OK)
+    if (rc == FI_OK && ms)
       for (size_t i = 0; i < nl; ++i) (void)hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]);
+    if (rc == FI_OK && timeline)
+      for (size_t i = 0; i < nl; ++i) {
+        tl_begin[i] = 0.0f;
+        if (ev_before[i]) (void)hipEventElapsedTime(&tl_begin[i], ev[0], ev[ev_before[i]]);
+        (void)hipEventElapsedTime(&tl_end[i], ev[0], ev[i + 1]);
+      }
     for (auto& e : ev) (void)hipEventDestroy(e);
   }
   return rc;
@@ -673,6 +693,12 @@ fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_o
 fi_status fi_profile(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream, float* ms, int32_t n_ms) {
   if (!ms) { set_error("null ms"); return FI_EINVAL; }
   return run_impl(g, d_input, batch, d_outputs, stream, ms, n_ms);
+}
+
+fi_status fi_timeline(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream,
+                      float* begin_ms, float* end_ms, int32_t n) {
+  if (!begin_ms || !end_ms) { set_error("null timeline array"); return FI_EINVAL; }
+  return run_impl(g, d_input, batch, d_outputs, stream, nullptr, n, begin_ms, end_ms);
 }
 
 fi_status fi_unload(fi_dag* g) {

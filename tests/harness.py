@@ -64,7 +64,9 @@ class GpuDag:
         ptrs = [o.data_ptr() for o in outs]
         if self.side is not None:
             torch.cuda.synchronize()  # inputs were prepared on torch's current stream
-        if profile:
+        if profile == "timeline":
+            ms = self.dag.timeline(xin.data_ptr(), b, ptrs, self.stream)
+        elif profile:
             ms = self.dag.profile(xin.data_ptr(), b, ptrs, self.stream)
         else:
             self.dag.run(xin.data_ptr(), b, ptrs, self.stream)

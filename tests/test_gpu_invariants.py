@@ -144,3 +144,30 @@ def test_concurrent_lanes_equal_serial_schedule():
             assert all(np.array_equal(a, b) for a, b in zip(got, serial))
     finally:
         g.close()
+
+
+def test_timeline_pass_gives_the_same_bits_and_ordered_intervals():
+    """The timed pass is the ordinary pass plus events: same outputs; on every lane the launches follow
+    each other (a launch begins where the previous one on its stream ended), the input staging precedes
+    everything, and no interval is empty or reversed."""
+    mem = _members()
+    x = gen.make_input(7, 3, 3, 64, 64, "normal", "bf16")
+    from tests import harness
+    g = harness.GpuDag(mem, 3)
+    try:
+        ref = g.run(x)
+        got, (tb, te) = g.run(x, profile="timeline")
+        assert all(np.array_equal(a, b) for a, b in zip(got, ref))
+        launches = g.dag.launches()
+        assert len(tb) == len(te) == len(launches)
+        last_end = {}
+        stage_end = max(e for L, e in zip(launches, te) if L.level == 0)
+        for L, b, e in zip(launches, tb, te):
+            assert 0.0 <= b <= e
+            if L.level > 0:
+                assert b >= stage_end - 1e-3
+                assert b >= last_end.get(L.lane, 0.0) - 1e-3  # issue order on a stream is execution order
+                last_end[L.lane] = e
+        assert len(last_end) == g.dag.query().n_lanes
+    finally:
+        g.close()
