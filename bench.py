@@ -152,7 +152,10 @@ def main():
                     flops_per_step=dom["flops"], bytes_per_step=dom["bytes"],
                     timing="HIP events after every launch on the stream it is issued to, in the schedule the timed region runs; "
                            "achieved = algorithmic work of all launches of the kernel / time at least one of them was running",
-                    traffic=counter_traffic(dom_name, a.workload))
+                    algorithmic_bytes_per_launch=dom["bytes"] / dom["launches"])
+    tr = counter_traffic(dom_name, a.workload)
+    roofline["traffic"] = tr["bytes_per_launch"] if tr else None   # HBM bytes per launch from the counters
+    roofline["traffic_detail"] = tr
     kernels = {n: dict(launches=v["launches"], ms=round(v["ms"], 4), busy_ms=round(v["busy_ms"], 4),
                        tflops=round(v["flops"] / (v["busy_ms"] * 1e-3) / 1e12, 2) if v["flops"] else 0.0,
                        gbps=round(v["bytes"] / (v["busy_ms"] * 1e-3) / 1e9, 1)) for n, v in per_kernel.items()}
@@ -213,11 +216,11 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "",
+    "sources_sha256": "a6c038937873f348a8b0ab510529c57301e36c1c1b4ca5d606a8520c753c4ada",
     "workload": "cfg4",
-    "kernel": "",
-    "launches_per_step": 0,
-    "fetch_kib_per_step": 0.0, "write_kib_per_step": 0.0,
+    "kernel": "conv_mfma_128x128",
+    "launches_per_step": 54,
+    "fetch_kib_per_step": 2889688.4, "write_kib_per_step": 3976448.0,
     "fetch_scale": 2.0, "write_scale": 1.0,
 }
 
