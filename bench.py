@@ -90,10 +90,13 @@ def main():
     t0 = time.perf_counter()
     dag = make_dag(members, serial_lanes=a.serial_lanes)
     t_build = time.perf_counter() - t0
+    torch.cuda.empty_cache()
+    free0 = torch.cuda.mem_get_info()[0]
     t0 = time.perf_counter()
     dag.load(stream)
     torch.cuda.synchronize()
     t_load = time.perf_counter() - t0
+    hbm_delta = free0 - torch.cuda.mem_get_info()[0]   # what the device reports (allocator granularity included)
     q = dag.query()
     for _ in range(a.warmup):
         dag.run(xin.data_ptr(), B, optr, stream)
@@ -103,6 +106,15 @@ def main():
         dag.run(xin.data_ptr(), B, optr, stream)
     torch.cuda.synchronize()
     fused_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    # per-step distribution: an event pair on the caller's stream around every step (lanes fork from
+    # and join that stream, so the pair brackets the whole schedule)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        dag.run(xin.data_ptr(), B, optr, stream)
+        e1.record()
+    torch.cuda.synchronize()
+    step_ms = np.array([e0.elapsed_time(e1) for e0, e1 in evs])
 
     # ---- per-launch HIP-event timing on the streams the launches go to -------------------------
     # fi_timeline issues the step exactly as fi_run does (lanes concurrent) with an event after every
@@ -162,7 +174,8 @@ def main():
     res = {
         "metric": "fused-DAG images/sec + MFMA util; peak HBM and swap latency vs per-model",
         "value": B / (fused_ms * 1e-3), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": fused_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": fused_ms, "ms_per_step_median": float(np.median(step_ms)), "ms_per_step_p95": float(np.percentile(step_ms, 95)),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl["desc"], "members": len(members), "batch": B,
                    "model_inferences_per_s": B * len(members) / (fused_ms * 1e-3)},
@@ -172,7 +185,7 @@ def main():
         "kernels": kernels,
         "dag": dict(nodes=q.n_nodes, levels=q.n_levels, launches=q.n_launches, device_allocs=q.n_device_allocs,
                     h2d_copies=q.n_h2d_copies, arena_bytes=q.arena_bytes, act_bytes=q.act_bytes,
-                    lanes=q.n_lanes, device_bytes=q.device_bytes, build_ms=t_build * 1e3, load_ms=t_load * 1e3,
+                    lanes=q.n_lanes, device_bytes=q.device_bytes, device_bytes_mem_get_info=hbm_delta, build_ms=t_build * 1e3, load_ms=t_load * 1e3,
                     load_gbps=q.arena_bytes / t_load / 1e9),
     }
     dag.unload()
@@ -181,9 +194,12 @@ def main():
     if not a.no_extras:
         # ---- the same members as n single-model DAGs ("without fusion") -----------------------
         singles = [make_dag([mb]) for mb in members]
+        torch.cuda.empty_cache()
+        free0 = torch.cuda.mem_get_info()[0]
         for d in singles:
             d.load(stream)
         torch.cuda.synchronize()
+        sep_delta = free0 - torch.cuda.mem_get_info()[0]
         sq = [d.query() for d in singles]
 
         def run_sep():
@@ -197,8 +213,24 @@ def main():
             run_sep()
         torch.cuda.synchronize()
         sep_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+        # second variant: every single-model handle on a stream of its own
+        side = [torch.cuda.Stream() for _ in singles]
+
+        def run_sep_streams():
+            for d, p, st in zip(singles, optr, side):
+                d.run(xin.data_ptr(), B, [p], st.cuda_stream)
+        for _ in range(a.warmup):
+            run_sep_streams()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            run_sep_streams()
+        torch.cuda.synchronize()
+        sep_streams_ms = (time.perf_counter() - t0) * 1e3 / a.steps
         res["fused_vs_separate"] = dict(
             fused_ms=fused_ms, separate_ms=sep_ms, speedup=sep_ms / fused_ms,
+            separate_on_own_streams_ms=sep_streams_ms, speedup_vs_own_streams=sep_streams_ms / fused_ms,
+            hbm_mem_get_info_fused=hbm_delta, hbm_mem_get_info_separate_resident=sep_delta,
             launches_fused=q.n_launches, launches_separate=sum(s.n_launches for s in sq),
             hbm_bytes_fused=q.device_bytes, hbm_bytes_separate_resident=sum(s.device_bytes for s in sq),
             hbm_bytes_separate_sequential=max(s.device_bytes for s in sq),
@@ -296,7 +328,61 @@ def swap_churn(fi, torch, gen, zoo, alloc, stream, n_req):
         for slot, mi in enumerate(members):
             serve([mi], bi, [outs[slot].data_ptr()], fi.FI_LOAD_ONE_COPY)
         lat["per_model"].append(time.perf_counter() - t0)
-    out = {"requests": len(reqs), "mean_arena_mb": float(np.mean(arena)) / 1e6}
+    # incremental (Section V, individual model swaps in a DAG): one resident handle; members that
+    # leave are replaced in place by those that arrive, the ones that stay are not touched.
+    def spec_of(mi):
+        m, act, packed = pool[mi]
+        return fi.make_spec(m, packed.data_ptr(), packed.numel(), act_dtype=act, packed=True)
+
+    cur = list(reqs[0][1])
+    sk = [spec_of(mi) for mi in cur]
+    res_dag = fi.Dag([a for a, _ in sk], 8, alloc, keepalive=[b for _, b in sk], load_mode=fi.FI_LOAD_PER_MODEL,
+                     swap_headroom_bytes=3 << 29)
+    res_dag.load(stream)
+    torch.cuda.synchronize()
+    inc_lat, swapped, moved, fallbacks = [], 0, 0, 0
+    for _, members, bi in reqs:
+        t0 = time.perf_counter()
+        arriving = [mi for mi in members if mi not in cur]
+        for slot in range(4):
+            if cur[slot] in members:
+                continue
+            mi = arriving.pop()
+            spec, keep = spec_of(mi)
+            try:
+                res_dag.swap_model(slot, spec, stream, keepalive=keep)
+                moved += res_dag.query().last_h2d_bytes
+            except fi.FiError:
+                fallbacks += 1      # does not fit the resident allocation: rebuild from scratch
+                cur[slot] = mi
+                res_dag.unload()
+                res_dag.destroy()
+                sk = [spec_of(c) for c in cur]
+                res_dag = fi.Dag([a for a, _ in sk], 8, alloc, keepalive=[b for _, b in sk], load_mode=fi.FI_LOAD_PER_MODEL,
+                                 swap_headroom_bytes=3 << 29)
+                res_dag.load(stream)
+            cur[slot] = mi
+            swapped += 1
+        res_dag.run(xs[bi].data_ptr(), 8, [o.data_ptr() for o in outs], stream)
+        torch.cuda.synchronize()
+        inc_lat.append(time.perf_counter() - t0)
+    res_dag.unload()
+    res_dag.destroy()
+    lat["resident_dag_member_swaps"] = inc_lat
+
+    # open loop: requests arrive at the stream's own (Poisson, 50/s) times and queue behind each other
+    open_lat = []
+    t_start = time.perf_counter()
+    for t_arr, members, bi in reqs:
+        now = time.perf_counter() - t_start
+        if now < t_arr - reqs[0][0]:
+            time.sleep(t_arr - reqs[0][0] - now)
+        serve(members, bi, [o.data_ptr() for o in outs], fi.FI_LOAD_PER_MODEL)
+        open_lat.append(time.perf_counter() - t_start - (t_arr - reqs[0][0]))
+    lat["fused_per_model_copies_open_loop_50rps"] = open_lat
+    out = {"requests": len(reqs), "mean_arena_mb": float(np.mean(arena)) / 1e6,
+           "member_swaps": dict(swaps=swapped, per_request=swapped / len(reqs), mean_h2d_mb_per_request=moved / len(reqs) / 1e6,
+                                rebuild_fallbacks=fallbacks)}
     for k, v in lat.items():
         v = np.array(v) * 1e3
         out[k] = dict(p50_ms=float(np.percentile(v, 50)), p95_ms=float(np.percentile(v, 95)),
@@ -316,8 +402,15 @@ def cpu_baseline(member, x, n_members):
     oracle.run_models_parallel(units, threads=cores)
     dt = time.perf_counter() - t0
     model_inf_per_s = len(units) / dt
+    cpu = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            cpu = next((l.split(":", 1)[1].strip() for l in fh if l.startswith("model name")), cpu)
+    except OSError:
+        pass
     return dict(value=model_inf_per_s / n_members, unit="images/s", cores=cores, kind="oracle",
-                model_inferences_per_s=model_inf_per_s,
+                model_inferences_per_s=model_inf_per_s, per_thread_model_inferences_per_s=model_inf_per_s / cores,
+                cpu=cpu, nproc=os.cpu_count(),
                 sample=f"{len(units)} single-image {m.name} forward passes on {cores} threads ({dt:.1f} s); "
                        f"images/s = model-inferences/s / {n_members} members")
 

@@ -118,6 +118,7 @@ typedef struct {
   void* (*pin_alloc)(size_t bytes, void* user);
   void (*pin_free)(void* ptr, void* user);
   void* user;
+  uint64_t swap_headroom_bytes; /* extra device bytes fi_load allocates beyond the plan, for later fi_swap_model calls */
 } fi_build_opts;
 
 typedef struct {
@@ -131,7 +132,18 @@ typedef struct {
   int32_t n_h2d_copies;      /* host-to-device copies per fi_load (1 in FI_LOAD_ONE_COPY) */
   int32_t state;             /* 0 BUILT, 1 LOADED */
   int32_t n_lanes;           /* concurrent launch lanes (groups of members with identical architecture) */
+  uint64_t device_capacity;  /* bytes of the loaded allocation (device_bytes at load + swap headroom); 0 when BUILT */
+  uint64_t last_h2d_bytes;   /* bytes moved by the most recent fi_load or fi_swap_model */
+  int32_t last_h2d_copies;   /* copies issued by the most recent fi_load or fi_swap_model */
+  int32_t reserved;
 } fi_dag_info;
+
+typedef struct {
+  uint64_t arena_off, packed_bytes; /* placement of the member's packed weights in the weight arena */
+  int32_t lane;                     /* launch lane of the member */
+  int32_t first_node, n_nodes;      /* its nodes are [first_node, first_node + n_nodes) */
+  int32_t reserved;
+} fi_member_info;
 
 /* Introspection of the compiled DAG (tests, reports). */
 typedef struct {
@@ -167,6 +179,7 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
 fi_status fi_query(const fi_dag* dag, fi_dag_info* info);
 fi_status fi_node(const fi_dag* dag, int32_t i, fi_node_info* info);     /* i in [0, n_nodes) */
 fi_status fi_launch(const fi_dag* dag, int32_t i, fi_launch_info* info); /* i in [0, n_launches) */
+fi_status fi_member(const fi_dag* dag, int32_t m, fi_member_info* info); /* m in [0, n_models) */
 
 /* Load: one device allocation, one pinned-to-device copy of the weight arena
  * (asynchronous on hip_stream; hip_stream is a hipStream_t, NULL = default stream). */
@@ -196,6 +209,21 @@ fi_status fi_profile(fi_dag* dag, const void* d_input, int32_t batch, void* cons
  * end.  Intervals of different lanes overlap.  Synchronises the stream. */
 fi_status fi_timeline(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream,
                       float* begin_ms, float* end_ms, int32_t n);
+
+/* Section V, "individual model swaps in a DAG" (Table IV): replaces member `slot`
+ * by `model` without recompiling or reloading the rest.  The sub-graph of the
+ * outgoing member is dropped, the newcomer's is compiled into the schedule, and
+ * in a LOADED handle only the newcomer's packed weights travel to the device
+ * (one copy, asynchronous on hip_stream) into the lowest free range of the weight
+ * arena that holds them; every other member's weights stay where they are, and
+ * their outputs keep their bits.  The handle may be BUILT (host work only) or
+ * LOADED; no fi_run may be in flight on another stream.  `model` follows the rules
+ * of fi_build_dag (borrowed; same weight dtype and input shape as the other
+ * members; device layout required in FI_LOAD_PER_MODEL).  Fails, leaving the DAG
+ * exactly as it was, with FI_EBUDGET when the new plan does not fit the loaded
+ * allocation (fi_build_opts.swap_headroom_bytes reserves room at load) or
+ * max_device_bytes, and with the fi_build_dag errors for a bad model. */
+fi_status fi_swap_model(fi_dag* dag, int32_t slot, const fi_model_spec* model, void* hip_stream);
 
 /* Synchronise, release the device allocation; the handle returns to BUILT. */
 fi_status fi_unload(fi_dag* dag);

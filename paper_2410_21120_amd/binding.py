@@ -45,7 +45,8 @@ class fi_build_opts(C.Structure):
     _fields_ = [("max_batch", C.c_int32), ("group_levels", C.c_int32), ("load_mode", C.c_int32),
                 ("use_graph", C.c_int32), ("serial_lanes", C.c_int32), ("reserved", C.c_int32),
                 ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
-                ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p)]
+                ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p),
+                ("swap_headroom_bytes", C.c_uint64)]
 
 
 class fi_dag_info(C.Structure):
@@ -53,7 +54,13 @@ class fi_dag_info(C.Structure):
                 ("device_bytes", C.c_uint64), ("macs_per_image", C.c_uint64), ("n_models", C.c_int32),
                 ("n_nodes", C.c_int32), ("n_levels", C.c_int32), ("n_launches", C.c_int32),
                 ("n_device_allocs", C.c_int32), ("n_h2d_copies", C.c_int32), ("state", C.c_int32),
-                ("n_lanes", C.c_int32)]
+                ("n_lanes", C.c_int32), ("device_capacity", C.c_uint64), ("last_h2d_bytes", C.c_uint64),
+                ("last_h2d_copies", C.c_int32), ("reserved", C.c_int32)]
+
+
+class fi_member_info(C.Structure):
+    _fields_ = [("arena_off", C.c_uint64), ("packed_bytes", C.c_uint64), ("lane", C.c_int32),
+                ("first_node", C.c_int32), ("n_nodes", C.c_int32), ("reserved", C.c_int32)]
 
 
 class fi_node_info(C.Structure):
@@ -71,8 +78,8 @@ class fi_launch_info(C.Structure):
 
 
 LIB_PATH = _build.OUT
-EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_query", "fi_node", "fi_launch", "fi_load",
-           "fi_run", "fi_profile", "fi_timeline", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
+EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
+           "fi_run", "fi_profile", "fi_timeline", "fi_swap_model", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
 
@@ -98,6 +105,8 @@ def lib():
         L.fi_run.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
         L.fi_profile.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), i32]
         L.fi_timeline.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32]
+        L.fi_swap_model.argtypes = [vp, i32, C.POINTER(fi_model_spec), vp]
+        L.fi_member.argtypes = [vp, i32, C.POINTER(fi_member_info)]
         L.fi_unload.argtypes = [vp]
         L.fi_destroy.argtypes = [vp]
         L.fi_destroy.restype = None
@@ -187,6 +196,16 @@ def fi_timeline(h, d_input_ptr, batch, d_output_ptrs, stream_ptr, n_launches):
     e = (C.c_float * n_launches)()
     _check(lib().fi_timeline(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr), b, e, n_launches), "fi_timeline")
     return list(b), list(e)
+
+
+def fi_swap_model(h, slot, spec, stream_ptr=0) -> None:
+    _check(lib().fi_swap_model(h, slot, C.byref(spec), C.c_void_p(stream_ptr)), "fi_swap_model")
+
+
+def fi_member(h, m):
+    info = fi_member_info()
+    _check(lib().fi_member(h, m, C.byref(info)), "fi_member")
+    return info
 
 
 def fi_unload(h) -> None:
@@ -291,12 +310,13 @@ class Dag:
     """Owner of one fi_dag handle."""
 
     def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
-                 max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False):
-        self.keepalive = (specs, keepalive, allocators)
+                 max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False, swap_headroom_bytes=0):
+        self.keepalive = [specs, keepalive, allocators]
         opts = fi_build_opts()
         opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
         opts.use_graph = int(use_graph)
         opts.serial_lanes = int(serial_lanes)
+        opts.swap_headroom_bytes = int(swap_headroom_bytes)
         if allocators is not None:
             allocators.apply(opts)
         self.opts = opts
@@ -312,8 +332,16 @@ class Dag:
     def launches(self):
         return [fi_launch(self.h, i) for i in range(self.query().n_launches)]
 
+    def members(self):
+        return [fi_member(self.h, m) for m in range(self.n_models)]
+
     def load(self, stream_ptr=0):
         fi_load(self.h, stream_ptr)
+
+    def swap_model(self, slot, spec, stream_ptr=0, keepalive=None):
+        """Replaces member `slot`; `keepalive` holds whatever backs the spec's borrowed pointers."""
+        fi_swap_model(self.h, slot, spec, stream_ptr)
+        self.keepalive.append((spec, keepalive))
 
     def run(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
         fi_run(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr)

@@ -47,6 +47,10 @@ struct fi_dag {
   uint64_t stage_off[2] = {fi::kNone, fi::kNone};  // staged input per activation dtype
   uint8_t* image = nullptr;           // pinned host image
   uint8_t* dev = nullptr;             // the one device allocation (LOADED only)
+  uint64_t dev_capacity = 0;          // its size: what the plan needed at load plus the swap headroom
+  uint64_t last_h2d_bytes = 0;        // bytes and copies of the most recent load or member swap
+  int32_t last_h2d_copies = 0;
+  hipEvent_t copy_done = nullptr;     // recorded after the latest copy out of the pinned image
   int32_t state = 0;
   uint64_t macs = 0;
   // captured launch schedule (use_graph): valid for exactly these call arguments
@@ -157,6 +161,24 @@ fi_status fi_model_pack(const fi_model_spec* model, void* dst, uint64_t dst_byte
   return FI_OK;
 }
 
+// Checks one member against the handle's common dtype / input shape and derives its layout.
+static fi_status analyze_member(const fi_build_opts& opts, Member& mb, int32_t m, const fi_model_spec* first) {
+  if (!mb.spec.weights) { set_error("model %d: no weights", m); return FI_EINVAL; }
+  fi_status st = analyze_model(mb.spec, mb.plan);
+  if (st != FI_OK) return st;
+  if (mb.spec.weights_packed && mb.spec.weight_bytes < mb.plan.packed_bytes) {
+    set_error("model %d: packed blob is %llu bytes, layout needs %llu", m, (unsigned long long)mb.spec.weight_bytes, (unsigned long long)mb.plan.packed_bytes);
+    return FI_EINVAL; }
+  if (opts.load_mode == FI_LOAD_PER_MODEL && !mb.spec.weights_packed) {
+    set_error("FI_LOAD_PER_MODEL needs members in device layout (fi_model_pack)"); return FI_EINVAL; }
+  if (first && (mb.spec.dtype != first->dtype || mb.spec.in_c != first->in_c || mb.spec.in_h != first->in_h || mb.spec.in_w != first->in_w)) {
+    set_error("model %d: members of one DAG share weight dtype and input shape", m); return FI_EINVAL; }
+  mb.arena_off = kNone;
+  return FI_OK;
+}
+
+static fi_status plan_dag(fi_dag* g);
+
 fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, fi_dag** out) {
   if (!models || n < 1 || !opts || !out) { set_error("null argument or no models"); return FI_EINVAL; }
   if (opts->max_batch < 1) { set_error("max_batch must be >= 1"); return FI_EINVAL; }
@@ -172,19 +194,39 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   for (int32_t m = 0; m < n; ++m) {
     Member& mb = g->members[(size_t)m];
     mb.spec = models[m];
-    if (!mb.spec.weights) { set_error("model %d: no weights", m); return FI_EINVAL; }
-    fi_status st = analyze_model(mb.spec, mb.plan);
+    const fi_status st = analyze_member(*opts, mb, m, m ? &models[0] : nullptr);
     if (st != FI_OK) return st;
-    if (mb.spec.weights_packed && mb.spec.weight_bytes < mb.plan.packed_bytes) {
-      set_error("model %d: packed blob is %llu bytes, layout needs %llu", m, (unsigned long long)mb.spec.weight_bytes, (unsigned long long)mb.plan.packed_bytes);
-      return FI_EINVAL; }
-    if (opts->load_mode == FI_LOAD_PER_MODEL && !mb.spec.weights_packed) {
-      set_error("FI_LOAD_PER_MODEL needs members in device layout (fi_model_pack)"); return FI_EINVAL; }
-    const fi_model_spec& a = models[0];
-    if (mb.spec.dtype != a.dtype || mb.spec.in_c != a.in_c || mb.spec.in_h != a.in_h || mb.spec.in_w != a.in_w) {
-      set_error("model %d: members of one DAG share weight dtype and input shape", m); return FI_EINVAL; }
   }
-  g->wdtype = models[0].dtype;
+  fi_status st = plan_dag(g.get());
+  if (st != FI_OK) return st;
+
+  // ---- pinned image: the bytes fi_load copies ----------------------------------------------
+  g->image_bytes = opts->load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;
+  g->image = static_cast<uint8_t*>(pin_alloc(*opts, (size_t)g->image_bytes));
+  if (!g->image) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)g->image_bytes); return FI_ENOMEM_HOST; }
+  std::memset(g->image, 0, (size_t)g->desc_bytes);
+  std::memcpy(g->image, "fusedinf-arena-1", 16);
+  if (opts->load_mode == FI_LOAD_ONE_COPY) {
+    for (const Member& mb : g->members) {
+      if (mb.spec.weights_packed) parallel_copy(g->image + mb.arena_off, static_cast<const uint8_t*>(mb.spec.weights), mb.plan.packed_bytes);
+      else pack_model(mb.spec, mb.plan, g->image + mb.arena_off);
+    }
+  }
+  *out = g.release();
+  return FI_OK;
+}
+
+// Everything derived from the member list: union graph, levels, lanes, kernels and tiles, launch
+// schedule, activation plan, weight arena placement, workspace, descriptors.  Members whose
+// arena_off is already set keep their place in the weight arena (their bytes may be resident);
+// the others go to the lowest gap that holds them.
+static fi_status plan_dag(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  g->nodes.clear(); g->launches.clear(); g->descs.clear();
+  g->n_levels = 0; g->macs = 0; g->n_lanes = 1;
+  g->stage_off[0] = g->stage_off[1] = kNone;
+  g->wdtype = g->members[0].spec.dtype;
 
   // ---- union of the member graphs (no edge between members) and depth levels --------
   int32_t total = 0;
@@ -402,9 +444,22 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   for (Launch& L : g->launches) { L.first_desc = (int32_t)n_desc; if (L.kind == K_STAGE) L.n = 1; n_desc += (size_t)L.n; }
   g->descs.assign(n_desc, Desc{});
   g->desc_bytes = kAlign;  // arena header; problem descriptors travel as launch arguments
-  uint64_t off = g->desc_bytes;
-  for (Member& mb : g->members) { mb.arena_off = off; off += mb.plan.packed_bytes; }
-  g->arena_bytes = off;
+  {
+    std::vector<std::pair<uint64_t, uint64_t>> used;   // resident members, in address order
+    for (const Member& mb : g->members)
+      if (mb.arena_off != kNone) used.emplace_back(mb.arena_off, mb.arena_off + mb.plan.packed_bytes);
+    for (Member& mb : g->members) {
+      if (mb.arena_off != kNone) continue;
+      std::sort(used.begin(), used.end());
+      uint64_t off = g->desc_bytes;
+      for (const auto& u : used) { if (off + mb.plan.packed_bytes <= u.first) break; off = std::max(off, u.second); }
+      mb.arena_off = off;
+      used.emplace_back(off, off + mb.plan.packed_bytes);
+    }
+    uint64_t top = g->desc_bytes;
+    for (const auto& u : used) top = std::max(top, u.second);
+    g->arena_bytes = align_up(top);
+  }
   for (Node& nd : g->nodes) {
     const Member& mb = g->members[(size_t)nd.model];
     nd.w_off = nd.w_rel == kNone ? kNone : mb.arena_off + nd.w_rel;
@@ -489,19 +544,6 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
     for (int32_t s = 0; s < L.n; ++s) g->descs[(size_t)(L.first_desc + s)].vec = vec ? 1 : 0;
   }
 
-  // ---- pinned image: the bytes fi_load copies ----------------------------------------------
-  g->image_bytes = opts->load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;
-  g->image = static_cast<uint8_t*>(pin_alloc(*opts, (size_t)g->image_bytes));
-  if (!g->image) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)g->image_bytes); return FI_ENOMEM_HOST; }
-  std::memset(g->image, 0, (size_t)g->desc_bytes);
-  std::memcpy(g->image, "fusedinf-arena-1", 16);
-  if (opts->load_mode == FI_LOAD_ONE_COPY) {
-    for (const Member& mb : g->members) {
-      if (mb.spec.weights_packed) parallel_copy(g->image + mb.arena_off, static_cast<const uint8_t*>(mb.spec.weights), mb.plan.packed_bytes);
-      else pack_model(mb.spec, mb.plan, g->image + mb.arena_off);
-    }
-  }
-  *out = g.release();
   return FI_OK;
 }
 
@@ -516,6 +558,9 @@ fi_status fi_query(const fi_dag* g, fi_dag_info* info) {
   info->n_h2d_copies = g->opts.load_mode == FI_LOAD_ONE_COPY ? 1 : 1 + (int32_t)g->members.size();
   info->state = g->state;
   info->n_lanes = g->n_lanes;
+  info->device_capacity = g->dev_capacity;
+  info->last_h2d_bytes = g->last_h2d_bytes;
+  info->last_h2d_copies = g->last_h2d_copies;
   return FI_OK;
 }
 
@@ -530,6 +575,15 @@ fi_status fi_node(const fi_dag* g, int32_t i, fi_node_info* o) {
   return FI_OK;
 }
 
+fi_status fi_member(const fi_dag* g, int32_t m, fi_member_info* o) {
+  if (!g || !o || m < 0 || m >= (int32_t)g->members.size()) { set_error("bad member index"); return FI_EINVAL; }
+  const Member& mb = g->members[(size_t)m];
+  std::memset(o, 0, sizeof(*o));
+  o->arena_off = mb.arena_off; o->packed_bytes = mb.plan.packed_bytes;
+  o->lane = mb.lane; o->first_node = mb.node0; o->n_nodes = (int32_t)mb.plan.nodes.size();
+  return FI_OK;
+}
+
 fi_status fi_launch(const fi_dag* g, int32_t i, fi_launch_info* o) {
   if (!g || !o || i < 0 || i >= (int32_t)g->launches.size()) { set_error("bad launch index"); return FI_EINVAL; }
   const Launch& L = g->launches[(size_t)i];
@@ -541,38 +595,47 @@ fi_status fi_launch(const fi_dag* g, int32_t i, fi_launch_info* o) {
   return FI_OK;
 }
 
+// internal streams (default priority) and events for the concurrent lanes; all or nothing
+static void ensure_lanes(fi_dag* g) {
+  while ((int32_t)g->lane_streams.size() < g->n_lanes - 1) {
+    hipStream_t ls = nullptr;
+    if (hipStreamCreateWithFlags(&ls, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); return; }
+    g->lane_streams.push_back(ls);
+  }
+  while ((int32_t)g->lane_events.size() < g->n_lanes) {
+    hipEvent_t ev = nullptr;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); return; }
+    g->lane_events.push_back(ev);
+  }
+}
+
 fi_status fi_load(fi_dag* g, void* stream) {
   if (!g) { set_error("null handle"); return FI_EINVAL; }
   if (g->state != 0) { set_error("fi_load: handle is already loaded"); return FI_ESTATE; }
+  const uint64_t want = g->device_bytes + g->opts.swap_headroom_bytes;
   uint8_t* d = nullptr;
-  if (g->opts.dev_alloc) d = static_cast<uint8_t*>(g->opts.dev_alloc((size_t)g->device_bytes, g->opts.user));
-  else if (hipMalloc(reinterpret_cast<void**>(&d), (size_t)g->device_bytes) != hipSuccess) { (void)hipGetLastError(); d = nullptr; }
-  if (!d) { set_error("device allocation of %llu bytes failed", (unsigned long long)g->device_bytes); return FI_ENOMEM_DEVICE; }
+  if (g->opts.dev_alloc) d = static_cast<uint8_t*>(g->opts.dev_alloc((size_t)want, g->opts.user));
+  else if (hipMalloc(reinterpret_cast<void**>(&d), (size_t)want) != hipSuccess) { (void)hipGetLastError(); d = nullptr; }
+  if (!d) { set_error("device allocation of %llu bytes failed", (unsigned long long)want); return FI_ENOMEM_DEVICE; }
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipMemcpyAsync(d, g->image, (size_t)g->image_bytes, hipMemcpyHostToDevice, s);
+  g->last_h2d_bytes = g->image_bytes; g->last_h2d_copies = 1;
   if (e == hipSuccess && g->opts.load_mode == FI_LOAD_PER_MODEL)
     for (const Member& mb : g->members) {
       e = hipMemcpyAsync(d + mb.arena_off, mb.spec.weights, (size_t)mb.plan.packed_bytes, hipMemcpyHostToDevice, s);
       if (e != hipSuccess) break;
+      g->last_h2d_bytes += mb.plan.packed_bytes; ++g->last_h2d_copies;
     }
   if (e != hipSuccess) {
     set_error("hipMemcpyAsync: %s", hipGetErrorString(e));
     if (g->opts.dev_free) g->opts.dev_free(d, g->opts.user); else (void)hipFree(d);
     return FI_EHIP;
   }
-  // internal streams (default priority) and events for the concurrent lanes
-  for (int32_t l = 1; l < g->n_lanes; ++l) {
-    hipStream_t ls = nullptr;
-    if (hipStreamCreateWithFlags(&ls, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); break; }
-    g->lane_streams.push_back(ls);
-  }
-  if ((int32_t)g->lane_streams.size() == g->n_lanes - 1)
-    for (int32_t l = 0; l < g->n_lanes; ++l) {
-      hipEvent_t ev = nullptr;
-      if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); break; }
-      g->lane_events.push_back(ev);
-    }
+  if (!g->copy_done && hipEventCreateWithFlags(&g->copy_done, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); g->copy_done = nullptr; }
+  if (g->copy_done) (void)hipEventRecord(g->copy_done, s);
+  ensure_lanes(g);
   g->dev = d;
+  g->dev_capacity = want;
   g->state = 1;
   return FI_OK;
 }
@@ -608,13 +671,13 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   // Lanes: after the shared input is staged on the caller's stream the internal streams fork from
   // it, every launch goes to its lane's stream, and the caller's stream joins them at the end.
   const bool lanes = !ms && !g->opts.use_graph && g->n_lanes > 1 &&
-                     (int32_t)g->lane_streams.size() == g->n_lanes - 1 && (int32_t)g->lane_events.size() == g->n_lanes;
+                     (int32_t)g->lane_streams.size() >= g->n_lanes - 1 && (int32_t)g->lane_events.size() >= g->n_lanes;
   bool forked = false;
   for (size_t i = 0; i < nl; ++i) {
     const Launch& L = g->launches[i];
     if (lanes && !forked && L.level > 0) {
       (void)hipEventRecord(g->lane_events[0], s);
-      for (hipStream_t ls : g->lane_streams) (void)hipStreamWaitEvent(ls, g->lane_events[0], 0);
+      for (int32_t l = 1; l < g->n_lanes; ++l) (void)hipStreamWaitEvent(g->lane_streams[(size_t)l - 1], g->lane_events[0], 0);
       forked = true;
     }
     hipStream_t ls = (lanes && L.lane > 0) ? g->lane_streams[(size_t)L.lane - 1] : s;
@@ -701,6 +764,64 @@ fi_status fi_timeline(fi_dag* g, const void* d_input, int32_t batch, void* const
   return run_impl(g, d_input, batch, d_outputs, stream, nullptr, n, begin_ms, end_ms);
 }
 
+fi_status fi_swap_model(fi_dag* g, int32_t slot, const fi_model_spec* model, void* stream) {
+  if (!g || !model) { set_error("null argument"); return FI_EINVAL; }
+  if (slot < 0 || slot >= (int32_t)g->members.size()) { set_error("slot %d outside [0, %zu)", slot, g->members.size()); return FI_EINVAL; }
+  // Plan on a scratch handle: a failure leaves the DAG as it was.  The other members keep their
+  // arena offsets (their weights stay where they are); the newcomer takes the lowest gap that holds it.
+  fi_dag t;
+  t.opts = g->opts;
+  t.members = g->members;
+  Member& nm = t.members[(size_t)slot];
+  nm = Member{};
+  nm.spec = *model;
+  const fi_model_spec* first = g->members.size() > 1 ? &g->members[slot == 0 ? 1 : 0].spec : nullptr;
+  fi_status st = analyze_member(t.opts, nm, slot, first);
+  if (st != FI_OK) return st;
+  st = plan_dag(&t);
+  if (st != FI_OK) return st;
+  if (g->state == 1 && t.device_bytes > g->dev_capacity) {
+    set_error("after the swap the DAG needs %llu device bytes, the loaded allocation holds %llu (unload and rebuild, or load with more swap_headroom_bytes)",
+              (unsigned long long)t.device_bytes, (unsigned long long)g->dev_capacity);
+    return FI_EBUDGET;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Member& placed = t.members[(size_t)slot];
+  const uint8_t* src = static_cast<const uint8_t*>(placed.spec.weights);
+  if (g->opts.load_mode == FI_LOAD_ONE_COPY) {
+    // the pinned image stays the exact image of the arena; copies out of it must have finished
+    if (g->copy_done) (void)hipEventSynchronize(g->copy_done);
+    if (t.arena_bytes > g->image_bytes) {
+      uint8_t* bigger = static_cast<uint8_t*>(pin_alloc(g->opts, (size_t)t.arena_bytes));
+      if (!bigger) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)t.arena_bytes); return FI_ENOMEM_HOST; }
+      parallel_copy(bigger, g->image, g->image_bytes);
+      pin_free(g->opts, g->image);
+      g->image = bigger;
+      g->image_bytes = t.arena_bytes;
+    }
+    if (placed.spec.weights_packed) parallel_copy(g->image + placed.arena_off, src, placed.plan.packed_bytes);
+    else pack_model(placed.spec, placed.plan, g->image + placed.arena_off);
+    src = g->image + placed.arena_off;
+  }
+  if (g->state == 1) {
+    const hipError_t e = hipMemcpyAsync(g->dev + placed.arena_off, src, (size_t)placed.plan.packed_bytes, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) { set_error("hipMemcpyAsync: %s", hipGetErrorString(e)); return FI_EHIP; }
+    if (g->copy_done) (void)hipEventRecord(g->copy_done, s);
+    g->last_h2d_bytes = placed.plan.packed_bytes; g->last_h2d_copies = 1;
+  }
+  drop_graph(g);
+  g->members = std::move(t.members);
+  g->nodes = std::move(t.nodes);
+  g->launches = std::move(t.launches);
+  g->descs = std::move(t.descs);
+  g->n_levels = t.n_levels; g->wdtype = t.wdtype; g->macs = t.macs; g->n_lanes = t.n_lanes;
+  g->desc_bytes = t.desc_bytes; g->arena_bytes = t.arena_bytes; g->act_bytes = t.act_bytes;
+  g->workspace_bytes = t.workspace_bytes; g->device_bytes = t.device_bytes;
+  g->stage_off[0] = t.stage_off[0]; g->stage_off[1] = t.stage_off[1];
+  if (g->state == 1) ensure_lanes(g);
+  return FI_OK;
+}
+
 fi_status fi_unload(fi_dag* g) {
   if (!g) { set_error("null handle"); return FI_EINVAL; }
   if (g->state != 1) { set_error("fi_unload: handle is not loaded"); return FI_ESTATE; }
@@ -710,8 +831,10 @@ fi_status fi_unload(fi_dag* g) {
   for (hipEvent_t ev : g->lane_events) (void)hipEventDestroy(ev);
   g->lane_streams.clear();
   g->lane_events.clear();
+  if (g->copy_done) { (void)hipEventDestroy(g->copy_done); g->copy_done = nullptr; }
   if (g->opts.dev_free) g->opts.dev_free(g->dev, g->opts.user); else (void)hipFree(g->dev);
   g->dev = nullptr;
+  g->dev_capacity = 0;
   g->state = 0;
   return FI_OK;
 }

@@ -23,7 +23,8 @@ def rel_l2(a, ref):
 class GpuDag:
     """Builds one fused DAG from (model, blob[, act_dtype]) members and runs it."""
 
-    def __init__(self, members, max_batch, group_levels=True, load_mode=fi.FI_LOAD_ONE_COPY, packed=False, use_graph=False, serial_lanes=False):
+    def __init__(self, members, max_batch, group_levels=True, load_mode=fi.FI_LOAD_ONE_COPY, packed=False, use_graph=False, serial_lanes=False,
+                 swap_headroom_bytes=0):
         import torch
         self.torch = torch
         self.alloc = fi.TorchAllocators("cuda:0")
@@ -36,7 +37,8 @@ class GpuDag:
             specs.append(spec)
             keep.append((k, blob))
         self.dag = fi.Dag(specs, max_batch, self.alloc, group_levels=group_levels, load_mode=load_mode, keepalive=keep,
-                          use_graph=use_graph, serial_lanes=serial_lanes)
+                          use_graph=use_graph, serial_lanes=serial_lanes, swap_headroom_bytes=swap_headroom_bytes)
+        self.packed = packed
         self.side = torch.cuda.Stream() if use_graph else None  # graph capture needs a non-default stream
         self.stream = self.side.cuda_stream if use_graph else torch.cuda.current_stream().cuda_stream
         self.dag.load(self.stream)
@@ -74,6 +76,16 @@ class GpuDag:
         torch.cuda.synchronize()
         res = [o.cpu().numpy() for o in outs]
         return (res, ms) if profile else res
+
+    def swap(self, slot, member):
+        """Replaces member `slot` by (model, blob[, act_dtype]) through fi_swap_model."""
+        model, blob = member[0], member[1]
+        act = member[2] if len(member) > 2 else None
+        spec, k = fi.make_spec(model, blob.ctypes.data, blob.nbytes, act_dtype=act, packed=self.packed)
+        self.dag.swap_model(slot, spec, self.stream, keepalive=(k, blob))
+        self.models[slot] = model
+        self.out_elems[slot] = model.layers[model.output].cout * model.layers[model.output].out_h * model.layers[model.output].out_w
+        self.keep_buffers = None
 
     def close(self):
         self.dag.unload()

@@ -1,0 +1,120 @@
+"""Individual model swaps inside a loaded DAG (Section V, "individual model swaps in a DAG",
+Table IV) on the GPU, through the C-ABI: after every swap each member's output equals, bit for
+bit, that of a freshly built and loaded DAG of the same member set; members that stayed keep
+their bits; the newcomer meets the oracle tolerance; only the newcomer's weights are copied."""
+import numpy as np
+import pytest
+
+from workloads import gen, zoo
+
+pytestmark = pytest.mark.gpu
+
+HW = 64
+
+
+def _member(fam, seed, act=None):
+    m = zoo.FAMILIES[fam](hw=HW)
+    return (m, gen.make_blob(m, seed), act)
+
+
+def _fresh(mem, x, **kw):
+    from tests import harness
+    g = harness.GpuDag(mem, x.shape[0], **kw)
+    try:
+        return g.run(x)
+    finally:
+        g.close()
+
+
+def _check_oracle(member, y, x):
+    from tests import harness
+    m, blob, act = member
+    ref = harness.oracle_nhwc(m, blob, x, False)
+    assert harness.rel_l2(y, ref) <= (1e-4 if act == "f32" else 1e-2)
+
+
+def test_chain_of_swaps_matches_fresh_builds_bitwise():
+    from tests import harness
+    x = gen.make_input(7, 3, 3, HW, HW, "normal", "bf16")
+    mem = [_member("resnet18", 1000), _member("vgg16", 1001), _member("mobilenetv2", 1002, "f32"), _member("resnet18", 1003)]
+    swaps = [(1, _member("resnet50", 2001)),            # large -> smaller: reuses the gap
+             (2, _member("resnet18", 2002)),             # fp32-activation member -> bf16 member
+             (0, _member("vgg16", 2003)),                # small -> large: placed past the others
+             (3, _member("resnet18", 2004)),             # same architecture, other weights
+             (1, _member("mobilenetv2", 2005, "f32"))]
+    g = harness.GpuDag(mem, 3, swap_headroom_bytes=256 << 20)
+    try:
+        prev = g.run(x)
+        assert all(np.array_equal(a, b) for a, b in zip(prev, _fresh(mem, x)))
+        for slot, newcomer in swaps:
+            stay = {i: g.dag.members()[i].arena_off for i in range(len(mem)) if i != slot}
+            g.swap(slot, newcomer)
+            mem[slot] = newcomer
+            q = g.dag.query()
+            info = g.dag.members()
+            assert q.last_h2d_copies == 1 and q.last_h2d_bytes == info[slot].packed_bytes
+            assert all(info[i].arena_off == off for i, off in stay.items())
+            got = g.run(x)
+            fresh = _fresh(mem, x)
+            for i in range(len(mem)):
+                assert np.array_equal(got[i], fresh[i]), f"member {i} after swapping slot {slot}"
+                if i != slot:
+                    assert np.array_equal(got[i], prev[i]), f"member {i} moved when slot {slot} was swapped"
+            _check_oracle(newcomer, got[slot], x)
+            prev = got
+        # the pinned image is still the exact image of the arena: unload, load, same bits
+        g.dag.unload()
+        g.dag.load(g.stream)
+        assert all(np.array_equal(a, b) for a, b in zip(g.run(x), prev))
+    finally:
+        g.close()
+
+
+def test_swap_with_packed_members_and_per_model_copies():
+    import torch
+    import paper_2410_21120_amd as fi
+    from tests import harness
+    x = gen.make_input(7, 2, 3, HW, HW, "normal", "bf16")
+
+    def packed(member):
+        m, blob, act = member
+        spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        n = fi.fi_model_packed_size(spec)
+        buf = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+        fi.fi_model_pack(spec, buf.data_ptr(), n)
+        return (m, buf.numpy(), act)
+
+    canon = [_member("resnet18", 1000), _member("mobilenetv2", 1001, "f32"), _member("resnet50", 1002)]
+    newcomer = _member("vgg16", 3001)
+    g = harness.GpuDag([packed(c) for c in canon], 2, load_mode=fi.FI_LOAD_PER_MODEL, packed=True, swap_headroom_bytes=128 << 20)
+    try:
+        base = g.run(x)
+        g.swap(1, packed(newcomer))
+        got = g.run(x)
+    finally:
+        g.close()
+    fresh = _fresh([canon[0], newcomer, canon[2]], x)
+    assert all(np.array_equal(a, b) for a, b in zip(got, fresh))
+    assert np.array_equal(got[0], base[0]) and np.array_equal(got[2], base[2])
+    _check_oracle(newcomer, got[1], x)
+
+
+def test_swap_that_does_not_fit_is_refused_and_the_dag_still_runs():
+    import paper_2410_21120_amd as fi
+    from tests import harness
+    x = gen.make_input(7, 2, 3, HW, HW, "normal", "bf16")
+    mem = [_member("resnet18", 1000), _member("mobilenetv2", 1001)]
+    g = harness.GpuDag(mem, 2)                       # no headroom
+    try:
+        base = g.run(x)
+        with pytest.raises(fi.FiError) as e:
+            g.swap(1, _member("vgg16", 3002))
+        assert e.value.status == fi.FI_EBUDGET
+        g.models[1] = mem[1][0]
+        again = g.run(x)
+        assert all(np.array_equal(a, b) for a, b in zip(again, base))
+        g.swap(1, _member("mobilenetv2", 3003))      # same size: fits without headroom
+        got = g.run(x)
+        assert np.array_equal(got[0], base[0]) and not np.array_equal(got[1], base[1])
+    finally:
+        g.close()

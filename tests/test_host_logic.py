@@ -274,3 +274,66 @@ def test_large_family_is_halved_into_two_lanes():
     assert small.query().n_lanes == 1
     ser, _, _ = _build(["resnet18"] * 4, 256, serial_lanes=True)
     assert ser.query().n_lanes == 1
+
+
+def test_swap_model_replans_without_moving_the_other_members():
+    """Individual model swap (Section V, Table IV): the other members keep their arena offsets, the
+    newcomer takes the lowest gap that holds it, and the schedule is that of a fresh build of the
+    new member set (same nodes, levels and launch count)."""
+    d, models, _ = _build(["resnet18", "vgg16", "mobilenetv2"], 2)
+    before = d.members()
+    m_new = zoo.FAMILIES["resnet18"](hw=64)
+    blob = gen.make_blob(m_new, 77)
+    spec, keep = fi.make_spec(m_new, blob.ctypes.data, blob.nbytes)
+    d.swap_model(1, spec, keepalive=(keep, blob))      # vgg16 (large) -> resnet18 (smaller): fits the gap
+    after = d.members()
+    assert (after[0].arena_off, after[2].arena_off) == (before[0].arena_off, before[2].arena_off)
+    assert after[1].arena_off == before[1].arena_off and after[1].packed_bytes < before[1].packed_bytes
+    fresh, _, _ = _build(["resnet18", "resnet18", "mobilenetv2"], 2)
+    qa, qb = d.query(), fresh.query()
+    assert (qa.n_nodes, qa.n_levels, qa.n_launches, qa.n_lanes, qa.act_bytes, qa.macs_per_image) == \
+           (qb.n_nodes, qb.n_levels, qb.n_launches, qb.n_lanes, qb.act_bytes, qb.macs_per_image)
+    assert qa.arena_bytes >= qb.arena_bytes          # the gap the larger member left is still inside the arena
+    for na, nb in zip(d.nodes(), fresh.nodes()):
+        assert (na.model, na.index, na.op, na.level, na.out_off) == (nb.model, nb.index, nb.op, nb.level, nb.out_off)
+    # a larger newcomer does not fit the gap: it goes past the last member and the arena grows
+    big = zoo.FAMILIES["vgg16"](hw=64)
+    bblob = gen.make_blob(big, 78)
+    bspec, bkeep = fi.make_spec(big, bblob.ctypes.data, bblob.nbytes)
+    d.swap_model(0, bspec, keepalive=(bkeep, bblob))
+    again = d.members()
+    assert again[1].arena_off == after[1].arena_off and again[2].arena_off == after[2].arena_off
+    spans = sorted((m.arena_off, m.arena_off + m.packed_bytes) for m in again)
+    assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+    assert d.query().arena_bytes >= spans[-1][1]
+
+
+def test_swap_model_errors_leave_the_dag_unchanged():
+    d, _, _ = _build(["resnet18", "resnet18"], 2)
+    q0 = d.query()
+    off0 = [(m.arena_off, m.packed_bytes) for m in d.members()]
+    other = zoo.FAMILIES["resnet18"](hw=32)            # different input shape
+    blob = gen.make_blob(other, 5)
+    spec, keep = fi.make_spec(other, blob.ctypes.data, blob.nbytes)
+    with pytest.raises(fi.FiError) as e:
+        d.swap_model(0, spec, keepalive=(keep, blob))
+    assert e.value.status == fi.FI_EINVAL
+    ok = zoo.FAMILIES["resnet18"](hw=64)
+    okb = gen.make_blob(ok, 6)
+    okspec, okkeep = fi.make_spec(ok, okb.ctypes.data, okb.nbytes)
+    for bad_slot in (-1, 2):
+        with pytest.raises(fi.FiError) as e:
+            d.swap_model(bad_slot, okspec, keepalive=(okkeep, okb))
+        assert e.value.status == fi.FI_EINVAL
+    q1 = d.query()
+    assert (q1.n_nodes, q1.n_launches, q1.arena_bytes, q1.act_bytes) == (q0.n_nodes, q0.n_launches, q0.arena_bytes, q0.act_bytes)
+    assert [(m.arena_off, m.packed_bytes) for m in d.members()] == off0
+    # a budget that the larger member set would exceed: FI_EBUDGET, nothing changes
+    tight, _, _ = _build(["resnet18", "resnet18"], 2, max_device_bytes=q0.device_bytes + 4096)
+    big = zoo.FAMILIES["vgg16"](hw=64)
+    bb = gen.make_blob(big, 9)
+    bspec, bkeep = fi.make_spec(big, bb.ctypes.data, bb.nbytes)
+    with pytest.raises(fi.FiError) as e:
+        tight.swap_model(1, bspec, keepalive=(bkeep, bb))
+    assert e.value.status == fi.FI_EBUDGET
+    assert tight.query().n_nodes == q0.n_nodes
