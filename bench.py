@@ -380,7 +380,29 @@ def swap_churn(fi, torch, gen, zoo, alloc, stream, n_req):
         serve(members, bi, [o.data_ptr() for o in outs], fi.FI_LOAD_PER_MODEL)
         open_lat.append(time.perf_counter() - t_start - (t_arr - reqs[0][0]))
     lat["fused_per_model_copies_open_loop_50rps"] = open_lat
-    out = {"requests": len(reqs), "mean_arena_mb": float(np.mean(arena)) / 1e6,
+    # ---- manager batching + round-robin scheduler over the whole pool (Section IV) ----------------
+    # The 16 models do not get the device at once: batches of at most a quarter of the pool's footprint,
+    # 20 iterations per DAG, 2 rounds; fused batches with and without the overlapped load, against one
+    # model per DAG ("without fusion": same scheduler, 16 batches).
+    all_specs = [spec_of(mi) for mi in range(16)]
+    rr_specs, rr_keep = [a for a, _ in all_specs], [b for _, b in all_specs]
+    rr_opts = fi.make_opts(8, alloc, load_mode=fi.FI_LOAD_PER_MODEL)
+    rr_outs = [torch.zeros((8, 1000), dtype=torch.float32, device="cuda:0") for _ in range(16)]
+    rr_ptrs = [o.data_ptr() for o in rr_outs]
+    whole = fi.fi_footprint(rr_specs, rr_opts).device_bytes
+    largest = max(fi.fi_footprint([sp], rr_opts).device_bytes for sp in rr_specs)
+    budget = max(whole // 4, largest)
+    group_of, n_groups = fi.fi_partition(rr_specs, rr_opts, budget)
+    rr = {"budget_bytes": budget, "pool_bytes": whole, "batches": n_groups, "iterations": 20, "rounds": 2}
+    for name, grp, ng, ov in (("fused_overlapped_load", group_of, n_groups, True), ("fused", group_of, n_groups, False),
+                              ("one_model_per_dag", list(range(16)), 16, False), ("one_model_per_dag_overlapped_load", list(range(16)), 16, True)):
+        torch.cuda.synchronize()
+        st = fi.fi_round_robin(rr_specs, rr_opts, grp, ng, 20, 2, ov, xs[0].data_ptr(), 8, rr_ptrs, stream)
+        rr[name] = dict(total_ms=st.total_ms, run_ms=st.run_ms, swap_ms=st.swap_ms, build_ms=st.build_ms,
+                        peak_device_bytes=st.peak_device_bytes, loads=st.n_loads, runs=st.n_runs)
+    del rr_keep
+
+    out = {"requests": len(reqs), "mean_arena_mb": float(np.mean(arena)) / 1e6, "round_robin": rr,
            "member_swaps": dict(swaps=swapped, per_request=swapped / len(reqs), mean_h2d_mb_per_request=moved / len(reqs) / 1e6,
                                 rebuild_fallbacks=fallbacks)}
     for k, v in lat.items():

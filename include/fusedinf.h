@@ -181,6 +181,12 @@ fi_status fi_node(const fi_dag* dag, int32_t i, fi_node_info* info);     /* i in
 fi_status fi_launch(const fi_dag* dag, int32_t i, fi_launch_info* info); /* i in [0, n_launches) */
 fi_status fi_member(const fi_dag* dag, int32_t m, fi_member_info* info); /* m in [0, n_models) */
 
+/* The footprint fi_build_dag would report for these members (Section IV: the
+ * repository knows every model's memory requirement, the manager sizes DAGs by
+ * it), computed from the architectures alone: no pinned image is made and no
+ * weight byte is read.  Same errors as fi_build_dag. */
+fi_status fi_footprint(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, fi_dag_info* info);
+
 /* Load: one device allocation, one pinned-to-device copy of the weight arena
  * (asynchronous on hip_stream; hip_stream is a hipStream_t, NULL = default stream). */
 fi_status fi_load(fi_dag* dag, void* hip_stream);
@@ -224,6 +230,47 @@ fi_status fi_timeline(fi_dag* dag, const void* d_input, int32_t batch, void* con
  * allocation (fi_build_opts.swap_headroom_bytes reserves room at load) or
  * max_device_bytes, and with the fi_build_dag errors for a bad model. */
 fi_status fi_swap_model(fi_dag* dag, int32_t slot, const fi_model_spec* model, void* hip_stream);
+
+/* ---- manager-side scheduling (Section IV, "Manager"; Section V, consecutive swaps) ----
+ * A set of models that does not fit the device at once is cut into batches that
+ * each fit; every batch is compiled into its own DAG; the scheduler runs a fixed
+ * number of iterations per DAG, swaps it out and takes the next, round robin. */
+
+/* Batches in the caller's order, first fit: model m joins the current batch while
+ * the batch's exact device footprint (fi_footprint) stays within budget_bytes.
+ * group_of: host, n entries out (batch index of every model, non-decreasing);
+ * n_groups: out.  FI_EBUDGET when a single model exceeds the budget. */
+fi_status fi_partition(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, uint64_t budget_bytes,
+                       int32_t* group_of, int32_t* n_groups);
+
+typedef struct {
+  int32_t iterations;   /* fi_run passes per DAG before it is swapped out (>= 1) */
+  int32_t rounds;       /* round-robin rounds over all batches (>= 1) */
+  int32_t overlap_load; /* 1: the next batch is loaded on an internal copy stream while the current one
+                           computes, so two batches are resident at a time; 0: unload, then load */
+  int32_t reserved;
+} fi_sched_opts;
+
+typedef struct {
+  double build_ms;            /* compiling every batch (host, once) */
+  double total_ms;            /* all rounds: loads, runs, unloads */
+  double run_ms;              /* time spent waiting for the runs of a batch (incl. a load still in flight) */
+  double swap_ms;             /* time spent in unload (+ the next load when not overlapped) */
+  uint64_t peak_device_bytes; /* largest resident footprint (two batches with overlap_load) */
+  int32_t n_loads, n_runs, n_groups, reserved;
+} fi_sched_stats;
+
+/* Compiles one DAG per batch (group_of as produced by fi_partition; any grouping
+ * with every batch non-empty is accepted), then for `rounds` rounds visits the
+ * batches in order: load, `iterations` x fi_run on hip_stream with the shared
+ * d_input (device, as for fi_run), unload.  d_outputs: HOST array of n DEVICE
+ * pointers indexed like `models`; model m's buffer holds the output of its last
+ * run on return.  A single batch stays resident for all rounds.  With
+ * opts->max_device_bytes set, FI_EBUDGET if the resident peak would exceed it.
+ * Synchronous: returns after the last unload.  stats may be NULL. */
+fi_status fi_round_robin(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, const int32_t* group_of,
+                         int32_t n_groups, const fi_sched_opts* sched, const void* d_input, int32_t batch,
+                         void* const* d_outputs, void* hip_stream, fi_sched_stats* stats);
 
 /* Synchronise, release the device allocation; the handle returns to BUILT. */
 fi_status fi_unload(fi_dag* dag);

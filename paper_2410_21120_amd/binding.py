@@ -58,6 +58,16 @@ class fi_dag_info(C.Structure):
                 ("last_h2d_copies", C.c_int32), ("reserved", C.c_int32)]
 
 
+class fi_sched_opts(C.Structure):
+    _fields_ = [("iterations", C.c_int32), ("rounds", C.c_int32), ("overlap_load", C.c_int32), ("reserved", C.c_int32)]
+
+
+class fi_sched_stats(C.Structure):
+    _fields_ = [("build_ms", C.c_double), ("total_ms", C.c_double), ("run_ms", C.c_double), ("swap_ms", C.c_double),
+                ("peak_device_bytes", C.c_uint64), ("n_loads", C.c_int32), ("n_runs", C.c_int32),
+                ("n_groups", C.c_int32), ("reserved", C.c_int32)]
+
+
 class fi_member_info(C.Structure):
     _fields_ = [("arena_off", C.c_uint64), ("packed_bytes", C.c_uint64), ("lane", C.c_int32),
                 ("first_node", C.c_int32), ("n_nodes", C.c_int32), ("reserved", C.c_int32)]
@@ -78,7 +88,7 @@ class fi_launch_info(C.Structure):
 
 
 LIB_PATH = _build.OUT
-EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
+EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_footprint", "fi_partition", "fi_round_robin", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
            "fi_run", "fi_profile", "fi_timeline", "fi_swap_model", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
@@ -105,6 +115,10 @@ def lib():
         L.fi_run.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
         L.fi_profile.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), i32]
         L.fi_timeline.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32]
+        L.fi_footprint.argtypes = [C.POINTER(fi_model_spec), i32, C.POINTER(fi_build_opts), C.POINTER(fi_dag_info)]
+        L.fi_partition.argtypes = [C.POINTER(fi_model_spec), i32, C.POINTER(fi_build_opts), C.c_uint64, C.POINTER(i32), C.POINTER(i32)]
+        L.fi_round_robin.argtypes = [C.POINTER(fi_model_spec), i32, C.POINTER(fi_build_opts), C.POINTER(i32), i32,
+                                     C.POINTER(fi_sched_opts), vp, i32, C.POINTER(vp), vp, C.POINTER(fi_sched_stats)]
         L.fi_swap_model.argtypes = [vp, i32, C.POINTER(fi_model_spec), vp]
         L.fi_member.argtypes = [vp, i32, C.POINTER(fi_member_info)]
         L.fi_unload.argtypes = [vp]
@@ -154,6 +168,45 @@ def fi_build_dag(specs, opts: fi_build_opts) -> int:
     h = C.c_void_p(0)
     _check(lib().fi_build_dag(arr, len(specs), C.byref(opts), C.byref(h)), "fi_build_dag")
     return h.value
+
+
+def fi_footprint(specs, opts: fi_build_opts) -> fi_dag_info:
+    arr = (fi_model_spec * len(specs))(*specs)
+    info = fi_dag_info()
+    _check(lib().fi_footprint(arr, len(specs), C.byref(opts), C.byref(info)), "fi_footprint")
+    return info
+
+
+def fi_partition(specs, opts: fi_build_opts, budget_bytes):
+    arr = (fi_model_spec * len(specs))(*specs)
+    group_of = (C.c_int32 * len(specs))()
+    n_groups = C.c_int32(0)
+    _check(lib().fi_partition(arr, len(specs), C.byref(opts), budget_bytes, group_of, C.byref(n_groups)), "fi_partition")
+    return list(group_of), n_groups.value
+
+
+def fi_round_robin(specs, opts: fi_build_opts, group_of, n_groups, iterations, rounds, overlap_load,
+                   d_input_ptr, batch, d_output_ptrs, stream_ptr=0) -> fi_sched_stats:
+    arr = (fi_model_spec * len(specs))(*specs)
+    grp = (C.c_int32 * len(specs))(*group_of)
+    outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
+    sched = fi_sched_opts(iterations, rounds, int(overlap_load), 0)
+    stats = fi_sched_stats()
+    _check(lib().fi_round_robin(arr, len(specs), C.byref(opts), grp, n_groups, C.byref(sched), C.c_void_p(d_input_ptr),
+                                batch, outs, C.c_void_p(stream_ptr), C.byref(stats)), "fi_round_robin")
+    return stats
+
+
+def make_opts(max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY, max_device_bytes=0,
+              use_graph=False, serial_lanes=False, swap_headroom_bytes=0) -> fi_build_opts:
+    opts = fi_build_opts()
+    opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
+    opts.use_graph = int(use_graph)
+    opts.serial_lanes = int(serial_lanes)
+    opts.swap_headroom_bytes = int(swap_headroom_bytes)
+    if allocators is not None:
+        allocators.apply(opts)
+    return opts
 
 
 def fi_query(h) -> fi_dag_info:
@@ -312,13 +365,8 @@ class Dag:
     def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
                  max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False, swap_headroom_bytes=0):
         self.keepalive = [specs, keepalive, allocators]
-        opts = fi_build_opts()
-        opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
-        opts.use_graph = int(use_graph)
-        opts.serial_lanes = int(serial_lanes)
-        opts.swap_headroom_bytes = int(swap_headroom_bytes)
-        if allocators is not None:
-            allocators.apply(opts)
+        opts = make_opts(max_batch, allocators, group_levels, load_mode, max_device_bytes, use_graph, serial_lanes,
+                         swap_headroom_bytes)
         self.opts = opts
         self.h = fi_build_dag(specs, opts)
         self.n_models = len(specs)

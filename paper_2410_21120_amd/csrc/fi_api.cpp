@@ -179,7 +179,23 @@ static fi_status analyze_member(const fi_build_opts& opts, Member& mb, int32_t m
 
 static fi_status plan_dag(fi_dag* g);
 
+static fi_status build_core(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, bool with_image, fi_dag** out);
+
 fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, fi_dag** out) {
+  return build_core(models, n, opts, true, out);
+}
+
+fi_status fi_footprint(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, fi_dag_info* info) {
+  if (!info) { set_error("null info"); return FI_EINVAL; }
+  fi_dag* g = nullptr;
+  fi_status st = build_core(models, n, opts, false, &g);   // plan only: no pinned image, no weight bytes touched
+  if (st != FI_OK) return st;
+  st = fi_query(g, info);
+  delete g;
+  return st;
+}
+
+static fi_status build_core(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, bool with_image, fi_dag** out) {
   if (!models || n < 1 || !opts || !out) { set_error("null argument or no models"); return FI_EINVAL; }
   if (opts->max_batch < 1) { set_error("max_batch must be >= 1"); return FI_EINVAL; }
   if (opts->load_mode != FI_LOAD_ONE_COPY && opts->load_mode != FI_LOAD_PER_MODEL) { set_error("bad load_mode"); return FI_EINVAL; }
@@ -199,6 +215,8 @@ fi_status fi_build_dag(const fi_model_spec* models, int32_t n, const fi_build_op
   }
   fi_status st = plan_dag(g.get());
   if (st != FI_OK) return st;
+
+  if (!with_image) { *out = g.release(); return FI_OK; }
 
   // ---- pinned image: the bytes fi_load copies ----------------------------------------------
   g->image_bytes = opts->load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;

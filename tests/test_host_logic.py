@@ -337,3 +337,57 @@ def test_swap_model_errors_leave_the_dag_unchanged():
         tight.swap_model(1, bspec, keepalive=(bkeep, bb))
     assert e.value.status == fi.FI_EBUDGET
     assert tight.query().n_nodes == q0.n_nodes
+
+
+def _specs(fams, hw=64, seed0=1000):
+    specs, keep = [], []
+    for i, f in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=hw)
+        blob = gen.make_blob(m, seed0 + i)
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+        specs.append(sp)
+        keep.append((k, blob))
+    return specs, keep
+
+
+def test_footprint_equals_the_built_dag_without_touching_weights():
+    fams = ["resnet18", "mobilenetv2", "resnet18"]
+    specs, keep = _specs(fams)
+    alloc = fi.HostAllocators()
+    opts = fi.make_opts(4, alloc)
+    fp = fi.fi_footprint(specs, opts)
+    d = fi.Dag(specs, 4, alloc, keepalive=keep)
+    q = d.query()
+    assert (fp.arena_bytes, fp.act_bytes, fp.workspace_bytes, fp.device_bytes, fp.n_nodes, fp.n_launches, fp.n_lanes) == \
+           (q.arena_bytes, q.act_bytes, q.workspace_bytes, q.device_bytes, q.n_nodes, q.n_launches, q.n_lanes)
+    # the footprint needs the architecture only: a spec whose weight pointer leads nowhere readable still answers
+    ghost = []
+    for sp in specs:
+        g = fi.fi_model_spec.from_buffer_copy(sp)
+        g.weights = 4096
+        ghost.append(g)
+    assert fi.fi_footprint(ghost, opts).device_bytes == q.device_bytes
+
+
+def test_partition_first_fit_in_order_within_budget():
+    """Manager batching (Section IV): batches in the caller's order, each within the budget by the exact
+    footprint of its DAG; a budget below one model's need is refused."""
+    fams = ["resnet18", "vgg16", "mobilenetv2", "resnet50", "resnet18", "vgg16", "mobilenetv2"]
+    specs, keep = _specs(fams)
+    opts = fi.make_opts(4, fi.HostAllocators())
+    single = [fi.fi_footprint([sp], opts).device_bytes for sp in specs]
+    everything = fi.fi_footprint(specs, opts).device_bytes
+    group_of, n = fi.fi_partition(specs, opts, everything)
+    assert n == 1 and group_of == [0] * len(fams)
+    budget = max(single) + min(single)                  # room for the largest model plus a small one
+    group_of, n = fi.fi_partition(specs, opts, budget)
+    assert n > 1 and group_of == sorted(group_of) and group_of[0] == 0 and group_of[-1] == n - 1
+    for g in range(n):
+        members = [sp for sp, go in zip(specs, group_of) if go == g]
+        assert fi.fi_footprint(members, opts).device_bytes <= budget
+        nxt = [sp for sp, go in zip(specs, group_of) if go == g + 1][:1]
+        if nxt:                                         # first fit: the next model would not have fitted
+            assert fi.fi_footprint(members + nxt, opts).device_bytes > budget
+    with pytest.raises(fi.FiError) as e:
+        fi.fi_partition(specs, opts, max(single) - 1)
+    assert e.value.status == fi.FI_EBUDGET
