@@ -111,7 +111,7 @@ typedef struct {
   int32_t load_mode;         /* fi_load_mode */
   int32_t use_graph;         /* 1: fi_run replays the schedule as one HIP graph (needs a non-NULL stream) */
   int32_t serial_lanes;      /* 0: members of different architecture run concurrently on internal streams; 1: one stream */
-  int32_t reserved;
+  int32_t per_member_inputs; /* 1: every member reads an input of its own (fi_run_inputs); 0: one shared input */
   uint64_t max_device_bytes; /* 0 = unlimited; else fi_build_dag fails with FI_EBUDGET beyond it */
   void* (*dev_alloc)(size_t bytes, void* user);
   void (*dev_free)(void* ptr, void* user);
@@ -199,6 +199,16 @@ fi_status fi_load(fi_dag* dag, void* hip_stream);
  * [batch, classes_m] logits for a classifier, or probabilities if the output
  * node is a softmax.  1 <= batch <= max_batch.  Allocates nothing. */
 fi_status fi_run(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream);
+
+/* Algorithm 1 gives every member model m its own input x^m: the same pass with
+ * d_inputs a HOST array of n_models DEVICE pointers, member m reading
+ * d_inputs[m] ([batch, in_h, in_w, in_c] NHWC in the weight dtype, read-only; all
+ * members share the input shape and the batch).  Needs a DAG built with
+ * fi_build_opts.per_member_inputs = 1 (else FI_ESTATE); such a DAG stages one
+ * channel-padded copy per member instead of one per activation dtype, and fi_run
+ * on it feeds the one input to every member.  Always launches eagerly (use_graph
+ * applies to fi_run). */
+fi_status fi_run_inputs(fi_dag* dag, const void* const* d_inputs, int32_t batch, void* const* d_outputs, void* hip_stream);
 
 /* Same pass with every launch issued on hip_stream (lanes serialised) and a HIP
  * event between launches; ms[i] (host, n_launches floats) receives launch i's

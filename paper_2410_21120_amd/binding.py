@@ -43,7 +43,7 @@ FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
 
 class fi_build_opts(C.Structure):
     _fields_ = [("max_batch", C.c_int32), ("group_levels", C.c_int32), ("load_mode", C.c_int32),
-                ("use_graph", C.c_int32), ("serial_lanes", C.c_int32), ("reserved", C.c_int32),
+                ("use_graph", C.c_int32), ("serial_lanes", C.c_int32), ("per_member_inputs", C.c_int32),
                 ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
                 ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p),
                 ("swap_headroom_bytes", C.c_uint64)]
@@ -89,7 +89,7 @@ class fi_launch_info(C.Structure):
 
 LIB_PATH = _build.OUT
 EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_footprint", "fi_partition", "fi_round_robin", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
-           "fi_run", "fi_profile", "fi_timeline", "fi_swap_model", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
+           "fi_run", "fi_run_inputs", "fi_profile", "fi_timeline", "fi_swap_model", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
 
@@ -113,6 +113,7 @@ def lib():
         L.fi_launch.argtypes = [vp, i32, C.POINTER(fi_launch_info)]
         L.fi_load.argtypes = [vp, vp]
         L.fi_run.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
+        L.fi_run_inputs.argtypes = [vp, C.POINTER(vp), i32, C.POINTER(vp), vp]
         L.fi_profile.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), i32]
         L.fi_timeline.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32]
         L.fi_footprint.argtypes = [C.POINTER(fi_model_spec), i32, C.POINTER(fi_build_opts), C.POINTER(fi_dag_info)]
@@ -198,12 +199,13 @@ def fi_round_robin(specs, opts: fi_build_opts, group_of, n_groups, iterations, r
 
 
 def make_opts(max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY, max_device_bytes=0,
-              use_graph=False, serial_lanes=False, swap_headroom_bytes=0) -> fi_build_opts:
+              use_graph=False, serial_lanes=False, swap_headroom_bytes=0, per_member_inputs=False) -> fi_build_opts:
     opts = fi_build_opts()
     opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
     opts.use_graph = int(use_graph)
     opts.serial_lanes = int(serial_lanes)
     opts.swap_headroom_bytes = int(swap_headroom_bytes)
+    opts.per_member_inputs = int(per_member_inputs)
     if allocators is not None:
         allocators.apply(opts)
     return opts
@@ -234,6 +236,12 @@ def fi_load(h, stream_ptr=0) -> None:
 def fi_run(h, d_input_ptr, batch, d_output_ptrs, stream_ptr=0) -> None:
     outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
     _check(lib().fi_run(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr)), "fi_run")
+
+
+def fi_run_inputs(h, d_input_ptrs, batch, d_output_ptrs, stream_ptr=0) -> None:
+    ins = (C.c_void_p * len(d_input_ptrs))(*d_input_ptrs)
+    outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
+    _check(lib().fi_run_inputs(h, ins, batch, outs, C.c_void_p(stream_ptr)), "fi_run_inputs")
 
 
 def fi_profile(h, d_input_ptr, batch, d_output_ptrs, stream_ptr, n_launches):
@@ -363,10 +371,11 @@ class Dag:
     """Owner of one fi_dag handle."""
 
     def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
-                 max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False, swap_headroom_bytes=0):
+                 max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False, swap_headroom_bytes=0,
+                 per_member_inputs=False):
         self.keepalive = [specs, keepalive, allocators]
         opts = make_opts(max_batch, allocators, group_levels, load_mode, max_device_bytes, use_graph, serial_lanes,
-                         swap_headroom_bytes)
+                         swap_headroom_bytes, per_member_inputs)
         self.opts = opts
         self.h = fi_build_dag(specs, opts)
         self.n_models = len(specs)
@@ -393,6 +402,9 @@ class Dag:
 
     def run(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
         fi_run(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr)
+
+    def run_inputs(self, d_input_ptrs, batch, d_output_ptrs, stream_ptr=0):
+        fi_run_inputs(self.h, d_input_ptrs, batch, d_output_ptrs, stream_ptr)
 
     def profile(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
         return fi_profile(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr, self.query().n_launches)

@@ -23,12 +23,21 @@ struct Tensor {           // one stored activation tensor (a node's output, or a
   uint64_t bytes, off;
 };
 
+struct StageTensor {      // a staged (channel-padded, activation-dtype) copy of a caller's input
+  int32_t adt;            // activation dtype of the copy
+  int32_t member;         // owner when every member has its own input; -1: shared by every member of this dtype
+  int32_t lane;           // -1: shared by all lanes
+  int32_t last;           // last level that reads it
+  uint64_t off;           // placement in the activation arena
+};
+
 struct Member {
   fi_model_spec spec;     // borrowed pointers inside
   ModelPlan plan;
   int32_t node0;          // first global node id
   int32_t lane;           // members of identical architecture share a lane (two lanes when they are many and large)
   int32_t sibling_lanes;  // lanes that run this member's architecture side by side
+  int32_t stage;          // index of the staged input this member reads
   uint64_t arena_off;     // placement of the packed blob in the weight arena
 };
 
@@ -44,7 +53,7 @@ struct fi_dag {
   int32_t wdtype = FI_BF16;
   uint64_t desc_bytes = 0, arena_bytes = 0, act_bytes = 0, workspace_bytes = 0, device_bytes = 0;
   uint64_t image_bytes = 0;           // bytes of the pinned image (whole arena, or tables only)
-  uint64_t stage_off[2] = {fi::kNone, fi::kNone};  // staged input per activation dtype
+  std::vector<fi::StageTensor> stages;  // staged inputs: one per activation dtype, or one per member
   uint8_t* image = nullptr;           // pinned host image
   uint8_t* dev = nullptr;             // the one device allocation (LOADED only)
   uint64_t dev_capacity = 0;          // its size: what the plan needed at load plus the swap headroom
@@ -243,7 +252,7 @@ static fi_status plan_dag(fi_dag* g) {
   const int32_t n = (int32_t)g->members.size();
   g->nodes.clear(); g->launches.clear(); g->descs.clear();
   g->n_levels = 0; g->macs = 0; g->n_lanes = 1;
-  g->stage_off[0] = g->stage_off[1] = kNone;
+  g->stages.clear();
   g->wdtype = g->members[0].spec.dtype;
 
   // ---- union of the member graphs (no edge between members) and depth levels --------
@@ -361,9 +370,21 @@ static fi_status plan_dag(fi_dag* g) {
 
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
   //      share a launch, FI_MAX_GROUP problems at most --------------------------------------
-  bool need_stage[2] = {false, false};
-  for (const Node& nd : g->nodes)
-    if (nd.input == FI_INPUT) need_stage[g->members[(size_t)nd.model].spec.act_dtype] = true;
+  // staged inputs: the shared input once per activation dtype, or every member's own input
+  if (opts->per_member_inputs) {
+    for (int32_t m = 0; m < n; ++m) {
+      Member& mb = g->members[(size_t)m];
+      mb.stage = (int32_t)g->stages.size();
+      g->stages.push_back(StageTensor{mb.spec.act_dtype, m, g->n_lanes > 1 ? mb.lane : -1, 0, 0});
+    }
+  } else {
+    int32_t of_adt[2] = {-1, -1};
+    for (Member& mb : g->members) {
+      const int adt = mb.spec.act_dtype;
+      if (of_adt[adt] < 0) { of_adt[adt] = (int32_t)g->stages.size(); g->stages.push_back(StageTensor{adt, -1, -1, 0, 0}); }
+      mb.stage = of_adt[adt];
+    }
+  }
   auto new_launch = [&](int level, int kind, int tile, int adt) -> Launch& {
     Launch L{};
     L.level = level; L.kind = kind; L.tile = tile; L.wdtype = g->wdtype; L.adtype = adt; L.lane = 0;
@@ -372,8 +393,19 @@ static fi_status plan_dag(fi_dag* g) {
     g->launches.push_back(L);
     return g->launches.back();
   };
-  for (int adt = 0; adt < 2; ++adt)
-    if (need_stage[adt]) new_launch(0, K_STAGE, 0, adt);   // one staged copy per activation dtype
+  for (int adt = 0; adt < 2; ++adt) {
+    int32_t open_stage = -1;
+    for (size_t t = 0; t < g->stages.size(); ++t) {
+      if (g->stages[t].adt != adt) continue;
+      if (open_stage < 0 || g->launches[(size_t)open_stage].n >= FI_MAX_GROUP) {
+        new_launch(0, K_STAGE, 0, adt);
+        open_stage = (int32_t)g->launches.size() - 1;
+      }
+      Launch& L = g->launches[(size_t)open_stage];
+      L.nodes.push_back((int32_t)t);   // a staging launch lists staged tensors, not nodes
+      ++L.n;
+    }
+  }
   for (int32_t lv = 1; lv <= g->n_levels; ++lv) {
     std::map<std::tuple<int, int, int>, int32_t> open;   // (kind, tile, adtype/split/lane) -> launch index
     for (int32_t i = 0; i < total; ++i) {
@@ -407,17 +439,16 @@ static fi_status plan_dag(fi_dag* g) {
   }
 
   // ---- activation arena: live range of every stored tensor, then first-fit by size -----
-  std::vector<Tensor> tens((size_t)total + 2);
+  const int32_t n_stage = (int32_t)g->stages.size();
+  std::vector<Tensor> tens((size_t)total + (size_t)n_stage);
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
     nd.first_level = nd.last_level = nd.level;
   }
-  int32_t stage_last[2] = {0, 0};
   for (int32_t i = 0; i < total; ++i) {
     const Node& nd = g->nodes[(size_t)i];
-    const int adt = g->members[(size_t)nd.model].spec.act_dtype;
     if (nd.input >= 0) g->nodes[(size_t)nd.input].last_level = std::max(g->nodes[(size_t)nd.input].last_level, nd.level);
-    else stage_last[adt] = std::max(stage_last[adt], nd.level);
+    else { StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage]; st.last = std::max(st.last, nd.level); }
     if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.level);
   }
   for (int32_t i = 0; i < total; ++i) {
@@ -426,12 +457,14 @@ static fi_status plan_dag(fi_dag* g) {
     tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.lane, nd.out_bytes, 0};
   }
   const Member& m0 = g->members[0];
-  for (int adt = 0; adt < 2; ++adt)
-    tens[(size_t)total + adt] = Tensor{0, stage_last[adt], -1,
-        need_stage[adt] ? align_up((uint64_t)B * m0.spec.in_h * m0.spec.in_w * m0.plan.in_cp * esize(adt)) : 0, 0};
+  for (int32_t t = 0; t < n_stage; ++t) {
+    const StageTensor& st = g->stages[(size_t)t];
+    tens[(size_t)(total + t)] = Tensor{0, st.last, st.lane,
+        align_up((uint64_t)B * m0.spec.in_h * m0.spec.in_w * m0.plan.in_cp * esize(st.adt)), 0};
+  }
   {
     std::vector<int32_t> order;
-    for (int32_t i = 0; i < total + 2; ++i) if (tens[(size_t)i].bytes) order.push_back(i);
+    for (int32_t i = 0; i < total + n_stage; ++i) if (tens[(size_t)i].bytes) order.push_back(i);
     std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return tens[(size_t)a].bytes > tens[(size_t)b].bytes; });
     std::vector<int32_t> placed;
     uint64_t top = 0;
@@ -455,11 +488,11 @@ static fi_status plan_dag(fi_dag* g) {
     g->act_bytes = align_up(top ? top : kAlign);
   }
   for (int32_t i = 0; i < total; ++i) g->nodes[(size_t)i].out_off = tens[(size_t)i].off;
-  for (int adt = 0; adt < 2; ++adt) if (need_stage[adt]) g->stage_off[adt] = tens[(size_t)total + adt].off;
+  for (int32_t t = 0; t < n_stage; ++t) g->stages[(size_t)t].off = tens[(size_t)(total + t)].off;
 
   // ---- weight arena: [descriptor table][member 0][member 1]... --------------------------
   size_t n_desc = 0;
-  for (Launch& L : g->launches) { L.first_desc = (int32_t)n_desc; if (L.kind == K_STAGE) L.n = 1; n_desc += (size_t)L.n; }
+  for (Launch& L : g->launches) { L.first_desc = (int32_t)n_desc; n_desc += (size_t)L.n; }
   g->descs.assign(n_desc, Desc{});
   g->desc_bytes = kAlign;  // arena header; problem descriptors travel as launch arguments
   {
@@ -510,17 +543,19 @@ static fi_status plan_dag(fi_dag* g) {
   // ---- descriptors ---------------------------------------------------------------------
   for (Launch& L : g->launches) {
     if (L.kind == K_STAGE) {
-      Desc& d = g->descs[(size_t)L.first_desc];
-      d.H = m0.spec.in_h; d.W = m0.spec.in_w; d.C = m0.spec.in_c; d.Cp = m0.plan.in_cp;
-      d.y_off = g->stage_off[L.adtype]; d.r_off = kNone; d.x_off = d.w_off = d.b_off = kNone;
-      L.act_bytes = (uint64_t)d.H * d.W * (d.C * esize(L.wdtype) + d.Cp * esize(L.adtype));
+      for (int32_t k = 0; k < L.n; ++k) {
+        Desc& d = g->descs[(size_t)(L.first_desc + k)];
+        d.H = m0.spec.in_h; d.W = m0.spec.in_w; d.C = m0.spec.in_c; d.Cp = m0.plan.in_cp;
+        d.y_off = g->stages[(size_t)L.nodes[(size_t)k]].off; d.r_off = kNone; d.x_off = d.w_off = d.b_off = kNone;
+        L.act_bytes += (uint64_t)d.H * d.W * (d.C * esize(L.wdtype) + d.Cp * esize(L.adtype));
+      }
       continue;
     }
     for (int32_t s = 0; s < L.n; ++s) {
       const Node& nd = g->nodes[(size_t)L.nodes[(size_t)s]];
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
       Desc& d = g->descs[(size_t)(L.first_desc + s)];
-      d.x_off = nd.input >= 0 ? g->nodes[(size_t)nd.input].out_off : g->stage_off[adt];
+      d.x_off = nd.input >= 0 ? g->nodes[(size_t)nd.input].out_off : g->stages[(size_t)g->members[(size_t)nd.model].stage].off;
       d.y_off = nd.is_output ? kNone : nd.out_off;
       d.r_off = nd.residual >= 0 ? g->nodes[(size_t)nd.residual].out_off : kNone;
       d.w_off = nd.w_off; d.b_off = nd.b_off;
@@ -607,7 +642,8 @@ fi_status fi_launch(const fi_dag* g, int32_t i, fi_launch_info* o) {
   const Launch& L = g->launches[(size_t)i];
   std::memset(o, 0, sizeof(*o));
   o->lane = L.lane;
-  o->level = L.level; o->kind = L.kind; o->n_problems = L.n; o->first_node = L.nodes.empty() ? -1 : L.nodes[0];
+  o->level = L.level; o->kind = L.kind; o->n_problems = L.n;
+  o->first_node = (L.nodes.empty() || L.kind == K_STAGE) ? -1 : L.nodes[0];
   o->macs_per_image = L.macs; o->bytes_per_image = L.act_bytes; o->weight_bytes = L.weight_bytes;
   std::snprintf(o->name, sizeof(o->name), "%s", L.name.c_str());
   return FI_OK;
@@ -662,8 +698,14 @@ fi_status fi_load(fi_dag* g, void* stream) {
 // fi_run issues it (lanes concurrent), launch i spanning [previous event on its stream, event after it],
 // in milliseconds since the pass began.
 static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream,
-                          float* ms, int32_t n_ms, float* tl_begin = nullptr, float* tl_end = nullptr) {
-  if (!g || !d_input || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
+                          float* ms, int32_t n_ms, float* tl_begin = nullptr, float* tl_end = nullptr,
+                          const void* const* d_inputs = nullptr) {
+  if (!g || (!d_input && !d_inputs) || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
+  if (d_inputs) {
+    if (!g->opts.per_member_inputs) { set_error("per-member inputs need a DAG built with per_member_inputs"); return FI_ESTATE; }
+    for (size_t m = 0; m < g->members.size(); ++m)
+      if (!d_inputs[m]) { set_error("input %zu is null", m); return FI_EINVAL; }
+  }
   if (g->state != 1) { set_error("fi_run: handle is not loaded"); return FI_ESTATE; }
   if (batch < 1 || batch > g->opts.max_batch) { set_error("batch %d outside [1, %d]", batch, g->opts.max_batch); return FI_EINVAL; }
   for (size_t m = 0; m < g->members.size(); ++m)
@@ -684,7 +726,6 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   a.wbase = g->dev;
   a.abase = g->dev + g->arena_bytes;
   a.batch = batch;
-  a.ext_in = d_input;
   fi_status rc = FI_OK;
   // Lanes: after the shared input is staged on the caller's stream the internal streams fork from
   // it, every launch goes to its lane's stream, and the caller's stream joins them at the end.
@@ -700,6 +741,10 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
     }
     hipStream_t ls = (lanes && L.lane > 0) ? g->lane_streams[(size_t)L.lane - 1] : s;
     a.n = L.n;
+    for (int32_t k = 0; k < L.n && L.kind == K_STAGE; ++k) {
+      const StageTensor& st = g->stages[(size_t)L.nodes[(size_t)k]];
+      a.ext_in[k] = (d_inputs && st.member >= 0) ? d_inputs[st.member] : d_input;
+    }
     for (int32_t k = 0; k < L.n && L.kind != K_STAGE; ++k) {
       const Node& nd = g->nodes[(size_t)L.nodes[(size_t)k]];
       a.ext_out[k] = nd.is_output ? d_outputs[nd.model] : nullptr;
@@ -771,6 +816,11 @@ fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_o
   return FI_OK;
 }
 
+fi_status fi_run_inputs(fi_dag* g, const void* const* d_inputs, int32_t batch, void* const* d_outputs, void* stream) {
+  if (!d_inputs) { set_error("null inputs"); return FI_EINVAL; }
+  return run_impl(g, nullptr, batch, d_outputs, stream, nullptr, 0, nullptr, nullptr, d_inputs);
+}
+
 fi_status fi_profile(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream, float* ms, int32_t n_ms) {
   if (!ms) { set_error("null ms"); return FI_EINVAL; }
   return run_impl(g, d_input, batch, d_outputs, stream, ms, n_ms);
@@ -835,7 +885,7 @@ fi_status fi_swap_model(fi_dag* g, int32_t slot, const fi_model_spec* model, voi
   g->n_levels = t.n_levels; g->wdtype = t.wdtype; g->macs = t.macs; g->n_lanes = t.n_lanes;
   g->desc_bytes = t.desc_bytes; g->arena_bytes = t.arena_bytes; g->act_bytes = t.act_bytes;
   g->workspace_bytes = t.workspace_bytes; g->device_bytes = t.device_bytes;
-  g->stage_off[0] = t.stage_off[0]; g->stage_off[1] = t.stage_off[1];
+  g->stages = std::move(t.stages);
   if (g->state == 1) ensure_lanes(g);
   return FI_OK;
 }

@@ -102,7 +102,7 @@ struct KArgs {
   uint8_t* abase;                // activation region (device)
   int32_t n, batch;
   int32_t first_block[FI_MAX_GROUP + 1];  // workgroup index where each problem starts (filled per launch)
-  const void* ext_in;            // caller's input (K_STAGE only)
+  const void* ext_in[FI_MAX_GROUP];  // caller's input per problem slot (K_STAGE only)
   void* ext_out[FI_MAX_GROUP];   // caller's output per problem slot (when Desc.ext)
   Desc d[FI_MAX_GROUP];          // the launch's problems: read through the scalar cache, no memory round trip
 };

@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(256) stage_kernel(KArgs a) {
   const Desc d = a.d[p];
   const int64_t pix = (int64_t)bid * 256 + threadIdx.x;
   if (pix >= (int64_t)a.batch * d.H * d.W) return;
-  const TI* x = static_cast<const TI*>(a.ext_in) + pix * d.C;
+  const TI* x = static_cast<const TI*>(a.ext_in[p]) + pix * d.C;
   TA* y = reinterpret_cast<TA*>(a.abase + d.y_off) + pix * d.Cp;
   for (int c = 0; c < d.Cp; ++c) st(y + c, c < d.C ? ld(x + c) : 0.0f);
 }

@@ -171,3 +171,49 @@ def test_timeline_pass_gives_the_same_bits_and_ordered_intervals():
         assert len(last_end) == g.dag.query().n_lanes
     finally:
         g.close()
+
+
+def test_per_member_inputs_equal_each_member_alone_on_its_input():
+    """Algorithm 1 feeds every member model its own input: member m of a DAG built for per-member inputs,
+    given input m, produces the bits of member m alone on that input; one pointer for all of them gives
+    the bits of the shared-input DAG."""
+    import torch
+    import paper_2410_21120_amd as fi
+    from tests import harness
+    mem = _members()
+    xs = [gen.make_input(20 + i, 3, 3, 64, 64, "normal", "bf16") for i in range(len(mem))]
+    alone = [_run([mb], x)[0] for mb, x in zip(mem, xs)]
+    shared = _run(mem, xs[0])
+    specs, keep = [], []
+    for m, blob, act in mem:
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        specs.append(sp)
+        keep.append((k, blob))
+    alloc = fi.TorchAllocators("cuda:0")
+    dag = fi.Dag(specs, 3, alloc, keepalive=keep, per_member_inputs=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    dag.load(stream)
+    try:
+        dev_in = [torch.from_numpy(gen.to_nhwc_storage(x, "bf16").view(np.int16)).cuda() for x in xs]
+        outs = [torch.full((3, 1000), float("nan"), dtype=torch.float32, device="cuda:0") for _ in mem]
+        assert dag.query().n_lanes == 5
+        for _ in range(2):
+            dag.run_inputs([t.data_ptr() for t in dev_in], 3, [o.data_ptr() for o in outs], stream)
+            torch.cuda.synchronize()
+            for i, o in enumerate(outs):
+                assert np.array_equal(o.cpu().numpy(), alone[i]), f"member {i}"
+        dag.run(dev_in[0].data_ptr(), 3, [o.data_ptr() for o in outs], stream)
+        torch.cuda.synchronize()
+        for i, o in enumerate(outs):
+            assert np.array_equal(o.cpu().numpy(), shared[i])
+    finally:
+        dag.unload()
+        dag.destroy()
+    # a DAG built for a shared input refuses per-member inputs
+    g = harness.GpuDag(mem[:2], 3)
+    try:
+        with pytest.raises(fi.FiError) as e:
+            g.dag.run_inputs([dev_in[0].data_ptr()] * 2, 3, [outs[0].data_ptr(), outs[1].data_ptr()], g.stream)
+        assert e.value.status == fi.FI_ESTATE
+    finally:
+        g.close()

@@ -391,3 +391,17 @@ def test_partition_first_fit_in_order_within_budget():
     with pytest.raises(fi.FiError) as e:
         fi.fi_partition(specs, opts, max(single) - 1)
     assert e.value.status == fi.FI_EBUDGET
+
+
+def test_per_member_inputs_stage_one_copy_per_member():
+    """With per-member inputs (Algorithm 1's x^m) the staging level holds one problem per member and the
+    activation arena one staged copy per member; the rest of the schedule is unchanged."""
+    fams = ["resnet18", "resnet18", "mobilenetv2"]
+    shared, _, _ = _build(fams, 2)
+    own, _, _ = _build(fams, 2, per_member_inputs=True)
+    ls, lo = shared.launches(), own.launches()
+    assert [L.n_problems for L in ls if L.level == 0] == [1]
+    assert sum(L.n_problems for L in lo if L.level == 0) == len(fams)
+    assert [(L.level, L.name, L.n_problems) for L in ls if L.level > 0] == [(L.level, L.name, L.n_problems) for L in lo if L.level > 0]
+    qs, qo = shared.query(), own.query()
+    assert (qo.n_nodes, qo.n_levels, qo.arena_bytes) == (qs.n_nodes, qs.n_levels, qs.arena_bytes)
