@@ -114,6 +114,7 @@ int pick_tile(const Node& n, int max_batch, int group, bool wide) {
   // Short reductions stream activations (bandwidth-bound): medium tiles keep more workgroups
   // and loads in flight.  Long reductions are matrix-core-bound: the largest tile re-reads least.
   if (n.Cp == 4) return n.Co <= 64 ? T_128x64 : T_128x128;  // 4-channel input: the two-tap gather exists for these tiles
+  if (!wide && n.Co <= 64 && n.Kp > 512 && blocks(T_256x64) >= 256) return T_256x64;  // narrow, long reduction: four waves stacked in M
   const int want = (n.Kp <= 512 || wide) ? T_128x128 : T_256x128;  // fp32-activation members: no 256-row tile
   const int order[4] = {T_256x128, T_128x128, T_128x64, T_64x64};
   bool started = false;
@@ -130,7 +131,7 @@ const char* kind_name(int kind, int tile) {
   switch (kind) {
     case K_STAGE: return "stage_input";
     case K_CONV_DIRECT: return "conv_direct";
-    case K_CONV_MFMA: return tile == T_256x128 ? "conv_mfma_256x128" : tile == T_128x128 ? "conv_mfma_128x128" : tile == T_128x64 ? "conv_mfma_128x64" : "conv_mfma_64x64";
+    case K_CONV_MFMA: return tile == T_256x128 ? "conv_mfma_256x128" : tile == T_256x64 ? "conv_mfma_256x64" : tile == T_128x128 ? "conv_mfma_128x128" : tile == T_128x64 ? "conv_mfma_128x64" : "conv_mfma_64x64";
     case K_DWCONV: return "dwconv";
     case K_MAXPOOL: return "maxpool";
     case K_GAP: return "global_avgpool";

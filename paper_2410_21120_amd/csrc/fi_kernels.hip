@@ -227,10 +227,16 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // filter rows / columns land inside the image (bit r: row r valid; bit 8+s: column s valid).
   int a_row[AR], a_rc[AR];
   const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho, inv_k = 1.0f / (float)d.k;
+  const bool pointwise = d.k == 1 && d.stride == 1 && d.pad == 0;  // output pixel m reads input pixel m: nothing to decode
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int m = m0 + srow + RPP * i;
     const bool ok = m < M;
+    if (pointwise) {
+      a_row[i] = (ok ? m : 0) * d.Cp * AE;
+      a_rc[i] = ok ? 0x101 : 0;
+      continue;
+    }
     const int mm = ok ? m : 0;
     const int t = fast_div(mm, d.Wo, inv_wo);
     const int q = mm - t * d.Wo;
@@ -1048,6 +1054,7 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
         return (int)hipErrorInvalidValue;
       }
       if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false, 1>, nb, 256, a, s);
+      if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false, 1>, nb, 256, a, s);
       if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false>, nb, 256, a, s);
       if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false>, nb, 256, a, s);
       return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false>, nb, 256, a, s);
