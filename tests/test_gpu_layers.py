@@ -54,6 +54,28 @@ def test_conv_relu(case, mode):
     _run_case(m, 100 + cin + cout, b, act_dtype="f32" if mode == "bf16_wide" else None)
 
 
+@pytest.mark.parametrize("case", [(128, 128, 3, 1, 1, 127, 129, 4),   # 256x128 tile: long reduction, ragged last tile
+                                  (64, 64, 3, 1, 1, 127, 129, 4),     # 256x64 tile: narrow, long reduction
+                                  (256, 128, 1, 1, 0, 127, 129, 4)])  # 128x128 tile, pointwise prologue
+def test_conv_large_tiles_bf16(case):
+    """Shapes large enough (>= 256 workgroups) for the planner to pick the 256-row tiles."""
+    import paper_2410_21120_amd as fi
+    from tests import harness
+    cin, cout, k, s, p, h, w, b = case
+    m = zoo.Model("t", "bf16", cin, h, w)
+    m.add(zoo.CONV, -1, cin=cin, cout=cout, k=k, stride=s, pad=p, act=zoo.RELU)
+    m.shapes()
+    blob = gen.make_blob(m, 300 + cin)
+    g = harness.GpuDag([(m, blob, None)], b)
+    try:
+        names = [L.name.decode() for L in g.dag.launches()]
+    finally:
+        g.close()
+    want = "conv_mfma_256x128" if (cin, cout) == (128, 128) else "conv_mfma_256x64" if cin == 64 else "conv_mfma_128x128"
+    assert want in names, names
+    _run_case(m, 300 + cin, b)
+
+
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 @pytest.mark.parametrize("act", [zoo.NONE, zoo.RELU, zoo.RELU6])
 def test_conv_residual_and_activation(mode, act):
