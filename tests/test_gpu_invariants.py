@@ -217,3 +217,34 @@ def test_per_member_inputs_equal_each_member_alone_on_its_input():
         assert e.value.status == fi.FI_ESTATE
     finally:
         g.close()
+
+
+def test_run_time_argument_errors_on_a_loaded_dag():
+    """Empty and oversized batches and missing buffers are refused before any launch; the DAG keeps working."""
+    import ctypes as C
+    import paper_2410_21120_amd as fi
+    from tests import harness
+    mem = _members()[:2]
+    x = gen.make_input(7, 3, 3, 64, 64, "normal", "bf16")
+    g = harness.GpuDag(mem, 3)
+    try:
+        base = g.run(x)
+        b, xin, outs = g.keep_buffers
+        ptrs = [o.data_ptr() for o in outs]
+        for bad_batch in (0, -1, 4):
+            with pytest.raises(fi.FiError) as e:
+                g.dag.run(xin.data_ptr(), bad_batch, ptrs, g.stream)
+            assert e.value.status == fi.FI_EINVAL
+        with pytest.raises(fi.FiError) as e:
+            g.dag.run(xin.data_ptr(), 3, [ptrs[0], 0], g.stream)
+        assert e.value.status == fi.FI_EINVAL
+        with pytest.raises(fi.FiError) as e:
+            g.dag.run(0, 3, ptrs, g.stream)
+        assert e.value.status == fi.FI_EINVAL
+        with pytest.raises(fi.FiError) as e:
+            g.dag.load(g.stream)                      # already loaded
+        assert e.value.status == fi.FI_ESTATE
+        assert all(np.array_equal(a, b2) for a, b2 in zip(g.run(x), base))
+        assert all(np.array_equal(a[:1], b2) for a, b2 in zip(base, g.run(x[:1])))   # batch 1 of max 3: rows are independent
+    finally:
+        g.close()

@@ -405,3 +405,26 @@ def test_per_member_inputs_stage_one_copy_per_member():
     assert [(L.level, L.name, L.n_problems) for L in ls if L.level > 0] == [(L.level, L.name, L.n_problems) for L in lo if L.level > 0]
     qs, qo = shared.query(), own.query()
     assert (qo.n_nodes, qo.n_levels, qo.arena_bytes) == (qs.n_nodes, qs.n_levels, qs.arena_bytes)
+
+
+def test_maximum_sizes_are_refused_at_build_time():
+    """The MFMA convolution addresses its input through a 32-bit buffer resource and decodes output rows
+    with exact float arithmetic: more than 2^24 output pixels per launch, or an input tensor of 2 GiB or
+    more, is refused when the DAG is built, never at run time."""
+    alloc = fi.HostAllocators()
+    m = zoo.Model("wide_input", "bf16", 1024, 32, 32)   # one image = 32 x 32 x 1024 bf16 = 2 MiB
+    m.add(zoo.CONV, -1, cin=1024, cout=8, k=1, stride=1, pad=0, act=zoo.RELU)
+    m.shapes()
+    blob = gen.make_blob(m, 1)
+    spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    assert fi.fi_footprint([spec], fi.make_opts(1023, alloc)).device_bytes > 0
+    with pytest.raises(fi.FiError) as e:
+        fi.fi_footprint([spec], fi.make_opts(1024, alloc))   # 1024 x 2 MiB = 2^31
+    assert e.value.status == fi.FI_EUNSUPPORTED and "2 GiB" in str(e.value)
+    r = zoo.FAMILIES["resnet18"](hw=64)                 # stem output 32 x 32 pixels per image
+    rb = gen.make_blob(r, 2)
+    rspec, rkeep = fi.make_spec(r, rb.ctypes.data, rb.nbytes)
+    assert fi.fi_footprint([rspec], fi.make_opts((1 << 14) - 1, alloc)).n_nodes == len(r.layers)
+    with pytest.raises(fi.FiError) as e:
+        fi.fi_footprint([rspec], fi.make_opts(1 << 14, alloc))   # 2^14 x 2^10 = 2^24 output pixels
+    assert e.value.status == fi.FI_EUNSUPPORTED and "2^24" in str(e.value)
