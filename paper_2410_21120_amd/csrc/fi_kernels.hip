@@ -224,7 +224,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
   const int srow = tid >> 3, kvec = (tid & 7) * 8;
   // Per row: the byte offset of its window origin (n, p*stride-pad, q*stride-pad, 0) and which
-  // filter rows / columns land inside the image (bit r: row r valid; bit 8+s: column s valid).
+  // filter rows / columns land inside the image (bit r: row r valid; bit 16+s: column s valid).
   int a_row[AR], a_rc[AR];
   const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho, inv_k = 1.0f / (float)d.k;
   const bool pointwise = d.k == 1 && d.stride == 1 && d.pad == 0;  // output pixel m reads input pixel m: nothing to decode
@@ -234,7 +234,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     const bool ok = m < M;
     if (pointwise) {
       a_row[i] = (ok ? m : 0) * d.Cp * AE;
-      a_rc[i] = ok ? 0x101 : 0;
+      a_rc[i] = ok ? 0x10001 : 0;
       continue;
     }
     const int mm = ok ? m : 0;
@@ -247,7 +247,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     int rc = 0;
     for (int r = 0; r < d.k; ++r) {
       rc |= ((unsigned)(ih0 + r) < (unsigned)d.H) ? (1 << r) : 0;
-      rc |= ((unsigned)(iw0 + r) < (unsigned)d.W) ? (256 << r) : 0;
+      rc |= ((unsigned)(iw0 + r) < (unsigned)d.W) ? (65536 << r) : 0;
     }
     a_rc[i] = ok ? rc : 0;  // rows past M read as zero
   }
@@ -292,7 +292,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     if constexpr (!C4) {                                                                          \
       const int tvar = ((kr * d.W + ks) * d.Cp + kc) * AE;                                        \
       _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                            \
-        const bool ok = ((a_rc[i] >> kr) & (a_rc[i] >> (8 + ks)) & 1) != 0;                       \
+        const bool ok = ((a_rc[i] >> kr) & (a_rc[i] >> (16 + ks)) & 1) != 0;                       \
         const uint32_t off = ok ? (uint32_t)(a_row[i] + tvar) : OOB;                              \
         _Pragma("unroll") for (int h = 0; h < AV; ++h)                                            \
             av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);        \
@@ -307,7 +307,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       }                                                                                           \
       _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                            \
         _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                           \
-          const bool ok = tr[h] < d.k && ((a_rc[i] >> tr[h]) & (a_rc[i] >> (8 + tc[h])) & 1) != 0; \
+          const bool ok = tr[h] < d.k && ((a_rc[i] >> tr[h]) & (a_rc[i] >> (16 + tc[h])) & 1) != 0; \
           const uint32_t off = ok ? (uint32_t)(a_row[i] + tv[h]) : OOB;                           \
           if constexpr (WIDE) {                                                                   \
             av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);                 \

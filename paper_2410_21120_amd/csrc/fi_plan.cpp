@@ -76,7 +76,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         if (L.kh != L.kw || L.kh < 1 || L.stride < 1 || L.pad < 0 || L.cout < 1) {
           set_error("model %s node %d: unsupported kernel geometry", nm, i); return FI_EUNSUPPORTED; }
         if (L.cin != n.C) { set_error("model %s node %d: cin %d != producer channels %d", nm, i, L.cin, n.C); return FI_EINVAL; }
-        if (L.kh > 8) { set_error("model %s node %d: kernels larger than 8x8 are not supported", nm, i); return FI_EUNSUPPORTED; }
+        if (L.kh > 15) { set_error("model %s node %d: kernels larger than 15x15 are not supported", nm, i); return FI_EUNSUPPORTED; }
         if (L.op == FI_DWCONV2D && L.cout != L.cin) { set_error("model %s node %d: depthwise needs cin == cout", nm, i); return FI_EINVAL; }
         n.k = L.kh; n.stride = L.stride; n.pad = L.pad; n.Co = L.cout;
         n.Ho = (n.H + 2 * L.pad - L.kh) / L.stride + 1;

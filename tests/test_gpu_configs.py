@@ -126,6 +126,31 @@ def test_config4_eight_resnet50_batch32_sampled():
     assert not np.array_equal(ys[0], ys[1])
 
 
+def test_further_table3_families_fused():
+    """Families of the paper's Table III that the five operators cover (AlexNet, VGG-11/13/19, ResNet-34/101/152,
+    Wide ResNet-50-2/101-2, MnasNet 1.0), all ten fused in one DAG at a reduced image size, each member against
+    the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
+    from tests import harness
+    fams = ["alexnet", "vgg11", "vgg13", "vgg19", "resnet34", "resnet101", "resnet152", "wide_resnet50_2", "wide_resnet101_2", "mnasnet1_0"]
+    mem = []
+    for i, f in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=96)
+        mem.append((m, gen.make_blob(m, 1000 + i), "f32" if f == "mnasnet1_0" else None))
+    x = gen.make_input(7, 2, 3, 96, 96, "normal", "bf16")
+    g = harness.GpuDag(mem, 2)
+    try:
+        ys = g.run(x)
+    finally:
+        g.close()
+    units = []
+    for (m, b, act) in mem:
+        units.append((m, b, x, False))
+        units.append((m, b, x, act is None))
+    res = harness.oracle_units(units)
+    for i, f in enumerate(fams):
+        _check_member(f, ys[i], res[2 * i], res[2 * i + 1], 1e-4 if f == "mnasnet1_0" else 1e-2)
+
+
 def test_config5_swap_churn_sampled():
     """Pool of 16 packed models, seeded Poisson request stream; per request build, load, run, unload.
     By the fused == alone invariant a member's correct output depends only on (model, input batch), so

@@ -41,6 +41,7 @@ CONV_CASES = [  # cin, cout, k, stride, pad, H, W, batch
     (3, 16, 3, 1, 1, 32, 32, 1), (3, 64, 7, 2, 3, 37, 41, 2), (16, 24, 1, 1, 0, 17, 19, 3), (24, 144, 1, 1, 0, 28, 28, 2),
     (64, 64, 3, 1, 1, 14, 14, 2), (32, 160, 3, 2, 1, 15, 15, 3), (128, 256, 3, 2, 1, 9, 9, 2), (72, 40, 3, 1, 0, 11, 13, 1),
     (256, 512, 1, 2, 0, 14, 14, 2), (8, 8, 3, 1, 1, 5, 5, 1), (320, 1280, 1, 1, 0, 7, 7, 2), (64, 192, 3, 1, 1, 56, 56, 1),
+    (3, 64, 11, 4, 2, 67, 71, 2), (64, 192, 5, 1, 2, 27, 27, 2), (16, 32, 15, 1, 7, 19, 17, 1),   # large kernels (up to 15x15)
 ]
 
 
@@ -87,7 +88,8 @@ def test_conv_residual_and_activation(mode, act):
     _run_case(m, 7, 2, act_dtype="f32" if mode == "bf16_wide" else None)
 
 
-@pytest.mark.parametrize("case", [(32, 3, 1, 1, 20, 20, 2), (96, 3, 2, 1, 15, 17, 2), (144, 3, 1, 1, 7, 7, 3), (24, 3, 2, 1, 9, 9, 1)])
+@pytest.mark.parametrize("case", [(32, 3, 1, 1, 20, 20, 2), (96, 3, 2, 1, 15, 17, 2), (144, 3, 1, 1, 7, 7, 3), (24, 3, 2, 1, 9, 9, 1),
+                                  (72, 5, 2, 2, 21, 19, 2), (120, 5, 1, 2, 14, 14, 2)])
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_depthwise(case, mode):
     c, k, s, p, h, w, b = case

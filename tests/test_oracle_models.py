@@ -31,6 +31,8 @@ def test_structure(fam):
     assert m.macs() == g["macs"]
     fc_or_sm = m.layers[m.output]
     assert fc_or_sm.cout == g["classes"]
+    if "gmacs_published" in g:
+        assert round(m.macs() / 1e9, 2) == g["gmacs_published"]
     if "params_with_batchnorm" in g:  # folding removes one of BatchNorm's two parameters per normalised channel
         bn_channels = sum(L.cout for L in m.layers if L.op in ("conv", "dwconv"))
         assert g["params_with_batchnorm"] - g["params"] in (bn_channels, 0)

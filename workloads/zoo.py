@@ -6,11 +6,13 @@ is added before the activation, and the operator's integer hyper-parameters.
 This is the per-model graph (nodes u_i, edges {u_i,u_j}, activations phi_i)
 that the paper's Algorithm 1 unions into one DAG.
 
-The five families are the ones the benchmark configurations name: a tiny CNN,
-ResNet-18 / ResNet-50 (BatchNorm folded into the preceding convolution, so each
-convolution carries one bias per output channel), MobileNetV2 (width 1.0) and
-VGG-16.  Shapes follow the published architecture tables; ResNet-50 carries the
-bottleneck stride on its 3x3 convolution.
+The first five families are the ones the benchmark configurations name: a tiny
+CNN, ResNet-18 / ResNet-50 (BatchNorm folded into the preceding convolution, so
+each convolution carries one bias per output channel), MobileNetV2 (width 1.0)
+and VGG-16; the others are families of the paper's Table III that the same five
+operators cover (AlexNet, VGG-11/13/19, ResNet-34/101/152, Wide ResNet-50-2 /
+101-2, MnasNet 1.0).  Shapes follow the published architecture tables; the
+bottleneck ResNets carry the stride on their 3x3 convolution.
 """
 from __future__ import annotations
 
@@ -144,12 +146,13 @@ def _resnet_stem(m: Model) -> int:
     return m.add(MAXPOOL, a, k=3, stride=2, pad=1)
 
 
-def resnet18(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
-    m = Model("resnet18", dtype, 3, hw, hw)
+def _basic_resnet(name: str, reps, dtype: str, classes: int, hw: int) -> Model:
+    """ResNet with two-convolution basic blocks (He et al. 2016, Table 1: 18 and 34 layers)."""
+    m = Model(name, dtype, 3, hw, hw)
     x = _resnet_stem(m)
     cin = 64
-    for stage, width in enumerate((64, 128, 256, 512)):
-        for blk in range(2):
+    for stage, (width, n) in enumerate(zip((64, 128, 256, 512), reps)):
+        for blk in range(n):
             stride = 2 if (stage > 0 and blk == 0) else 1
             a = m.add(CONV, x, cin=cin, cout=width, k=3, stride=stride, pad=1, act=RELU)
             if stride != 1 or cin != width:
@@ -163,24 +166,55 @@ def resnet18(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
     return m.shapes()
 
 
-def resnet50(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
-    m = Model("resnet50", dtype, 3, hw, hw)
+def _bottleneck_resnet(name: str, reps, inner: int, dtype: str, classes: int, hw: int) -> Model:
+    """ResNet with 1x1 / 3x3 / 1x1 bottleneck blocks (50, 101, 152 layers); `inner` scales the width of
+    the two inner convolutions (2 for the wide variants of Zagoruyko & Komodakis 2016).  Stride on the 3x3."""
+    m = Model(name, dtype, 3, hw, hw)
     x = _resnet_stem(m)
     cin = 64
-    for stage, (width, reps) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3))):
-        for blk in range(reps):
+    for stage, (width, n) in enumerate(zip((64, 128, 256, 512), reps)):
+        mid = width * inner
+        for blk in range(n):
             stride = 2 if (stage > 0 and blk == 0) else 1
-            a = m.add(CONV, x, cin=cin, cout=width, k=1, stride=1, pad=0, act=RELU)
+            a = m.add(CONV, x, cin=cin, cout=mid, k=1, stride=1, pad=0, act=RELU)
             if blk == 0:
                 skip = m.add(CONV, x, cin=cin, cout=4 * width, k=1, stride=stride, pad=0, act=NONE)
             else:
                 skip = x
-            a = m.add(CONV, a, cin=width, cout=width, k=3, stride=stride, pad=1, act=RELU)
-            x = m.add(CONV, a, cin=width, cout=4 * width, k=1, stride=1, pad=0, act=RELU, residual=skip)
+            a = m.add(CONV, a, cin=mid, cout=mid, k=3, stride=stride, pad=1, act=RELU)
+            x = m.add(CONV, a, cin=mid, cout=4 * width, k=1, stride=1, pad=0, act=RELU, residual=skip)
             cin = 4 * width
     x = m.add(GAP, x)
     m.add(FC, x, cin=2048, cout=classes)
     return m.shapes()
+
+
+def resnet18(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _basic_resnet("resnet18", (2, 2, 2, 2), dtype, classes, hw)
+
+
+def resnet34(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _basic_resnet("resnet34", (3, 4, 6, 3), dtype, classes, hw)
+
+
+def resnet50(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _bottleneck_resnet("resnet50", (3, 4, 6, 3), 1, dtype, classes, hw)
+
+
+def resnet101(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _bottleneck_resnet("resnet101", (3, 4, 23, 3), 1, dtype, classes, hw)
+
+
+def resnet152(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _bottleneck_resnet("resnet152", (3, 8, 36, 3), 1, dtype, classes, hw)
+
+
+def wide_resnet50_2(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _bottleneck_resnet("wide_resnet50_2", (3, 4, 6, 3), 2, dtype, classes, hw)
+
+
+def wide_resnet101_2(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _bottleneck_resnet("wide_resnet101_2", (3, 4, 23, 3), 2, dtype, classes, hw)
 
 
 def mobilenetv2(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
@@ -205,10 +239,18 @@ def mobilenetv2(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Mode
     return m.shapes()
 
 
-def vgg16(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
-    m = Model("vgg16", dtype, 3, hw, hw)
+_VGG = {  # Simonyan & Zisserman 2015, Table 1: configurations A, B, D, E
+    "vgg11": (64, "M", 128, "M", 256, 256, "M", 512, 512, "M", 512, 512, "M"),
+    "vgg13": (64, 64, "M", 128, 128, "M", 256, 256, "M", 512, 512, "M", 512, 512, "M"),
+    "vgg16": (64, 64, "M", 128, 128, "M", 256, 256, 256, "M", 512, 512, 512, "M", 512, 512, 512, "M"),
+    "vgg19": (64, 64, "M", 128, 128, "M", 256, 256, 256, 256, "M", 512, 512, 512, 512, "M", 512, 512, 512, 512, "M"),
+}
+
+
+def _vgg(name: str, dtype: str, classes: int, hw: int) -> Model:
+    m = Model(name, dtype, 3, hw, hw)
     x, cin, side = MODEL_INPUT, 3, hw
-    for v in (64, 64, "M", 128, 128, "M", 256, 256, 256, "M", 512, 512, 512, "M", 512, 512, 512, "M"):
+    for v in _VGG[name]:
         if v == "M":
             x = m.add(MAXPOOL, x, k=2, stride=2, pad=0)
             side //= 2
@@ -221,5 +263,70 @@ def vgg16(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
     return m.shapes()
 
 
+def vgg11(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _vgg("vgg11", dtype, classes, hw)
+
+
+def vgg13(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _vgg("vgg13", dtype, classes, hw)
+
+
+def vgg16(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _vgg("vgg16", dtype, classes, hw)
+
+
+def vgg19(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _vgg("vgg19", dtype, classes, hw)
+
+
+def alexnet(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    """The single-tower AlexNet (Krizhevsky 2014): 11x11/4, 5x5 and three 3x3 convolutions, 3x3/2 max
+    pooling after the first, second and fifth, three fully connected layers (6x6x256 inputs at 224)."""
+    m = Model("alexnet", dtype, 3, hw, hw)
+    side = (hw + 2 * 2 - 11) // 4 + 1
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=64, k=11, stride=4, pad=2, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0)
+    side = (side - 3) // 2 + 1
+    x = m.add(CONV, x, cin=64, cout=192, k=5, stride=1, pad=2, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0)
+    side = (side - 3) // 2 + 1
+    x = m.add(CONV, x, cin=192, cout=384, k=3, stride=1, pad=1, act=RELU)
+    x = m.add(CONV, x, cin=384, cout=256, k=3, stride=1, pad=1, act=RELU)
+    x = m.add(CONV, x, cin=256, cout=256, k=3, stride=1, pad=1, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0)
+    side = (side - 3) // 2 + 1
+    x = m.add(FC, x, cin=256 * side * side, cout=4096, act=RELU)
+    x = m.add(FC, x, cin=4096, cout=4096, act=RELU)
+    m.add(FC, x, cin=4096, cout=classes)
+    return m.shapes()
+
+
+def mnasnet1_0(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    """MnasNet-A1 without squeeze-excite at depth multiplier 1.0 (Tan et al. 2019, the B1 variant): a
+    separable stem, then inverted residuals (expansion, kernel, stride, repeats, width) with ReLU."""
+    m = Model("mnasnet1_0", dtype, 3, hw, hw)
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=32, k=3, stride=2, pad=1, act=RELU)
+    x = m.add(DWCONV, x, cin=32, cout=32, k=3, stride=1, pad=1, act=RELU)
+    x = m.add(CONV, x, cin=32, cout=16, k=1, stride=1, pad=0, act=NONE)
+    cin = 16
+    for t, k, s, n, c in ((3, 3, 2, 3, 24), (3, 5, 2, 3, 40), (6, 5, 2, 3, 80), (6, 3, 1, 2, 96), (6, 5, 2, 4, 192), (6, 3, 1, 1, 320)):
+        for rep in range(n):
+            stride = s if rep == 0 else 1
+            hidden = cin * t
+            a = m.add(CONV, x, cin=cin, cout=hidden, k=1, stride=1, pad=0, act=RELU)
+            a = m.add(DWCONV, a, cin=hidden, cout=hidden, k=k, stride=stride, pad=k // 2, act=RELU)
+            skip = x if (stride == 1 and cin == c) else NO_RESIDUAL
+            x = m.add(CONV, a, cin=hidden, cout=c, k=1, stride=1, pad=0, act=NONE, residual=skip)
+            cin = c
+    x = m.add(CONV, x, cin=320, cout=1280, k=1, stride=1, pad=0, act=RELU)
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=1280, cout=classes)
+    return m.shapes()
+
+
 FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
-            "mobilenetv2": mobilenetv2, "vgg16": vgg16}
+            "mobilenetv2": mobilenetv2, "vgg16": vgg16,
+            # further families of the paper's Table III that need no operator beyond the five above
+            "alexnet": alexnet, "vgg11": vgg11, "vgg13": vgg13, "vgg19": vgg19,
+            "resnet34": resnet34, "resnet101": resnet101, "resnet152": resnet152,
+            "wide_resnet50_2": wide_resnet50_2, "wide_resnet101_2": wide_resnet101_2, "mnasnet1_0": mnasnet1_0}
