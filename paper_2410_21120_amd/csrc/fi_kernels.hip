@@ -183,7 +183,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // fp32: bf16 matrix-core throughput at fp32-grade activation accuracy.
 // C4: the input has 4 stored channels (an RGB-like model input); an 8-element reduction vector
 // then spans two neighbouring filter taps and is gathered with two half-width loads.
-template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, int NS = 1, bool C4 = false>
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false>
 __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
   constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
@@ -194,9 +194,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int AR = BM / RPP, BR = BN / RPP;  // 8-element vectors each thread stages per tile
   constexpr int STAGE = (AT * BM + BN) * LDS_STRIDE;   // bf16 elements per LDS buffer
-  constexpr int SMEM = NS * STAGE * 2;
+  constexpr int SMEM = STAGE * 2;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
-  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);   // [NS][AT][BM][LDS_STRIDE] then B
+  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);   // [AT][BM][LDS_STRIDE] then B
   bf16_t* const Bs = As + AT * BM * LDS_STRIDE;
 
   // locate the problem and the tile (block-uniform)
@@ -280,11 +280,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  // NS register stages feed NS LDS buffers.  NS == 1: fetch one tile ahead, two barriers per
-  // tile.  NS == 2 (DEEP): fetch two tiles ahead and alternate LDS buffers, one barrier per tile;
-  // a tile's loads then have two full multiply phases to land.
-  u32x4 av[NS][AR][AV];
-  uint4 bv[NS][BR];
+  // One register stage feeds one LDS buffer: fetch one tile ahead, two barriers per tile.
+  u32x4 av[1][AR][AV];
+  uint4 bv[1][BR];
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
 
 #define FI_FETCH(KT, S)                                                                           \
@@ -378,31 +376,13 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     }                                                                                             \
   }
 
-  if constexpr (NS == 1) {
-    if (kt0 < ntiles) FI_FETCH(kt0, 0)
-    for (int kt = kt0; kt < ntiles; ++kt) {
-      FI_PARK(0)
-      __syncthreads();
-      if (kt + 1 < ntiles) FI_FETCH(kt + 1, 0)  // in flight while this tile is multiplied
-      FI_MULTIPLY(0)
-      __syncthreads();  // every wave is done with this tile before it is overwritten
-    }
-  } else {
-    if (kt0 < ntiles) FI_FETCH(kt0, 0)
-    if (kt0 + 1 < ntiles) FI_FETCH(kt0 + 1, 1)
-    for (int kt = kt0; kt < ntiles; kt += 2) {
-      FI_PARK(0)
-      __syncthreads();  // tile kt is in buffer 0; buffer 1 was last read two steps ago
-      if (kt + 2 < ntiles) FI_FETCH(kt + 2, 0)
-      FI_MULTIPLY(0)
-      if (kt + 1 < ntiles) {
-        FI_PARK(1)
-        __syncthreads();
-        if (kt + 3 < ntiles) FI_FETCH(kt + 3, 1)
-        FI_MULTIPLY(1)
-      }
-    }
-    __syncthreads();  // the epilogue reuses the tile memory
+  if (kt0 < ntiles) FI_FETCH(kt0, 0)
+  for (int kt = kt0; kt < ntiles; ++kt) {
+    FI_PARK(0)
+    __syncthreads();
+    if (kt + 1 < ntiles) FI_FETCH(kt + 1, 0)  // in flight while this tile is multiplied
+    FI_MULTIPLY(0)
+    __syncthreads();  // every wave is done with this tile before it is overwritten
   }
 #undef FI_FETCH
 #undef FI_PARK
@@ -1039,12 +1019,12 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       if (!wb) return (int)hipErrorInvalidValue;
       if (hd[(size_t)L.first_desc].Cp == 4) {  // 4-channel model input
         if (!ab) {
-          if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, true, 1, true>, nb, 256, a, s);
-          if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, true, 1, true>, nb, 256, a, s);
+          if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, true, true>, nb, 256, a, s);
+          if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, true, true>, nb, 256, a, s);
           return (int)hipErrorInvalidValue;
         }
-        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false, 1, true>, nb, 256, a, s);
-        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, 1, true>, nb, 256, a, s);
+        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false, true>, nb, 256, a, s);
+        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, true>, nb, 256, a, s);
         return (int)hipErrorInvalidValue;
       }
       if (!ab) {  // fp32 activations: split-bf16 inputs
@@ -1053,8 +1033,8 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
         if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, true>, nb, 256, a, s);
         return (int)hipErrorInvalidValue;
       }
-      if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false, 1>, nb, 256, a, s);
-      if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false, 1>, nb, 256, a, s);
+      if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false>, nb, 256, a, s);
+      if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false>, nb, 256, a, s);
       if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false>, nb, 256, a, s);
       if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false>, nb, 256, a, s);
       return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false>, nb, 256, a, s);
