@@ -23,7 +23,10 @@ WORKLOADS = {
     "cfg3": dict(desc="ResNet-50 + MobileNetV2 + VGG-16 fused, bf16, batch 8x3x224x224", fams=["resnet50", "mobilenetv2", "vgg16"], batch=8),
     "cfg4": dict(desc="8x ResNet-50 fused (grouped conv GEMMs), bf16, batch 32x3x224x224", fams=["resnet50"] * 8, batch=32),
 }
-WIDE = {"mobilenetv2"}  # members that keep fp32 activations (tolerance derivation)
+# Members that keep fp32 activations: with synthetic He-normal weights MobileNetV2 amplifies bf16 storage
+# rounding about twentyfold (the CPU oracle's own bf16-storage mode sits 2e-2 from its fp32 mode), so bf16
+# storage cannot meet the 1e-2 bar; its convolutions still run on the bf16 matrix cores (hi/lo split).
+WIDE = {"mobilenetv2"}
 PEAK_MFMA_BF16 = 2500.0  # TFLOP/s dense
 PEAK_HBM = 8000.0        # GB/s
 
@@ -43,8 +46,8 @@ def main():
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to calibrate rocprofv3 counters)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (member models shard across GPUs without any collective; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (member models are independent, so more GPUs would each take "
+              "a subset of members with its own arena and schedule, no collective); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

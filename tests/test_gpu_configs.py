@@ -2,7 +2,7 @@
 C-ABI, against the CPU oracle on the same seeded inputs, at full size and in the
 launch configuration the benchmark times (grouped levels, one-copy load).
 
-Tolerances (the benchmark spec): relative L2 <= 1e-2 on logits for bf16 members against the
+Tolerances: relative L2 <= 1e-2 on logits for bf16 members against the
 fp32-activation oracle (mode F), <= 1e-4 for fp32; top-1 identical, judged against the
 oracle run with the same storage rounding (mode S), a near tie being reported, never dropped.
 MobileNetV2 with these synthetic weights amplifies bf16 storage noise about tenfold (the
