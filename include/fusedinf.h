@@ -49,7 +49,7 @@ typedef enum {
 } fi_status;
 
 typedef enum { FI_F32 = 0, FI_BF16 = 1 } fi_dtype;
-typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5 } fi_op;
+typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5, FI_CONCAT = 6 } fi_op;
 typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
 
 #define FI_INPUT (-1)       /* fi_layer_spec.input: the model's input tensor */
@@ -61,7 +61,11 @@ typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
  *   conv2d / depthwise: y = act(conv(x, w) + b [+ residual]); cross-correlation,
  *     zero padding, square kernel (kh == kw), floor output size.  The residual
  *     is added BEFORE the activation.  Depthwise: cin == cout, one filter/channel.
- *   maxpool2d: max over in-range taps (padding acts as -inf), floor output size.
+ *   maxpool2d: max over in-range taps (padding acts as -inf); floor output size, or with
+ *     ceil_mode the size rounded up (windows may hang over the far edge, the last one still
+ *     starts inside the input or its leading padding).
+ *   concat: the channels of `input` followed by the channels of `residual` (here: the
+ *     second source, same height and width); no activation.  cout = sum of both.
  *   global_avgpool: mean over H*W.   softmax: over the channel axis of a 1x1 tensor.
  *   fc: y = act(x W^T + b); cin = C*H*W of its input, flattened in (c,h,w) order.
  * w_off / b_off: byte offsets into the member's CANONICAL blob: weights
@@ -73,6 +77,8 @@ typedef struct {
   int32_t residual; /* node index, or FI_NO_RESIDUAL */
   int32_t cin, cout, kh, kw, stride, pad;
   int32_t act;      /* fi_act */
+  int32_t ceil_mode; /* maxpool2d only: 1 = output size rounds up */
+  int32_t reserved;
   uint64_t w_off, b_off;
 } fi_layer_spec;
 

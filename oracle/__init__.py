@@ -16,7 +16,7 @@ import numpy as np
 from . import build as _build
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_OPS = {"conv": 0, "dwconv": 1, "maxpool": 2, "gap": 3, "fc": 4, "softmax": 5}
+_OPS = {"conv": 0, "dwconv": 1, "maxpool": 2, "gap": 3, "fc": 4, "softmax": 5, "concat": 6}
 _ACTS = {"none": 0, "relu": 1, "relu6": 2}
 _DT = {"f32": 0, "bf16": 1}
 
@@ -24,7 +24,7 @@ _DT = {"f32": 0, "bf16": 1}
 class OrcLayer(C.Structure):
     _fields_ = [("op", C.c_int32), ("act", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32),
                 ("cin", C.c_int32), ("cout", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("reserved", C.c_int32), ("w_off", C.c_int64), ("b_off", C.c_int64)]
+                ("pad", C.c_int32), ("ceil_mode", C.c_int32), ("w_off", C.c_int64), ("b_off", C.c_int64)]
 
 
 _FP = C.POINTER(C.c_float)
@@ -90,11 +90,27 @@ def dwconv2d(x, w, b, stride=1, pad=0, f64=False):
     return y
 
 
-def maxpool2d(x, k, stride, pad=0):
+def _osz_ceil(n, k, stride, pad):
+    out = -((n + 2 * pad - k) // -stride) + 1
+    return out - 1 if (out - 1) * stride >= n + pad else out
+
+
+def maxpool2d(x, k, stride, pad=0, ceil=False):
     x, xp = _f(x)
     n, c, h, w = x.shape
-    y = np.empty((n, c, _osz(h, k, stride, pad), _osz(w, k, stride, pad)), dtype=np.float32)
-    lib().orc_maxpool2d(xp, n, c, h, w, k, stride, pad, y.ctypes.data_as(_FP))
+    osz = _osz_ceil if ceil else _osz
+    y = np.empty((n, c, osz(h, k, stride, pad), osz(w, k, stride, pad)), dtype=np.float32)
+    lib().orc_maxpool2d_ex(xp, n, c, h, w, k, stride, pad, int(ceil), y.ctypes.data_as(_FP))
+    return y
+
+
+def concat(a, b):
+    a, ap = _f(a)
+    b, bp = _f(b)
+    n, ca, h, w = a.shape
+    assert b.shape[0] == n and b.shape[2:] == (h, w)
+    y = np.empty((n, ca + b.shape[1], h, w), dtype=np.float32)
+    lib().orc_concat(ap, ca, bp, b.shape[1], n, h, w, y.ctypes.data_as(_FP))
     return y
 
 
@@ -150,7 +166,7 @@ def layer_table(model):
     arr = (OrcLayer * len(model.layers))()
     for i, L in enumerate(model.layers):
         arr[i] = OrcLayer(_OPS[L.op], _ACTS[L.act], L.input, L.residual, L.cin, L.cout, L.k, L.stride,
-                          L.pad, 0, L.w_off, L.b_off)
+                          L.pad, int(getattr(L, "ceil", False)), L.w_off, L.b_off)
     return arr
 
 

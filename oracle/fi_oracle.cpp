@@ -59,7 +59,7 @@ typedef ORC_ACC acc_t;
 
 extern "C" {
 
-enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5 };
+enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5, ORC_CONCAT = 6 };
 enum { ORC_NONE = 0, ORC_RELU = 1, ORC_RELU6 = 2 };
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
 
@@ -68,9 +68,9 @@ struct orc_layer {
   int32_t op;
   int32_t act;
   int32_t input;     // node index, -1 = model input
-  int32_t residual;  // node index added before the activation, < 0 = none
+  int32_t residual;  // node index added before the activation, < 0 = none; concat: the second source
   int32_t cin, cout, k, stride, pad;
-  int32_t reserved;
+  int32_t ceil_mode; // pooling: output size rounds up
   int64_t w_off, b_off;  // byte offsets into the canonical weight blob
 };
 
@@ -115,6 +115,13 @@ void orc_add(float* y, const float* skip, int64_t n) {
 }
 
 static inline int out_size(int in, int k, int s, int p) { return (in + 2 * p - k) / s + 1; }
+// Output size that rounds up: windows may hang over the far edge, but the last one must still
+// start inside the input or its leading padding.
+static inline int out_size_ceil(int in, int k, int s, int p) {
+  int out = (in + 2 * p - k + s - 1) / s + 1;
+  if ((out - 1) * s >= in + p) --out;
+  return out;
+}
 
 // ---- layers ---------------------------------------------------------------
 
@@ -172,8 +179,15 @@ void orc_dwconv2d(const float* x, int N, int C, int H, int W, const float* w, co
     }
 }
 
+void orc_maxpool2d_ex(const float* x, int N, int C, int H, int W, int k, int s, int p, int ceil_mode, float* y);
 void orc_maxpool2d(const float* x, int N, int C, int H, int W, int k, int s, int p, float* y) {
-  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+  orc_maxpool2d_ex(x, N, C, H, W, k, s, p, 0, y);
+}
+
+// Max over the taps that fall inside the image (padding and overhang are never candidates).
+void orc_maxpool2d_ex(const float* x, int N, int C, int H, int W, int k, int s, int p, int ceil_mode, float* y) {
+  const int Ho = ceil_mode ? out_size_ceil(H, k, s, p) : out_size(H, k, s, p);
+  const int Wo = ceil_mode ? out_size_ceil(W, k, s, p) : out_size(W, k, s, p);
   for (int64_t nc = 0; nc < (int64_t)N * C; ++nc) {
     const float* xc = x + nc * H * W;
     float* yc = y + nc * Ho * Wo;
@@ -189,6 +203,16 @@ void orc_maxpool2d(const float* x, int N, int C, int H, int W, int k, int s, int
           }
         yc[(int64_t)i * Wo + j] = m;
       }
+  }
+}
+
+// Channel concatenation (NCHW): image n of y holds a's Ca planes, then b's Cb planes.
+void orc_concat(const float* a, int Ca, const float* b, int Cb, int N, int H, int W, float* y) {
+  const int64_t hw = (int64_t)H * W;
+  for (int n = 0; n < N; ++n) {
+    float* yn = y + (int64_t)n * (Ca + Cb) * hw;
+    for (int64_t i = 0; i < Ca * hw; ++i) yn[i] = a[(int64_t)n * Ca * hw + i];
+    for (int64_t i = 0; i < Cb * hw; ++i) yn[Ca * hw + i] = b[(int64_t)n * Cb * hw + i];
   }
 }
 
@@ -303,9 +327,20 @@ int64_t orc_run_model(const orc_layer* layers, int n_layers, int output_node, co
         break;
       }
       case ORC_MAXPOOL: {
-        o.c = c; o.h = out_size(h, L.k, L.stride, L.pad); o.w = out_size(w, L.k, L.stride, L.pad);
+        o.c = c;
+        o.h = L.ceil_mode ? out_size_ceil(h, L.k, L.stride, L.pad) : out_size(h, L.k, L.stride, L.pad);
+        o.w = L.ceil_mode ? out_size_ceil(w, L.k, L.stride, L.pad) : out_size(w, L.k, L.stride, L.pad);
         o.v.resize((size_t)N * o.c * o.h * o.w);
-        orc_maxpool2d(in, N, c, h, w, L.k, L.stride, L.pad, o.v.data());
+        orc_maxpool2d_ex(in, N, c, h, w, L.k, L.stride, L.pad, L.ceil_mode, o.v.data());
+        break;
+      }
+      case ORC_CONCAT: {
+        if (L.residual < 0) return -1;
+        const T& s2 = val[(size_t)L.residual];
+        if (s2.h != h || s2.w != w || L.cout != c + s2.c) return -2;
+        o.c = c + s2.c; o.h = h; o.w = w;
+        o.v.resize((size_t)N * o.c * o.h * o.w);
+        orc_concat(in, c, s2.v.data(), s2.c, N, h, w, o.v.data());
         break;
       }
       case ORC_GAP: {

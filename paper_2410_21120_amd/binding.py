@@ -15,7 +15,7 @@ from . import build as _build
 
 FI_OK, FI_EINVAL, FI_EUNSUPPORTED, FI_ESTATE, FI_ENOMEM_HOST, FI_ENOMEM_DEVICE, FI_EBUDGET, FI_EHIP = range(8)
 FI_F32, FI_BF16 = 0, 1
-FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX = range(6)
+FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX, FI_CONCAT = range(7)
 FI_ACT_NONE, FI_ACT_RELU, FI_ACT_RELU6 = range(3)
 FI_INPUT, FI_NO_RESIDUAL = -1, -2
 FI_LOAD_ONE_COPY, FI_LOAD_PER_MODEL = 0, 1
@@ -27,7 +27,8 @@ STATUS_NAMES = ["FI_OK", "FI_EINVAL", "FI_EUNSUPPORTED", "FI_ESTATE", "FI_ENOMEM
 class fi_layer_spec(C.Structure):
     _fields_ = [("op", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32), ("cin", C.c_int32),
                 ("cout", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("act", C.c_int32), ("w_off", C.c_uint64), ("b_off", C.c_uint64)]
+                ("pad", C.c_int32), ("act", C.c_int32), ("ceil_mode", C.c_int32), ("reserved", C.c_int32),
+                ("w_off", C.c_uint64), ("b_off", C.c_uint64)]
 
 
 class fi_model_spec(C.Structure):
@@ -279,7 +280,7 @@ def fi_destroy(h) -> None:
 
 # ---- marshalling helpers ---------------------------------------------------------------------
 _OPS = {"conv": FI_CONV2D, "dwconv": FI_DWCONV2D, "maxpool": FI_MAXPOOL2D, "gap": FI_GLOBAL_AVGPOOL,
-        "fc": FI_FC, "softmax": FI_SOFTMAX}
+        "fc": FI_FC, "softmax": FI_SOFTMAX, "concat": FI_CONCAT}
 _ACTS = {"none": FI_ACT_NONE, "relu": FI_ACT_RELU, "relu6": FI_ACT_RELU6}
 _DT = {"f32": FI_F32, "bf16": FI_BF16}
 
@@ -290,7 +291,7 @@ def make_spec(model, weights_ptr: int, weight_bytes: int, act_dtype=None, packed
     layers = (fi_layer_spec * len(model.layers))()
     for i, L in enumerate(model.layers):
         layers[i] = fi_layer_spec(_OPS[L.op], L.input, L.residual, L.cin, L.cout, L.k, L.k, L.stride, L.pad,
-                                  _ACTS[L.act], L.w_off, L.b_off)
+                                  _ACTS[L.act], int(getattr(L, "ceil", False)), 0, L.w_off, L.b_off)
     name = model.name.encode()
     dt = _DT[model.dtype]
     spec = fi_model_spec(name, dt, dt if act_dtype is None else _DT.get(act_dtype, act_dtype), model.in_c, model.in_h,

@@ -138,6 +138,7 @@ const char* kind_name(int kind, int tile) {
     case K_SOFTMAX: return "softmax";
     case K_FC: return "fc_splitk";
     case K_REDUCE: return "splitk_reduce";
+    case K_CONCAT: return "concat";
   }
   return "?";
 }
@@ -365,6 +366,7 @@ static fi_status plan_dag(fi_dag* g) {
       case FI_DWCONV2D: nd.kind = K_DWCONV; break;
       case FI_MAXPOOL2D: nd.kind = K_MAXPOOL; break;
       case FI_GLOBAL_AVGPOOL: nd.kind = K_GAP; break;
+      case FI_CONCAT: nd.kind = K_CONCAT; break;
       default: nd.kind = K_SOFTMAX; break;
     }
   }
@@ -563,6 +565,9 @@ static fi_status plan_dag(fi_dag* g) {
       d.H = nd.H; d.W = nd.W; d.C = nd.C; d.Cp = nd.Cp;
       d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop;
       d.k = nd.k; d.stride = nd.stride; d.pad = nd.pad; d.act = nd.act; d.Kp = nd.Kp;
+      if (nd.op == FI_CONCAT) {  // second source: channels in Kp, channel stride in tiles_n (set below)
+        d.Kp = g->nodes[(size_t)nd.residual].Co;
+      }
       if (nd.op == FI_FC) {  // a fully connected node is a 1x1 convolution over the flattened input
         d.C = d.Cp = nd.H * nd.W * nd.Cp; d.H = d.W = 1; d.k = 1; d.stride = 1; d.pad = 0;
       }
@@ -574,6 +579,11 @@ static fi_status plan_dag(fi_dag* g) {
       d.splits = std::max(1, nd.splits);
       d.ws_off = g->act_bytes + nd.ws_off;  // the workspace follows the activation arena
       if (L.kind == K_FC) d.tiles_n = (nd.Co + 31) / 32;
+      if (L.kind == K_CONCAT) {
+        const Node& second = g->nodes[(size_t)nd.residual];
+        d.tiles_n = second.Cop;
+        d.vec = (d.vec && nd.C % 8 == 0 && second.Cop % 8 == 0) ? 1 : 0;  // whole 8-channel vectors come from one source
+      }
       if (L.kind == K_REDUCE) {
         L.act_bytes += ((uint64_t)nd.splits * nd.Cop * 4 + (uint64_t)nd.Co * esize(nd.out_dtype)) * nd.Ho * nd.Wo;
         continue;

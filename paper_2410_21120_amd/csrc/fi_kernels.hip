@@ -52,6 +52,7 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
+    case K_CONCAT: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
   }
   return 0;
 }
@@ -588,6 +589,43 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// channel concatenation: output pixel = C channels of the first source (stride Cp), then Kp
+// channels of the second (stride tiles_n), then zero padding up to Cop
+// ---------------------------------------------------------------------------------
+template <typename TA>
+__global__ void __launch_bounds__(256) concat_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_CONCAT, 0, p, bid)) return;
+  const Desc d = a.d[p];
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  const TA* xa = reinterpret_cast<const TA*>(a.abase + d.x_off);
+  const TA* xb = reinterpret_cast<const TA*>(a.abase + d.r_off);
+  const int64_t M = (int64_t)a.batch * d.Ho * d.Wo;
+  if (sizeof(TA) == 2 && d.vec) {  // C % 8 == 0: an 8-channel vector never straddles the two sources
+    const int cv = d.Cop / 8;
+    if (idx >= M * cv) return;
+    const int c8 = (int)(idx % cv) * 8;
+    const int64_t m = idx / cv;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (c8 < d.C) v = *reinterpret_cast<const uint4*>(xa + m * d.Cp + c8);
+    else if (c8 - d.C < d.tiles_n) v = *reinterpret_cast<const uint4*>(xb + m * d.tiles_n + (c8 - d.C));  // the source's own pad channels are zero
+    *reinterpret_cast<uint4*>(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c8) = v;
+    return;
+  }
+  if (idx >= M * d.Cop) return;
+  const int c = (int)(idx % d.Cop);
+  const int64_t m = idx / d.Cop;
+  float v = 0.0f;
+  if (c < d.C) v = ld(xa + m * d.Cp + c);
+  else if (c - d.C < d.Kp) v = ld(xb + m * d.tiles_n + (c - d.C));
+  if (d.ext) {
+    if (c < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + c] = v;
+  } else {
+    st(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c, v);
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // depthwise convolution: one thread per (pixel, channel), channel fastest (coalesced)
 // ---------------------------------------------------------------------------------
 template <typename TW, typename TA>
@@ -1059,6 +1097,8 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       return ab ? go(reduce_kernel<bf16_t>, nb, 256, a, s) : go(reduce_kernel<float>, nb, 256, a, s);
     case K_SOFTMAX:
       return go(softmax_kernel, nb, 64, a, s);
+    case K_CONCAT:
+      return ab ? go(concat_kernel<bf16_t>, nb, 256, a, s) : go(concat_kernel<float>, nb, 256, a, s);
   }
   return (int)hipErrorInvalidValue;
 }

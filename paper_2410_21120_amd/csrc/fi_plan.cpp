@@ -91,8 +91,24 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         n.Ho = (n.H + 2 * L.pad - L.kh) / L.stride + 1;
         n.Wo = (n.W + 2 * L.pad - L.kh) / L.stride + 1;
         if (n.Ho < 1 || n.Wo < 1 || n.H + 2 * L.pad < L.kh) { set_error("model %s node %d: empty output", nm, i); return FI_EINVAL; }
+        if (L.ceil_mode) {  // round up, but the last window must start inside the input or its leading padding
+          n.Ho = (n.H + 2 * L.pad - L.kh + L.stride - 1) / L.stride + 1;
+          n.Wo = (n.W + 2 * L.pad - L.kh + L.stride - 1) / L.stride + 1;
+          if ((n.Ho - 1) * L.stride >= n.H + L.pad) --n.Ho;
+          if ((n.Wo - 1) * L.stride >= n.W + L.pad) --n.Wo;
+        }
         if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: pooling takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
         break;
+      case FI_CONCAT: {
+        if (L.residual == FI_NO_RESIDUAL) { set_error("model %s node %d: concat needs a second source", nm, i); return FI_EINVAL; }
+        const Node& b = out.nodes[(size_t)L.residual];
+        if (L.input == FI_INPUT) { set_error("model %s node %d: concat of the model input is not supported", nm, i); return FI_EUNSUPPORTED; }
+        if (b.Ho != n.H || b.Wo != n.W) { set_error("model %s node %d: concat sources differ in height or width", nm, i); return FI_EINVAL; }
+        if (L.act != FI_ACT_NONE) { set_error("model %s node %d: concat takes no activation", nm, i); return FI_EUNSUPPORTED; }
+        n.Co = n.C + b.Co; n.Ho = n.H; n.Wo = n.W;
+        if (L.cout != n.Co) { set_error("model %s node %d: concat cout %d != %d + %d", nm, i, L.cout, n.C, b.Co); return FI_EINVAL; }
+        break;
+      }
       case FI_GLOBAL_AVGPOOL:
         n.Co = n.C; n.Ho = 1; n.Wo = 1;
         if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: pooling takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
@@ -113,7 +129,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         return FI_EUNSUPPORTED;
     }
     n.Cop = round_up(n.Co, g);
-    if (L.residual != FI_NO_RESIDUAL) {
+    if (L.residual != FI_NO_RESIDUAL && L.op != FI_CONCAT) {
       const Node& r = out.nodes[(size_t)L.residual];
       if (r.Co != n.Co || r.Ho != n.Ho || r.Wo != n.Wo) {
         set_error("model %s node %d: residual shape mismatch", nm, i); return FI_EINVAL; }

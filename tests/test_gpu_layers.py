@@ -120,6 +120,62 @@ def test_maxpool_exact(case, mode):
     assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, False))
 
 
+@pytest.mark.parametrize("case", [(16, 24, 13, 15), (8, 8, 6, 6), (20, 12, 9, 7), (64, 64, 28, 28)])   # channels of the two sources, H, W
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_concat_of_two_branches(case, mode):
+    """Concatenation followed by a convolution that mixes all channels: vector path (first source a multiple
+    of 8 channels) and element path (20 + 12), padded channel strides on both sides."""
+    ca, cb, h, w = case
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("cat", dtype, 8, h, w)
+    a = m.add(zoo.CONV, -1, cin=8, cout=ca, k=1, stride=1, pad=0, act=zoo.RELU)
+    b = m.add(zoo.CONV, -1, cin=8, cout=cb, k=3, stride=1, pad=1, act=zoo.RELU)
+    c = m.add(zoo.CONCAT, a, residual=b)
+    m.add(zoo.CONV, c, cin=ca + cb, cout=10, k=1, stride=1, pad=0, act=zoo.NONE)
+    _run_case(m, 500 + ca + cb, 2, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+def test_concat_as_output_node_is_exact():
+    """A concat that is the member's output copies values: the fp32 result equals the oracle's exactly in
+    storage-rounding mode (both sides hold the same bf16 values)."""
+    from tests import harness
+    m = zoo.Model("cat_out", "bf16", 8, 8, 10)
+    a = m.add(zoo.MAXPOOL, -1, k=3, stride=2, pad=0, ceil=True)
+    b = m.add(zoo.MAXPOOL, -1, k=2, stride=2, pad=0, ceil=True)
+    m.add(zoo.CONCAT, a, residual=b)
+    m.shapes()
+    blob = np.zeros(64, np.uint8)   # no weighted node
+    x = gen.make_input(3, 2, 8, 8, 10, "normal", "bf16")
+    g = harness.GpuDag([(m, blob, None)], 2)
+    try:
+        y = g.run(x)[0]
+    finally:
+        g.close()
+    assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, True))
+
+
+@pytest.mark.parametrize("case", [(64, 3, 2, 0, 23, 24, 2), (16, 3, 2, 0, 8, 8, 1), (24, 3, 1, 1, 14, 14, 2), (40, 2, 2, 0, 7, 9, 3), (8, 2, 2, 1, 5, 5, 1)])
+@pytest.mark.parametrize("mode", ["bf16", "f32"])
+def test_maxpool_ceil_mode_exact(case, mode):
+    """Pooling whose size rounds up: windows hang over the far edge; those taps never win (all-negative input)."""
+    from tests import harness
+    c, k, s, p, h, w, b = case
+    m = zoo.Model("pc", mode, c, h, w)
+    m.add(zoo.MAXPOOL, -1, k=k, stride=s, pad=p, ceil=True)
+    m.shapes()
+    blob = np.zeros(64, np.uint8)   # no weighted node
+    x = -np.abs(gen.make_input(3, b, c, h, w, "normal", mode)) - 0.5
+    if mode == "bf16":
+        x = gen.bf16_to_f32(gen.bf16_bits(x)).reshape(x.shape)
+    g = harness.GpuDag([(m, blob, None)], b)
+    try:
+        y = g.run(x)[0]
+    finally:
+        g.close()
+    ref = harness.oracle_nhwc(m, blob, x, False)
+    assert y.shape == ref.shape and np.array_equal(y, ref)
+
+
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_gap_fc_softmax_chain(mode):
     dtype = "f32" if mode == "f32" else "bf16"

@@ -428,3 +428,34 @@ def test_maximum_sizes_are_refused_at_build_time():
     with pytest.raises(fi.FiError) as e:
         fi.fi_footprint([rspec], fi.make_opts(1 << 14, alloc))   # 2^14 x 2^10 = 2^24 output pixels
     assert e.value.status == fi.FI_EUNSUPPORTED and "2^24" in str(e.value)
+
+
+def test_concat_and_ceil_pooling_in_the_planner():
+    """A concat node has the channels of both sources and reads both (live ranges extend to it); pooling with
+    ceil_mode takes the rounded-up size; malformed concats are refused."""
+    m = zoo.Model("cat", "bf16", 8, 9, 9)
+    a = m.add(zoo.CONV, -1, cin=8, cout=16, k=1, stride=1, pad=0, act=zoo.RELU)
+    b = m.add(zoo.CONV, -1, cin=8, cout=24, k=3, stride=1, pad=1, act=zoo.RELU)
+    c = m.add(zoo.CONCAT, a, residual=b)
+    p = m.add(zoo.MAXPOOL, c, k=2, stride=2, pad=0, ceil=True)
+    m.add(zoo.CONV, p, cin=40, cout=10, k=1, stride=1, pad=0)
+    m.shapes()
+    blob = gen.make_blob(m, 1)
+    spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    d = fi.Dag([spec], 2, fi.HostAllocators(), keepalive=keep)
+    nodes = d.nodes()
+    assert (nodes[2].out_c, nodes[2].out_h, nodes[2].out_w) == (40, 9, 9)
+    assert (nodes[3].out_h, nodes[3].out_w) == (5, 5)                      # floor would give 4
+    assert nodes[0].last_level >= nodes[2].level and nodes[1].last_level >= nodes[2].level
+    assert "concat" in [L.name.decode() for L in d.launches()]
+
+    def broken(edit):
+        spec2, keep2 = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+        edit(spec2)
+        with pytest.raises(fi.FiError) as e:
+            fi.Dag([spec2], 2, fi.HostAllocators(), keepalive=keep2)
+        return e.value.status
+    assert broken(lambda s: setattr(s.layers[2], "residual", fi.FI_NO_RESIDUAL)) == fi.FI_EINVAL     # no second source
+    assert broken(lambda s: setattr(s.layers[2], "cout", 41)) == fi.FI_EINVAL                        # wrong channel sum
+    assert broken(lambda s: setattr(s.layers[2], "act", fi.FI_ACT_RELU)) == fi.FI_EUNSUPPORTED
+    assert broken(lambda s: setattr(s.layers[1], "stride", 2)) == fi.FI_EINVAL                       # sources differ in size

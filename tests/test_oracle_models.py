@@ -26,11 +26,11 @@ def test_structure(fam):
     assert len(ops) == g["nodes"]
     assert (ops.count("conv"), ops.count("dwconv"), ops.count("maxpool"), ops.count("gap"), ops.count("fc")) == \
         (g["conv"], g["dwconv"], g["maxpool"], g["gap"], g["fc"])
+    assert ops.count("concat") == g.get("concat", 0)
     assert max(m.levels()) == g["depth"]
     assert m.n_params() == g["params"]
     assert m.macs() == g["macs"]
-    fc_or_sm = m.layers[m.output]
-    assert fc_or_sm.cout == g["classes"]
+    assert m.layers[m.output].cout == g["classes"]
     if "gmacs_published" in g:
         assert round(m.macs() / 1e9, 2) == g["gmacs_published"]
     if "params_with_batchnorm" in g:  # folding removes one of BatchNorm's two parameters per normalised channel
@@ -86,14 +86,16 @@ def _torch_forward(model, blob, x, dtype=torch.float64):
         elif L.op == "dwconv":
             y = F.conv2d(inp, w.reshape(L.cout, 1, L.k, L.k), b, stride=L.stride, padding=L.pad, groups=L.cout)
         elif L.op == "maxpool":
-            y = F.max_pool2d(inp, L.k, L.stride, L.pad)
+            y = F.max_pool2d(inp, L.k, L.stride, L.pad, ceil_mode=bool(L.ceil))
+        elif L.op == "concat":
+            y = torch.cat([inp, vals[L.residual]], dim=1)
         elif L.op == "gap":
             y = inp.mean(dim=(2, 3), keepdim=True)
         elif L.op == "fc":
             y = F.linear(inp.reshape(inp.shape[0], -1), w.reshape(L.cout, L.cin), b).reshape(-1, L.cout, 1, 1)
         elif L.op == "softmax":
             y = torch.softmax(inp.reshape(inp.shape[0], -1), dim=1).reshape(inp.shape)
-        if L.residual >= 0:
+        if L.residual >= 0 and L.op != "concat":
             y = y + vals[L.residual]
         if L.act == "relu":
             y = torch.relu(y)
@@ -107,7 +109,8 @@ def _rel(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
 
 
-@pytest.mark.parametrize("fam,hw", [("tiny", 32), ("resnet18", 64), ("resnet50", 64), ("mobilenetv2", 64), ("vgg16", 32)])
+@pytest.mark.parametrize("fam,hw", [("tiny", 32), ("resnet18", 64), ("resnet50", 64), ("mobilenetv2", 64), ("vgg16", 32),
+                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70)])
 def test_model_runner_vs_library_forward(fam, hw):
     m = zoo.tiny_cnn() if fam == "tiny" else zoo.FAMILIES[fam](hw=hw)
     blob = gen.make_blob(m, 1000 + hw)

@@ -180,6 +180,32 @@ def test_maxpool_closed_forms():
     assert oracle.maxpool2d(np.zeros((1, 1, 7, 7), np.float32), 2, 2, 0).shape == (1, 1, 3, 3)
 
 
+def test_maxpool_ceil_mode_and_concat(rng):
+    """Rounding the pooled size up lets windows hang over the far edge (those taps are never candidates) but
+    never adds a window that starts past the input; the ramp's closed form and a library routine pin it.
+    Concatenation is plane order: a's channels, then b's."""
+    import torch.nn.functional as F
+    x = np.arange(7 * 7, dtype=np.float32).reshape(1, 1, 7, 7)
+    y = oracle.maxpool2d(x, 3, 2, 0, ceil=True)          # floor gives 3x3, ceil also 3x3: (7-3)/2 is whole
+    assert y.shape == (1, 1, 3, 3) and np.array_equal(y, oracle.maxpool2d(x, 3, 2, 0))
+    x = np.arange(8 * 8, dtype=np.float32).reshape(1, 1, 8, 8)
+    y = oracle.maxpool2d(x, 3, 2, 0, ceil=True)          # floor 3x3, ceil 4x4: the last window holds rows/cols 6..7 only
+    assert y.shape == (1, 1, 4, 4)
+    want = np.array([[min(2 * i + 2, 7) * 8 + min(2 * j + 2, 7) for j in range(4)] for i in range(4)], dtype=np.float32)
+    assert np.array_equal(y[0, 0], want)
+    assert oracle.maxpool2d(np.zeros((1, 1, 5, 5), np.float32), 2, 2, 1, ceil=True).shape == (1, 1, 3, 3)  # not 4: window 3 would start in the padding past the input
+    for (h, w, k, s, p) in [(13, 13, 3, 2, 0), (55, 57, 3, 2, 0), (7, 9, 3, 2, 1), (14, 14, 3, 1, 1), (27, 28, 3, 2, 0), (6, 6, 3, 2, 0), (5, 8, 2, 2, 0)]:
+        x = -np.abs(rng.standard_normal((2, 3, h, w))).astype(np.float32)   # all negative: a zero from padding or overhang would win
+        y = oracle.maxpool2d(x, k, s, p, ceil=True)
+        ref = F.max_pool2d(torch.from_numpy(x), k, s, p, ceil_mode=True).numpy()
+        assert y.shape == ref.shape and np.array_equal(y, ref)
+    a = rng.standard_normal((2, 3, 4, 5)).astype(np.float32)
+    b = rng.standard_normal((2, 2, 4, 5)).astype(np.float32)
+    y = oracle.concat(a, b)
+    assert y.shape == (2, 5, 4, 5) and np.array_equal(y[:, :3], a) and np.array_equal(y[:, 3:], b)
+    assert np.array_equal(oracle.concat(a, a[:, :0]), a)
+
+
 def test_global_avgpool_closed_forms():
     h, w = 7, 7
     ramp = np.arange(h * w, dtype=np.float32).reshape(1, 1, h, w)

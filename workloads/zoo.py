@@ -21,7 +21,7 @@ from typing import List
 
 # operator / activation names (strings on purpose: each executor maps them to
 # its own enum, so the two sides share no numeric constants)
-CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX = "conv", "dwconv", "maxpool", "gap", "fc", "softmax"
+CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX, CONCAT = "conv", "dwconv", "maxpool", "gap", "fc", "softmax", "concat"
 NONE, RELU, RELU6 = "none", "relu", "relu6"
 NO_RESIDUAL = -2
 MODEL_INPUT = -1
@@ -37,7 +37,8 @@ class Layer:
     stride: int = 1
     pad: int = 0
     act: str = NONE
-    residual: int = NO_RESIDUAL
+    residual: int = NO_RESIDUAL   # node added before the activation; for a concat node: the second source
+    ceil: bool = False            # pooling: output size rounds up (windows may hang over the bottom / right edge)
     # filled by shapes(): logical input / output spatial sizes
     in_h: int = 0
     in_w: int = 0
@@ -67,7 +68,14 @@ class Model:
 
     # -- derived facts used by structural pins ------------------------------
     def shapes(self) -> "Model":
-        """Fill in per-node logical shapes (floor output size everywhere)."""
+        """Fill in per-node logical shapes (floor output size, except pooling nodes that ask for ceil)."""
+        def pooled(n, L):
+            if not L.ceil:
+                return (n + 2 * L.pad - L.k) // L.stride + 1
+            out = -((n + 2 * L.pad - L.k) // -L.stride) + 1
+            if (out - 1) * L.stride >= n + L.pad:   # the last window must start inside the input or its left padding
+                out -= 1
+            return out
         dims = {}
         for i, L in enumerate(self.layers):
             c, h, w = (self.in_c, self.in_h, self.in_w) if L.input == MODEL_INPUT else dims[L.input]
@@ -77,10 +85,13 @@ class Model:
                 wo = (w + 2 * L.pad - L.k) // L.stride + 1
                 dims[i] = (L.cout, ho, wo)
             elif L.op == MAXPOOL:
-                ho = (h + 2 * L.pad - L.k) // L.stride + 1
-                wo = (w + 2 * L.pad - L.k) // L.stride + 1
                 L.cin = L.cout = c
-                dims[i] = (c, ho, wo)
+                dims[i] = (c, pooled(h, L), pooled(w, L))
+            elif L.op == CONCAT:   # channels of `input`, then channels of `residual`
+                c2, h2, w2 = dims[L.residual]
+                assert (h2, w2) == (h, w), (self.name, i)
+                L.cin, L.cout = c, c + c2
+                dims[i] = (c + c2, h, w)
             elif L.op == GAP:
                 L.cin = L.cout = c
                 dims[i] = (c, 1, 1)
@@ -324,9 +335,70 @@ def mnasnet1_0(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model
     return m.shapes()
 
 
+def squeezenet1_1(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    """SqueezeNet 1.1 (Iandola et al. 2016, the lighter revision): fire modules = 1x1 squeeze, then 1x1 and
+    3x3 expands side by side, concatenated; 3x3/2 max pooling with the size rounded up; a 1x1 classifier
+    convolution followed by global average pooling (no fully connected layer, no BatchNorm)."""
+    m = Model("squeezenet1_1", dtype, 3, hw, hw)
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=64, k=3, stride=2, pad=0, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0, ceil=True)
+    cin = 64
+    for idx, (sq, ex) in enumerate(((16, 64), (16, 64), (32, 128), (32, 128), (48, 192), (48, 192), (64, 256), (64, 256))):
+        if idx in (2, 4):
+            x = m.add(MAXPOOL, x, k=3, stride=2, pad=0, ceil=True)
+        q = m.add(CONV, x, cin=cin, cout=sq, k=1, stride=1, pad=0, act=RELU)
+        e1 = m.add(CONV, q, cin=sq, cout=ex, k=1, stride=1, pad=0, act=RELU)
+        e3 = m.add(CONV, q, cin=sq, cout=ex, k=3, stride=1, pad=1, act=RELU)
+        x = m.add(CONCAT, e1, residual=e3)
+        cin = 2 * ex
+    x = m.add(CONV, x, cin=512, cout=classes, k=1, stride=1, pad=0, act=RELU)
+    m.add(GAP, x)
+    return m.shapes()
+
+
+def googlenet(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    """GoogLeNet / Inception v1 (Szegedy et al. 2015) in its BatchNorm form without auxiliary heads: every
+    inception module concatenates a 1x1 branch, a 1x1 -> 3x3 branch, a second 1x1 -> 3x3 branch (the widely
+    used implementation's stand-in for the 5x5) and a 3x3/1 max pool -> 1x1 branch."""
+    m = Model("googlenet", dtype, 3, hw, hw)
+
+    def inception(x, cin, c1, c3r, c3, c5r, c5, cp):
+        b1 = m.add(CONV, x, cin=cin, cout=c1, k=1, stride=1, pad=0, act=RELU)
+        b2 = m.add(CONV, x, cin=cin, cout=c3r, k=1, stride=1, pad=0, act=RELU)
+        b2 = m.add(CONV, b2, cin=c3r, cout=c3, k=3, stride=1, pad=1, act=RELU)
+        b3 = m.add(CONV, x, cin=cin, cout=c5r, k=1, stride=1, pad=0, act=RELU)
+        b3 = m.add(CONV, b3, cin=c5r, cout=c5, k=3, stride=1, pad=1, act=RELU)
+        b4 = m.add(MAXPOOL, x, k=3, stride=1, pad=1, ceil=True)
+        b4 = m.add(CONV, b4, cin=cin, cout=cp, k=1, stride=1, pad=0, act=RELU)
+        y = m.add(CONCAT, b1, residual=b2)
+        y = m.add(CONCAT, y, residual=b3)
+        return m.add(CONCAT, y, residual=b4), c1 + c3 + c5 + cp
+
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=64, k=7, stride=2, pad=3, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0, ceil=True)
+    x = m.add(CONV, x, cin=64, cout=64, k=1, stride=1, pad=0, act=RELU)
+    x = m.add(CONV, x, cin=64, cout=192, k=3, stride=1, pad=1, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0, ceil=True)
+    c = 192
+    for cfg in ((64, 96, 128, 16, 32, 32), (128, 128, 192, 32, 96, 64)):
+        x, c = inception(x, c, *cfg)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0, ceil=True)
+    for cfg in ((192, 96, 208, 16, 48, 64), (160, 112, 224, 24, 64, 64), (128, 128, 256, 24, 64, 64),
+                (112, 144, 288, 32, 64, 64), (256, 160, 320, 32, 128, 128)):
+        x, c = inception(x, c, *cfg)
+    x = m.add(MAXPOOL, x, k=2, stride=2, pad=0, ceil=True)
+    for cfg in ((256, 160, 320, 32, 128, 128), (384, 192, 384, 48, 128, 128)):
+        x, c = inception(x, c, *cfg)
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=1024, cout=classes)
+    return m.shapes()
+
+
 FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             "mobilenetv2": mobilenetv2, "vgg16": vgg16,
             # further families of the paper's Table III that need no operator beyond the five above
             "alexnet": alexnet, "vgg11": vgg11, "vgg13": vgg13, "vgg19": vgg19,
             "resnet34": resnet34, "resnet101": resnet101, "resnet152": resnet152,
-            "wide_resnet50_2": wide_resnet50_2, "wide_resnet101_2": wide_resnet101_2, "mnasnet1_0": mnasnet1_0}
+            "wide_resnet50_2": wide_resnet50_2, "wide_resnet101_2": wide_resnet101_2, "mnasnet1_0": mnasnet1_0,
+            # ... and two that add channel concatenation and pooling sizes that round up
+            "squeezenet1_1": squeezenet1_1, "googlenet": googlenet}
