@@ -61,6 +61,9 @@ typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
  *   conv2d / depthwise: y = act(conv(x, w) + b [+ residual]); cross-correlation,
  *     zero padding, square kernel (kh == kw), floor output size.  The residual
  *     is added BEFORE the activation.  Depthwise: cin == cout, one filter/channel.
+ *     conv2d with groups = G > 1: output channel o sees only the input channels of
+ *     its group o / (cout/G); canonical weights are then [cout][cin/G][kh][kw].  (Packed
+ *     as block-diagonal dense rows: exact, at dense cost.)
  *   maxpool2d: max over in-range taps (padding acts as -inf); floor output size, or with
  *     ceil_mode the size rounded up (windows may hang over the far edge, the last one still
  *     starts inside the input or its leading padding).
@@ -78,7 +81,7 @@ typedef struct {
   int32_t cin, cout, kh, kw, stride, pad;
   int32_t act;      /* fi_act */
   int32_t ceil_mode; /* maxpool2d only: 1 = output size rounds up */
-  int32_t reserved;
+  int32_t groups;    /* conv2d only: channel groups (0 or 1 = dense); must divide cin and cout */
   uint64_t w_off, b_off;
 } fi_layer_spec;
 

@@ -24,7 +24,8 @@ _DT = {"f32": 0, "bf16": 1}
 class OrcLayer(C.Structure):
     _fields_ = [("op", C.c_int32), ("act", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32),
                 ("cin", C.c_int32), ("cout", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("ceil_mode", C.c_int32), ("w_off", C.c_int64), ("b_off", C.c_int64)]
+                ("pad", C.c_int32), ("ceil_mode", C.c_int32), ("w_off", C.c_int64), ("b_off", C.c_int64),
+                ("groups", C.c_int32), ("reserved", C.c_int32)]
 
 
 _FP = C.POINTER(C.c_float)
@@ -37,6 +38,9 @@ def lib(f64: bool = False):
         _build.build(force=False)
         L = C.CDLL(os.path.join(_HERE, "liboracle_f64.so" if f64 else "liboracle.so"))
         L.orc_conv2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
+        L.orc_conv2d_grouped.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
+        L.orc_maxpool2d_ex.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
+        L.orc_concat.argtypes = [_FP, C.c_int, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_dwconv2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_maxpool2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_global_avgpool.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
@@ -75,6 +79,19 @@ def conv2d(x, w, b, stride=1, pad=0, f64=False):
         b, bp = _f(b)
     y = np.empty((n, o, _osz(h, k, stride, pad), _osz(ww, k, stride, pad)), dtype=np.float32)
     lib(f64).orc_conv2d(xp, n, c, h, ww, wp, bp, o, k, stride, pad, y.ctypes.data_as(_FP))
+    return y
+
+
+def conv2d_grouped(x, w, b, groups, stride=1, pad=0, f64=False):
+    x, xp = _f(x); w, wp = _f(w)
+    n, c, h, ww = x.shape
+    o, ci, k, _ = w.shape
+    assert ci * groups == c and o % groups == 0
+    bp = None
+    if b is not None:
+        b, bp = _f(b)
+    y = np.empty((n, o, _osz(h, k, stride, pad), _osz(ww, k, stride, pad)), dtype=np.float32)
+    lib(f64).orc_conv2d_grouped(xp, n, c, h, ww, wp, bp, o, k, stride, pad, groups, y.ctypes.data_as(_FP))
     return y
 
 
@@ -166,7 +183,7 @@ def layer_table(model):
     arr = (OrcLayer * len(model.layers))()
     for i, L in enumerate(model.layers):
         arr[i] = OrcLayer(_OPS[L.op], _ACTS[L.act], L.input, L.residual, L.cin, L.cout, L.k, L.stride,
-                          L.pad, int(getattr(L, "ceil", False)), L.w_off, L.b_off)
+                          L.pad, int(getattr(L, "ceil", False)), L.w_off, L.b_off, int(getattr(L, "groups", 1)), 0)
     return arr
 
 

@@ -72,6 +72,8 @@ struct orc_layer {
   int32_t cin, cout, k, stride, pad;
   int32_t ceil_mode; // pooling: output size rounds up
   int64_t w_off, b_off;  // byte offsets into the canonical weight blob
+  int32_t groups;        // conv: number of channel groups (0 or 1 = dense)
+  int32_t reserved;
 };
 
 // ---- scalar helpers -------------------------------------------------------
@@ -157,6 +159,27 @@ void orc_conv2d(const float* x, int N, int C, int H, int W, const float* w, cons
           for (int t = 0; t < k; ++t)
             tap_accumulate(plane.data(), x + ((int64_t)n * C + c) * H * W,
                            w[(((int64_t)o * C + c) * k + r) * k + t], H, W, Ho, Wo, s, p, r, t);
+      float* yo = y + ((int64_t)n * O + o) * Ho * Wo;
+      for (size_t q = 0; q < plane.size(); ++q) yo[q] = (float)plane[q];
+    }
+}
+
+// Grouped convolution: output channel o belongs to group g = o / (O/G) and sees only the input channels
+// [g*C/G, (g+1)*C/G); w is [O][C/G][k][k].  G == 1 is orc_conv2d, G == C == O is the depthwise case.
+void orc_conv2d_grouped(const float* x, int N, int C, int H, int W, const float* w, const float* b, int O,
+                        int k, int s, int p, int G, float* y) {
+  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+  const int cg = C / G, og = O / G;
+  std::vector<acc_t> plane((size_t)Ho * Wo);
+  for (int n = 0; n < N; ++n)
+    for (int o = 0; o < O; ++o) {
+      const int g = o / og;
+      for (size_t q = 0; q < plane.size(); ++q) plane[q] = (acc_t)(b ? b[o] : 0.0f);
+      for (int c = 0; c < cg; ++c)
+        for (int r = 0; r < k; ++r)
+          for (int t = 0; t < k; ++t)
+            tap_accumulate(plane.data(), x + ((int64_t)n * C + g * cg + c) * H * W,
+                           w[(((int64_t)o * cg + c) * k + r) * k + t], H, W, Ho, Wo, s, p, r, t);
       float* yo = y + ((int64_t)n * O + o) * Ho * Wo;
       for (size_t q = 0; q < plane.size(); ++q) yo[q] = (float)plane[q];
     }
@@ -312,9 +335,12 @@ int64_t orc_run_model(const orc_layer* layers, int n_layers, int output_node, co
         if (L.cin != c) return -2;
         o.c = L.cout; o.h = out_size(h, L.k, L.stride, L.pad); o.w = out_size(w, L.k, L.stride, L.pad);
         o.v.resize((size_t)N * o.c * o.h * o.w);
-        std::vector<float> wt = read_tensor(blob, L.w_off, (int64_t)L.cout * L.cin * L.k * L.k, dtype);
+        const int G = L.groups > 1 ? L.groups : 1;
+        if (L.cin % G || L.cout % G) return -2;
+        std::vector<float> wt = read_tensor(blob, L.w_off, (int64_t)L.cout * (L.cin / G) * L.k * L.k, dtype);
         std::vector<float> bs = read_tensor(blob, L.b_off, L.cout, ORC_F32);
-        orc_conv2d(in, N, c, h, w, wt.data(), bs.data(), L.cout, L.k, L.stride, L.pad, o.v.data());
+        if (G == 1) orc_conv2d(in, N, c, h, w, wt.data(), bs.data(), L.cout, L.k, L.stride, L.pad, o.v.data());
+        else orc_conv2d_grouped(in, N, c, h, w, wt.data(), bs.data(), L.cout, L.k, L.stride, L.pad, G, o.v.data());
         break;
       }
       case ORC_DWCONV: {

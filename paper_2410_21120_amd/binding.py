@@ -27,7 +27,7 @@ STATUS_NAMES = ["FI_OK", "FI_EINVAL", "FI_EUNSUPPORTED", "FI_ESTATE", "FI_ENOMEM
 class fi_layer_spec(C.Structure):
     _fields_ = [("op", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32), ("cin", C.c_int32),
                 ("cout", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("act", C.c_int32), ("ceil_mode", C.c_int32), ("reserved", C.c_int32),
+                ("pad", C.c_int32), ("act", C.c_int32), ("ceil_mode", C.c_int32), ("groups", C.c_int32),
                 ("w_off", C.c_uint64), ("b_off", C.c_uint64)]
 
 
@@ -291,7 +291,7 @@ def make_spec(model, weights_ptr: int, weight_bytes: int, act_dtype=None, packed
     layers = (fi_layer_spec * len(model.layers))()
     for i, L in enumerate(model.layers):
         layers[i] = fi_layer_spec(_OPS[L.op], L.input, L.residual, L.cin, L.cout, L.k, L.k, L.stride, L.pad,
-                                  _ACTS[L.act], int(getattr(L, "ceil", False)), 0, L.w_off, L.b_off)
+                                  _ACTS[L.act], int(getattr(L, "ceil", False)), int(getattr(L, "groups", 1)), L.w_off, L.b_off)
     name = model.name.encode()
     dt = _DT[model.dtype]
     spec = fi_model_spec(name, dt, dt if act_dtype is None else _DT.get(act_dtype, act_dtype), model.in_c, model.in_h,

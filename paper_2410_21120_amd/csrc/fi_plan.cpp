@@ -78,11 +78,14 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         if (L.cin != n.C) { set_error("model %s node %d: cin %d != producer channels %d", nm, i, L.cin, n.C); return FI_EINVAL; }
         if (L.kh > 15) { set_error("model %s node %d: kernels larger than 15x15 are not supported", nm, i); return FI_EUNSUPPORTED; }
         if (L.op == FI_DWCONV2D && L.cout != L.cin) { set_error("model %s node %d: depthwise needs cin == cout", nm, i); return FI_EINVAL; }
+        if (L.groups > 1 && (L.op != FI_CONV2D || L.cin % L.groups || L.cout % L.groups)) {
+          set_error("model %s node %d: %d groups do not divide cin %d and cout %d of a conv2d", nm, i, L.groups, L.cin, L.cout); return FI_EINVAL; }
+        if (L.groups < 0) { set_error("model %s node %d: negative groups", nm, i); return FI_EINVAL; }
         n.k = L.kh; n.stride = L.stride; n.pad = L.pad; n.Co = L.cout;
         n.Ho = (n.H + 2 * L.pad - L.kh) / L.stride + 1;
         n.Wo = (n.W + 2 * L.pad - L.kh) / L.stride + 1;
         if (n.Ho < 1 || n.Wo < 1 || n.H + 2 * L.pad < L.kh) { set_error("model %s node %d: empty output", nm, i); return FI_EINVAL; }
-        n.macs = (uint64_t)n.Ho * n.Wo * n.Co * (uint64_t)(L.op == FI_CONV2D ? n.C : 1) * L.kh * L.kh;
+        n.macs = (uint64_t)n.Ho * n.Wo * n.Co * (uint64_t)(L.op == FI_CONV2D ? n.C / (L.groups > 1 ? L.groups : 1) : 1) * L.kh * L.kh;
         break;
       case FI_MAXPOOL2D:
         if (L.kh != L.kw || L.kh < 1 || L.stride < 1 || L.pad < 0 || 2 * L.pad > L.kh) {
@@ -144,7 +147,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
       n.w_rel = off; off = align_up(off + wbytes);
       n.b_rel = off; off = align_up(off + (uint64_t)n.Cop * 4);
       // canonical blob bounds
-      const uint64_t cw = (L.op == FI_CONV2D ? (uint64_t)n.Co * n.C * n.k * n.k
+      const uint64_t cw = (L.op == FI_CONV2D ? (uint64_t)n.Co * (n.C / (L.groups > 1 ? L.groups : 1)) * n.k * n.k
                            : L.op == FI_FC  ? (uint64_t)n.Co * L.cin : (uint64_t)n.Co * n.k * n.k) * wsz;
       if (!m.weights_packed && m.weights &&
           (L.w_off + cw > m.weight_bytes || L.b_off + (uint64_t)n.Co * 4 > m.weight_bytes)) {
@@ -197,13 +200,18 @@ static void pack_typed(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst8
     T* d = reinterpret_cast<T*>(dst8 + n.w_rel);
     const int32_t kk = n.k * n.k;
     if (n.op == FI_CONV2D) {
+      // A grouped convolution becomes a dense one whose weight rows are zero outside the row's own
+      // group of input channels (block-diagonal): the kernels need no notion of groups.
+      const int32_t G = L.groups > 1 ? L.groups : 1;
+      const int32_t cg = n.C / G, og = n.Co / G;
       for (int32_t o = 0; o < n.Co; ++o) {
-        const T* wo = w + (size_t)o * n.C * kk;
+        const T* wo = w + (size_t)o * cg * kk;
         T* dorow = d + (size_t)o * n.Kp;
-        if (kk == 1) { std::memcpy(dorow, wo, (size_t)n.C * sizeof(T)); continue; }
+        const int32_t c0 = (o / og) * cg;   // first input channel of this row's group
+        if (kk == 1) { std::memcpy(dorow + c0, wo, (size_t)cg * sizeof(T)); continue; }
         for (int32_t t = 0; t < kk; ++t) {
-          T* dt = dorow + (size_t)t * n.Cp;
-          for (int32_t c = 0; c < n.C; ++c) dt[c] = wo[(size_t)c * kk + t];
+          T* dt = dorow + (size_t)t * n.Cp + c0;
+          for (int32_t c = 0; c < cg; ++c) dt[c] = wo[(size_t)c * kk + t];
         }
       }
     } else if (n.op == FI_FC) {

@@ -120,6 +120,18 @@ def test_maxpool_exact(case, mode):
     assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, False))
 
 
+@pytest.mark.parametrize("case", [(128, 128, 32, 3, 1, 1, 14, 14, 2), (64, 96, 4, 3, 2, 1, 15, 17, 2), (48, 48, 48, 3, 1, 1, 9, 9, 1),
+                                  (32, 64, 2, 1, 1, 0, 12, 12, 3), (256, 256, 32, 3, 2, 1, 28, 28, 1)])  # cin, cout, groups, k, stride, pad, H, W, batch
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_grouped_conv(case, mode):
+    """Grouped convolution (each output channel sees its own group of input channels), up to one group per channel."""
+    cin, cout, groups, k, s, p, h, w, b = case
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("gc", dtype, cin, h, w)
+    m.add(zoo.CONV, -1, cin=cin, cout=cout, k=k, stride=s, pad=p, act=zoo.RELU, groups=groups)
+    _run_case(m, 700 + cin + groups, b, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
 @pytest.mark.parametrize("case", [(16, 24, 13, 15), (8, 8, 6, 6), (20, 12, 9, 7), (64, 64, 28, 28)])   # channels of the two sources, H, W
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_concat_of_two_branches(case, mode):

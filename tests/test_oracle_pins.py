@@ -180,6 +180,27 @@ def test_maxpool_closed_forms():
     assert oracle.maxpool2d(np.zeros((1, 1, 7, 7), np.float32), 2, 2, 0).shape == (1, 1, 3, 3)
 
 
+@pytest.mark.parametrize("case", [(12, 8, 4, 3, 1, 1), (16, 16, 2, 3, 2, 1), (6, 9, 3, 1, 1, 0), (8, 8, 8, 3, 1, 1), (10, 4, 1, 5, 2, 2)])
+def test_grouped_conv_vs_per_group_dense_conv_and_library(case, rng):
+    """A grouped convolution is G dense convolutions on channel slices laid side by side; one group is the
+    dense convolution; as many groups as channels is the depthwise one; a library routine agrees."""
+    import torch.nn.functional as F
+    c, o, g, k, s, p = case
+    x = rng.standard_normal((2, c, 9, 7)).astype(np.float32)
+    w = rng.standard_normal((o, c // g, k, k)).astype(np.float32)
+    b = rng.standard_normal(o).astype(np.float32)
+    y = oracle.conv2d_grouped(x, w, b, g, s, p)
+    cg, og = c // g, o // g
+    parts = [oracle.conv2d(x[:, i * cg:(i + 1) * cg], w[i * og:(i + 1) * og], b[i * og:(i + 1) * og], s, p) for i in range(g)]
+    assert np.array_equal(y, np.concatenate(parts, axis=1))
+    ref = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double(), s, p, 1, g).numpy()
+    assert np.abs(y - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max())
+    if g == 1:
+        assert np.array_equal(y, oracle.conv2d(x, w, b, s, p))
+    if g == c == o:
+        assert np.array_equal(y, oracle.dwconv2d(x, w, b, s, p))
+
+
 def test_maxpool_ceil_mode_and_concat(rng):
     """Rounding the pooled size up lets windows hang over the far edge (those taps are never candidates) but
     never adds a window that starts past the input; the ramp's closed form and a library routine pin it.

@@ -39,6 +39,7 @@ class Layer:
     act: str = NONE
     residual: int = NO_RESIDUAL   # node added before the activation; for a concat node: the second source
     ceil: bool = False            # pooling: output size rounds up (windows may hang over the bottom / right edge)
+    groups: int = 1               # conv: input and output channels are cut into this many independent groups
     # filled by shapes(): logical input / output spatial sizes
     in_h: int = 0
     in_w: int = 0
@@ -110,7 +111,7 @@ class Model:
         n = 0
         for L in self.layers:
             if L.op == CONV:
-                n += L.cout * L.cin * L.k * L.k + L.cout
+                n += L.cout * (L.cin // L.groups) * L.k * L.k + L.cout
             elif L.op == DWCONV:
                 n += L.cout * L.k * L.k + L.cout
             elif L.op == FC:
@@ -122,7 +123,7 @@ class Model:
         n = 0
         for L in self.layers:
             if L.op == CONV:
-                n += L.out_h * L.out_w * L.cout * L.cin * L.k * L.k
+                n += L.out_h * L.out_w * L.cout * (L.cin // L.groups) * L.k * L.k
             elif L.op == DWCONV:
                 n += L.out_h * L.out_w * L.cout * L.k * L.k
             elif L.op == FC:
@@ -177,9 +178,10 @@ def _basic_resnet(name: str, reps, dtype: str, classes: int, hw: int) -> Model:
     return m.shapes()
 
 
-def _bottleneck_resnet(name: str, reps, inner: int, dtype: str, classes: int, hw: int) -> Model:
+def _bottleneck_resnet(name: str, reps, inner: int, dtype: str, classes: int, hw: int, groups: int = 1) -> Model:
     """ResNet with 1x1 / 3x3 / 1x1 bottleneck blocks (50, 101, 152 layers); `inner` scales the width of
-    the two inner convolutions (2 for the wide variants of Zagoruyko & Komodakis 2016).  Stride on the 3x3."""
+    the two inner convolutions (2 for the wide variants of Zagoruyko & Komodakis 2016; 2 with 32 groups in
+    the 3x3 is ResNeXt 32x4d, Xie et al. 2017).  Stride on the 3x3."""
     m = Model(name, dtype, 3, hw, hw)
     x = _resnet_stem(m)
     cin = 64
@@ -192,7 +194,7 @@ def _bottleneck_resnet(name: str, reps, inner: int, dtype: str, classes: int, hw
                 skip = m.add(CONV, x, cin=cin, cout=4 * width, k=1, stride=stride, pad=0, act=NONE)
             else:
                 skip = x
-            a = m.add(CONV, a, cin=mid, cout=mid, k=3, stride=stride, pad=1, act=RELU)
+            a = m.add(CONV, a, cin=mid, cout=mid, k=3, stride=stride, pad=1, act=RELU, groups=groups)
             x = m.add(CONV, a, cin=mid, cout=4 * width, k=1, stride=1, pad=0, act=RELU, residual=skip)
             cin = 4 * width
     x = m.add(GAP, x)
@@ -222,6 +224,14 @@ def resnet152(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
 
 def wide_resnet50_2(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
     return _bottleneck_resnet("wide_resnet50_2", (3, 4, 6, 3), 2, dtype, classes, hw)
+
+
+def resnext50_32x4d(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _bottleneck_resnet("resnext50_32x4d", (3, 4, 6, 3), 2, dtype, classes, hw, groups=32)
+
+
+def resnext101_32x8d(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _bottleneck_resnet("resnext101_32x8d", (3, 4, 23, 3), 4, dtype, classes, hw, groups=32)
 
 
 def wide_resnet101_2(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
@@ -401,4 +411,6 @@ FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             "resnet34": resnet34, "resnet101": resnet101, "resnet152": resnet152,
             "wide_resnet50_2": wide_resnet50_2, "wide_resnet101_2": wide_resnet101_2, "mnasnet1_0": mnasnet1_0,
             # ... and two that add channel concatenation and pooling sizes that round up
-            "squeezenet1_1": squeezenet1_1, "googlenet": googlenet}
+            "squeezenet1_1": squeezenet1_1, "googlenet": googlenet,
+            # ... and grouped convolution
+            "resnext50_32x4d": resnext50_32x4d, "resnext101_32x8d": resnext101_32x8d}
