@@ -366,6 +366,25 @@ def squeezenet1_1(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Mo
     return m.shapes()
 
 
+def squeezenet1_0(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    """SqueezeNet 1.0 (Iandola et al. 2016, Table 1): 7x7/2 stem with 96 channels, pooling after fire 4 and fire 8."""
+    m = Model("squeezenet1_0", dtype, 3, hw, hw)
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=96, k=7, stride=2, pad=0, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0, ceil=True)
+    cin = 96
+    for idx, (sq, ex) in enumerate(((16, 64), (16, 64), (32, 128), (32, 128), (48, 192), (48, 192), (64, 256), (64, 256))):
+        if idx in (3, 7):
+            x = m.add(MAXPOOL, x, k=3, stride=2, pad=0, ceil=True)
+        q = m.add(CONV, x, cin=cin, cout=sq, k=1, stride=1, pad=0, act=RELU)
+        e1 = m.add(CONV, q, cin=sq, cout=ex, k=1, stride=1, pad=0, act=RELU)
+        e3 = m.add(CONV, q, cin=sq, cout=ex, k=3, stride=1, pad=1, act=RELU)
+        x = m.add(CONCAT, e1, residual=e3)
+        cin = 2 * ex
+    x = m.add(CONV, x, cin=512, cout=classes, k=1, stride=1, pad=0, act=RELU)
+    m.add(GAP, x)
+    return m.shapes()
+
+
 def googlenet(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
     """GoogLeNet / Inception v1 (Szegedy et al. 2015) in its BatchNorm form without auxiliary heads: every
     inception module concatenates a 1x1 branch, a 1x1 -> 3x3 branch, a second 1x1 -> 3x3 branch (the widely
@@ -411,6 +430,6 @@ FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             "resnet34": resnet34, "resnet101": resnet101, "resnet152": resnet152,
             "wide_resnet50_2": wide_resnet50_2, "wide_resnet101_2": wide_resnet101_2, "mnasnet1_0": mnasnet1_0,
             # ... and two that add channel concatenation and pooling sizes that round up
-            "squeezenet1_1": squeezenet1_1, "googlenet": googlenet,
+            "squeezenet1_0": squeezenet1_0, "squeezenet1_1": squeezenet1_1, "googlenet": googlenet,
             # ... and grouped convolution
             "resnext50_32x4d": resnext50_32x4d, "resnext101_32x8d": resnext101_32x8d}
