@@ -49,7 +49,7 @@ typedef enum {
 } fi_status;
 
 typedef enum { FI_F32 = 0, FI_BF16 = 1 } fi_dtype;
-typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5, FI_CONCAT = 6 } fi_op;
+typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5, FI_CONCAT = 6, FI_AVGPOOL2D = 7 } fi_op;
 typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
 
 #define FI_INPUT (-1)       /* fi_layer_spec.input: the model's input tensor */
@@ -67,6 +67,8 @@ typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
  *   maxpool2d: max over in-range taps (padding acts as -inf); floor output size, or with
  *     ceil_mode the size rounded up (windows may hang over the far edge, the last one still
  *     starts inside the input or its leading padding).
+ *   avgpool2d: in-range taps summed, divided by the window area kh*kw (zero padding counts),
+ *     floor output size, one rounding on store.
  *   concat: the channels of `input` followed by the channels of `residual` (here: the
  *     second source, same height and width); no activation.  cout = sum of both.
  *   global_avgpool: mean over H*W.   softmax: over the channel axis of a 1x1 tensor.

@@ -59,7 +59,7 @@ typedef ORC_ACC acc_t;
 
 extern "C" {
 
-enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5, ORC_CONCAT = 6 };
+enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5, ORC_CONCAT = 6, ORC_AVGPOOL = 7 };
 enum { ORC_NONE = 0, ORC_RELU = 1, ORC_RELU6 = 2 };
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
 
@@ -229,6 +229,27 @@ void orc_maxpool2d_ex(const float* x, int N, int C, int H, int W, int k, int s, 
   }
 }
 
+// Average pooling, floor output size: the in-range taps of the window summed, divided by the full
+// window area k*k (zero padding counts as zeros).
+void orc_avgpool2d(const float* x, int N, int C, int H, int W, int k, int s, int p, float* y) {
+  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+  for (int64_t nc = 0; nc < (int64_t)N * C; ++nc) {
+    const float* xc = x + nc * H * W;
+    float* yc = y + nc * Ho * Wo;
+    for (int i = 0; i < Ho; ++i)
+      for (int j = 0; j < Wo; ++j) {
+        acc_t sum = 0;
+        for (int r = 0; r < k; ++r)
+          for (int t = 0; t < k; ++t) {
+            const int ih = i * s - p + r, iw = j * s - p + t;
+            if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+            sum += (acc_t)xc[(int64_t)ih * W + iw];
+          }
+        yc[(int64_t)i * Wo + j] = (float)(sum / (acc_t)(k * k));
+      }
+  }
+}
+
 // Channel concatenation (NCHW): image n of y holds a's Ca planes, then b's Cb planes.
 void orc_concat(const float* a, int Ca, const float* b, int Cb, int N, int H, int W, float* y) {
   const int64_t hw = (int64_t)H * W;
@@ -358,6 +379,12 @@ int64_t orc_run_model(const orc_layer* layers, int n_layers, int output_node, co
         o.w = L.ceil_mode ? out_size_ceil(w, L.k, L.stride, L.pad) : out_size(w, L.k, L.stride, L.pad);
         o.v.resize((size_t)N * o.c * o.h * o.w);
         orc_maxpool2d_ex(in, N, c, h, w, L.k, L.stride, L.pad, L.ceil_mode, o.v.data());
+        break;
+      }
+      case ORC_AVGPOOL: {
+        o.c = c; o.h = out_size(h, L.k, L.stride, L.pad); o.w = out_size(w, L.k, L.stride, L.pad);
+        o.v.resize((size_t)N * o.c * o.h * o.w);
+        orc_avgpool2d(in, N, c, h, w, L.k, L.stride, L.pad, o.v.data());
         break;
       }
       case ORC_CONCAT: {

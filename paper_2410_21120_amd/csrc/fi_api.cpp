@@ -139,6 +139,7 @@ const char* kind_name(int kind, int tile) {
     case K_FC: return "fc_splitk";
     case K_REDUCE: return "splitk_reduce";
     case K_CONCAT: return "concat";
+    case K_AVGPOOL: return "avgpool";
   }
   return "?";
 }
@@ -367,6 +368,7 @@ static fi_status plan_dag(fi_dag* g) {
       case FI_MAXPOOL2D: nd.kind = K_MAXPOOL; break;
       case FI_GLOBAL_AVGPOOL: nd.kind = K_GAP; break;
       case FI_CONCAT: nd.kind = K_CONCAT; break;
+      case FI_AVGPOOL2D: nd.kind = K_AVGPOOL; break;
       default: nd.kind = K_SOFTMAX; break;
     }
   }

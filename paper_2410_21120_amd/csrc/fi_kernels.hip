@@ -47,7 +47,8 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
       return ((batch * d.Ho * d.Wo + bm - 1) / bm) * d.tiles_n * d.splits;
     }
     case K_DWCONV: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
-    case K_MAXPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
+    case K_MAXPOOL:
+    case K_AVGPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_GAP: return (batch * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256;
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits + 3) / 4;
@@ -666,14 +667,16 @@ __global__ void __launch_bounds__(256) dwconv_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
-// max pooling: out-of-range taps are skipped (padding behaves as -inf).  One thread per
-// (pixel, 8 channels) with 16-byte loads and stores when the channel stride allows it
-// (bf16, Cp % 8 == 0); one thread per element otherwise.
+// window pooling: out-of-range taps are skipped.  Max: padding behaves as -inf and the result is
+// one of the inputs (exact).  AVG: the in-range taps are summed in fp32 and divided by the full
+// window area k*k (padding counts as zeros), rounded once on store.  One thread per (pixel,
+// 8 channels) with 16-byte loads and stores when the channel stride allows it (bf16,
+// Cp % 8 == 0); one thread per element otherwise.
 // ---------------------------------------------------------------------------------
-template <typename TA>
-__global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
+template <typename TA, bool AVG>
+__global__ void __launch_bounds__(256) pool_kernel(KArgs a) {
   int p, bid;
-  if (!find_problem(a, K_MAXPOOL, 0, p, bid)) return;
+  if (!find_problem(a, AVG ? K_AVGPOOL : K_MAXPOOL, 0, p, bid)) return;
   const Desc d = a.d[p];
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
@@ -687,7 +690,7 @@ __global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
     const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
     float best[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) best[i] = -INFINITY;
+    for (int i = 0; i < 8; ++i) best[i] = AVG ? 0.0f : -INFINITY;
     for (int r = 0; r < d.k; ++r) {
       const int ih = pp * d.stride - d.pad + r;
       if (ih < 0 || ih >= d.H) continue;
@@ -698,12 +701,21 @@ __global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
         const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          best[2 * i] = fmaxf(best[2 * i], __uint_as_float(u[i] << 16));
-          best[2 * i + 1] = fmaxf(best[2 * i + 1], __uint_as_float(u[i] & 0xFFFF0000u));
+          const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xFFFF0000u);
+          best[2 * i] = AVG ? best[2 * i] + lo : fmaxf(best[2 * i], lo);
+          best[2 * i + 1] = AVG ? best[2 * i + 1] + hi : fmaxf(best[2 * i + 1], hi);
         }
       }
     }
-    uint4 o;  // the maxima are bf16 values already: packing is exact
+    uint4 o;
+    if constexpr (AVG) {
+      const float area = (float)(d.k * d.k);
+      o.x = pack_bf16x2(best[0] / area, best[1] / area); o.y = pack_bf16x2(best[2] / area, best[3] / area);
+      o.z = pack_bf16x2(best[4] / area, best[5] / area); o.w = pack_bf16x2(best[6] / area, best[7] / area);
+      *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.Cop + c8) = o;
+      return;
+    }
+    // the maxima are bf16 values already: packing is exact
     o.x = (__float_as_uint(best[0]) >> 16) | (__float_as_uint(best[1]) & 0xFFFF0000u);
     o.y = (__float_as_uint(best[2]) >> 16) | (__float_as_uint(best[3]) & 0xFFFF0000u);
     o.z = (__float_as_uint(best[4]) >> 16) | (__float_as_uint(best[5]) & 0xFFFF0000u);
@@ -717,16 +729,18 @@ __global__ void __launch_bounds__(256) maxpool_kernel(KArgs a) {
   const int q = (int)(m % d.Wo);
   const int pp = (int)((m / d.Wo) % d.Ho);
   const int n = (int)(m / ((int64_t)d.Wo * d.Ho));
-  float best = -INFINITY;
+  float best = AVG ? 0.0f : -INFINITY;
   for (int r = 0; r < d.k; ++r) {
     const int ih = pp * d.stride - d.pad + r;
     if (ih < 0 || ih >= d.H) continue;
     for (int s = 0; s < d.k; ++s) {
       const int iw = q * d.stride - d.pad + s;
       if (iw < 0 || iw >= d.W) continue;
-      best = fmaxf(best, ld(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp + c));
+      const float v = ld(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp + c);
+      best = AVG ? best + v : fmaxf(best, v);
     }
   }
+  if (AVG) best = best / (float)(d.k * d.k);
   if (d.ext) {
     if (c < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + c] = best;
   } else {
@@ -1084,7 +1098,9 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       return go(dwconv_kernel<float, float>, nb, 256, a, s);
     }
     case K_MAXPOOL:
-      return ab ? go(maxpool_kernel<bf16_t>, nb, 256, a, s) : go(maxpool_kernel<float>, nb, 256, a, s);
+      return ab ? go(pool_kernel<bf16_t, false>, nb, 256, a, s) : go(pool_kernel<float, false>, nb, 256, a, s);
+    case K_AVGPOOL:
+      return ab ? go(pool_kernel<bf16_t, true>, nb, 256, a, s) : go(pool_kernel<float, true>, nb, 256, a, s);
     case K_GAP: {
       const bool vec = hd[(size_t)L.first_desc].vec != 0;
       if (vec) return ab ? go(gap_vec_kernel<bf16_t>, nb, 256, a, s) : go(gap_vec_kernel<float>, nb, 256, a, s);

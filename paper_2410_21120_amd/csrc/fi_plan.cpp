@@ -88,6 +88,8 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         n.macs = (uint64_t)n.Ho * n.Wo * n.Co * (uint64_t)(L.op == FI_CONV2D ? n.C / (L.groups > 1 ? L.groups : 1) : 1) * L.kh * L.kh;
         break;
       case FI_MAXPOOL2D:
+      case FI_AVGPOOL2D:
+        if (L.op == FI_AVGPOOL2D && L.ceil_mode) { set_error("model %s node %d: average pooling takes the floor output size only", nm, i); return FI_EUNSUPPORTED; }
         if (L.kh != L.kw || L.kh < 1 || L.stride < 1 || L.pad < 0 || 2 * L.pad > L.kh) {
           set_error("model %s node %d: unsupported pooling geometry", nm, i); return FI_EUNSUPPORTED; }
         n.k = L.kh; n.stride = L.stride; n.pad = L.pad; n.Co = n.C;

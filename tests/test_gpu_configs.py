@@ -129,10 +129,10 @@ def test_config4_eight_resnet50_batch32_sampled():
 def test_further_table3_families_fused():
     """Further families of the paper's Table III (AlexNet, VGG-11/13/19, ResNet-34/101/152, Wide ResNet-50-2/101-2,
     MnasNet 1.0; SqueezeNet 1.0 / 1.1 and GoogLeNet with channel concatenation and pooling sizes that round up; ResNeXt-50
-    32x4d with grouped convolution), all fourteen fused in one DAG at a reduced image size, each member against the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
+    32x4d with grouped convolution; DenseNet-121 with window average pooling and per-channel affine nodes), all fifteen fused in one DAG at a reduced image size, each member against the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
     from tests import harness
     fams = ["alexnet", "vgg11", "vgg13", "vgg19", "resnet34", "resnet101", "resnet152", "wide_resnet50_2", "wide_resnet101_2", "mnasnet1_0",
-            "squeezenet1_0", "squeezenet1_1", "googlenet", "resnext50_32x4d"]
+            "squeezenet1_0", "squeezenet1_1", "googlenet", "resnext50_32x4d", "densenet121"]
     mem = []
     for i, f in enumerate(fams):
         m = zoo.FAMILIES[f](hw=96)

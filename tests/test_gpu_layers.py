@@ -188,6 +188,19 @@ def test_maxpool_ceil_mode_exact(case, mode):
     assert y.shape == ref.shape and np.array_equal(y, ref)
 
 
+@pytest.mark.parametrize("case", [(64, 2, 2, 0, 28, 28, 2), (24, 3, 1, 1, 9, 11, 2), (40, 3, 2, 1, 15, 14, 1), (8, 5, 1, 2, 7, 7, 3)])
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_avgpool_between_convs(case, mode):
+    """Window average pooling (divisor = window area, zero padding counted) between two convolutions."""
+    c, k, s, p, h, w, b = case
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("ap", dtype, 8, h, w)
+    a = m.add(zoo.CONV, -1, cin=8, cout=c, k=1, stride=1, pad=0, act=zoo.RELU)
+    a = m.add(zoo.AVGPOOL, a, k=k, stride=s, pad=p)
+    m.add(zoo.CONV, a, cin=c, cout=12, k=1, stride=1, pad=0, act=zoo.NONE)
+    _run_case(m, 900 + c + k, b, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_gap_fc_softmax_chain(mode):
     dtype = "f32" if mode == "f32" else "bf16"

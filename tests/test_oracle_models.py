@@ -26,15 +26,17 @@ def test_structure(fam):
     assert len(ops) == g["nodes"]
     assert (ops.count("conv"), ops.count("dwconv"), ops.count("maxpool"), ops.count("gap"), ops.count("fc")) == \
         (g["conv"], g["dwconv"], g["maxpool"], g["gap"], g["fc"])
-    assert ops.count("concat") == g.get("concat", 0)
+    assert ops.count("concat") == g.get("concat", 0) and ops.count("avgpool") == g.get("avgpool", 0)
     assert max(m.levels()) == g["depth"]
     assert m.n_params() == g["params"]
     assert m.macs() == g["macs"]
     assert m.layers[m.output].cout == g["classes"]
     if "gmacs_published" in g:
-        assert round(m.macs() / 1e9, 2) == g["gmacs_published"]
+        affine = sum(L.out_h * L.out_w * L.cout for L in m.layers if L.op == "dwconv" and L.k == 1 and not L.bn)
+        assert affine == g.get("affine_macs", 0)
+        assert round((m.macs() - affine) / 1e9, 2) == g["gmacs_published"]
     if "params_with_batchnorm" in g:  # folding removes one of BatchNorm's two parameters per normalised channel
-        bn_channels = sum(L.cout for L in m.layers if L.op in ("conv", "dwconv"))
+        bn_channels = sum(L.cout for L in m.layers if L.op in ("conv", "dwconv") and L.bn and L.bias)
         assert g["params_with_batchnorm"] - g["params"] in (bn_channels, 0)
 
 
@@ -87,6 +89,8 @@ def _torch_forward(model, blob, x, dtype=torch.float64):
             y = F.conv2d(inp, w.reshape(L.cout, 1, L.k, L.k), b, stride=L.stride, padding=L.pad, groups=L.cout)
         elif L.op == "maxpool":
             y = F.max_pool2d(inp, L.k, L.stride, L.pad, ceil_mode=bool(L.ceil))
+        elif L.op == "avgpool":
+            y = F.avg_pool2d(inp, L.k, L.stride, L.pad)
         elif L.op == "concat":
             y = torch.cat([inp, vals[L.residual]], dim=1)
         elif L.op == "gap":
@@ -110,7 +114,7 @@ def _rel(a, b):
 
 
 @pytest.mark.parametrize("fam,hw", [("tiny", 32), ("resnet18", 64), ("resnet50", 64), ("mobilenetv2", 64), ("vgg16", 32),
-                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64)])
+                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64), ("densenet121", 64)])
 def test_model_runner_vs_library_forward(fam, hw):
     m = zoo.tiny_cnn() if fam == "tiny" else zoo.FAMILIES[fam](hw=hw)
     blob = gen.make_blob(m, 1000 + hw)

@@ -227,6 +227,26 @@ def test_maxpool_ceil_mode_and_concat(rng):
     assert np.array_equal(oracle.concat(a, a[:, :0]), a)
 
 
+def test_avgpool_closed_forms_and_library(rng):
+    """Window average: a constant stays the constant without padding and shrinks where the window hangs into
+    zero padding (divisor is the full window area); a window covering the image is the global average; a
+    library routine agrees."""
+    import torch.nn.functional as F
+    x = np.full((1, 2, 6, 6), 3.0, np.float32)
+    assert np.array_equal(oracle.avgpool2d(x, 2, 2, 0), np.full((1, 2, 3, 3), 3.0, np.float32))
+    y = oracle.avgpool2d(x, 3, 1, 1)
+    assert y[0, 0, 0, 0] == np.float32(3.0 * 4 / 9) and y[0, 0, 0, 2] == np.float32(3.0 * 6 / 9) and y[0, 0, 2, 2] == 3.0
+    ramp = np.arange(4 * 4, dtype=np.float32).reshape(1, 1, 4, 4)
+    assert np.array_equal(oracle.avgpool2d(ramp, 2, 2, 0)[0, 0], np.array([[2.5, 4.5], [10.5, 12.5]], np.float32))
+    x = rng.standard_normal((2, 3, 7, 7)).astype(np.float32)
+    assert np.allclose(oracle.avgpool2d(x, 7, 1, 0).reshape(2, 3), oracle.global_avgpool(x), rtol=0, atol=1e-6)
+    for (h, w, k, s, p) in [(8, 8, 2, 2, 0), (7, 9, 3, 1, 1), (14, 15, 3, 2, 1), (9, 6, 2, 2, 0), (5, 5, 5, 1, 2)]:
+        x = rng.standard_normal((2, 3, h, w)).astype(np.float32)
+        ref = F.avg_pool2d(torch.from_numpy(x).double(), k, s, p).numpy()
+        y = oracle.avgpool2d(x, k, s, p)
+        assert y.shape == ref.shape and np.abs(y - ref).max() < 1e-6
+
+
 def test_global_avgpool_closed_forms():
     h, w = 7, 7
     ramp = np.arange(h * w, dtype=np.float32).reshape(1, 1, h, w)

@@ -116,7 +116,7 @@ def make_blob(model: zoo.Model, seed: int, bias_std: float = 0.1, out: np.ndarra
         else:
             _normal_into(seed, 2 * i, nw, std, blob[L.w_off:L.w_off + 2 * nw].view(np.uint16), True)
         bview = blob[L.b_off:L.b_off + 4 * L.cout].view(np.float32)
-        if bias_std > 0:
+        if bias_std > 0 and L.bias:
             _normal_into(seed, 2 * i + 1, L.cout, bias_std, bview, False)
         else:
             bview[:] = 0

@@ -21,7 +21,7 @@ from typing import List
 
 # operator / activation names (strings on purpose: each executor maps them to
 # its own enum, so the two sides share no numeric constants)
-CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX, CONCAT = "conv", "dwconv", "maxpool", "gap", "fc", "softmax", "concat"
+CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX, CONCAT, AVGPOOL = "conv", "dwconv", "maxpool", "gap", "fc", "softmax", "concat", "avgpool"
 NONE, RELU, RELU6 = "none", "relu", "relu6"
 NO_RESIDUAL = -2
 MODEL_INPUT = -1
@@ -40,6 +40,8 @@ class Layer:
     residual: int = NO_RESIDUAL   # node added before the activation; for a concat node: the second source
     ceil: bool = False            # pooling: output size rounds up (windows may hang over the bottom / right edge)
     groups: int = 1               # conv: input and output channels are cut into this many independent groups
+    bias: bool = True             # False: the layer has no bias in the architecture (its stored bias is all zero)
+    bn: bool = True               # conv / depthwise with a bias: the bias stands for a folded BatchNorm
     # filled by shapes(): logical input / output spatial sizes
     in_h: int = 0
     in_w: int = 0
@@ -85,7 +87,8 @@ class Model:
                 ho = (h + 2 * L.pad - L.k) // L.stride + 1
                 wo = (w + 2 * L.pad - L.k) // L.stride + 1
                 dims[i] = (L.cout, ho, wo)
-            elif L.op == MAXPOOL:
+            elif L.op in (MAXPOOL, AVGPOOL):
+                assert not (L.op == AVGPOOL and L.ceil)
                 L.cin = L.cout = c
                 dims[i] = (c, pooled(h, L), pooled(w, L))
             elif L.op == CONCAT:   # channels of `input`, then channels of `residual`
@@ -110,12 +113,13 @@ class Model:
     def n_params(self) -> int:
         n = 0
         for L in self.layers:
+            b = L.cout if L.bias else 0
             if L.op == CONV:
-                n += L.cout * (L.cin // L.groups) * L.k * L.k + L.cout
+                n += L.cout * (L.cin // L.groups) * L.k * L.k + b
             elif L.op == DWCONV:
-                n += L.cout * L.k * L.k + L.cout
+                n += L.cout * L.k * L.k + b
             elif L.op == FC:
-                n += L.cout * L.cin + L.cout
+                n += L.cout * L.cin + b
         return n
 
     def macs(self) -> int:
@@ -366,6 +370,50 @@ def squeezenet1_1(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Mo
     return m.shapes()
 
 
+def _densenet(name: str, growth: int, blocks, init: int, dtype: str, classes: int, hw: int) -> Model:
+    """DenseNet-BC (Huang et al. 2017): every dense layer normalises and rectifies the concatenation of all
+    earlier features (a per-channel scale and shift: a 1x1 depthwise node here, it cannot be folded because
+    every consumer has its own), squeezes it to 4*growth channels (1x1, its BatchNorm folded), adds `growth`
+    new channels (3x3, no bias) and concatenates them; transitions halve channels (1x1, no bias) and size
+    (2x2 average pooling)."""
+    m = Model(name, dtype, 3, hw, hw)
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=init, k=7, stride=2, pad=3, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=1)
+    c = init
+    for bi, n in enumerate(blocks):
+        for _ in range(n):
+            a = m.add(DWCONV, x, cin=c, cout=c, k=1, stride=1, pad=0, act=RELU, bn=False)
+            a = m.add(CONV, a, cin=c, cout=4 * growth, k=1, stride=1, pad=0, act=RELU)
+            a = m.add(CONV, a, cin=4 * growth, cout=growth, k=3, stride=1, pad=1, act=NONE, bias=False, bn=False)
+            x = m.add(CONCAT, x, residual=a)
+            c += growth
+        if bi + 1 < len(blocks):
+            a = m.add(DWCONV, x, cin=c, cout=c, k=1, stride=1, pad=0, act=RELU, bn=False)
+            a = m.add(CONV, a, cin=c, cout=c // 2, k=1, stride=1, pad=0, act=NONE, bias=False, bn=False)
+            x = m.add(AVGPOOL, a, k=2, stride=2, pad=0)
+            c //= 2
+    x = m.add(DWCONV, x, cin=c, cout=c, k=1, stride=1, pad=0, act=RELU, bn=False)
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=c, cout=classes)
+    return m.shapes()
+
+
+def densenet121(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _densenet("densenet121", 32, (6, 12, 24, 16), 64, dtype, classes, hw)
+
+
+def densenet169(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _densenet("densenet169", 32, (6, 12, 32, 32), 64, dtype, classes, hw)
+
+
+def densenet201(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _densenet("densenet201", 32, (6, 12, 48, 32), 64, dtype, classes, hw)
+
+
+def densenet161(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _densenet("densenet161", 48, (6, 12, 36, 24), 96, dtype, classes, hw)
+
+
 def squeezenet1_0(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
     """SqueezeNet 1.0 (Iandola et al. 2016, Table 1): 7x7/2 stem with 96 channels, pooling after fire 4 and fire 8."""
     m = Model("squeezenet1_0", dtype, 3, hw, hw)
@@ -432,4 +480,6 @@ FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             # ... and two that add channel concatenation and pooling sizes that round up
             "squeezenet1_0": squeezenet1_0, "squeezenet1_1": squeezenet1_1, "googlenet": googlenet,
             # ... and grouped convolution
-            "resnext50_32x4d": resnext50_32x4d, "resnext101_32x8d": resnext101_32x8d}
+            "resnext50_32x4d": resnext50_32x4d, "resnext101_32x8d": resnext101_32x8d,
+            # ... and window average pooling with per-channel affine nodes
+            "densenet121": densenet121, "densenet169": densenet169, "densenet201": densenet201, "densenet161": densenet161}
