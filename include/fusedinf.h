@@ -49,8 +49,10 @@ typedef enum {
 } fi_status;
 
 typedef enum { FI_F32 = 0, FI_BF16 = 1 } fi_dtype;
-typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5, FI_CONCAT = 6, FI_AVGPOOL2D = 7 } fi_op;
-typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
+typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5, FI_CONCAT = 6, FI_AVGPOOL2D = 7, FI_MUL = 8 } fi_op;
+/* hard sigmoid h(v) = min(max(v + 3, 0), 6) / 6, hard swish v * h(v); sigmoid s(v) = 1 / (1 + exp(-v)), SiLU v * s(v) */
+typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2, FI_ACT_HARDSWISH = 3, FI_ACT_HARDSIGMOID = 4,
+               FI_ACT_SILU = 5, FI_ACT_SIGMOID = 6 } fi_act;
 
 #define FI_INPUT (-1)       /* fi_layer_spec.input: the model's input tensor */
 #define FI_NO_RESIDUAL (-2) /* fi_layer_spec.residual: nothing is added */
@@ -69,6 +71,8 @@ typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2 } fi_act;
  *     starts inside the input or its leading padding).
  *   avgpool2d: in-range taps summed, divided by the window area kh*kw (zero padding counts),
  *     floor output size, one rounding on store.
+ *   mul: `input` scaled per (image, channel) by the 1x1 tensor `residual` (the gate of a
+ *     squeeze-and-excitation block); no activation.
  *   concat: the channels of `input` followed by the channels of `residual` (here: the
  *     second source, same height and width); no activation.  cout = sum of both.
  *   global_avgpool: mean over H*W.   softmax: over the channel axis of a 1x1 tensor.

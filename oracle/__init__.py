@@ -16,8 +16,8 @@ import numpy as np
 from . import build as _build
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_OPS = {"conv": 0, "dwconv": 1, "maxpool": 2, "gap": 3, "fc": 4, "softmax": 5, "concat": 6, "avgpool": 7}
-_ACTS = {"none": 0, "relu": 1, "relu6": 2}
+_OPS = {"conv": 0, "dwconv": 1, "maxpool": 2, "gap": 3, "fc": 4, "softmax": 5, "concat": 6, "avgpool": 7, "mul": 8}
+_ACTS = {"none": 0, "relu": 1, "relu6": 2, "hardswish": 3, "hardsigmoid": 4, "silu": 5, "sigmoid": 6}
 _DT = {"f32": 0, "bf16": 1}
 
 
@@ -41,6 +41,7 @@ def lib(f64: bool = False):
         L.orc_conv2d_grouped.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_maxpool2d_ex.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_avgpool2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
+        L.orc_channel_scale.argtypes = [_FP, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_concat.argtypes = [_FP, C.c_int, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_dwconv2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_maxpool2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
@@ -127,6 +128,16 @@ def avgpool2d(x, k, stride, pad=0, f64=False):
     n, c, h, w = x.shape
     y = np.empty((n, c, _osz(h, k, stride, pad), _osz(w, k, stride, pad)), dtype=np.float32)
     lib(f64).orc_avgpool2d(xp, n, c, h, w, k, stride, pad, y.ctypes.data_as(_FP))
+    return y
+
+
+def channel_scale(x, g):
+    x, xp = _f(x)
+    g, gp = _f(g)
+    n, c, h, w = x.shape
+    assert g.size == n * c
+    y = np.empty_like(x)
+    lib().orc_channel_scale(xp, gp, n, c, h, w, y.ctypes.data_as(_FP))
     return y
 
 

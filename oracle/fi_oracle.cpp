@@ -59,8 +59,8 @@ typedef ORC_ACC acc_t;
 
 extern "C" {
 
-enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5, ORC_CONCAT = 6, ORC_AVGPOOL = 7 };
-enum { ORC_NONE = 0, ORC_RELU = 1, ORC_RELU6 = 2 };
+enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5, ORC_CONCAT = 6, ORC_AVGPOOL = 7, ORC_MUL = 8 };
+enum { ORC_NONE = 0, ORC_RELU = 1, ORC_RELU6 = 2, ORC_HARDSWISH = 3, ORC_HARDSIGMOID = 4, ORC_SILU = 5, ORC_SIGMOID = 6 };
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
 
 // One node of a model's layer graph (the oracle's own description format).
@@ -109,7 +109,28 @@ void orc_activate(float* y, int64_t n, int act) {
       float v = y[i] > 0.0f ? y[i] : 0.0f;
       y[i] = v < 6.0f ? v : 6.0f;
     }
+  } else if (act == ORC_HARDSWISH || act == ORC_HARDSIGMOID) {
+    // hard sigmoid h(v) = min(max(v + 3, 0), 6) / 6; hard swish = v * h(v)
+    for (int64_t i = 0; i < n; ++i) {
+      float t = y[i] + 3.0f;
+      t = t > 0.0f ? t : 0.0f;
+      t = t < 6.0f ? t : 6.0f;
+      y[i] = act == ORC_HARDSWISH ? y[i] * t / 6.0f : t / 6.0f;
+    }
+  } else if (act == ORC_SILU || act == ORC_SIGMOID) {
+    // logistic sigmoid s(v) = 1 / (1 + exp(-v)); SiLU = v * s(v)
+    for (int64_t i = 0; i < n; ++i) {
+      const float sg = 1.0f / (1.0f + std::exp(-y[i]));
+      y[i] = act == ORC_SILU ? y[i] * sg : sg;
+    }
   }
+}
+
+// Per-(image, channel) gate: y[n,c,h,w] = x[n,c,h,w] * g[n,c]  (squeeze-and-excitation's rescaling).
+void orc_channel_scale(const float* x, const float* g, int N, int C, int H, int W, float* y) {
+  const int64_t hw = (int64_t)H * W;
+  for (int64_t nc = 0; nc < (int64_t)N * C; ++nc)
+    for (int64_t i = 0; i < hw; ++i) y[nc * hw + i] = x[nc * hw + i] * g[nc];
 }
 
 void orc_add(float* y, const float* skip, int64_t n) {
@@ -379,6 +400,15 @@ int64_t orc_run_model(const orc_layer* layers, int n_layers, int output_node, co
         o.w = L.ceil_mode ? out_size_ceil(w, L.k, L.stride, L.pad) : out_size(w, L.k, L.stride, L.pad);
         o.v.resize((size_t)N * o.c * o.h * o.w);
         orc_maxpool2d_ex(in, N, c, h, w, L.k, L.stride, L.pad, L.ceil_mode, o.v.data());
+        break;
+      }
+      case ORC_MUL: {
+        if (L.residual < 0) return -1;
+        const T& gt = val[(size_t)L.residual];
+        if (gt.c != c || gt.h != 1 || gt.w != 1) return -2;
+        o.c = c; o.h = h; o.w = w;
+        o.v.resize((size_t)N * c * h * w);
+        orc_channel_scale(in, gt.v.data(), N, c, h, w, o.v.data());
         break;
       }
       case ORC_AVGPOOL: {

@@ -15,8 +15,8 @@ from . import build as _build
 
 FI_OK, FI_EINVAL, FI_EUNSUPPORTED, FI_ESTATE, FI_ENOMEM_HOST, FI_ENOMEM_DEVICE, FI_EBUDGET, FI_EHIP = range(8)
 FI_F32, FI_BF16 = 0, 1
-FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX, FI_CONCAT, FI_AVGPOOL2D = range(8)
-FI_ACT_NONE, FI_ACT_RELU, FI_ACT_RELU6 = range(3)
+FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX, FI_CONCAT, FI_AVGPOOL2D, FI_MUL = range(9)
+FI_ACT_NONE, FI_ACT_RELU, FI_ACT_RELU6, FI_ACT_HARDSWISH, FI_ACT_HARDSIGMOID, FI_ACT_SILU, FI_ACT_SIGMOID = range(7)
 FI_INPUT, FI_NO_RESIDUAL = -1, -2
 FI_LOAD_ONE_COPY, FI_LOAD_PER_MODEL = 0, 1
 FI_MAX_GROUP = 16
@@ -280,8 +280,9 @@ def fi_destroy(h) -> None:
 
 # ---- marshalling helpers ---------------------------------------------------------------------
 _OPS = {"conv": FI_CONV2D, "dwconv": FI_DWCONV2D, "maxpool": FI_MAXPOOL2D, "gap": FI_GLOBAL_AVGPOOL,
-        "fc": FI_FC, "softmax": FI_SOFTMAX, "concat": FI_CONCAT, "avgpool": FI_AVGPOOL2D}
-_ACTS = {"none": FI_ACT_NONE, "relu": FI_ACT_RELU, "relu6": FI_ACT_RELU6}
+        "fc": FI_FC, "softmax": FI_SOFTMAX, "concat": FI_CONCAT, "avgpool": FI_AVGPOOL2D, "mul": FI_MUL}
+_ACTS = {"none": FI_ACT_NONE, "relu": FI_ACT_RELU, "relu6": FI_ACT_RELU6, "hardswish": FI_ACT_HARDSWISH,
+         "hardsigmoid": FI_ACT_HARDSIGMOID, "silu": FI_ACT_SILU, "sigmoid": FI_ACT_SIGMOID}
 _DT = {"f32": FI_F32, "bf16": FI_BF16}
 
 

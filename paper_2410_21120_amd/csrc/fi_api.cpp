@@ -140,6 +140,7 @@ const char* kind_name(int kind, int tile) {
     case K_REDUCE: return "splitk_reduce";
     case K_CONCAT: return "concat";
     case K_AVGPOOL: return "avgpool";
+    case K_MUL: return "channel_scale";
   }
   return "?";
 }
@@ -369,6 +370,7 @@ static fi_status plan_dag(fi_dag* g) {
       case FI_GLOBAL_AVGPOOL: nd.kind = K_GAP; break;
       case FI_CONCAT: nd.kind = K_CONCAT; break;
       case FI_AVGPOOL2D: nd.kind = K_AVGPOOL; break;
+      case FI_MUL: nd.kind = K_MUL; break;
       default: nd.kind = K_SOFTMAX; break;
     }
   }

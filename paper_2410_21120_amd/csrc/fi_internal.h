@@ -26,6 +26,7 @@ enum Kind : int32_t {
   K_REDUCE = 8,       // finishes a split-K node: sums partials, bias, residual, activation, store
   K_CONCAT = 9,       // channels of the first source, then of the second
   K_AVGPOOL = 10,     // window average (divisor k*k)
+  K_MUL = 11,         // per-(image, channel) gate
   K_NKINDS
 };
 

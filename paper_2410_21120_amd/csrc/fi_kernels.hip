@@ -34,6 +34,10 @@ __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
 __device__ __forceinline__ float activate(float v, int act) {
   if (act == FI_ACT_RELU) return fmaxf(v, 0.0f);
   if (act == FI_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+  if (act == FI_ACT_HARDSWISH) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+  if (act == FI_ACT_HARDSIGMOID) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+  if (act == FI_ACT_SILU) return v * (1.0f / (1.0f + expf(-v)));
+  if (act == FI_ACT_SIGMOID) return 1.0f / (1.0f + expf(-v));
   return v;
 }
 
@@ -53,7 +57,8 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
-    case K_CONCAT: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
+    case K_CONCAT:
+    case K_MUL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
   }
   return 0;
 }
@@ -819,6 +824,43 @@ __device__ __forceinline__ void store8(float* p, const float* v) {
 }
 
 // ---------------------------------------------------------------------------------
+// per-(image, channel) gate: y[n,h,w,c] = x[n,h,w,c] * g[n,c], fp32 product, one rounding on store
+// ---------------------------------------------------------------------------------
+template <typename TA>
+__global__ void __launch_bounds__(256) mul_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_MUL, 0, p, bid)) return;
+  const Desc d = a.d[p];
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
+  const TA* g = reinterpret_cast<const TA*>(a.abase + d.r_off);
+  const int64_t HW = (int64_t)d.Ho * d.Wo;
+  if (sizeof(TA) == 2 && d.vec) {
+    const int cv = d.Cop / 8;
+    if (idx >= (int64_t)a.batch * HW * cv) return;
+    const int c8 = (int)(idx % cv) * 8;
+    const int64_t m = idx / cv;
+    float xv[8], gv[8];
+    load8(x + m * d.Cp + c8, xv);
+    load8(g + (m / HW) * d.Cp + c8, gv);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) xv[i] *= gv[i];
+    store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c8, xv);
+    return;
+  }
+  if (idx >= (int64_t)a.batch * HW * d.Cop) return;
+  const int c = (int)(idx % d.Cop);
+  const int64_t m = idx / d.Cop;
+  const float v = c < d.Co ? ld(x + m * d.Cp + c) * ld(g + (m / HW) * d.Cp + c) : 0.0f;
+  if (d.ext) {
+    if (c < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + c] = v;
+  } else {
+    st(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c, v);
+  }
+}
+
+
+// ---------------------------------------------------------------------------------
 // depthwise convolution, bf16 weights: one thread per (pixel, 8 channels); 16-byte (bf16) or
 // 2x16-byte (fp32) activation vectors, coalesced along the channel axis.
 // ---------------------------------------------------------------------------------
@@ -1113,6 +1155,8 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       return ab ? go(reduce_kernel<bf16_t>, nb, 256, a, s) : go(reduce_kernel<float>, nb, 256, a, s);
     case K_SOFTMAX:
       return go(softmax_kernel, nb, 64, a, s);
+    case K_MUL:
+      return ab ? go(mul_kernel<bf16_t>, nb, 256, a, s) : go(mul_kernel<float>, nb, 256, a, s);
     case K_CONCAT:
       return ab ? go(concat_kernel<bf16_t>, nb, 256, a, s) : go(concat_kernel<float>, nb, 256, a, s);
   }

@@ -66,7 +66,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
       set_error("model %s node %d: residual %d is not an earlier node", nm, i, L.residual);
       return FI_EINVAL;
     }
-    if (L.act < FI_ACT_NONE || L.act > FI_ACT_RELU6) { set_error("model %s node %d: bad activation", nm, i); return FI_EINVAL; }
+    if (L.act < FI_ACT_NONE || L.act > FI_ACT_SIGMOID) { set_error("model %s node %d: bad activation", nm, i); return FI_EINVAL; }
     if (L.input == FI_INPUT) { n.C = m.in_c; n.H = m.in_h; n.W = m.in_w; n.Cp = out.in_cp; }
     else { const Node& s = out.nodes[(size_t)L.input]; n.C = s.Co; n.H = s.Ho; n.W = s.Wo; n.Cp = s.Cop; }
     n.k = 1; n.stride = 1; n.pad = 0;
@@ -104,6 +104,14 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         }
         if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: pooling takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
         break;
+      case FI_MUL: {
+        if (L.residual == FI_NO_RESIDUAL || L.input == FI_INPUT) { set_error("model %s node %d: channel scaling needs a tensor and a gate node", nm, i); return FI_EINVAL; }
+        const Node& gt = out.nodes[(size_t)L.residual];
+        if (gt.Co != n.C || gt.Ho != 1 || gt.Wo != 1) { set_error("model %s node %d: the gate must be a 1x1 tensor with the input's %d channels", nm, i, n.C); return FI_EINVAL; }
+        if (L.act != FI_ACT_NONE) { set_error("model %s node %d: channel scaling takes no activation", nm, i); return FI_EUNSUPPORTED; }
+        n.Co = n.C; n.Ho = n.H; n.Wo = n.W;
+        break;
+      }
       case FI_CONCAT: {
         if (L.residual == FI_NO_RESIDUAL) { set_error("model %s node %d: concat needs a second source", nm, i); return FI_EINVAL; }
         const Node& b = out.nodes[(size_t)L.residual];
@@ -134,7 +142,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         return FI_EUNSUPPORTED;
     }
     n.Cop = round_up(n.Co, g);
-    if (L.residual != FI_NO_RESIDUAL && L.op != FI_CONCAT) {
+    if (L.residual != FI_NO_RESIDUAL && L.op != FI_CONCAT && L.op != FI_MUL) {
       const Node& r = out.nodes[(size_t)L.residual];
       if (r.Co != n.Co || r.Ho != n.Ho || r.Wo != n.Wo) {
         set_error("model %s node %d: residual shape mismatch", nm, i); return FI_EINVAL; }

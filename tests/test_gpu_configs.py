@@ -129,14 +129,16 @@ def test_config4_eight_resnet50_batch32_sampled():
 def test_further_table3_families_fused():
     """Further families of the paper's Table III (AlexNet, VGG-11/13/19, ResNet-34/101/152, Wide ResNet-50-2/101-2,
     MnasNet 1.0; SqueezeNet 1.0 / 1.1 and GoogLeNet with channel concatenation and pooling sizes that round up; ResNeXt-50
-    32x4d with grouped convolution; DenseNet-121 with window average pooling and per-channel affine nodes), all fifteen fused in one DAG at a reduced image size, each member against the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
+    32x4d with grouped convolution; DenseNet-121 with window average pooling and per-channel affine nodes; MobileNetV3 Large with squeeze-excite gates
+    and hard-swish), all sixteen fused in one DAG at a reduced image size, each member against the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
     from tests import harness
+    WIDE_HERE = {"mnasnet1_0", "mobilenet_v3_large"}   # MobileNet-style inverted-residual networks keep fp32 activations
     fams = ["alexnet", "vgg11", "vgg13", "vgg19", "resnet34", "resnet101", "resnet152", "wide_resnet50_2", "wide_resnet101_2", "mnasnet1_0",
-            "squeezenet1_0", "squeezenet1_1", "googlenet", "resnext50_32x4d", "densenet121"]
+            "squeezenet1_0", "squeezenet1_1", "googlenet", "resnext50_32x4d", "densenet121", "mobilenet_v3_large"]
     mem = []
     for i, f in enumerate(fams):
         m = zoo.FAMILIES[f](hw=96)
-        mem.append((m, gen.make_blob(m, 1000 + i), "f32" if f == "mnasnet1_0" else None))
+        mem.append((m, gen.make_blob(m, 1000 + i), "f32" if f in WIDE_HERE else None))
     x = gen.make_input(7, 2, 3, 96, 96, "normal", "bf16")
     g = harness.GpuDag(mem, 2)
     try:
@@ -149,7 +151,7 @@ def test_further_table3_families_fused():
         units.append((m, b, x, act is None))
     res = harness.oracle_units(units)
     for i, f in enumerate(fams):
-        _check_member(f, ys[i], res[2 * i], res[2 * i + 1], 1e-4 if f == "mnasnet1_0" else 1e-2)
+        _check_member(f, ys[i], res[2 * i], res[2 * i + 1], 1e-4 if f in WIDE_HERE else 1e-2)
 
 
 def test_config5_swap_churn_sampled():

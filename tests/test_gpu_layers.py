@@ -201,6 +201,37 @@ def test_avgpool_between_convs(case, mode):
     _run_case(m, 900 + c + k, b, act_dtype="f32" if mode == "bf16_wide" else None)
 
 
+@pytest.mark.parametrize("act", [zoo.HARDSWISH, zoo.HARDSIGMOID, zoo.SILU, zoo.SIGMOID])
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_smooth_activations_in_every_epilogue(act, mode):
+    """Hard-swish, hard-sigmoid, SiLU and sigmoid after an MFMA / direct convolution, a split-K convolution
+    (finished by the reduce kernel), a depthwise convolution and a small-batch FC."""
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("acts", dtype, 16, 12, 12)
+    a = m.add(zoo.CONV, -1, cin=16, cout=40, k=3, stride=1, pad=1, act=act)
+    a = m.add(zoo.DWCONV, a, cin=40, cout=40, k=3, stride=2, pad=1, act=act)
+    a = m.add(zoo.CONV, a, cin=40, cout=64, k=3, stride=1, pad=1, act=act)      # 6x6 outputs, K = 360: split-K at this size
+    a = m.add(zoo.GAP, a)
+    m.add(zoo.FC, a, cin=64, cout=20, act=act)
+    _run_case(m, 1100, 2, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+@pytest.mark.parametrize("case", [(64, 16, 9, 11, 2), (24, 8, 7, 7, 3), (120, 32, 14, 14, 1)])   # channels, squeeze width, H, W, batch
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_squeeze_excite_block(case, mode):
+    """global average -> FC (ReLU) -> FC (hard sigmoid) -> per-channel scaling of the block's tensor -> 1x1 projection."""
+    c, sq, h, w, b = case
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("se", dtype, 8, h, w)
+    x = m.add(zoo.CONV, -1, cin=8, cout=c, k=1, stride=1, pad=0, act=zoo.HARDSWISH)
+    g = m.add(zoo.GAP, x)
+    g = m.add(zoo.FC, g, cin=c, cout=sq, act=zoo.RELU)
+    g = m.add(zoo.FC, g, cin=sq, cout=c, act=zoo.HARDSIGMOID)
+    y = m.add(zoo.MUL, x, residual=g)
+    m.add(zoo.CONV, y, cin=c, cout=16, k=1, stride=1, pad=0, act=zoo.NONE)
+    _run_case(m, 1200 + c, b, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_gap_fc_softmax_chain(mode):
     dtype = "f32" if mode == "f32" else "bf16"

@@ -26,7 +26,7 @@ def test_structure(fam):
     assert len(ops) == g["nodes"]
     assert (ops.count("conv"), ops.count("dwconv"), ops.count("maxpool"), ops.count("gap"), ops.count("fc")) == \
         (g["conv"], g["dwconv"], g["maxpool"], g["gap"], g["fc"])
-    assert ops.count("concat") == g.get("concat", 0) and ops.count("avgpool") == g.get("avgpool", 0)
+    assert ops.count("concat") == g.get("concat", 0) and ops.count("avgpool") == g.get("avgpool", 0) and ops.count("mul") == g.get("mul", 0)
     assert max(m.levels()) == g["depth"]
     assert m.n_params() == g["params"]
     assert m.macs() == g["macs"]
@@ -89,6 +89,8 @@ def _torch_forward(model, blob, x, dtype=torch.float64):
             y = F.conv2d(inp, w.reshape(L.cout, 1, L.k, L.k), b, stride=L.stride, padding=L.pad, groups=L.cout)
         elif L.op == "maxpool":
             y = F.max_pool2d(inp, L.k, L.stride, L.pad, ceil_mode=bool(L.ceil))
+        elif L.op == "mul":
+            y = inp * vals[L.residual]
         elif L.op == "avgpool":
             y = F.avg_pool2d(inp, L.k, L.stride, L.pad)
         elif L.op == "concat":
@@ -99,12 +101,14 @@ def _torch_forward(model, blob, x, dtype=torch.float64):
             y = F.linear(inp.reshape(inp.shape[0], -1), w.reshape(L.cout, L.cin), b).reshape(-1, L.cout, 1, 1)
         elif L.op == "softmax":
             y = torch.softmax(inp.reshape(inp.shape[0], -1), dim=1).reshape(inp.shape)
-        if L.residual >= 0 and L.op != "concat":
+        if L.residual >= 0 and L.op not in ("concat", "mul"):
             y = y + vals[L.residual]
         if L.act == "relu":
             y = torch.relu(y)
         elif L.act == "relu6":
             y = torch.clamp(y, 0.0, 6.0)
+        elif L.act != "none":
+            y = {"hardswish": F.hardswish, "hardsigmoid": F.hardsigmoid, "silu": F.silu, "sigmoid": torch.sigmoid}[L.act](y)
         vals.append(y)
     return vals[-1].reshape(x.shape[0], -1).numpy()
 
@@ -114,7 +118,7 @@ def _rel(a, b):
 
 
 @pytest.mark.parametrize("fam,hw", [("tiny", 32), ("resnet18", 64), ("resnet50", 64), ("mobilenetv2", 64), ("vgg16", 32),
-                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64), ("densenet121", 64)])
+                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64), ("densenet121", 64), ("mobilenet_v3_large", 64), ("mobilenet_v3_small", 64)])
 def test_model_runner_vs_library_forward(fam, hw):
     m = zoo.tiny_cnn() if fam == "tiny" else zoo.FAMILIES[fam](hw=hw)
     blob = gen.make_blob(m, 1000 + hw)

@@ -302,6 +302,26 @@ def test_activations_and_top1():
     assert list(oracle.top1(z)) == [1, 0]  # lowest index on ties
 
 
+def test_smooth_activations_and_channel_scale(rng):
+    """Hard sigmoid is 0 below -3, 1 above 3 and (v+3)/6 between; hard swish is v times it; the logistic
+    sigmoid satisfies s(0) = 1/2 and s(v) + s(-v) = 1, SiLU is v times it; a library routine agrees on a grid.
+    The channel gate multiplies every pixel of plane (n, c) by g[n, c]."""
+    import torch.nn.functional as F
+    v = np.array([-7.0, -3.0, -1.5, 0.0, 1.5, 3.0, 7.0], np.float32)
+    assert np.array_equal(oracle.activate(v.copy(), "hardsigmoid"), np.array([0, 0, 0.25, 0.5, 0.75, 1, 1], np.float32))
+    assert np.array_equal(oracle.activate(v.copy(), "hardswish"), np.array([0, 0, -0.375, 0, 1.125, 3, 7], np.float32))
+    s = oracle.activate(v.copy(), "sigmoid")
+    assert s[3] == 0.5 and np.allclose(s + s[::-1], 1.0, atol=1e-7) and np.all(np.diff(s) > 0)
+    assert np.allclose(oracle.activate(v.copy(), "silu"), v * s, atol=1e-7)
+    grid = np.linspace(-9, 9, 721).astype(np.float32)
+    for name, fn in (("hardswish", F.hardswish), ("hardsigmoid", F.hardsigmoid), ("silu", F.silu), ("sigmoid", torch.sigmoid)):
+        ref = fn(torch.from_numpy(grid).double()).numpy()
+        assert np.abs(oracle.activate(grid.copy(), name) - ref).max() < 1e-6
+    x = rng.standard_normal((2, 3, 4, 5)).astype(np.float32)
+    g = rng.standard_normal((2, 3)).astype(np.float32)
+    assert np.array_equal(oracle.channel_scale(x, g), x * g[:, :, None, None])
+
+
 def test_bf16_rounding_is_nearest_even():
     # 1 + 2^-8 is exactly half-way between bf16 neighbours 1 and 1 + 2^-7: ties go to even (1.0)
     assert oracle.round_bf16(np.array([1.0 + 2.0 ** -8], np.float32))[0] == 1.0

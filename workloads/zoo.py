@@ -21,8 +21,8 @@ from typing import List
 
 # operator / activation names (strings on purpose: each executor maps them to
 # its own enum, so the two sides share no numeric constants)
-CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX, CONCAT, AVGPOOL = "conv", "dwconv", "maxpool", "gap", "fc", "softmax", "concat", "avgpool"
-NONE, RELU, RELU6 = "none", "relu", "relu6"
+CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX, CONCAT, AVGPOOL, MUL = "conv", "dwconv", "maxpool", "gap", "fc", "softmax", "concat", "avgpool", "mul"
+NONE, RELU, RELU6, HARDSWISH, HARDSIGMOID, SILU, SIGMOID = "none", "relu", "relu6", "hardswish", "hardsigmoid", "silu", "sigmoid"
 NO_RESIDUAL = -2
 MODEL_INPUT = -1
 
@@ -91,6 +91,11 @@ class Model:
                 assert not (L.op == AVGPOOL and L.ceil)
                 L.cin = L.cout = c
                 dims[i] = (c, pooled(h, L), pooled(w, L))
+            elif L.op == MUL:      # `input` scaled per (image, channel) by the 1x1 tensor `residual`
+                c2, h2, w2 = dims[L.residual]
+                assert (c2, h2, w2) == (c, 1, 1), (self.name, i)
+                L.cin = L.cout = c
+                dims[i] = (c, h, w)
             elif L.op == CONCAT:   # channels of `input`, then channels of `residual`
                 c2, h2, w2 = dims[L.residual]
                 assert (h2, w2) == (h, w), (self.name, i)
@@ -370,6 +375,56 @@ def squeezenet1_1(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Mo
     return m.shapes()
 
 
+def _divisible(v: float, d: int = 8) -> int:
+    n = max(d, int(v + d / 2) // d * d)
+    return n + d if n < 0.9 * v else n
+
+
+def _mobilenetv3(name: str, cfg, last: int, head: int, dtype: str, classes: int, hw: int) -> Model:
+    """MobileNetV3 (Howard et al. 2019, Tables 1 and 2): inverted residuals (kernel, expansion, width,
+    squeeze-excite, activation, stride); the squeeze-excite gate is global average -> FC (ReLU) -> FC (hard
+    sigmoid) with expansion/4 (rounded to 8) hidden units, applied per channel before the projection."""
+    m = Model(name, dtype, 3, hw, hw)
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=16, k=3, stride=2, pad=1, act=HARDSWISH)
+    cin = 16
+    for k, exp, c, se, act, stride in cfg:
+        a = x
+        if exp != cin:
+            a = m.add(CONV, a, cin=cin, cout=exp, k=1, stride=1, pad=0, act=act)
+        a = m.add(DWCONV, a, cin=exp, cout=exp, k=k, stride=stride, pad=k // 2, act=act)
+        if se:
+            sq = _divisible(exp // 4)
+            g = m.add(GAP, a)
+            g = m.add(FC, g, cin=exp, cout=sq, act=RELU)
+            g = m.add(FC, g, cin=sq, cout=exp, act=HARDSIGMOID)
+            a = m.add(MUL, a, residual=g)
+        skip = x if (stride == 1 and cin == c) else NO_RESIDUAL
+        x = m.add(CONV, a, cin=exp, cout=c, k=1, stride=1, pad=0, act=NONE, residual=skip)
+        cin = c
+    x = m.add(CONV, x, cin=cin, cout=last, k=1, stride=1, pad=0, act=HARDSWISH)
+    x = m.add(GAP, x)
+    x = m.add(FC, x, cin=last, cout=head, act=HARDSWISH)
+    m.add(FC, x, cin=head, cout=classes)
+    return m.shapes()
+
+
+def mobilenet_v3_large(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    R, H = RELU, HARDSWISH
+    cfg = ((3, 16, 16, False, R, 1), (3, 64, 24, False, R, 2), (3, 72, 24, False, R, 1), (5, 72, 40, True, R, 2),
+           (5, 120, 40, True, R, 1), (5, 120, 40, True, R, 1), (3, 240, 80, False, H, 2), (3, 200, 80, False, H, 1),
+           (3, 184, 80, False, H, 1), (3, 184, 80, False, H, 1), (3, 480, 112, True, H, 1), (3, 672, 112, True, H, 1),
+           (5, 672, 160, True, H, 2), (5, 960, 160, True, H, 1), (5, 960, 160, True, H, 1))
+    return _mobilenetv3("mobilenet_v3_large", cfg, 960, 1280, dtype, classes, hw)
+
+
+def mobilenet_v3_small(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    R, H = RELU, HARDSWISH
+    cfg = ((3, 16, 16, True, R, 2), (3, 72, 24, False, R, 2), (3, 88, 24, False, R, 1), (5, 96, 40, True, H, 2),
+           (5, 240, 40, True, H, 1), (5, 240, 40, True, H, 1), (5, 120, 48, True, H, 1), (5, 144, 48, True, H, 1),
+           (5, 288, 96, True, H, 2), (5, 576, 96, True, H, 1), (5, 576, 96, True, H, 1))
+    return _mobilenetv3("mobilenet_v3_small", cfg, 576, 1024, dtype, classes, hw)
+
+
 def _densenet(name: str, growth: int, blocks, init: int, dtype: str, classes: int, hw: int) -> Model:
     """DenseNet-BC (Huang et al. 2017): every dense layer normalises and rectifies the concatenation of all
     earlier features (a per-channel scale and shift: a 1x1 depthwise node here, it cannot be folded because
@@ -482,4 +537,6 @@ FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             # ... and grouped convolution
             "resnext50_32x4d": resnext50_32x4d, "resnext101_32x8d": resnext101_32x8d,
             # ... and window average pooling with per-channel affine nodes
+            # ... and squeeze-excite gates with hard-swish / hard-sigmoid activations
+            "mobilenet_v3_large": mobilenet_v3_large, "mobilenet_v3_small": mobilenet_v3_small,
             "densenet121": densenet121, "densenet169": densenet169, "densenet201": densenet201, "densenet161": densenet161}
