@@ -132,7 +132,7 @@ def test_further_table3_families_fused():
     32x4d with grouped convolution; DenseNet-121 with window average pooling and per-channel affine nodes; MobileNetV3 Large with squeeze-excite gates
     and hard-swish), all sixteen fused in one DAG at a reduced image size, each member against the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
     from tests import harness
-    WIDE_HERE = {"mnasnet1_0", "mobilenet_v3_large"}   # MobileNet-style inverted-residual networks keep fp32 activations
+    WIDE_HERE = {"mnasnet1_0", "mobilenet_v3_large"}   # inverted-residual networks keep fp32 activations
     fams = ["alexnet", "vgg11", "vgg13", "vgg19", "resnet34", "resnet101", "resnet152", "wide_resnet50_2", "wide_resnet101_2", "mnasnet1_0",
             "squeezenet1_0", "squeezenet1_1", "googlenet", "resnext50_32x4d", "densenet121", "mobilenet_v3_large"]
     mem = []
@@ -152,6 +152,35 @@ def test_further_table3_families_fused():
     res = harness.oracle_units(units)
     for i, f in enumerate(fams):
         _check_member(f, ys[i], res[2 * i], res[2 * i + 1], 1e-4 if f in WIDE_HERE else 1e-2)
+
+
+def test_efficientnet_v2_prefix():
+    """EfficientNetV2-S with these synthetic weights is ill-conditioned as a whole: its activations grow by orders
+    of magnitude through 40 residual blocks and the oracle's own fp32 and fp64-accumulation builds end 0.7 apart in
+    relative L2, so the full model has no meaningful parity target (parity unpinned).  The prefix through the second
+    squeeze-excite block (fused blocks, depthwise blocks, SiLU, sigmoid gate), where the two oracle builds still
+    agree to 1e-5, is held to the fp32-activation bar."""
+    import copy
+    import oracle
+    from tests import harness
+    full = zoo.FAMILIES["efficientnet_v2_s"](hw=96)
+    cut = [i for i, L in enumerate(full.layers) if L.op == "mul"][1] + 1     # the projection after the second gate
+    m = zoo.Model("efficientnet_v2_s_prefix", "bf16", 3, 96, 96)
+    m.layers = [copy.copy(L) for L in full.layers[:cut + 1]]
+    m.shapes()
+    blob = gen.make_blob(m, 1016)
+    x = gen.make_input(7, 2, 3, 96, 96, "normal", "bf16")
+    y32 = oracle.run_model(m, blob, x, round_storage=False)
+    y64 = oracle.run_model(m, blob, x, round_storage=False, f64=True)
+    assert harness.rel_l2(y32, y64) < 1e-5                                    # the target itself is well conditioned here
+    g = harness.GpuDag([(m, blob, "f32")], 2)
+    try:
+        y = g.run(x)[0]
+    finally:
+        g.close()
+    e = harness.rel_l2(y, harness.oracle_nhwc(m, blob, x, False))
+    print(f"  efficientnet_v2_s prefix ({cut + 1} nodes): relL2 {e:.3e}")
+    assert e <= 1e-4
 
 
 def test_config5_swap_churn_sampled():

@@ -425,6 +425,53 @@ def mobilenet_v3_small(dtype: str = "bf16", classes: int = 1000, hw: int = 224) 
     return _mobilenetv3("mobilenet_v3_small", cfg, 576, 1024, dtype, classes, hw)
 
 
+def _efficientnet_v2(name: str, stages, dtype: str, classes: int, hw: int) -> Model:
+    """EfficientNetV2 (Tan & Le 2021, Table 4): fused blocks (3x3 expansion convolution, 1x1 projection) in
+    the early stages, then depthwise blocks with a squeeze-excite gate whose hidden width is a quarter of
+    the block's input width; SiLU throughout, a sigmoid on the gate.  stages: (fused, expansion, stride,
+    width, repeats)."""
+    m = Model(name, dtype, 3, hw, hw)
+    cin = stages[0][3]
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=cin, k=3, stride=2, pad=1, act=SILU)
+    for fused, e, s0, c, n in stages:
+        for rep in range(n):
+            stride = s0 if rep == 0 else 1
+            skip = x if (stride == 1 and cin == c) else NO_RESIDUAL
+            if fused and e == 1:
+                x = m.add(CONV, x, cin=cin, cout=c, k=3, stride=stride, pad=1, act=SILU, residual=skip)
+            elif fused:
+                a = m.add(CONV, x, cin=cin, cout=cin * e, k=3, stride=stride, pad=1, act=SILU)
+                x = m.add(CONV, a, cin=cin * e, cout=c, k=1, stride=1, pad=0, act=NONE, residual=skip)
+            else:
+                a = m.add(CONV, x, cin=cin, cout=cin * e, k=1, stride=1, pad=0, act=SILU)
+                a = m.add(DWCONV, a, cin=cin * e, cout=cin * e, k=3, stride=stride, pad=1, act=SILU)
+                g = m.add(GAP, a)
+                g = m.add(FC, g, cin=cin * e, cout=max(1, cin // 4), act=SILU)
+                g = m.add(FC, g, cin=max(1, cin // 4), cout=cin * e, act=SIGMOID)
+                a = m.add(MUL, a, residual=g)
+                x = m.add(CONV, a, cin=cin * e, cout=c, k=1, stride=1, pad=0, act=NONE, residual=skip)
+            cin = c
+    x = m.add(CONV, x, cin=cin, cout=1280, k=1, stride=1, pad=0, act=SILU)
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=1280, cout=classes)
+    return m.shapes()
+
+
+def efficientnet_v2_s(dtype: str = "bf16", classes: int = 1000, hw: int = 384) -> Model:
+    return _efficientnet_v2("efficientnet_v2_s", ((True, 1, 1, 24, 2), (True, 4, 2, 48, 4), (True, 4, 2, 64, 4),
+                            (False, 4, 2, 128, 6), (False, 6, 1, 160, 9), (False, 6, 2, 256, 15)), dtype, classes, hw)
+
+
+def efficientnet_v2_m(dtype: str = "bf16", classes: int = 1000, hw: int = 480) -> Model:
+    return _efficientnet_v2("efficientnet_v2_m", ((True, 1, 1, 24, 3), (True, 4, 2, 48, 5), (True, 4, 2, 80, 5), (False, 4, 2, 160, 7),
+                            (False, 6, 1, 176, 14), (False, 6, 2, 304, 18), (False, 6, 1, 512, 5)), dtype, classes, hw)
+
+
+def efficientnet_v2_l(dtype: str = "bf16", classes: int = 1000, hw: int = 480) -> Model:
+    return _efficientnet_v2("efficientnet_v2_l", ((True, 1, 1, 32, 4), (True, 4, 2, 64, 7), (True, 4, 2, 96, 7), (False, 4, 2, 192, 10),
+                            (False, 6, 1, 224, 19), (False, 6, 2, 384, 25), (False, 6, 1, 640, 7)), dtype, classes, hw)
+
+
 def _densenet(name: str, growth: int, blocks, init: int, dtype: str, classes: int, hw: int) -> Model:
     """DenseNet-BC (Huang et al. 2017): every dense layer normalises and rectifies the concatenation of all
     earlier features (a per-channel scale and shift: a 1x1 depthwise node here, it cannot be folded because
@@ -539,4 +586,5 @@ FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             # ... and window average pooling with per-channel affine nodes
             # ... and squeeze-excite gates with hard-swish / hard-sigmoid activations
             "mobilenet_v3_large": mobilenet_v3_large, "mobilenet_v3_small": mobilenet_v3_small,
+            "efficientnet_v2_s": efficientnet_v2_s, "efficientnet_v2_m": efficientnet_v2_m, "efficientnet_v2_l": efficientnet_v2_l,
             "densenet121": densenet121, "densenet169": densenet169, "densenet201": densenet201, "densenet161": densenet161}
