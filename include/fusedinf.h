@@ -49,7 +49,7 @@ typedef enum {
 } fi_status;
 
 typedef enum { FI_F32 = 0, FI_BF16 = 1 } fi_dtype;
-typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5, FI_CONCAT = 6, FI_AVGPOOL2D = 7, FI_MUL = 8 } fi_op;
+typedef enum { FI_CONV2D = 0, FI_DWCONV2D = 1, FI_MAXPOOL2D = 2, FI_GLOBAL_AVGPOOL = 3, FI_FC = 4, FI_SOFTMAX = 5, FI_CONCAT = 6, FI_AVGPOOL2D = 7, FI_MUL = 8, FI_SLICE = 9, FI_SHUFFLE = 10 } fi_op;
 /* hard sigmoid h(v) = min(max(v + 3, 0), 6) / 6, hard swish v * h(v); sigmoid s(v) = 1 / (1 + exp(-v)), SiLU v * s(v) */
 typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2, FI_ACT_HARDSWISH = 3, FI_ACT_HARDSIGMOID = 4,
                FI_ACT_SILU = 5, FI_ACT_SIGMOID = 6 } fi_act;
@@ -73,6 +73,9 @@ typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2, FI_ACT_HARDSW
  *     floor output size, one rounding on store.
  *   mul: `input` scaled per (image, channel) by the 1x1 tensor `residual` (the gate of a
  *     squeeze-and-excitation block); no activation.
+ *   slice: channels [c_first, c_first + cout) of `input`.   shuffle: the channels, seen as a
+ *     groups x (C/groups) matrix, transposed (output channel i*groups + g = input channel
+ *     g*(C/groups) + i).  Both move values unchanged; no activation.
  *   concat: the channels of `input` followed by the channels of `residual` (here: the
  *     second source, same height and width); no activation.  cout = sum of both.
  *   global_avgpool: mean over H*W.   softmax: over the channel axis of a 1x1 tensor.
@@ -87,7 +90,9 @@ typedef struct {
   int32_t cin, cout, kh, kw, stride, pad;
   int32_t act;      /* fi_act */
   int32_t ceil_mode; /* maxpool2d only: 1 = output size rounds up */
-  int32_t groups;    /* conv2d only: channel groups (0 or 1 = dense); must divide cin and cout */
+  int32_t groups;    /* conv2d: channel groups (0 or 1 = dense), must divide cin and cout; shuffle: groups */
+  int32_t c_first;   /* slice only: first channel taken */
+  int32_t reserved;
   uint64_t w_off, b_off;
 } fi_layer_spec;
 

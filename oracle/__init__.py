@@ -16,7 +16,7 @@ import numpy as np
 from . import build as _build
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_OPS = {"conv": 0, "dwconv": 1, "maxpool": 2, "gap": 3, "fc": 4, "softmax": 5, "concat": 6, "avgpool": 7, "mul": 8}
+_OPS = {"conv": 0, "dwconv": 1, "maxpool": 2, "gap": 3, "fc": 4, "softmax": 5, "concat": 6, "avgpool": 7, "mul": 8, "slice": 9, "shuffle": 10}
 _ACTS = {"none": 0, "relu": 1, "relu6": 2, "hardswish": 3, "hardsigmoid": 4, "silu": 5, "sigmoid": 6}
 _DT = {"f32": 0, "bf16": 1}
 
@@ -25,7 +25,7 @@ class OrcLayer(C.Structure):
     _fields_ = [("op", C.c_int32), ("act", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32),
                 ("cin", C.c_int32), ("cout", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32),
                 ("pad", C.c_int32), ("ceil_mode", C.c_int32), ("w_off", C.c_int64), ("b_off", C.c_int64),
-                ("groups", C.c_int32), ("reserved", C.c_int32)]
+                ("groups", C.c_int32), ("c_first", C.c_int32)]
 
 
 _FP = C.POINTER(C.c_float)
@@ -42,6 +42,8 @@ def lib(f64: bool = False):
         L.orc_maxpool2d_ex.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_avgpool2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_channel_scale.argtypes = [_FP, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
+        L.orc_slice.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
+        L.orc_channel_shuffle.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_concat.argtypes = [_FP, C.c_int, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_dwconv2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_maxpool2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
@@ -141,6 +143,22 @@ def channel_scale(x, g):
     return y
 
 
+def channel_slice(x, first, count):
+    x, xp = _f(x)
+    n, c, h, w = x.shape
+    y = np.empty((n, count, h, w), dtype=np.float32)
+    lib().orc_slice(xp, n, c, h, w, first, count, y.ctypes.data_as(_FP))
+    return y
+
+
+def channel_shuffle(x, groups):
+    x, xp = _f(x)
+    n, c, h, w = x.shape
+    y = np.empty_like(x)
+    lib().orc_channel_shuffle(xp, n, c, h, w, groups, y.ctypes.data_as(_FP))
+    return y
+
+
 def concat(a, b):
     a, ap = _f(a)
     b, bp = _f(b)
@@ -203,7 +221,7 @@ def layer_table(model):
     arr = (OrcLayer * len(model.layers))()
     for i, L in enumerate(model.layers):
         arr[i] = OrcLayer(_OPS[L.op], _ACTS[L.act], L.input, L.residual, L.cin, L.cout, L.k, L.stride,
-                          L.pad, int(getattr(L, "ceil", False)), L.w_off, L.b_off, int(getattr(L, "groups", 1)), 0)
+                          L.pad, int(getattr(L, "ceil", False)), L.w_off, L.b_off, int(getattr(L, "groups", 1)), int(getattr(L, "first", 0)))
     return arr
 
 

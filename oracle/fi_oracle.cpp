@@ -59,7 +59,7 @@ typedef ORC_ACC acc_t;
 
 extern "C" {
 
-enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5, ORC_CONCAT = 6, ORC_AVGPOOL = 7, ORC_MUL = 8 };
+enum { ORC_CONV = 0, ORC_DWCONV = 1, ORC_MAXPOOL = 2, ORC_GAP = 3, ORC_FC = 4, ORC_SOFTMAX = 5, ORC_CONCAT = 6, ORC_AVGPOOL = 7, ORC_MUL = 8, ORC_SLICE = 9, ORC_SHUFFLE = 10 };
 enum { ORC_NONE = 0, ORC_RELU = 1, ORC_RELU6 = 2, ORC_HARDSWISH = 3, ORC_HARDSIGMOID = 4, ORC_SILU = 5, ORC_SIGMOID = 6 };
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
 
@@ -72,8 +72,8 @@ struct orc_layer {
   int32_t cin, cout, k, stride, pad;
   int32_t ceil_mode; // pooling: output size rounds up
   int64_t w_off, b_off;  // byte offsets into the canonical weight blob
-  int32_t groups;        // conv: number of channel groups (0 or 1 = dense)
-  int32_t reserved;
+  int32_t groups;        // conv: number of channel groups (0 or 1 = dense); shuffle: number of groups
+  int32_t c_first;       // slice: first channel taken
 };
 
 // ---- scalar helpers -------------------------------------------------------
@@ -271,6 +271,27 @@ void orc_avgpool2d(const float* x, int N, int C, int H, int W, int k, int s, int
   }
 }
 
+// Channel slice: planes [first, first + count) of every image.
+void orc_slice(const float* x, int N, int C, int H, int W, int first, int count, float* y) {
+  const int64_t hw = (int64_t)H * W;
+  for (int n = 0; n < N; ++n)
+    for (int64_t i = 0; i < count * hw; ++i) y[(int64_t)n * count * hw + i] = x[((int64_t)n * C + first) * hw + i];
+}
+
+// Channel shuffle with G groups: the channels seen as a G x (C/G) matrix are transposed, i.e.
+// output channel i*G + g is input channel g*(C/G) + i.
+void orc_channel_shuffle(const float* x, int N, int C, int H, int W, int G, float* y) {
+  const int64_t hw = (int64_t)H * W;
+  const int per = C / G;
+  for (int n = 0; n < N; ++n)
+    for (int g = 0; g < G; ++g)
+      for (int i = 0; i < per; ++i) {
+        const float* src = x + ((int64_t)n * C + g * per + i) * hw;
+        float* dst = y + ((int64_t)n * C + i * G + g) * hw;
+        for (int64_t q = 0; q < hw; ++q) dst[q] = src[q];
+      }
+}
+
 // Channel concatenation (NCHW): image n of y holds a's Ca planes, then b's Cb planes.
 void orc_concat(const float* a, int Ca, const float* b, int Cb, int N, int H, int W, float* y) {
   const int64_t hw = (int64_t)H * W;
@@ -409,6 +430,20 @@ int64_t orc_run_model(const orc_layer* layers, int n_layers, int output_node, co
         o.c = c; o.h = h; o.w = w;
         o.v.resize((size_t)N * c * h * w);
         orc_channel_scale(in, gt.v.data(), N, c, h, w, o.v.data());
+        break;
+      }
+      case ORC_SLICE: {
+        if (L.c_first < 0 || L.cout < 1 || L.c_first + L.cout > c) return -2;
+        o.c = L.cout; o.h = h; o.w = w;
+        o.v.resize((size_t)N * o.c * h * w);
+        orc_slice(in, N, c, h, w, L.c_first, L.cout, o.v.data());
+        break;
+      }
+      case ORC_SHUFFLE: {
+        if (L.groups < 1 || c % L.groups) return -2;
+        o.c = c; o.h = h; o.w = w;
+        o.v.resize((size_t)N * c * h * w);
+        orc_channel_shuffle(in, N, c, h, w, L.groups, o.v.data());
         break;
       }
       case ORC_AVGPOOL: {

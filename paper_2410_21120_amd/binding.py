@@ -15,7 +15,7 @@ from . import build as _build
 
 FI_OK, FI_EINVAL, FI_EUNSUPPORTED, FI_ESTATE, FI_ENOMEM_HOST, FI_ENOMEM_DEVICE, FI_EBUDGET, FI_EHIP = range(8)
 FI_F32, FI_BF16 = 0, 1
-FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX, FI_CONCAT, FI_AVGPOOL2D, FI_MUL = range(9)
+FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX, FI_CONCAT, FI_AVGPOOL2D, FI_MUL, FI_SLICE, FI_SHUFFLE = range(11)
 FI_ACT_NONE, FI_ACT_RELU, FI_ACT_RELU6, FI_ACT_HARDSWISH, FI_ACT_HARDSIGMOID, FI_ACT_SILU, FI_ACT_SIGMOID = range(7)
 FI_INPUT, FI_NO_RESIDUAL = -1, -2
 FI_LOAD_ONE_COPY, FI_LOAD_PER_MODEL = 0, 1
@@ -28,7 +28,7 @@ class fi_layer_spec(C.Structure):
     _fields_ = [("op", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32), ("cin", C.c_int32),
                 ("cout", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32),
                 ("pad", C.c_int32), ("act", C.c_int32), ("ceil_mode", C.c_int32), ("groups", C.c_int32),
-                ("w_off", C.c_uint64), ("b_off", C.c_uint64)]
+                ("c_first", C.c_int32), ("reserved", C.c_int32), ("w_off", C.c_uint64), ("b_off", C.c_uint64)]
 
 
 class fi_model_spec(C.Structure):
@@ -280,7 +280,7 @@ def fi_destroy(h) -> None:
 
 # ---- marshalling helpers ---------------------------------------------------------------------
 _OPS = {"conv": FI_CONV2D, "dwconv": FI_DWCONV2D, "maxpool": FI_MAXPOOL2D, "gap": FI_GLOBAL_AVGPOOL,
-        "fc": FI_FC, "softmax": FI_SOFTMAX, "concat": FI_CONCAT, "avgpool": FI_AVGPOOL2D, "mul": FI_MUL}
+        "fc": FI_FC, "softmax": FI_SOFTMAX, "concat": FI_CONCAT, "avgpool": FI_AVGPOOL2D, "mul": FI_MUL, "slice": FI_SLICE, "shuffle": FI_SHUFFLE}
 _ACTS = {"none": FI_ACT_NONE, "relu": FI_ACT_RELU, "relu6": FI_ACT_RELU6, "hardswish": FI_ACT_HARDSWISH,
          "hardsigmoid": FI_ACT_HARDSIGMOID, "silu": FI_ACT_SILU, "sigmoid": FI_ACT_SIGMOID}
 _DT = {"f32": FI_F32, "bf16": FI_BF16}
@@ -292,7 +292,7 @@ def make_spec(model, weights_ptr: int, weight_bytes: int, act_dtype=None, packed
     layers = (fi_layer_spec * len(model.layers))()
     for i, L in enumerate(model.layers):
         layers[i] = fi_layer_spec(_OPS[L.op], L.input, L.residual, L.cin, L.cout, L.k, L.k, L.stride, L.pad,
-                                  _ACTS[L.act], int(getattr(L, "ceil", False)), int(getattr(L, "groups", 1)), L.w_off, L.b_off)
+                                  _ACTS[L.act], int(getattr(L, "ceil", False)), int(getattr(L, "groups", 1)), int(getattr(L, "first", 0)), 0, L.w_off, L.b_off)
     name = model.name.encode()
     dt = _DT[model.dtype]
     spec = fi_model_spec(name, dt, dt if act_dtype is None else _DT.get(act_dtype, act_dtype), model.in_c, model.in_h,

@@ -141,6 +141,7 @@ const char* kind_name(int kind, int tile) {
     case K_CONCAT: return "concat";
     case K_AVGPOOL: return "avgpool";
     case K_MUL: return "channel_scale";
+    case K_GATHER: return "channel_gather";
   }
   return "?";
 }
@@ -371,6 +372,8 @@ static fi_status plan_dag(fi_dag* g) {
       case FI_CONCAT: nd.kind = K_CONCAT; break;
       case FI_AVGPOOL2D: nd.kind = K_AVGPOOL; break;
       case FI_MUL: nd.kind = K_MUL; break;
+      case FI_SLICE:
+      case FI_SHUFFLE: nd.kind = K_GATHER; break;
       default: nd.kind = K_SOFTMAX; break;
     }
   }
@@ -569,6 +572,8 @@ static fi_status plan_dag(fi_dag* g) {
       d.H = nd.H; d.W = nd.W; d.C = nd.C; d.Cp = nd.Cp;
       d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop;
       d.k = nd.k; d.stride = nd.stride; d.pad = nd.pad; d.act = nd.act; d.Kp = nd.Kp;
+      if (nd.op == FI_SLICE) d.stride = 0;     // gather mode: slice
+      if (nd.op == FI_SHUFFLE) d.stride = 1;   // gather mode: shuffle
       if (nd.op == FI_CONCAT) {  // second source: channels in Kp, channel stride in tiles_n (set below)
         d.Kp = g->nodes[(size_t)nd.residual].Co;
       }

@@ -27,6 +27,7 @@ enum Kind : int32_t {
   K_CONCAT = 9,       // channels of the first source, then of the second
   K_AVGPOOL = 10,     // window average (divisor k*k)
   K_MUL = 11,         // per-(image, channel) gate
+  K_GATHER = 12,      // channel slice (stride == 0: channels from pad on) or shuffle (stride == 1: k groups)
   K_NKINDS
 };
 

@@ -57,6 +57,7 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
+    case K_GATHER: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
     case K_CONCAT:
     case K_MUL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
   }
@@ -591,6 +592,32 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
         }
       }
     }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// channel gather: output channel c is input channel pad + c (slice, stride == 0) or
+// (c mod k) * (C / k) + c / k (shuffle in k groups, stride == 1); values move unchanged
+// ---------------------------------------------------------------------------------
+template <typename TA>
+__global__ void __launch_bounds__(256) gather_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_GATHER, 0, p, bid)) return;
+  const Desc d = a.d[p];
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
+  const int c = (int)(idx % d.Cop);
+  const int64_t m = idx / d.Cop;
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
+  float v = 0.0f;
+  if (c < d.Co) {
+    const int src = d.stride == 0 ? d.pad + c : (c % d.k) * (d.C / d.k) + c / d.k;
+    v = ld(x + m * d.Cp + src);
+  }
+  if (d.ext) {
+    if (c < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + c] = v;
+  } else {
+    st(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c, v);
   }
 }
 
@@ -1155,6 +1182,8 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       return ab ? go(reduce_kernel<bf16_t>, nb, 256, a, s) : go(reduce_kernel<float>, nb, 256, a, s);
     case K_SOFTMAX:
       return go(softmax_kernel, nb, 64, a, s);
+    case K_GATHER:
+      return ab ? go(gather_kernel<bf16_t>, nb, 256, a, s) : go(gather_kernel<float>, nb, 256, a, s);
     case K_MUL:
       return ab ? go(mul_kernel<bf16_t>, nb, 256, a, s) : go(mul_kernel<float>, nb, 256, a, s);
     case K_CONCAT:

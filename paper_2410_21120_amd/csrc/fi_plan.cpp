@@ -104,6 +104,20 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         }
         if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: pooling takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
         break;
+      case FI_SLICE:
+        if (L.input == FI_INPUT) { set_error("model %s node %d: slicing the model input is not supported", nm, i); return FI_EUNSUPPORTED; }
+        if (L.c_first < 0 || L.cout < 1 || L.c_first + L.cout > n.C) { set_error("model %s node %d: slice [%d, %d) outside %d channels", nm, i, L.c_first, L.c_first + L.cout, n.C); return FI_EINVAL; }
+        if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: slice takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
+        n.Co = L.cout; n.Ho = n.H; n.Wo = n.W;
+        n.pad = L.c_first;   // first channel, carried in the pad field of the descriptor
+        break;
+      case FI_SHUFFLE:
+        if (L.input == FI_INPUT) { set_error("model %s node %d: shuffling the model input is not supported", nm, i); return FI_EUNSUPPORTED; }
+        if (L.groups < 1 || n.C % L.groups) { set_error("model %s node %d: %d groups do not divide %d channels", nm, i, L.groups, n.C); return FI_EINVAL; }
+        if (L.act != FI_ACT_NONE || L.residual != FI_NO_RESIDUAL) { set_error("model %s node %d: shuffle takes no activation/residual", nm, i); return FI_EUNSUPPORTED; }
+        n.Co = n.C; n.Ho = n.H; n.Wo = n.W;
+        n.k = L.groups;      // groups, carried in the k field of the descriptor
+        break;
       case FI_MUL: {
         if (L.residual == FI_NO_RESIDUAL || L.input == FI_INPUT) { set_error("model %s node %d: channel scaling needs a tensor and a gate node", nm, i); return FI_EINVAL; }
         const Node& gt = out.nodes[(size_t)L.residual];

@@ -233,6 +233,40 @@ def test_squeeze_excite_block(case, mode):
 
 
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_slice_branch_concat_shuffle_unit(mode):
+    """One ShuffleNet-V2-style unit: half of the channels kept, the other half through 1x1 -> depthwise -> 1x1,
+    concatenated and shuffled in two groups; odd half-width (29) so the element paths with ragged padding run."""
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("shuf", dtype, 8, 10, 9)
+    x = m.add(zoo.CONV, -1, cin=8, cout=58, k=1, stride=1, pad=0, act=zoo.RELU)
+    a = m.add(zoo.SLICE, x, first=0, cout=29)
+    b = m.add(zoo.SLICE, x, first=29, cout=29)
+    b = m.add(zoo.CONV, b, cin=29, cout=29, k=1, stride=1, pad=0, act=zoo.RELU)
+    b = m.add(zoo.DWCONV, b, cin=29, cout=29, k=3, stride=1, pad=1, act=zoo.NONE)
+    y = m.add(zoo.CONCAT, a, residual=b)
+    y = m.add(zoo.SHUFFLE, y, groups=2)
+    m.add(zoo.CONV, y, cin=58, cout=12, k=1, stride=1, pad=0, act=zoo.NONE)
+    _run_case(m, 1300, 2, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+def test_shuffle_as_output_node_is_exact():
+    from tests import harness
+    m = zoo.Model("shuf_out", "bf16", 24, 5, 7)
+    a = m.add(zoo.MAXPOOL, -1, k=1, stride=1, pad=0)
+    a = m.add(zoo.SLICE, a, first=6, cout=12)
+    m.add(zoo.SHUFFLE, a, groups=4)
+    m.shapes()
+    x = gen.make_input(3, 2, 24, 5, 7, "normal", "bf16")
+    blob = np.zeros(64, np.uint8)
+    g = harness.GpuDag([(m, blob, None)], 2)
+    try:
+        y = g.run(x)[0]
+    finally:
+        g.close()
+    assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, True))
+
+
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_gap_fc_softmax_chain(mode):
     dtype = "f32" if mode == "f32" else "bf16"
     m = zoo.Model("g", dtype, 24, 7, 9)

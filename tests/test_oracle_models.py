@@ -27,6 +27,7 @@ def test_structure(fam):
     assert (ops.count("conv"), ops.count("dwconv"), ops.count("maxpool"), ops.count("gap"), ops.count("fc")) == \
         (g["conv"], g["dwconv"], g["maxpool"], g["gap"], g["fc"])
     assert ops.count("concat") == g.get("concat", 0) and ops.count("avgpool") == g.get("avgpool", 0) and ops.count("mul") == g.get("mul", 0)
+    assert ops.count("slice") == g.get("slice", 0) and ops.count("shuffle") == g.get("shuffle", 0)
     assert max(m.levels()) == g["depth"]
     assert m.n_params() == g["params"]
     assert m.macs() == g["macs"]
@@ -91,6 +92,11 @@ def _torch_forward(model, blob, x, dtype=torch.float64):
             y = F.max_pool2d(inp, L.k, L.stride, L.pad, ceil_mode=bool(L.ceil))
         elif L.op == "mul":
             y = inp * vals[L.residual]
+        elif L.op == "slice":
+            y = inp[:, L.first:L.first + L.cout]
+        elif L.op == "shuffle":
+            n_, c_, h_, w_ = inp.shape
+            y = inp.view(n_, L.groups, c_ // L.groups, h_, w_).transpose(1, 2).reshape(n_, c_, h_, w_)
         elif L.op == "avgpool":
             y = F.avg_pool2d(inp, L.k, L.stride, L.pad)
         elif L.op == "concat":
@@ -118,7 +124,7 @@ def _rel(a, b):
 
 
 @pytest.mark.parametrize("fam,hw", [("tiny", 32), ("resnet18", 64), ("resnet50", 64), ("mobilenetv2", 64), ("vgg16", 32),
-                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64), ("densenet121", 64), ("mobilenet_v3_large", 64), ("mobilenet_v3_small", 64)])
+                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64), ("densenet121", 64), ("mobilenet_v3_large", 64), ("mobilenet_v3_small", 64), ("shufflenet_v2_x1_0", 64)])
 def test_model_runner_vs_library_forward(fam, hw):
     m = zoo.tiny_cnn() if fam == "tiny" else zoo.FAMILIES[fam](hw=hw)
     blob = gen.make_blob(m, 1000 + hw)

@@ -322,6 +322,22 @@ def test_smooth_activations_and_channel_scale(rng):
     assert np.array_equal(oracle.channel_scale(x, g), x * g[:, :, None, None])
 
 
+def test_channel_slice_and_shuffle(rng):
+    """A slice is a range of planes; a shuffle in G groups transposes the G x (C/G) channel matrix: with the
+    channel index stored in the values it sends channel g*(C/G)+i to i*G+g, G = 1 and G = C are the identity,
+    and shuffling by G then by C/G restores the input."""
+    x = rng.standard_normal((2, 12, 3, 4)).astype(np.float32)
+    assert np.array_equal(oracle.channel_slice(x, 5, 4), x[:, 5:9])
+    assert np.array_equal(oracle.channel_slice(x, 0, 12), x)
+    idx = np.broadcast_to(np.arange(12, dtype=np.float32)[None, :, None, None], (1, 12, 2, 2)).copy()
+    y = oracle.channel_shuffle(idx, 3)[0, :, 0, 0]
+    assert np.array_equal(y, np.array([0, 4, 8, 1, 5, 9, 2, 6, 10, 3, 7, 11], np.float32))
+    assert np.array_equal(oracle.channel_shuffle(x, 1), x) and np.array_equal(oracle.channel_shuffle(x, 12), x)
+    assert np.array_equal(oracle.channel_shuffle(oracle.channel_shuffle(x, 3), 4), x)
+    ref = torch.from_numpy(x).view(2, 2, 6, 3, 4).transpose(1, 2).reshape(2, 12, 3, 4).numpy()
+    assert np.array_equal(oracle.channel_shuffle(x, 2), ref)
+
+
 def test_bf16_rounding_is_nearest_even():
     # 1 + 2^-8 is exactly half-way between bf16 neighbours 1 and 1 + 2^-7: ties go to even (1.0)
     assert oracle.round_bf16(np.array([1.0 + 2.0 ** -8], np.float32))[0] == 1.0

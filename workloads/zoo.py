@@ -21,7 +21,7 @@ from typing import List
 
 # operator / activation names (strings on purpose: each executor maps them to
 # its own enum, so the two sides share no numeric constants)
-CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX, CONCAT, AVGPOOL, MUL = "conv", "dwconv", "maxpool", "gap", "fc", "softmax", "concat", "avgpool", "mul"
+CONV, DWCONV, MAXPOOL, GAP, FC, SOFTMAX, CONCAT, AVGPOOL, MUL, SLICE, SHUFFLE = "conv", "dwconv", "maxpool", "gap", "fc", "softmax", "concat", "avgpool", "mul", "slice", "shuffle"
 NONE, RELU, RELU6, HARDSWISH, HARDSIGMOID, SILU, SIGMOID = "none", "relu", "relu6", "hardswish", "hardsigmoid", "silu", "sigmoid"
 NO_RESIDUAL = -2
 MODEL_INPUT = -1
@@ -39,7 +39,8 @@ class Layer:
     act: str = NONE
     residual: int = NO_RESIDUAL   # node added before the activation; for a concat node: the second source
     ceil: bool = False            # pooling: output size rounds up (windows may hang over the bottom / right edge)
-    groups: int = 1               # conv: input and output channels are cut into this many independent groups
+    groups: int = 1               # conv: input and output channels are cut into this many independent groups; shuffle: groups
+    first: int = 0                # slice: first channel taken (cout channels from there)
     bias: bool = True             # False: the layer has no bias in the architecture (its stored bias is all zero)
     bn: bool = True               # conv / depthwise with a bias: the bias stands for a folded BatchNorm
     # filled by shapes(): logical input / output spatial sizes
@@ -91,6 +92,14 @@ class Model:
                 assert not (L.op == AVGPOOL and L.ceil)
                 L.cin = L.cout = c
                 dims[i] = (c, pooled(h, L), pooled(w, L))
+            elif L.op == SLICE:
+                assert 0 <= L.first and L.first + L.cout <= c, (self.name, i)
+                L.cin = c
+                dims[i] = (L.cout, h, w)
+            elif L.op == SHUFFLE:
+                assert c % L.groups == 0, (self.name, i)
+                L.cin = L.cout = c
+                dims[i] = (c, h, w)
             elif L.op == MUL:      # `input` scaled per (image, channel) by the 1x1 tensor `residual`
                 c2, h2, w2 = dims[L.residual]
                 assert (c2, h2, w2) == (c, 1, 1), (self.name, i)
@@ -472,6 +481,45 @@ def efficientnet_v2_l(dtype: str = "bf16", classes: int = 1000, hw: int = 480) -
                             (False, 6, 1, 224, 19), (False, 6, 2, 384, 25), (False, 6, 1, 640, 7)), dtype, classes, hw)
 
 
+def _shufflenet_v2(name: str, widths, dtype: str, classes: int, hw: int) -> Model:
+    """ShuffleNet V2 (Ma et al. 2018, Table 5): a unit keeps half of its channels and sends the other half
+    through 1x1 -> 3x3 depthwise (no activation) -> 1x1, concatenates and shuffles the channels in two groups;
+    a down-sampling unit runs both halves from the whole input, the first through depthwise/2 -> 1x1."""
+    m = Model(name, dtype, 3, hw, hw)
+    x = m.add(CONV, MODEL_INPUT, cin=3, cout=24, k=3, stride=2, pad=1, act=RELU)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=1)
+    cin = 24
+    for c, reps in zip(widths[:3], (4, 8, 4)):
+        half = c // 2
+        for rep in range(reps):
+            if rep == 0:
+                a = m.add(DWCONV, x, cin=cin, cout=cin, k=3, stride=2, pad=1, act=NONE)
+                a = m.add(CONV, a, cin=cin, cout=half, k=1, stride=1, pad=0, act=RELU)
+                b = m.add(CONV, x, cin=cin, cout=half, k=1, stride=1, pad=0, act=RELU)
+                b = m.add(DWCONV, b, cin=half, cout=half, k=3, stride=2, pad=1, act=NONE)
+            else:
+                a = m.add(SLICE, x, first=0, cout=half)
+                b = m.add(SLICE, x, first=half, cout=half)
+                b = m.add(CONV, b, cin=half, cout=half, k=1, stride=1, pad=0, act=RELU)
+                b = m.add(DWCONV, b, cin=half, cout=half, k=3, stride=1, pad=1, act=NONE)
+            b = m.add(CONV, b, cin=half, cout=half, k=1, stride=1, pad=0, act=RELU)
+            x = m.add(CONCAT, a, residual=b)
+            x = m.add(SHUFFLE, x, groups=2)
+            cin = c
+    x = m.add(CONV, x, cin=cin, cout=widths[3], k=1, stride=1, pad=0, act=RELU)
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=widths[3], cout=classes)
+    return m.shapes()
+
+
+def shufflenet_v2_x1_0(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _shufflenet_v2("shufflenet_v2_x1_0", (116, 232, 464, 1024), dtype, classes, hw)
+
+
+def shufflenet_v2_x0_5(dtype: str = "bf16", classes: int = 1000, hw: int = 224) -> Model:
+    return _shufflenet_v2("shufflenet_v2_x0_5", (48, 96, 192, 1024), dtype, classes, hw)
+
+
 def _densenet(name: str, growth: int, blocks, init: int, dtype: str, classes: int, hw: int) -> Model:
     """DenseNet-BC (Huang et al. 2017): every dense layer normalises and rectifies the concatenation of all
     earlier features (a per-channel scale and shift: a 1x1 depthwise node here, it cannot be folded because
@@ -587,4 +635,6 @@ FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             # ... and squeeze-excite gates with hard-swish / hard-sigmoid activations
             "mobilenet_v3_large": mobilenet_v3_large, "mobilenet_v3_small": mobilenet_v3_small,
             "efficientnet_v2_s": efficientnet_v2_s, "efficientnet_v2_m": efficientnet_v2_m, "efficientnet_v2_l": efficientnet_v2_l,
+            # ... and channel slices and shuffles
+            "shufflenet_v2_x1_0": shufflenet_v2_x1_0, "shufflenet_v2_x0_5": shufflenet_v2_x0_5,
             "densenet121": densenet121, "densenet169": densenet169, "densenet201": densenet201, "densenet161": densenet161}
