@@ -61,7 +61,9 @@ typedef enum { FI_ACT_NONE = 0, FI_ACT_RELU = 1, FI_ACT_RELU6 = 2, FI_ACT_HARDSW
 /* One node u_i of a member's layer graph (Algorithm 1: node, its in-edge, its
  * activation phi_i).  Nodes are listed in topological order.
  *   conv2d / depthwise: y = act(conv(x, w) + b [+ residual]); cross-correlation,
- *     zero padding, square kernel (kh == kw), floor output size.  The residual
+ *     zero padding, floor output size.  Kernels are square (kh == kw) except that a
+ *     dense conv2d may be rectangular (e.g. 1x7, 7x1); `pad` then applies only along the
+ *     dimensions the kernel extends over (size > 1).  The residual
  *     is added BEFORE the activation.  Depthwise: cin == cout, one filter/channel.
  *     conv2d with groups = G > 1: output channel o sees only the input channels of
  *     its group o / (cout/G); canonical weights are then [cout][cin/G][kh][kw].  (Packed

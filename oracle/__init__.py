@@ -25,7 +25,8 @@ class OrcLayer(C.Structure):
     _fields_ = [("op", C.c_int32), ("act", C.c_int32), ("input", C.c_int32), ("residual", C.c_int32),
                 ("cin", C.c_int32), ("cout", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32),
                 ("pad", C.c_int32), ("ceil_mode", C.c_int32), ("w_off", C.c_int64), ("b_off", C.c_int64),
-                ("groups", C.c_int32), ("c_first", C.c_int32)]
+                ("groups", C.c_int32), ("c_first", C.c_int32),
+                ("kw", C.c_int32), ("reserved", C.c_int32)]
 
 
 _FP = C.POINTER(C.c_float)
@@ -44,6 +45,7 @@ def lib(f64: bool = False):
         L.orc_channel_scale.argtypes = [_FP, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_slice.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_channel_shuffle.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
+        L.orc_conv2d_rect.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_concat.argtypes = [_FP, C.c_int, _FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_dwconv2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, _FP, _FP, C.c_int, C.c_int, C.c_int, _FP]
         L.orc_maxpool2d.argtypes = [_FP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _FP]
@@ -83,6 +85,19 @@ def conv2d(x, w, b, stride=1, pad=0, f64=False):
         b, bp = _f(b)
     y = np.empty((n, o, _osz(h, k, stride, pad), _osz(ww, k, stride, pad)), dtype=np.float32)
     lib(f64).orc_conv2d(xp, n, c, h, ww, wp, bp, o, k, stride, pad, y.ctypes.data_as(_FP))
+    return y
+
+
+def conv2d_rect(x, w, b, stride=1, pad_h=0, pad_w=0, f64=False):
+    x, xp = _f(x); w, wp = _f(w)
+    n, c, h, ww = x.shape
+    o, ci, kh, kw = w.shape
+    assert ci == c
+    bp = None
+    if b is not None:
+        b, bp = _f(b)
+    y = np.empty((n, o, _osz(h, kh, stride, pad_h), _osz(ww, kw, stride, pad_w)), dtype=np.float32)
+    lib(f64).orc_conv2d_rect(xp, n, c, h, ww, wp, bp, o, kh, kw, stride, pad_h, pad_w, y.ctypes.data_as(_FP))
     return y
 
 
@@ -221,7 +236,8 @@ def layer_table(model):
     arr = (OrcLayer * len(model.layers))()
     for i, L in enumerate(model.layers):
         arr[i] = OrcLayer(_OPS[L.op], _ACTS[L.act], L.input, L.residual, L.cin, L.cout, L.k, L.stride,
-                          L.pad, int(getattr(L, "ceil", False)), L.w_off, L.b_off, int(getattr(L, "groups", 1)), int(getattr(L, "first", 0)))
+                          L.pad, int(getattr(L, "ceil", False)), L.w_off, L.b_off, int(getattr(L, "groups", 1)), int(getattr(L, "first", 0)),
+                          int(getattr(L, "kw", 0)), 0)
     return arr
 
 

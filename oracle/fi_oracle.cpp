@@ -74,6 +74,9 @@ struct orc_layer {
   int64_t w_off, b_off;  // byte offsets into the canonical weight blob
   int32_t groups;        // conv: number of channel groups (0 or 1 = dense); shuffle: number of groups
   int32_t c_first;       // slice: first channel taken
+  int32_t kw;            // conv: kernel width when it differs from the height k (0 = square); the padding
+                         // then applies only along a dimension the kernel extends over (size > 1)
+  int32_t reserved;
 };
 
 // ---- scalar helpers -------------------------------------------------------
@@ -183,6 +186,27 @@ void orc_conv2d(const float* x, int N, int C, int H, int W, const float* w, cons
       float* yo = y + ((int64_t)n * O + o) * Ho * Wo;
       for (size_t q = 0; q < plane.size(); ++q) yo[q] = (float)plane[q];
     }
+}
+
+// Rectangular kernel, separate paddings: the definition written out per output element,
+// y[n,o,i,j] = b[o] + sum_c sum_r sum_t x[n,c,i*s-ph+r,j*s-pw+t] * w[o,c,r,t], out-of-range x = 0.
+void orc_conv2d_rect(const float* x, int N, int C, int H, int W, const float* w, const float* b, int O,
+                     int kh, int kw, int s, int ph, int pw, float* y) {
+  const int Ho = out_size(H, kh, s, ph), Wo = out_size(W, kw, s, pw);
+  for (int n = 0; n < N; ++n)
+    for (int o = 0; o < O; ++o)
+      for (int i = 0; i < Ho; ++i)
+        for (int j = 0; j < Wo; ++j) {
+          acc_t sum = (acc_t)(b ? b[o] : 0.0f);
+          for (int c = 0; c < C; ++c)
+            for (int r = 0; r < kh; ++r)
+              for (int t = 0; t < kw; ++t) {
+                const int ih = i * s - ph + r, iw = j * s - pw + t;
+                if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                sum = sum + (acc_t)w[(((int64_t)o * C + c) * kh + r) * kw + t] * (acc_t)x[(((int64_t)n * C + c) * H + ih) * W + iw];
+              }
+          y[(((int64_t)n * O + o) * Ho + i) * Wo + j] = (float)sum;
+        }
 }
 
 // Grouped convolution: output channel o belongs to group g = o / (O/G) and sees only the input channels
@@ -396,6 +420,16 @@ int64_t orc_run_model(const orc_layer* layers, int n_layers, int output_node, co
     switch (L.op) {
       case ORC_CONV: {
         if (L.cin != c) return -2;
+        if (L.kw > 0 && L.kw != L.k) {   // rectangular kernel: padding only along the dimensions it extends over
+          if (L.groups > 1) return -2;
+          const int ph = L.k > 1 ? L.pad : 0, pw = L.kw > 1 ? L.pad : 0;
+          o.c = L.cout; o.h = out_size(h, L.k, L.stride, ph); o.w = out_size(w, L.kw, L.stride, pw);
+          o.v.resize((size_t)N * o.c * o.h * o.w);
+          std::vector<float> wt = read_tensor(blob, L.w_off, (int64_t)L.cout * L.cin * L.k * L.kw, dtype);
+          std::vector<float> bs = read_tensor(blob, L.b_off, L.cout, ORC_F32);
+          orc_conv2d_rect(in, N, c, h, w, wt.data(), bs.data(), L.cout, L.k, L.kw, L.stride, ph, pw, o.v.data());
+          break;
+        }
         o.c = L.cout; o.h = out_size(h, L.k, L.stride, L.pad); o.w = out_size(w, L.k, L.stride, L.pad);
         o.v.resize((size_t)N * o.c * o.h * o.w);
         const int G = L.groups > 1 ? L.groups : 1;

@@ -291,7 +291,7 @@ def make_spec(model, weights_ptr: int, weight_bytes: int, act_dtype=None, packed
     layers carry op/input/residual/cin/cout/k/stride/pad/act/w_off/b_off).  Returns (spec, keepalive)."""
     layers = (fi_layer_spec * len(model.layers))()
     for i, L in enumerate(model.layers):
-        layers[i] = fi_layer_spec(_OPS[L.op], L.input, L.residual, L.cin, L.cout, L.k, L.k, L.stride, L.pad,
+        layers[i] = fi_layer_spec(_OPS[L.op], L.input, L.residual, L.cin, L.cout, L.k, getattr(L, "kw", 0) or L.k, L.stride, L.pad,
                                   _ACTS[L.act], int(getattr(L, "ceil", False)), int(getattr(L, "groups", 1)), int(getattr(L, "first", 0)), 0, L.w_off, L.b_off)
     name = model.name.encode()
     dt = _DT[model.dtype]

@@ -294,7 +294,7 @@ static fi_status plan_dag(fi_dag* g) {
       std::string sig = std::to_string(mb.spec.act_dtype);
       for (const Node& n : mb.plan.nodes) {
         char buf[96];
-        std::snprintf(buf, sizeof(buf), "|%d,%d,%d,%d,%d,%d,%d,%d,%d", n.op, n.input, n.residual, n.C, n.Co, n.k, n.stride, n.pad, n.act);
+        std::snprintf(buf, sizeof(buf), "|%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", n.op, n.input, n.residual, n.C, n.Co, n.k, n.kw, n.stride, n.pad, n.act);
         sig += buf;
       }
       if (!family.count(sig)) order.push_back(sig);
@@ -572,13 +572,14 @@ static fi_status plan_dag(fi_dag* g) {
       d.H = nd.H; d.W = nd.W; d.C = nd.C; d.Cp = nd.Cp;
       d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop;
       d.k = nd.k; d.stride = nd.stride; d.pad = nd.pad; d.act = nd.act; d.Kp = nd.Kp;
+      d.kw = nd.kw; d.pad_w = nd.pad_w;
       if (nd.op == FI_SLICE) d.stride = 0;     // gather mode: slice
       if (nd.op == FI_SHUFFLE) d.stride = 1;   // gather mode: shuffle
       if (nd.op == FI_CONCAT) {  // second source: channels in Kp, channel stride in tiles_n (set below)
         d.Kp = g->nodes[(size_t)nd.residual].Co;
       }
       if (nd.op == FI_FC) {  // a fully connected node is a 1x1 convolution over the flattened input
-        d.C = d.Cp = nd.H * nd.W * nd.Cp; d.H = d.W = 1; d.k = 1; d.stride = 1; d.pad = 0;
+        d.C = d.Cp = nd.H * nd.W * nd.Cp; d.H = d.W = 1; d.k = d.kw = 1; d.stride = 1; d.pad = d.pad_w = 0;
       }
       d.ext = nd.is_output;
       d.vec = (adt == FI_BF16 && nd.Cp % 8 == 0 && nd.Cop % 8 == 0 && !nd.is_output && nd.out_dtype == FI_BF16) ? 1 : 0;

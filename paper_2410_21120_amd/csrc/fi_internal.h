@@ -57,7 +57,7 @@ struct Desc {
   int32_t vec;                   // 1: bf16 tensors with Cp % 8 == 0, kernels work on 8-channel vectors
   int32_t splits;                // reduction splits (>1: fp32 partials [splits][rows][Cop] at ws_off)
   uint64_t ws_off;               // split-K partials, relative to the activation base
-  int32_t rsv[2];
+  int32_t kw, pad_w;             // dense conv: kernel width and horizontal padding (k, pad are the vertical ones)
 };
 static_assert(sizeof(Desc) == 128, "Desc is 128 bytes");
 
@@ -66,6 +66,7 @@ struct Node {
   int32_t op, act;
   int32_t input, residual;       // global node ids (or -1 / -2)
   int32_t H, W, C, Cp, Ho, Wo, Co, Cop, k, stride, pad;
+  int32_t kw, pad_w;             // dense conv: kernel width / horizontal padding (k / pad are the vertical ones)
   int32_t Kp;
   int32_t level;
   int32_t out_dtype;             // FI_F32 / FI_BF16 as stored

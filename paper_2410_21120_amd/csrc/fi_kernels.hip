@@ -117,11 +117,11 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
     for (int r = 0; r < d.k; ++r) {
       const int ih = pp * d.stride - d.pad + r;
       if (ih < 0 || ih >= d.H) continue;
-      for (int s = 0; s < d.k; ++s) {
-        const int iw = q * d.stride - d.pad + s;
+      for (int s = 0; s < d.kw; ++s) {
+        const int iw = q * d.stride - d.pad_w + s;
         if (iw < 0 || iw >= d.W) continue;
         const TA* xr = x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp;
-        const TW* wr = w + (r * d.k + s) * d.Cp;
+        const TW* wr = w + (r * d.kw + s) * d.Cp;
         for (int c = 0; c < d.C; ++c) acc += ld(xr + c) * ld(wr + c);
       }
     }
@@ -234,8 +234,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // Per row: the byte offset of its window origin (n, p*stride-pad, q*stride-pad, 0) and which
   // filter rows / columns land inside the image (bit r: row r valid; bit 16+s: column s valid).
   int a_row[AR], a_rc[AR];
-  const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho, inv_k = 1.0f / (float)d.k;
-  const bool pointwise = d.k == 1 && d.stride == 1 && d.pad == 0;  // output pixel m reads input pixel m: nothing to decode
+  const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho, inv_k = 1.0f / (float)d.kw;
+  const bool pointwise = d.k == 1 && d.kw == 1 && d.stride == 1 && d.pad == 0 && d.pad_w == 0;  // output pixel m reads input pixel m: nothing to decode
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int m = m0 + srow + RPP * i;
@@ -250,13 +250,11 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     const int q = mm - t * d.Wo;
     const int n = fast_div(t, d.Ho, inv_ho);
     const int pp = t - n * d.Ho;
-    const int ih0 = pp * d.stride - d.pad, iw0 = q * d.stride - d.pad;
+    const int ih0 = pp * d.stride - d.pad, iw0 = q * d.stride - d.pad_w;
     a_row[i] = ((n * d.H + ih0) * d.W + iw0) * d.Cp * AE;
     int rc = 0;
-    for (int r = 0; r < d.k; ++r) {
-      rc |= ((unsigned)(ih0 + r) < (unsigned)d.H) ? (1 << r) : 0;
-      rc |= ((unsigned)(iw0 + r) < (unsigned)d.W) ? (65536 << r) : 0;
-    }
+    for (int r = 0; r < d.k; ++r) rc |= ((unsigned)(ih0 + r) < (unsigned)d.H) ? (1 << r) : 0;
+    for (int r = 0; r < d.kw; ++r) rc |= ((unsigned)(iw0 + r) < (unsigned)d.W) ? (65536 << r) : 0;
     a_rc[i] = ok ? rc : 0;  // rows past M read as zero
   }
   const uint4* b_ptr[BR];
@@ -276,8 +274,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     const int k0 = kt0 * BK + kvec;
     const int rs = k0 / d.Cp;
     kc = k0 - rs * d.Cp;
-    kr = rs / d.k;
-    ks = rs - kr * d.k;
+    kr = rs / d.kw;
+    ks = rs - kr * d.kw;
   }
 
   f32x16 acc[MI][NI];
@@ -307,8 +305,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       const int tap0 = ((KT) * BK + kvec) >> 2; /* elements 0-3: tap0, elements 4-7: tap0 + 1 */  \
       int tr[2], tc[2], tv[2];                                                                    \
       _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                             \
-        tr[h] = fast_div(tap0 + h, d.k, inv_k);                                                   \
-        tc[h] = tap0 + h - tr[h] * d.k;                                                           \
+        tr[h] = fast_div(tap0 + h, d.kw, inv_k);                                                   \
+        tc[h] = tap0 + h - tr[h] * d.kw;                                                           \
         tv[h] = (tr[h] * d.W + tc[h]) * 4 * AE;                                                   \
       }                                                                                           \
       _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                            \
@@ -333,7 +331,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       const bool wrap = kc >= d.Cp;                                                               \
       kc -= wrap ? d.Cp : 0;                                                                      \
       ks += wrap ? 1 : 0;                                                                         \
-      const bool wrap2 = ks == d.k;                                                               \
+      const bool wrap2 = ks == d.kw;                                                              \
       ks = wrap2 ? 0 : ks;                                                                        \
       kr += wrap2 ? 1 : 0;                                                                        \
     }                                                                                             \

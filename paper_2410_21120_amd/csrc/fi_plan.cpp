@@ -69,23 +69,28 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
     if (L.act < FI_ACT_NONE || L.act > FI_ACT_SIGMOID) { set_error("model %s node %d: bad activation", nm, i); return FI_EINVAL; }
     if (L.input == FI_INPUT) { n.C = m.in_c; n.H = m.in_h; n.W = m.in_w; n.Cp = out.in_cp; }
     else { const Node& s = out.nodes[(size_t)L.input]; n.C = s.Co; n.H = s.Ho; n.W = s.Wo; n.Cp = s.Cop; }
-    n.k = 1; n.stride = 1; n.pad = 0;
+    n.k = 1; n.kw = 1; n.stride = 1; n.pad = 0; n.pad_w = 0;
     switch (L.op) {
       case FI_CONV2D:
       case FI_DWCONV2D:
-        if (L.kh != L.kw || L.kh < 1 || L.stride < 1 || L.pad < 0 || L.cout < 1) {
+        if (L.kh < 1 || L.kw < 1 || L.stride < 1 || L.pad < 0 || L.cout < 1 ||
+            (L.kh != L.kw && (L.op != FI_CONV2D || L.groups > 1))) {   // rectangular kernels: dense conv2d only
           set_error("model %s node %d: unsupported kernel geometry", nm, i); return FI_EUNSUPPORTED; }
         if (L.cin != n.C) { set_error("model %s node %d: cin %d != producer channels %d", nm, i, L.cin, n.C); return FI_EINVAL; }
-        if (L.kh > 15) { set_error("model %s node %d: kernels larger than 15x15 are not supported", nm, i); return FI_EUNSUPPORTED; }
+        if (L.kh > 15 || L.kw > 15) { set_error("model %s node %d: kernels larger than 15x15 are not supported", nm, i); return FI_EUNSUPPORTED; }
         if (L.op == FI_DWCONV2D && L.cout != L.cin) { set_error("model %s node %d: depthwise needs cin == cout", nm, i); return FI_EINVAL; }
         if (L.groups > 1 && (L.op != FI_CONV2D || L.cin % L.groups || L.cout % L.groups)) {
           set_error("model %s node %d: %d groups do not divide cin %d and cout %d of a conv2d", nm, i, L.groups, L.cin, L.cout); return FI_EINVAL; }
         if (L.groups < 0) { set_error("model %s node %d: negative groups", nm, i); return FI_EINVAL; }
-        n.k = L.kh; n.stride = L.stride; n.pad = L.pad; n.Co = L.cout;
-        n.Ho = (n.H + 2 * L.pad - L.kh) / L.stride + 1;
-        n.Wo = (n.W + 2 * L.pad - L.kh) / L.stride + 1;
-        if (n.Ho < 1 || n.Wo < 1 || n.H + 2 * L.pad < L.kh) { set_error("model %s node %d: empty output", nm, i); return FI_EINVAL; }
-        n.macs = (uint64_t)n.Ho * n.Wo * n.Co * (uint64_t)(L.op == FI_CONV2D ? n.C / (L.groups > 1 ? L.groups : 1) : 1) * L.kh * L.kh;
+        n.k = L.kh; n.kw = L.kw; n.stride = L.stride; n.pad = L.pad; n.pad_w = L.pad; n.Co = L.cout;
+        if (L.kh != L.kw) {   // a rectangular kernel is padded only along the dimensions it extends over
+          n.pad = L.kh > 1 ? L.pad : 0;
+          n.pad_w = L.kw > 1 ? L.pad : 0;
+        }
+        n.Ho = (n.H + 2 * n.pad - L.kh) / L.stride + 1;
+        n.Wo = (n.W + 2 * n.pad_w - L.kw) / L.stride + 1;
+        if (n.Ho < 1 || n.Wo < 1 || n.H + 2 * n.pad < L.kh || n.W + 2 * n.pad_w < L.kw) { set_error("model %s node %d: empty output", nm, i); return FI_EINVAL; }
+        n.macs = (uint64_t)n.Ho * n.Wo * n.Co * (uint64_t)(L.op == FI_CONV2D ? n.C / (L.groups > 1 ? L.groups : 1) : 1) * L.kh * L.kw;
         break;
       case FI_MAXPOOL2D:
       case FI_AVGPOOL2D:
@@ -164,14 +169,14 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
     // packed weight placement
     n.w_rel = n.b_rel = kNone;
     uint64_t wbytes = 0;
-    if (L.op == FI_CONV2D) { n.Kp = round_up(n.k * n.k * n.Cp, kg); wbytes = (uint64_t)n.Co * n.Kp * wsz; }
+    if (L.op == FI_CONV2D) { n.Kp = round_up(n.k * n.kw * n.Cp, kg); wbytes = (uint64_t)n.Co * n.Kp * wsz; }
     else if (L.op == FI_FC) { n.Kp = round_up(n.H * n.W * n.Cp, kg); wbytes = (uint64_t)n.Co * n.Kp * wsz; }
     else if (L.op == FI_DWCONV2D) { n.Kp = n.k * n.k; wbytes = (uint64_t)n.k * n.k * n.Cp * wsz; }
     if (wbytes) {
       n.w_rel = off; off = align_up(off + wbytes);
       n.b_rel = off; off = align_up(off + (uint64_t)n.Cop * 4);
       // canonical blob bounds
-      const uint64_t cw = (L.op == FI_CONV2D ? (uint64_t)n.Co * (n.C / (L.groups > 1 ? L.groups : 1)) * n.k * n.k
+      const uint64_t cw = (L.op == FI_CONV2D ? (uint64_t)n.Co * (n.C / (L.groups > 1 ? L.groups : 1)) * n.k * n.kw
                            : L.op == FI_FC  ? (uint64_t)n.Co * L.cin : (uint64_t)n.Co * n.k * n.k) * wsz;
       if (!m.weights_packed && m.weights &&
           (L.w_off + cw > m.weight_bytes || L.b_off + (uint64_t)n.Co * 4 > m.weight_bytes)) {
@@ -222,7 +227,7 @@ static void pack_typed(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst8
     const fi_layer_spec& L = m.layers[i];
     const T* w = reinterpret_cast<const T*>(src + L.w_off);
     T* d = reinterpret_cast<T*>(dst8 + n.w_rel);
-    const int32_t kk = n.k * n.k;
+    const int32_t kk = n.op == FI_CONV2D ? n.k * n.kw : n.k * n.k;
     if (n.op == FI_CONV2D) {
       // A grouped convolution becomes a dense one whose weight rows are zero outside the row's own
       // group of input channels (block-diagonal): the kernels need no notion of groups.

@@ -130,11 +130,11 @@ def test_further_table3_families_fused():
     """Further families of the paper's Table III (AlexNet, VGG-11/13/19, ResNet-34/101/152, Wide ResNet-50-2/101-2,
     MnasNet 1.0; SqueezeNet 1.0 / 1.1 and GoogLeNet with channel concatenation and pooling sizes that round up; ResNeXt-50
     32x4d with grouped convolution; DenseNet-121 with window average pooling and per-channel affine nodes; MobileNetV3 Large with squeeze-excite gates
-    and hard-swish; ShuffleNet V2 with channel slices and shuffles), all seventeen fused in one DAG at a reduced image size, each member against the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
+    and hard-swish; ShuffleNet V2 with channel slices and shuffles; Inception v3 with rectangular kernels), all eighteen fused in one DAG at a reduced image size, each member against the oracle.  MnasNet is a MobileNet-style inverted-residual network and keeps fp32 activations."""
     from tests import harness
     WIDE_HERE = {"mnasnet1_0", "mobilenet_v3_large"}   # inverted-residual networks keep fp32 activations
     fams = ["alexnet", "vgg11", "vgg13", "vgg19", "resnet34", "resnet101", "resnet152", "wide_resnet50_2", "wide_resnet101_2", "mnasnet1_0",
-            "squeezenet1_0", "squeezenet1_1", "googlenet", "resnext50_32x4d", "densenet121", "mobilenet_v3_large", "shufflenet_v2_x1_0"]
+            "squeezenet1_0", "squeezenet1_1", "googlenet", "resnext50_32x4d", "densenet121", "mobilenet_v3_large", "shufflenet_v2_x1_0", "inception_v3"]
     mem = []
     for i, f in enumerate(fams):
         m = zoo.FAMILIES[f](hw=96)

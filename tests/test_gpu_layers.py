@@ -120,6 +120,19 @@ def test_maxpool_exact(case, mode):
     assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, False))
 
 
+@pytest.mark.parametrize("case", [(128, 128, 1, 7, 1, 3, 17, 17, 2), (128, 192, 7, 1, 1, 3, 17, 17, 2), (384, 384, 1, 3, 1, 1, 8, 8, 2),
+                                  (384, 384, 3, 1, 1, 1, 8, 8, 2), (24, 40, 3, 1, 2, 1, 15, 13, 1), (3, 16, 1, 5, 1, 2, 20, 21, 2),
+                                  (16, 16, 5, 2, 2, 2, 19, 18, 1)])   # cin, cout, kh, kw, stride, pad, H, W, batch
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
+def test_rectangular_kernels(case, mode):
+    """1 x n, n x 1 and other rectangular kernels; padding only along the dimensions the kernel extends over."""
+    cin, cout, kh, kw, s, p, h, w, b = case
+    dtype = "f32" if mode == "f32" else "bf16"
+    m = zoo.Model("rect", dtype, cin, h, w)
+    m.add(zoo.CONV, -1, cin=cin, cout=cout, k=kh, kw=kw, stride=s, pad=p, act=zoo.RELU)
+    _run_case(m, 1500 + cin + kh * 16 + kw, b, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
 @pytest.mark.parametrize("case", [(128, 128, 32, 3, 1, 1, 14, 14, 2), (64, 96, 4, 3, 2, 1, 15, 17, 2), (48, 48, 48, 3, 1, 1, 9, 9, 1),
                                   (32, 64, 2, 1, 1, 0, 12, 12, 3), (256, 256, 32, 3, 2, 1, 28, 28, 1)])  # cin, cout, groups, k, stride, pad, H, W, batch
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])

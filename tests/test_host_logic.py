@@ -179,7 +179,8 @@ def _spec_with(mutator, fam="tiny"):
     (lambda s: setattr(s.layers[2], "input", 77), fi.FI_EINVAL),          # dangling edge
     (lambda s: setattr(s.layers[2], "cin", 17), fi.FI_EINVAL),            # shape mismatch
     (lambda s: setattr(s.layers[0], "op", 42), fi.FI_EUNSUPPORTED),       # unknown operator
-    (lambda s: setattr(s.layers[0], "kw", 5), fi.FI_EUNSUPPORTED),        # non-square kernel
+    (lambda s: setattr(s.layers[1], "kw", 3), fi.FI_EUNSUPPORTED),        # non-square pooling window
+    (lambda s: setattr(s.layers[0], "kw", 16), fi.FI_EUNSUPPORTED),       # kernel wider than 15
     (lambda s: setattr(s.layers[2], "residual", 0), fi.FI_EINVAL),        # residual shape mismatch
     (lambda s: setattr(s.layers[4], "w_off", 1 << 40), fi.FI_EINVAL),     # weights past the blob
     (lambda s: setattr(s, "output_node", 99), fi.FI_EINVAL),

@@ -77,7 +77,7 @@ def _torch_forward(model, blob, x, dtype=torch.float64):
     for L in model.layers:
         inp = xt if L.input == -1 else vals[L.input]
         if L.op in ("conv", "dwconv", "fc"):
-            nw = {"conv": L.cout * (L.cin // L.groups) * L.k * L.k, "dwconv": L.cout * L.k * L.k, "fc": L.cout * L.cin}[L.op]
+            nw = {"conv": L.cout * (L.cin // L.groups) * L.k * (L.kw or L.k), "dwconv": L.cout * L.k * L.k, "fc": L.cout * L.cin}[L.op]
             if model.dtype == "f32":
                 w = blob[L.w_off:L.w_off + 4 * nw].view(np.float32)
             else:
@@ -85,7 +85,9 @@ def _torch_forward(model, blob, x, dtype=torch.float64):
             w = torch.from_numpy(np.array(w)).to(dtype)
             b = torch.from_numpy(np.array(blob[L.b_off:L.b_off + 4 * L.cout].view(np.float32))).to(dtype)
         if L.op == "conv":
-            y = F.conv2d(inp, w.reshape(L.cout, L.cin // L.groups, L.k, L.k), b, stride=L.stride, padding=L.pad, groups=L.groups)
+            kw = L.kw or L.k
+            pad = (L.pad, L.pad) if kw == L.k else (L.pad if L.k > 1 else 0, L.pad if kw > 1 else 0)
+            y = F.conv2d(inp, w.reshape(L.cout, L.cin // L.groups, L.k, kw), b, stride=L.stride, padding=pad, groups=L.groups)
         elif L.op == "dwconv":
             y = F.conv2d(inp, w.reshape(L.cout, 1, L.k, L.k), b, stride=L.stride, padding=L.pad, groups=L.cout)
         elif L.op == "maxpool":
@@ -124,7 +126,7 @@ def _rel(a, b):
 
 
 @pytest.mark.parametrize("fam,hw", [("tiny", 32), ("resnet18", 64), ("resnet50", 64), ("mobilenetv2", 64), ("vgg16", 32),
-                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64), ("densenet121", 64), ("mobilenet_v3_large", 64), ("mobilenet_v3_small", 64), ("shufflenet_v2_x1_0", 64)])
+                                    ("alexnet", 67), ("mnasnet1_0", 64), ("squeezenet1_1", 65), ("googlenet", 70), ("resnext50_32x4d", 64), ("densenet121", 64), ("mobilenet_v3_large", 64), ("mobilenet_v3_small", 64), ("shufflenet_v2_x1_0", 64), ("inception_v3", 96)])
 def test_model_runner_vs_library_forward(fam, hw):
     m = zoo.tiny_cnn() if fam == "tiny" else zoo.FAMILIES[fam](hw=hw)
     blob = gen.make_blob(m, 1000 + hw)

@@ -201,6 +201,33 @@ def test_grouped_conv_vs_per_group_dense_conv_and_library(case, rng):
         assert np.array_equal(y, oracle.dwconv2d(x, w, b, s, p))
 
 
+@pytest.mark.parametrize("case", [(1, 7, 1, 0, 3), (7, 1, 1, 3, 0), (1, 3, 1, 0, 1), (3, 1, 2, 1, 0), (3, 3, 1, 1, 1), (5, 2, 2, 2, 0), (2, 4, 1, 1, 2)])
+def test_rectangular_conv_vs_bruteforce_and_library(case, rng):
+    """kh x kw kernels with separate paddings: against an explicit im2col x matmul written here, against a
+    library routine in fp64, and (square case) bit for bit against the square convolution; a 1 x kw kernel
+    applied to a transposed image equals the kw x 1 kernel's result transposed."""
+    import torch.nn.functional as F
+    kh, kw, s, ph, pw = case
+    x = rng.standard_normal((2, 4, 10, 9)).astype(np.float32)
+    w = rng.standard_normal((5, 4, kh, kw)).astype(np.float32)
+    b = rng.standard_normal(5).astype(np.float32)
+    y = oracle.conv2d_rect(x, w, b, s, ph, pw)
+    xp = np.pad(x.astype(np.float64), ((0, 0), (0, 0), (ph, ph), (pw, pw)))
+    ho, wo = (10 + 2 * ph - kh) // s + 1, (9 + 2 * pw - kw) // s + 1
+    cols = np.empty((2, ho, wo, 4 * kh * kw))
+    for i in range(ho):
+        for j in range(wo):
+            cols[:, i, j] = xp[:, :, i * s:i * s + kh, j * s:j * s + kw].reshape(2, -1)
+    ref = (cols @ w.reshape(5, -1).astype(np.float64).T + b).transpose(0, 3, 1, 2)
+    assert y.shape == ref.shape and np.abs(y - ref).max() < 1e-4
+    lib = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double(), s, (ph, pw)).numpy()
+    assert np.abs(y - lib).max() < 1e-4
+    if kh == kw and ph == pw:
+        assert np.array_equal(y, oracle.conv2d(x, w, b, s, ph))
+    yt = oracle.conv2d_rect(np.ascontiguousarray(x.transpose(0, 1, 3, 2)), np.ascontiguousarray(w.transpose(0, 1, 3, 2)), b, s, pw, ph)
+    assert np.allclose(yt.transpose(0, 1, 3, 2), y, rtol=0, atol=1e-5)
+
+
 def test_maxpool_ceil_mode_and_concat(rng):
     """Rounding the pooled size up lets windows hang over the far edge (those taps are never candidates) but
     never adds a window that starts past the input; the ramp's closed form and a library routine pin it.

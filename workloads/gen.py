@@ -81,7 +81,7 @@ def layout_blob(model: zoo.Model) -> int:
     off = 0
     for L in model.layers:
         if L.op == zoo.CONV:
-            nw = L.cout * (L.cin // L.groups) * L.k * L.k
+            nw = L.cout * (L.cin // L.groups) * L.k * (L.kw or L.k)
         elif L.op == zoo.DWCONV:
             nw = L.cout * L.k * L.k
         elif L.op == zoo.FC:
@@ -103,7 +103,8 @@ def make_blob(model: zoo.Model, seed: int, bias_std: float = 0.1, out: np.ndarra
     assert blob.nbytes >= size
     for i, L in enumerate(model.layers):
         if L.op == zoo.CONV:
-            fan_in, nw = (L.cin // L.groups) * L.k * L.k, L.cout * (L.cin // L.groups) * L.k * L.k
+            kk = L.k * (L.kw or L.k)
+            fan_in, nw = (L.cin // L.groups) * kk, L.cout * (L.cin // L.groups) * kk
         elif L.op == zoo.DWCONV:
             fan_in, nw = L.k * L.k, L.cout * L.k * L.k
         elif L.op == zoo.FC:

@@ -41,6 +41,8 @@ class Layer:
     ceil: bool = False            # pooling: output size rounds up (windows may hang over the bottom / right edge)
     groups: int = 1               # conv: input and output channels are cut into this many independent groups; shuffle: groups
     first: int = 0                # slice: first channel taken (cout channels from there)
+    kw: int = 0                   # conv: kernel width when it differs from the height k (0 = square); `pad` then
+                                  # applies only along a dimension the kernel extends over (size > 1)
     bias: bool = True             # False: the layer has no bias in the architecture (its stored bias is all zero)
     bn: bool = True               # conv / depthwise with a bias: the bias stands for a folded BatchNorm
     # filled by shapes(): logical input / output spatial sizes
@@ -85,8 +87,10 @@ class Model:
             c, h, w = (self.in_c, self.in_h, self.in_w) if L.input == MODEL_INPUT else dims[L.input]
             L.in_h, L.in_w = h, w
             if L.op in (CONV, DWCONV):
-                ho = (h + 2 * L.pad - L.k) // L.stride + 1
-                wo = (w + 2 * L.pad - L.k) // L.stride + 1
+                kw = L.kw or L.k
+                ph, pw = (L.pad, L.pad) if kw == L.k else (L.pad if L.k > 1 else 0, L.pad if kw > 1 else 0)
+                ho = (h + 2 * ph - L.k) // L.stride + 1
+                wo = (w + 2 * pw - kw) // L.stride + 1
                 dims[i] = (L.cout, ho, wo)
             elif L.op in (MAXPOOL, AVGPOOL):
                 assert not (L.op == AVGPOOL and L.ceil)
@@ -129,7 +133,7 @@ class Model:
         for L in self.layers:
             b = L.cout if L.bias else 0
             if L.op == CONV:
-                n += L.cout * (L.cin // L.groups) * L.k * L.k + b
+                n += L.cout * (L.cin // L.groups) * L.k * (L.kw or L.k) + b
             elif L.op == DWCONV:
                 n += L.cout * L.k * L.k + b
             elif L.op == FC:
@@ -141,7 +145,7 @@ class Model:
         n = 0
         for L in self.layers:
             if L.op == CONV:
-                n += L.out_h * L.out_w * L.cout * (L.cin // L.groups) * L.k * L.k
+                n += L.out_h * L.out_w * L.cout * (L.cin // L.groups) * L.k * (L.kw or L.k)
             elif L.op == DWCONV:
                 n += L.out_h * L.out_w * L.cout * L.k * L.k
             elif L.op == FC:
@@ -520,6 +524,85 @@ def shufflenet_v2_x0_5(dtype: str = "bf16", classes: int = 1000, hw: int = 224) 
     return _shufflenet_v2("shufflenet_v2_x0_5", (48, 96, 192, 1024), dtype, classes, hw)
 
 
+def inception_v3(dtype: str = "bf16", classes: int = 1000, hw: int = 299) -> Model:
+    """Inception v3 (Szegedy et al. 2016) without the auxiliary head: factorised 5x5 -> two 3x3, n x n -> 1 x n
+    and n x 1 pairs, average-pool branches, grid reductions that concatenate strided convolutions with a
+    max pool."""
+    m = Model("inception_v3", dtype, 3, hw, hw)
+
+    def conv(x, cin, cout, k, stride=1, pad=0, kw=0):
+        return m.add(CONV, x, cin=cin, cout=cout, k=k, kw=kw, stride=stride, pad=pad, act=RELU)
+
+    def cat(parts):
+        y, c = parts[0]
+        for z, cz in parts[1:]:
+            y = m.add(CONCAT, y, residual=z)
+            c += cz
+        return y, c
+
+    def block_a(x, cin, pf):
+        b1 = conv(x, cin, 64, 1)
+        b2 = conv(conv(x, cin, 48, 1), 48, 64, 5, pad=2)
+        b3 = conv(conv(conv(x, cin, 64, 1), 64, 96, 3, pad=1), 96, 96, 3, pad=1)
+        b4 = conv(m.add(AVGPOOL, x, k=3, stride=1, pad=1), cin, pf, 1)
+        return cat([(b1, 64), (b2, 64), (b3, 96), (b4, pf)])
+
+    def block_b(x, cin):
+        b1 = conv(x, cin, 384, 3, stride=2)
+        b2 = conv(conv(conv(x, cin, 64, 1), 64, 96, 3, pad=1), 96, 96, 3, stride=2)
+        b3 = m.add(MAXPOOL, x, k=3, stride=2, pad=0)
+        return cat([(b1, 384), (b2, 96), (b3, cin)])
+
+    def block_c(x, cin, c7):
+        b1 = conv(x, cin, 192, 1)
+        b2 = conv(conv(conv(x, cin, c7, 1), c7, c7, 1, kw=7, pad=3), c7, 192, 7, kw=1, pad=3)
+        b3 = conv(x, cin, c7, 1)
+        b3 = conv(b3, c7, c7, 7, kw=1, pad=3)
+        b3 = conv(b3, c7, c7, 1, kw=7, pad=3)
+        b3 = conv(b3, c7, c7, 7, kw=1, pad=3)
+        b3 = conv(b3, c7, 192, 1, kw=7, pad=3)
+        b4 = conv(m.add(AVGPOOL, x, k=3, stride=1, pad=1), cin, 192, 1)
+        return cat([(b1, 192), (b2, 192), (b3, 192), (b4, 192)])
+
+    def block_d(x, cin):
+        b1 = conv(conv(x, cin, 192, 1), 192, 320, 3, stride=2)
+        b2 = conv(x, cin, 192, 1)
+        b2 = conv(b2, 192, 192, 1, kw=7, pad=3)
+        b2 = conv(b2, 192, 192, 7, kw=1, pad=3)
+        b2 = conv(b2, 192, 192, 3, stride=2)
+        b3 = m.add(MAXPOOL, x, k=3, stride=2, pad=0)
+        return cat([(b1, 320), (b2, 192), (b3, cin)])
+
+    def block_e(x, cin):
+        b1 = conv(x, cin, 320, 1)
+        t = conv(x, cin, 384, 1)
+        b2 = cat([(conv(t, 384, 384, 1, kw=3, pad=1), 384), (conv(t, 384, 384, 3, kw=1, pad=1), 384)])
+        t = conv(conv(x, cin, 448, 1), 448, 384, 3, pad=1)
+        b3 = cat([(conv(t, 384, 384, 1, kw=3, pad=1), 384), (conv(t, 384, 384, 3, kw=1, pad=1), 384)])
+        b4 = conv(m.add(AVGPOOL, x, k=3, stride=1, pad=1), cin, 192, 1)
+        return cat([(b1, 320), b2, b3, (b4, 192)])
+
+    x = conv(MODEL_INPUT, 3, 32, 3, stride=2)
+    x = conv(x, 32, 32, 3)
+    x = conv(x, 32, 64, 3, pad=1)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0)
+    x = conv(x, 64, 80, 1)
+    x = conv(x, 80, 192, 3)
+    x = m.add(MAXPOOL, x, k=3, stride=2, pad=0)
+    c = 192
+    for pf in (32, 64, 64):
+        x, c = block_a(x, c, pf)
+    x, c = block_b(x, c)
+    for c7 in (128, 160, 160, 192):
+        x, c = block_c(x, c, c7)
+    x, c = block_d(x, c)
+    for _ in range(2):
+        x, c = block_e(x, c)
+    x = m.add(GAP, x)
+    m.add(FC, x, cin=c, cout=classes)
+    return m.shapes()
+
+
 def _densenet(name: str, growth: int, blocks, init: int, dtype: str, classes: int, hw: int) -> Model:
     """DenseNet-BC (Huang et al. 2017): every dense layer normalises and rectifies the concatenation of all
     earlier features (a per-channel scale and shift: a 1x1 depthwise node here, it cannot be folded because
@@ -637,4 +720,6 @@ FAMILIES = {"tiny": tiny_cnn, "resnet18": resnet18, "resnet50": resnet50,
             "efficientnet_v2_s": efficientnet_v2_s, "efficientnet_v2_m": efficientnet_v2_m, "efficientnet_v2_l": efficientnet_v2_l,
             # ... and channel slices and shuffles
             "shufflenet_v2_x1_0": shufflenet_v2_x1_0, "shufflenet_v2_x0_5": shufflenet_v2_x0_5,
+            # ... and rectangular kernels
+            "inception_v3": inception_v3,
             "densenet121": densenet121, "densenet169": densenet169, "densenet201": densenet201, "densenet161": densenet161}
