@@ -31,13 +31,27 @@ __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
 __device__ __forceinline__ void st(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
 
-__device__ __forceinline__ float activate(float v, int act) {
-  if (act == FI_ACT_RELU) return fmaxf(v, 0.0f);
-  if (act == FI_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+// ReLU / ReLU6 / identity as branch-free selects (the common case), the smooth activations behind ONE
+// block-uniform branch per call: `act` is the same for every lane of a problem.
+__device__ __forceinline__ float activate_smooth(float v, int act) {
   if (act == FI_ACT_HARDSWISH) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
   if (act == FI_ACT_HARDSIGMOID) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
-  if (act == FI_ACT_SILU) return v * (1.0f / (1.0f + expf(-v)));
-  if (act == FI_ACT_SIGMOID) return 1.0f / (1.0f + expf(-v));
+  const float sg = 1.0f / (1.0f + expf(-v));
+  return act == FI_ACT_SILU ? v * sg : sg;
+}
+template <int N>
+__device__ __forceinline__ void activate_n(float* v, int act) {
+  if (__builtin_amdgcn_readfirstlane(act) > FI_ACT_RELU6) {
+#pragma unroll
+    for (int t = 0; t < N; ++t) v[t] = activate_smooth(v[t], act);
+    return;
+  }
+  const float hi = act == FI_ACT_RELU6 ? 6.0f : INFINITY;
+#pragma unroll
+  for (int t = 0; t < N; ++t) v[t] = act == FI_ACT_NONE ? v[t] : fminf(fmaxf(v[t], 0.0f), hi);
+}
+__device__ __forceinline__ float activate(float v, int act) {
+  activate_n<1>(&v, act);
   return v;
 }
 
@@ -471,8 +485,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
           v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
           v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
         }
+        activate_n<8>(v, d.act);
   #pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] = (o + t < d.Co) ? activate(v[t], d.act) : 0.0f;  // pad channels hold zero
+        for (int t = 0; t < 8; ++t) v[t] = (o + t < d.Co) ? v[t] : 0.0f;  // pad channels hold zero
         if (d.ext) {
           float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)m * d.Co + o;
   #pragma unroll
@@ -570,8 +585,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
           v[4] += __uint_as_float(r.z << 16); v[5] += __uint_as_float(r.z & 0xFFFF0000u);
           v[6] += __uint_as_float(r.w << 16); v[7] += __uint_as_float(r.w & 0xFFFF0000u);
         }
+        activate_n<8>(v, d.act);
   #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = (o + i < d.Co) ? activate(v[i], d.act) : 0.0f;  // pad channels hold zero
+        for (int i = 0; i < 8; ++i) v[i] = (o + i < d.Co) ? v[i] : 0.0f;  // pad channels hold zero
         if (d.ext) {
           float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)m * d.Co + o;
   #pragma unroll
@@ -929,7 +945,10 @@ __global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
     for (int i = 0; i < 8; ++i) bv[i] += rv[i];
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = (c8 + i < d.Co) ? activate(acc[i] + bv[i], d.act) : 0.0f;
+  for (int i = 0; i < 8; ++i) acc[i] += bv[i];
+  activate_n<8>(acc, d.act);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = (c8 + i < d.Co) ? acc[i] : 0.0f;
   if (d.ext) {
     float* y = static_cast<float*>(a.ext_out[p]) + m * d.Co + c8;
 #pragma unroll
@@ -1088,8 +1107,9 @@ __global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) v[t] += ld(r + t);
   }
+  activate_n<4>(v, d.act);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) v[t] = (o + t < d.Co) ? activate(v[t], d.act) : 0.0f;
+  for (int t = 0; t < 4; ++t) v[t] = (o + t < d.Co) ? v[t] : 0.0f;
   if (d.ext) {
     float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)n * d.Co + o;
 #pragma unroll
