@@ -10,9 +10,10 @@
  * (every node evaluates phi(sum_j u_j x_j) on tensors of its own model) becomes
  * one launch schedule in which nodes of different members at the same depth run
  * as grouped kernels; members of different architecture, which rarely share a
- * kernel shape, form separate lanes of that schedule that run concurrently.  Properties C1 / C4 (Section III-A, Section IV-C) are kept:
- * no operator is merged across members, each member's output is bit-identical to
- * the member run alone, and no member reads another member's tensors.
+ * kernel shape, form separate lanes of that schedule that run concurrently.
+ * Properties C1 / C4 (Section III-A, Section IV-C) are kept: no operator is
+ * merged across members, each member's output is bit-identical to the member run
+ * alone, and no member reads another member's tensors.
  *
  * Conventions
  *  - Every call returns fi_status; on error out-parameters are untouched and
@@ -21,9 +22,9 @@
  *    are BORROWED: the caller keeps them alive until fi_destroy().
  *  - State machine:  BUILT --fi_load--> LOADED --fi_run*--> LOADED --fi_unload-->
  *    BUILT --fi_destroy--> gone.  Any other transition returns FI_ESTATE.
- *  - All members of one DAG share the weight dtype and the input shape, and read
- *    the same input batch (Algorithm 1's per-model inputs x^m collapse to one
- *    shared x; per-member inputs are not part of this ABI yet).
+ *  - All members of one DAG share the weight dtype and the input shape.  fi_run
+ *    feeds one shared input batch to every member; fi_run_inputs gives each
+ *    member an input of its own (Algorithm 1's per-model inputs x^m).
  */
 #ifndef FUSEDINF_H
 #define FUSEDINF_H

@@ -187,6 +187,11 @@ static fi_status analyze_member(const fi_build_opts& opts, Member& mb, int32_t m
     set_error("FI_LOAD_PER_MODEL needs members in device layout (fi_model_pack)"); return FI_EINVAL; }
   if (first && (mb.spec.dtype != first->dtype || mb.spec.in_c != first->in_c || mb.spec.in_h != first->in_h || mb.spec.in_w != first->in_w)) {
     set_error("model %d: members of one DAG share weight dtype and input shape", m); return FI_EINVAL; }
+  for (const Node& n : mb.plan.nodes)
+    if ((int64_t)opts.max_batch * n.Ho * n.Wo > INT32_MAX || (int64_t)opts.max_batch * n.H * n.W > INT32_MAX) {
+      set_error("model %d node %d: batch %d x %d x %d pixels exceeds the 2^31 rows a launch can index", m, n.index, opts.max_batch,
+                n.Ho > n.H ? n.Ho : n.H, n.Wo > n.W ? n.Wo : n.W);
+      return FI_EUNSUPPORTED; }
   mb.arena_off = kNone;
   return FI_OK;
 }
@@ -211,7 +216,7 @@ fi_status fi_footprint(const fi_model_spec* models, int32_t n, const fi_build_op
 
 static fi_status build_core(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, bool with_image, fi_dag** out) {
   if (!models || n < 1 || !opts || !out) { set_error("null argument or no models"); return FI_EINVAL; }
-  if (opts->max_batch < 1) { set_error("max_batch must be >= 1"); return FI_EINVAL; }
+  if (opts->max_batch < 1 || opts->max_batch > kMaxBatch) { set_error("max_batch must be in [1, %d]", kMaxBatch); return FI_EINVAL; }
   if (opts->load_mode != FI_LOAD_ONE_COPY && opts->load_mode != FI_LOAD_PER_MODEL) { set_error("bad load_mode"); return FI_EINVAL; }
   if ((opts->pin_alloc == nullptr) != (opts->pin_free == nullptr) || (opts->dev_alloc == nullptr) != (opts->dev_free == nullptr)) {
     set_error("allocator callbacks come in alloc/free pairs"); return FI_EINVAL; }

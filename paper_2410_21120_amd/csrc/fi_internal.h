@@ -11,6 +11,13 @@ namespace fi {
 
 constexpr uint64_t kAlign = 256;       // every arena object starts on a 256-byte boundary
 constexpr uint64_t kNone = ~0ull;
+// Largest sizes a spec may name.  They keep the planner's and the kernels' 32-bit index arithmetic exact:
+// rows of an implicit GEMM (batch x pixels) and elements of one tensor per image stay below 2^31.
+constexpr int32_t kMaxChannels = 1 << 18;   // channels of any tensor
+constexpr int32_t kMaxSide = 1 << 14;       // input height / width
+constexpr int32_t kMaxWindow = 1 << 10;     // kernel size, stride, padding as spec fields (kernels themselves stop at 15)
+constexpr int32_t kMaxElems = 1 << 28;      // elements of one tensor, per image (padded channels included)
+constexpr int32_t kMaxBatch = 1 << 16;
 inline uint64_t align_up(uint64_t v, uint64_t a = kAlign) { return (v + a - 1) / a * a; }
 
 // Kernel families.  A launch runs one family over 1..FI_MAX_GROUP problems.

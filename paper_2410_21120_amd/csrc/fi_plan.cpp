@@ -37,6 +37,9 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
   if (m.dtype == FI_F32 && m.act_dtype != FI_F32) { set_error("model %s: fp32 weights need fp32 activations", nm); return FI_EINVAL; }
   if (m.n_layers <= 0 || !m.layers) { set_error("model %s: no layers", nm); return FI_EINVAL; }
   if (m.in_c <= 0 || m.in_h <= 0 || m.in_w <= 0) { set_error("model %s: bad input shape", nm); return FI_EINVAL; }
+  if (m.in_c > kMaxChannels || m.in_h > kMaxSide || m.in_w > kMaxSide || (int64_t)m.in_c * m.in_h * m.in_w > kMaxElems) {
+    set_error("model %s: input larger than %d channels, %d x %d pixels or %d elements per image", nm, kMaxChannels, kMaxSide, kMaxSide, kMaxElems);
+    return FI_EUNSUPPORTED; }
   if (m.output_node < 0 || m.output_node >= m.n_layers) { set_error("model %s: output_node out of range", nm); return FI_EINVAL; }
   const int32_t g = m.dtype == FI_BF16 ? 8 : 1;
   const int32_t kg = m.dtype == FI_BF16 ? 32 : 1;
@@ -67,6 +70,11 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
       return FI_EINVAL;
     }
     if (L.act < FI_ACT_NONE || L.act > FI_ACT_SIGMOID) { set_error("model %s node %d: bad activation", nm, i); return FI_EINVAL; }
+    // Every size field is bounded before any arithmetic on it, so that nothing below can overflow.
+    if (L.cin < 0 || L.cin > kMaxElems || L.cout < 0 || L.cout > kMaxChannels || L.kh < 0 || L.kh > kMaxWindow ||
+        L.kw < 0 || L.kw > kMaxWindow || L.stride < 0 || L.stride > kMaxWindow || L.pad < 0 || L.pad > kMaxWindow ||
+        L.groups < 0 || L.groups > kMaxChannels || L.c_first < 0 || L.c_first > kMaxChannels) {
+      set_error("model %s node %d: a size field is negative or beyond the supported range", nm, i); return FI_EINVAL; }
     if (L.input == FI_INPUT) { n.C = m.in_c; n.H = m.in_h; n.W = m.in_w; n.Cp = out.in_cp; }
     else { const Node& s = out.nodes[(size_t)L.input]; n.C = s.Co; n.H = s.Ho; n.W = s.Wo; n.Cp = s.Cop; }
     n.k = 1; n.kw = 1; n.stride = 1; n.pad = 0; n.pad_w = 0;
@@ -147,7 +155,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         break;
       case FI_FC:
         if (L.cout < 1) { set_error("model %s node %d: bad cout", nm, i); return FI_EINVAL; }
-        if (L.cin != n.C * n.H * n.W) { set_error("model %s node %d: fc cin %d != %d*%d*%d", nm, i, L.cin, n.C, n.H, n.W); return FI_EINVAL; }
+        if ((int64_t)L.cin != (int64_t)n.C * n.H * n.W) { set_error("model %s node %d: fc cin %d != %d*%d*%d", nm, i, L.cin, n.C, n.H, n.W); return FI_EINVAL; }
         n.Co = L.cout; n.Ho = 1; n.Wo = 1;
         n.macs = (uint64_t)L.cout * L.cin;
         break;
@@ -160,6 +168,9 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         set_error("model %s node %d: unknown op %d", nm, i, L.op);
         return FI_EUNSUPPORTED;
     }
+    if (n.Co > kMaxChannels || (int64_t)round_up(n.Co, g) * n.Ho * n.Wo > kMaxElems) {
+      set_error("model %s node %d: output larger than %d channels or %d elements per image", nm, i, kMaxChannels, kMaxElems);
+      return FI_EUNSUPPORTED; }
     n.Cop = round_up(n.Co, g);
     if (L.residual != FI_NO_RESIDUAL && L.op != FI_CONCAT && L.op != FI_MUL) {
       const Node& r = out.nodes[(size_t)L.residual];
@@ -179,7 +190,8 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
       const uint64_t cw = (L.op == FI_CONV2D ? (uint64_t)n.Co * (n.C / (L.groups > 1 ? L.groups : 1)) * n.k * n.kw
                            : L.op == FI_FC  ? (uint64_t)n.Co * L.cin : (uint64_t)n.Co * n.k * n.k) * wsz;
       if (!m.weights_packed && m.weights &&
-          (L.w_off + cw > m.weight_bytes || L.b_off + (uint64_t)n.Co * 4 > m.weight_bytes)) {
+          (L.w_off > m.weight_bytes || cw > m.weight_bytes - L.w_off ||
+           L.b_off > m.weight_bytes || (uint64_t)n.Co * 4 > m.weight_bytes - L.b_off)) {
         set_error("model %s node %d: weight/bias offsets run past the blob", nm, i); return FI_EINVAL; }
     }
   }
