@@ -460,3 +460,32 @@ def test_concat_and_ceil_pooling_in_the_planner():
     assert broken(lambda s: setattr(s.layers[2], "cout", 41)) == fi.FI_EINVAL                        # wrong channel sum
     assert broken(lambda s: setattr(s.layers[2], "act", fi.FI_ACT_RELU)) == fi.FI_EUNSUPPORTED
     assert broken(lambda s: setattr(s.layers[1], "stride", 2)) == fi.FI_EINVAL                       # sources differ in size
+
+
+@pytest.mark.parametrize("seed", range(0, 60, 3))
+def test_random_graphs_compile_into_one_dag(seed):
+    """Three random layer graphs over every operator, sharing the input shape, compile into one DAG that holds
+    exactly their nodes, with every tensor inside the planned arenas."""
+    from workloads import randnet
+    first = randnet.random_model(seed)
+    models = [first] + [randnet.random_model(seed + j, in_c=first.in_c, hw=(first.in_h, first.in_w)) for j in (1, 2)]
+    alloc = fi.HostAllocators()
+    specs, keep = [], []
+    for i, m in enumerate(models):
+        blob = gen.make_blob(m, 7000 + seed + i)
+        s, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype="f32" if i == 2 else None)
+        specs.append(s)
+        keep.append((k, blob))
+    d = fi.Dag(specs, 3, alloc, keepalive=keep)
+    q = d.query()
+    assert q.n_nodes == sum(len(m.layers) for m in models) and q.n_models == 3
+    assert q.macs_per_image == sum(m.macs() for m in models)
+    nodes = d.nodes()
+    k = 0
+    for m in models:
+        for L in m.layers:
+            n = nodes[k]
+            assert (n.out_c, n.out_h, n.out_w) == (L.cout, L.out_h, L.out_w)
+            assert n.is_output or n.out_off + n.out_bytes <= q.act_bytes
+            k += 1
+    d.destroy()

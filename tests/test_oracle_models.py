@@ -8,7 +8,7 @@ import torch
 import torch.nn.functional as F
 
 import oracle
-from workloads import gen, zoo
+from workloads import gen, randnet, zoo
 
 import json
 import os
@@ -142,6 +142,22 @@ def test_model_runner_vs_library_forward(fam, hw):
     # batch independence: image 1 alone gives image 1's row, bit for bit
     y1 = oracle.run_model(m, blob, x[1:2], round_storage=False)
     assert np.array_equal(y1[0], y[1])
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_graphs_vs_library_forward(seed):
+    """Random layer graphs over every operator (odd channel counts, non-square inputs, residuals and
+    concatenations across distant nodes): the oracle's model runner against the library forward pass."""
+    m = randnet.random_model(seed, max_nodes=12)
+    blob = gen.make_blob(m, 5000 + seed)
+    x = gen.make_input(11 + seed, 2, m.in_c, m.in_h, m.in_w, "normal", m.dtype)
+    ref = _torch_forward(m, blob, x)
+    y = oracle.run_model(m, blob, x, round_storage=False)
+    assert y.shape == ref.shape and np.isfinite(y).all()
+    scale = np.linalg.norm(ref)
+    assert np.linalg.norm(y.astype(np.float64) - ref) <= 2e-5 * scale + 1e-6
+    y64 = oracle.run_model(m, blob, x, round_storage=False, f64=True)
+    assert np.linalg.norm(y64 - ref) <= 2e-6 * scale + 1e-9
 
 
 def test_residual_is_added_before_activation():
