@@ -340,8 +340,8 @@ static fi_status plan_dag(fi_dag* g) {
     switch (nd.op) {
       case FI_CONV2D:
       case FI_FC:
-        if (g->wdtype == FI_BF16 && nd.op == FI_FC && B <= 32 && nd.residual < 0) {
-          // batch <= 32: one 32-wide MFMA column block holds the whole batch; the layer is a weight stream
+        if (g->wdtype == FI_BF16 && nd.op == FI_FC) {
+          // a weight stream: 32 images fill one MFMA column block, larger batches take one pass per 32 images
           nd.kind = K_FC;
           const int tiles = (nd.Co + 31) / 32, steps = nd.Kp / 16;
           nd.splits = std::max(1, std::min(std::min(64, std::max(1, steps / 8)), std::max(1, 2048 / tiles)));

@@ -69,7 +69,7 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_AVGPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_GAP: return (batch * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256;
     case K_SOFTMAX: return batch;
-    case K_FC: return (d.tiles_n * d.splits + 3) / 4;
+    case K_FC: return (d.tiles_n * d.splits * ((batch + 31) / 32) + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
     case K_GATHER: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
     case K_CONCAT:
@@ -996,14 +996,16 @@ __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
-// small-batch fully connected layer (batch <= 32): y = x W^T is a weight stream, so the
-// reduction is split across waves to put the whole chip on the weight matrix.  One wave owns
-// 32 output features x one slice of K: per 16 reduction elements it loads its 32x16 weight
-// block (each lane walks one weight row, 16 bytes at a time) and the 16x32 slice of x
-// (batch in the MFMA column dimension, rows past the batch are zero), issues one 32x32x16
-// MFMA (two for fp32 activations: hi/lo split), and finally writes its fp32 partial
-// [feature][batch] block to the workspace.  reduce_kernel sums the partials in a fixed
-// order (deterministic), adds the bias, applies the activation and stores.
+// fully connected layer: y = x W^T is a weight stream, so the reduction is split across waves
+// to put the whole chip on the weight matrix.  One wave owns 32 output features x one slice of
+// K x up to 32 images: per 16 reduction elements it loads its 32x16 weight block -- one
+// contiguous kilobyte, the packed layout stores the blocks in the order the lanes consume them,
+// so every cache line is requested exactly once -- and the 16x32 slice of x (batch in the MFMA
+// column dimension, columns past the batch are zero), issues one 32x32x16 MFMA (two for fp32
+// activations: hi/lo split), and finally writes its fp32 partial [batch][feature] block to the
+// workspace.  Batches above 32 take one such pass per 32 images (the matrix is then streamed
+// once per pass).  reduce_kernel sums the partials in a fixed order (deterministic), adds the
+// bias and the residual, applies the activation and stores.
 // ---------------------------------------------------------------------------------
 template <bool WIDE>
 __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
@@ -1011,17 +1013,19 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
   if (!find_problem(a, K_FC, 0, p, bid)) return;
   const Desc d = a.d[p];
   const int lane = threadIdx.x & 63;
-  const int unit = bid * 4 + (threadIdx.x >> 6);
-  if (unit >= d.tiles_n * d.splits) return;
+  int unit = bid * 4 + (threadIdx.x >> 6);
+  const int per_chunk = d.tiles_n * d.splits;
+  if (unit >= per_chunk * ((a.batch + 31) / 32)) return;
+  const int chunk = unit / per_chunk;   // which 32 images
+  unit -= chunk * per_chunk;
   const int tile = unit % d.tiles_n, split = unit / d.tiles_n;
   const int steps = d.Kp / 16;
   const int per = (steps + d.splits - 1) / d.splits;
   const int s0 = split * per, s1 = min(steps, s0 + per);
-  int f = tile * 32 + (lane & 31);
-  f = f < d.Co ? f : d.Co - 1;  // clamped rows are computed and discarded
   const int kq = (lane >> 5) * 8;
-  const uint4* wp = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(a.wbase + d.w_off) + (int64_t)f * d.Kp + kq);
-  const int n = lane & 31;
+  // block (tile, step) of the packed matrix is 64 x 16 bytes in lane order
+  const uint4* wp = reinterpret_cast<const uint4*>(a.wbase + d.w_off) + (int64_t)tile * steps * 64 + lane;
+  const int n = chunk * 32 + (lane & 31);
   const bool nok = n < a.batch;
   const int K = d.Cp;  // flattened input length (elements), a multiple of 8
   f32x16 acc;
@@ -1035,7 +1039,7 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
     for (int u = 0; u < U; ++u) {
       const int st = sb + u;
       const bool ok = st < s1;
-      wv[u] = ok ? wp[st * 2] : make_uint4(0, 0, 0, 0);
+      wv[u] = ok ? wp[(int64_t)st * 64] : make_uint4(0, 0, 0, 0);
       const int k = st * 16 + kq;
       const bool xok = ok && nok && k < K;
       if constexpr (WIDE) {

@@ -4,7 +4,10 @@
 // Packed layout of a member (all offsets 256-byte aligned, node order):
 //   conv       w [cout][kh][kw][Cp]  each row zero-padded to Kp elements, model dtype
 //   depthwise  w [kh][kw][Cp]        (tap-major, channel innermost), model dtype
-//   fc         w [cout][H][W][Cp]    i.e. the input tensor's NHWC storage order, row padded to Kp
+//   fc         w [cout][H][W][Cp]    i.e. the input tensor's NHWC storage order, row padded to Kp (fp32 weights);
+//              bf16 weights: the same rows cut into the blocks the matrix cores consume, so that a wave's load is
+//              one contiguous kilobyte: [cout/32][Kp/16][64][8] where entry (t, s, l) holds elements
+//              s*16 + (l/32)*8 .. +8 of row t*32 + l%32 (rows past cout are zero)
 //   bias       fp32 [Cop]
 // Cp rounds channels up to 8 for bf16 weights (16-byte vectors along C) and to 1 for
 // fp32.  Kp rounds the row up to 32 elements for bf16 so a reduction tile never straddles
@@ -12,7 +15,9 @@
 // channel contributes nothing.
 #include <cstdarg>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
+#include <vector>
 
 #include "fi_internal.h"
 
@@ -181,7 +186,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
     n.w_rel = n.b_rel = kNone;
     uint64_t wbytes = 0;
     if (L.op == FI_CONV2D) { n.Kp = round_up(n.k * n.kw * n.Cp, kg); wbytes = (uint64_t)n.Co * n.Kp * wsz; }
-    else if (L.op == FI_FC) { n.Kp = round_up(n.H * n.W * n.Cp, kg); wbytes = (uint64_t)n.Co * n.Kp * wsz; }
+    else if (L.op == FI_FC) { n.Kp = round_up(n.H * n.W * n.Cp, kg); wbytes = (uint64_t)(m.dtype == FI_BF16 ? round_up(n.Co, 32) : n.Co) * n.Kp * wsz; }
     else if (L.op == FI_DWCONV2D) { n.Kp = n.k * n.k; wbytes = (uint64_t)n.k * n.k * n.Cp * wsz; }
     if (wbytes) {
       n.w_rel = off; off = align_up(off + wbytes);
@@ -258,13 +263,22 @@ static void pack_typed(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst8
     } else if (n.op == FI_FC) {
       // canonical column index runs over (c, h, w); packed over (h, w, c) with stride Cp
       const int32_t HW = n.H * n.W;
+      std::vector<T> row((size_t)n.Kp);
       for (int32_t o = 0; o < n.Co; ++o) {
         const T* wr = w + (size_t)o * n.C * HW;
-        T* dr = d + (size_t)o * n.Kp;
-        if (HW == 1) { std::memcpy(dr, wr, (size_t)n.C * sizeof(T)); continue; }
-        for (int32_t q = 0; q < HW; ++q) {
-          T* dq = dr + (size_t)q * n.Cp;
-          for (int32_t c = 0; c < n.C; ++c) dq[c] = wr[(size_t)c * HW + q];
+        T* dr = sizeof(T) == 2 ? row.data() : d + (size_t)o * n.Kp;
+        if (sizeof(T) == 2) std::fill(row.begin(), row.end(), T(0));
+        if (HW == 1) std::memcpy(dr, wr, (size_t)n.C * sizeof(T));
+        else
+          for (int32_t q = 0; q < HW; ++q) {
+            T* dq = dr + (size_t)q * n.Cp;
+            for (int32_t c = 0; c < n.C; ++c) dq[c] = wr[(size_t)c * HW + q];
+          }
+        if (sizeof(T) == 2) {   // bf16: scatter the row into its 32-row tile, 8 elements (16 bytes) per (step, lane)
+          const size_t steps = (size_t)n.Kp / 16;
+          T* tile = d + (size_t)(o / 32) * steps * 64 * 8;
+          for (size_t k8 = 0; k8 < (size_t)n.Kp / 8; ++k8)
+            std::memcpy(tile + ((k8 / 2) * 64 + (k8 % 2) * 32 + (size_t)(o % 32)) * 8, dr + k8 * 8, 8 * sizeof(T));
         }
       }
     } else {  // depthwise: [c][0][r][s] -> [r][s][c]

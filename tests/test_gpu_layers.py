@@ -298,6 +298,19 @@ def test_fc_on_spatial_input_bf16():
     _run_case(m, 5, 8)
 
 
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide"])
+@pytest.mark.parametrize("batch", [33, 70])
+def test_fc_batches_above_32_and_residual(batch, mode):
+    """The FC kernel takes 32 images per pass: batches that need two and three passes (the last one ragged), a
+    feature count that is not a multiple of 32, and an FC that adds a residual."""
+    m = zoo.Model("f", "bf16", 24, 5, 3)
+    a = m.add(zoo.FC, -1, cin=24 * 15, cout=77, act=zoo.RELU)
+    b = m.add(zoo.FC, a, cin=77, cout=77, act=zoo.NONE)
+    c = m.add(zoo.FC, b, cin=77, cout=77, act=zoo.RELU, residual=a)
+    m.add(zoo.FC, c, cin=77, cout=1000)
+    _run_case(m, 77, batch, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
 def test_batch_smaller_than_max_batch():
     from tests import harness
     m = zoo.resnet18(hw=64)

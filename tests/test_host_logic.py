@@ -150,6 +150,32 @@ def test_pack_is_a_permutation_with_zero_padding():
     assert n % 256 == 0 and n >= canon.nbytes
 
 
+def test_fc_weights_are_packed_in_matrix_core_blocks():
+    """bf16 FC weights: rows over (h, w, c padded to 8), cut into blocks of 32 features x 16 reduction elements
+    stored in the order the 64 lanes of a wave load them (lane l: feature l % 32, elements (l / 32) * 8 .. + 8),
+    so one block is one contiguous kilobyte; features past cout are zero rows."""
+    m = zoo.Model("f", "bf16", 5, 2, 3)
+    m.add(zoo.FC, -1, cin=30, cout=40)
+    m.shapes()
+    blob = gen.make_blob(m, 9)
+    spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    n = fi.fi_model_packed_size(spec)
+    dst = np.full(n, 0xAB, np.uint8)
+    fi.fi_model_pack(spec, dst.ctypes.data, n)
+    L = m.layers[0]
+    w = blob[L.w_off:L.w_off + 2 * 40 * 30].view(np.uint16).reshape(40, 5, 2, 3)
+    kp = 64                                    # 2 * 3 pixels x 8 padded channels = 48, rounded up to 32s
+    rows = np.zeros((64, kp), np.uint16)       # 40 features padded to two tiles of 32
+    rows[:40, :48].reshape(40, 2, 3, 8)[..., :5] = w.transpose(0, 2, 3, 1)
+    steps = kp // 16
+    blocks = dst[:2 * 64 * kp].view(np.uint16).reshape(2, steps, 64, 8)
+    for t in range(2):
+        for s_ in range(steps):
+            for lane in range(64):
+                f, k0 = t * 32 + lane % 32, s_ * 16 + (lane // 32) * 8
+                assert np.array_equal(blocks[t, s_, lane], rows[f, k0:k0 + 8]), (t, s_, lane)
+
+
 def test_packed_and_canonical_members_build_the_same_image():
     m = zoo.resnet18(hw=32)
     blob = gen.make_blob(m, 9)
