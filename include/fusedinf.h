@@ -228,7 +228,8 @@ fi_status fi_run(fi_dag* dag, const void* d_input, int32_t batch, void* const* d
  * d_inputs[m] ([batch, in_h, in_w, in_c] NHWC in the weight dtype, read-only; all
  * members share the input shape and the batch).  Needs a DAG built with
  * fi_build_opts.per_member_inputs = 1 (else FI_ESTATE); such a DAG stages one
- * channel-padded copy per member instead of one per activation dtype, and fi_run
+ * channel-padded copy per member instead of one per activation dtype and channel
+ * stride, and fi_run
  * on it feeds the one input to every member.  Always launches eagerly (use_graph
  * applies to fi_run). */
 fi_status fi_run_inputs(fi_dag* dag, const void* const* d_inputs, int32_t batch, void* const* d_outputs, void* hip_stream);

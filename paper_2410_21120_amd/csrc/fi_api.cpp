@@ -25,7 +25,8 @@ struct Tensor {           // one stored activation tensor (a node's output, or a
 
 struct StageTensor {      // a staged (channel-padded, activation-dtype) copy of a caller's input
   int32_t adt;            // activation dtype of the copy
-  int32_t member;         // owner when every member has its own input; -1: shared by every member of this dtype
+  int32_t cp;             // channel stride of the copy (a member's in_cp: 4 when only convolutions read an RGB-like input)
+  int32_t member;         // owner when every member has its own input; -1: shared by every member of this dtype and stride
   int32_t lane;           // -1: shared by all lanes
   int32_t last;           // last level that reads it
   uint64_t off;           // placement in the activation arena
@@ -390,14 +391,16 @@ static fi_status plan_dag(fi_dag* g) {
     for (int32_t m = 0; m < n; ++m) {
       Member& mb = g->members[(size_t)m];
       mb.stage = (int32_t)g->stages.size();
-      g->stages.push_back(StageTensor{mb.spec.act_dtype, m, g->n_lanes > 1 ? mb.lane : -1, 0, 0});
+      g->stages.push_back(StageTensor{mb.spec.act_dtype, mb.plan.in_cp, m, g->n_lanes > 1 ? mb.lane : -1, 0, 0});
     }
   } else {
-    int32_t of_adt[2] = {-1, -1};
+    // one copy per (activation dtype, channel stride) that some member reads
     for (Member& mb : g->members) {
       const int adt = mb.spec.act_dtype;
-      if (of_adt[adt] < 0) { of_adt[adt] = (int32_t)g->stages.size(); g->stages.push_back(StageTensor{adt, -1, -1, 0, 0}); }
-      mb.stage = of_adt[adt];
+      mb.stage = -1;
+      for (size_t t = 0; t < g->stages.size(); ++t)
+        if (g->stages[t].adt == adt && g->stages[t].cp == mb.plan.in_cp) mb.stage = (int32_t)t;
+      if (mb.stage < 0) { mb.stage = (int32_t)g->stages.size(); g->stages.push_back(StageTensor{adt, mb.plan.in_cp, -1, -1, 0, 0}); }
     }
   }
   auto new_launch = [&](int level, int kind, int tile, int adt) -> Launch& {
@@ -475,7 +478,7 @@ static fi_status plan_dag(fi_dag* g) {
   for (int32_t t = 0; t < n_stage; ++t) {
     const StageTensor& st = g->stages[(size_t)t];
     tens[(size_t)(total + t)] = Tensor{0, st.last, st.lane,
-        align_up((uint64_t)B * m0.spec.in_h * m0.spec.in_w * m0.plan.in_cp * esize(st.adt)), 0};
+        align_up((uint64_t)B * m0.spec.in_h * m0.spec.in_w * st.cp * esize(st.adt)), 0};
   }
   {
     std::vector<int32_t> order;
@@ -560,7 +563,7 @@ static fi_status plan_dag(fi_dag* g) {
     if (L.kind == K_STAGE) {
       for (int32_t k = 0; k < L.n; ++k) {
         Desc& d = g->descs[(size_t)(L.first_desc + k)];
-        d.H = m0.spec.in_h; d.W = m0.spec.in_w; d.C = m0.spec.in_c; d.Cp = m0.plan.in_cp;
+        d.H = m0.spec.in_h; d.W = m0.spec.in_w; d.C = m0.spec.in_c; d.Cp = g->stages[(size_t)L.nodes[(size_t)k]].cp;
         d.y_off = g->stages[(size_t)L.nodes[(size_t)k]].off; d.r_off = kNone; d.x_off = d.w_off = d.b_off = kNone;
         L.act_bytes += (uint64_t)d.H * d.W * (d.C * esize(L.wdtype) + d.Cp * esize(L.adtype));
       }

@@ -77,8 +77,9 @@ Model well_formed(Rng& r) {
   for (int step = 0; step < want; ++step) {
     const Shape s = shape_of(m, cur);
     const int act = r.below(7);
-    const int what = r.below(100);
-    if (what < 45 || cur == FI_INPUT) {   // dense convolution, sometimes grouped / rectangular / with a residual
+    int what = r.below(100);
+    if (cur == FI_INPUT && what >= 67) what = 0;   // concat, gate, slice and shuffle do not take the model input directly
+    if (what < 45) {   // dense convolution, sometimes grouped / rectangular / with a residual
       int kh = r.pick({1, 1, 3, 3, 3, 5, 7}), kw = kh;
       if (r.chance(15)) { kh = r.pick({1, 3, 7}); kw = kh == 1 ? r.pick({3, 7}) : 1; }
       const int stride = r.chance(25) ? 2 : 1;

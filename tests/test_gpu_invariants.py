@@ -248,3 +248,35 @@ def test_run_time_argument_errors_on_a_loaded_dag():
         assert all(np.array_equal(a[:1], b2) for a, b2 in zip(base, g.run(x[:1])))   # batch 1 of max 3: rows are independent
     finally:
         g.close()
+
+
+def test_members_that_stage_the_input_differently():
+    """An RGB-like input is staged with 4 channels for members whose input feeds only convolutions and with 8
+    for the others (here: a pooling-first and a depthwise-first member): one DAG holds both copies and every
+    member reads its own."""
+    from tests import harness
+    from workloads import zoo
+
+    def member(first):
+        m = zoo.Model(first, "bf16", 3, 20, 24)
+        cur = -1
+        if first == "pool":
+            cur = m.add(zoo.MAXPOOL, cur, k=2, stride=2, pad=0)
+        elif first == "dw":
+            cur = m.add(zoo.DWCONV, cur, cin=3, cout=3, k=3, stride=1, pad=1, act=zoo.RELU)
+        cur = m.add(zoo.CONV, cur, cin=3, cout=16, k=3, stride=1, pad=1, act=zoo.RELU)
+        cur = m.add(zoo.GAP, cur)
+        m.add(zoo.FC, cur, cin=16, cout=10)
+        return m.shapes()
+    for order in (["conv", "pool", "dw"], ["pool", "conv", "dw"]):
+        models = [member(f) for f in order]
+        blobs = [gen.make_blob(m, 40 + i) for i, m in enumerate(models)]
+        x = gen.make_input(3, 3, 3, 20, 24, "normal", "bf16")
+        g = harness.GpuDag([(m, b, "f32" if i == 2 else None) for i, (m, b) in enumerate(zip(models, blobs))], 3)
+        try:
+            ys = g.run(x)
+        finally:
+            g.close()
+        for i, (m, b, y) in enumerate(zip(models, blobs, ys)):
+            ref = harness.oracle_nhwc(m, b, x, False)
+            assert harness.rel_l2(y, ref) <= (1e-4 if i == 2 else 1e-2), (order, i)

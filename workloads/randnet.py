@@ -33,7 +33,9 @@ def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: 
         c, hh, ww = shape(cur)
         act = r.choice(ACTS)
         what = r.random()
-        if what < 0.42 or cur == zoo.MODEL_INPUT:
+        if cur == zoo.MODEL_INPUT and what >= 0.64:
+            what = 0.0   # the operators below do not take the model input directly
+        if what < 0.42:
             k = r.choice([1, 1, 3, 3, 3, 5, 7]); kw = 0
             if r.random() < 0.15:
                 k, kw = r.choice([(1, 3), (1, 7), (3, 1), (7, 1)])
