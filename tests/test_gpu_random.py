@@ -45,3 +45,94 @@ def test_three_random_graphs_fused(seed):
         assert e_s <= max(2e-3, 0.5 * d_sf) + floor, f"member {i}: rel L2 vs storage-rounding oracle {e_s}, modes differ by {d_sf}"
         if d_sf <= 0.5 * BF16_TOL:   # graphs on which bf16 storage itself stays inside the bar
             assert e_f <= BF16_TOL + floor, f"member {i}: rel L2 {e_f}"
+
+
+@pytest.mark.parametrize("seed", range(1, 120, 6))
+def test_random_graphs_keep_their_bits_under_every_build_option(seed):
+    """The invariants of the method on random graphs: a member's output is the same, bit for bit, alone, next to
+    other members, in another slot, ungrouped, on one stream, replayed as a HIP graph, loaded from device-layout
+    blobs with one copy per member, with fewer images in the batch, given its input through the
+    per-member entry point, and after its neighbour was swapped for another model."""
+    import torch
+    import paper_2410_21120_amd as fi
+    from tests import harness
+    first = randnet.random_model(seed)
+    same = dict(in_c=first.in_c, hw=(first.in_h, first.in_w))
+    models = [first, randnet.random_model(seed + 1, **same), randnet.random_model(seed + 2, **same), first]
+    acts = [None, "f32", None, None]   # members 0 and 3 share an architecture (one lane, grouped launches)
+    batch = 2 + seed % 3
+    mem = [(m, gen.make_blob(m, 9000 + seed + i), a) for i, (m, a) in enumerate(zip(models, acts))]
+    x = gen.make_input(51 + seed, batch, first.in_c, first.in_h, first.in_w, "normal", "bf16")
+    print(f"seed {seed}: batch {batch}, input {first.in_c}x{first.in_h}x{first.in_w}, nodes {[len(m.layers) for m in models]}", flush=True)
+
+    def run(members, xx, **kw):
+        g = harness.GpuDag(members, kw.pop("max_batch", xx.shape[0]), **kw)
+        try:
+            return g.run(xx)
+        finally:
+            g.close()
+    base = run(mem, x)
+    assert all(np.isfinite(y).all() for y in base)
+    for i, mb in enumerate(mem):
+        assert np.array_equal(run([mb], x)[0], base[i]), f"member {i} alone"
+    order = [2, 3, 0, 1]
+    for slot, y in zip(order, run([mem[i] for i in order], x)):
+        assert np.array_equal(y, base[slot]), f"member {slot} permuted"
+    packed = []   # repository-time device-layout blobs in pinned memory
+    for m, blob, act in mem:
+        spec, keep_spec = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        n = fi.fi_model_packed_size(spec)
+        t = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+        fi.fi_model_pack(spec, t.data_ptr(), n)
+        packed.append((m, t.numpy(), act))
+    variants = dict(ungrouped=(mem, dict(group_levels=False)), serial=(mem, dict(serial_lanes=True)), graph=(mem, dict(use_graph=True)),
+                    per_model_copies=(packed, dict(packed=True, load_mode=fi.FI_LOAD_PER_MODEL)),
+                    packed_one_copy=(packed, dict(packed=True)))
+    for name, (members, kw) in variants.items():
+        for i, y in enumerate(run(members, x, **kw)):
+            assert np.array_equal(y, base[i]), f"{name}: member {i}"
+    # a DAG built for a larger batch: an image's output does not depend on how many images accompany it
+    # (the split factors, and with them the summation order, belong to the DAG's max_batch, so the comparison
+    # stays inside one DAG)
+    more = np.concatenate([x, gen.make_input(52 + seed, 3, first.in_c, first.in_h, first.in_w, "normal", "bf16")])
+    g = harness.GpuDag(mem, batch + 3)
+    try:
+        full, part = g.run(more), g.run(x)
+    finally:
+        g.close()
+    for i in range(4):
+        assert np.array_equal(full[i][:batch], part[i]), f"member {i} at a smaller batch"
+    # per-member inputs: member i on input i equals member i alone on input i
+    xs = [gen.make_input(60 + seed + i, batch, first.in_c, first.in_h, first.in_w, "normal", "bf16") for i in range(4)]
+    alone = [run([mb], xi)[0] for mb, xi in zip(mem, xs)]
+    specs, keep = [], []
+    for m, blob, act in mem:
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        specs.append(sp)
+        keep.append((k, blob))
+    dag = fi.Dag(specs, batch, fi.TorchAllocators("cuda:0"), keepalive=keep, per_member_inputs=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    dag.load(stream)
+    try:
+        dev_in = [torch.from_numpy(gen.to_nhwc_storage(xi, "bf16").view(np.int16)).cuda() for xi in xs]
+        outs = [torch.full((batch, y.shape[1]), float("nan"), dtype=torch.float32, device="cuda:0") for y in base]
+        dag.run_inputs([t.data_ptr() for t in dev_in], batch, [o.data_ptr() for o in outs], stream)
+        torch.cuda.synchronize()
+        for i, o in enumerate(outs):
+            assert np.array_equal(o.cpu().numpy(), alone[i]), f"per-member input {i}"
+    finally:
+        dag.unload()
+        dag.destroy()
+    # swap member 1 for a fresh model: the others keep their bits, the newcomer equals itself alone
+    fresh = randnet.random_model(seed + 7, **same)
+    newcomer = (fresh, gen.make_blob(fresh, 9900 + seed), None)
+    g = harness.GpuDag(mem, batch, swap_headroom_bytes=64 << 20)
+    try:
+        assert all(np.array_equal(a, b) for a, b in zip(g.run(x), base))
+        g.swap(1, newcomer)
+        after = g.run(x)
+    finally:
+        g.close()
+    for i in (0, 2, 3):
+        assert np.array_equal(after[i], base[i]), f"member {i} after its neighbour was swapped"
+    assert np.array_equal(after[1], run([newcomer], x)[0])
