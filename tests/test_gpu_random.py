@@ -136,3 +136,38 @@ def test_random_graphs_keep_their_bits_under_every_build_option(seed):
     for i in (0, 2, 3):
         assert np.array_equal(after[i], base[i]), f"member {i} after its neighbour was swapped"
     assert np.array_equal(after[1], run([newcomer], x)[0])
+
+
+@pytest.mark.parametrize("seed", range(200, 214))
+def test_large_random_graphs_fused(seed):
+    """Random graphs on tensors large enough for the big convolution tiles (40-90 pixels a side, up to 512
+    channels, batch 6): two members of one architecture with bf16-stored activations (one grouped launch per
+    level) and a third with fp32-stored ones, each against the oracle on that member alone."""
+    from tests import harness
+    m = randnet.random_model(seed, large=True, max_nodes=8)
+    batch = 6
+    blobs = [gen.make_blob(m, 8000 + seed + i) for i in range(3)]
+    x = gen.make_input(71 + seed, batch, m.in_c, m.in_h, m.in_w, "normal", "bf16")
+    g = harness.GpuDag([(m, blobs[0], None), (m, blobs[1], None), (m, blobs[2], "f32")], batch)
+    try:
+        names = sorted({L.name.decode() for L in g.dag.launches()})
+        ys = g.run(x)
+    finally:
+        g.close()
+    print(f"seed {seed}: input {m.in_c}x{m.in_h}x{m.in_w}, {len(m.layers)} nodes, {m.macs() / 1e9:.2f} GMAC/image, kernels {names}", flush=True)
+    refs = harness.oracle_units([(m, blobs[0], x, False), (m, blobs[0], x, True), (m, blobs[1], x, False), (m, blobs[1], x, True), (m, blobs[2], x, False)])
+    L = m.layers[m.output]
+
+    def nhwc(r):
+        return r.reshape(batch, L.cout, L.out_h, L.out_w).transpose(0, 2, 3, 1).reshape(batch, -1)
+    for i in range(2):
+        ref_f, ref_s = nhwc(refs[2 * i]), nhwc(refs[2 * i + 1])
+        assert ys[i].shape == ref_f.shape and np.isfinite(ys[i]).all()
+        floor = 1e-5 * np.sqrt(ref_f.size) / max(float(np.linalg.norm(ref_f)), 1e-30)
+        d_sf = harness.rel_l2(ref_s, ref_f)
+        assert harness.rel_l2(ys[i], ref_s) <= max(2e-3, 0.5 * d_sf) + floor, (i, harness.rel_l2(ys[i], ref_s), d_sf)
+        if d_sf <= 0.5 * BF16_TOL:
+            assert harness.rel_l2(ys[i], ref_f) <= BF16_TOL + floor
+    ref_w = nhwc(refs[4])
+    floor = 1e-5 * np.sqrt(ref_w.size) / max(float(np.linalg.norm(ref_w)), 1e-30)
+    assert harness.rel_l2(ys[2], ref_w) <= WIDE_TOL + floor

@@ -13,10 +13,14 @@ from . import zoo
 ACTS = [zoo.NONE, zoo.RELU, zoo.RELU, zoo.RELU6, zoo.HARDSWISH, zoo.HARDSIGMOID, zoo.SILU, zoo.SIGMOID]
 
 
-def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: int = 14) -> zoo.Model:
+def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: int = 14, large: bool = False) -> zoo.Model:
+    """large: fewer nodes on bigger tensors (40-90 pixels a side, 64-512 channels), the shapes that reach the
+    large convolution tiles."""
     r = random.Random(seed)
     in_c = in_c or r.choice([1, 3, 3, 4, 8])
-    h, w = hw or ((lambda s: (s, s))(r.randint(9, 40)) if r.random() < 0.6 else (r.randint(9, 40), r.randint(9, 40)))
+    lo, hi = (40, 90) if large else (9, 40)
+    widths = [64, 64, 96, 128, 128, 192, 256, 320, 512] if large else [1, 3, 8, 10, 16, 24, 32, 40, 64, 72, 96, 130]
+    h, w = hw or ((lambda s: (s, s))(r.randint(lo, hi)) if r.random() < 0.6 else (r.randint(lo, hi), r.randint(lo, hi)))
     m = zoo.Model(f"rand{seed}", dtype, in_c, h, w)
     dims = {}   # node -> (c, h, w)
 
@@ -29,10 +33,12 @@ def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: 
         return i
 
     cur = zoo.MODEL_INPUT
-    for _ in range(r.randint(2, max_nodes)):
+    for _ in range(r.randint(4 if large else 2, max_nodes)):
         c, hh, ww = shape(cur)
         act = r.choice(ACTS)
         what = r.random()
+        if large and what >= 0.42 and r.random() < 0.5:
+            what = 0.0   # mostly dense convolutions
         if cur == zoo.MODEL_INPUT and what >= 0.64:
             what = 0.0   # the operators below do not take the model input directly
         if what < 0.42:
@@ -45,11 +51,11 @@ def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: 
             ph, pw = (pad, pad) if kww == k else (pad if k > 1 else 0, pad if kww > 1 else 0)
             if hh + 2 * ph < k or ww + 2 * pw < kww:
                 continue
-            cout, groups = r.choice([1, 3, 8, 10, 16, 24, 32, 40, 64, 72, 96, 130]), 1
+            cout, groups = r.choice(widths), 1
             if not kw and r.random() < 0.2:
                 g = r.choice([2, 4, 8])
                 if c % g == 0:
-                    groups, cout = g, g * r.randint(1, 12)
+                    groups, cout = g, g * r.randint(1, 12) * (4 if large else 1)
             out = (cout, (hh + 2 * ph - k) // stride + 1, (ww + 2 * pw - kww) // stride + 1)
             res = zoo.NO_RESIDUAL
             if r.random() < 0.4:
