@@ -234,6 +234,17 @@ fi_status fi_run(fi_dag* dag, const void* d_input, int32_t batch, void* const* d
  * applies to fi_run). */
 fi_status fi_run_inputs(fi_dag* dag, const void* const* d_inputs, int32_t batch, void* const* d_outputs, void* hip_stream);
 
+/* The same pass when the members have gathered different numbers of requests
+ * (Section IV: the manager aggregates, per model, the requests that arrived while
+ * the device was busy): member m runs on batches[m] images (HOST array of n_models
+ * entries, 0 <= batches[m] <= max_batch) read from d_inputs[m] and writes
+ * [batches[m], classes_m] to d_outputs[m].  A member with batches[m] == 0 sits the
+ * pass out: none of its kernels get a workgroup, its pointers may be NULL and its
+ * output buffer is not touched.  An image's output bits do not depend on the batch
+ * it travels in.  Needs per_member_inputs = 1 (else FI_ESTATE); launches eagerly. */
+fi_status fi_run_batches(fi_dag* dag, const void* const* d_inputs, const int32_t* batches, void* const* d_outputs,
+                         void* hip_stream);
+
 /* Same pass with every launch issued on hip_stream (lanes serialised) and a HIP
  * event between launches; ms[i] (host, n_launches floats) receives launch i's
  * elapsed milliseconds: the kernel's own time with the chip to itself.

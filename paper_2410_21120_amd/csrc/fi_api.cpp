@@ -728,17 +728,19 @@ fi_status fi_load(fi_dag* g, void* stream) {
 // in milliseconds since the pass began.
 static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream,
                           float* ms, int32_t n_ms, float* tl_begin = nullptr, float* tl_end = nullptr,
-                          const void* const* d_inputs = nullptr) {
+                          const void* const* d_inputs = nullptr, const int32_t* batches = nullptr) {
   if (!g || (!d_input && !d_inputs) || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
   if (d_inputs) {
     if (!g->opts.per_member_inputs) { set_error("per-member inputs need a DAG built with per_member_inputs"); return FI_ESTATE; }
     for (size_t m = 0; m < g->members.size(); ++m)
-      if (!d_inputs[m]) { set_error("input %zu is null", m); return FI_EINVAL; }
+      if (!d_inputs[m] && !(batches && batches[m] == 0)) { set_error("input %zu is null", m); return FI_EINVAL; }
   }
   if (g->state != 1) { set_error("fi_run: handle is not loaded"); return FI_ESTATE; }
-  if (batch < 1 || batch > g->opts.max_batch) { set_error("batch %d outside [1, %d]", batch, g->opts.max_batch); return FI_EINVAL; }
+  if (!batches && (batch < 1 || batch > g->opts.max_batch)) { set_error("batch %d outside [1, %d]", batch, g->opts.max_batch); return FI_EINVAL; }
+  for (size_t m = 0; batches && m < g->members.size(); ++m)
+    if (batches[m] < 0 || batches[m] > g->opts.max_batch) { set_error("batch %d of member %zu outside [0, %d]", batches[m], m, g->opts.max_batch); return FI_EINVAL; }
   for (size_t m = 0; m < g->members.size(); ++m)
-    if (!d_outputs[m]) { set_error("output %zu is null", m); return FI_EINVAL; }
+    if (!d_outputs[m] && !(batches && batches[m] == 0)) { set_error("output %zu is null", m); return FI_EINVAL; }
   const size_t nl = g->launches.size();
   const bool timeline = tl_begin && tl_end;
   if ((ms || timeline) && n_ms < (int32_t)nl) { set_error("timing arrays hold %d entries, schedule has %zu launches", n_ms, nl); return FI_EINVAL; }
@@ -754,7 +756,6 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   KArgs a{};
   a.wbase = g->dev;
   a.abase = g->dev + g->arena_bytes;
-  a.batch = batch;
   fi_status rc = FI_OK;
   // Lanes: after the shared input is staged on the caller's stream the internal streams fork from
   // it, every launch goes to its lane's stream, and the caller's stream joins them at the end.
@@ -773,10 +774,12 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
     for (int32_t k = 0; k < L.n && L.kind == K_STAGE; ++k) {
       const StageTensor& st = g->stages[(size_t)L.nodes[(size_t)k]];
       a.ext_in[k] = (d_inputs && st.member >= 0) ? d_inputs[st.member] : d_input;
+      a.batch[k] = (batches && st.member >= 0) ? batches[st.member] : batch;
     }
     for (int32_t k = 0; k < L.n && L.kind != K_STAGE; ++k) {
       const Node& nd = g->nodes[(size_t)L.nodes[(size_t)k]];
       a.ext_out[k] = nd.is_output ? d_outputs[nd.model] : nullptr;
+      a.batch[k] = batches ? batches[nd.model] : batch;   // a member with no image this pass gets no workgroup
     }
     const int e = launch_kernel(L, a, ls, g->descs);
     if (e != (int)hipSuccess) { set_error("launch %zu (%s): %s", i, L.name.c_str(), hipGetErrorString((hipError_t)e)); rc = FI_EHIP; break; }
@@ -848,6 +851,11 @@ fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_o
 fi_status fi_run_inputs(fi_dag* g, const void* const* d_inputs, int32_t batch, void* const* d_outputs, void* stream) {
   if (!d_inputs) { set_error("null inputs"); return FI_EINVAL; }
   return run_impl(g, nullptr, batch, d_outputs, stream, nullptr, 0, nullptr, nullptr, d_inputs);
+}
+
+fi_status fi_run_batches(fi_dag* g, const void* const* d_inputs, const int32_t* batches, void* const* d_outputs, void* stream) {
+  if (!d_inputs || !batches) { set_error("null inputs or batches"); return FI_EINVAL; }
+  return run_impl(g, nullptr, 0, d_outputs, stream, nullptr, 0, nullptr, nullptr, d_inputs, batches);
 }
 
 fi_status fi_profile(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream, float* ms, int32_t n_ms) {

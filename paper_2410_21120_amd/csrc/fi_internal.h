@@ -112,7 +112,8 @@ struct ModelPlan {
 struct KArgs {
   const uint8_t* wbase;          // weight arena (device)
   uint8_t* abase;                // activation region (device)
-  int32_t n, batch;
+  int32_t n, reserved;
+  int32_t batch[FI_MAX_GROUP];   // images per problem slot in this pass (members may bring batches of their own)
   int32_t first_block[FI_MAX_GROUP + 1];  // workgroup index where each problem starts (filled per launch)
   const void* ext_in[FI_MAX_GROUP];  // caller's input per problem slot (K_STAGE only)
   void* ext_out[FI_MAX_GROUP];   // caller's output per problem slot (when Desc.ext)

@@ -99,8 +99,9 @@ __global__ void __launch_bounds__(256) stage_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_STAGE, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t pix = (int64_t)bid * 256 + threadIdx.x;
-  if (pix >= (int64_t)a.batch * d.H * d.W) return;
+  if (pix >= (int64_t)batch * d.H * d.W) return;
   const TI* x = static_cast<const TI*>(a.ext_in[p]) + pix * d.C;
   TA* y = reinterpret_cast<TA*>(a.abase + d.y_off) + pix * d.Cp;
   for (int c = 0; c < d.Cp; ++c) st(y + c, c < d.C ? ld(x + c) : 0.0f);
@@ -115,8 +116,9 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_CONV_DIRECT, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
-  const int64_t M = (int64_t)a.batch * d.Ho * d.Wo;
+  const int64_t M = (int64_t)batch * d.Ho * d.Wo;
   if (idx >= M * d.Cop) return;
   const int o = (int)(idx % d.Cop);
   const int64_t m = idx / d.Cop;
@@ -225,7 +227,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   int p, bid;
   if (!find_problem_at(a, xcd_contiguous((int)blockIdx.x, (int)gridDim.x), p, bid)) return;
   const Desc d = a.d[p];
-  const int M = a.batch * d.Ho * d.Wo;
+  const int batch = a.batch[p];   // images of this problem's member in this pass
+  const int M = batch * d.Ho * d.Wo;
   // Outputs far larger than the last-level cache are streamed past it; smaller ones are left to the
   // cache, which absorbs the store burst of a launch whose workgroups all finish together.
   const bool stream_out = (int64_t)M * d.Cop * 2 > (int64_t)STREAM_OUT_BYTES;
@@ -241,7 +244,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 
   const bf16_t* __restrict__ w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(a.abase + d.x_off), 0, (int)((int64_t)a.batch * d.H * d.W * d.Cp * AE), 0x00020000);
+      const_cast<uint8_t*>(a.abase + d.x_off), 0, (int)((int64_t)batch * d.H * d.W * d.Cp * AE), 0x00020000);
 
   // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
   const int srow = tid >> 3, kvec = (tid & 7) * 8;
@@ -618,8 +621,9 @@ __global__ void __launch_bounds__(256) gather_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_GATHER, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
-  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
+  if (idx >= (int64_t)batch * d.Ho * d.Wo * d.Cop) return;
   const int c = (int)(idx % d.Cop);
   const int64_t m = idx / d.Cop;
   const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
@@ -644,10 +648,11 @@ __global__ void __launch_bounds__(256) concat_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_CONCAT, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   const TA* xa = reinterpret_cast<const TA*>(a.abase + d.x_off);
   const TA* xb = reinterpret_cast<const TA*>(a.abase + d.r_off);
-  const int64_t M = (int64_t)a.batch * d.Ho * d.Wo;
+  const int64_t M = (int64_t)batch * d.Ho * d.Wo;
   if (sizeof(TA) == 2 && d.vec) {  // C % 8 == 0: an 8-channel vector never straddles the two sources
     const int cv = d.Cop / 8;
     if (idx >= M * cv) return;
@@ -680,8 +685,9 @@ __global__ void __launch_bounds__(256) dwconv_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_DWCONV, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
-  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
+  if (idx >= (int64_t)batch * d.Ho * d.Wo * d.Cop) return;
   const int c = (int)(idx % d.Cop);
   const int64_t m = idx / d.Cop;
   const int q = (int)(m % d.Wo);
@@ -724,11 +730,12 @@ __global__ void __launch_bounds__(256) pool_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, AVG ? K_AVGPOOL : K_MAXPOOL, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
   if (sizeof(TA) == 2 && d.vec) {
     const int cv = d.Cp / 8;
-    if (idx >= (int64_t)a.batch * d.Ho * d.Wo * cv) return;
+    if (idx >= (int64_t)batch * d.Ho * d.Wo * cv) return;
     const int c8 = (int)(idx % cv) * 8;
     const int64_t m = idx / cv;
     const int q = (int)(m % d.Wo);
@@ -769,7 +776,7 @@ __global__ void __launch_bounds__(256) pool_kernel(KArgs a) {
     *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.Cop + c8) = o;
     return;
   }
-  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * d.Cop) return;
+  if (idx >= (int64_t)batch * d.Ho * d.Wo * d.Cop) return;
   const int c = (int)(idx % d.Cop);
   const int64_t m = idx / d.Cop;
   const int q = (int)(m % d.Wo);
@@ -802,8 +809,9 @@ __global__ void __launch_bounds__(256) gap_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_GAP, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int idx = bid * 256 + threadIdx.x;
-  if (idx >= a.batch * d.Cop) return;
+  if (idx >= batch * d.Cop) return;
   const int c = idx % d.Cop, n = idx / d.Cop;
   const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c;
   float sum = 0.0f;
@@ -872,13 +880,14 @@ __global__ void __launch_bounds__(256) mul_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_MUL, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
   const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off);
   const TA* g = reinterpret_cast<const TA*>(a.abase + d.r_off);
   const int64_t HW = (int64_t)d.Ho * d.Wo;
   if (sizeof(TA) == 2 && d.vec) {
     const int cv = d.Cop / 8;
-    if (idx >= (int64_t)a.batch * HW * cv) return;
+    if (idx >= (int64_t)batch * HW * cv) return;
     const int c8 = (int)(idx % cv) * 8;
     const int64_t m = idx / cv;
     float xv[8], gv[8];
@@ -889,7 +898,7 @@ __global__ void __launch_bounds__(256) mul_kernel(KArgs a) {
     store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c8, xv);
     return;
   }
-  if (idx >= (int64_t)a.batch * HW * d.Cop) return;
+  if (idx >= (int64_t)batch * HW * d.Cop) return;
   const int c = (int)(idx % d.Cop);
   const int64_t m = idx / d.Cop;
   const float v = c < d.Co ? ld(x + m * d.Cp + c) * ld(g + (m / HW) * d.Cp + c) : 0.0f;
@@ -910,9 +919,10 @@ __global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_DWCONV, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int cv = d.Cop / 8;
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
-  if (idx >= (int64_t)a.batch * d.Ho * d.Wo * cv) return;
+  if (idx >= (int64_t)batch * d.Ho * d.Wo * cv) return;
   const int c8 = (int)(idx % cv) * 8;
   const int64_t m = idx / cv;
   const int q = (int)(m % d.Wo);
@@ -967,9 +977,10 @@ __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_GAP, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int cv = d.Cop / 8;
   const int idx = bid * 256 + threadIdx.x;
-  if (idx >= a.batch * cv) return;
+  if (idx >= batch * cv) return;
   const int c8 = (idx % cv) * 8, n = idx / cv;
   const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c8;
   float sum[8];
@@ -1012,10 +1023,11 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_FC, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int lane = threadIdx.x & 63;
   int unit = bid * 4 + (threadIdx.x >> 6);
   const int per_chunk = d.tiles_n * d.splits;
-  if (unit >= per_chunk * ((a.batch + 31) / 32)) return;
+  if (unit >= per_chunk * ((batch + 31) / 32)) return;
   const int chunk = unit / per_chunk;   // which 32 images
   unit -= chunk * per_chunk;
   const int tile = unit % d.tiles_n, split = unit / d.tiles_n;
@@ -1026,7 +1038,7 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
   // block (tile, step) of the packed matrix is 64 x 16 bytes in lane order
   const uint4* wp = reinterpret_cast<const uint4*>(a.wbase + d.w_off) + (int64_t)tile * steps * 64 + lane;
   const int n = chunk * 32 + (lane & 31);
-  const bool nok = n < a.batch;
+  const bool nok = n < batch;
   const int K = d.Cp;  // flattened input length (elements), a multiple of 8
   f32x16 acc;
 #pragma unroll
@@ -1076,7 +1088,7 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
   }
   // partial block: lane holds batch column n, features 8*g + 4*(lane/32) + t
   if (nok) {
-    float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * a.batch + n) * d.Cop + tile * 32;
+    float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * batch + n) * d.Cop + tile * 32;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int fo = 8 * g + 4 * (lane >> 5);
@@ -1093,8 +1105,9 @@ __global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
   int p, bid;
   if (!find_problem(a, K_REDUCE, 0, p, bid)) return;
   const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int q4 = d.Cop / 4;
-  const int rows = a.batch * d.Ho * d.Wo;
+  const int rows = batch * d.Ho * d.Wo;
   const int idx = bid * 256 + threadIdx.x;
   if (idx >= rows * q4) return;
   const int o = (idx % q4) * 4, n = idx / q4;
@@ -1144,7 +1157,7 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
   int64_t blocks = 0;
   for (int i = 0; i < FI_MAX_GROUP + 1; ++i) {
     a.first_block[i] = (int32_t)blocks;
-    if (i < L.n) blocks += problem_blocks(L.kind, L.tile, hd[(size_t)(L.first_desc + i)], a.batch);
+    if (i < L.n) blocks += problem_blocks(L.kind, L.tile, hd[(size_t)(L.first_desc + i)], a.batch[i]);
     if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
   }
   const bool wb = L.wdtype == FI_BF16, ab = L.adtype == FI_BF16;

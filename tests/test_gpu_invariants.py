@@ -280,3 +280,47 @@ def test_members_that_stage_the_input_differently():
         for i, (m, b, y) in enumerate(zip(models, blobs, ys)):
             ref = harness.oracle_nhwc(m, b, x, False)
             assert harness.rel_l2(y, ref) <= (1e-4 if i == 2 else 1e-2), (order, i)
+
+
+def test_per_member_batches():
+    """The manager aggregates requests per model, so members arrive at a pass with different numbers of images:
+    member m on batches[m] images gives, bit for bit, what the same DAG gives for those images at the full
+    batch; a member with no image sits the pass out and its output buffer is not touched."""
+    import torch
+    import paper_2410_21120_amd as fi
+    mem = _members()
+    B = 5
+    xs = [gen.make_input(80 + i, B, 3, 64, 64, "normal", "bf16") for i in range(len(mem))]
+    specs, keep = [], []
+    for m, blob, act in mem:
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        specs.append(sp)
+        keep.append((k, blob))
+    dag = fi.Dag(specs, B, fi.TorchAllocators("cuda:0"), keepalive=keep, per_member_inputs=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    dag.load(stream)
+    try:
+        dev_in = [torch.from_numpy(gen.to_nhwc_storage(x, "bf16").view(np.int16)).cuda() for x in xs]
+        full = [torch.full((B, 1000), float("nan"), dtype=torch.float32, device="cuda:0") for _ in mem]
+        dag.run_inputs([t.data_ptr() for t in dev_in], B, [o.data_ptr() for o in full], stream)
+        torch.cuda.synchronize()
+        full = [o.cpu().numpy() for o in full]
+        for batches in ([5, 1, 0, 3, 2], [0, 0, 4, 0, 0], [1, 5, 5, 0, 5]):
+            outs = [torch.full((B, 1000), -7.0, dtype=torch.float32, device="cuda:0") for _ in mem]
+            ins = [t.data_ptr() if b else 0 for t, b in zip(dev_in, batches)]
+            ops = [o.data_ptr() if b else 0 for o, b in zip(outs, batches)]
+            dag.run_batches(ins, batches, ops, stream)
+            torch.cuda.synchronize()
+            for i, (o, b) in enumerate(zip(outs, batches)):
+                y = o.cpu().numpy()
+                assert np.array_equal(y[:b], full[i][:b]), (batches, i)
+                assert np.all(y[b:] == -7.0), (batches, i)   # rows past the member's batch stay as they were
+        with pytest.raises(fi.FiError) as e:
+            dag.run_batches([t.data_ptr() for t in dev_in], [B + 1, 1, 1, 1, 1], [o.data_ptr() for o in outs], stream)
+        assert e.value.status == fi.FI_EINVAL
+        with pytest.raises(fi.FiError) as e:
+            dag.run_batches([0] + [t.data_ptr() for t in dev_in[1:]], [1, 1, 1, 1, 1], [o.data_ptr() for o in outs], stream)
+        assert e.value.status == fi.FI_EINVAL
+    finally:
+        dag.unload()
+        dag.destroy()
