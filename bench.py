@@ -242,6 +242,7 @@ def main():
             d.unload()
             d.destroy()
         res["swap"] = swap_churn(fi, torch, gen, zoo, alloc, stream, a.swap_requests)
+        res["serving"] = serving(fi, torch, gen, zoo, alloc, stream)
         res["cpu_baseline"] = cpu_baseline(members[0], x, len(members))
     print(json.dumps(res))
 
@@ -278,6 +279,75 @@ def counter_traffic(kernel, workload):
     return dict(bytes_per_launch=per_launch, fetch_bytes_per_launch=c["fetch_kib_per_step"] * c["fetch_scale"] * 1024.0 / c["launches_per_step"],
                 write_bytes_per_launch=c["write_kib_per_step"] * c["write_scale"] * 1024.0 / c["launches_per_step"],
                 source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy probe")
+
+
+def serving(fi, torch, gen, zoo, alloc, stream, seconds=1.0):
+    """Request aggregation (Section IV, Manager): single-image requests for four resident models arrive as a
+    seeded Poisson stream; the library's server gathers, per model, what arrived while the device was busy into
+    the next pass.  Open loop at several rates, against the capacity of serving every request in a pass of its
+    own."""
+    import numpy as np
+    fams = ["resnet18", "resnet50", "mobilenetv2", "vgg16"]
+    B = 8
+    specs, keep = [], []
+    for i, fam in enumerate(fams):
+        m = zoo.FAMILIES[fam]()
+        blob = gen.make_blob(m, 1000 + i)
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype="f32" if fam in WIDE else None)
+        specs.append(sp)
+        keep.append((k, blob))
+    dag = fi.Dag(specs, B, alloc, keepalive=keep, per_member_inputs=True)
+    dag.load(stream)
+    imgs = [torch.from_numpy(gen.to_nhwc_storage(gen.make_input(70 + j, 1, 3, 224, 224, "normal", "bf16"), "bf16").view(np.int16)).cuda() for j in range(4)]
+    n = len(fams)
+    one = torch.zeros((1, 1000), dtype=torch.float32, device="cuda:0")
+    torch.cuda.synchronize()
+    # capacity without aggregation: every request is a pass of its own (one member, one image)
+    alone_ms = []
+    for m in range(n):
+        ins = [imgs[0].data_ptr() if k == m else 0 for k in range(n)]
+        outs = [one.data_ptr() if k == m else 0 for k in range(n)]
+        nb = [1 if k == m else 0 for k in range(n)]
+        for _ in range(3):
+            dag.run_batches(ins, nb, outs, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            dag.run_batches(ins, nb, outs, stream)
+        torch.cuda.synchronize()
+        alone_ms.append((time.perf_counter() - t0) * 1e3 / 20)
+    out = dict(models=fams, max_batch=B, one_request_per_pass_ms=[round(v, 4) for v in alone_ms],
+               one_request_per_pass_capacity_rps=1e3 / (sum(alone_ms) / n), rates=[])
+    rng = np.random.default_rng(2024)
+    for rate in (1000.0, 4000.0, 16000.0):
+        n_req = int(rate * seconds)
+        gaps = rng.exponential(1.0 / rate, n_req)
+        who = rng.integers(0, n, n_req)
+        outs = torch.zeros((n_req, 1000), dtype=torch.float32, device="cuda:0")
+        base, row = outs.data_ptr(), 4000
+        torch.cuda.synchronize()
+        srv = fi.Server(dag)
+        tickets = []
+        t0 = time.perf_counter()
+        due = 0.0
+        for r in range(n_req):
+            due += gaps[r]
+            while time.perf_counter() - t0 < due:   # open loop: arrivals do not wait for the server
+                pass
+            tickets.append(srv.submit(int(who[r]), imgs[r & 3].data_ptr(), base + r * row))
+        t_sub = time.perf_counter() - t0
+        srv.wait(tickets[-1])
+        for t in tickets[-64:]:
+            srv.wait(t)
+        t_all = time.perf_counter() - t0
+        st = srv.stats()
+        srv.stop()
+        out["rates"].append(dict(offered_rps=rate, submitted_rps=n_req / t_sub, served_rps=n_req / t_all, requests=n_req, passes=int(st.passes),
+                                 mean_images_per_pass=st.mean_images_per_pass, max_images_per_pass=int(st.max_images_per_pass),
+                                 mean_latency_ms=st.mean_latency_ms, max_latency_ms=st.max_latency_ms, device_busy_frac=st.busy_ms / (t_all * 1e3)))
+    dag.unload()
+    dag.destroy()
+    return out
 
 
 def swap_churn(fi, torch, gen, zoo, alloc, stream, n_req):

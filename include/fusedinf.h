@@ -317,6 +317,45 @@ fi_status fi_round_robin(const fi_model_spec* models, int32_t n, const fi_build_
                          int32_t n_groups, const fi_sched_opts* sched, const void* d_input, int32_t batch,
                          void* const* d_outputs, void* hip_stream, fi_sched_stats* stats);
 
+/* ---- request aggregation (Section IV, "Manager": requests that arrive while the device
+ * is busy are gathered per model into the next batch) ----
+ * A server sits in front of a LOADED DAG built with per_member_inputs = 1.  Callers submit
+ * single images for single members; one worker thread (with a stream of its own) repeatedly
+ * takes up to max_batch waiting requests of every member, runs ONE fi_run_batches pass over
+ * the whole DAG and hands every request its output row.  The busier the device, the larger
+ * the batches.  While a server runs, nothing else may use the DAG. */
+typedef struct fi_server fi_server; /* opaque, owned by the library */
+
+typedef struct {
+  int32_t max_wait_us; /* when a request finds the server idle, wait this long for companions before
+                          the pass starts (0 = start at once) */
+  int32_t reserved;
+} fi_server_opts;
+
+typedef struct {
+  uint64_t requests, passes;    /* requests served; fi_run_batches passes issued */
+  uint64_t max_images_per_pass; /* most requests one pass carried (all members together) */
+  double mean_images_per_pass;
+  double mean_latency_ms, max_latency_ms; /* submit to output written, host clock */
+  double busy_ms;               /* time with a pass in flight */
+} fi_server_stats;
+
+/* Allocates, through the DAG's allocator callbacks, one batch buffer of max_batch images and one of
+ * max_batch output rows per member, and starts the worker on the current device.  opts may be NULL.
+ * FI_ESTATE unless the DAG is LOADED and was built with per_member_inputs = 1. */
+fi_status fi_server_start(fi_dag* dag, const fi_server_opts* opts, fi_server** out);
+/* Queues one image for member `member`.  d_image: device, [in_h, in_w, in_c] in the weight dtype,
+ * complete in memory before the call and untouched until fi_server_wait returns; d_output: device,
+ * receives the member's output row (fp32, classes_m values).  Requests of one member are served in
+ * order.  Thread-safe.  ticket: out, never 0. */
+fi_status fi_server_submit(fi_server* srv, int32_t member, const void* d_image, void* d_output, uint64_t* ticket);
+/* Blocks until the request's output is in d_output (the copy has completed).  Thread-safe.  Reports
+ * the worker's error, if it met one, on this and every later call. */
+fi_status fi_server_wait(fi_server* srv, uint64_t ticket);
+fi_status fi_server_query(fi_server* srv, fi_server_stats* stats);
+/* Serves what is queued, joins the worker, releases the buffers and the handle; the DAG stays LOADED. */
+fi_status fi_server_stop(fi_server* srv);
+
 /* Synchronise, release the device allocation; the handle returns to BUILT. */
 fi_status fi_unload(fi_dag* dag);
 void fi_destroy(fi_dag* dag); /* unloads if needed; NULL is allowed */

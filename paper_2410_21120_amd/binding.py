@@ -69,6 +69,16 @@ class fi_sched_stats(C.Structure):
                 ("n_groups", C.c_int32), ("reserved", C.c_int32)]
 
 
+class fi_server_opts(C.Structure):
+    _fields_ = [("max_wait_us", C.c_int32), ("reserved", C.c_int32)]
+
+
+class fi_server_stats(C.Structure):
+    _fields_ = [("requests", C.c_uint64), ("passes", C.c_uint64), ("max_images_per_pass", C.c_uint64),
+                ("mean_images_per_pass", C.c_double), ("mean_latency_ms", C.c_double), ("max_latency_ms", C.c_double),
+                ("busy_ms", C.c_double)]
+
+
 class fi_member_info(C.Structure):
     _fields_ = [("arena_off", C.c_uint64), ("packed_bytes", C.c_uint64), ("lane", C.c_int32),
                 ("first_node", C.c_int32), ("n_nodes", C.c_int32), ("reserved", C.c_int32)]
@@ -90,7 +100,8 @@ class fi_launch_info(C.Structure):
 
 LIB_PATH = _build.OUT
 EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_footprint", "fi_partition", "fi_round_robin", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
-           "fi_run", "fi_run_inputs", "fi_run_batches", "fi_profile", "fi_timeline", "fi_swap_model", "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
+           "fi_run", "fi_run_inputs", "fi_run_batches", "fi_profile", "fi_timeline", "fi_swap_model", "fi_server_start", "fi_server_submit", "fi_server_wait", "fi_server_query", "fi_server_stop",
+           "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
 
@@ -124,6 +135,11 @@ def lib():
                                      C.POINTER(fi_sched_opts), vp, i32, C.POINTER(vp), vp, C.POINTER(fi_sched_stats)]
         L.fi_swap_model.argtypes = [vp, i32, C.POINTER(fi_model_spec), vp]
         L.fi_member.argtypes = [vp, i32, C.POINTER(fi_member_info)]
+        L.fi_server_start.argtypes = [vp, C.POINTER(fi_server_opts), C.POINTER(vp)]
+        L.fi_server_submit.argtypes = [vp, i32, vp, vp, C.POINTER(u64)]
+        L.fi_server_wait.argtypes = [vp, u64]
+        L.fi_server_query.argtypes = [vp, C.POINTER(fi_server_stats)]
+        L.fi_server_stop.argtypes = [vp]
         L.fi_unload.argtypes = [vp]
         L.fi_destroy.argtypes = [vp]
         L.fi_destroy.restype = None
@@ -375,6 +391,35 @@ class TorchAllocators:
     def apply(self, opts: fi_build_opts):
         opts.dev_alloc, opts.dev_free, opts.pin_alloc, opts.pin_free = self.cb
         return opts
+
+
+class Server:
+    """Request aggregator in front of a loaded Dag built with per_member_inputs (argument marshalling only)."""
+
+    def __init__(self, dag, max_wait_us=0):
+        h = C.c_void_p()
+        opts = fi_server_opts(max_wait_us, 0)
+        _check(lib().fi_server_start(dag.h, C.byref(opts), C.byref(h)), "fi_server_start")
+        self.h = h
+        self.dag = dag   # the DAG must outlive the server
+
+    def submit(self, member, d_image_ptr, d_output_ptr) -> int:
+        t = C.c_uint64()
+        _check(lib().fi_server_submit(self.h, member, C.c_void_p(d_image_ptr), C.c_void_p(d_output_ptr), C.byref(t)), "fi_server_submit")
+        return t.value
+
+    def wait(self, ticket) -> None:
+        _check(lib().fi_server_wait(self.h, ticket), "fi_server_wait")
+
+    def stats(self) -> fi_server_stats:
+        st = fi_server_stats()
+        _check(lib().fi_server_query(self.h, C.byref(st)), "fi_server_query")
+        return st
+
+    def stop(self) -> None:
+        if self.h:
+            h, self.h = self.h, None
+            _check(lib().fi_server_stop(h), "fi_server_stop")
 
 
 class Dag:

@@ -952,3 +952,18 @@ void fi_destroy(fi_dag* g) {
 }
 
 }  // extern "C"
+
+namespace fi {
+void serving_info(const fi_dag* g, ServingInfo* out) {
+  out->n_models = (int32_t)g->members.size();
+  out->max_batch = g->opts.max_batch;
+  out->per_member_inputs = g->opts.per_member_inputs;
+  out->state = g->state;
+  const fi_model_spec& m0 = g->members[0].spec;
+  out->image_bytes = (uint64_t)m0.in_h * m0.in_w * m0.in_c * esize(m0.dtype);
+  out->out_bytes.assign(g->members.size(), 0);
+  for (const Node& nd : g->nodes)
+    if (nd.is_output) out->out_bytes[(size_t)nd.model] = (uint64_t)nd.Ho * nd.Wo * nd.Co * 4;
+  out->opts = g->opts;
+}
+}  // namespace fi

@@ -120,6 +120,15 @@ struct KArgs {
   Desc d[FI_MAX_GROUP];          // the launch's problems: read through the scalar cache, no memory round trip
 };
 
+// What the request aggregator needs to know about a handle (filled by serving_info in fi_api.cpp).
+struct ServingInfo {
+  int32_t n_models = 0, max_batch = 0, per_member_inputs = 0, state = 0;
+  uint64_t image_bytes = 0;                 // one input image [in_h, in_w, in_c] in the weight dtype
+  std::vector<uint64_t> out_bytes;          // one output row of every member (fp32)
+  fi_build_opts opts{};                     // allocator callbacks
+};
+void serving_info(const fi_dag* dag, ServingInfo* out);
+
 void set_error(const char* fmt, ...);
 fi_status analyze_model(const fi_model_spec& m, ModelPlan& out);
 void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst);

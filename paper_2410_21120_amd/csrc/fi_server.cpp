@@ -1,0 +1,228 @@
+// Request aggregation in front of a loaded DAG (Section IV, "Manager": requests for the member models
+// arrive one by one; those that arrive while the device is busy are gathered, per model, into the batch of the
+// next pass).  One worker thread owns a stream of its own: it takes up to max_batch waiting requests of
+// every member, copies their images into the members' batch buffers, runs ONE fi_run_batches pass over the
+// whole DAG, copies every output row to its request's buffer and wakes the waiters.  While that pass is in
+// flight new requests queue up: the busier the device, the larger the batches.  Host logic only: every
+// device step is a copy or the public fi_run_batches.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <condition_variable>
+#include <deque>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <unordered_set>
+#include <vector>
+
+#include "fi_internal.h"
+
+using namespace fi;
+
+namespace {
+
+double now_ms() {
+  using clk = std::chrono::steady_clock;
+  return std::chrono::duration<double, std::milli>(clk::now().time_since_epoch()).count();
+}
+
+struct Request {
+  uint64_t ticket;
+  const void* d_image;
+  void* d_output;
+  double t_submit;
+};
+
+}  // namespace
+
+struct fi_server {
+  fi_dag* dag = nullptr;
+  ServingInfo info;
+  fi_server_opts opts{};
+  int device = 0;
+  hipStream_t stream = nullptr;
+  std::vector<uint8_t*> in_buf, out_buf;    // per member: max_batch images / max_batch output rows (device)
+  std::thread worker;
+  std::mutex mu;
+  std::condition_variable cv_work, cv_done;
+  std::vector<std::deque<Request>> queue;   // per member, first in first out
+  std::unordered_set<uint64_t> pending;     // tickets submitted and not yet served
+  uint64_t next_ticket = 1;
+  size_t waiting = 0;                       // requests in the queues
+  bool stopping = false;
+  fi_status failed = FI_OK;                 // first error of the worker; every later wait reports it
+  std::string failure;
+  // statistics (under mu)
+  uint64_t n_requests = 0, n_passes = 0, max_images = 0;
+  double sum_latency_ms = 0.0, max_latency_ms = 0.0, busy_ms = 0.0;
+
+  void* dev_alloc(size_t n) const {
+    if (info.opts.dev_alloc) return info.opts.dev_alloc(n, info.opts.user);
+    void* p = nullptr;
+    if (hipMalloc(&p, n) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    return p;
+  }
+  void dev_free(void* p) const {
+    if (!p) return;
+    if (info.opts.dev_free) info.opts.dev_free(p, info.opts.user); else (void)hipFree(p);
+  }
+  void release() {
+    for (uint8_t* p : in_buf) dev_free(p);
+    for (uint8_t* p : out_buf) dev_free(p);
+    in_buf.clear(); out_buf.clear();
+    if (stream) { (void)hipStreamDestroy(stream); stream = nullptr; }
+  }
+  void fail(fi_status st, const std::string& why) {   // under mu
+    if (failed == FI_OK) { failed = st; failure = why; }
+  }
+  void serve();
+};
+
+void fi_server::serve() {
+  (void)hipSetDevice(device);
+  const int32_t n = info.n_models;
+  std::vector<std::vector<Request>> take((size_t)n);
+  std::vector<const void*> ins((size_t)n);
+  std::vector<void*> outs((size_t)n);
+  std::vector<int32_t> batches((size_t)n);
+  for (;;) {
+    {
+      std::unique_lock<std::mutex> lk(mu);
+      cv_work.wait(lk, [&] { return waiting > 0 || stopping; });
+      if (waiting == 0 && stopping) return;
+      if (opts.max_wait_us > 0 && !stopping) {
+        // a first request after an idle period: give its companions a moment to arrive
+        const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(opts.max_wait_us);
+        cv_work.wait_until(lk, until, [&] { return stopping || waiting >= (size_t)n * (size_t)info.max_batch; });
+      }
+      for (int32_t m = 0; m < n; ++m) {
+        take[(size_t)m].clear();
+        std::deque<Request>& q = queue[(size_t)m];
+        while (!q.empty() && (int32_t)take[(size_t)m].size() < info.max_batch) { take[(size_t)m].push_back(q.front()); q.pop_front(); --waiting; }
+      }
+    }
+    const double t0 = now_ms();
+    hipError_t e = hipSuccess;
+    uint64_t images = 0;
+    for (int32_t m = 0; m < n && e == hipSuccess; ++m) {
+      batches[(size_t)m] = (int32_t)take[(size_t)m].size();
+      ins[(size_t)m] = in_buf[(size_t)m];
+      outs[(size_t)m] = out_buf[(size_t)m];
+      images += take[(size_t)m].size();
+      for (size_t i = 0; i < take[(size_t)m].size() && e == hipSuccess; ++i)
+        e = hipMemcpyAsync(in_buf[(size_t)m] + i * info.image_bytes, take[(size_t)m][i].d_image, (size_t)info.image_bytes, hipMemcpyDeviceToDevice, stream);
+    }
+    fi_status st = e == hipSuccess ? fi_run_batches(dag, ins.data(), batches.data(), outs.data(), stream) : FI_EHIP;
+    std::string why = st != FI_OK ? (e != hipSuccess ? std::string("hipMemcpyAsync: ") + hipGetErrorString(e) : std::string(fi_last_error())) : std::string();
+    for (int32_t m = 0; m < n && st == FI_OK; ++m)
+      for (size_t i = 0; i < take[(size_t)m].size(); ++i) {
+        e = hipMemcpyAsync(take[(size_t)m][i].d_output, out_buf[(size_t)m] + i * info.out_bytes[(size_t)m], (size_t)info.out_bytes[(size_t)m], hipMemcpyDeviceToDevice, stream);
+        if (e != hipSuccess) { st = FI_EHIP; why = std::string("hipMemcpyAsync: ") + hipGetErrorString(e); break; }
+      }
+    e = hipStreamSynchronize(stream);
+    if (e != hipSuccess && st == FI_OK) { st = FI_EHIP; why = std::string("hipStreamSynchronize: ") + hipGetErrorString(e); }
+    const double t1 = now_ms();
+    {
+      std::lock_guard<std::mutex> lk(mu);
+      if (st != FI_OK) fail(st, why);
+      for (int32_t m = 0; m < n; ++m)
+        for (const Request& r : take[(size_t)m]) {
+          pending.erase(r.ticket);
+          const double lat = t1 - r.t_submit;
+          sum_latency_ms += lat;
+          if (lat > max_latency_ms) max_latency_ms = lat;
+          ++n_requests;
+        }
+      ++n_passes;
+      if (images > max_images) max_images = images;
+      busy_ms += t1 - t0;
+    }
+    cv_done.notify_all();
+  }
+}
+
+extern "C" {
+
+fi_status fi_server_start(fi_dag* dag, const fi_server_opts* opts, fi_server** out) {
+  if (!dag || !out) { set_error("null argument"); return FI_EINVAL; }
+  if (opts && opts->max_wait_us < 0) { set_error("max_wait_us must be >= 0"); return FI_EINVAL; }
+  fi_server* s = new (std::nothrow) fi_server;
+  if (!s) { set_error("out of host memory"); return FI_ENOMEM_HOST; }
+  s->dag = dag;
+  serving_info(dag, &s->info);
+  if (opts) s->opts = *opts;
+  if (s->info.state != 1) { set_error("fi_server_start: the DAG is not loaded"); delete s; return FI_ESTATE; }
+  if (!s->info.per_member_inputs) { set_error("fi_server_start: the DAG was not built with per_member_inputs"); delete s; return FI_ESTATE; }
+  if (hipGetDevice(&s->device) != hipSuccess || hipStreamCreateWithFlags(&s->stream, hipStreamNonBlocking) != hipSuccess) {
+    (void)hipGetLastError();
+    set_error("fi_server_start: no stream"); delete s; return FI_EHIP; }
+  const size_t n = (size_t)s->info.n_models;
+  s->queue.resize(n);
+  for (size_t m = 0; m < n; ++m) {
+    uint8_t* in = static_cast<uint8_t*>(s->dev_alloc((size_t)(s->info.image_bytes * (uint64_t)s->info.max_batch)));
+    uint8_t* ob = static_cast<uint8_t*>(s->dev_alloc((size_t)(s->info.out_bytes[m] * (uint64_t)s->info.max_batch)));
+    s->in_buf.push_back(in);
+    s->out_buf.push_back(ob);
+    if (!in || !ob) { set_error("fi_server_start: device allocation failed"); s->release(); delete s; return FI_ENOMEM_DEVICE; }
+  }
+  s->worker = std::thread([s] { s->serve(); });
+  *out = s;
+  return FI_OK;
+}
+
+fi_status fi_server_submit(fi_server* s, int32_t member, const void* d_image, void* d_output, uint64_t* ticket) {
+  if (!s || !d_image || !d_output || !ticket) { set_error("null argument"); return FI_EINVAL; }
+  if (member < 0 || member >= s->info.n_models) { set_error("member %d outside [0, %d)", member, s->info.n_models); return FI_EINVAL; }
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    if (s->stopping) { set_error("fi_server_submit: the server is stopping"); return FI_ESTATE; }
+    if (s->failed != FI_OK) { set_error("server failed: %s", s->failure.c_str()); return s->failed; }
+    const uint64_t t = s->next_ticket++;
+    s->queue[(size_t)member].push_back(Request{t, d_image, d_output, now_ms()});
+    s->pending.insert(t);
+    ++s->waiting;
+    *ticket = t;
+  }
+  s->cv_work.notify_one();
+  return FI_OK;
+}
+
+fi_status fi_server_wait(fi_server* s, uint64_t ticket) {
+  if (!s) { set_error("null server"); return FI_EINVAL; }
+  std::unique_lock<std::mutex> lk(s->mu);
+  if (ticket == 0 || ticket >= s->next_ticket) { set_error("unknown ticket %llu", (unsigned long long)ticket); return FI_EINVAL; }
+  s->cv_done.wait(lk, [&] { return s->pending.count(ticket) == 0; });
+  if (s->failed != FI_OK) { set_error("server failed: %s", s->failure.c_str()); return s->failed; }
+  return FI_OK;
+}
+
+fi_status fi_server_query(fi_server* s, fi_server_stats* st) {
+  if (!s || !st) { set_error("null argument"); return FI_EINVAL; }
+  std::lock_guard<std::mutex> lk(s->mu);
+  st->requests = s->n_requests;
+  st->passes = s->n_passes;
+  st->max_images_per_pass = s->max_images;
+  st->mean_images_per_pass = s->n_passes ? (double)s->n_requests / (double)s->n_passes : 0.0;
+  st->mean_latency_ms = s->n_requests ? s->sum_latency_ms / (double)s->n_requests : 0.0;
+  st->max_latency_ms = s->max_latency_ms;
+  st->busy_ms = s->busy_ms;
+  return FI_OK;
+}
+
+fi_status fi_server_stop(fi_server* s) {
+  if (!s) { set_error("null server"); return FI_EINVAL; }
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    s->stopping = true;
+  }
+  s->cv_work.notify_all();
+  if (s->worker.joinable()) s->worker.join();
+  const fi_status st = s->failed;
+  if (st != FI_OK) set_error("server failed: %s", s->failure.c_str());
+  s->release();
+  delete s;
+  return st;
+}
+
+}  // extern "C"

@@ -1,0 +1,147 @@
+"""The request aggregator (Section IV, "Manager": requests that arrive while the device is busy are gathered per
+model into the next batch): every request's output equals, bit for bit, the member run on that image alone; a
+burst of requests is served in fewer passes than requests."""
+import threading
+
+import numpy as np
+import pytest
+
+from workloads import gen, zoo
+
+pytestmark = pytest.mark.gpu
+
+
+def _dag(max_batch, hw=64):
+    import torch
+    import paper_2410_21120_amd as fi
+    fams = [("resnet18", None), ("mobilenetv2", "f32"), ("resnet18", None), ("vgg11", None)]
+    specs, keep, models = [], [], []
+    for i, (f, act) in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=hw)
+        blob = gen.make_blob(m, 3000 + i)
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        specs.append(sp)
+        keep.append((k, blob))
+        models.append(m)
+    dag = fi.Dag(specs, max_batch, fi.TorchAllocators("cuda:0"), keepalive=keep, per_member_inputs=True)
+    dag.load(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return dag, models
+
+
+def test_every_request_gets_its_member_alone_output():
+    import torch
+    import paper_2410_21120_amd as fi
+    B, hw, n_img = 4, 64, 6
+    dag, models = _dag(B, hw)
+    n = len(models)
+    stream = torch.cuda.current_stream().cuda_stream
+    try:
+        imgs = [torch.from_numpy(gen.to_nhwc_storage(gen.make_input(500 + j, 1, 3, hw, hw, "normal", "bf16"), "bf16").view(np.int16)).cuda() for j in range(n_img)]
+        # expected: member m on image j alone in a pass (an image's bits do not depend on its batch)
+        expect = {}
+        for m in range(n):
+            for j in range(n_img):
+                o = torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda:0")
+                ins = [imgs[j].data_ptr() if k == m else 0 for k in range(n)]
+                dag.run_batches(ins, [1 if k == m else 0 for k in range(n)], [o.data_ptr() if k == m else 0 for k in range(n)], stream)
+                torch.cuda.synchronize()
+                expect[(m, j)] = o.cpu().numpy()[0]
+        srv = fi.Server(dag)
+        try:
+            # a burst from two threads: 60 requests, members and images interleaved
+            reqs = [(r % n, (r * 7) % n_img) for r in range(60)]
+            outs = [torch.full((1000,), float("nan"), dtype=torch.float32, device="cuda:0") for _ in reqs]
+            torch.cuda.synchronize()
+            tickets = [None] * len(reqs)
+
+            def feed(lo, hi):
+                for r in range(lo, hi):
+                    m, j = reqs[r]
+                    tickets[r] = srv.submit(m, imgs[j].data_ptr(), outs[r].data_ptr())
+            th = [threading.Thread(target=feed, args=(0, 30)), threading.Thread(target=feed, args=(30, 60))]
+            for t in th:
+                t.start()
+            for t in th:
+                t.join()
+            for r in reversed(range(len(reqs))):   # waiting out of order is fine
+                srv.wait(tickets[r])
+            for r, (m, j) in enumerate(reqs):
+                assert np.array_equal(outs[r].cpu().numpy(), expect[(m, j)]), (r, m, j)
+            st = srv.stats()
+            assert st.requests == 60 and 60 / (n * B) <= st.passes < 60, (st.requests, st.passes)
+            assert st.max_images_per_pass <= n * B and st.mean_images_per_pass > 1.0
+            assert st.mean_latency_ms > 0 and st.max_latency_ms >= st.mean_latency_ms
+            # argument errors
+            with pytest.raises(fi.FiError) as e:
+                srv.submit(n, imgs[0].data_ptr(), outs[0].data_ptr())
+            assert e.value.status == fi.FI_EINVAL
+            with pytest.raises(fi.FiError) as e:
+                srv.wait(10 ** 9)
+            assert e.value.status == fi.FI_EINVAL
+            # a lone request after the burst: served by itself
+            t = srv.submit(1, imgs[2].data_ptr(), outs[0].data_ptr())
+            srv.wait(t)
+            assert np.array_equal(outs[0].cpu().numpy(), expect[(1, 2)])
+        finally:
+            srv.stop()
+        # the DAG is still loaded and usable after the server has gone
+        o = torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda:0")
+        dag.run_batches([imgs[0].data_ptr(), 0, 0, 0], [1, 0, 0, 0], [o.data_ptr(), 0, 0, 0], stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(o.cpu().numpy()[0], expect[(0, 0)])
+    finally:
+        dag.unload()
+        dag.destroy()
+
+
+def test_waiting_for_companions_fills_the_batches():
+    """With a waiting window, requests that trickle in are still served together."""
+    import time
+    import torch
+    import paper_2410_21120_amd as fi
+    B, hw = 4, 64
+    dag, models = _dag(B, hw)
+    n = len(models)
+    try:
+        img = torch.from_numpy(gen.to_nhwc_storage(gen.make_input(9, 1, 3, hw, hw, "normal", "bf16"), "bf16").view(np.int16)).cuda()
+        outs = [torch.zeros((1000,), dtype=torch.float32, device="cuda:0") for _ in range(n * B)]
+        torch.cuda.synchronize()
+        srv = fi.Server(dag, max_wait_us=200000)
+        try:
+            tickets = []
+            for r in range(n * B):
+                tickets.append(srv.submit(r % n, img.data_ptr(), outs[r].data_ptr()))
+                time.sleep(0.001)
+            for t in tickets:
+                srv.wait(t)
+            st = srv.stats()
+            assert st.requests == n * B and st.passes <= 2, (st.requests, st.passes)   # the window closes early once every batch is full
+            ref = [outs[m].cpu().numpy() for m in range(n)]
+            for r in range(n * B):
+                assert np.array_equal(outs[r].cpu().numpy(), ref[r % n])
+        finally:
+            srv.stop()
+    finally:
+        dag.unload()
+        dag.destroy()
+
+
+def test_server_needs_a_loaded_dag_with_per_member_inputs():
+    import torch
+    import paper_2410_21120_amd as fi
+    m = zoo.resnet18(hw=32)
+    blob = gen.make_blob(m, 1)
+    sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    for per_member, load in ((True, False), (False, True)):
+        dag = fi.Dag([sp], 2, fi.TorchAllocators("cuda:0"), keepalive=[(k, blob)], per_member_inputs=per_member)
+        if load:
+            dag.load(torch.cuda.current_stream().cuda_stream)
+        try:
+            with pytest.raises(fi.FiError) as e:
+                fi.Server(dag)
+            assert e.value.status == fi.FI_ESTATE
+        finally:
+            if load:
+                dag.unload()
+            dag.destroy()

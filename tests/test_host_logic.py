@@ -515,3 +515,15 @@ def test_random_graphs_compile_into_one_dag(seed):
             assert n.is_output or n.out_off + n.out_bytes <= q.act_bytes
             k += 1
     d.destroy()
+
+
+def test_server_refuses_an_unloaded_dag():
+    """The request aggregator needs a LOADED DAG built for per-member inputs; the check comes before any device call."""
+    d, _, _ = _build(["resnet18"], 2, hw=32, per_member_inputs=True)
+    with pytest.raises(fi.FiError) as e:
+        fi.Server(d)
+    assert e.value.status == fi.FI_ESTATE and "not loaded" in str(e.value)
+    h = C.c_void_p()
+    assert fi.lib().fi_server_start(None, None, C.byref(h)) == fi.FI_EINVAL
+    assert fi.lib().fi_server_stop(None) == fi.FI_EINVAL
+    d.destroy()
