@@ -353,6 +353,13 @@ fi_status fi_server_submit(fi_server* srv, int32_t member, const void* d_image, 
  * the worker's error, if it met one, on this and every later call. */
 fi_status fi_server_wait(fi_server* srv, uint64_t ticket);
 fi_status fi_server_query(fi_server* srv, fi_server_stats* stats);
+/* Section V, individual model swaps, under load: replaces member `slot` of the served DAG (fi_swap_model)
+ * between two passes.  The requests already queued for the slot are served by the outgoing model first;
+ * requests for the slot submitted while the call is in progress are refused with FI_ESTATE; the other
+ * members keep being served before and after.  Blocks until the newcomer's weights are on the device.
+ * `model` is borrowed as by fi_swap_model (until fi_destroy of the DAG).  Errors of fi_swap_model are
+ * returned and leave the server as it was. */
+fi_status fi_server_swap(fi_server* srv, int32_t slot, const fi_model_spec* model);
 /* Serves what is queued, joins the worker, releases the buffers and the handle; the DAG stays LOADED. */
 fi_status fi_server_stop(fi_server* srv);
 

@@ -100,7 +100,7 @@ class fi_launch_info(C.Structure):
 
 LIB_PATH = _build.OUT
 EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_footprint", "fi_partition", "fi_round_robin", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
-           "fi_run", "fi_run_inputs", "fi_run_batches", "fi_profile", "fi_timeline", "fi_swap_model", "fi_server_start", "fi_server_submit", "fi_server_wait", "fi_server_query", "fi_server_stop",
+           "fi_run", "fi_run_inputs", "fi_run_batches", "fi_profile", "fi_timeline", "fi_swap_model", "fi_server_start", "fi_server_submit", "fi_server_wait", "fi_server_query", "fi_server_swap", "fi_server_stop",
            "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
@@ -140,6 +140,7 @@ def lib():
         L.fi_server_wait.argtypes = [vp, u64]
         L.fi_server_query.argtypes = [vp, C.POINTER(fi_server_stats)]
         L.fi_server_stop.argtypes = [vp]
+        L.fi_server_swap.argtypes = [vp, i32, C.POINTER(fi_model_spec)]
         L.fi_unload.argtypes = [vp]
         L.fi_destroy.argtypes = [vp]
         L.fi_destroy.restype = None
@@ -415,6 +416,10 @@ class Server:
         st = fi_server_stats()
         _check(lib().fi_server_query(self.h, C.byref(st)), "fi_server_query")
         return st
+
+    def swap(self, slot, spec, keepalive=None) -> None:
+        self.dag.keepalive.append((spec, keepalive))   # borrowed by the DAG until it is destroyed
+        _check(lib().fi_server_swap(self.h, slot, C.byref(spec)), "fi_server_swap")
 
     def stop(self) -> None:
         if self.h:

@@ -53,6 +53,12 @@ struct fi_server {
   bool stopping = false;
   fi_status failed = FI_OK;                 // first error of the worker; every later wait reports it
   std::string failure;
+  // a member swap asked for by fi_server_swap, carried out by the worker between two passes
+  bool swap_wanted = false, swap_done = false;
+  int32_t swap_slot = -1;
+  const fi_model_spec* swap_model = nullptr;
+  fi_status swap_status = FI_OK;
+  std::string swap_error;
   // statistics (under mu)
   uint64_t n_requests = 0, n_passes = 0, max_images = 0;
   double sum_latency_ms = 0.0, max_latency_ms = 0.0, busy_ms = 0.0;
@@ -89,8 +95,36 @@ void fi_server::serve() {
   for (;;) {
     {
       std::unique_lock<std::mutex> lk(mu);
-      cv_work.wait(lk, [&] { return waiting > 0 || stopping; });
+      cv_work.wait(lk, [&] { return waiting > 0 || stopping || swap_wanted; });
+      if (swap_wanted && queue[(size_t)swap_slot].empty()) {
+        // Every request addressed to the outgoing model has been served and no pass is in flight.
+        lk.unlock();
+        fi_status st = fi_swap_model(dag, swap_slot, swap_model, stream);
+        std::string why = st != FI_OK ? std::string(fi_last_error()) : std::string();
+        if (st == FI_OK && hipStreamSynchronize(stream) != hipSuccess) { st = FI_EHIP; why = "hipStreamSynchronize failed after the swap"; }
+        uint8_t* bigger = nullptr;
+        ServingInfo now;
+        if (st == FI_OK) {
+          serving_info(dag, &now);
+          if (now.out_bytes[(size_t)swap_slot] > info.out_bytes[(size_t)swap_slot]) {
+            bigger = static_cast<uint8_t*>(dev_alloc((size_t)(now.out_bytes[(size_t)swap_slot] * (uint64_t)info.max_batch)));
+            if (!bigger) { st = FI_ENOMEM_DEVICE; why = "no device memory for the newcomer's output rows"; }
+          }
+        }
+        lk.lock();
+        if (st == FI_OK) {
+          if (bigger) { dev_free(out_buf[(size_t)swap_slot]); out_buf[(size_t)swap_slot] = bigger; }
+          info.out_bytes[(size_t)swap_slot] = now.out_bytes[(size_t)swap_slot];
+        } else if (st == FI_ENOMEM_DEVICE) {
+          fail(st, why);   // the DAG already holds the newcomer but the server cannot serve it
+        }
+        swap_status = st; swap_error = why;
+        swap_wanted = false; swap_done = true;
+        cv_done.notify_all();
+        continue;
+      }
       if (waiting == 0 && stopping) return;
+      if (waiting == 0) continue;
       if (opts.max_wait_us > 0 && !stopping) {
         // a first request after an idle period: give its companions a moment to arrive
         const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(opts.max_wait_us);
@@ -178,6 +212,7 @@ fi_status fi_server_submit(fi_server* s, int32_t member, const void* d_image, vo
     std::lock_guard<std::mutex> lk(s->mu);
     if (s->stopping) { set_error("fi_server_submit: the server is stopping"); return FI_ESTATE; }
     if (s->failed != FI_OK) { set_error("server failed: %s", s->failure.c_str()); return s->failed; }
+    if (s->swap_wanted && s->swap_slot == member) { set_error("fi_server_submit: member %d is being swapped", member); return FI_ESTATE; }
     const uint64_t t = s->next_ticket++;
     s->queue[(size_t)member].push_back(Request{t, d_image, d_output, now_ms()});
     s->pending.insert(t);
@@ -208,6 +243,21 @@ fi_status fi_server_query(fi_server* s, fi_server_stats* st) {
   st->max_latency_ms = s->max_latency_ms;
   st->busy_ms = s->busy_ms;
   return FI_OK;
+}
+
+fi_status fi_server_swap(fi_server* s, int32_t slot, const fi_model_spec* model) {
+  if (!s || !model) { set_error("null argument"); return FI_EINVAL; }
+  if (slot < 0 || slot >= s->info.n_models) { set_error("slot %d outside [0, %d)", slot, s->info.n_models); return FI_EINVAL; }
+  std::unique_lock<std::mutex> lk(s->mu);
+  if (s->stopping) { set_error("fi_server_swap: the server is stopping"); return FI_ESTATE; }
+  if (s->failed != FI_OK) { set_error("server failed: %s", s->failure.c_str()); return s->failed; }
+  if (s->swap_wanted) { set_error("fi_server_swap: another swap is in progress"); return FI_ESTATE; }
+  s->swap_wanted = true; s->swap_done = false; s->swap_slot = slot; s->swap_model = model;
+  s->cv_work.notify_all();
+  s->cv_done.wait(lk, [&] { return s->swap_done; });
+  s->swap_done = false;
+  if (s->swap_status != FI_OK) set_error("%s", s->swap_error.c_str());
+  return s->swap_status;
 }
 
 fi_status fi_server_stop(fi_server* s) {

@@ -145,3 +145,76 @@ def test_server_needs_a_loaded_dag_with_per_member_inputs():
             if load:
                 dag.unload()
             dag.destroy()
+
+
+def test_member_swap_under_load():
+    """Section V, individual model swaps, while requests keep arriving: requests queued for the slot before the
+    swap are served by the outgoing model, requests after it by the newcomer, and the other members' outputs keep
+    their bits throughout."""
+    import torch
+    import paper_2410_21120_amd as fi
+    B, hw = 4, 64
+    fams = [("resnet18", None), ("mobilenetv2", "f32"), ("resnet34", None)]
+    specs, keep, models = [], [], []
+    for i, (f, act) in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=hw)
+        blob = gen.make_blob(m, 3100 + i)
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        specs.append(sp)
+        keep.append((k, blob))
+    dag = fi.Dag(specs, B, fi.TorchAllocators("cuda:0"), keepalive=keep, per_member_inputs=True, swap_headroom_bytes=128 << 20)
+    stream = torch.cuda.current_stream().cuda_stream
+    dag.load(stream)
+    torch.cuda.synchronize()
+    newcomer = zoo.FAMILIES["resnet50"](hw=hw)
+    nblob = gen.make_blob(newcomer, 3199)
+    nspec, nkeep = fi.make_spec(newcomer, nblob.ctypes.data, nblob.nbytes)
+    n = 3
+    try:
+        img = torch.from_numpy(gen.to_nhwc_storage(gen.make_input(77, 1, 3, hw, hw, "normal", "bf16"), "bf16").view(np.int16)).cuda()
+
+        def alone(m):
+            o = torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda:0")
+            dag.run_batches([img.data_ptr() if k == m else 0 for k in range(n)], [1 if k == m else 0 for k in range(n)],
+                            [o.data_ptr() if k == m else 0 for k in range(n)], stream)
+            torch.cuda.synchronize()
+            return o.cpu().numpy()[0]
+        before = [alone(m) for m in range(n)]
+        srv = fi.Server(dag)
+        try:
+            outs = [torch.full((1000,), float("nan"), dtype=torch.float32, device="cuda:0") for _ in range(90)]
+            torch.cuda.synchronize()
+            tickets = [srv.submit(r % n, img.data_ptr(), outs[r].data_ptr()) for r in range(45)]   # queued for the old member 1
+            srv.swap(1, nspec, keepalive=(nkeep, nblob))
+            tickets += [srv.submit(r % n, img.data_ptr(), outs[r].data_ptr()) for r in range(45, 90)]
+            for t in tickets:
+                srv.wait(t)
+            assert srv.stats().requests == 90
+        finally:
+            srv.stop()
+        after = [alone(m) for m in range(n)]
+        assert np.array_equal(after[0], before[0]) and np.array_equal(after[2], before[2])
+        assert not np.array_equal(after[1], before[1])
+        for r in range(90):
+            want = (before if r < 45 else after)[r % n]
+            assert np.array_equal(outs[r].cpu().numpy(), want), r
+        # a newcomer that does not fit the DAG (another input size) is refused and the server keeps serving
+        srv = fi.Server(dag)
+        try:
+            odd = zoo.FAMILIES["resnet18"](hw=32)
+            oblob = gen.make_blob(odd, 3198)
+            ospec, okeep = fi.make_spec(odd, oblob.ctypes.data, oblob.nbytes)
+            with pytest.raises(fi.FiError) as e:
+                srv.swap(0, ospec, keepalive=(okeep, oblob))
+            assert e.value.status == fi.FI_EINVAL
+            with pytest.raises(fi.FiError) as e:
+                srv.swap(3, nspec)
+            assert e.value.status == fi.FI_EINVAL
+            t = srv.submit(0, img.data_ptr(), outs[0].data_ptr())
+            srv.wait(t)
+            assert np.array_equal(outs[0].cpu().numpy(), before[0])
+        finally:
+            srv.stop()
+    finally:
+        dag.unload()
+        dag.destroy()
