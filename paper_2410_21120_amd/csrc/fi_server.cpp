@@ -127,7 +127,7 @@ void fi_server::serve() {
       if (waiting == 0) continue;
       if (opts.max_wait_us > 0 && !stopping) {
         // a first request after an idle period: give its companions a moment to arrive
-        const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(opts.max_wait_us);
+        const auto until = std::chrono::system_clock::now() + std::chrono::microseconds(opts.max_wait_us);
         cv_work.wait_until(lk, until, [&] { return stopping || waiting >= (size_t)n * (size_t)info.max_batch; });
       }
       for (int32_t m = 0; m < n; ++m) {
