@@ -252,11 +252,11 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "3f337e95b4a036380be817a8dcc82a96a192fe29b74528d7661dde3f71f794c3",
+    "sources_sha256": "5dc9fca7f1811dba31d7857c1c06773699c327bf3da1a9e08bebbbb7a6084a6e",
     "workload": "cfg4",
     "kernel": "conv_mfma_128x128",
     "launches_per_step": 54,
-    "fetch_kib_per_step": 2891897.1, "write_kib_per_step": 3976448.0,
+    "fetch_kib_per_step": 2891838.2, "write_kib_per_step": 3976448.0,
     "fetch_scale": 2.0, "write_scale": 1.0,
 }
 
@@ -347,6 +347,48 @@ def serving(fi, torch, gen, zoo, alloc, stream, seconds=1.0):
                                  mean_latency_ms=st.mean_latency_ms, max_latency_ms=st.max_latency_ms, device_busy_frac=st.busy_ms / (t_all * 1e3)))
     dag.unload()
     dag.destroy()
+    # the same stream against four single-model handles, each behind a server (worker thread and stream) of its own
+    singles = []
+    for sp, kp in zip(specs, keep):
+        d1 = fi.Dag([sp], B, alloc, keepalive=[kp], per_member_inputs=True)
+        d1.load(stream)
+        singles.append(d1)
+    torch.cuda.synchronize()
+    rate = 16000.0
+    n_req = int(rate * seconds)
+    rng = np.random.default_rng(2024)
+    for _ in range(2):   # the third draw of the loop above: the same arrivals as the 16 k/s run
+        rng.exponential(1.0, int((1000.0 if _ == 0 else 4000.0) * seconds)); rng.integers(0, n, int((1000.0 if _ == 0 else 4000.0) * seconds))
+    gaps = rng.exponential(1.0 / rate, n_req)
+    who = rng.integers(0, n, n_req)
+    outs = torch.zeros((n_req, 1000), dtype=torch.float32, device="cuda:0")
+    base, row = outs.data_ptr(), 4000
+    torch.cuda.synchronize()
+    servers = [fi.Server(d1) for d1 in singles]
+    tickets = []
+    t0 = time.perf_counter()
+    due = 0.0
+    for r in range(n_req):
+        due += gaps[r]
+        while time.perf_counter() - t0 < due:
+            pass
+        m = int(who[r])
+        tickets.append((m, servers[m].submit(0, imgs[r & 3].data_ptr(), base + r * row)))
+    t_sub = time.perf_counter() - t0
+    for m, t in tickets[-256:]:
+        servers[m].wait(t)
+    t_all = time.perf_counter() - t0
+    sts = [sv.stats() for sv in servers]
+    for sv in servers:
+        sv.stop()
+    for d1 in singles:
+        d1.unload()
+        d1.destroy()
+    served = sum(int(st.requests) for st in sts)
+    out["per_model_servers"] = dict(offered_rps=rate, submitted_rps=n_req / t_sub, served_rps=n_req / t_all, requests=served,
+                                    passes=[int(st.passes) for st in sts], mean_images_per_pass=[st.mean_images_per_pass for st in sts],
+                                    mean_latency_ms=sum(st.mean_latency_ms * st.requests for st in sts) / max(served, 1),
+                                    max_latency_ms=max(st.max_latency_ms for st in sts))
     return out
 
 

@@ -129,6 +129,12 @@ struct ServingInfo {
 };
 void serving_info(const fi_dag* dag, ServingInfo* out);
 
+// Copies n rows of `bytes` bytes each, row i from src[i] to dst[i] (device pointers, 16-byte aligned, bytes a
+// multiple of 16), with as few kernel launches as the argument space allows (kCopyRows rows per launch): the
+// request aggregator gathers and scatters a pass's images with it instead of issuing one copy per request.
+constexpr int32_t kCopyRows = 64;
+int launch_copy_rows(const void* const* src, void* const* dst, int32_t n, uint64_t bytes, void* stream);
+
 void set_error(const char* fmt, ...);
 fi_status analyze_model(const fi_model_spec& m, ModelPlan& out);
 void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst);

@@ -1141,6 +1141,46 @@ __global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// row copies for the request aggregator: row r of the launch goes from src[r] to dst[r]
+// (the pointers travel as kernel arguments), 16 bytes per thread and step
+// ---------------------------------------------------------------------------------
+struct CopyArgs {
+  const uint4* src[kCopyRows];
+  uint4* dst[kCopyRows];
+  uint32_t vecs;            // 16-byte vectors per row
+  uint32_t blocks_per_row;
+};
+
+__global__ void __launch_bounds__(256) copy_rows_kernel(CopyArgs c) {
+  const uint32_t row = blockIdx.x / c.blocks_per_row, part = blockIdx.x % c.blocks_per_row;
+  const uint4* __restrict__ s = c.src[row];
+  uint4* __restrict__ d = c.dst[row];
+  for (uint32_t i = part * 256 + threadIdx.x; i < c.vecs; i += c.blocks_per_row * 256) d[i] = s[i];
+}
+
+int launch_copy_rows(const void* const* src, void* const* dst, int32_t n, uint64_t bytes, void* stream) {
+  if (bytes % 16 || bytes / 16 > 0xFFFFFFFFull) return (int)hipErrorInvalidValue;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int32_t first = 0; first < n; first += kCopyRows) {
+    CopyArgs c{};
+    const int32_t rows = n - first < kCopyRows ? n - first : kCopyRows;
+    for (int32_t r = 0; r < rows; ++r) {
+      if ((reinterpret_cast<uintptr_t>(src[first + r]) | reinterpret_cast<uintptr_t>(dst[first + r])) & 15) return (int)hipErrorInvalidValue;
+      c.src[r] = static_cast<const uint4*>(src[first + r]);
+      c.dst[r] = static_cast<uint4*>(dst[first + r]);
+    }
+    c.vecs = (uint32_t)(bytes / 16);
+    c.blocks_per_row = (c.vecs + 2047) / 2048;          // a thread moves up to eight vectors
+    if (c.blocks_per_row > 64) c.blocks_per_row = 64;
+    if (c.blocks_per_row == 0) continue;
+    hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)rows * c.blocks_per_row), dim3(256), 0, st, c);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return (int)hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------
 // host-side dispatch
 // ---------------------------------------------------------------------------------
 template <typename F>

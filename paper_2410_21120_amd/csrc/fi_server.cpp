@@ -92,6 +92,8 @@ void fi_server::serve() {
   std::vector<const void*> ins((size_t)n);
   std::vector<void*> outs((size_t)n);
   std::vector<int32_t> batches((size_t)n);
+  std::vector<const void*> csrc;
+  std::vector<void*> cdst;
   for (;;) {
     {
       std::unique_lock<std::mutex> lk(mu);
@@ -139,21 +141,40 @@ void fi_server::serve() {
     const double t0 = now_ms();
     hipError_t e = hipSuccess;
     uint64_t images = 0;
+    // gather: the images of every member's requests into that member's batch buffer.  Rows that allow it (16-byte
+    // aligned, a multiple of 16 bytes long) travel in one copy kernel per kCopyRows rows, the others one by one.
+    csrc.clear(); cdst.clear();
     for (int32_t m = 0; m < n && e == hipSuccess; ++m) {
       batches[(size_t)m] = (int32_t)take[(size_t)m].size();
       ins[(size_t)m] = in_buf[(size_t)m];
       outs[(size_t)m] = out_buf[(size_t)m];
       images += take[(size_t)m].size();
-      for (size_t i = 0; i < take[(size_t)m].size() && e == hipSuccess; ++i)
-        e = hipMemcpyAsync(in_buf[(size_t)m] + i * info.image_bytes, take[(size_t)m][i].d_image, (size_t)info.image_bytes, hipMemcpyDeviceToDevice, stream);
-    }
-    fi_status st = e == hipSuccess ? fi_run_batches(dag, ins.data(), batches.data(), outs.data(), stream) : FI_EHIP;
-    std::string why = st != FI_OK ? (e != hipSuccess ? std::string("hipMemcpyAsync: ") + hipGetErrorString(e) : std::string(fi_last_error())) : std::string();
-    for (int32_t m = 0; m < n && st == FI_OK; ++m)
-      for (size_t i = 0; i < take[(size_t)m].size(); ++i) {
-        e = hipMemcpyAsync(take[(size_t)m][i].d_output, out_buf[(size_t)m] + i * info.out_bytes[(size_t)m], (size_t)info.out_bytes[(size_t)m], hipMemcpyDeviceToDevice, stream);
-        if (e != hipSuccess) { st = FI_EHIP; why = std::string("hipMemcpyAsync: ") + hipGetErrorString(e); break; }
+      for (size_t i = 0; i < take[(size_t)m].size() && e == hipSuccess; ++i) {
+        uint8_t* to = in_buf[(size_t)m] + i * info.image_bytes;
+        const void* from = take[(size_t)m][i].d_image;
+        if (info.image_bytes % 16 == 0 && ((reinterpret_cast<uintptr_t>(from) | reinterpret_cast<uintptr_t>(to)) & 15) == 0) { csrc.push_back(from); cdst.push_back(to); }
+        else e = hipMemcpyAsync(to, from, (size_t)info.image_bytes, hipMemcpyDeviceToDevice, stream);
       }
+    }
+    if (e == hipSuccess && !csrc.empty()) e = (hipError_t)launch_copy_rows(csrc.data(), cdst.data(), (int32_t)csrc.size(), info.image_bytes, stream);
+    fi_status st = e == hipSuccess ? fi_run_batches(dag, ins.data(), batches.data(), outs.data(), stream) : FI_EHIP;
+    std::string why = st != FI_OK ? (e != hipSuccess ? std::string("gathering the images: ") + hipGetErrorString(e) : std::string(fi_last_error())) : std::string();
+    // scatter: every output row to its request's buffer (rows of one length share a copy kernel)
+    for (int32_t m = 0; m < n && st == FI_OK; ++m) {
+      csrc.clear(); cdst.clear();
+      const uint64_t ob = info.out_bytes[(size_t)m];
+      for (size_t i = 0; i < take[(size_t)m].size() && st == FI_OK; ++i) {
+        const uint8_t* from = out_buf[(size_t)m] + i * ob;
+        void* to = take[(size_t)m][i].d_output;
+        if (ob % 16 == 0 && ((reinterpret_cast<uintptr_t>(from) | reinterpret_cast<uintptr_t>(to)) & 15) == 0) { csrc.push_back(from); cdst.push_back(to); continue; }
+        e = hipMemcpyAsync(to, from, (size_t)ob, hipMemcpyDeviceToDevice, stream);
+        if (e != hipSuccess) { st = FI_EHIP; why = std::string("hipMemcpyAsync: ") + hipGetErrorString(e); }
+      }
+      if (st == FI_OK && !csrc.empty()) {
+        e = (hipError_t)launch_copy_rows(csrc.data(), cdst.data(), (int32_t)csrc.size(), ob, stream);
+        if (e != hipSuccess) { st = FI_EHIP; why = std::string("scattering the outputs: ") + hipGetErrorString(e); }
+      }
+    }
     e = hipStreamSynchronize(stream);
     if (e != hipSuccess && st == FI_OK) { st = FI_EHIP; why = std::string("hipStreamSynchronize: ") + hipGetErrorString(e); }
     const double t1 = now_ms();
