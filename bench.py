@@ -256,7 +256,7 @@ COUNTERS = {
     "workload": "cfg4",
     "kernel": "conv_mfma_128x128",
     "launches_per_step": 54,
-    "fetch_kib_per_step": 2891838.2, "write_kib_per_step": 3976448.0,
+    "fetch_kib_per_step": 2891686.8, "write_kib_per_step": 3976448.0,
     "fetch_scale": 2.0, "write_scale": 1.0,
 }
 
