@@ -245,6 +245,14 @@ fi_status fi_run_inputs(fi_dag* dag, const void* const* d_inputs, int32_t batch,
 fi_status fi_run_batches(fi_dag* dag, const void* const* d_inputs, const int32_t* batches, void* const* d_outputs,
                          void* hip_stream);
 
+/* One lane of that pass, on the caller's stream: only the launches of the members of `lane`
+ * (fi_member_info.lane; lanes are 0 .. fi_dag_info.n_lanes - 1) run, for batches[m] images of each of
+ * them; the entries of members of other lanes are ignored.  Lanes share no tensor and the call touches
+ * no state of the handle, so calls for DIFFERENT lanes may be in flight at the same time, on different
+ * streams and from different threads (two calls for one lane may not).  Needs per_member_inputs = 1. */
+fi_status fi_run_lane(fi_dag* dag, int32_t lane, const void* const* d_inputs, const int32_t* batches,
+                      void* const* d_outputs, void* hip_stream);
+
 /* Same pass with every launch issued on hip_stream (lanes serialised) and a HIP
  * event between launches; ms[i] (host, n_launches floats) receives launch i's
  * elapsed milliseconds: the kernel's own time with the chip to itself.

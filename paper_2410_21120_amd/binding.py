@@ -100,7 +100,7 @@ class fi_launch_info(C.Structure):
 
 LIB_PATH = _build.OUT
 EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_footprint", "fi_partition", "fi_round_robin", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
-           "fi_run", "fi_run_inputs", "fi_run_batches", "fi_profile", "fi_timeline", "fi_swap_model", "fi_server_start", "fi_server_submit", "fi_server_wait", "fi_server_query", "fi_server_swap", "fi_server_stop",
+           "fi_run", "fi_run_inputs", "fi_run_batches", "fi_run_lane", "fi_profile", "fi_timeline", "fi_swap_model", "fi_server_start", "fi_server_submit", "fi_server_wait", "fi_server_query", "fi_server_swap", "fi_server_stop",
            "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
@@ -127,6 +127,7 @@ def lib():
         L.fi_run.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
         L.fi_run_inputs.argtypes = [vp, C.POINTER(vp), i32, C.POINTER(vp), vp]
         L.fi_run_batches.argtypes = [vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), vp]
+        L.fi_run_lane.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), vp]
         L.fi_profile.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), i32]
         L.fi_timeline.argtypes = [vp, vp, i32, C.POINTER(vp), vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32]
         L.fi_footprint.argtypes = [C.POINTER(fi_model_spec), i32, C.POINTER(fi_build_opts), C.POINTER(fi_dag_info)]
@@ -268,6 +269,13 @@ def fi_run_batches(h, d_input_ptrs, batches, d_output_ptrs, stream_ptr=0) -> Non
     outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
     nb = (C.c_int32 * len(batches))(*batches)
     _check(lib().fi_run_batches(h, ins, nb, outs, C.c_void_p(stream_ptr)), "fi_run_batches")
+
+
+def fi_run_lane(h, lane, d_input_ptrs, batches, d_output_ptrs, stream_ptr=0) -> None:
+    ins = (C.c_void_p * len(d_input_ptrs))(*d_input_ptrs)
+    outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
+    nb = (C.c_int32 * len(batches))(*batches)
+    _check(lib().fi_run_lane(h, lane, ins, nb, outs, C.c_void_p(stream_ptr)), "fi_run_lane")
 
 
 def fi_profile(h, d_input_ptr, batch, d_output_ptrs, stream_ptr, n_launches):
@@ -468,6 +476,9 @@ class Dag:
 
     def run_batches(self, d_input_ptrs, batches, d_output_ptrs, stream_ptr=0):
         fi_run_batches(self.h, d_input_ptrs, batches, d_output_ptrs, stream_ptr)
+
+    def run_lane(self, lane, d_input_ptrs, batches, d_output_ptrs, stream_ptr=0):
+        fi_run_lane(self.h, lane, d_input_ptrs, batches, d_output_ptrs, stream_ptr)
 
     def profile(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
         return fi_profile(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr, self.query().n_launches)

@@ -728,19 +728,20 @@ fi_status fi_load(fi_dag* g, void* stream) {
 // in milliseconds since the pass began.
 static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream,
                           float* ms, int32_t n_ms, float* tl_begin = nullptr, float* tl_end = nullptr,
-                          const void* const* d_inputs = nullptr, const int32_t* batches = nullptr) {
+                          const void* const* d_inputs = nullptr, const int32_t* batches = nullptr, int32_t only_lane = -1) {
   if (!g || (!d_input && !d_inputs) || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
-  if (d_inputs) {
-    if (!g->opts.per_member_inputs) { set_error("per-member inputs need a DAG built with per_member_inputs"); return FI_ESTATE; }
-    for (size_t m = 0; m < g->members.size(); ++m)
-      if (!d_inputs[m] && !(batches && batches[m] == 0)) { set_error("input %zu is null", m); return FI_EINVAL; }
-  }
+  if (d_inputs && !g->opts.per_member_inputs) { set_error("per-member inputs need a DAG built with per_member_inputs"); return FI_ESTATE; }
   if (g->state != 1) { set_error("fi_run: handle is not loaded"); return FI_ESTATE; }
+  if (only_lane >= g->n_lanes) { set_error("lane %d outside [0, %d)", only_lane, g->n_lanes); return FI_EINVAL; }
   if (!batches && (batch < 1 || batch > g->opts.max_batch)) { set_error("batch %d outside [1, %d]", batch, g->opts.max_batch); return FI_EINVAL; }
-  for (size_t m = 0; batches && m < g->members.size(); ++m)
-    if (batches[m] < 0 || batches[m] > g->opts.max_batch) { set_error("batch %d of member %zu outside [0, %d]", batches[m], m, g->opts.max_batch); return FI_EINVAL; }
-  for (size_t m = 0; m < g->members.size(); ++m)
-    if (!d_outputs[m] && !(batches && batches[m] == 0)) { set_error("output %zu is null", m); return FI_EINVAL; }
+  // members that take part in this pass: those of the lane asked for (all lanes by default) that bring an image
+  auto idle = [&](size_t m) { return (only_lane >= 0 && g->members[m].lane != only_lane) || (batches && batches[m] == 0); };
+  for (size_t m = 0; m < g->members.size(); ++m) {
+    if (idle(m)) continue;
+    if (batches && (batches[m] < 0 || batches[m] > g->opts.max_batch)) { set_error("batch %d of member %zu outside [0, %d]", batches[m], m, g->opts.max_batch); return FI_EINVAL; }
+    if (d_inputs && !d_inputs[m]) { set_error("input %zu is null", m); return FI_EINVAL; }
+    if (!d_outputs[m]) { set_error("output %zu is null", m); return FI_EINVAL; }
+  }
   const size_t nl = g->launches.size();
   const bool timeline = tl_begin && tl_end;
   if ((ms || timeline) && n_ms < (int32_t)nl) { set_error("timing arrays hold %d entries, schedule has %zu launches", n_ms, nl); return FI_EINVAL; }
@@ -759,11 +760,12 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   fi_status rc = FI_OK;
   // Lanes: after the shared input is staged on the caller's stream the internal streams fork from
   // it, every launch goes to its lane's stream, and the caller's stream joins them at the end.
-  const bool lanes = !ms && !g->opts.use_graph && g->n_lanes > 1 &&
+  const bool lanes = !ms && !g->opts.use_graph && g->n_lanes > 1 && only_lane < 0 &&
                      (int32_t)g->lane_streams.size() >= g->n_lanes - 1 && (int32_t)g->lane_events.size() >= g->n_lanes;
   bool forked = false;
   for (size_t i = 0; i < nl; ++i) {
     const Launch& L = g->launches[i];
+    if (only_lane >= 0 && L.kind != K_STAGE && L.lane != only_lane) continue;   // another lane's launch
     if (lanes && !forked && L.level > 0) {
       (void)hipEventRecord(g->lane_events[0], s);
       for (int32_t l = 1; l < g->n_lanes; ++l) (void)hipStreamWaitEvent(g->lane_streams[(size_t)l - 1], g->lane_events[0], 0);
@@ -775,11 +777,12 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
       const StageTensor& st = g->stages[(size_t)L.nodes[(size_t)k]];
       a.ext_in[k] = (d_inputs && st.member >= 0) ? d_inputs[st.member] : d_input;
       a.batch[k] = (batches && st.member >= 0) ? batches[st.member] : batch;
+      if (st.member >= 0 && idle((size_t)st.member)) a.batch[k] = 0;   // staged by its own lane's pass
     }
     for (int32_t k = 0; k < L.n && L.kind != K_STAGE; ++k) {
       const Node& nd = g->nodes[(size_t)L.nodes[(size_t)k]];
       a.ext_out[k] = nd.is_output ? d_outputs[nd.model] : nullptr;
-      a.batch[k] = batches ? batches[nd.model] : batch;   // a member with no image this pass gets no workgroup
+      a.batch[k] = idle((size_t)nd.model) ? 0 : batches ? batches[nd.model] : batch;   // a member with no image this pass gets no workgroup
     }
     const int e = launch_kernel(L, a, ls, g->descs);
     if (e != (int)hipSuccess) { set_error("launch %zu (%s): %s", i, L.name.c_str(), hipGetErrorString((hipError_t)e)); rc = FI_EHIP; break; }
@@ -856,6 +859,12 @@ fi_status fi_run_inputs(fi_dag* g, const void* const* d_inputs, int32_t batch, v
 fi_status fi_run_batches(fi_dag* g, const void* const* d_inputs, const int32_t* batches, void* const* d_outputs, void* stream) {
   if (!d_inputs || !batches) { set_error("null inputs or batches"); return FI_EINVAL; }
   return run_impl(g, nullptr, 0, d_outputs, stream, nullptr, 0, nullptr, nullptr, d_inputs, batches);
+}
+
+fi_status fi_run_lane(fi_dag* g, int32_t lane, const void* const* d_inputs, const int32_t* batches, void* const* d_outputs, void* stream) {
+  if (!d_inputs || !batches) { set_error("null inputs or batches"); return FI_EINVAL; }
+  if (lane < 0) { set_error("lane %d is negative", lane); return FI_EINVAL; }
+  return run_impl(g, nullptr, 0, d_outputs, stream, nullptr, 0, nullptr, nullptr, d_inputs, batches, lane);
 }
 
 fi_status fi_profile(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream, float* ms, int32_t n_ms) {

@@ -324,3 +324,60 @@ def test_per_member_batches():
     finally:
         dag.unload()
         dag.destroy()
+
+
+def test_lanes_run_alone_and_side_by_side():
+    """fi_run_lane issues one lane of the schedule on the caller's stream: every lane on a stream of its own, all
+    in flight together, gives each member the bits of the whole-DAG pass; a lane run alone leaves the members of
+    the other lanes untouched."""
+    import torch
+    import paper_2410_21120_amd as fi
+    mem = _members()   # five architectures: five lanes
+    mem = mem + [(mem[0][0], gen.make_blob(mem[0][0], 2222), None)]   # and a second ResNet-18 that shares lane 0
+    B = 3
+    xs = [gen.make_input(90 + i, B, 3, 64, 64, "normal", "bf16") for i in range(len(mem))]
+    specs, keep = [], []
+    for m, blob, act in mem:
+        sp, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        specs.append(sp)
+        keep.append((k, blob))
+    dag = fi.Dag(specs, B, fi.TorchAllocators("cuda:0"), keepalive=keep, per_member_inputs=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    dag.load(stream)
+    try:
+        q = dag.query()
+        lane_of = [mi.lane for mi in dag.members()]
+        assert q.n_lanes == 5 and lane_of[0] == lane_of[5] and len(set(lane_of)) == 5
+        dev_in = [torch.from_numpy(gen.to_nhwc_storage(x, "bf16").view(np.int16)).cuda() for x in xs]
+        batches = [3, 2, 1, 3, 2, 1]
+        ref = [torch.full((B, 1000), -3.0, dtype=torch.float32, device="cuda:0") for _ in mem]
+        dag.run_batches([t.data_ptr() for t in dev_in], batches, [o.data_ptr() for o in ref], stream)
+        torch.cuda.synchronize()
+        ref = [o.cpu().numpy() for o in ref]
+        # one lane alone
+        outs = [torch.full((B, 1000), -3.0, dtype=torch.float32, device="cuda:0") for _ in mem]
+        torch.cuda.synchronize()
+        dag.run_lane(lane_of[0], [t.data_ptr() for t in dev_in], batches, [o.data_ptr() for o in outs], stream)
+        torch.cuda.synchronize()
+        for i, o in enumerate(outs):
+            y = o.cpu().numpy()
+            if lane_of[i] == lane_of[0]:
+                assert np.array_equal(y, ref[i]), i
+            else:
+                assert np.all(y == -3.0), i
+        # every lane on its own stream, all issued before any is waited for, three times over
+        streams = [torch.cuda.Stream() for _ in range(q.n_lanes)]
+        for _ in range(3):
+            outs = [torch.full((B, 1000), -3.0, dtype=torch.float32, device="cuda:0") for _ in mem]
+            torch.cuda.synchronize()
+            for lane, st in enumerate(streams):
+                dag.run_lane(lane, [t.data_ptr() for t in dev_in], batches, [o.data_ptr() for o in outs], st.cuda_stream)
+            torch.cuda.synchronize()
+            for i, o in enumerate(outs):
+                assert np.array_equal(o.cpu().numpy(), ref[i]), i
+        with pytest.raises(fi.FiError) as e:
+            dag.run_lane(q.n_lanes, [t.data_ptr() for t in dev_in], batches, [o.data_ptr() for o in outs], stream)
+        assert e.value.status == fi.FI_EINVAL
+    finally:
+        dag.unload()
+        dag.destroy()
