@@ -284,8 +284,8 @@ def counter_traffic(kernel, workload):
 def serving(fi, torch, gen, zoo, alloc, stream, seconds=1.0):
     """Request aggregation (Section IV, Manager): single-image requests for four resident models arrive as a
     seeded Poisson stream; the library's server gathers, per model, what arrived while the device was busy into
-    the next pass.  Open loop at several rates, against the capacity of serving every request in a pass of its
-    own."""
+    the next pass of the model's lane.  Open loop at several rates, against the capacity of serving every request in
+    a pass of its own, and against four single-model handles with a server each."""
     import numpy as np
     fams = ["resnet18", "resnet50", "mobilenetv2", "vgg16"]
     B = 8
@@ -319,7 +319,7 @@ def serving(fi, torch, gen, zoo, alloc, stream, seconds=1.0):
     out = dict(models=fams, max_batch=B, one_request_per_pass_ms=[round(v, 4) for v in alone_ms],
                one_request_per_pass_capacity_rps=1e3 / (sum(alone_ms) / n), rates=[])
     rng = np.random.default_rng(2024)
-    for rate in (1000.0, 4000.0, 16000.0):
+    for rate in (1000.0, 4000.0, 16000.0, 32000.0):
         n_req = int(rate * seconds)
         gaps = rng.exponential(1.0 / rate, n_req)
         who = rng.integers(0, n, n_req)
@@ -344,7 +344,7 @@ def serving(fi, torch, gen, zoo, alloc, stream, seconds=1.0):
         srv.stop()
         out["rates"].append(dict(offered_rps=rate, submitted_rps=n_req / t_sub, served_rps=n_req / t_all, requests=n_req, passes=int(st.passes),
                                  mean_images_per_pass=st.mean_images_per_pass, max_images_per_pass=int(st.max_images_per_pass),
-                                 mean_latency_ms=st.mean_latency_ms, max_latency_ms=st.max_latency_ms, device_busy_frac=st.busy_ms / (t_all * 1e3)))
+                                 mean_latency_ms=st.mean_latency_ms, max_latency_ms=st.max_latency_ms, lanes_busy=st.busy_ms / (t_all * 1e3)))
     dag.unload()
     dag.destroy()
     # the same stream against four single-model handles, each behind a server (worker thread and stream) of its own
@@ -354,11 +354,11 @@ def serving(fi, torch, gen, zoo, alloc, stream, seconds=1.0):
         d1.load(stream)
         singles.append(d1)
     torch.cuda.synchronize()
-    rate = 16000.0
+    rate = 32000.0
     n_req = int(rate * seconds)
     rng = np.random.default_rng(2024)
-    for _ in range(2):   # the third draw of the loop above: the same arrivals as the 16 k/s run
-        rng.exponential(1.0, int((1000.0 if _ == 0 else 4000.0) * seconds)); rng.integers(0, n, int((1000.0 if _ == 0 else 4000.0) * seconds))
+    for earlier in (1000.0, 4000.0, 16000.0):   # skip the draws of the loop above: the same arrivals as its 32 k/s run (beyond capacity: served_rps is the capacity)
+        rng.exponential(1.0, int(earlier * seconds)); rng.integers(0, n, int(earlier * seconds))
     gaps = rng.exponential(1.0 / rate, n_req)
     who = rng.integers(0, n, n_req)
     outs = torch.zeros((n_req, 1000), dtype=torch.float32, device="cuda:0")

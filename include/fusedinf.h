@@ -328,10 +328,11 @@ fi_status fi_round_robin(const fi_model_spec* models, int32_t n, const fi_build_
 /* ---- request aggregation (Section IV, "Manager": requests that arrive while the device
  * is busy are gathered per model into the next batch) ----
  * A server sits in front of a LOADED DAG built with per_member_inputs = 1.  Callers submit
- * single images for single members; one worker thread (with a stream of its own) repeatedly
- * takes up to max_batch waiting requests of every member, runs ONE fi_run_batches pass over
- * the whole DAG and hands every request its output row.  The busier the device, the larger
- * the batches.  While a server runs, nothing else may use the DAG. */
+ * single images for single members; every lane of the DAG has a worker thread (with a stream
+ * of its own) that repeatedly takes up to max_batch waiting requests of each of its members,
+ * runs ONE fi_run_lane pass and hands every request its output row.  The busier the device,
+ * the larger the batches; a short model never waits for a long one.  While a server runs,
+ * nothing else may use the DAG. */
 typedef struct fi_server fi_server; /* opaque, owned by the library */
 
 typedef struct {
@@ -341,11 +342,11 @@ typedef struct {
 } fi_server_opts;
 
 typedef struct {
-  uint64_t requests, passes;    /* requests served; fi_run_batches passes issued */
-  uint64_t max_images_per_pass; /* most requests one pass carried (all members together) */
+  uint64_t requests, passes;    /* requests served; lane passes (fi_run_lane) issued */
+  uint64_t max_images_per_pass; /* most requests one lane pass carried (all members of the lane together) */
   double mean_images_per_pass;
   double mean_latency_ms, max_latency_ms; /* submit to output written, host clock */
-  double busy_ms;               /* time with a pass in flight */
+  double busy_ms;               /* time with a pass in flight, summed over the lanes */
 } fi_server_stats;
 
 /* Allocates, through the DAG's allocator callbacks, one batch buffer of max_batch images and one of
@@ -361,10 +362,12 @@ fi_status fi_server_submit(fi_server* srv, int32_t member, const void* d_image, 
  * the worker's error, if it met one, on this and every later call. */
 fi_status fi_server_wait(fi_server* srv, uint64_t ticket);
 fi_status fi_server_query(fi_server* srv, fi_server_stats* stats);
-/* Section V, individual model swaps, under load: replaces member `slot` of the served DAG (fi_swap_model)
- * between two passes.  The requests already queued for the slot are served by the outgoing model first;
- * requests for the slot submitted while the call is in progress are refused with FI_ESTATE; the other
- * members keep being served before and after.  Blocks until the newcomer's weights are on the device.
+/* Section V, individual model swaps, under load: replaces member `slot` of the served DAG (fi_swap_model).
+ * The requests already queued for the slot are served by the outgoing model first; then every lane
+ * finishes its pass in flight, the swap re-plans the DAG (its lanes included) and new workers start.
+ * Requests for the slot submitted while the call is in progress are refused with FI_ESTATE; requests
+ * for the other members are accepted throughout and served before or after the swap.  Blocks until
+ * the newcomer's weights are on the device.
  * `model` is borrowed as by fi_swap_model (until fi_destroy of the DAG).  Errors of fi_swap_model are
  * returned and leave the server as it was. */
 fi_status fi_server_swap(fi_server* srv, int32_t slot, const fi_model_spec* model);

@@ -973,6 +973,9 @@ void serving_info(const fi_dag* g, ServingInfo* out) {
   out->out_bytes.assign(g->members.size(), 0);
   for (const Node& nd : g->nodes)
     if (nd.is_output) out->out_bytes[(size_t)nd.model] = (uint64_t)nd.Ho * nd.Wo * nd.Co * 4;
+  out->lane.clear();
+  for (const Member& mb : g->members) out->lane.push_back(mb.lane);
+  out->n_lanes = g->n_lanes;
   out->opts = g->opts;
 }
 }  // namespace fi

@@ -125,6 +125,8 @@ struct ServingInfo {
   int32_t n_models = 0, max_batch = 0, per_member_inputs = 0, state = 0;
   uint64_t image_bytes = 0;                 // one input image [in_h, in_w, in_c] in the weight dtype
   std::vector<uint64_t> out_bytes;          // one output row of every member (fp32)
+  std::vector<int32_t> lane;                // launch lane of every member
+  int32_t n_lanes = 1;
   fi_build_opts opts{};                     // allocator callbacks
 };
 void serving_info(const fi_dag* dag, ServingInfo* out);

@@ -1,7 +1,7 @@
 // Host simulation of the request aggregator for ThreadSanitizer (no device is touched).
 // Built by tests/test_host_sanitizers.py from fi_server.cpp alone; the HIP runtime calls and the DAG entry
 // points the server uses are replaced below by host stand-ins: "device" memory is host memory, a copy is a
-// memcpy, and a pass writes, for every image of member m, the row {m, first input word, generation of m}.
+// memcpy, and a lane's pass writes, for every image of its member m, the row {m, first input word, generation of m}.
 // Several client threads submit and wait at random while the main thread swaps members; every request must
 // come back with the row of its own image and member, whatever batch it travelled in.
 // Usage: server_sim <clients> <requests per client>.  Exit status 0 when every row was right.
@@ -21,6 +21,10 @@
 namespace {
 constexpr int kSimMembers = 3, kSimBatch = 4, kImageWords = 16, kOutWords = 4;
 std::atomic<int> generation[kSimMembers];   // bumped by every swap of the member
+int lane_of[kSimMembers] = {0, 1, 0};       // members 0 and 2 share a lane; every swap regroups (only while no pass runs)
+int n_lanes = 2;
+std::atomic<int> lane_busy[kSimMembers];    // a lane never has two passes in flight
+std::atomic<long> overlap{0};
 std::atomic<long> passes{0}, images{0};
 thread_local char err_text[256] = "";
 }  // namespace
@@ -41,9 +45,12 @@ const char* hipGetErrorString(hipError_t) { return "simulated"; }
 hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind, hipStream_t) { std::memcpy(dst, src, n); return hipSuccess; }
 
 // ---- stand-ins for the DAG entry points ----------------------------------------------------------------
-fi_status fi_run_batches(fi_dag*, const void* const* d_inputs, const int32_t* batches, void* const* d_outputs, void*) {
+fi_status fi_run_lane(fi_dag*, int32_t lane, const void* const* d_inputs, const int32_t* batches, void* const* d_outputs, void*) {
   ++passes;
+  if (lane < 0 || lane >= n_lanes) return FI_EINVAL;
+  if (lane_busy[lane].exchange(1) != 0) ++overlap;
   for (int m = 0; m < kSimMembers; ++m) {
+    if (lane_of[m] != lane) continue;
     if (batches[m] < 0 || batches[m] > kSimBatch) return FI_EINVAL;
     for (int i = 0; i < batches[m]; ++i) {
       const uint32_t* x = static_cast<const uint32_t*>(d_inputs[m]) + (size_t)i * kImageWords;
@@ -52,11 +59,17 @@ fi_status fi_run_batches(fi_dag*, const void* const* d_inputs, const int32_t* ba
       ++images;
     }
   }
+  lane_busy[lane].store(0);
   return FI_OK;
 }
 fi_status fi_swap_model(fi_dag*, int32_t slot, const fi_model_spec* model, void*) {
   if (model->n_layers < 0) { std::snprintf(err_text, sizeof(err_text), "refused"); return FI_EINVAL; }
   ++generation[slot];
+  // the newcomer forms a lane of its own or joins another member's, by turns
+  const int g = generation[slot].load();
+  if (g % 3 == 0) { lane_of[0] = 0; lane_of[1] = 1; lane_of[2] = 2; n_lanes = 3; }
+  else if (g % 3 == 1) { lane_of[0] = 0; lane_of[1] = 0; lane_of[2] = 1; n_lanes = 2; }
+  else { lane_of[0] = 0; lane_of[1] = 0; lane_of[2] = 0; n_lanes = 1; }
   return FI_OK;
 }
 const char* fi_last_error(void) { return err_text; }
@@ -77,6 +90,8 @@ void serving_info(const fi_dag*, ServingInfo* out) {
   out->n_models = kSimMembers; out->max_batch = kSimBatch; out->per_member_inputs = 1; out->state = 1;
   out->image_bytes = kImageWords * 4;
   out->out_bytes.assign(kSimMembers, kOutWords * 4);
+  out->lane.assign(lane_of, lane_of + kSimMembers);
+  out->n_lanes = n_lanes;
   out->opts = fi_build_opts{};
 }
 }  // namespace fi
@@ -132,7 +147,7 @@ int main(int argc, char** argv) {
   if (fi_server_query(srv, &st) != FI_OK) ++wrong;
   const long served = (long)st.requests;
   if (served + refused.load() != (long)clients * per_client || served != images.load() || (long)st.passes != passes.load()) ++wrong;
-  if (st.max_images_per_pass > (uint64_t)kSimMembers * kSimBatch) ++wrong;
+  if (st.max_images_per_pass > (uint64_t)kSimMembers * kSimBatch || overlap.load() != 0) ++wrong;
   if (fi_server_stop(srv) != FI_OK) ++wrong;
   std::printf("server_sim: %ld requests served in %ld passes (%.2f per pass), %ld refused during swaps, %ld swaps, %ld wrong\n",
               served, passes.load(), st.mean_images_per_pass, refused.load(), swaps, wrong.load());

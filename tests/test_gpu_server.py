@@ -1,6 +1,7 @@
 """The request aggregator (Section IV, "Manager": requests that arrive while the device is busy are gathered per
-model into the next batch): every request's output equals, bit for bit, the member run on that image alone; a
-burst of requests is served in fewer passes than requests."""
+model into the next batch; every lane of the DAG is served by a worker of its own): every request's output
+equals, bit for bit, the member run on that image alone; a burst of requests is served in fewer passes than
+requests."""
 import threading
 
 import numpy as np
@@ -116,7 +117,8 @@ def test_waiting_for_companions_fills_the_batches():
             for t in tickets:
                 srv.wait(t)
             st = srv.stats()
-            assert st.requests == n * B and st.passes <= 2, (st.requests, st.passes)   # the window closes early once every batch is full
+            # one pass per lane: each lane's window closes early once all its batches are full
+            assert st.requests == n * B and st.passes <= dag.query().n_lanes, (st.requests, st.passes)
             ref = [outs[m].cpu().numpy() for m in range(n)]
             for r in range(n * B):
                 assert np.array_equal(outs[r].cpu().numpy(), ref[r % n])
