@@ -434,6 +434,14 @@ class Server:
             h, self.h = self.h, None
             _check(lib().fi_server_stop(h), "fi_server_stop")
 
+    def __del__(self):
+        try:
+            if getattr(self, "h", None):   # a forgotten server still has worker threads: stop them before the DAG goes
+                h, self.h = self.h, None
+                lib().fi_server_stop(h)
+        except Exception:
+            pass
+
 
 class Dag:
     """Owner of one fi_dag handle."""
