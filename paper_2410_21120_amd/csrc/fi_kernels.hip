@@ -67,7 +67,7 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_DWCONV: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_MAXPOOL:
     case K_AVGPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
-    case K_GAP: return (batch * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256;
+    case K_GAP: return d.vec ? (batch * ((d.Cop / 8 + 7) / 8) + 3) / 4 : (batch * d.Cop + 255) / 256;
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits * ((batch + 31) / 32) + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
@@ -974,25 +974,39 @@ __global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
 // ---------------------------------------------------------------------------------
 template <typename TA>
 __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
+  // One wave = one image x 8 channel groups (128 contiguous bytes of a bf16 pixel) x 8 pixel phases: lane
+  // (phase, group) sums pixels phase, phase + 8, ... of its 8 channels, then the 8 phases are added pairwise
+  // across lanes (a fixed tree: the order depends on nothing but H*W).  A per-thread walk over all H*W pixels
+  // is one long chain of load latencies; this keeps 8 pixels x 128 bytes in flight per wave.
   int p, bid;
   if (!find_problem(a, K_GAP, 0, p, bid)) return;
   const Desc d = a.d[p];
   const int batch = a.batch[p];   // images of this problem's member in this pass
-  const int cv = d.Cop / 8;
-  const int idx = bid * 256 + threadIdx.x;
-  if (idx >= batch * cv) return;
-  const int c8 = (idx % cv) * 8, n = idx / cv;
-  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c8;
+  const int cv = d.Cop / 8, cvb = (cv + 7) / 8;
+  const int lane = threadIdx.x & 63;
+  const int unit = bid * 4 + (threadIdx.x >> 6);
+  if (unit >= batch * cvb) return;   // whole waves leave together
+  const int n = unit / cvb, cg = (unit % cvb) * 8 + (lane & 7), phase = lane >> 3;
+  const bool live = cg < cv;
+  const int c8 = cg * 8;
+  const int HW = d.H * d.W;
+  const TA* x = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * HW * d.Cp + c8;
   float sum[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) sum[i] = 0.0f;
-  for (int t = 0; t < d.H * d.W; ++t) {
-    float v[8];
-    load8(x + (int64_t)t * d.Cp, v);
+  if (live)
+    for (int t = phase; t < HW; t += 8) {
+      float v[8];
+      load8(x + (int64_t)t * d.Cp, v);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) sum[i] += v[i];
-  }
-  const float hw = (float)(d.H * d.W);
+      for (int i = 0; i < 8; ++i) sum[i] += v[i];
+    }
+#pragma unroll
+  for (int step = 8; step < 64; step <<= 1)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum[i] += __shfl_xor(sum[i], step);
+  if (!live || phase != 0) return;
+  const float hw = (float)HW;
 #pragma unroll
   for (int i = 0; i < 8; ++i) sum[i] = sum[i] / hw;
   if (d.ext) {
@@ -1113,8 +1127,17 @@ __global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
   const int o = (idx % q4) * 4, n = idx / q4;
   const float* ws = reinterpret_cast<const float*>(a.abase + d.ws_off) + (int64_t)n * d.Cop + o;
   float4 sum = make_float4(0, 0, 0, 0);
-  for (int s = 0; s < d.splits; ++s) {
-    const float4 v = *reinterpret_cast<const float4*>(ws + (int64_t)s * rows * d.Cop);
+  const int64_t stride = (int64_t)rows * d.Cop;
+  int s = 0;
+  for (; s + 8 <= d.splits; s += 8) {   // eight partials in flight, added in split order
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(ws + (s + u) * stride);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w; }
+  }
+  for (; s < d.splits; ++s) {
+    const float4 v = *reinterpret_cast<const float4*>(ws + s * stride);
     sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
   }
   const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.wbase + d.b_off) + o);
