@@ -46,7 +46,7 @@ def main():
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to calibrate rocprofv3 counters)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (member models are independent, so more GPUs would each take "
+        print("bench.py runs on ONE GPU (member models are independent, so more GPUs would each take "
               "a subset of members with its own arena and schedule, no collective); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
