@@ -624,6 +624,18 @@ static fi_status plan_dag(fi_dag* g) {
       vec = vec && d.Cp % 8 == 0 && d.Cop % 8 == 0;
     }
     for (int32_t s = 0; s < L.n; ++s) g->descs[(size_t)(L.first_desc + s)].vec = vec ? 1 : 0;
+    // A depthwise launch whose problems all have the same 3x3 / 5x5 / 7x7 filter and stride 1 or 2 runs the
+    // strip kernel: a thread computes 4 (stride 1) or 2 (stride 2) neighbouring outputs of a row from one
+    // pass over the input pixels they share.  The strip length travels in the (otherwise unused) tiles_n.
+    if (L.kind == K_DWCONV) {
+      const Desc& d0 = g->descs[(size_t)L.first_desc];
+      bool strip = vec && (d0.k == 3 || d0.k == 5 || d0.k == 7) && (d0.stride == 1 || d0.stride == 2);
+      for (int32_t s = 1; s < L.n; ++s) {
+        const Desc& d = g->descs[(size_t)(L.first_desc + s)];
+        strip = strip && d.k == d0.k && d.stride == d0.stride;
+      }
+      for (int32_t s = 0; s < L.n; ++s) g->descs[(size_t)(L.first_desc + s)].tiles_n = strip ? (d0.stride == 1 ? 4 : 2) : 1;
+    }
   }
 
   return FI_OK;

@@ -64,7 +64,10 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
       const int bm = tile_bm(tile);
       return ((batch * d.Ho * d.Wo + bm - 1) / bm) * d.tiles_n * d.splits;
     }
-    case K_DWCONV: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
+    case K_DWCONV: {
+      const int strip = d.tiles_n > 1 ? d.tiles_n : 1;   // outputs per thread along a row (strip kernel)
+      return (int)(((int64_t)batch * d.Ho * ((d.Wo + strip - 1) / strip) * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
+    }
     case K_MAXPOOL:
     case K_AVGPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_GAP: return d.vec ? (batch * ((d.Cop / 8 + 7) / 8) + 3) / 4 : (batch * d.Cop + 255) / 256;
@@ -970,6 +973,90 @@ __global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// depthwise convolution, strip form (3x3 / 5x5 / 7x7, stride 1 or 2, 8-channel vectors): a thread owns
+// S neighbouring outputs of one output row (S = 4 at stride 1, 2 at stride 2) for 8 channels.  Per filter
+// row it loads the (S-1)*stride + KS input pixels the strip touches and the KS weight vectors once, and
+// feeds every output from them: a third of the loads, address arithmetic and weight conversions of the
+// one-output-per-thread form.  Each output still accumulates its taps in (r, s) order.
+// ---------------------------------------------------------------------------------
+template <typename TA, int KS, int ST>
+__global__ void __launch_bounds__(256) dwconv_strip_kernel(KArgs a) {
+  constexpr int S = ST == 1 ? 4 : 2;
+  constexpr int NPIX = (S - 1) * ST + KS;
+  int p, bid;
+  if (!find_problem(a, K_DWCONV, 0, p, bid)) return;
+  const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
+  const int cv = d.Cop / 8, strips = (d.Wo + S - 1) / S;
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  if (idx >= (int64_t)batch * d.Ho * strips * cv) return;
+  const int c8 = (int)(idx % cv) * 8;
+  const int64_t t = idx / cv;
+  const int q0 = (int)(t % strips) * S;
+  const int pp = (int)((t / strips) % d.Ho);
+  const int n = (int)(t / ((int64_t)strips * d.Ho));
+  const TA* const xn = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c8;
+  const bf16_t* const w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off) + c8;
+  float acc[S][8];
+#pragma unroll
+  for (int j = 0; j < S; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[j][i] = 0.0f;
+  const int ih0 = pp * ST - d.pad, iw0 = q0 * ST - d.pad;
+#pragma unroll
+  for (int r = 0; r < KS; ++r) {
+    const int ih = ih0 + r;
+    if ((unsigned)ih >= (unsigned)d.H) continue;   // a row outside the image adds nothing
+    const TA* const xr = xn + (int64_t)ih * d.W * d.Cp;
+    float xv[NPIX][8], wv[KS][8];
+#pragma unroll
+    for (int c = 0; c < NPIX; ++c) {
+      const int iw = iw0 + c;
+      const bool ok = (unsigned)iw < (unsigned)d.W;
+      load8(xr + (ok ? (int64_t)iw * d.Cp : 0), xv[c]);   // always a valid address; masked below
+#pragma unroll
+      for (int i = 0; i < 8; ++i) xv[c][i] = ok ? xv[c][i] : 0.0f;
+    }
+#pragma unroll
+    for (int sx = 0; sx < KS; ++sx) load8(w + (r * KS + sx) * d.Cp, wv[sx]);
+#pragma unroll
+    for (int j = 0; j < S; ++j)
+#pragma unroll
+      for (int sx = 0; sx < KS; ++sx)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[j][i] += xv[j * ST + sx][i] * wv[sx][i];
+  }
+  float bv[8];
+  load8(reinterpret_cast<const float*>(a.wbase + d.b_off) + c8, bv);
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    const int q = q0 + j;
+    if (q >= d.Wo) break;
+    const int64_t m = ((int64_t)n * d.Ho + pp) * d.Wo + q;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = acc[j][i] + bv[i];
+    if (d.r_off != kNone) {
+      float rv[8];
+      load8(reinterpret_cast<const TA*>(a.abase + d.r_off) + m * d.Cop + c8, rv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] += rv[i];
+    }
+    activate_n<8>(v, d.act);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (c8 + i < d.Co) ? v[i] : 0.0f;
+    if (d.ext) {
+      float* y = static_cast<float*>(a.ext_out[p]) + m * d.Co + c8;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (c8 + i < d.Co) y[i] = v[i];
+    } else {
+      store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c8, v);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // global average pooling, 8 channels per thread
 // ---------------------------------------------------------------------------------
 template <typename TA>
@@ -1259,6 +1346,13 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false>, nb, 256, a, s);
     case K_DWCONV: {
       const bool vec = hd[(size_t)L.first_desc].vec != 0;
+      if (vec && hd[(size_t)L.first_desc].tiles_n > 1) {   // the planner found one filter size and stride for the whole launch
+        const int ks = hd[(size_t)L.first_desc].k, st = hd[(size_t)L.first_desc].stride;
+#define FI_DW_STRIP(K, T) if (ks == K && st == T) return ab ? go(dwconv_strip_kernel<bf16_t, K, T>, nb, 256, a, s) : go(dwconv_strip_kernel<float, K, T>, nb, 256, a, s);
+        FI_DW_STRIP(3, 1) FI_DW_STRIP(3, 2) FI_DW_STRIP(5, 1) FI_DW_STRIP(5, 2) FI_DW_STRIP(7, 1) FI_DW_STRIP(7, 2)
+#undef FI_DW_STRIP
+        return (int)hipErrorInvalidValue;
+      }
       if (vec) return ab ? go(dwconv_vec_kernel<bf16_t>, nb, 256, a, s) : go(dwconv_vec_kernel<float>, nb, 256, a, s);
       if (wb && ab) return go(dwconv_kernel<bf16_t, bf16_t>, nb, 256, a, s);
       if (wb) return go(dwconv_kernel<bf16_t, float>, nb, 256, a, s);
