@@ -70,7 +70,7 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     }
     case K_MAXPOOL:
     case K_AVGPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
-    case K_GAP: return d.vec ? (batch * ((d.Cop / 8 + 7) / 8) + 3) / 4 : (batch * d.Cop + 255) / 256;
+    case K_GAP: return d.vec ? batch * ((d.Cop / 8 + 7) / 8) : (batch * d.Cop + 255) / 256;
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits * ((batch + 31) / 32) + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
@@ -1061,19 +1061,18 @@ __global__ void __launch_bounds__(256) dwconv_strip_kernel(KArgs a) {
 // ---------------------------------------------------------------------------------
 template <typename TA>
 __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
-  // One wave = one image x 8 channel groups (128 contiguous bytes of a bf16 pixel) x 8 pixel phases: lane
-  // (phase, group) sums pixels phase, phase + 8, ... of its 8 channels, then the 8 phases are added pairwise
-  // across lanes (a fixed tree: the order depends on nothing but H*W).  A per-thread walk over all H*W pixels
-  // is one long chain of load latencies; this keeps 8 pixels x 128 bytes in flight per wave.
+  // One workgroup = one image x 8 channel groups (128 contiguous bytes of a bf16 pixel) x 32 pixel phases:
+  // thread (phase, group) sums pixels phase, phase + 32, ... of its 8 channels; the 8 phases of a wave are
+  // added pairwise across lanes, the 4 waves' sums through LDS in wave order (a fixed tree: the order depends
+  // on nothing but H*W).  A per-thread walk over all H*W pixels is one long chain of load latencies; this
+  // keeps 32 pixels x 128 bytes in flight per workgroup.
+  __shared__ float part[4][8][8];   // [wave][group][channel]
   int p, bid;
   if (!find_problem(a, K_GAP, 0, p, bid)) return;
   const Desc d = a.d[p];
-  const int batch = a.batch[p];   // images of this problem's member in this pass
   const int cv = d.Cop / 8, cvb = (cv + 7) / 8;
-  const int lane = threadIdx.x & 63;
-  const int unit = bid * 4 + (threadIdx.x >> 6);
-  if (unit >= batch * cvb) return;   // whole waves leave together
-  const int n = unit / cvb, cg = (unit % cvb) * 8 + (lane & 7), phase = lane >> 3;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = bid / cvb, gl = lane & 7, cg = (bid % cvb) * 8 + gl, phase = wave * 8 + (lane >> 3);
   const bool live = cg < cv;
   const int c8 = cg * 8;
   const int HW = d.H * d.W;
@@ -1082,7 +1081,7 @@ __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) sum[i] = 0.0f;
   if (live)
-    for (int t = phase; t < HW; t += 8) {
+    for (int t = phase; t < HW; t += 32) {
       float v[8];
       load8(x + (int64_t)t * d.Cp, v);
 #pragma unroll
@@ -1092,10 +1091,14 @@ __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
   for (int step = 8; step < 64; step <<= 1)
 #pragma unroll
     for (int i = 0; i < 8; ++i) sum[i] += __shfl_xor(sum[i], step);
-  if (!live || phase != 0) return;
+  if (lane < 8)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part[wave][gl][i] = sum[i];
+  __syncthreads();
+  if (wave != 0 || lane >= 8 || !live) return;
   const float hw = (float)HW;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) sum[i] = sum[i] / hw;
+  for (int i = 0; i < 8; ++i) sum[i] = (((part[0][gl][i] + part[1][gl][i]) + part[2][gl][i]) + part[3][gl][i]) / hw;
   if (d.ext) {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
