@@ -346,6 +346,7 @@ static fi_status plan_dag(fi_dag* g) {
           nd.kind = K_FC;
           const int tiles = (nd.Co + 31) / 32, steps = nd.Kp / 16;
           nd.splits = std::max(1, std::min(std::min(64, std::max(1, steps / 8)), std::max(1, 2048 / tiles)));
+          if (nd.Kp <= 512) nd.splits = 1;   // a short reduction (a squeeze-excite gate, a small head): the kernel finishes it itself
         } else if (g->wdtype == FI_BF16) {
           nd.kind = K_CONV_MFMA;
           {
@@ -430,7 +431,7 @@ static fi_status plan_dag(fi_dag* g) {
       Node& nd = g->nodes[(size_t)i];
       if (nd.level != lv) continue;
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 8 + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 + (nd.kind == K_CONV_MFMA && nd.splits > 1 ? 1 : 0));
+      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 8 + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 + ((nd.kind == K_CONV_MFMA || nd.kind == K_FC) && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
       if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
         new_launch(lv, nd.kind, nd.tile, adt).lane = nd.lane;
@@ -448,6 +449,11 @@ static fi_status plan_dag(fi_dag* g) {
       const Launch& cand = g->launches[li];
       const bool split_conv = cand.kind == K_CONV_MFMA && !cand.nodes.empty() && g->nodes[(size_t)cand.nodes[0]].splits > 1;
       if (cand.level != lv || !(cand.kind == K_FC || split_conv)) continue;
+      if (cand.kind == K_FC) {   // FC launches whose problems are all unsplit finish in their own kernel
+        bool any_split = false;
+        for (int32_t ni : cand.nodes) any_split = any_split || g->nodes[(size_t)ni].splits > 1;
+        if (!any_split) continue;
+      }
       const Launch src = cand;
       Launch& R = new_launch(lv, K_REDUCE, 0, src.adtype);
       R.lane = src.lane;

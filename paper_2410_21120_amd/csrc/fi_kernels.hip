@@ -10,6 +10,8 @@
 // Tensors are NHWC with the channel stride padded to Cp; pad channels always hold zero.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "fi_internal.h"
 
 namespace fi {
@@ -202,6 +204,33 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int total) {
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+// Finishes four consecutive features [o, o + 4) of output row n from their complete fp32 sums: bias
+// (and residual), activation, zero in the padded features, store.  p: the problem's slot in the launch.
+template <typename TA>
+__device__ __forceinline__ void finish_row4(const KArgs& a, const Desc& d, int p, int n, int o, float4 sum) {
+  const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.wbase + d.b_off) + o);
+  float v[4] = {sum.x + b.x, sum.y + b.y, sum.z + b.z, sum.w + b.w};
+  if (d.r_off != kNone) {
+    const TA* r = reinterpret_cast<const TA*>(a.abase + d.r_off) + (int64_t)n * d.Cop + o;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) v[t] += ld(r + t);
+  }
+  activate_n<4>(v, d.act);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) v[t] = (o + t < d.Co) ? v[t] : 0.0f;
+  if (d.ext) {
+    float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)n * d.Co + o;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      if (o + t < d.Co) y[t] = v[t];
+  } else if (sizeof(TA) == 4 || d.out_f32) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) =
+        make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+  }
 }
 
 // WIDE: the member keeps fp32 activations.  Each fp32 input is split on the fly into
@@ -1190,7 +1219,16 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
       }
     }
   }
-  // partial block: lane holds batch column n, features 8*g + 4*(lane/32) + t
+  // lane holds batch column n, features 8*g + 4*(lane/32) + t
+  if (nok && d.splits == 1) {   // the whole reduction was this wave's: no partials, no reduce launch
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int fo = tile * 32 + 8 * g + 4 * (lane >> 5);
+      if (fo < d.Cop)
+        finish_row4<typename std::conditional<WIDE, float, bf16_t>::type>(a, d, p, n, fo, make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]));
+    }
+    return;
+  }
   if (nok) {
     float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * batch + n) * d.Cop + tile * 32;
 #pragma unroll
@@ -1230,27 +1268,7 @@ __global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
     const float4 v = *reinterpret_cast<const float4*>(ws + s * stride);
     sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
   }
-  const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.wbase + d.b_off) + o);
-  float v[4] = {sum.x + b.x, sum.y + b.y, sum.z + b.z, sum.w + b.w};
-  if (d.r_off != kNone) {
-    const TA* r = reinterpret_cast<const TA*>(a.abase + d.r_off) + (int64_t)n * d.Cop + o;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) v[t] += ld(r + t);
-  }
-  activate_n<4>(v, d.act);
-#pragma unroll
-  for (int t = 0; t < 4; ++t) v[t] = (o + t < d.Co) ? v[t] : 0.0f;
-  if (d.ext) {
-    float* y = static_cast<float*>(a.ext_out[p]) + (int64_t)n * d.Co + o;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-      if (o + t < d.Co) y[t] = v[t];
-  } else if (sizeof(TA) == 4 || d.out_f32) {
-    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) = make_float4(v[0], v[1], v[2], v[3]);
-  } else {
-    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) =
-        make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-  }
+  finish_row4<TA>(a, d, p, n, o, sum);
 }
 
 // ---------------------------------------------------------------------------------
