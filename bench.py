@@ -12,6 +12,7 @@ fused-vs-separate throughput, memory and swap-latency comparison.
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -31,12 +32,29 @@ PEAK_MFMA_BF16 = 2500.0  # TFLOP/s dense
 PEAK_HBM = 8000.0        # GB/s
 
 
+def workload(name, families):
+    """A named configuration, or `fam:<family>[x<members>][@<batch>]`: identical members of one family."""
+    if name in WORKLOADS:
+        return WORKLOADS[name]
+    m = re.fullmatch(r"fam:([a-z0-9_]+?)(?:x(\d+))?(?:@(\d+))?", name)
+    if not m or m.group(1) not in families:
+        sys.exit("unknown workload %r: one of %s or fam:<family>[x<members>][@<batch>] with a family of "
+                 "workloads/zoo.py" % (name, ", ".join(sorted(WORKLOADS))))
+    fam, n, b = m.group(1), int(m.group(2) or 1), int(m.group(3) or 32)
+    if not (1 <= n <= 64 and 1 <= b <= 1024):
+        sys.exit("fam: workloads take 1..64 members and a batch of 1..1024")
+    shape = families[fam]()   # the family's own input size (299 for Inception v3, 384 for EfficientNetV2-S, ...)
+    return dict(desc="%dx %s fused, bf16, batch %dx%dx%dx%d" % (n, fam, b, shape.in_c, shape.in_h, shape.in_w), fams=[fam] * n, batch=b)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="cfg4",
+                    help="cfg4 | cfg3 | cfg2, or fam:<family>[x<members>][@<batch>] for identical members of one "
+                         "family of workloads/zoo.py (e.g. fam:densenet121x4@32)")
     ap.add_argument("--swap-requests", type=int, default=200)
     ap.add_argument("--no-extras", action="store_true", help="skip separate-DAG, swap and CPU legs")
     ap.add_argument("--serial-lanes", action="store_true",
@@ -58,7 +76,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     fi.lib()
-    wl = WORKLOADS[a.workload]
+    wl = workload(a.workload, zoo.FAMILIES)
     B = wl["batch"]
     stream = torch.cuda.current_stream().cuda_stream
     alloc = fi.TorchAllocators("cuda:0")
@@ -76,9 +94,13 @@ def main():
             keep.append((k, blob))
         return fi.Dag(specs, B, alloc, keepalive=keep, **kw)
 
-    x = gen.make_input(7, B, 3, 224, 224, "normal", "bf16")
+    m0 = members[0][0]
+    # one input feeds every member: they must agree on its shape, and the buffer handed over must hold it
+    assert all((m.in_c, m.in_h, m.in_w) == (m0.in_c, m0.in_h, m0.in_w) for m, _, _ in members), "members disagree on the input shape"
+    x = gen.make_input(7, B, m0.in_c, m0.in_h, m0.in_w, "normal", "bf16")
     xin = torch.from_numpy(gen.to_nhwc_storage(x, "bf16").view(np.int16)).cuda()
-    outs = [torch.zeros((B, 1000), dtype=torch.float32, device="cuda:0") for _ in members]
+    assert xin.numel() == B * m0.in_h * m0.in_w * m0.in_c
+    outs = [torch.zeros((B, m.layers[-1].cout), dtype=torch.float32, device="cuda:0") for m, _, _ in members]
     optr = [o.data_ptr() for o in outs]
 
     if a.probe_copy:

@@ -128,6 +128,22 @@ int pick_tile(const Node& n, int max_batch, int group, bool wide) {
   return T_64x64;
 }
 
+// A grouped convolution on the MFMA path whose column tiles can skip the input channels outside their own
+// groups: bf16 activations, and a channel stride that whole 64-element reduction tiles divide.  (Other grouped
+// convolutions walk all channels; their packed rows are zero outside the group, so the result is the same.)
+bool walks_groups(const Node& n, int adt) {
+  return n.kind == K_CONV_MFMA && n.groups > 1 && adt == FI_BF16 && n.Cp % 64 == 0 && n.Cp != 4;
+}
+
+// Tile of a group-walking convolution: 64 columns (the narrower the tile, the fewer foreign groups it spans and
+// the shorter its reduction), rows as for any problem: the largest that still covers the chip.
+int pick_group_tile(const Node& n, int max_batch, int group) {
+  const int64_t M = (int64_t)max_batch * n.Ho * n.Wo;
+  for (int t : {T_256x64, T_128x64})
+    if (group * ((M + tile_bm(t) - 1) / tile_bm(t)) * ((n.Co + 63) / 64) >= 256) return t;
+  return T_64x64;
+}
+
 const char* kind_name(int kind, int tile) {
   switch (kind) {
     case K_STAGE: return "stage_input";
@@ -371,6 +387,10 @@ static fi_status plan_dag(fi_dag* g) {
           const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.level + 1000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
           // sibling lanes run the same level at about the same time: the chip is shared by all of them
           nd.tile = pick_tile(nd, B, std::min(grp * g->members[(size_t)nd.model].sibling_lanes, (int)FI_MAX_GROUP), adt == FI_F32);
+          if (walks_groups(nd, adt)) {   // the reduction shrinks to the tile's own groups: short, never split
+            nd.tile = pick_group_tile(nd, B, std::min(grp * g->members[(size_t)nd.model].sibling_lanes, (int)FI_MAX_GROUP));
+            nd.splits = 1;
+          }
         } else nd.kind = K_CONV_DIRECT;
         break;
       case FI_DWCONV2D: nd.kind = K_DWCONV; break;
@@ -431,7 +451,8 @@ static fi_status plan_dag(fi_dag* g) {
       Node& nd = g->nodes[(size_t)i];
       if (nd.level != lv) continue;
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 8 + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 + ((nd.kind == K_CONV_MFMA || nd.kind == K_FC) && nd.splits > 1 ? 1 : 0));
+      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 16 + (walks_groups(nd, adt) ? 8 : 0) + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 +
+                                       ((nd.kind == K_CONV_MFMA || nd.kind == K_FC) && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
       if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
         new_launch(lv, nd.kind, nd.tile, adt).lane = nd.lane;
@@ -601,6 +622,7 @@ static fi_status plan_dag(fi_dag* g) {
       if (nd.out_dtype == FI_F32 && adt != FI_F32 && !nd.is_output) d.Cop = nd.Cop;  // fp32 rows keep the padded stride
       d.tiles_n = L.kind == K_CONV_MFMA ? (nd.Co + tile_bn(L.tile) - 1) / tile_bn(L.tile) : 0;
       d.splits = std::max(1, nd.splits);
+      if (walks_groups(nd, adt)) { d.gin = nd.C / nd.groups; d.gout = nd.Co / nd.groups; }
       d.ws_off = g->act_bytes + nd.ws_off;  // the workspace follows the activation arena
       if (L.kind == K_FC) d.tiles_n = (nd.Co + 31) / 32;
       if (L.kind == K_CONCAT) {

@@ -65,8 +65,9 @@ struct Desc {
   int32_t splits;                // reduction splits (>1: fp32 partials [splits][rows][Cop] at ws_off)
   uint64_t ws_off;               // split-K partials, relative to the activation base
   int32_t kw, pad_w;             // dense conv: kernel width and horizontal padding (k, pad are the vertical ones)
+  int32_t gin, gout;             // MFMA conv of a grouped convolution: input / output channels per group (0 = dense walk over all channels)
 };
-static_assert(sizeof(Desc) == 128, "Desc is 128 bytes");
+static_assert(sizeof(Desc) == 136, "Desc is 136 bytes");
 
 struct Node {
   int32_t model, index;
@@ -75,6 +76,7 @@ struct Node {
   int32_t H, W, C, Cp, Ho, Wo, Co, Cop, k, stride, pad;
   int32_t kw, pad_w;             // dense conv: kernel width / horizontal padding (k / pad are the vertical ones)
   int32_t Kp;
+  int32_t groups;                // conv2d: channel groups (1 = dense)
   int32_t level;
   int32_t out_dtype;             // FI_F32 / FI_BF16 as stored
   int32_t is_output;

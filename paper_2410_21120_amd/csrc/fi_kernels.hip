@@ -76,7 +76,7 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits * ((batch + 31) / 32) + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
-    case K_GATHER: return (int)(((int64_t)batch * d.Ho * d.Wo * d.Cop + 255) / 256);
+    case K_GATHER: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_CONCAT:
     case K_MUL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
   }
@@ -239,8 +239,13 @@ __device__ __forceinline__ void finish_row4(const KArgs& a, const Desc& d, int p
 // fp32: bf16 matrix-core throughput at fp32-grade activation accuracy.
 // C4: the input has 4 stored channels (an RGB-like model input); an 8-element reduction vector
 // then spans two neighbouring filter taps and is gathered with two half-width loads.
-template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false>
+// GROUPED: a grouped convolution (packed as dense rows that are zero outside the row's group).  A column
+// tile then needs only the input channels of the groups its output channels belong to: per filter tap the
+// reduction walks channels [c_lo, c_hi) (whole 64-element tiles; the planner guarantees Cp % 64 == 0)
+// instead of all Cp.  The skipped products are exact zeros, so the sums are the dense walk's.
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false>
 __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
+  static_assert(!GROUPED || (!WIDE && !C4), "the group walk exists for bf16 activations with 8-channel vectors");
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
   constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
   constexpr int AE = WIDE ? 4 : 2;       // bytes per stored activation element
@@ -314,12 +319,25 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     b_ptr[i] = reinterpret_cast<const uint4*>(w + (int64_t)o * d.Kp + kvec);
   }
   // this thread's reduction position (r, s, c) for the tile being fetched
-  const int ntiles_all = (d.Kp + BK - 1) / BK;
+  int c_lo = 0, c_hi = d.Cp;   // channels walked per filter tap
+  if constexpr (GROUPED) {
+    const int g0 = n0 / d.gout, g1 = (min(n0 + BN, d.Co) - 1) / d.gout;   // groups of this tile's output channels
+    c_lo = (g0 * d.gin) / BK * BK;
+    c_hi = min(d.Cp, ((g1 + 1) * d.gin + BK - 1) / BK * BK);
+  }
+  const int c_len = c_hi - c_lo;
+  const int ntiles_all = GROUPED ? d.k * d.kw * (c_len / BK) : (d.Kp + BK - 1) / BK;
   const int per_split = (ntiles_all + d.splits - 1) / d.splits;
   const int kt0 = split * per_split;
   const int ntiles = min(ntiles_all, kt0 + per_split);  // this workgroup multiplies tiles [kt0, ntiles)
   int kr, ks, kc;
-  {
+  if constexpr (GROUPED) {
+    const int per_tap = c_len / BK;
+    const int rs = kt0 / per_tap;
+    kc = c_lo + (kt0 - rs * per_tap) * BK + kvec;
+    kr = rs / d.kw;
+    ks = rs - kr * d.kw;
+  } else {
     const int k0 = kt0 * BK + kvec;
     const int rs = k0 / d.Cp;
     kc = k0 - rs * d.Cp;
@@ -373,12 +391,14 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       }                                                                                           \
     }                                                                                             \
     const bool bok = !(b_tail && (KT) == ntiles_all - 1 && kvec >= 32);                           \
+    /* position of this tile in a weight row, in 8-element vectors past the thread's own kvec */  \
+    const int wt = GROUPED ? ((kr * d.kw + ks) * d.Cp + kc - kvec) >> 3 : (KT) * (BK / 8);        \
     _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
-        bv[S][i] = bok ? b_ptr[i][(KT) * (BK / 8)] : make_uint4(0, 0, 0, 0);                      \
+        bv[S][i] = bok ? b_ptr[i][wt] : make_uint4(0, 0, 0, 0);                                   \
     kc += BK;                                                                                     \
-    _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                               \
-      const bool wrap = kc >= d.Cp;                                                               \
-      kc -= wrap ? d.Cp : 0;                                                                      \
+    _Pragma("unroll") for (int t = 0; t < (GROUPED ? 1 : 8); ++t) {                               \
+      const bool wrap = kc >= c_hi;                                                               \
+      kc -= wrap ? c_len : 0;                                                                     \
       ks += wrap ? 1 : 0;                                                                         \
       const bool wrap2 = ks == d.kw;                                                              \
       ks = wrap2 ? 0 : ks;                                                                        \
@@ -655,6 +675,29 @@ __global__ void __launch_bounds__(256) gather_kernel(KArgs a) {
   const Desc d = a.d[p];
   const int batch = a.batch[p];   // images of this problem's member in this pass
   const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  if (sizeof(TA) == 2 && d.vec) {   // bf16 tensors inside the arena: a thread gathers 8 output channels and stores them as one vector
+    const int cv = d.Cop / 8;
+    if (idx >= (int64_t)batch * d.Ho * d.Wo * cv) return;
+    const int c8 = (int)(idx % cv) * 8;
+    const int64_t m = idx / cv;
+    const uint16_t* x = reinterpret_cast<const uint16_t*>(a.abase + d.x_off) + m * d.Cp;
+    uint16_t* y = reinterpret_cast<uint16_t*>(a.abase + d.y_off) + m * d.Cop + c8;
+    if (d.stride == 0 && (d.pad & 7) == 0 && c8 + 8 <= d.Co) {   // aligned slice: the 8 channels are one vector of the source too
+      *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(x + d.pad + c8);
+      return;
+    }
+    const int per = d.stride == 0 ? 0 : d.C / d.k;
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int c = c8 + i;
+      const int src = d.stride == 0 ? d.pad + c : (c % d.k) * per + c / d.k;
+      const uint32_t v = c < d.Co ? x[src] : 0u;   // values move as bits; channels past Co are zero padding
+      w[i >> 1] = (i & 1) ? (w[i >> 1] | (v << 16)) : v;
+    }
+    *reinterpret_cast<uint4*>(y) = make_uint4(w[0], w[1], w[2], w[3]);
+    return;
+  }
   if (idx >= (int64_t)batch * d.Ho * d.Wo * d.Cop) return;
   const int c = (int)(idx % d.Cop);
   const int64_t m = idx / d.Cop;
@@ -1358,6 +1401,16 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
         if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, true>, nb, 256, a, s);
         if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, true>, nb, 256, a, s);
         if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, true>, nb, 256, a, s);
+        return (int)hipErrorInvalidValue;
+      }
+      if (hd[(size_t)L.first_desc].gin > 0) {  // grouped convolutions whose tiles walk their own groups only
+        for (int i = 0; i < L.n; ++i) {
+          const Desc& g = hd[(size_t)(L.first_desc + i)];
+          if (g.gin <= 0 || g.gout <= 0 || g.Cp % 64 || g.splits != 1) return (int)hipErrorInvalidValue;
+        }
+        if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false, false, true>, nb, 256, a, s);
+        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, false, true>, nb, 256, a, s);
+        if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false, false, true>, nb, 256, a, s);
         return (int)hipErrorInvalidValue;
       }
       if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false>, nb, 256, a, s);

@@ -104,6 +104,7 @@ fi_status analyze_model(const fi_model_spec& m, ModelPlan& out) {
         n.Wo = (n.W + 2 * n.pad_w - L.kw) / L.stride + 1;
         if (n.Ho < 1 || n.Wo < 1 || n.H + 2 * n.pad < L.kh || n.W + 2 * n.pad_w < L.kw) { set_error("model %s node %d: empty output", nm, i); return FI_EINVAL; }
         n.macs = (uint64_t)n.Ho * n.Wo * n.Co * (uint64_t)(L.op == FI_CONV2D ? n.C / (L.groups > 1 ? L.groups : 1) : 1) * L.kh * L.kw;
+        n.groups = (L.op == FI_CONV2D && L.groups > 1) ? L.groups : 1;
         break;
       case FI_MAXPOOL2D:
       case FI_AVGPOOL2D:

@@ -134,7 +134,13 @@ def test_rectangular_kernels(case, mode):
 
 
 @pytest.mark.parametrize("case", [(128, 128, 32, 3, 1, 1, 14, 14, 2), (64, 96, 4, 3, 2, 1, 15, 17, 2), (48, 48, 48, 3, 1, 1, 9, 9, 1),
-                                  (32, 64, 2, 1, 1, 0, 12, 12, 3), (256, 256, 32, 3, 2, 1, 28, 28, 1)])  # cin, cout, groups, k, stride, pad, H, W, batch
+                                  (32, 64, 2, 1, 1, 0, 12, 12, 3), (256, 256, 32, 3, 2, 1, 28, 28, 1),
+                                  # channel strides that whole reduction tiles divide: a column tile walks its own groups' channels only.
+                                  # One group per 64-channel tile; two groups per tile; groups wider than a tile (tiles straddle them);
+                                  # the 256-row and the 128-row tile; a 1x1 and a 5x5 filter
+                                  (192, 192, 3, 3, 1, 1, 13, 11, 2), (256, 128, 4, 3, 2, 1, 14, 14, 2), (128, 320, 2, 3, 1, 1, 9, 10, 2),
+                                  (128, 128, 32, 3, 1, 1, 56, 56, 24), (128, 128, 32, 3, 1, 1, 32, 32, 16), (256, 192, 8, 1, 1, 0, 12, 12, 2),
+                                  (64, 128, 2, 5, 1, 2, 11, 11, 1)])  # cin, cout, groups, k, stride, pad, H, W, batch
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_grouped_conv(case, mode):
     """Grouped convolution (each output channel sees its own group of input channels), up to one group per channel."""
@@ -260,6 +266,29 @@ def test_slice_branch_concat_shuffle_unit(mode):
     y = m.add(zoo.SHUFFLE, y, groups=2)
     m.add(zoo.CONV, y, cin=58, cout=12, k=1, stride=1, pad=0, act=zoo.NONE)
     _run_case(m, 1300, 2, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+@pytest.mark.parametrize("case", [(64, 16, 24, 2), (64, 8, 20, 4), (48, 0, 48, 3), (120, 56, 64, 2), (24, 0, 24, 3), (64, 32, 32, 1)])  # C, first, width, shuffle groups
+def test_slice_and_shuffle_inside_the_arena_are_exact(case):
+    """Channel slices at vector-aligned and unaligned offsets, widths that do and do not fill whole 8-channel vectors,
+    shuffles in 1..4 groups, all between other nodes (bf16 tensors in the arena: the 8-channel form of the gather):
+    values only move, so the result equals the oracle's bit for bit."""
+    from tests import harness
+    c, first, width, groups = case
+    m = zoo.Model("gath", "bf16", c, 6, 5)
+    a = m.add(zoo.MAXPOOL, -1, k=1, stride=1, pad=0)
+    a = m.add(zoo.SLICE, a, first=first, cout=width)
+    a = m.add(zoo.SHUFFLE, a, groups=groups)
+    m.add(zoo.MAXPOOL, a, k=1, stride=1, pad=0)
+    m.shapes()
+    x = gen.make_input(5 + c, 3, c, 6, 5, "normal", "bf16")
+    blob = np.zeros(64, np.uint8)
+    g = harness.GpuDag([(m, blob, None)], 3)
+    try:
+        y = g.run(x)[0]
+    finally:
+        g.close()
+    assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, True))
 
 
 def test_shuffle_as_output_node_is_exact():
