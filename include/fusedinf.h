@@ -142,6 +142,10 @@ typedef struct {
   void (*pin_free)(void* ptr, void* user);
   void* user;
   uint64_t swap_headroom_bytes; /* extra device bytes fi_load allocates beyond the plan, for later fi_swap_model calls */
+  int32_t copy_concats;      /* 0: producers whose only other readers allow it write straight into the concatenation's
+                              * tensor and the concatenation needs no launch; 1: every concatenation copies its sources.
+                              * The outputs are the same bits either way. */
+  int32_t reserved;          /* 0 */
 } fi_build_opts;
 
 typedef struct {

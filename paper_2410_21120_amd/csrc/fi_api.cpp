@@ -405,6 +405,62 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
+  // ---- concatenations in place --------------------------------------------------------------
+  // A concatenation copies its two sources into one tensor.  When a source's producer can write with a
+  // channel stride other than its own (the MFMA convolution and the bf16 vector kernels can) and whoever
+  // else reads that source can read with such a stride (the depthwise kernels can), the source is stored
+  // inside the concatenation's tensor from the start and the copy disappears: DenseNet blocks, Inception
+  // and fire modules then write every branch once.  Nested concatenations resolve to the outermost tensor.
+  for (Node& nd : g->nodes) { nd.root = -1; nd.chan = 0; nd.elided = 0; }
+  if (!opts->copy_concats && g->wdtype == FI_BF16) {
+    std::vector<std::vector<int32_t>> readers((size_t)total);   // nodes reading a tensor as their first input
+    std::vector<int32_t> as_second((size_t)total, 0);           // times a tensor is a second operand (residual, gate, second source)
+    for (int32_t i = 0; i < total; ++i) {
+      const Node& nd = g->nodes[(size_t)i];
+      if (nd.input >= 0) readers[(size_t)nd.input].push_back(i);
+      if (nd.residual >= 0) as_second[(size_t)nd.residual]++;
+    }
+    std::vector<int8_t> can_elide((size_t)total, 0);
+    auto stored_in_place = [&](int32_t s, int32_t q, bool second) {
+      const Node& S = g->nodes[(size_t)s];
+      const int adt = g->members[(size_t)S.model].spec.act_dtype;
+      if (adt != FI_BF16 || S.is_output || S.out_dtype != FI_BF16 || S.Cop % 8) return false;
+      // the concatenation is the only node that takes S as a second operand (once) or lists it first (once) ...
+      if (as_second[(size_t)s] != (second ? 1 : 0)) return false;
+      int first_uses = 0;
+      for (int32_t r : readers[(size_t)s]) {
+        if (r == q) { ++first_uses; continue; }
+        if (g->nodes[(size_t)r].kind != K_DWCONV) return false;   // ... and every other reader takes an input stride
+      }
+      if (first_uses != (second ? 0 : 1)) return false;
+      switch (S.kind) {
+        case K_CONV_MFMA: return true;
+        case K_DWCONV: case K_MAXPOOL: case K_AVGPOOL: case K_GATHER: return S.Cp % 8 == 0;   // their 8-channel forms
+        case K_CONCAT: return can_elide[(size_t)s] != 0;
+        default: return false;
+      }
+    };
+    for (int32_t i = 0; i < total; ++i) {   // sources come before the concatenation that joins them
+      const Node& Q = g->nodes[(size_t)i];
+      if (Q.kind != K_CONCAT || Q.input < 0 || Q.residual < 0 || Q.input == Q.residual) continue;
+      if (Q.is_output || Q.out_dtype != FI_BF16) continue;   // a model output goes to the caller's buffer: that copy stays
+      const Node& A = g->nodes[(size_t)Q.input];
+      if (A.Co % 8 || Q.Cop % 8) continue;   // the second source starts on a vector boundary and A has no padding channels
+      can_elide[(size_t)i] = stored_in_place(Q.input, i, false) && stored_in_place(Q.residual, i, true);
+    }
+    for (int32_t i = total - 1; i >= 0; --i) {   // outermost first: an inner concatenation inherits its place
+      Node& Q = g->nodes[(size_t)i];
+      if (!can_elide[(size_t)i]) continue;
+      // an inner concatenation that could be elided but whose outer one cannot still owns its tensor (root stays -1)
+      Q.elided = 1;
+      const int32_t root = Q.root >= 0 ? Q.root : i;
+      Node& A = g->nodes[(size_t)Q.input];
+      Node& Bn = g->nodes[(size_t)Q.residual];
+      A.root = root; A.chan = Q.chan;
+      Bn.root = root; Bn.chan = Q.chan + A.Co;
+    }
+  }
+
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
   //      share a launch, FI_MAX_GROUP problems at most --------------------------------------
   // staged inputs: the shared input once per activation dtype, or every member's own input
@@ -450,6 +506,11 @@ static fi_status plan_dag(fi_dag* g) {
     for (int32_t i = 0; i < total; ++i) {
       Node& nd = g->nodes[(size_t)i];
       if (nd.level != lv) continue;
+      if (nd.elided) {   // complete once its second source is written: reported under that launch
+        nd.launch = g->nodes[(size_t)nd.residual].launch;
+        nd.slot = 0;
+        continue;
+      }
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
       const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 16 + (walks_groups(nd, adt) ? 8 : 0) + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 +
                                        ((nd.kind == K_CONV_MFMA || nd.kind == K_FC) && nd.splits > 1 ? 1 : 0));
@@ -496,9 +557,16 @@ static fi_status plan_dag(fi_dag* g) {
     else { StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage]; st.last = std::max(st.last, nd.level); }
     if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.level);
   }
+  for (int32_t i = 0; i < total; ++i) {   // a tensor stored inside a concatenation lives in that node's buffer
+    const Node& nd = g->nodes[(size_t)i];
+    if (nd.root < 0) continue;
+    Node& R = g->nodes[(size_t)nd.root];
+    R.first_level = std::min(R.first_level, nd.first_level);
+    R.last_level = std::max(R.last_level, nd.last_level);
+  }
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
-    nd.out_bytes = nd.is_output ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
+    nd.out_bytes = (nd.is_output || nd.root >= 0) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
     tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.lane, nd.out_bytes, 0};
   }
   const Member& m0 = g->members[0];
@@ -533,6 +601,10 @@ static fi_status plan_dag(fi_dag* g) {
     g->act_bytes = align_up(top ? top : kAlign);
   }
   for (int32_t i = 0; i < total; ++i) g->nodes[(size_t)i].out_off = tens[(size_t)i].off;
+  for (int32_t i = 0; i < total; ++i) {
+    Node& nd = g->nodes[(size_t)i];
+    if (nd.root >= 0) nd.out_off = g->nodes[(size_t)nd.root].out_off + (uint64_t)nd.chan * esize(nd.out_dtype);
+  }
   for (int32_t t = 0; t < n_stage; ++t) g->stages[(size_t)t].off = tens[(size_t)(total + t)].off;
 
   // ---- weight arena: [descriptor table][member 0][member 1]... --------------------------
@@ -623,6 +695,11 @@ static fi_status plan_dag(fi_dag* g) {
       d.tiles_n = L.kind == K_CONV_MFMA ? (nd.Co + tile_bn(L.tile) - 1) / tile_bn(L.tile) : 0;
       d.splits = std::max(1, nd.splits);
       if (walks_groups(nd, adt)) { d.gin = nd.C / nd.groups; d.gout = nd.Co / nd.groups; }
+      {
+        const Node* in = nd.input >= 0 ? &g->nodes[(size_t)nd.input] : nullptr;
+        d.xs = (in && in->root >= 0) ? g->nodes[(size_t)in->root].Cop : d.Cp;
+        d.ys = nd.root >= 0 ? g->nodes[(size_t)nd.root].Cop : d.Cop;
+      }
       d.ws_off = g->act_bytes + nd.ws_off;  // the workspace follows the activation arena
       if (L.kind == K_FC) d.tiles_n = (nd.Co + 31) / 32;
       if (L.kind == K_CONCAT) {

@@ -66,8 +66,11 @@ struct Desc {
   uint64_t ws_off;               // split-K partials, relative to the activation base
   int32_t kw, pad_w;             // dense conv: kernel width and horizontal padding (k, pad are the vertical ones)
   int32_t gin, gout;             // MFMA conv of a grouped convolution: input / output channels per group (0 = dense walk over all channels)
+  int32_t xs, ys;                // elements between neighbouring pixels of the input / output: Cp / Cop, or the channel stride of the
+                                 // concatenation the tensor is stored inside (read by the depthwise kernels, written by the bf16
+                                 // vector kernels and the MFMA convolution; every other kernel sees xs == Cp, ys == Cop)
 };
-static_assert(sizeof(Desc) == 136, "Desc is 136 bytes");
+static_assert(sizeof(Desc) == 144, "Desc is 144 bytes");
 
 struct Node {
   int32_t model, index;
@@ -77,6 +80,9 @@ struct Node {
   int32_t kw, pad_w;             // dense conv: kernel width / horizontal padding (k / pad are the vertical ones)
   int32_t Kp;
   int32_t groups;                // conv2d: channel groups (1 = dense)
+  int32_t root, chan;            // root >= 0: the tensor is stored inside concatenation node `root`, from channel `chan` on, with
+                                 // that node's channel stride, and has no buffer of its own
+  int32_t elided;                // a concatenation whose sources are both stored in place: no launch
   int32_t level;
   int32_t out_dtype;             // FI_F32 / FI_BF16 as stored
   int32_t is_output;

@@ -226,9 +226,9 @@ __device__ __forceinline__ void finish_row4(const KArgs& a, const Desc& d, int p
     for (int t = 0; t < 4; ++t)
       if (o + t < d.Co) y[t] = v[t];
   } else if (sizeof(TA) == 4 || d.out_f32) {
-    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)n * d.ys + o) = make_float4(v[0], v[1], v[2], v[3]);
   } else {
-    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)n * d.Cop + o) =
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)n * d.ys + o) =
         make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
   }
 }
@@ -549,14 +549,14 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
           for (int t = 0; t < 8; ++t)
             if (o + t < d.Co) y[t] = v[t];
         } else if (WIDE || d.out_f32) {
-          float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o;
+          float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.ys + o;
           *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
           *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
         } else {
             u32x4 pk;
           pk[0] = pack_bf16x2(v[0], v[1]); pk[1] = pack_bf16x2(v[2], v[3]);
           pk[2] = pack_bf16x2(v[4], v[5]); pk[3] = pack_bf16x2(v[6], v[7]);
-          u32x4* const yp = reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o);
+          u32x4* const yp = reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.ys + o);
           if (stream_out) __builtin_nontemporal_store(pk, yp); else *yp = pk;
         }
       }
@@ -649,14 +649,14 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
           for (int i = 0; i < 8; ++i)
             if (o + i < d.Co) y[i] = v[i];
         } else if (WIDE || d.out_f32) {
-          float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o;
+          float* y = reinterpret_cast<float*>(a.abase + d.y_off) + (int64_t)m * d.ys + o;
           *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2], v[3]);
           *reinterpret_cast<float4*>(y + 4) = make_float4(v[4], v[5], v[6], v[7]);
         } else {
           uint4 pk;
           pk.x = pack_bf16x2(v[0], v[1]); pk.y = pack_bf16x2(v[2], v[3]);
           pk.z = pack_bf16x2(v[4], v[5]); pk.w = pack_bf16x2(v[6], v[7]);
-            u32x4* const yp = reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.Cop + o);
+            u32x4* const yp = reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + (int64_t)m * d.ys + o);
           if (stream_out) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, pk), yp); else *yp = __builtin_bit_cast(u32x4, pk);
         }
       }
@@ -681,7 +681,7 @@ __global__ void __launch_bounds__(256) gather_kernel(KArgs a) {
     const int c8 = (int)(idx % cv) * 8;
     const int64_t m = idx / cv;
     const uint16_t* x = reinterpret_cast<const uint16_t*>(a.abase + d.x_off) + m * d.Cp;
-    uint16_t* y = reinterpret_cast<uint16_t*>(a.abase + d.y_off) + m * d.Cop + c8;
+    uint16_t* y = reinterpret_cast<uint16_t*>(a.abase + d.y_off) + m * d.ys + c8;
     if (d.stride == 0 && (d.pad & 7) == 0 && c8 + 8 <= d.Co) {   // aligned slice: the 8 channels are one vector of the source too
       *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(x + d.pad + c8);
       return;
@@ -840,7 +840,7 @@ __global__ void __launch_bounds__(256) pool_kernel(KArgs a) {
       const float area = (float)(d.k * d.k);
       o.x = pack_bf16x2(best[0] / area, best[1] / area); o.y = pack_bf16x2(best[2] / area, best[3] / area);
       o.z = pack_bf16x2(best[4] / area, best[5] / area); o.w = pack_bf16x2(best[6] / area, best[7] / area);
-      *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.Cop + c8) = o;
+      *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.ys + c8) = o;
       return;
     }
     // the maxima are bf16 values already: packing is exact
@@ -848,7 +848,7 @@ __global__ void __launch_bounds__(256) pool_kernel(KArgs a) {
     o.y = (__float_as_uint(best[2]) >> 16) | (__float_as_uint(best[3]) & 0xFFFF0000u);
     o.z = (__float_as_uint(best[4]) >> 16) | (__float_as_uint(best[5]) & 0xFFFF0000u);
     o.w = (__float_as_uint(best[6]) >> 16) | (__float_as_uint(best[7]) & 0xFFFF0000u);
-    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.Cop + c8) = o;
+    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.ys + c8) = o;
     return;
   }
   if (idx >= (int64_t)batch * d.Ho * d.Wo * d.Cop) return;
@@ -1015,7 +1015,7 @@ __global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
       const int iw = q * d.stride - d.pad + s;
       if (iw < 0 || iw >= d.W) continue;
       float xv[8], wv[8];
-      load8(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.Cp + c8, xv);
+      load8(x + (((int64_t)n * d.H + ih) * d.W + iw) * d.xs + c8, xv);
       load8(w + (r * d.k + s) * d.Cp + c8, wv);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] += xv[i] * wv[i];
@@ -1040,7 +1040,7 @@ __global__ void __launch_bounds__(256) dwconv_vec_kernel(KArgs a) {
     for (int i = 0; i < 8; ++i)
       if (c8 + i < d.Co) y[i] = acc[i];
   } else {
-    store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c8, acc);
+    store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.ys + c8, acc);
   }
 }
 
@@ -1067,7 +1067,7 @@ __global__ void __launch_bounds__(256) dwconv_strip_kernel(KArgs a) {
   const int q0 = (int)(t % strips) * S;
   const int pp = (int)((t / strips) % d.Ho);
   const int n = (int)(t / ((int64_t)strips * d.Ho));
-  const TA* const xn = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c8;
+  const TA* const xn = reinterpret_cast<const TA*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.xs + c8;
   const bf16_t* const w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off) + c8;
   float acc[S][8];
 #pragma unroll
@@ -1079,13 +1079,13 @@ __global__ void __launch_bounds__(256) dwconv_strip_kernel(KArgs a) {
   for (int r = 0; r < KS; ++r) {
     const int ih = ih0 + r;
     if ((unsigned)ih >= (unsigned)d.H) continue;   // a row outside the image adds nothing
-    const TA* const xr = xn + (int64_t)ih * d.W * d.Cp;
+    const TA* const xr = xn + (int64_t)ih * d.W * d.xs;
     float xv[NPIX][8], wv[KS][8];
 #pragma unroll
     for (int c = 0; c < NPIX; ++c) {
       const int iw = iw0 + c;
       const bool ok = (unsigned)iw < (unsigned)d.W;
-      load8(xr + (ok ? (int64_t)iw * d.Cp : 0), xv[c]);   // always a valid address; masked below
+      load8(xr + (ok ? (int64_t)iw * d.xs : 0), xv[c]);   // always a valid address; masked below
 #pragma unroll
       for (int i = 0; i < 8; ++i) xv[c][i] = ok ? xv[c][i] : 0.0f;
     }
@@ -1123,7 +1123,7 @@ __global__ void __launch_bounds__(256) dwconv_strip_kernel(KArgs a) {
       for (int i = 0; i < 8; ++i)
         if (c8 + i < d.Co) y[i] = v[i];
     } else {
-      store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.Cop + c8, v);
+      store8(reinterpret_cast<TA*>(a.abase + d.y_off) + m * d.ys + c8, v);
     }
   }
 }
@@ -1376,6 +1376,16 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
   }
   const bool wb = L.wdtype == FI_BF16, ab = L.adtype == FI_BF16;
   const int nb = (int)blocks;
+  // Tensors stored inside a concatenation have a pixel stride of their own: only the kernels that take one may see them.
+  for (int i = 0; i < L.n; ++i) {
+    const Desc& t = hd[(size_t)(L.first_desc + i)];
+    if (L.kind == K_STAGE || (t.xs == t.Cp && t.ys == t.Cop)) continue;
+    const bool reads = L.kind == K_DWCONV && wb && ab && hd[(size_t)L.first_desc].vec;
+    const bool writes = ab && !t.ext && !t.out_f32 &&
+                        (L.kind == K_CONV_MFMA || L.kind == K_REDUCE || (L.kind == K_DWCONV && wb && hd[(size_t)L.first_desc].vec) ||
+                         ((L.kind == K_MAXPOOL || L.kind == K_AVGPOOL || L.kind == K_GATHER) && t.vec));
+    if ((t.xs != t.Cp && !reads) || (t.ys != t.Cop && !writes)) return (int)hipErrorInvalidValue;
+  }
   switch (L.kind) {
     case K_STAGE:
       if (wb && ab) return go(stage_kernel<bf16_t, bf16_t>, nb, 256, a, s);

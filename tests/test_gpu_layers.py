@@ -268,6 +268,47 @@ def test_slice_branch_concat_shuffle_unit(mode):
     _run_case(m, 1300, 2, act_dtype="f32" if mode == "bf16_wide" else None)
 
 
+@pytest.mark.parametrize("case", [(16, 8, 3, 9, 7, 2), (64, 32, 4, 28, 28, 4), (24, 16, 2, 5, 5, 1)])   # first width, growth, layers, H, W, batch
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide"])
+def test_dense_block_concatenations(case, mode):
+    """A DenseNet-style block: every layer normalises (per-channel affine + ReLU) everything concatenated so far and appends
+    `growth` new channels.  With bf16 activations the new channels are written straight into the block's final tensor and
+    the affine nodes read its prefixes with that tensor's channel stride; with fp32 activations every concatenation copies."""
+    c0, growth, layers, h, w, b = case
+    m = zoo.Model("dense", "bf16", 8, h, w)
+    t = m.add(zoo.CONV, -1, cin=8, cout=c0, k=3, stride=1, pad=1, act=zoo.RELU)
+    c = c0
+    for _ in range(layers):
+        a = m.add(zoo.DWCONV, t, cin=c, cout=c, k=1, stride=1, pad=0, act=zoo.RELU)
+        a = m.add(zoo.CONV, a, cin=c, cout=4 * growth, k=1, stride=1, pad=0, act=zoo.RELU)
+        a = m.add(zoo.CONV, a, cin=4 * growth, cout=growth, k=3, stride=1, pad=1, act=zoo.NONE)
+        t = m.add(zoo.CONCAT, t, residual=a)
+        c += growth
+    t = m.add(zoo.DWCONV, t, cin=c, cout=c, k=3, stride=2, pad=1, act=zoo.RELU)
+    t = m.add(zoo.GAP, t)
+    m.add(zoo.FC, t, cin=c, cout=10)
+    _run_case(m, 1700 + c0, b, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
+@pytest.mark.parametrize("mode", ["bf16", "bf16_wide"])
+def test_reduction_module_concatenations(mode):
+    """An Inception-style reduction module: a strided convolution, a two-convolution branch, a strided max pool and an
+    average pool of the same input, joined by nested concatenations (pool outputs and convolution outputs side by side in
+    one tensor), then read by a dense convolution."""
+    m = zoo.Model("red", "bf16", 8, 17, 15)
+    x = m.add(zoo.CONV, -1, cin=8, cout=48, k=1, stride=1, pad=0, act=zoo.RELU)
+    b1 = m.add(zoo.CONV, x, cin=48, cout=40, k=3, stride=2, pad=0, act=zoo.RELU)
+    b2 = m.add(zoo.CONV, x, cin=48, cout=16, k=1, stride=1, pad=0, act=zoo.RELU)
+    b2 = m.add(zoo.CONV, b2, cin=16, cout=24, k=3, stride=2, pad=0, act=zoo.RELU)
+    b3 = m.add(zoo.MAXPOOL, x, k=3, stride=2, pad=0)
+    b4 = m.add(zoo.AVGPOOL, x, k=3, stride=2, pad=0)
+    y = m.add(zoo.CONCAT, b1, residual=b2)
+    y = m.add(zoo.CONCAT, y, residual=b3)
+    y = m.add(zoo.CONCAT, y, residual=b4)
+    m.add(zoo.CONV, y, cin=160, cout=12, k=3, stride=1, pad=1, act=zoo.NONE)
+    _run_case(m, 1800, 3, act_dtype="f32" if mode == "bf16_wide" else None)
+
+
 @pytest.mark.parametrize("case", [(64, 16, 24, 2), (64, 8, 20, 4), (48, 0, 48, 3), (120, 56, 64, 2), (24, 0, 24, 3), (64, 32, 32, 1)])  # C, first, width, shuffle groups
 def test_slice_and_shuffle_inside_the_arena_are_exact(case):
     """Channel slices at vector-aligned and unaligned offsets, widths that do and do not fill whole 8-channel vectors,

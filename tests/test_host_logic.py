@@ -474,7 +474,19 @@ def test_concat_and_ceil_pooling_in_the_planner():
     assert (nodes[2].out_c, nodes[2].out_h, nodes[2].out_w) == (40, 9, 9)
     assert (nodes[3].out_h, nodes[3].out_w) == (5, 5)                      # floor would give 4
     assert nodes[0].last_level >= nodes[2].level and nodes[1].last_level >= nodes[2].level
-    assert "concat" in [L.name.decode() for L in d.launches()]
+    # both sources are convolutions nobody else reads: they are written straight into the concatenation's tensor
+    # (16 channels of the first, then the second), which lives from the first of them on and needs no launch
+    assert "concat" not in [L.name.decode() for L in d.launches()]
+    assert nodes[0].out_bytes == 0 and nodes[1].out_bytes == 0 and nodes[2].out_bytes >= 2 * 9 * 9 * 40 * 2
+    assert nodes[0].out_off == nodes[2].out_off and nodes[1].out_off == nodes[2].out_off + 16 * 2
+    assert nodes[2].first_level <= min(nodes[0].level, nodes[1].level)
+    assert nodes[2].launch == nodes[1].launch
+    # ... unless the handle is built to copy
+    spec_c, keep_c = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    dc = fi.Dag([spec_c], 2, fi.HostAllocators(), keepalive=keep_c, copy_concats=True)
+    assert "concat" in [L.name.decode() for L in dc.launches()]
+    assert all(n.out_bytes > 0 for n in dc.nodes()[:3])
+    assert dc.query().n_launches == d.query().n_launches + 1
 
     def broken(edit):
         spec2, keep2 = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
