@@ -373,6 +373,7 @@ static fi_status plan_dag(fi_dag* g) {
             const int64_t nb64 = ((M + 63) / 64) * ((nd.Co + 63) / 64);
             const int ntiles = (nd.Kp + 63) / 64;
             nd.splits = nd.Cp == 4 ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, ntiles / 4), 256 / nb64));
+            if (ntiles < 16) nd.splits = 1;   // a reduction under 1024 elements is over before the extra reduce launch would pay
           }
           // the kernel addresses its input with 32-bit byte offsets through a buffer resource
           if ((uint64_t)B * nd.Ho * nd.Wo >= (1ull << 24)) {  // row indices are decoded with exact float arithmetic
