@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused-DAG hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg3|cfg2] [--swap-requests R]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg3|cfg2|fam:<family>[x<members>][@<batch>]] [--swap-requests R]
 
 A step is one pass of the whole launch schedule (input staging, every member's convolutions,
 pooling, FC) over one synthetic batch that is already resident in HBM.  Prints ONE JSON line:
