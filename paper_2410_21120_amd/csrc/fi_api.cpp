@@ -721,6 +721,18 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
+  // pooling launches whose problems are all 3x3 stride-1 windows on bf16 vectors run the strip kernel
+  // (4 neighbouring outputs per thread; the strip length travels in the otherwise unused tiles_n)
+  for (Launch& L : g->launches) {
+    if (L.kind != K_MAXPOOL && L.kind != K_AVGPOOL) continue;
+    bool strip = L.adtype == FI_BF16;
+    for (int32_t s = 0; s < L.n; ++s) {
+      const Desc& d = g->descs[(size_t)(L.first_desc + s)];
+      strip = strip && d.vec && d.k == 3 && d.stride == 1 && !d.ext;
+    }
+    for (int32_t s = 0; s < L.n; ++s) g->descs[(size_t)(L.first_desc + s)].tiles_n = strip ? 4 : 0;
+  }
+
   // depthwise / global-average launches use the 8-channel vector kernels only when every problem allows it
   for (Launch& L : g->launches) {
     if (L.kind != K_DWCONV && L.kind != K_GAP) continue;

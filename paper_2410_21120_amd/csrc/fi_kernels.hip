@@ -71,7 +71,10 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
       return (int)(((int64_t)batch * d.Ho * ((d.Wo + strip - 1) / strip) * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     }
     case K_MAXPOOL:
-    case K_AVGPOOL: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
+    case K_AVGPOOL: {
+      if (d.vec && d.tiles_n > 1) return (int)(((int64_t)batch * d.Ho * ((d.Wo + d.tiles_n - 1) / d.tiles_n) * (d.Cop / 8) + 255) / 256);   // strip kernel
+      return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
+    }
     case K_GAP: return d.vec ? batch * ((d.Cop / 8 + 7) / 8) : (batch * d.Cop + 255) / 256;
     case K_SOFTMAX: return batch;
     case K_FC: return (d.tiles_n * d.splits * ((batch + 31) / 32) + 3) / 4;
@@ -877,6 +880,71 @@ __global__ void __launch_bounds__(256) pool_kernel(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// 3x3 stride-1 window pooling in strip form (bf16 tensors, 8-channel vectors): a thread owns 4 neighbouring
+// outputs of one output row.  Per window row it loads the 6 input pixels the strip touches once and feeds
+// every output from them (18 loads for 4 outputs instead of 36); taps outside the image are skipped exactly
+// as in pool_kernel, and every output combines its taps in the same (row, column) order.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const bf16_t* p, float* v);
+__device__ __forceinline__ void store8(bf16_t* p, const float* v);
+template <bool AVG>
+__global__ void __launch_bounds__(256) pool_strip_kernel(KArgs a) {
+  constexpr int S = 4, KS = 3, NPIX = S + KS - 1;
+  int p, bid;
+  if (!find_problem(a, AVG ? K_AVGPOOL : K_MAXPOOL, 0, p, bid)) return;
+  const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
+  const int cv = d.Cp / 8, strips = (d.Wo + S - 1) / S;
+  const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
+  if (idx >= (int64_t)batch * d.Ho * strips * cv) return;
+  const int c8 = (int)(idx % cv) * 8;
+  const int64_t t = idx / cv;
+  const int q0 = (int)(t % strips) * S;
+  const int pp = (int)((t / strips) % d.Ho);
+  const int n = (int)(t / ((int64_t)strips * d.Ho));
+  const bf16_t* const xn = reinterpret_cast<const bf16_t*>(a.abase + d.x_off) + (int64_t)n * d.H * d.W * d.Cp + c8;
+  float best[S][8];
+#pragma unroll
+  for (int j = 0; j < S; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) best[j][i] = AVG ? 0.0f : -INFINITY;
+  const int ih0 = pp - d.pad, iw0 = q0 - d.pad;
+#pragma unroll
+  for (int r = 0; r < KS; ++r) {
+    const int ih = ih0 + r;
+    if ((unsigned)ih >= (unsigned)d.H) continue;
+    const bf16_t* const xr = xn + (int64_t)ih * d.W * d.Cp;
+    float xv[NPIX][8];
+    bool ok[NPIX];
+#pragma unroll
+    for (int c = 0; c < NPIX; ++c) {
+      const int iw = iw0 + c;
+      ok[c] = (unsigned)iw < (unsigned)d.W;
+      load8(xr + (ok[c] ? (int64_t)iw * d.Cp : 0), xv[c]);   // always a valid address; skipped below when outside
+    }
+#pragma unroll
+    for (int j = 0; j < S; ++j)
+#pragma unroll
+      for (int sx = 0; sx < KS; ++sx)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float v = xv[j + sx][i];
+          best[j][i] = !ok[j + sx] ? best[j][i] : AVG ? best[j][i] + v : fmaxf(best[j][i], v);
+        }
+  }
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    const int q = q0 + j;
+    if (q >= d.Wo) break;
+    const int64_t m = ((int64_t)n * d.Ho + pp) * d.Wo + q;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = AVG ? best[j][i] / (float)(KS * KS) : best[j][i];
+    store8(reinterpret_cast<bf16_t*>(a.abase + d.y_off) + m * d.ys + c8, v);   // maxima are bf16 values already: the rounding is exact
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // global average pooling: one thread per (image, channel), fp32 sum, divide by H*W
 // ---------------------------------------------------------------------------------
 template <typename TA>
@@ -1443,9 +1511,18 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       return go(dwconv_kernel<float, float>, nb, 256, a, s);
     }
     case K_MAXPOOL:
+    case K_AVGPOOL: {
+      const bool avg = L.kind == K_AVGPOOL;
+      if (hd[(size_t)L.first_desc].tiles_n > 1) {   // the planner found 3x3 stride-1 windows on bf16 vectors in the whole launch
+        for (int i = 0; i < L.n; ++i) {
+          const Desc& t = hd[(size_t)(L.first_desc + i)];
+          if (!ab || !t.vec || t.tiles_n != 4 || t.k != 3 || t.stride != 1 || t.ext) return (int)hipErrorInvalidValue;
+        }
+        return avg ? go(pool_strip_kernel<true>, nb, 256, a, s) : go(pool_strip_kernel<false>, nb, 256, a, s);
+      }
+      if (avg) return ab ? go(pool_kernel<bf16_t, true>, nb, 256, a, s) : go(pool_kernel<float, true>, nb, 256, a, s);
       return ab ? go(pool_kernel<bf16_t, false>, nb, 256, a, s) : go(pool_kernel<float, false>, nb, 256, a, s);
-    case K_AVGPOOL:
-      return ab ? go(pool_kernel<bf16_t, true>, nb, 256, a, s) : go(pool_kernel<float, true>, nb, 256, a, s);
+    }
     case K_GAP: {
       const bool vec = hd[(size_t)L.first_desc].vec != 0;
       if (vec) return ab ? go(gap_vec_kernel<bf16_t>, nb, 256, a, s) : go(gap_vec_kernel<float>, nb, 256, a, s);

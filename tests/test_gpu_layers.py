@@ -120,6 +120,30 @@ def test_maxpool_exact(case, mode):
     assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, False))
 
 
+@pytest.mark.parametrize("case", [(64, 1, 9, 11, 2), (24, 1, 5, 2, 3), (40, 0, 7, 6, 1), (192, 1, 28, 28, 4), (8, 1, 1, 1, 2), (16, 1, 3, 13, 1)])  # C, pad, H, W, batch
+def test_maxpool_3x3_stride1_inside_the_arena_is_exact(case):
+    """The 3x3 stride-1 max pool of an Inception branch (bf16 tensors between other nodes: four outputs per thread),
+    widths that are not multiples of four, with and without padding, all-negative inputs so that padding must not win."""
+    from tests import harness
+    c, p, h, w, b = case
+    m = zoo.Model("p3", "bf16", c, h, w)
+    a = m.add(zoo.MAXPOOL, -1, k=1, stride=1, pad=0)
+    a = m.add(zoo.MAXPOOL, a, k=3, stride=1, pad=p)
+    m.add(zoo.MAXPOOL, a, k=1, stride=1, pad=0)
+    m.shapes()
+    blob = np.zeros(64, np.uint8)
+    x = -np.abs(gen.make_input(4 + c, b, c, h, w, "normal", "bf16")) - 1.0
+    x = gen.bf16_to_f32(gen.bf16_bits(x)).reshape(x.shape)
+    g = harness.GpuDag([(m, blob)], b)
+    try:
+        y = g.run(x)[0]
+        names = [L.name.decode() for L in g.dag.launches()]
+    finally:
+        g.close()
+    assert names.count("maxpool") == 3
+    assert np.array_equal(y, harness.oracle_nhwc(m, blob, x, False))
+
+
 @pytest.mark.parametrize("case", [(128, 128, 1, 7, 1, 3, 17, 17, 2), (128, 192, 7, 1, 1, 3, 17, 17, 2), (384, 384, 1, 3, 1, 1, 8, 8, 2),
                                   (384, 384, 3, 1, 1, 1, 8, 8, 2), (24, 40, 3, 1, 2, 1, 15, 13, 1), (3, 16, 1, 5, 1, 2, 20, 21, 2),
                                   (16, 16, 5, 2, 2, 2, 19, 18, 1)])   # cin, cout, kh, kw, stride, pad, H, W, batch
@@ -207,7 +231,8 @@ def test_maxpool_ceil_mode_exact(case, mode):
     assert y.shape == ref.shape and np.array_equal(y, ref)
 
 
-@pytest.mark.parametrize("case", [(64, 2, 2, 0, 28, 28, 2), (24, 3, 1, 1, 9, 11, 2), (40, 3, 2, 1, 15, 14, 1), (8, 5, 1, 2, 7, 7, 3)])
+@pytest.mark.parametrize("case", [(64, 2, 2, 0, 28, 28, 2), (24, 3, 1, 1, 9, 11, 2), (40, 3, 2, 1, 15, 14, 1), (8, 5, 1, 2, 7, 7, 3),
+                                  (192, 3, 1, 1, 17, 17, 3), (16, 3, 1, 0, 6, 5, 2)])
 @pytest.mark.parametrize("mode", ["bf16", "bf16_wide", "f32"])
 def test_avgpool_between_convs(case, mode):
     """Window average pooling (divisor = window area, zero padding counted) between two convolutions."""
