@@ -412,7 +412,7 @@ static fi_status plan_dag(fi_dag* g) {
   // else reads that source can read with such a stride (the depthwise kernels can), the source is stored
   // inside the concatenation's tensor from the start and the copy disappears: DenseNet blocks, Inception
   // and fire modules then write every branch once.  Nested concatenations resolve to the outermost tensor.
-  for (Node& nd : g->nodes) { nd.root = -1; nd.chan = 0; nd.elided = 0; }
+  for (Node& nd : g->nodes) { nd.root = -1; nd.chan = 0; nd.elided = 0; nd.pre = -1; }
   if (!opts->copy_concats && g->wdtype == FI_BF16) {
     std::vector<std::vector<int32_t>> readers((size_t)total);   // nodes reading a tensor as their first input
     std::vector<int32_t> as_second((size_t)total, 0);           // times a tensor is a second operand (residual, gate, second source)
@@ -462,6 +462,37 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
+  // ---- per-channel affine nodes applied by the convolution that reads them -------------------
+  // y = act(x * scale[c] + shift[c]) (a 1x1 depthwise node: the normalisation + ReLU in front of a DenseNet
+  // layer's 1x1 convolution) read by nothing but one pointwise MFMA convolution: that convolution applies it to
+  // its input vectors on their way into LDS, with the arithmetic and the single rounding of the depthwise
+  // kernel, so the bits are the same and the node needs neither a launch nor a tensor.
+  if (!opts->separate_affine && g->wdtype == FI_BF16) {
+    std::vector<int32_t> n_readers((size_t)total, 0), only_reader((size_t)total, -1);
+    for (int32_t i = 0; i < total; ++i) {
+      const Node& nd = g->nodes[(size_t)i];
+      if (nd.input >= 0) { n_readers[(size_t)nd.input]++; only_reader[(size_t)nd.input] = i; }
+      if (nd.residual >= 0) n_readers[(size_t)nd.residual] += 2;   // a second operand: never fused
+    }
+    for (int32_t i = 0; i < total; ++i) {
+      Node& A = g->nodes[(size_t)i];
+      const int adt = g->members[(size_t)A.model].spec.act_dtype;
+      if (A.kind != K_DWCONV || A.k != 1 || A.stride != 1 || A.pad != 0 || A.residual >= 0 || A.input < 0) continue;
+      if (adt != FI_BF16 || A.is_output || A.out_dtype != FI_BF16 || A.root >= 0) continue;
+      if (!(A.act == FI_ACT_NONE || A.act == FI_ACT_RELU || A.act == FI_ACT_RELU6)) continue;   // act(0) = 0 keeps padding channels zero
+      if (n_readers[(size_t)i] != 1) continue;
+      Node& V = g->nodes[(size_t)only_reader[(size_t)i]];
+      if (V.kind != K_CONV_MFMA || V.k != 1 || V.kw != 1 || V.stride != 1 || V.pad != 0 || V.pad_w != 0) continue;
+      if (V.groups > 1 || V.Cp == 4 || V.Cp != A.Cp) continue;
+      const Node& T = g->nodes[(size_t)A.input];
+      if (T.out_dtype != FI_BF16) continue;
+      const int64_t stride = T.root >= 0 ? g->nodes[(size_t)T.root].Cop : T.Cop;
+      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * 2 >= (1ull << 31)) continue;   // the conv kernel's 32-bit byte offsets
+      V.pre = i;
+      A.elided = 1;
+    }
+  }
+
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
   //      share a launch, FI_MAX_GROUP problems at most --------------------------------------
   // staged inputs: the shared input once per activation dtype, or every member's own input
@@ -507,13 +538,13 @@ static fi_status plan_dag(fi_dag* g) {
     for (int32_t i = 0; i < total; ++i) {
       Node& nd = g->nodes[(size_t)i];
       if (nd.level != lv) continue;
-      if (nd.elided) {   // complete once its second source is written: reported under that launch
-        nd.launch = g->nodes[(size_t)nd.residual].launch;
+      if (nd.elided) {   // a concatenation in place is complete once its second source is written: reported under that launch
+        nd.launch = nd.kind == K_CONCAT ? g->nodes[(size_t)nd.residual].launch : 0;   // (a fused affine node: set below)
         nd.slot = 0;
         continue;
       }
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 16 + (walks_groups(nd, adt) ? 8 : 0) + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 +
+      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 32 + (nd.pre >= 0 ? 16 : 0) + (walks_groups(nd, adt) ? 8 : 0) + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 +
                                        ((nd.kind == K_CONV_MFMA || nd.kind == K_FC) && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
       if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
@@ -545,6 +576,9 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
+  for (const Node& nd : g->nodes)
+    if (nd.pre >= 0) { g->nodes[(size_t)nd.pre].launch = nd.launch; g->nodes[(size_t)nd.pre].slot = nd.slot; }
+
   // ---- activation arena: live range of every stored tensor, then first-fit by size -----
   const int32_t n_stage = (int32_t)g->stages.size();
   std::vector<Tensor> tens((size_t)total + (size_t)n_stage);
@@ -557,6 +591,10 @@ static fi_status plan_dag(fi_dag* g) {
     if (nd.input >= 0) g->nodes[(size_t)nd.input].last_level = std::max(g->nodes[(size_t)nd.input].last_level, nd.level);
     else { StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage]; st.last = std::max(st.last, nd.level); }
     if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.level);
+    if (nd.pre >= 0) {   // the convolution reads the fused affine node's input itself
+      Node& T = g->nodes[(size_t)g->nodes[(size_t)nd.pre].input];
+      T.last_level = std::max(T.last_level, nd.level);
+    }
   }
   for (int32_t i = 0; i < total; ++i) {   // a tensor stored inside a concatenation lives in that node's buffer
     const Node& nd = g->nodes[(size_t)i];
@@ -567,7 +605,7 @@ static fi_status plan_dag(fi_dag* g) {
   }
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
-    nd.out_bytes = (nd.is_output || nd.root >= 0) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
+    nd.out_bytes = (nd.is_output || nd.root >= 0 || (nd.elided && nd.kind == K_DWCONV)) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
     tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.lane, nd.out_bytes, 0};
   }
   const Member& m0 = g->members[0];
@@ -698,6 +736,13 @@ static fi_status plan_dag(fi_dag* g) {
       if (walks_groups(nd, adt)) { d.gin = nd.C / nd.groups; d.gout = nd.Co / nd.groups; }
       {
         const Node* in = nd.input >= 0 ? &g->nodes[(size_t)nd.input] : nullptr;
+        d.pw_off = d.pb_off = kNone;
+        if (nd.pre >= 0) {   // read the affine node's input, apply the node on the way in
+          const Node& A = g->nodes[(size_t)nd.pre];
+          in = &g->nodes[(size_t)A.input];
+          d.x_off = in->out_off;
+          d.pw_off = A.w_off; d.pb_off = A.b_off; d.pre_act = A.act;
+        }
         d.xs = (in && in->root >= 0) ? g->nodes[(size_t)in->root].Cop : d.Cp;
         d.ys = nd.root >= 0 ? g->nodes[(size_t)nd.root].Cop : d.Cop;
       }

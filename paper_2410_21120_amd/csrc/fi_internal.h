@@ -69,8 +69,11 @@ struct Desc {
   int32_t xs, ys;                // elements between neighbouring pixels of the input / output: Cp / Cop, or the channel stride of the
                                  // concatenation the tensor is stored inside (read by the depthwise kernels, written by the bf16
                                  // vector kernels and the MFMA convolution; every other kernel sees xs == Cp, ys == Cop)
+  uint64_t pw_off, pb_off;       // MFMA conv with a fused per-channel affine on its input: scale (bf16 [Cp]) and shift (fp32 [Cp])
+                                 // in the weight arena (kNone = no such stage)
+  int32_t pre_act, reserved;     // activation of that stage
 };
-static_assert(sizeof(Desc) == 144, "Desc is 144 bytes");
+static_assert(sizeof(Desc) == 168, "Desc is 168 bytes");
 
 struct Node {
   int32_t model, index;
@@ -82,7 +85,9 @@ struct Node {
   int32_t groups;                // conv2d: channel groups (1 = dense)
   int32_t root, chan;            // root >= 0: the tensor is stored inside concatenation node `root`, from channel `chan` on, with
                                  // that node's channel stride, and has no buffer of its own
-  int32_t elided;                // a concatenation whose sources are both stored in place: no launch
+  int32_t elided;                // no launch: a concatenation whose sources are both stored in place, or a per-channel affine
+                                 // node that the convolution reading it applies while loading its input
+  int32_t pre;                   // MFMA conv: the per-channel affine node fused into its input side (-1 = none)
   int32_t level;
   int32_t out_dtype;             // FI_F32 / FI_BF16 as stored
   int32_t is_output;

@@ -246,9 +246,15 @@ __device__ __forceinline__ void finish_row4(const KArgs& a, const Desc& d, int p
 // tile then needs only the input channels of the groups its output channels belong to: per filter tap the
 // reduction walks channels [c_lo, c_hi) (whole 64-element tiles; the planner guarantees Cp % 64 == 0)
 // instead of all Cp.  The skipped products are exact zeros, so the sums are the dense walk's.
-template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false>
+// PRE: a pointwise convolution whose input goes through a per-channel affine stage first,
+// x' = act(x * scale[c] + shift[c]) rounded to bf16 (the 1x1 depthwise node in front of it, which then has no
+// launch of its own): applied to every input vector between its load and its LDS store, with the depthwise
+// kernel's operations (product and sum rounded separately, one rounding to bf16).  The input may sit inside a
+// concatenation's tensor, so its pixel stride is Desc.xs.
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false, bool PRE = false>
 __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   static_assert(!GROUPED || (!WIDE && !C4), "the group walk exists for bf16 activations with 8-channel vectors");
+  static_assert(!PRE || (!WIDE && !C4 && !GROUPED), "the fused affine stage exists for dense pointwise convolutions on bf16 activations");
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
   constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
   constexpr int AE = WIDE ? 4 : 2;       // bytes per stored activation element
@@ -283,8 +289,11 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   const int wm = wave / WGN, wn = wave % WGN;
 
   const bf16_t* __restrict__ w = reinterpret_cast<const bf16_t*>(a.wbase + d.w_off);
-  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(a.abase + d.x_off), 0, (int)((int64_t)batch * d.H * d.W * d.Cp * AE), 0x00020000);
+  // bytes of the input this launch may touch: all pixels at their stride (PRE: the last pixel ends after its Cp channels)
+  const int x_bytes = PRE ? (int)((((int64_t)batch * d.H * d.W - 1) * d.xs + d.Cp) * AE) : (int)((int64_t)batch * d.H * d.W * d.Cp * AE);
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.abase + d.x_off), 0, batch > 0 ? x_bytes : 0, 0x00020000);
+  const bf16_t* const pre_w = PRE ? reinterpret_cast<const bf16_t*>(a.wbase + d.pw_off) : nullptr;
+  const float* const pre_b = PRE ? reinterpret_cast<const float*>(a.wbase + d.pb_off) : nullptr;
 
   // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
   const int srow = tid >> 3, kvec = (tid & 7) * 8;
@@ -298,7 +307,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     const int m = m0 + srow + RPP * i;
     const bool ok = m < M;
     if (pointwise) {
-      a_row[i] = (ok ? m : 0) * d.Cp * AE;
+      a_row[i] = (ok ? m : 0) * (PRE ? d.xs : d.Cp) * AE;
       a_rc[i] = ok ? 0x10001 : 0;
       continue;
     }
@@ -359,6 +368,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // One register stage feeds one LDS buffer: fetch one tile ahead, two barriers per tile.
   u32x4 av[1][AR][AV];
   uint4 bv[1][BR];
+  uint4 pre_s[1];        // PRE: scale (8 bf16) and shift (8 fp32) of this thread's channels in the tile being fetched
+  float4 pre_t[1][2];
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
 
 #define FI_FETCH(KT, S)                                                                           \
@@ -393,6 +404,12 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
         }                                                                                         \
       }                                                                                           \
     }                                                                                             \
+    if constexpr (PRE) { /* channels past Cp (the tile tail) have walked on to filter row 1: no stage, the input reads as zero */ \
+      const bool pok = kr == 0;                                                                   \
+      pre_s[S] = pok ? *reinterpret_cast<const uint4*>(pre_w + kc) : make_uint4(0, 0, 0, 0);      \
+      pre_t[S][0] = pok ? *reinterpret_cast<const float4*>(pre_b + kc) : make_float4(0, 0, 0, 0); \
+      pre_t[S][1] = pok ? *reinterpret_cast<const float4*>(pre_b + kc + 4) : make_float4(0, 0, 0, 0); \
+    }                                                                                             \
     const bool bok = !(b_tail && (KT) == ntiles_all - 1 && kvec >= 32);                           \
     /* position of this tile in a weight row, in 8-element vectors past the thread's own kvec */  \
     const int wt = GROUPED ? ((kr * d.kw + ks) * d.Cp + kc - kvec) >> 3 : (KT) * (BK / 8);        \
@@ -414,7 +431,21 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     bf16_t* const Ap = As + (S) * STAGE;                                                          \
     bf16_t* const Bp = Bs + (S) * STAGE;                                                          \
     _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
-      if constexpr (!WIDE) {                                                                      \
+      if constexpr (PRE) {                                                                        \
+        const uint32_t sw[4] = {pre_s[S].x, pre_s[S].y, pre_s[S].z, pre_s[S].w};                  \
+        const float sh[8] = {pre_t[S][0].x, pre_t[S][0].y, pre_t[S][0].z, pre_t[S][0].w,          \
+                             pre_t[S][1].x, pre_t[S][1].y, pre_t[S][1].z, pre_t[S][1].w};         \
+        float v[8];                                                                               \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
+          const uint32_t xw = av[S][i][0][e];                                                     \
+          v[2 * e] = __fadd_rn(__fmul_rn(__uint_as_float(xw << 16), __uint_as_float(sw[e] << 16)), sh[2 * e]); \
+          v[2 * e + 1] = __fadd_rn(__fmul_rn(__uint_as_float(xw & 0xFFFF0000u), __uint_as_float(sw[e] & 0xFFFF0000u)), sh[2 * e + 1]); \
+        }                                                                                         \
+        activate_n<8>(v, d.pre_act);                                                              \
+        u32x4 pk;                                                                                 \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) pk[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]); \
+        *reinterpret_cast<u32x4*>(&Ap[(srow + RPP * i) * LDS_STRIDE + kvec]) = pk;                \
+      } else if constexpr (!WIDE) {                                                               \
         *reinterpret_cast<u32x4*>(&Ap[(srow + RPP * i) * LDS_STRIDE + kvec]) = av[S][i][0];       \
       } else {                                                                                    \
         u32x4 hi, lo;                                                                             \
@@ -1448,7 +1479,8 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
   for (int i = 0; i < L.n; ++i) {
     const Desc& t = hd[(size_t)(L.first_desc + i)];
     if (L.kind == K_STAGE || (t.xs == t.Cp && t.ys == t.Cop)) continue;
-    const bool reads = L.kind == K_DWCONV && wb && ab && hd[(size_t)L.first_desc].vec;
+    const bool reads = (L.kind == K_DWCONV && wb && ab && hd[(size_t)L.first_desc].vec) ||
+                       ((L.kind == K_CONV_MFMA || L.kind == K_REDUCE) && ab && t.pw_off != kNone);   // (the reduce launch shares the node's descriptor and reads no input)
     const bool writes = ab && !t.ext && !t.out_f32 &&
                         (L.kind == K_CONV_MFMA || L.kind == K_REDUCE || (L.kind == K_DWCONV && wb && hd[(size_t)L.first_desc].vec) ||
                          ((L.kind == K_MAXPOOL || L.kind == K_AVGPOOL || L.kind == K_GATHER) && t.vec));
@@ -1490,6 +1522,19 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
         if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, false, true>, nb, 256, a, s);
         if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false, false, true>, nb, 256, a, s);
         return (int)hipErrorInvalidValue;
+      }
+      if (hd[(size_t)L.first_desc].pw_off != kNone) {  // pointwise convolutions that apply a per-channel affine stage to their input
+        for (int i = 0; i < L.n; ++i) {
+          const Desc& t = hd[(size_t)(L.first_desc + i)];
+          if (t.pw_off == kNone || t.pb_off == kNone || t.k != 1 || t.kw != 1 || t.stride != 1 || t.pad != 0 || t.pad_w != 0 || t.gin > 0 ||
+              t.xs < t.Cp || t.Cp % 8 || (uint64_t)t.H * t.W * (uint64_t)t.xs * 2 * (uint64_t)a.batch[i] >= (1ull << 31))
+            return (int)hipErrorInvalidValue;
+        }
+        if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false, false, false, true>, nb, 256, a, s);
+        if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false, false, false, true>, nb, 256, a, s);
+        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false, false, false, true>, nb, 256, a, s);
+        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, false, false, true>, nb, 256, a, s);
+        return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false, false, false, true>, nb, 256, a, s);
       }
       if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false>, nb, 256, a, s);
       if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false>, nb, 256, a, s);

@@ -212,6 +212,7 @@ fi_build_opts options(Rng& r) {
   o.serial_lanes = r.chance(30);
   o.per_member_inputs = r.chance(30);
   o.copy_concats = r.chance(30);
+  o.separate_affine = r.chance(30);
   o.pin_alloc = host_alloc; o.pin_free = host_free;   // keeps the build off the HIP runtime
   o.dev_alloc = host_alloc; o.dev_free = host_free;
   return o;

@@ -407,3 +407,50 @@ def test_concatenations_in_place_equal_copied_ones(fam):
     for r0, r1 in zip(res[False], res[True]):
         for y0, y1 in zip(r0, r1):
             assert np.isfinite(y0).all() and np.array_equal(y0, y1)
+
+
+def _dense_block(c0, growth, layers, h, w):
+    m = zoo.Model("dense", "bf16", 8, h, w)
+    t = m.add(zoo.CONV, -1, cin=8, cout=c0, k=3, stride=1, pad=1, act=zoo.RELU)
+    c = c0
+    for _ in range(layers):
+        a = m.add(zoo.DWCONV, t, cin=c, cout=c, k=1, stride=1, pad=0, act=zoo.RELU)
+        a = m.add(zoo.CONV, a, cin=c, cout=4 * growth, k=1, stride=1, pad=0, act=zoo.RELU)
+        a = m.add(zoo.CONV, a, cin=4 * growth, cout=growth, k=3, stride=1, pad=1, act=zoo.NONE)
+        t = m.add(zoo.CONCAT, t, residual=a)
+        c += growth
+    t = m.add(zoo.DWCONV, t, cin=c, cout=c, k=1, stride=1, pad=0, act=zoo.RELU6)     # a transition: affine, 1x1 convolution, pooling
+    t = m.add(zoo.CONV, t, cin=c, cout=c // 2, k=1, stride=1, pad=0, act=zoo.NONE)
+    t = m.add(zoo.AVGPOOL, t, k=2, stride=2, pad=0)
+    t = m.add(zoo.GAP, t)
+    m.add(zoo.FC, t, cin=c // 2, cout=10)
+    return m.shapes()
+
+
+@pytest.mark.parametrize("case", ["densenet121", "densenet161", (16, 8, 3, 9, 7), (64, 32, 5, 28, 28), (24, 16, 2, 6, 6), (200, 40, 2, 14, 14)])
+def test_affine_applied_by_the_convolution_equals_its_own_launch(case):
+    """The per-channel affine + ReLU in front of a dense layer's 1x1 convolution, applied by that convolution while it
+    loads its input (no launch, no tensor) against a handle that runs it as a depthwise launch: fewer launches, the
+    same bits -- whole DenseNets and blocks whose channel counts leave ragged reduction tiles, split reductions and
+    inputs inside a concatenation's tensor; also with copied concatenations (the input then has its own stride)."""
+    from tests import harness
+    if isinstance(case, str):
+        m, hw = zoo.FAMILIES[case](hw=64), (64, 64)
+    else:
+        m, hw = _dense_block(*case), case[3:]
+    blobs = [gen.make_blob(m, 400 + i) for i in range(2)]
+    x = gen.make_input(12, 3, m.in_c, hw[0], hw[1], "normal", "bf16")
+    res, launches = {}, {}
+    for key, kw in (("fused", {}), ("separate", dict(separate_affine=True)), ("fused_copy", dict(copy_concats=True)),
+                    ("plain", dict(separate_affine=True, copy_concats=True))):
+        g = harness.GpuDag([(m, b, None) for b in blobs], 3, **kw)
+        try:
+            launches[key] = g.dag.query().n_launches
+            res[key] = [g.run(x), g.run(x[:1])]
+        finally:
+            g.close()
+    assert launches["fused"] < launches["separate"] < launches["plain"] and launches["fused_copy"] < launches["plain"]
+    for key in ("separate", "fused_copy", "plain"):
+        for r0, r1 in zip(res["fused"], res[key]):
+            for y0, y1 in zip(r0, r1):
+                assert np.isfinite(y0).all() and np.array_equal(y0, y1), key
