@@ -126,6 +126,37 @@ def test_config4_eight_resnet50_batch32_sampled():
     assert not np.array_equal(ys[0], ys[1])
 
 
+@pytest.mark.parametrize("fam", ["resnext50_32x4d", "densenet121", "googlenet", "squeezenet1_1"])
+def test_full_size_family_batch32_sampled(fam):
+    """Two identical-architecture members at the family's full image size and batch 32, the launch configuration the
+    per-family benchmark times (64-column group-walking tiles for ResNeXt; dense blocks written in place with the
+    affine stage applied by the 1x1 convolutions for DenseNet; Inception modules and fire modules written in place,
+    four-output pooling strips); the oracle checks two sampled images per member."""
+    from tests import harness
+    mem = [_member(fam, 2000 + i) for i in range(2)]
+    hw = mem[0][0].in_h
+    x = gen.make_input(9, 32, 3, hw, hw, "normal", "bf16")
+    g = harness.GpuDag(mem, 32)
+    try:
+        ys = g.run(x)
+    finally:
+        g.close()
+    units, picks = [], []
+    for i, (m, b, _) in enumerate(mem):
+        imgs = [(3 + 11 * i) % 32, (30 - 7 * i) % 32]
+        picks.append(imgs)
+        for img in imgs:
+            units.append((m, b, x[img:img + 1], False))
+            units.append((m, b, x[img:img + 1], True))
+    res = harness.oracle_units(units)
+    for i in range(2):
+        ref_f = np.concatenate([res[(i * 2 + j) * 2] for j in range(2)])
+        ref_s = np.concatenate([res[(i * 2 + j) * 2 + 1] for j in range(2)])
+        _check_member(f"{fam}[{i}]", ys[i][picks[i]], ref_f, ref_s, 1e-2)
+        assert np.isfinite(ys[i]).all()
+    assert not np.array_equal(ys[0], ys[1])
+
+
 def test_further_table3_families_fused():
     """Further families of the paper's Table III (AlexNet, VGG-11/13/19, ResNet-34/101/152, Wide ResNet-50-2/101-2,
     MnasNet 1.0; SqueezeNet 1.0 / 1.1 and GoogLeNet with channel concatenation and pooling sizes that round up; ResNeXt-50
