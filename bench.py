@@ -100,6 +100,8 @@ def main():
     x = gen.make_input(7, B, m0.in_c, m0.in_h, m0.in_w, "normal", "bf16")
     xin = torch.from_numpy(gen.to_nhwc_storage(x, "bf16").view(np.int16)).cuda()
     assert xin.numel() == B * m0.in_h * m0.in_w * m0.in_c
+    check_buffers = lambda d: (xin.numel() * xin.element_size() == B * d.query().input_image_bytes and
+                               all(o.numel() * 4 == B * mi.output_row_bytes for mi, o in zip(d.members(), outs)))
     outs = [torch.zeros((B, m.layers[-1].cout), dtype=torch.float32, device="cuda:0") for m, _, _ in members]
     optr = [o.data_ptr() for o in outs]
 
@@ -123,6 +125,7 @@ def main():
     t_load = time.perf_counter() - t0
     hbm_delta = free0 - torch.cuda.mem_get_info()[0]   # what the device reports (allocator granularity included)
     q = dag.query()
+    assert check_buffers(dag), "input / output buffers do not have the sizes the handle reads and writes"
     for _ in range(a.warmup):
         dag.run(xin.data_ptr(), B, optr, stream)
     torch.cuda.synchronize()
@@ -274,11 +277,11 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "9cf94a05084e4f7a25e9318800f60fe72024e5b5098aa84945e275d53657481f",
+    "sources_sha256": "c8a7d388cdfcc674242f63c74dceedc6216a36609ca9d17f65d4bcc3807f8cfe",
     "workload": "cfg4",
     "kernel": "conv_mfma_128x128",
     "launches_per_step": 54,
-    "fetch_kib_per_step": 2891516.4, "write_kib_per_step": 3976448.0,
+    "fetch_kib_per_step": 2891339.8, "write_kib_per_step": 3976448.0,
     "fetch_scale": 2.0, "write_scale": 1.0,
 }
 

@@ -165,6 +165,8 @@ typedef struct {
   uint64_t last_h2d_bytes;   /* bytes moved by the most recent fi_load or fi_swap_model */
   int32_t last_h2d_copies;   /* copies issued by the most recent fi_load or fi_swap_model */
   int32_t reserved;
+  uint64_t input_image_bytes; /* one input image [in_h, in_w, in_c] in the weight dtype: a run over `batch` images reads
+                               * batch x this many bytes from the input pointer it is given, so size the buffer from it */
 } fi_dag_info;
 
 typedef struct {
@@ -172,6 +174,7 @@ typedef struct {
   int32_t lane;                     /* launch lane of the member */
   int32_t first_node, n_nodes;      /* its nodes are [first_node, first_node + n_nodes) */
   int32_t reserved;
+  uint64_t output_row_bytes;        /* one image's output row (fp32): a run writes batch x this many bytes to the member's output pointer */
 } fi_member_info;
 
 /* Introspection of the compiled DAG (tests, reports). */

@@ -56,7 +56,7 @@ class fi_dag_info(C.Structure):
                 ("n_nodes", C.c_int32), ("n_levels", C.c_int32), ("n_launches", C.c_int32),
                 ("n_device_allocs", C.c_int32), ("n_h2d_copies", C.c_int32), ("state", C.c_int32),
                 ("n_lanes", C.c_int32), ("device_capacity", C.c_uint64), ("last_h2d_bytes", C.c_uint64),
-                ("last_h2d_copies", C.c_int32), ("reserved", C.c_int32)]
+                ("last_h2d_copies", C.c_int32), ("reserved", C.c_int32), ("input_image_bytes", C.c_uint64)]
 
 
 class fi_sched_opts(C.Structure):
@@ -81,7 +81,7 @@ class fi_server_stats(C.Structure):
 
 class fi_member_info(C.Structure):
     _fields_ = [("arena_off", C.c_uint64), ("packed_bytes", C.c_uint64), ("lane", C.c_int32),
-                ("first_node", C.c_int32), ("n_nodes", C.c_int32), ("reserved", C.c_int32)]
+                ("first_node", C.c_int32), ("n_nodes", C.c_int32), ("reserved", C.c_int32), ("output_row_bytes", C.c_uint64)]
 
 
 class fi_node_info(C.Structure):

@@ -818,6 +818,10 @@ fi_status fi_query(const fi_dag* g, fi_dag_info* info) {
   info->device_capacity = g->dev_capacity;
   info->last_h2d_bytes = g->last_h2d_bytes;
   info->last_h2d_copies = g->last_h2d_copies;
+  if (!g->members.empty()) {
+    const fi_model_spec& m0 = g->members[0].spec;
+    info->input_image_bytes = (uint64_t)m0.in_h * m0.in_w * m0.in_c * esize(m0.dtype);
+  }
   return FI_OK;
 }
 
@@ -838,6 +842,8 @@ fi_status fi_member(const fi_dag* g, int32_t m, fi_member_info* o) {
   std::memset(o, 0, sizeof(*o));
   o->arena_off = mb.arena_off; o->packed_bytes = mb.plan.packed_bytes;
   o->lane = mb.lane; o->first_node = mb.node0; o->n_nodes = (int32_t)mb.plan.nodes.size();
+  for (const Node& nd : g->nodes)
+    if (nd.model == m && nd.is_output) o->output_row_bytes = (uint64_t)nd.Ho * nd.Wo * nd.Co * 4;
   return FI_OK;
 }
 

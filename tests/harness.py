@@ -52,6 +52,8 @@ class GpuDag:
         st = gen.to_nhwc_storage(x_nchw, dtype)
         xin = torch.from_numpy(st.view(np.int16) if dtype == "bf16" else st).cuda()
         b = x_nchw.shape[0]
+        # the buffer handed over holds exactly what the handle will read
+        assert xin.numel() * xin.element_size() == b * self.dag.query().input_image_bytes
         if getattr(self, "keep_buffers", None) and self.keep_buffers[0] == b:
             _, kin, kouts = self.keep_buffers  # same device buffers as last time: lets a captured graph replay
             kin.copy_(xin)

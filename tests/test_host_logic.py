@@ -477,6 +477,8 @@ def test_concat_and_ceil_pooling_in_the_planner():
     # both sources are convolutions nobody else reads: they are written straight into the concatenation's tensor
     # (16 channels of the first, then the second), which lives from the first of them on and needs no launch
     assert "concat" not in [L.name.decode() for L in d.launches()]
+    # the handle tells its caller how large the buffers of a run are
+    assert d.query().input_image_bytes == 9 * 9 * 8 * 2 and d.members()[0].output_row_bytes == 5 * 5 * 10 * 4
     assert nodes[0].out_bytes == 0 and nodes[1].out_bytes == 0 and nodes[2].out_bytes >= 2 * 9 * 9 * 40 * 2
     assert nodes[0].out_off == nodes[2].out_off and nodes[1].out_off == nodes[2].out_off + 16 * 2
     assert nodes[2].first_level <= min(nodes[0].level, nodes[1].level)
