@@ -88,7 +88,10 @@ def test_random_graphs_keep_their_bits_under_every_build_option(seed):
         packed.append((m, t.numpy(), act))
     variants = dict(ungrouped=(mem, dict(group_levels=False)), serial=(mem, dict(serial_lanes=True)), graph=(mem, dict(use_graph=True)),
                     per_model_copies=(packed, dict(packed=True, load_mode=fi.FI_LOAD_PER_MODEL)),
-                    packed_one_copy=(packed, dict(packed=True)))
+                    packed_one_copy=(packed, dict(packed=True)),
+                    # concatenations copied instead of written in place, affine nodes as launches of their own
+                    copied_concats=(mem, dict(copy_concats=True)), separate_affine=(mem, dict(separate_affine=True)),
+                    plain=(mem, dict(copy_concats=True, separate_affine=True, group_levels=False)))
     for name, (members, kw) in variants.items():
         for i, y in enumerate(run(members, x, **kw)):
             assert np.array_equal(y, base[i]), f"{name}: member {i}"
@@ -173,3 +176,43 @@ def test_large_random_graphs_fused(seed):
     ref_w = nhwc(refs[4])
     floor = 1e-5 * np.sqrt(ref_w.size) / max(float(np.linalg.norm(ref_w)), 1e-30)
     assert harness.rel_l2(ys[2], ref_w) <= WIDE_TOL + floor
+
+
+@pytest.mark.parametrize("seed", range(0, 72, 3))
+def test_random_graphs_with_concatenating_blocks(seed):
+    """Random graphs in which dense layers, modules with a pooling branch and slice / branch / concatenate units sit
+    between the random operators (channel counts in multiples of 8): concatenations written in place next to ones
+    that must copy, affine nodes absorbed by their convolution next to ones with other readers.  Two members; the
+    optimised schedule equals, bit for bit, the schedule that copies every concatenation and launches every affine
+    node, and that plain schedule's bf16 member meets the oracle as in the test above."""
+    from tests import harness
+    first = randnet.random_model(seed, aligned=True)
+    second = randnet.random_model(seed + 1000, in_c=first.in_c, hw=(first.in_h, first.in_w), aligned=True)
+    batch = 1 + seed % 3
+    mem = [(m, gen.make_blob(m, 8000 + seed + i), None) for i, m in enumerate((first, second))]
+    x = gen.make_input(77 + seed, batch, first.in_c, first.in_h, first.in_w, "normal", "bf16")
+    print(f"seed {seed}: batch {batch}, input {first.in_c}x{first.in_h}x{first.in_w}, nodes {[len(m[0].layers) for m in mem]}", flush=True)
+    res, launches = {}, {}
+    for key, kw in (("fast", {}), ("plain", dict(copy_concats=True, separate_affine=True))):
+        g = harness.GpuDag(mem, batch + 1, **kw)
+        try:
+            launches[key] = g.dag.query().n_launches
+            res[key] = g.run(x)
+        finally:
+            g.close()
+    assert launches["fast"] <= launches["plain"]
+    for i, (y0, y1) in enumerate(zip(res["fast"], res["plain"])):
+        assert np.array_equal(y0, y1, equal_nan=True), f"member {i}: the two schedules differ"
+    for i, (m, blob, _) in enumerate(mem):
+        y = res["fast"][i]
+        ref_f = harness.oracle_nhwc(m, blob, x, False)
+        ref_s = harness.oracle_nhwc(m, blob, x, True)
+        if not (np.isfinite(ref_f).all() and np.isfinite(ref_s).all()):
+            continue   # a graph whose activations overflow with these weights has no parity target
+        assert y.shape == ref_f.shape and np.isfinite(y).all()
+        scale = max(float(np.linalg.norm(ref_f)), 1e-30)
+        floor = 1e-5 * np.sqrt(ref_f.size) / scale
+        d_sf = harness.rel_l2(ref_s, ref_f)
+        e_s = harness.rel_l2(y, ref_s)
+        flip = 2.0 ** -8 / np.sqrt(ref_f.size)
+        assert e_s <= max(2e-3, d_sf) + flip + floor, f"member {i}: rel L2 vs storage-rounding oracle {e_s}, modes differ by {d_sf}"

@@ -541,3 +541,27 @@ def test_server_refuses_an_unloaded_dag():
     assert fi.lib().fi_server_start(None, None, C.byref(h)) == fi.FI_EINVAL
     assert fi.lib().fi_server_stop(None) == fi.FI_EINVAL
     d.destroy()
+
+
+@pytest.mark.parametrize("seed", range(0, 40, 2))
+def test_random_graphs_with_concatenating_blocks_compile_both_ways(seed):
+    """Random graphs with dense layers, pooling modules and slice / branch / concatenate units: the schedule that stores
+    concatenation sources in place and lets convolutions absorb affine nodes has no more launches than the plain one
+    (its arena may be a little larger: a concatenation's tensor lives from its first source on), holds the same nodes,
+    and every tensor lies inside the arena."""
+    from workloads import randnet
+    m = randnet.random_model(seed, aligned=True)
+    blob = gen.make_blob(m, 5)
+    dags = {}
+    for key, kw in (("fast", {}), ("plain", dict(copy_concats=True, separate_affine=True))):
+        spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+        dags[key] = fi.Dag([spec], 3, fi.HostAllocators(), keepalive=(keep, blob), **kw)
+    qf, qp = dags["fast"].query(), dags["plain"].query()
+    assert qf.n_nodes == qp.n_nodes == len(m.layers)
+    assert qf.n_launches <= qp.n_launches
+    for n in dags["fast"].nodes():
+        assert n.out_off + n.out_bytes <= qf.act_bytes
+        assert 0 <= n.launch < qf.n_launches
+    ops = [L.op for L in m.layers]
+    if "concat" not in ops and not any(L.op == "dwconv" and L.k == 1 for L in m.layers):
+        assert qf.n_launches == qp.n_launches

@@ -13,13 +13,20 @@ from . import zoo
 ACTS = [zoo.NONE, zoo.RELU, zoo.RELU, zoo.RELU6, zoo.HARDSWISH, zoo.HARDSIGMOID, zoo.SILU, zoo.SIGMOID]
 
 
-def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: int = 14, large: bool = False) -> zoo.Model:
+def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: int = 14, large: bool = False,
+                 aligned: bool = False) -> zoo.Model:
     """large: fewer nodes on bigger tensors (40-90 pixels a side, 64-512 channels), the shapes that reach the
-    large convolution tiles."""
+    large convolution tiles.  aligned: channel counts in multiples of 8 and, mixed into the random operators,
+    the building blocks of the concatenating families (a dense layer: per-channel affine, 1x1, 3x3, concatenate;
+    an Inception-style module with a pooling branch; a slice / branch / concatenate unit), so that
+    concatenations whose sources can be stored in place and affine nodes a convolution can absorb occur next to
+    ones that cannot.  The other modes draw exactly the graphs they always drew."""
     r = random.Random(seed)
     in_c = in_c or r.choice([1, 3, 3, 4, 8])
     lo, hi = (40, 90) if large else (9, 40)
     widths = [64, 64, 96, 128, 128, 192, 256, 320, 512] if large else [1, 3, 8, 10, 16, 24, 32, 40, 64, 72, 96, 130]
+    if aligned:
+        widths = [8, 16, 16, 24, 32, 40, 64, 64, 96, 128]
     h, w = hw or ((lambda s: (s, s))(r.randint(lo, hi)) if r.random() < 0.6 else (r.randint(lo, hi), r.randint(lo, hi)))
     m = zoo.Model(f"rand{seed}", dtype, in_c, h, w)
     dims = {}   # node -> (c, h, w)
@@ -37,6 +44,28 @@ def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: 
         c, hh, ww = shape(cur)
         act = r.choice(ACTS)
         what = r.random()
+        if aligned and cur != zoo.MODEL_INPUT and r.random() < 0.4:
+            block = r.randrange(3)
+            if block == 0:     # dense layer
+                g = r.choice([8, 16, 32])
+                a = put(zoo.DWCONV, cur, (c, hh, ww), cin=c, cout=c, k=1, stride=1, pad=0, act=r.choice([zoo.RELU, zoo.RELU, zoo.NONE, zoo.RELU6, zoo.SILU]))
+                a = put(zoo.CONV, a, (4 * g, hh, ww), cin=c, cout=4 * g, k=1, stride=1, pad=0, act=zoo.RELU)
+                a = put(zoo.CONV, a, (g, hh, ww), cin=4 * g, cout=g, k=3, stride=1, pad=1, act=zoo.NONE)
+                cur = put(zoo.CONCAT, cur, (c + g, hh, ww), residual=a)
+            elif block == 1:   # module with a pooling branch
+                c1, c2 = r.choice(widths), r.choice(widths)
+                b1 = put(zoo.CONV, cur, (c1, hh, ww), cin=c, cout=c1, k=1, stride=1, pad=0, act=act)
+                b2 = put(zoo.CONV, cur, (c2, hh, ww), cin=c, cout=c2, k=3, stride=1, pad=1, act=zoo.RELU)
+                b3 = put(r.choice([zoo.MAXPOOL, zoo.AVGPOOL]), cur, (c, hh, ww), k=3, stride=1, pad=1)
+                j = put(zoo.CONCAT, b1, (c1 + c2, hh, ww), residual=b2)
+                cur = put(zoo.CONCAT, j, (c1 + c2 + c, hh, ww), residual=b3)
+            elif c % 2 == 0 and c >= 4:   # kept half, worked half
+                half = c // 2
+                a = put(zoo.SLICE, cur, (half, hh, ww), first=0, cout=half)
+                b = put(zoo.SLICE, cur, (half, hh, ww), first=half, cout=half)
+                b = put(zoo.CONV, b, (half, hh, ww), cin=half, cout=half, k=1, stride=1, pad=0, act=zoo.RELU)
+                cur = put(zoo.CONCAT, a, (c, hh, ww), residual=b)
+            continue
         if large and what >= 0.42 and r.random() < 0.5:
             what = 0.0   # mostly dense convolutions
         if cur == zoo.MODEL_INPUT and what >= 0.64:
@@ -64,7 +93,7 @@ def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: 
                     res = r.choice(same)
             cur = put(zoo.CONV, cur, out, cin=c, cout=cout, k=k, kw=kw, stride=stride, pad=pad, act=act, residual=res, groups=groups)
         elif what < 0.52:
-            k = r.choice([3, 3, 5]); stride = 2 if r.random() < 0.3 else 1
+            k = r.choice([1, 1, 3, 5] if aligned else [3, 3, 5]); stride = 2 if r.random() < 0.3 else 1
             out = (c, (hh + 2 * (k // 2) - k) // stride + 1, (ww + 2 * (k // 2) - k) // stride + 1)
             cur = put(zoo.DWCONV, cur, out, cin=c, cout=c, k=k, stride=stride, pad=k // 2, act=act)
         elif what < 0.64:
