@@ -145,9 +145,10 @@ typedef struct {
   int32_t copy_concats;      /* 0: producers whose only other readers allow it write straight into the concatenation's
                               * tensor and the concatenation needs no launch; 1: every concatenation copies its sources.
                               * The outputs are the same bits either way. */
-  int32_t separate_affine;   /* 0: a per-channel affine node (1x1 depthwise, e.g. a DenseNet layer's normalisation + ReLU)
-                              * read only by a 1x1 convolution is applied by that convolution while it loads its input and
-                              * needs no launch; 1: it runs as a launch of its own.  The outputs are the same bits either way. */
+  int32_t separate_affine;   /* 0: a per-channel affine node (1x1 depthwise, e.g. a DenseNet layer's normalisation + ReLU) or a
+                              * squeeze-excite scaling (FI_MUL) read only by a 1x1 convolution is applied by that convolution
+                              * while it loads its input and needs no launch; 1: it runs as a launch of its own.  The outputs
+                              * are the same bits either way. */
 } fi_build_opts;
 
 typedef struct {

@@ -491,6 +491,25 @@ static fi_status plan_dag(fi_dag* g) {
       V.pre = i;
       A.elided = 1;
     }
+    // y = x * gate[image][c] (the scaling that ends a squeeze-excite block) read by nothing but one pointwise MFMA
+    // convolution (the block's projection): the convolution multiplies its input vectors by the gate on their way
+    // into LDS, with the scaling kernel's fp32 product and single rounding.
+    for (int32_t i = 0; i < total; ++i) {
+      Node& Y = g->nodes[(size_t)i];
+      const int adt = g->members[(size_t)Y.model].spec.act_dtype;
+      if (Y.kind != K_MUL || Y.input < 0 || Y.residual < 0 || adt != FI_BF16 || Y.is_output || Y.out_dtype != FI_BF16 || Y.root >= 0) continue;
+      if (n_readers[(size_t)i] != 1) continue;
+      Node& V = g->nodes[(size_t)only_reader[(size_t)i]];
+      if (V.kind != K_CONV_MFMA || V.k != 1 || V.kw != 1 || V.stride != 1 || V.pad != 0 || V.pad_w != 0 || V.pre >= 0) continue;
+      if (V.groups > 1 || V.Cp == 4 || V.Cp != Y.Cop || V.Cp % 8) continue;
+      const Node& T = g->nodes[(size_t)Y.input];
+      const Node& G = g->nodes[(size_t)Y.residual];
+      if (T.out_dtype != FI_BF16 || G.out_dtype != FI_BF16 || G.is_output || G.root >= 0 || G.Cop != V.Cp) continue;
+      const int64_t stride = T.root >= 0 ? g->nodes[(size_t)T.root].Cop : T.Cop;
+      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * 2 >= (1ull << 31)) continue;
+      V.pre = i;
+      Y.elided = 1;
+    }
   }
 
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
@@ -544,7 +563,8 @@ static fi_status plan_dag(fi_dag* g) {
         continue;
       }
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 32 + (nd.pre >= 0 ? 16 : 0) + (walks_groups(nd, adt) ? 8 : 0) + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 +
+      const int pre_kind = nd.pre < 0 ? 0 : g->nodes[(size_t)nd.pre].kind == K_MUL ? 2 : 1;
+      const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 64 + pre_kind * 16 + (walks_groups(nd, adt) ? 8 : 0) + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 +
                                        ((nd.kind == K_CONV_MFMA || nd.kind == K_FC) && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
       if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n >= FI_MAX_GROUP) {
@@ -591,9 +611,13 @@ static fi_status plan_dag(fi_dag* g) {
     if (nd.input >= 0) g->nodes[(size_t)nd.input].last_level = std::max(g->nodes[(size_t)nd.input].last_level, nd.level);
     else { StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage]; st.last = std::max(st.last, nd.level); }
     if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.level);
-    if (nd.pre >= 0) {   // the convolution reads the fused affine node's input itself
+    if (nd.pre >= 0) {   // the convolution reads the fused node's input (and gate) itself
       Node& T = g->nodes[(size_t)g->nodes[(size_t)nd.pre].input];
       T.last_level = std::max(T.last_level, nd.level);
+      if (g->nodes[(size_t)nd.pre].kind == K_MUL) {
+        Node& G = g->nodes[(size_t)g->nodes[(size_t)nd.pre].residual];
+        G.last_level = std::max(G.last_level, nd.level);
+      }
     }
   }
   for (int32_t i = 0; i < total; ++i) {   // a tensor stored inside a concatenation lives in that node's buffer
@@ -605,7 +629,7 @@ static fi_status plan_dag(fi_dag* g) {
   }
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
-    nd.out_bytes = (nd.is_output || nd.root >= 0 || (nd.elided && nd.kind == K_DWCONV)) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
+    nd.out_bytes = (nd.is_output || nd.root >= 0 || (nd.elided && nd.kind != K_CONCAT)) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
     tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.lane, nd.out_bytes, 0};
   }
   const Member& m0 = g->members[0];
@@ -741,7 +765,8 @@ static fi_status plan_dag(fi_dag* g) {
           const Node& A = g->nodes[(size_t)nd.pre];
           in = &g->nodes[(size_t)A.input];
           d.x_off = in->out_off;
-          d.pw_off = A.w_off; d.pb_off = A.b_off; d.pre_act = A.act;
+          if (A.kind == K_MUL) { d.pre_kind = 2; d.pw_off = g->nodes[(size_t)A.residual].out_off; }
+          else { d.pre_kind = 1; d.pw_off = A.w_off; d.pb_off = A.b_off; d.pre_act = A.act; }
         }
         d.xs = (in && in->root >= 0) ? g->nodes[(size_t)in->root].Cop : d.Cp;
         d.ys = nd.root >= 0 ? g->nodes[(size_t)nd.root].Cop : d.Cop;

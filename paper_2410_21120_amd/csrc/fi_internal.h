@@ -69,9 +69,10 @@ struct Desc {
   int32_t xs, ys;                // elements between neighbouring pixels of the input / output: Cp / Cop, or the channel stride of the
                                  // concatenation the tensor is stored inside (read by the depthwise kernels, written by the bf16
                                  // vector kernels and the MFMA convolution; every other kernel sees xs == Cp, ys == Cop)
-  uint64_t pw_off, pb_off;       // MFMA conv with a fused per-channel affine on its input: scale (bf16 [Cp]) and shift (fp32 [Cp])
-                                 // in the weight arena (kNone = no such stage)
-  int32_t pre_act, reserved;     // activation of that stage
+  uint64_t pw_off, pb_off;       // MFMA conv with a stage on its input side.  pre_kind 1, per-channel affine: scale (bf16 [Cp]) and
+                                 // shift (fp32 [Cp]) in the weight arena.  pre_kind 2, per-(image, channel) gate: pw_off is the gate
+                                 // tensor [batch][Cp] (bf16) in the activation region.  kNone where unused
+  int32_t pre_act, pre_kind;     // activation of the affine stage; 0 = no stage
 };
 static_assert(sizeof(Desc) == 168, "Desc is 168 bytes");
 
@@ -87,7 +88,8 @@ struct Node {
                                  // that node's channel stride, and has no buffer of its own
   int32_t elided;                // no launch: a concatenation whose sources are both stored in place, or a per-channel affine
                                  // node that the convolution reading it applies while loading its input
-  int32_t pre;                   // MFMA conv: the per-channel affine node fused into its input side (-1 = none)
+  int32_t pre;                   // MFMA conv: the node fused into its input side, a per-channel affine (depthwise 1x1) or a
+                                 // squeeze-excite scaling (-1 = none)
   int32_t level;
   int32_t out_dtype;             // FI_F32 / FI_BF16 as stored
   int32_t is_output;

@@ -251,7 +251,9 @@ __device__ __forceinline__ void finish_row4(const KArgs& a, const Desc& d, int p
 // launch of its own): applied to every input vector between its load and its LDS store, with the depthwise
 // kernel's operations (product and sum rounded separately, one rounding to bf16).  The input may sit inside a
 // concatenation's tensor, so its pixel stride is Desc.xs.
-template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false, bool PRE = false>
+// PRE == 2: the input is scaled by a per-(image, channel) gate instead, x' = x * gate[n][c] rounded to bf16 (the
+// scaling node that ends a squeeze-excite block; fp32 product, one rounding: the scaling kernel's operation).
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false, int PRE = 0>
 __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   static_assert(!GROUPED || (!WIDE && !C4), "the group walk exists for bf16 activations with 8-channel vectors");
   static_assert(!PRE || (!WIDE && !C4 && !GROUPED), "the fused affine stage exists for dense pointwise convolutions on bf16 activations");
@@ -292,20 +294,23 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // bytes of the input this launch may touch: all pixels at their stride (PRE: the last pixel ends after its Cp channels)
   const int x_bytes = PRE ? (int)((((int64_t)batch * d.H * d.W - 1) * d.xs + d.Cp) * AE) : (int)((int64_t)batch * d.H * d.W * d.Cp * AE);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.abase + d.x_off), 0, batch > 0 ? x_bytes : 0, 0x00020000);
-  const bf16_t* const pre_w = PRE ? reinterpret_cast<const bf16_t*>(a.wbase + d.pw_off) : nullptr;
-  const float* const pre_b = PRE ? reinterpret_cast<const float*>(a.wbase + d.pb_off) : nullptr;
+  const bf16_t* const pre_w = PRE == 1 ? reinterpret_cast<const bf16_t*>(a.wbase + d.pw_off)
+                            : PRE == 2 ? reinterpret_cast<const bf16_t*>(a.abase + d.pw_off) : nullptr;   // scale vector / gate tensor
+  const float* const pre_b = PRE == 1 ? reinterpret_cast<const float*>(a.wbase + d.pb_off) : nullptr;
 
   // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
   const int srow = tid >> 3, kvec = (tid & 7) * 8;
   // Per row: the byte offset of its window origin (n, p*stride-pad, q*stride-pad, 0) and which
   // filter rows / columns land inside the image (bit r: row r valid; bit 16+s: column s valid).
   int a_row[AR], a_rc[AR];
+  int a_gate[PRE == 2 ? AR : 1];   // PRE == 2: element offset of the row's image in the gate tensor
   const float inv_wo = 1.0f / (float)d.Wo, inv_ho = 1.0f / (float)d.Ho, inv_k = 1.0f / (float)d.kw;
   const bool pointwise = d.k == 1 && d.kw == 1 && d.stride == 1 && d.pad == 0 && d.pad_w == 0;  // output pixel m reads input pixel m: nothing to decode
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int m = m0 + srow + RPP * i;
     const bool ok = m < M;
+    if constexpr (PRE == 2) a_gate[i] = ((ok ? m : 0) / (d.H * d.W)) * d.Cp;
     if (pointwise) {
       a_row[i] = (ok ? m : 0) * (PRE ? d.xs : d.Cp) * AE;
       a_rc[i] = ok ? 0x10001 : 0;
@@ -368,8 +373,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // One register stage feeds one LDS buffer: fetch one tile ahead, two barriers per tile.
   u32x4 av[1][AR][AV];
   uint4 bv[1][BR];
-  uint4 pre_s[1];        // PRE: scale (8 bf16) and shift (8 fp32) of this thread's channels in the tile being fetched
+  uint4 pre_s[1];        // PRE == 1: scale (8 bf16) and shift (8 fp32) of this thread's channels in the tile being fetched
   float4 pre_t[1][2];
+  uint4 pre_g[1][PRE == 2 ? AR : 1];   // PRE == 2: the gate vectors of this thread's rows
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
 
 #define FI_FETCH(KT, S)                                                                           \
@@ -404,7 +410,11 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
         }                                                                                         \
       }                                                                                           \
     }                                                                                             \
-    if constexpr (PRE) { /* channels past Cp (the tile tail) have walked on to filter row 1: no stage, the input reads as zero */ \
+    if constexpr (PRE == 2) {                                                                     \
+      _Pragma("unroll") for (int i = 0; i < AR; ++i)                                              \
+          pre_g[S][i] = kr == 0 ? *reinterpret_cast<const uint4*>(pre_w + a_gate[i] + kc) : make_uint4(0, 0, 0, 0); \
+    }                                                                                             \
+    if constexpr (PRE == 1) { /* channels past Cp (the tile tail) have walked on to filter row 1: no stage, the input reads as zero */ \
       const bool pok = kr == 0;                                                                   \
       pre_s[S] = pok ? *reinterpret_cast<const uint4*>(pre_w + kc) : make_uint4(0, 0, 0, 0);      \
       pre_t[S][0] = pok ? *reinterpret_cast<const float4*>(pre_b + kc) : make_float4(0, 0, 0, 0); \
@@ -431,7 +441,16 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     bf16_t* const Ap = As + (S) * STAGE;                                                          \
     bf16_t* const Bp = Bs + (S) * STAGE;                                                          \
     _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
-      if constexpr (PRE) {                                                                        \
+      if constexpr (PRE == 2) {                                                                   \
+        const uint32_t gw[4] = {pre_g[S][i].x, pre_g[S][i].y, pre_g[S][i].z, pre_g[S][i].w};      \
+        u32x4 pk;                                                                                 \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
+          const uint32_t xw = av[S][i][0][e];                                                     \
+          pk[e] = pack_bf16x2(__fmul_rn(__uint_as_float(xw << 16), __uint_as_float(gw[e] << 16)), \
+                              __fmul_rn(__uint_as_float(xw & 0xFFFF0000u), __uint_as_float(gw[e] & 0xFFFF0000u))); \
+        }                                                                                         \
+        *reinterpret_cast<u32x4*>(&Ap[(srow + RPP * i) * LDS_STRIDE + kvec]) = pk;                \
+      } else if constexpr (PRE == 1) {                                                            \
         const uint32_t sw[4] = {pre_s[S].x, pre_s[S].y, pre_s[S].z, pre_s[S].w};                  \
         const float sh[8] = {pre_t[S][0].x, pre_t[S][0].y, pre_t[S][0].z, pre_t[S][0].w,          \
                              pre_t[S][1].x, pre_t[S][1].y, pre_t[S][1].z, pre_t[S][1].w};         \
@@ -1480,7 +1499,7 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
     const Desc& t = hd[(size_t)(L.first_desc + i)];
     if (L.kind == K_STAGE || (t.xs == t.Cp && t.ys == t.Cop)) continue;
     const bool reads = (L.kind == K_DWCONV && wb && ab && hd[(size_t)L.first_desc].vec) ||
-                       ((L.kind == K_CONV_MFMA || L.kind == K_REDUCE) && ab && t.pw_off != kNone);   // (the reduce launch shares the node's descriptor and reads no input)
+                       ((L.kind == K_CONV_MFMA || L.kind == K_REDUCE) && ab && t.pre_kind != 0);   // (the reduce launch shares the node's descriptor and reads no input)
     const bool writes = ab && !t.ext && !t.out_f32 &&
                         (L.kind == K_CONV_MFMA || L.kind == K_REDUCE || (L.kind == K_DWCONV && wb && hd[(size_t)L.first_desc].vec) ||
                          ((L.kind == K_MAXPOOL || L.kind == K_AVGPOOL || L.kind == K_GATHER) && t.vec));
@@ -1523,18 +1542,24 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
         if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false, false, true>, nb, 256, a, s);
         return (int)hipErrorInvalidValue;
       }
-      if (hd[(size_t)L.first_desc].pw_off != kNone) {  // pointwise convolutions that apply a per-channel affine stage to their input
+      if (hd[(size_t)L.first_desc].pre_kind != 0) {  // pointwise convolutions with a stage on their input side (per-channel affine, or gate)
+        const int pk = hd[(size_t)L.first_desc].pre_kind;
         for (int i = 0; i < L.n; ++i) {
           const Desc& t = hd[(size_t)(L.first_desc + i)];
-          if (t.pw_off == kNone || t.pb_off == kNone || t.k != 1 || t.kw != 1 || t.stride != 1 || t.pad != 0 || t.pad_w != 0 || t.gin > 0 ||
-              t.xs < t.Cp || t.Cp % 8 || (uint64_t)t.H * t.W * (uint64_t)t.xs * 2 * (uint64_t)a.batch[i] >= (1ull << 31))
+          if (t.pre_kind != pk || (pk != 1 && pk != 2) || t.pw_off == kNone || (pk == 1 && t.pb_off == kNone) ||
+              t.k != 1 || t.kw != 1 || t.stride != 1 || t.pad != 0 || t.pad_w != 0 || t.gin > 0 || t.xs < t.Cp || t.Cp % 8 ||
+              (uint64_t)t.H * t.W * (uint64_t)t.xs * 2 * (uint64_t)a.batch[i] >= (1ull << 31))
             return (int)hipErrorInvalidValue;
         }
-        if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false, false, false, true>, nb, 256, a, s);
-        if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false, false, false, true>, nb, 256, a, s);
-        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false, false, false, true>, nb, 256, a, s);
-        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, false, false, true>, nb, 256, a, s);
-        return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false, false, false, true>, nb, 256, a, s);
+#define FI_PRE_TILES(PK)                                                                                                             \
+        if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false, false, false, PK>, nb, 256, a, s);     \
+        if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false, false, false, PK>, nb, 256, a, s);        \
+        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false, false, false, PK>, nb, 256, a, s);     \
+        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, false, false, PK>, nb, 256, a, s);        \
+        return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false, false, false, PK>, nb, 256, a, s);
+        if (pk == 1) { FI_PRE_TILES(1) }
+        FI_PRE_TILES(2)
+#undef FI_PRE_TILES
       }
       if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false>, nb, 256, a, s);
       if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false>, nb, 256, a, s);

@@ -427,12 +427,14 @@ def _dense_block(c0, growth, layers, h, w):
     return m.shapes()
 
 
-@pytest.mark.parametrize("case", ["densenet121", "densenet161", (16, 8, 3, 9, 7), (64, 32, 5, 28, 28), (24, 16, 2, 6, 6), (200, 40, 2, 14, 14)])
+@pytest.mark.parametrize("case", ["densenet121", "densenet161", "mobilenet_v3_large", "mobilenet_v3_small", (16, 8, 3, 9, 7), (64, 32, 5, 28, 28),
+                                  (24, 16, 2, 6, 6), (200, 40, 2, 14, 14)])
 def test_affine_applied_by_the_convolution_equals_its_own_launch(case):
     """The per-channel affine + ReLU in front of a dense layer's 1x1 convolution, applied by that convolution while it
     loads its input (no launch, no tensor) against a handle that runs it as a depthwise launch: fewer launches, the
     same bits -- whole DenseNets and blocks whose channel counts leave ragged reduction tiles, split reductions and
-    inputs inside a concatenation's tensor; also with copied concatenations (the input then has its own stride)."""
+    inputs inside a concatenation's tensor; also with copied concatenations (the input then has its own stride).  The
+    MobileNetV3s cover the other absorbed node: the squeeze-excite scaling applied by the block's projection."""
     from tests import harness
     if isinstance(case, str):
         m, hw = zoo.FAMILIES[case](hw=64), (64, 64)
@@ -449,7 +451,7 @@ def test_affine_applied_by_the_convolution_equals_its_own_launch(case):
             res[key] = [g.run(x), g.run(x[:1])]
         finally:
             g.close()
-    assert launches["fused"] < launches["separate"] < launches["plain"] and launches["fused_copy"] < launches["plain"]
+    assert launches["fused"] < launches["separate"] <= launches["plain"] and launches["fused_copy"] < launches["plain"]
     for key in ("separate", "fused_copy", "plain"):
         for r0, r1 in zip(res["fused"], res[key]):
             for y0, y1 in zip(r0, r1):
