@@ -363,6 +363,9 @@ static fi_status plan_dag(fi_dag* g) {
           const int tiles = (nd.Co + 31) / 32, steps = nd.Kp / 16;
           nd.splits = std::max(1, std::min(std::min(64, std::max(1, steps / 8)), std::max(1, 2048 / tiles)));
           if (nd.Kp <= 512) nd.splits = 1;   // a short reduction (a squeeze-excite gate, a small head): the kernel finishes it itself
+          // A split layer with a small weight matrix (latency-bound: a gate, a classifier head) keeps all slices of a
+          // tile in one workgroup, which sums them in LDS and finishes: no partials in HBM, no reduce launch.
+          if (nd.splits > 1 && nd.splits <= 16 && (uint64_t)((nd.Co + 31) / 32 * 32) * (uint64_t)nd.Kp * 2 <= (4u << 20)) nd.tile = 1;
         } else if (g->wdtype == FI_BF16) {
           nd.kind = K_CONV_MFMA;
           {
@@ -586,7 +589,7 @@ static fi_status plan_dag(fi_dag* g) {
       if (cand.kind == K_FC) {   // FC launches whose problems are all unsplit finish in their own kernel
         bool any_split = false;
         for (int32_t ni : cand.nodes) any_split = any_split || g->nodes[(size_t)ni].splits > 1;
-        if (!any_split) continue;
+        if (!any_split || cand.tile == 1) continue;   // (tile 1: the FC kernel that sums its slices itself)
       }
       const Launch src = cand;
       Launch& R = new_launch(lv, K_REDUCE, 0, src.adtype);

@@ -77,7 +77,8 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
     }
     case K_GAP: return d.vec ? batch * ((d.Cop / 8 + 7) / 8) : (batch * d.Cop + 255) / 256;
     case K_SOFTMAX: return batch;
-    case K_FC: return (d.tiles_n * d.splits * ((batch + 31) / 32) + 3) / 4;
+    case K_FC: return tile == 1 ? d.tiles_n * ((batch + 31) / 32)   // every slice of a tile in one workgroup (fc_block_kernel)
+                                : (d.tiles_n * d.splits * ((batch + 31) / 32) + 3) / 4;
     case K_REDUCE: return (batch * d.Ho * d.Wo * (d.Cop / 4) + 255) / 256;
     case K_GATHER: return (int)(((int64_t)batch * d.Ho * d.Wo * (d.vec ? d.Cop / 8 : d.Cop) + 255) / 256);
     case K_CONCAT:
@@ -1312,19 +1313,11 @@ __global__ void __launch_bounds__(256) gap_vec_kernel(KArgs a) {
 // once per pass).  reduce_kernel sums the partials in a fixed order (deterministic), adds the
 // bias and the residual, applies the activation and stores.
 // ---------------------------------------------------------------------------------
+// One wave's share of a fully connected problem: the 32 x 32 block (features of `tile` x images of `chunk`)
+// reduced over slice `split` of the weight rows.  Lane l ends up with image chunk*32 + (l & 31), features
+// tile*32 + 8*g + 4*(l >> 5) + t in acc[4*g + t].
 template <bool WIDE>
-__global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
-  int p, bid;
-  if (!find_problem(a, K_FC, 0, p, bid)) return;
-  const Desc d = a.d[p];
-  const int batch = a.batch[p];   // images of this problem's member in this pass
-  const int lane = threadIdx.x & 63;
-  int unit = bid * 4 + (threadIdx.x >> 6);
-  const int per_chunk = d.tiles_n * d.splits;
-  if (unit >= per_chunk * ((batch + 31) / 32)) return;
-  const int chunk = unit / per_chunk;   // which 32 images
-  unit -= chunk * per_chunk;
-  const int tile = unit % d.tiles_n, split = unit / d.tiles_n;
+__device__ __forceinline__ f32x16 fc_partial(const KArgs& a, const Desc& d, int batch, int tile, int split, int chunk, int lane) {
   const int steps = d.Kp / 16;
   const int per = (steps + d.splits - 1) / d.splits;
   const int s0 = split * per, s1 = min(steps, s0 + per);
@@ -1380,6 +1373,25 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
       }
     }
   }
+  return acc;
+}
+
+template <bool WIDE>
+__global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
+  int p, bid;
+  if (!find_problem(a, K_FC, 0, p, bid)) return;
+  const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
+  const int lane = threadIdx.x & 63;
+  int unit = bid * 4 + (threadIdx.x >> 6);
+  const int per_chunk = d.tiles_n * d.splits;
+  if (unit >= per_chunk * ((batch + 31) / 32)) return;
+  const int chunk = unit / per_chunk;   // which 32 images
+  unit -= chunk * per_chunk;
+  const int tile = unit % d.tiles_n, split = unit / d.tiles_n;
+  const f32x16 acc = fc_partial<WIDE>(a, d, batch, tile, split, chunk, lane);
+  const int n = chunk * 32 + (lane & 31);
+  const bool nok = n < batch;
   // lane holds batch column n, features 8*g + 4*(lane/32) + t
   if (nok && d.splits == 1) {   // the whole reduction was this wave's: no partials, no reduce launch
 #pragma unroll
@@ -1399,6 +1411,38 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
         *reinterpret_cast<float4*>(ws + fo) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
     }
   }
+}
+
+// The same problem with every slice of a tile inside one workgroup (16 waves, one slice each): the partial blocks
+// meet in LDS, are summed in slice order and finished here, so a split layer whose weight matrix is small (a
+// squeeze-excite gate, a classifier head: latency-bound, a handful of tiles) needs neither the partials' round
+// trip through HBM nor the reduce launch.  Slices and summation order are those of fc_kernel + reduce_kernel.
+template <bool WIDE>
+__global__ void __launch_bounds__(1024) fc_block_kernel(KArgs a) {
+  __shared__ float part[16][32][32];   // [slice][image][feature]
+  int p, bid;
+  if (!find_problem(a, K_FC, 1, p, bid)) return;
+  const Desc d = a.d[p];
+  const int batch = a.batch[p];   // images of this problem's member in this pass
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunk = bid / d.tiles_n, tile = bid % d.tiles_n;
+  if (wave < d.splits) {
+    const f32x16 acc = fc_partial<WIDE>(a, d, batch, tile, wave, chunk, lane);
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<float4*>(&part[wave][lane & 31][8 * g + 4 * (lane >> 5)]) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+  }
+  __syncthreads();
+  if (threadIdx.x >= 256) return;
+  const int nl = threadIdx.x >> 3, o4 = (threadIdx.x & 7) * 4;
+  const int n = chunk * 32 + nl, fo = tile * 32 + o4;
+  if (n >= batch || fo >= d.Cop) return;
+  float4 sum = make_float4(0, 0, 0, 0);
+  for (int s = 0; s < d.splits; ++s) {   // slice order, as the reduce kernel adds them
+    const float4 v = *reinterpret_cast<const float4*>(&part[s][nl][o4]);
+    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+  }
+  finish_row4<typename std::conditional<WIDE, float, bf16_t>::type>(a, d, p, n, fo, sum);
 }
 
 // Finishes a split-K node (small-batch FC or a split convolution): sums the fp32 partials
@@ -1600,6 +1644,11 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
     }
     case K_FC:
       if (!wb) return (int)hipErrorInvalidValue;
+      if (L.tile == 1) {
+        for (int i = 0; i < L.n; ++i)
+          if (hd[(size_t)(L.first_desc + i)].splits < 1 || hd[(size_t)(L.first_desc + i)].splits > 16) return (int)hipErrorInvalidValue;
+        return ab ? go(fc_block_kernel<false>, nb, 1024, a, s) : go(fc_block_kernel<true>, nb, 1024, a, s);
+      }
       return ab ? go(fc_kernel<false>, nb, 256, a, s) : go(fc_kernel<true>, nb, 256, a, s);
     case K_REDUCE:
       return ab ? go(reduce_kernel<bf16_t>, nb, 256, a, s) : go(reduce_kernel<float>, nb, 256, a, s);
