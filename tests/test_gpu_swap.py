@@ -70,6 +70,35 @@ def test_chain_of_swaps_matches_fresh_builds_bitwise():
         g.close()
 
 
+def test_swaps_between_families_with_in_place_concatenations_and_absorbed_nodes():
+    """Members whose schedules store concatenation sources in place, let convolutions absorb affine nodes and
+    squeeze-excite scalings, and walk groups (DenseNet, GoogLeNet, MobileNetV3, ResNeXt, ShuffleNet) swapped in and
+    out of a loaded DAG: the whole plan is recomputed at every swap and must equal a fresh build bit for bit."""
+    from tests import harness
+    x = gen.make_input(8, 2, 3, HW, HW, "normal", "bf16")
+    mem = [_member("densenet121", 3000), _member("googlenet", 3001), _member("mobilenet_v3_large", 3002), _member("resnet18", 3003)]
+    swaps = [(3, _member("resnext50_32x4d", 4001)), (0, _member("squeezenet1_1", 4002)), (1, _member("densenet121", 4003)),
+             (2, _member("shufflenet_v2_x0_5", 4004)), (0, _member("mobilenet_v3_small", 4005))]
+    g = harness.GpuDag(mem, 2, swap_headroom_bytes=256 << 20)
+    try:
+        prev = g.run(x)
+        assert all(np.array_equal(a, b) for a, b in zip(prev, _fresh(mem, x)))
+        for slot, newcomer in swaps:
+            g.swap(slot, newcomer)
+            mem[slot] = newcomer
+            got = g.run(x)
+            fresh = _fresh(mem, x)
+            for i in range(len(mem)):
+                assert np.isfinite(got[i]).all()
+                assert np.array_equal(got[i], fresh[i]), f"member {i} after swapping slot {slot}"
+                if i != slot:
+                    assert np.array_equal(got[i], prev[i]), f"member {i} moved when slot {slot} was swapped"
+            _check_oracle(newcomer, got[slot], x)
+            prev = got
+    finally:
+        g.close()
+
+
 def test_swap_with_packed_members_and_per_model_copies():
     import torch
     import paper_2410_21120_amd as fi
