@@ -513,6 +513,20 @@ static fi_status plan_dag(fi_dag* g) {
       V.pre = i;
       Y.elided = 1;
     }
+    // shuffle_2(concat(A, B)) with equal halves (the end of a ShuffleNet unit) read by nothing else: the shuffle
+    // interleaves A and B itself and the concatenation is never built.  (A concatenation already stored in place
+    // costs nothing and stays.)
+    for (int32_t i = 0; i < total; ++i) {
+      Node& Z = g->nodes[(size_t)i];
+      if (Z.kind != K_GATHER || Z.op != FI_SHUFFLE || Z.k != 2 || Z.input < 0) continue;
+      Node& Q = g->nodes[(size_t)Z.input];
+      if (Q.kind != K_CONCAT || Q.elided || Q.root >= 0 || Q.is_output || n_readers[(size_t)Z.input] != 1 || Q.input < 0 || Q.residual < 0) continue;
+      const Node& A = g->nodes[(size_t)Q.input];
+      const Node& Bn = g->nodes[(size_t)Q.residual];
+      if (A.Co != Bn.Co || A.out_dtype != Q.out_dtype || Bn.out_dtype != Q.out_dtype || A.root >= 0 || Bn.root >= 0) continue;
+      Z.pre = Z.input;
+      Q.elided = 2;   // never built: no launch and no tensor
+    }
   }
 
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
@@ -617,7 +631,7 @@ static fi_status plan_dag(fi_dag* g) {
     if (nd.pre >= 0) {   // the convolution reads the fused node's input (and gate) itself
       Node& T = g->nodes[(size_t)g->nodes[(size_t)nd.pre].input];
       T.last_level = std::max(T.last_level, nd.level);
-      if (g->nodes[(size_t)nd.pre].kind == K_MUL) {
+      if (g->nodes[(size_t)nd.pre].kind == K_MUL || g->nodes[(size_t)nd.pre].kind == K_CONCAT) {
         Node& G = g->nodes[(size_t)g->nodes[(size_t)nd.pre].residual];
         G.last_level = std::max(G.last_level, nd.level);
       }
@@ -632,7 +646,7 @@ static fi_status plan_dag(fi_dag* g) {
   }
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
-    nd.out_bytes = (nd.is_output || nd.root >= 0 || (nd.elided && nd.kind != K_CONCAT)) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
+    nd.out_bytes = (nd.is_output || nd.root >= 0 || (nd.elided && nd.kind != K_CONCAT) || nd.elided == 2) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
     tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.lane, nd.out_bytes, 0};
   }
   const Member& m0 = g->members[0];
@@ -764,7 +778,15 @@ static fi_status plan_dag(fi_dag* g) {
       {
         const Node* in = nd.input >= 0 ? &g->nodes[(size_t)nd.input] : nullptr;
         d.pw_off = d.pb_off = kNone;
-        if (nd.pre >= 0) {   // read the affine node's input, apply the node on the way in
+        if (nd.pre >= 0 && g->nodes[(size_t)nd.pre].kind == K_CONCAT) {   // a shuffle that interleaves the concatenation's two sources
+          const Node& Q = g->nodes[(size_t)nd.pre];
+          const Node& A = g->nodes[(size_t)Q.input];
+          const Node& Bn = g->nodes[(size_t)Q.residual];
+          in = &A;
+          d.x_off = A.out_off; d.r_off = Bn.out_off;
+          d.Cp = A.Cop; d.tiles_n = Bn.Cop; d.stride = 2;
+          d.vec = (d.vec && A.Cop % 8 == 0 && Bn.Cop % 8 == 0) ? 1 : 0;
+        } else if (nd.pre >= 0) {   // read the affine node's input, apply the node on the way in
           const Node& A = g->nodes[(size_t)nd.pre];
           in = &g->nodes[(size_t)A.input];
           d.x_off = in->out_off;

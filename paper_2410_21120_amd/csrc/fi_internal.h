@@ -86,10 +86,11 @@ struct Node {
   int32_t groups;                // conv2d: channel groups (1 = dense)
   int32_t root, chan;            // root >= 0: the tensor is stored inside concatenation node `root`, from channel `chan` on, with
                                  // that node's channel stride, and has no buffer of its own
-  int32_t elided;                // no launch: a concatenation whose sources are both stored in place, or a per-channel affine
-                                 // node that the convolution reading it applies while loading its input
+  int32_t elided;                // no launch: a concatenation whose sources are both stored in place, a per-channel affine or
+                                 // scaling node that the convolution reading it applies while loading its input, or (2) a
+                                 // concatenation that the two-group shuffle reading it replaces by interleaving its sources
   int32_t pre;                   // MFMA conv: the node fused into its input side, a per-channel affine (depthwise 1x1) or a
-                                 // squeeze-excite scaling (-1 = none)
+                                 // squeeze-excite scaling; shuffle: the concatenation it replaces (-1 = none)
   int32_t level;
   int32_t out_dtype;             // FI_F32 / FI_BF16 as stored
   int32_t is_output;

@@ -720,7 +720,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 
 // ---------------------------------------------------------------------------------
 // channel gather: output channel c is input channel pad + c (slice, stride == 0) or
-// (c mod k) * (C / k) + c / k (shuffle in k groups, stride == 1); values move unchanged
+// (c mod k) * (C / k) + c / k (shuffle in k groups, stride == 1), or channel c / 2 of the first (c even) or the second
+// (c odd) of two sources of equal width (stride == 2: a concatenation shuffled in two groups, without building the
+// concatenation; the second source sits at r_off with pixel stride tiles_n); values move unchanged
 // ---------------------------------------------------------------------------------
 template <typename TA>
 __global__ void __launch_bounds__(256) gather_kernel(KArgs a) {
@@ -738,6 +740,24 @@ __global__ void __launch_bounds__(256) gather_kernel(KArgs a) {
     uint16_t* y = reinterpret_cast<uint16_t*>(a.abase + d.y_off) + m * d.ys + c8;
     if (d.stride == 0 && (d.pad & 7) == 0 && c8 + 8 <= d.Co) {   // aligned slice: the 8 channels are one vector of the source too
       *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(x + d.pad + c8);
+      return;
+    }
+    if (d.stride == 2) {   // interleave: four channels of each source make the eight outputs
+      const uint16_t* xb = reinterpret_cast<const uint16_t*>(a.abase + d.r_off) + m * d.tiles_n;
+      uint32_t w[4];
+      if (c8 + 8 <= d.Co) {
+        const uint2 va = *reinterpret_cast<const uint2*>(x + c8 / 2), vb = *reinterpret_cast<const uint2*>(xb + c8 / 2);
+        w[0] = (va.x & 0xFFFFu) | (vb.x << 16); w[1] = (va.x >> 16) | (vb.x & 0xFFFF0000u);
+        w[2] = (va.y & 0xFFFFu) | (vb.y << 16); w[3] = (va.y >> 16) | (vb.y & 0xFFFF0000u);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int c = c8 + i;
+          const uint32_t v = c < d.Co ? ((c & 1) ? xb[c >> 1] : x[c >> 1]) : 0u;
+          w[i >> 1] = (i & 1) ? (w[i >> 1] | (v << 16)) : v;
+        }
+      }
+      *reinterpret_cast<uint4*>(y) = make_uint4(w[0], w[1], w[2], w[3]);
       return;
     }
     const int per = d.stride == 0 ? 0 : d.C / d.k;
@@ -759,7 +779,8 @@ __global__ void __launch_bounds__(256) gather_kernel(KArgs a) {
   float v = 0.0f;
   if (c < d.Co) {
     const int src = d.stride == 0 ? d.pad + c : (c % d.k) * (d.C / d.k) + c / d.k;
-    v = ld(x + m * d.Cp + src);
+    v = d.stride == 2 ? ((c & 1) ? ld(reinterpret_cast<const TA*>(a.abase + d.r_off) + m * d.tiles_n + (c >> 1)) : ld(x + m * d.Cp + (c >> 1)))
+                      : ld(x + m * d.Cp + src);
   }
   if (d.ext) {
     if (c < d.Co) static_cast<float*>(a.ext_out[p])[m * d.Co + c] = v;
