@@ -16,9 +16,9 @@ ACTS = [zoo.NONE, zoo.RELU, zoo.RELU, zoo.RELU6, zoo.HARDSWISH, zoo.HARDSIGMOID,
 def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: int = 14, large: bool = False,
                  aligned: bool = False) -> zoo.Model:
     """large: fewer nodes on bigger tensors (40-90 pixels a side, 64-512 channels), the shapes that reach the
-    large convolution tiles.  aligned: channel counts in multiples of 8 and, mixed into the random operators,
+    large convolution tiles.  aligned: channel counts mostly in multiples of 8 and, mixed into the random operators,
     the building blocks of the concatenating families (a dense layer: per-channel affine, 1x1, 3x3, concatenate;
-    an Inception-style module with a pooling branch; a slice / branch / concatenate unit), so that
+    an Inception-style module with a pooling branch; a slice / branch / concatenate unit, often shuffled), so that
     concatenations whose sources can be stored in place and affine nodes a convolution can absorb occur next to
     ones that cannot.  The other modes draw exactly the graphs they always drew."""
     r = random.Random(seed)
@@ -26,7 +26,7 @@ def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: 
     lo, hi = (40, 90) if large else (9, 40)
     widths = [64, 64, 96, 128, 128, 192, 256, 320, 512] if large else [1, 3, 8, 10, 16, 24, 32, 40, 64, 72, 96, 130]
     if aligned:
-        widths = [8, 16, 16, 24, 32, 40, 64, 64, 96, 128]
+        widths = [8, 12, 16, 20, 24, 32, 40, 58, 64, 64, 96, 116, 128]
     h, w = hw or ((lambda s: (s, s))(r.randint(lo, hi)) if r.random() < 0.6 else (r.randint(lo, hi), r.randint(lo, hi)))
     m = zoo.Model(f"rand{seed}", dtype, in_c, h, w)
     dims = {}   # node -> (c, h, w)
@@ -65,6 +65,8 @@ def random_model(seed: int, dtype: str = "bf16", in_c=None, hw=None, max_nodes: 
                 b = put(zoo.SLICE, cur, (half, hh, ww), first=half, cout=half)
                 b = put(zoo.CONV, b, (half, hh, ww), cin=half, cout=half, k=1, stride=1, pad=0, act=zoo.RELU)
                 cur = put(zoo.CONCAT, a, (c, hh, ww), residual=b)
+                if r.random() < 0.6:   # ... and the two halves shuffled together, as a ShuffleNet unit ends
+                    cur = put(zoo.SHUFFLE, cur, (c, hh, ww), groups=2)
             continue
         if large and what >= 0.42 and r.random() < 0.5:
             what = 0.0   # mostly dense convolutions
