@@ -52,23 +52,27 @@ FI_HD inline int tile_bn(int t) { return (t == T_128x128 || t == T_256x128) ? 12
 // as launch arguments.  Tensor offsets are relative to the activation region, weight offsets
 // to the weight arena.
 struct Desc {
-  uint64_t x_off, y_off, r_off;  // input / output / residual (kNone = no residual)
+  uint64_t x_off, y_off, r_off;  // input / output / second operand: residual, gate, second source of a concatenation or of an
+                                 // interleaving shuffle (kNone = none)
   uint64_t w_off, b_off;
   int32_t H, W, C, Cp;           // input: logical dims and padded channel stride
   int32_t Ho, Wo, Co, Cop;       // output
-  int32_t k, stride, pad, act;
-  int32_t Kp;                    // padded reduction length of a weight row (elements)
+  int32_t k, stride, pad, act;   // channel gather: k = shuffle groups, pad = first channel of a slice, stride = mode
+                                 // (0 slice, 1 shuffle, 2 interleave two sources)
+  int32_t Kp;                    // padded reduction length of a weight row (elements); concatenation: channels of the second source
   int32_t ext;                   // 1: output is the caller's fp32 buffer of this problem
   int32_t out_f32;               // 1: output stored as fp32 whatever the activation dtype
-  int32_t tiles_n;               // MFMA conv: column tiles
+  int32_t tiles_n;               // MFMA conv: column tiles; FC: 32-feature tiles; depthwise / pooling strip kernels: outputs per
+                                 // thread along a row; concatenation / interleaving shuffle: pixel stride of the second source
   int32_t vec;                   // 1: bf16 tensors with Cp % 8 == 0, kernels work on 8-channel vectors
   int32_t splits;                // reduction splits (>1: fp32 partials [splits][rows][Cop] at ws_off)
   uint64_t ws_off;               // split-K partials, relative to the activation base
   int32_t kw, pad_w;             // dense conv: kernel width and horizontal padding (k, pad are the vertical ones)
   int32_t gin, gout;             // MFMA conv of a grouped convolution: input / output channels per group (0 = dense walk over all channels)
   int32_t xs, ys;                // elements between neighbouring pixels of the input / output: Cp / Cop, or the channel stride of the
-                                 // concatenation the tensor is stored inside (read by the depthwise kernels, written by the bf16
-                                 // vector kernels and the MFMA convolution; every other kernel sees xs == Cp, ys == Cop)
+                                 // concatenation the tensor is stored inside (read by the depthwise kernels and by MFMA convolutions
+                                 // with an input-side stage, written by the bf16 vector kernels and the MFMA convolution; every other
+                                 // kernel sees xs == Cp, ys == Cop: launch_kernel checks)
   uint64_t pw_off, pb_off;       // MFMA conv with a stage on its input side.  pre_kind 1, per-channel affine: scale (bf16 [Cp]) and
                                  // shift (fp32 [Cp]) in the weight arena.  pre_kind 2, per-(image, channel) gate: pw_off is the gate
                                  // tensor [batch][Cp] (bf16) in the activation region.  kNone where unused

@@ -2,12 +2,15 @@
 //
 // Every kernel is a GROUPED kernel: one launch carries 1..FI_MAX_GROUP independent
 // problems (nodes of different member models at the same depth).  A workgroup finds its
-// problem by walking the launch's descriptor range and subtracting each problem's
-// workgroup count; it then touches only that problem's input, weights and output, so a
+// problem from the table of starting workgroup indices that travels with the launch's
+// arguments; it then touches only that problem's input, weights and output, so a
 // member's bits never depend on which other members share the launch (Section III-A,
 // C1 and C4: no operator is merged across models, no tensor is shared between them).
 //
 // Tensors are NHWC with the channel stride padded to Cp; pad channels always hold zero.
+// A tensor that the planner stored inside a concatenation's tensor has that tensor's pixel
+// stride instead (Desc.xs / Desc.ys); a node the planner folded into its reader (a per-channel
+// affine, a squeeze-excite scaling, a concatenation that a shuffle interleaves) has no launch.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
