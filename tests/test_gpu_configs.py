@@ -195,6 +195,31 @@ def test_further_table3_families_fused():
         _check_member(f, ys[i], res[2 * i], res[2 * i + 1], tol)
 
 
+def test_remaining_table3_families_fused():
+    """The family members of Table III not covered above (DenseNet-169 / 201 / 161 with its 48-channel growth, ResNeXt-101
+    32x8d, MobileNetV3-Small, ShuffleNet V2 x0.5), fused in one DAG at a reduced image size, bf16 storage, each against
+    the oracle."""
+    from tests import harness
+    fams = ["densenet169", "densenet201", "densenet161", "resnext101_32x8d", "mobilenet_v3_small", "shufflenet_v2_x0_5"]
+    mem = []
+    for i, f in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=64)
+        mem.append((m, gen.make_blob(m, 1100 + i), None))
+    x = gen.make_input(17, 2, 3, 64, 64, "normal", "bf16")
+    g = harness.GpuDag(mem, 2)
+    try:
+        ys = g.run(x)
+    finally:
+        g.close()
+    units = []
+    for (m, b, act) in mem:
+        units.append((m, b, x, False))
+        units.append((m, b, x, True))
+    res = harness.oracle_units(units)
+    for i, f in enumerate(fams):
+        _check_member(f, ys[i], res[2 * i], res[2 * i + 1], 1e-2)
+
+
 def test_efficientnet_v2_prefix():
     """EfficientNetV2-S with these synthetic weights is ill-conditioned as a whole: its activations grow by orders
     of magnitude through 40 residual blocks and the oracle's own fp32 and fp64-accumulation builds end 0.7 apart in
