@@ -25,6 +25,17 @@
  *  - All members of one DAG share the weight dtype and the input shape.  fi_run
  *    feeds one shared input batch to every member; fi_run_inputs gives each
  *    member an input of its own (Algorithm 1's per-model inputs x^m).
+ *  - Buffers: a run over `batch` images reads batch x fi_dag_info.input_image_bytes
+ *    bytes from every input pointer it is given and writes batch x
+ *    fi_member_info.output_row_bytes bytes to each member's output pointer.  The
+ *    library cannot see how much memory stands behind a pointer: size the buffers
+ *    from those two figures.
+ *  - The planner may fold a node into its neighbours (a concatenation written in
+ *    place by its producers, a per-channel affine or squeeze-excite scaling
+ *    applied by the convolution that reads it, a concatenation that a shuffle
+ *    interleaves): such a node has no launch and no tensor of its own, and every
+ *    output keeps the bits of the unfolded schedule (fi_build_opts.copy_concats,
+ *    fi_build_opts.separate_affine switch the folding off).
  */
 #ifndef FUSEDINF_H
 #define FUSEDINF_H
