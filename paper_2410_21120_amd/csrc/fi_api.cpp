@@ -270,6 +270,137 @@ static fi_status build_core(const fi_model_spec* models, int32_t n, const fi_bui
   return FI_OK;
 }
 
+// Planner pass (kernel families, tiles and split factors are known; launches are not built yet).
+static void store_concat_sources_in_place(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t total = (int32_t)g->nodes.size();
+  // ---- concatenations in place --------------------------------------------------------------
+  // A concatenation copies its two sources into one tensor.  When a source's producer can write with a
+  // channel stride other than its own (the MFMA convolution and the bf16 vector kernels can) and whoever
+  // else reads that source can read with such a stride (the depthwise kernels can), the source is stored
+  // inside the concatenation's tensor from the start and the copy disappears: DenseNet blocks, Inception
+  // and fire modules then write every branch once.  Nested concatenations resolve to the outermost tensor.
+  for (Node& nd : g->nodes) { nd.root = -1; nd.chan = 0; nd.elided = 0; nd.pre = -1; }
+  if (!opts->copy_concats && g->wdtype == FI_BF16) {
+    std::vector<std::vector<int32_t>> readers((size_t)total);   // nodes reading a tensor as their first input
+    std::vector<int32_t> as_second((size_t)total, 0);           // times a tensor is a second operand (residual, gate, second source)
+    for (int32_t i = 0; i < total; ++i) {
+      const Node& nd = g->nodes[(size_t)i];
+      if (nd.input >= 0) readers[(size_t)nd.input].push_back(i);
+      if (nd.residual >= 0) as_second[(size_t)nd.residual]++;
+    }
+    std::vector<int8_t> can_elide((size_t)total, 0);
+    auto stored_in_place = [&](int32_t s, int32_t q, bool second) {
+      const Node& S = g->nodes[(size_t)s];
+      const int adt = g->members[(size_t)S.model].spec.act_dtype;
+      if (adt != FI_BF16 || S.is_output || S.out_dtype != FI_BF16 || S.Cop % 8) return false;
+      // the concatenation is the only node that takes S as a second operand (once) or lists it first (once) ...
+      if (as_second[(size_t)s] != (second ? 1 : 0)) return false;
+      int first_uses = 0;
+      for (int32_t r : readers[(size_t)s]) {
+        if (r == q) { ++first_uses; continue; }
+        if (g->nodes[(size_t)r].kind != K_DWCONV) return false;   // ... and every other reader takes an input stride
+      }
+      if (first_uses != (second ? 0 : 1)) return false;
+      switch (S.kind) {
+        case K_CONV_MFMA: return true;
+        case K_DWCONV: case K_MAXPOOL: case K_AVGPOOL: case K_GATHER: return S.Cp % 8 == 0;   // their 8-channel forms
+        case K_CONCAT: return can_elide[(size_t)s] != 0;
+        default: return false;
+      }
+    };
+    for (int32_t i = 0; i < total; ++i) {   // sources come before the concatenation that joins them
+      const Node& Q = g->nodes[(size_t)i];
+      if (Q.kind != K_CONCAT || Q.input < 0 || Q.residual < 0 || Q.input == Q.residual) continue;
+      if (Q.is_output || Q.out_dtype != FI_BF16) continue;   // a model output goes to the caller's buffer: that copy stays
+      const Node& A = g->nodes[(size_t)Q.input];
+      if (A.Co % 8 || Q.Cop % 8) continue;   // the second source starts on a vector boundary and A has no padding channels
+      can_elide[(size_t)i] = stored_in_place(Q.input, i, false) && stored_in_place(Q.residual, i, true);
+    }
+    for (int32_t i = total - 1; i >= 0; --i) {   // outermost first: an inner concatenation inherits its place
+      Node& Q = g->nodes[(size_t)i];
+      if (!can_elide[(size_t)i]) continue;
+      // an inner concatenation that could be elided but whose outer one cannot still owns its tensor (root stays -1)
+      Q.elided = 1;
+      const int32_t root = Q.root >= 0 ? Q.root : i;
+      Node& A = g->nodes[(size_t)Q.input];
+      Node& Bn = g->nodes[(size_t)Q.residual];
+      A.root = root; A.chan = Q.chan;
+      Bn.root = root; Bn.chan = Q.chan + A.Co;
+    }
+  }
+}
+
+// Planner pass, after store_concat_sources_in_place: nodes that their single reader applies itself.
+static void fold_nodes_into_readers(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t total = (int32_t)g->nodes.size();
+  const int B = opts->max_batch;
+  // ---- per-channel affine nodes applied by the convolution that reads them -------------------
+  // y = act(x * scale[c] + shift[c]) (a 1x1 depthwise node: the normalisation + ReLU in front of a DenseNet
+  // layer's 1x1 convolution) read by nothing but one pointwise MFMA convolution: that convolution applies it to
+  // its input vectors on their way into LDS, with the arithmetic and the single rounding of the depthwise
+  // kernel, so the bits are the same and the node needs neither a launch nor a tensor.
+  if (!opts->separate_affine && g->wdtype == FI_BF16) {
+    std::vector<int32_t> n_readers((size_t)total, 0), only_reader((size_t)total, -1);
+    for (int32_t i = 0; i < total; ++i) {
+      const Node& nd = g->nodes[(size_t)i];
+      if (nd.input >= 0) { n_readers[(size_t)nd.input]++; only_reader[(size_t)nd.input] = i; }
+      if (nd.residual >= 0) n_readers[(size_t)nd.residual] += 2;   // a second operand: never fused
+    }
+    for (int32_t i = 0; i < total; ++i) {
+      Node& A = g->nodes[(size_t)i];
+      const int adt = g->members[(size_t)A.model].spec.act_dtype;
+      if (A.kind != K_DWCONV || A.k != 1 || A.stride != 1 || A.pad != 0 || A.residual >= 0 || A.input < 0) continue;
+      if (adt != FI_BF16 || A.is_output || A.out_dtype != FI_BF16 || A.root >= 0) continue;
+      if (!(A.act == FI_ACT_NONE || A.act == FI_ACT_RELU || A.act == FI_ACT_RELU6)) continue;   // act(0) = 0 keeps padding channels zero
+      if (n_readers[(size_t)i] != 1) continue;
+      Node& V = g->nodes[(size_t)only_reader[(size_t)i]];
+      if (V.kind != K_CONV_MFMA || V.k != 1 || V.kw != 1 || V.stride != 1 || V.pad != 0 || V.pad_w != 0) continue;
+      if (V.groups > 1 || V.Cp == 4 || V.Cp != A.Cp) continue;
+      const Node& T = g->nodes[(size_t)A.input];
+      if (T.out_dtype != FI_BF16) continue;
+      const int64_t stride = T.root >= 0 ? g->nodes[(size_t)T.root].Cop : T.Cop;
+      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * 2 >= (1ull << 31)) continue;   // the conv kernel's 32-bit byte offsets
+      V.pre = i;
+      A.elided = 1;
+    }
+    // y = x * gate[image][c] (the scaling that ends a squeeze-excite block) read by nothing but one pointwise MFMA
+    // convolution (the block's projection): the convolution multiplies its input vectors by the gate on their way
+    // into LDS, with the scaling kernel's fp32 product and single rounding.
+    for (int32_t i = 0; i < total; ++i) {
+      Node& Y = g->nodes[(size_t)i];
+      const int adt = g->members[(size_t)Y.model].spec.act_dtype;
+      if (Y.kind != K_MUL || Y.input < 0 || Y.residual < 0 || adt != FI_BF16 || Y.is_output || Y.out_dtype != FI_BF16 || Y.root >= 0) continue;
+      if (n_readers[(size_t)i] != 1) continue;
+      Node& V = g->nodes[(size_t)only_reader[(size_t)i]];
+      if (V.kind != K_CONV_MFMA || V.k != 1 || V.kw != 1 || V.stride != 1 || V.pad != 0 || V.pad_w != 0 || V.pre >= 0) continue;
+      if (V.groups > 1 || V.Cp == 4 || V.Cp != Y.Cop || V.Cp % 8) continue;
+      const Node& T = g->nodes[(size_t)Y.input];
+      const Node& G = g->nodes[(size_t)Y.residual];
+      if (T.out_dtype != FI_BF16 || G.out_dtype != FI_BF16 || G.is_output || G.root >= 0 || G.Cop != V.Cp) continue;
+      const int64_t stride = T.root >= 0 ? g->nodes[(size_t)T.root].Cop : T.Cop;
+      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * 2 >= (1ull << 31)) continue;
+      V.pre = i;
+      Y.elided = 1;
+    }
+    // shuffle_2(concat(A, B)) with equal halves (the end of a ShuffleNet unit) read by nothing else: the shuffle
+    // interleaves A and B itself and the concatenation is never built.  (A concatenation already stored in place
+    // costs nothing and stays.)
+    for (int32_t i = 0; i < total; ++i) {
+      Node& Z = g->nodes[(size_t)i];
+      if (Z.kind != K_GATHER || Z.op != FI_SHUFFLE || Z.k != 2 || Z.input < 0) continue;
+      Node& Q = g->nodes[(size_t)Z.input];
+      if (Q.kind != K_CONCAT || Q.elided || Q.root >= 0 || Q.is_output || n_readers[(size_t)Z.input] != 1 || Q.input < 0 || Q.residual < 0) continue;
+      const Node& A = g->nodes[(size_t)Q.input];
+      const Node& Bn = g->nodes[(size_t)Q.residual];
+      if (A.Co != Bn.Co || A.out_dtype != Q.out_dtype || Bn.out_dtype != Q.out_dtype || A.root >= 0 || Bn.root >= 0) continue;
+      Z.pre = Z.input;
+      Q.elided = 2;   // never built: no launch and no tensor
+    }
+  }
+}
+
 // Everything derived from the member list: union graph, levels, lanes, kernels and tiles, launch
 // schedule, activation plan, weight arena placement, workspace, descriptors.  Members whose
 // arena_off is already set keep their place in the weight arena (their bytes may be resident);
@@ -409,125 +540,9 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
-  // ---- concatenations in place --------------------------------------------------------------
-  // A concatenation copies its two sources into one tensor.  When a source's producer can write with a
-  // channel stride other than its own (the MFMA convolution and the bf16 vector kernels can) and whoever
-  // else reads that source can read with such a stride (the depthwise kernels can), the source is stored
-  // inside the concatenation's tensor from the start and the copy disappears: DenseNet blocks, Inception
-  // and fire modules then write every branch once.  Nested concatenations resolve to the outermost tensor.
-  for (Node& nd : g->nodes) { nd.root = -1; nd.chan = 0; nd.elided = 0; nd.pre = -1; }
-  if (!opts->copy_concats && g->wdtype == FI_BF16) {
-    std::vector<std::vector<int32_t>> readers((size_t)total);   // nodes reading a tensor as their first input
-    std::vector<int32_t> as_second((size_t)total, 0);           // times a tensor is a second operand (residual, gate, second source)
-    for (int32_t i = 0; i < total; ++i) {
-      const Node& nd = g->nodes[(size_t)i];
-      if (nd.input >= 0) readers[(size_t)nd.input].push_back(i);
-      if (nd.residual >= 0) as_second[(size_t)nd.residual]++;
-    }
-    std::vector<int8_t> can_elide((size_t)total, 0);
-    auto stored_in_place = [&](int32_t s, int32_t q, bool second) {
-      const Node& S = g->nodes[(size_t)s];
-      const int adt = g->members[(size_t)S.model].spec.act_dtype;
-      if (adt != FI_BF16 || S.is_output || S.out_dtype != FI_BF16 || S.Cop % 8) return false;
-      // the concatenation is the only node that takes S as a second operand (once) or lists it first (once) ...
-      if (as_second[(size_t)s] != (second ? 1 : 0)) return false;
-      int first_uses = 0;
-      for (int32_t r : readers[(size_t)s]) {
-        if (r == q) { ++first_uses; continue; }
-        if (g->nodes[(size_t)r].kind != K_DWCONV) return false;   // ... and every other reader takes an input stride
-      }
-      if (first_uses != (second ? 0 : 1)) return false;
-      switch (S.kind) {
-        case K_CONV_MFMA: return true;
-        case K_DWCONV: case K_MAXPOOL: case K_AVGPOOL: case K_GATHER: return S.Cp % 8 == 0;   // their 8-channel forms
-        case K_CONCAT: return can_elide[(size_t)s] != 0;
-        default: return false;
-      }
-    };
-    for (int32_t i = 0; i < total; ++i) {   // sources come before the concatenation that joins them
-      const Node& Q = g->nodes[(size_t)i];
-      if (Q.kind != K_CONCAT || Q.input < 0 || Q.residual < 0 || Q.input == Q.residual) continue;
-      if (Q.is_output || Q.out_dtype != FI_BF16) continue;   // a model output goes to the caller's buffer: that copy stays
-      const Node& A = g->nodes[(size_t)Q.input];
-      if (A.Co % 8 || Q.Cop % 8) continue;   // the second source starts on a vector boundary and A has no padding channels
-      can_elide[(size_t)i] = stored_in_place(Q.input, i, false) && stored_in_place(Q.residual, i, true);
-    }
-    for (int32_t i = total - 1; i >= 0; --i) {   // outermost first: an inner concatenation inherits its place
-      Node& Q = g->nodes[(size_t)i];
-      if (!can_elide[(size_t)i]) continue;
-      // an inner concatenation that could be elided but whose outer one cannot still owns its tensor (root stays -1)
-      Q.elided = 1;
-      const int32_t root = Q.root >= 0 ? Q.root : i;
-      Node& A = g->nodes[(size_t)Q.input];
-      Node& Bn = g->nodes[(size_t)Q.residual];
-      A.root = root; A.chan = Q.chan;
-      Bn.root = root; Bn.chan = Q.chan + A.Co;
-    }
-  }
-
-  // ---- per-channel affine nodes applied by the convolution that reads them -------------------
-  // y = act(x * scale[c] + shift[c]) (a 1x1 depthwise node: the normalisation + ReLU in front of a DenseNet
-  // layer's 1x1 convolution) read by nothing but one pointwise MFMA convolution: that convolution applies it to
-  // its input vectors on their way into LDS, with the arithmetic and the single rounding of the depthwise
-  // kernel, so the bits are the same and the node needs neither a launch nor a tensor.
-  if (!opts->separate_affine && g->wdtype == FI_BF16) {
-    std::vector<int32_t> n_readers((size_t)total, 0), only_reader((size_t)total, -1);
-    for (int32_t i = 0; i < total; ++i) {
-      const Node& nd = g->nodes[(size_t)i];
-      if (nd.input >= 0) { n_readers[(size_t)nd.input]++; only_reader[(size_t)nd.input] = i; }
-      if (nd.residual >= 0) n_readers[(size_t)nd.residual] += 2;   // a second operand: never fused
-    }
-    for (int32_t i = 0; i < total; ++i) {
-      Node& A = g->nodes[(size_t)i];
-      const int adt = g->members[(size_t)A.model].spec.act_dtype;
-      if (A.kind != K_DWCONV || A.k != 1 || A.stride != 1 || A.pad != 0 || A.residual >= 0 || A.input < 0) continue;
-      if (adt != FI_BF16 || A.is_output || A.out_dtype != FI_BF16 || A.root >= 0) continue;
-      if (!(A.act == FI_ACT_NONE || A.act == FI_ACT_RELU || A.act == FI_ACT_RELU6)) continue;   // act(0) = 0 keeps padding channels zero
-      if (n_readers[(size_t)i] != 1) continue;
-      Node& V = g->nodes[(size_t)only_reader[(size_t)i]];
-      if (V.kind != K_CONV_MFMA || V.k != 1 || V.kw != 1 || V.stride != 1 || V.pad != 0 || V.pad_w != 0) continue;
-      if (V.groups > 1 || V.Cp == 4 || V.Cp != A.Cp) continue;
-      const Node& T = g->nodes[(size_t)A.input];
-      if (T.out_dtype != FI_BF16) continue;
-      const int64_t stride = T.root >= 0 ? g->nodes[(size_t)T.root].Cop : T.Cop;
-      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * 2 >= (1ull << 31)) continue;   // the conv kernel's 32-bit byte offsets
-      V.pre = i;
-      A.elided = 1;
-    }
-    // y = x * gate[image][c] (the scaling that ends a squeeze-excite block) read by nothing but one pointwise MFMA
-    // convolution (the block's projection): the convolution multiplies its input vectors by the gate on their way
-    // into LDS, with the scaling kernel's fp32 product and single rounding.
-    for (int32_t i = 0; i < total; ++i) {
-      Node& Y = g->nodes[(size_t)i];
-      const int adt = g->members[(size_t)Y.model].spec.act_dtype;
-      if (Y.kind != K_MUL || Y.input < 0 || Y.residual < 0 || adt != FI_BF16 || Y.is_output || Y.out_dtype != FI_BF16 || Y.root >= 0) continue;
-      if (n_readers[(size_t)i] != 1) continue;
-      Node& V = g->nodes[(size_t)only_reader[(size_t)i]];
-      if (V.kind != K_CONV_MFMA || V.k != 1 || V.kw != 1 || V.stride != 1 || V.pad != 0 || V.pad_w != 0 || V.pre >= 0) continue;
-      if (V.groups > 1 || V.Cp == 4 || V.Cp != Y.Cop || V.Cp % 8) continue;
-      const Node& T = g->nodes[(size_t)Y.input];
-      const Node& G = g->nodes[(size_t)Y.residual];
-      if (T.out_dtype != FI_BF16 || G.out_dtype != FI_BF16 || G.is_output || G.root >= 0 || G.Cop != V.Cp) continue;
-      const int64_t stride = T.root >= 0 ? g->nodes[(size_t)T.root].Cop : T.Cop;
-      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * 2 >= (1ull << 31)) continue;
-      V.pre = i;
-      Y.elided = 1;
-    }
-    // shuffle_2(concat(A, B)) with equal halves (the end of a ShuffleNet unit) read by nothing else: the shuffle
-    // interleaves A and B itself and the concatenation is never built.  (A concatenation already stored in place
-    // costs nothing and stays.)
-    for (int32_t i = 0; i < total; ++i) {
-      Node& Z = g->nodes[(size_t)i];
-      if (Z.kind != K_GATHER || Z.op != FI_SHUFFLE || Z.k != 2 || Z.input < 0) continue;
-      Node& Q = g->nodes[(size_t)Z.input];
-      if (Q.kind != K_CONCAT || Q.elided || Q.root >= 0 || Q.is_output || n_readers[(size_t)Z.input] != 1 || Q.input < 0 || Q.residual < 0) continue;
-      const Node& A = g->nodes[(size_t)Q.input];
-      const Node& Bn = g->nodes[(size_t)Q.residual];
-      if (A.Co != Bn.Co || A.out_dtype != Q.out_dtype || Bn.out_dtype != Q.out_dtype || A.root >= 0 || Bn.root >= 0) continue;
-      Z.pre = Z.input;
-      Q.elided = 2;   // never built: no launch and no tensor
-    }
-  }
+  // ---- nodes that need no launch: concatenations written in place, nodes applied by their reader ----
+  store_concat_sources_in_place(g);
+  fold_nodes_into_readers(g);
 
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
   //      share a launch, FI_MAX_GROUP problems at most --------------------------------------
