@@ -193,7 +193,8 @@ def test_random_graphs_with_concatenating_blocks(seed):
     x = gen.make_input(77 + seed, batch, first.in_c, first.in_h, first.in_w, "normal", "bf16")
     print(f"seed {seed}: batch {batch}, input {first.in_c}x{first.in_h}x{first.in_w}, nodes {[len(m[0].layers) for m in mem]}", flush=True)
     res, launches = {}, {}
-    for key, kw in (("fast", {}), ("plain", dict(copy_concats=True, separate_affine=True))):
+    for key, kw in (("fast", {}), ("plain", dict(copy_concats=True, separate_affine=True)), ("graph", dict(use_graph=True)),
+                    ("ungrouped", dict(group_levels=False)), ("serial", dict(serial_lanes=True))):
         g = harness.GpuDag(mem, batch + 1, **kw)
         try:
             launches[key] = g.dag.query().n_launches
@@ -201,8 +202,9 @@ def test_random_graphs_with_concatenating_blocks(seed):
         finally:
             g.close()
     assert launches["fast"] <= launches["plain"]
-    for i, (y0, y1) in enumerate(zip(res["fast"], res["plain"])):
-        assert np.array_equal(y0, y1, equal_nan=True), f"member {i}: the two schedules differ"
+    for key in ("plain", "graph", "ungrouped", "serial"):   # (the folded schedule also replayed as a HIP graph, ungrouped, on one stream)
+        for i, (y0, y1) in enumerate(zip(res["fast"], res[key])):
+            assert np.array_equal(y0, y1, equal_nan=True), f"member {i}: the folded schedule differs from {key}"
     for i, (m, blob, _) in enumerate(mem):
         y = res["fast"][i]
         ref_f = harness.oracle_nhwc(m, blob, x, False)
