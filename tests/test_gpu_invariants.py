@@ -282,13 +282,25 @@ def test_members_that_stage_the_input_differently():
             assert harness.rel_l2(y, ref) <= (1e-4 if i == 2 else 1e-2), (order, i)
 
 
-def test_per_member_batches():
+def _folded_members(hw=64):
+    """Members whose schedules fold nodes: concatenations in place, absorbed affine nodes and scalings, group walks,
+    interleaving shuffles; two of them of one architecture (grouped launches)."""
+    fams = ["densenet121", "googlenet", "mobilenet_v3_small", "shufflenet_v2_x1_0", "densenet121"]
+    out = []
+    for i, f in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=hw)
+        out.append((m, gen.make_blob(m, 1200 + i), None))
+    return out
+
+
+@pytest.mark.parametrize("members", ["classic", "folded"])
+def test_per_member_batches(members):
     """The manager aggregates requests per model, so members arrive at a pass with different numbers of images:
     member m on batches[m] images gives, bit for bit, what the same DAG gives for those images at the full
     batch; a member with no image sits the pass out and its output buffer is not touched."""
     import torch
     import paper_2410_21120_amd as fi
-    mem = _members()
+    mem = _members() if members == "classic" else _folded_members()
     B = 5
     xs = [gen.make_input(80 + i, B, 3, 64, 64, "normal", "bf16") for i in range(len(mem))]
     specs, keep = [], []
@@ -326,14 +338,19 @@ def test_per_member_batches():
         dag.destroy()
 
 
-def test_lanes_run_alone_and_side_by_side():
+@pytest.mark.parametrize("members", ["classic", "folded"])
+def test_lanes_run_alone_and_side_by_side(members):
     """fi_run_lane issues one lane of the schedule on the caller's stream: every lane on a stream of its own, all
     in flight together, gives each member the bits of the whole-DAG pass; a lane run alone leaves the members of
     the other lanes untouched."""
     import torch
     import paper_2410_21120_amd as fi
-    mem = _members()   # five architectures: five lanes
-    mem = mem + [(mem[0][0], gen.make_blob(mem[0][0], 2222), None)]   # and a second ResNet-18 that shares lane 0
+    if members == "classic":
+        mem = _members()   # five architectures: five lanes
+        mem = mem + [(mem[0][0], gen.make_blob(mem[0][0], 2222), None)]   # and a second ResNet-18 that shares lane 0
+    else:
+        mem = _folded_members()   # four architectures, the last member shares lane 0 with the first
+    n_arch = len(mem) - 1
     B = 3
     xs = [gen.make_input(90 + i, B, 3, 64, 64, "normal", "bf16") for i in range(len(mem))]
     specs, keep = [], []
@@ -347,9 +364,9 @@ def test_lanes_run_alone_and_side_by_side():
     try:
         q = dag.query()
         lane_of = [mi.lane for mi in dag.members()]
-        assert q.n_lanes == 5 and lane_of[0] == lane_of[5] and len(set(lane_of)) == 5
+        assert q.n_lanes == n_arch and lane_of[0] == lane_of[-1] and len(set(lane_of)) == n_arch
         dev_in = [torch.from_numpy(gen.to_nhwc_storage(x, "bf16").view(np.int16)).cuda() for x in xs]
-        batches = [3, 2, 1, 3, 2, 1]
+        batches = [3, 2, 1, 3, 2, 1][:len(mem) - 1] + [1]
         ref = [torch.full((B, 1000), -3.0, dtype=torch.float32, device="cuda:0") for _ in mem]
         dag.run_batches([t.data_ptr() for t in dev_in], batches, [o.data_ptr() for o in ref], stream)
         torch.cuda.synchronize()
