@@ -12,10 +12,13 @@ from workloads import gen, zoo
 pytestmark = pytest.mark.gpu
 
 
-def _dag(max_batch, hw=64):
+FOLDED = [("densenet121", None), ("mobilenet_v3_small", None), ("densenet121", None), ("googlenet", None)]   # schedules with folded nodes
+
+
+def _dag(max_batch, hw=64, fams=None):
     import torch
     import paper_2410_21120_amd as fi
-    fams = [("resnet18", None), ("mobilenetv2", "f32"), ("resnet18", None), ("vgg11", None)]
+    fams = fams or [("resnet18", None), ("mobilenetv2", "f32"), ("resnet18", None), ("vgg11", None)]
     specs, keep, models = [], [], []
     for i, (f, act) in enumerate(fams):
         m = zoo.FAMILIES[f](hw=hw)
@@ -30,11 +33,12 @@ def _dag(max_batch, hw=64):
     return dag, models
 
 
-def test_every_request_gets_its_member_alone_output():
+@pytest.mark.parametrize("fams", [None, FOLDED], ids=["classic", "folded"])
+def test_every_request_gets_its_member_alone_output(fams):
     import torch
     import paper_2410_21120_amd as fi
     B, hw, n_img = 4, 64, 6
-    dag, models = _dag(B, hw)
+    dag, models = _dag(B, hw, fams)
     n = len(models)
     stream = torch.cuda.current_stream().cuda_stream
     try:
