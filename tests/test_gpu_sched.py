@@ -10,7 +10,8 @@ from workloads import gen, zoo
 pytestmark = pytest.mark.gpu
 
 HW = 64
-FAMS = [("resnet18", None), ("vgg16", None), ("mobilenetv2", "f32"), ("resnet50", None), ("resnet18", None), ("mobilenetv2", "f32")]
+FAMS = [("resnet18", None), ("vgg16", None), ("mobilenetv2", "f32"), ("resnet50", None), ("resnet18", None), ("mobilenetv2", "f32"),
+        ("densenet121", None), ("googlenet", None)]   # ... and two whose schedules fold nodes (concatenations in place, absorbed affine nodes)
 
 
 def _setup(batch):
