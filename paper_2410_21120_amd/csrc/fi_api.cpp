@@ -371,16 +371,16 @@ static void fold_nodes_into_readers(fi_dag* g) {
     for (int32_t i = 0; i < total; ++i) {
       Node& Y = g->nodes[(size_t)i];
       const int adt = g->members[(size_t)Y.model].spec.act_dtype;
-      if (Y.kind != K_MUL || Y.input < 0 || Y.residual < 0 || adt != FI_BF16 || Y.is_output || Y.out_dtype != FI_BF16 || Y.root >= 0) continue;
+      if (Y.kind != K_MUL || Y.input < 0 || Y.residual < 0 || Y.is_output || Y.out_dtype != adt || Y.root >= 0) continue;   // (bf16 or fp32 tensors)
       if (n_readers[(size_t)i] != 1) continue;
       Node& V = g->nodes[(size_t)only_reader[(size_t)i]];
       if (V.kind != K_CONV_MFMA || V.k != 1 || V.kw != 1 || V.stride != 1 || V.pad != 0 || V.pad_w != 0 || V.pre >= 0) continue;
       if (V.groups > 1 || V.Cp == 4 || V.Cp != Y.Cop || V.Cp % 8) continue;
       const Node& T = g->nodes[(size_t)Y.input];
       const Node& G = g->nodes[(size_t)Y.residual];
-      if (T.out_dtype != FI_BF16 || G.out_dtype != FI_BF16 || G.is_output || G.root >= 0 || G.Cop != V.Cp) continue;
+      if (T.out_dtype != adt || G.out_dtype != adt || G.is_output || G.root >= 0 || G.Cop != V.Cp) continue;
       const int64_t stride = T.root >= 0 ? g->nodes[(size_t)T.root].Cop : T.Cop;
-      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * 2 >= (1ull << 31)) continue;
+      if ((uint64_t)B * V.H * V.W * (uint64_t)stride * esize(adt) >= (1ull << 31)) continue;
       V.pre = i;
       Y.elided = 1;
     }

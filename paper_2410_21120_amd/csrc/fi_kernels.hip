@@ -260,7 +260,8 @@ __device__ __forceinline__ void finish_row4(const KArgs& a, const Desc& d, int p
 template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false, int PRE = 0>
 __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   static_assert(!GROUPED || (!WIDE && !C4), "the group walk exists for bf16 activations with 8-channel vectors");
-  static_assert(!PRE || (!WIDE && !C4 && !GROUPED), "the fused affine stage exists for dense pointwise convolutions on bf16 activations");
+  static_assert(!PRE || (!C4 && !GROUPED && (!WIDE || PRE == 2)),
+                "input-side stages exist for dense pointwise convolutions: the affine one on bf16 activations, the gate on either");
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
   constexpr int RPP = NT / 8;            // tile rows staged per pass (8 threads per 64-element row)
   constexpr int AE = WIDE ? 4 : 2;       // bytes per stored activation element
@@ -300,7 +301,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.abase + d.x_off), 0, batch > 0 ? x_bytes : 0, 0x00020000);
   const bf16_t* const pre_w = PRE == 1 ? reinterpret_cast<const bf16_t*>(a.wbase + d.pw_off)
                             : PRE == 2 ? reinterpret_cast<const bf16_t*>(a.abase + d.pw_off) : nullptr;   // scale vector / gate tensor
-  const float* const pre_b = PRE == 1 ? reinterpret_cast<const float*>(a.wbase + d.pb_off) : nullptr;
+  const float* const pre_b = PRE == 1 ? reinterpret_cast<const float*>(a.wbase + d.pb_off)
+                           : (PRE == 2 && WIDE) ? reinterpret_cast<const float*>(a.abase + d.pw_off) : nullptr;   // shift vector / fp32 gate tensor
 
   // staging assignment: thread -> (row, 8-element k vector); 8 threads cover one 128-byte row
   const int srow = tid >> 3, kvec = (tid & 7) * 8;
@@ -379,7 +381,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   uint4 bv[1][BR];
   uint4 pre_s[1];        // PRE == 1: scale (8 bf16) and shift (8 fp32) of this thread's channels in the tile being fetched
   float4 pre_t[1][2];
-  uint4 pre_g[1][PRE == 2 ? AR : 1];   // PRE == 2: the gate vectors of this thread's rows
+  uint4 pre_g[1][PRE == 2 ? AR : 1][AV];   // PRE == 2: the gate vectors of this thread's rows
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
 
 #define FI_FETCH(KT, S)                                                                           \
@@ -416,7 +418,10 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     }                                                                                             \
     if constexpr (PRE == 2) {                                                                     \
       _Pragma("unroll") for (int i = 0; i < AR; ++i)                                              \
-          pre_g[S][i] = kr == 0 ? *reinterpret_cast<const uint4*>(pre_w + a_gate[i] + kc) : make_uint4(0, 0, 0, 0); \
+      _Pragma("unroll") for (int h = 0; h < AV; ++h) {                                            \
+        if constexpr (WIDE) pre_g[S][i][h] = kr == 0 ? *reinterpret_cast<const uint4*>(pre_b + a_gate[i] + kc + 4 * h) : make_uint4(0, 0, 0, 0); \
+        else pre_g[S][i][h] = kr == 0 ? *reinterpret_cast<const uint4*>(pre_w + a_gate[i] + kc) : make_uint4(0, 0, 0, 0); \
+      }                                                                                           \
     }                                                                                             \
     if constexpr (PRE == 1) { /* channels past Cp (the tile tail) have walked on to filter row 1: no stage, the input reads as zero */ \
       const bool pok = kr == 0;                                                                   \
@@ -445,8 +450,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     bf16_t* const Ap = As + (S) * STAGE;                                                          \
     bf16_t* const Bp = Bs + (S) * STAGE;                                                          \
     _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
-      if constexpr (PRE == 2) {                                                                   \
-        const uint32_t gw[4] = {pre_g[S][i].x, pre_g[S][i].y, pre_g[S][i].z, pre_g[S][i].w};      \
+      if constexpr (PRE == 2 && !WIDE) {                                                          \
+        const uint32_t gw[4] = {pre_g[S][i][0].x, pre_g[S][i][0].y, pre_g[S][i][0].z, pre_g[S][i][0].w}; \
         u32x4 pk;                                                                                 \
         _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
           const uint32_t xw = av[S][i][0][e];                                                     \
@@ -473,8 +478,17 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       } else {                                                                                    \
         u32x4 hi, lo;                                                                             \
         _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
-          const float x0 = __uint_as_float(av[S][i][e >> 1][(2 * e) & 3]);                        \
-          const float x1 = __uint_as_float(av[S][i][e >> 1][(2 * e + 1) & 3]);                    \
+          float x0 = __uint_as_float(av[S][i][e >> 1][(2 * e) & 3]);                              \
+          float x1 = __uint_as_float(av[S][i][e >> 1][(2 * e + 1) & 3]);                          \
+          if constexpr (PRE == 2) { /* fp32 tensors: the scaled value is an fp32 product, as the scaling kernel stores it */ \
+            const uint4 gq = pre_g[S][i][e >> 1];                                                 \
+            const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};                                      \
+            x0 = x0 * __uint_as_float(gw[(2 * e) & 3]);                                           \
+            x1 = x1 * __uint_as_float(gw[(2 * e + 1) & 3]);                                       \
+            /* the product is rounded to fp32 here, as the stored tensor would be: keep the compiler from */ \
+            /* contracting it into the subtraction of the hi term below (an fma would skip that rounding) */ \
+            asm volatile("" : "+v"(x0), "+v"(x1));                                                \
+          }                                                                                       \
           const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);                                            \
           hi[e] = h0 | (h1 << 16);                                                                \
           lo[e] = pack_bf16x2(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h1 << 16));    \
@@ -1567,7 +1581,7 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
     const Desc& t = hd[(size_t)(L.first_desc + i)];
     if (L.kind == K_STAGE || (t.xs == t.Cp && t.ys == t.Cop)) continue;
     const bool reads = (L.kind == K_DWCONV && wb && ab && hd[(size_t)L.first_desc].vec) ||
-                       ((L.kind == K_CONV_MFMA || L.kind == K_REDUCE) && ab && t.pre_kind != 0);   // (the reduce launch shares the node's descriptor and reads no input)
+                       ((L.kind == K_CONV_MFMA || L.kind == K_REDUCE) && (ab ? t.pre_kind != 0 : t.pre_kind == 2));   // (the reduce launch shares the node's descriptor and reads no input)
     const bool writes = ab && !t.ext && !t.out_f32 &&
                         (L.kind == K_CONV_MFMA || L.kind == K_REDUCE || (L.kind == K_DWCONV && wb && hd[(size_t)L.first_desc].vec) ||
                          ((L.kind == K_MAXPOOL || L.kind == K_AVGPOOL || L.kind == K_GATHER) && t.vec));
@@ -1592,6 +1606,18 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
         }
         if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false, true>, nb, 256, a, s);
         if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false, true>, nb, 256, a, s);
+        return (int)hipErrorInvalidValue;
+      }
+      if (!ab && hd[(size_t)L.first_desc].pre_kind != 0) {  // fp32 activations with the squeeze-excite gate applied on the input side
+        for (int i = 0; i < L.n; ++i) {
+          const Desc& t = hd[(size_t)(L.first_desc + i)];
+          if (t.pre_kind != 2 || t.pw_off == kNone || t.k != 1 || t.kw != 1 || t.stride != 1 || t.pad != 0 || t.pad_w != 0 || t.gin > 0 ||
+              t.xs < t.Cp || t.Cp % 8 || (uint64_t)t.H * t.W * (uint64_t)t.xs * 4 * (uint64_t)a.batch[i] >= (1ull << 31))
+            return (int)hipErrorInvalidValue;
+        }
+        if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, true, false, false, 2>, nb, 256, a, s);
+        if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, true, false, false, 2>, nb, 256, a, s);
+        if (L.tile == T_64x64) return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, true, false, false, 2>, nb, 256, a, s);
         return (int)hipErrorInvalidValue;
       }
       if (!ab) {  // fp32 activations: split-bf16 inputs

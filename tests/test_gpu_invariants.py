@@ -446,7 +446,7 @@ def _dense_block(c0, growth, layers, h, w):
     return m.shapes()
 
 
-@pytest.mark.parametrize("case", ["densenet121", "densenet161", "mobilenet_v3_large", "mobilenet_v3_small", (16, 8, 3, 9, 7), (64, 32, 5, 28, 28),
+@pytest.mark.parametrize("case", ["densenet121", "densenet161", "mobilenet_v3_large", "mobilenet_v3_small", "mobilenet_v3_large:f32", (16, 8, 3, 9, 7), (64, 32, 5, 28, 28),
                                   (24, 16, 2, 6, 6), (200, 40, 2, 14, 14)])
 def test_affine_applied_by_the_convolution_equals_its_own_launch(case):
     """The per-channel affine + ReLU in front of a dense layer's 1x1 convolution, applied by that convolution while it
@@ -455,8 +455,11 @@ def test_affine_applied_by_the_convolution_equals_its_own_launch(case):
     inputs inside a concatenation's tensor; also with copied concatenations (the input then has its own stride).  The
     MobileNetV3s cover the other absorbed node: the squeeze-excite scaling applied by the block's projection."""
     from tests import harness
+    act = None
     if isinstance(case, str):
-        m, hw = zoo.FAMILIES[case](hw=64), (64, 64)
+        fam, _, act = case.partition(":")   # "family:f32": fp32-stored activations (the scaling is absorbed there too)
+        act = act or None
+        m, hw = zoo.FAMILIES[fam](hw=64), (64, 64)
     else:
         m, hw = _dense_block(*case), case[3:]
     blobs = [gen.make_blob(m, 400 + i) for i in range(2)]
@@ -464,7 +467,7 @@ def test_affine_applied_by_the_convolution_equals_its_own_launch(case):
     res, launches = {}, {}
     for key, kw in (("fused", {}), ("separate", dict(separate_affine=True)), ("fused_copy", dict(copy_concats=True)),
                     ("plain", dict(separate_affine=True, copy_concats=True))):
-        g = harness.GpuDag([(m, b, None) for b in blobs], 3, **kw)
+        g = harness.GpuDag([(m, b, act) for b in blobs], 3, **kw)
         try:
             launches[key] = g.dag.query().n_launches
             res[key] = [g.run(x), g.run(x[:1])]
