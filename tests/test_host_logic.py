@@ -565,3 +565,41 @@ def test_random_graphs_with_concatenating_blocks_compile_both_ways(seed):
     ops = [L.op for L in m.layers]
     if "concat" not in ops and not any(L.op == "dwconv" and L.k == 1 for L in m.layers):
         assert qf.n_launches == qp.n_launches
+
+
+def test_folded_schedules_of_the_concatenating_and_gated_families():
+    """What the planner folds, family by family (launch names of the compiled schedule): DenseNet-121 has neither
+    concatenation nor affine (depthwise) launches left except the affine nodes a pooling layer reads; GoogLeNet and
+    SqueezeNet have no concatenation launch; MobileNetV3 has no scaling launch, with bf16 and with fp32 activations;
+    ShuffleNet V2 x1.0 (58-channel halves) has no concatenation launch because its shuffles interleave.  With the two
+    build options set the plain schedule is back."""
+    def names(fam, act=None, **kw):
+        m = zoo.FAMILIES[fam](hw=64)
+        blob = gen.make_blob(m, 3)
+        spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        d = fi.Dag([spec], 2, fi.HostAllocators(), keepalive=(keep, blob), **kw)
+        return [L.name.decode() for L in d.launches()], sum(1 for L in m.layers if L.op == "concat"), m
+    plain = dict(copy_concats=True, separate_affine=True)
+    n, cats, m = names("densenet121")
+    affine = sum(1 for L in m.layers if L.op == "dwconv" and L.k == 1)
+    assert cats == 58 and "concat" not in n and n.count("dwconv") <= 1 < affine      # only the final normalisation (read by a pooling node) keeps its launch
+    n_plain, _, _ = names("densenet121", **plain)
+    assert n_plain.count("concat") == 58 and n_plain.count("dwconv") == affine
+    for fam in ("googlenet", "squeezenet1_1", "shufflenet_v2_x1_0", "shufflenet_v2_x0_5"):
+        n, cats, _ = names(fam)
+        assert cats > 0 and "concat" not in n, fam
+        assert names(fam, **plain)[0].count("concat") == cats, fam
+    for act in (None, "f32"):
+        n, _, m = names("mobilenet_v3_large", act)
+        gates = sum(1 for L in m.layers if L.op == "mul")
+        assert gates == 8 and "channel_scale" not in n
+        assert names("mobilenet_v3_large", act, **plain)[0].count("channel_scale") == gates
+    # the grouped 3x3 convolutions of ResNeXt run on 64-column tiles (a tile then walks the channels of its own groups only)
+    m = zoo.FAMILIES["resnext50_32x4d"](hw=64)
+    blob = gen.make_blob(m, 3)
+    spec, keep = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    d = fi.Dag([spec], 2, fi.HostAllocators(), keepalive=(keep, blob))
+    launch_names = [L.name.decode() for L in d.launches()]
+    grouped = [i for i, L in enumerate(m.layers) if L.op == "conv" and L.groups > 1]
+    assert len(grouped) == 16
+    assert all(launch_names[d.nodes()[i].launch] in ("conv_mfma_256x64", "conv_mfma_128x64", "conv_mfma_64x64") for i in grouped)
