@@ -211,9 +211,18 @@ typedef struct {
   char name[32];             /* kernel family name, e.g. "conv_mfma_128x128" */
 } fi_launch_info;
 
-/* Size / content of a member's device-layout blob (repository time, host only). */
+/* Section IV, "DNN model repository": the repository keeps every model ready to
+ * be served, with its memory requirement.  Here: the size and the content of a
+ * member's device-layout blob, computed at repository time on the host (no device
+ * is touched).  model: host, borrowed for the call, canonical weights
+ * (weights_packed == 0).  bytes: out, untouched on error.  FI_EINVAL for a null
+ * argument or a malformed spec, FI_EUNSUPPORTED for an operator or size the
+ * kernels do not cover. */
 fi_status fi_model_packed_size(const fi_model_spec* model, uint64_t* bytes);
-/* dst (host, caller-owned, ideally pinned) receives fi_model_packed_size bytes. */
+/* Same passage.  dst (host, caller-owned, ideally pinned) receives
+ * fi_model_packed_size bytes: the exact image of the member's range in the weight
+ * arena, so that a later load is a plain copy.  FI_EINVAL when dst_bytes is too
+ * small or the blob is already packed; dst is then untouched. */
 fi_status fi_model_pack(const fi_model_spec* model, void* dst, uint64_t dst_bytes);
 
 /* Algorithm 1, DAG compilation: union the members' graphs, assign depth levels,
@@ -231,8 +240,16 @@ fi_status fi_member(const fi_dag* dag, int32_t m, fi_member_info* info); /* m in
  * weight byte is read.  Same errors as fi_build_dag. */
 fi_status fi_footprint(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, fi_dag_info* info);
 
-/* Load: one device allocation, one pinned-to-device copy of the weight arena
- * (asynchronous on hip_stream; hip_stream is a hipStream_t, NULL = default stream). */
+/* Section IV-B, "Efficient memory allocation" and "Fewer memory calls": the whole
+ * DAG gets ONE device allocation (weight arena, activation arena and workspace
+ * together, through fi_build_opts.dev_alloc when given) and, in FI_LOAD_ONE_COPY,
+ * ONE pinned-to-device copy of fi_dag_info.arena_bytes bytes (in
+ * FI_LOAD_PER_MODEL: the 256-byte header plus one copy per member).  The copy is
+ * asynchronous on hip_stream (a hipStream_t, NULL = default stream); every later
+ * pass, on whichever stream it is issued, is ordered after it by the library.
+ * BUILT -> LOADED.  FI_ESTATE when already loaded, FI_ENOMEM_DEVICE when the
+ * allocation fails, FI_EHIP when a copy cannot be issued (the handle stays BUILT
+ * and the allocation is returned). */
 fi_status fi_load(fi_dag* dag, void* hip_stream);
 
 /* Algorithm 1, DAG inference: one pass of the launch schedule, asynchronous on
@@ -395,9 +412,16 @@ fi_status fi_server_swap(fi_server* srv, int32_t slot, const fi_model_spec* mode
 /* Serves what is queued, joins the worker, releases the buffers and the handle; the DAG stays LOADED. */
 fi_status fi_server_stop(fi_server* srv);
 
-/* Synchronise, release the device allocation; the handle returns to BUILT. */
+/* Sections I and III (problem statement: models are swapped in and out of device
+ * memory many times a day; C3, low overhead): the swap-out half.  Synchronises the
+ * device, returns the one allocation (through fi_build_opts.dev_free when given);
+ * the handle goes back to BUILT with its plan and pinned image intact, so the same
+ * DAG can be loaded again without recompiling.  FI_ESTATE unless LOADED. */
 fi_status fi_unload(fi_dag* dag);
-void fi_destroy(fi_dag* dag); /* unloads if needed; NULL is allowed */
+/* Same passages: the end of a DAG's life.  Unloads if needed, frees the pinned image
+ * and the plan; the specs and host blobs the handle borrowed are the caller's again.
+ * NULL is allowed. */
+void fi_destroy(fi_dag* dag);
 
 const char* fi_last_error(void); /* thread-local, valid until the next call on this thread */
 const char* fi_version(void);

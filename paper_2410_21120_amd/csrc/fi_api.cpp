@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cstdio>
 #include <cstring>
@@ -53,7 +54,8 @@ struct fi_dag {
   int32_t n_levels = 0;
   int32_t wdtype = FI_BF16;
   uint64_t desc_bytes = 0, arena_bytes = 0, act_bytes = 0, workspace_bytes = 0, device_bytes = 0;
-  uint64_t image_bytes = 0;           // bytes of the pinned image (whole arena, or tables only)
+  uint64_t image_bytes = 0;           // bytes of the pinned image that a load copies (whole arena, or header only)
+  uint64_t image_capacity = 0;        // bytes the pinned allocation holds (a swap may shrink image_bytes, never this)
   std::vector<fi::StageTensor> stages;  // staged inputs: one per activation dtype, or one per member
   uint8_t* image = nullptr;           // pinned host image
   uint8_t* dev = nullptr;             // the one device allocation (LOADED only)
@@ -61,6 +63,7 @@ struct fi_dag {
   uint64_t last_h2d_bytes = 0;        // bytes and copies of the most recent load or member swap
   int32_t last_h2d_copies = 0;
   hipEvent_t copy_done = nullptr;     // recorded after the latest copy out of the pinned image
+  std::atomic<bool> copy_pending{false};   // copy_done may not have completed yet: runs order their stream after it
   int32_t state = 0;
   uint64_t macs = 0;
   // captured launch schedule (use_graph): valid for exactly these call arguments
@@ -71,6 +74,7 @@ struct fi_dag {
   int32_t g_batch = 0;
   const void* g_input = nullptr;
   std::vector<void*> g_outputs;
+  bool capturing = false;             // run_impl is being recorded into a graph: no wait on events from outside it
 };
 
 using namespace fi;
@@ -256,6 +260,7 @@ static fi_status build_core(const fi_model_spec* models, int32_t n, const fi_bui
 
   // ---- pinned image: the bytes fi_load copies ----------------------------------------------
   g->image_bytes = opts->load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;
+  g->image_capacity = g->image_bytes;
   g->image = static_cast<uint8_t*>(pin_alloc(*opts, (size_t)g->image_bytes));
   if (!g->image) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)g->image_bytes); return FI_ENOMEM_HOST; }
   std::memset(g->image, 0, (size_t)g->desc_bytes);
@@ -942,13 +947,21 @@ fi_status fi_load(fi_dag* g, void* stream) {
   if (!g) { set_error("null handle"); return FI_EINVAL; }
   if (g->state != 0) { set_error("fi_load: handle is already loaded"); return FI_ESTATE; }
   const uint64_t want = g->device_bytes + g->opts.swap_headroom_bytes;
+  // what the load copies is the plan's arena (or its header), not whatever the pinned allocation can hold:
+  // a member swap may have left the plan smaller than the image once was
+  const uint64_t copy_bytes = g->opts.load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;
+  if (copy_bytes > want || copy_bytes > g->image_capacity) {
+    set_error("fi_load: the arena image (%llu bytes) does not fit the pinned image (%llu) or the device allocation (%llu)",
+              (unsigned long long)copy_bytes, (unsigned long long)g->image_capacity, (unsigned long long)want);
+    return FI_ESTATE;
+  }
   uint8_t* d = nullptr;
   if (g->opts.dev_alloc) d = static_cast<uint8_t*>(g->opts.dev_alloc((size_t)want, g->opts.user));
   else if (hipMalloc(reinterpret_cast<void**>(&d), (size_t)want) != hipSuccess) { (void)hipGetLastError(); d = nullptr; }
   if (!d) { set_error("device allocation of %llu bytes failed", (unsigned long long)want); return FI_ENOMEM_DEVICE; }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = hipMemcpyAsync(d, g->image, (size_t)g->image_bytes, hipMemcpyHostToDevice, s);
-  g->last_h2d_bytes = g->image_bytes; g->last_h2d_copies = 1;
+  hipError_t e = hipMemcpyAsync(d, g->image, (size_t)copy_bytes, hipMemcpyHostToDevice, s);
+  g->last_h2d_bytes = copy_bytes; g->last_h2d_copies = 1;
   if (e == hipSuccess && g->opts.load_mode == FI_LOAD_PER_MODEL)
     for (const Member& mb : g->members) {
       e = hipMemcpyAsync(d + mb.arena_off, mb.spec.weights, (size_t)mb.plan.packed_bytes, hipMemcpyHostToDevice, s);
@@ -961,12 +974,23 @@ fi_status fi_load(fi_dag* g, void* stream) {
     return FI_EHIP;
   }
   if (!g->copy_done && hipEventCreateWithFlags(&g->copy_done, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); g->copy_done = nullptr; }
-  if (g->copy_done) (void)hipEventRecord(g->copy_done, s);
+  if (g->copy_done) { (void)hipEventRecord(g->copy_done, s); g->copy_pending.store(true); }
+  else (void)hipStreamSynchronize(s);   // no event to order later runs after the copy: finish it here
   ensure_lanes(g);
   g->dev = d;
   g->dev_capacity = want;
   g->state = 1;
   return FI_OK;
+}
+
+// The weight copy of a load or a member swap is asynchronous on the stream it was given.  A pass may be issued
+// to any other stream (a lane worker's, a caller's second stream), so every pass first orders its stream after
+// that copy; once the copy is known to have finished the wait is skipped.
+static void order_after_copy(fi_dag* g, hipStream_t s) {
+  if (!g->copy_done || !g->copy_pending.load(std::memory_order_acquire)) return;
+  if (hipEventQuery(g->copy_done) == hipSuccess) { g->copy_pending.store(false, std::memory_order_release); return; }
+  (void)hipGetLastError();   // hipErrorNotReady is not an error here
+  (void)hipStreamWaitEvent(s, g->copy_done, 0);
 }
 
 // ms: durations with every launch serialised on the caller's stream.  tl_begin / tl_end: the schedule as
@@ -992,6 +1016,7 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   const bool timeline = tl_begin && tl_end;
   if ((ms || timeline) && n_ms < (int32_t)nl) { set_error("timing arrays hold %d entries, schedule has %zu launches", n_ms, nl); return FI_EINVAL; }
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!g->capturing) order_after_copy(g, s);
   std::vector<hipEvent_t> ev;
   std::vector<size_t> ev_before(nl, 0);                        // timeline: index of the event that precedes launch i on its stream
   std::vector<size_t> last_on_lane((size_t)g->n_lanes, 0);
@@ -1074,6 +1099,7 @@ fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_o
   hipStream_t s = static_cast<hipStream_t>(stream);
   bool same = g->gexec && g->g_batch == batch && g->g_input == d_input;
   for (size_t m = 0; same && m < g->members.size(); ++m) same = g->g_outputs[m] == d_outputs[m];
+  order_after_copy(g, s);
   if (!same) {
     drop_graph(g);
     hipGraph_t graph = nullptr;
@@ -1081,7 +1107,9 @@ fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_o
       (void)hipGetLastError();
       return run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0);  // this stream cannot capture
     }
+    g->capturing = true;
     const fi_status rc = run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0);
+    g->capturing = false;
     const hipError_t e = hipStreamEndCapture(s, &graph);
     if (rc != FI_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
     if (e != hipSuccess || !graph) { set_error("hipStreamEndCapture: %s", hipGetErrorString(e)); return FI_EHIP; }
@@ -1148,16 +1176,17 @@ fi_status fi_swap_model(fi_dag* g, int32_t slot, const fi_model_spec* model, voi
   hipStream_t s = static_cast<hipStream_t>(stream);
   const Member& placed = t.members[(size_t)slot];
   const uint8_t* src = static_cast<const uint8_t*>(placed.spec.weights);
-  if (g->opts.load_mode == FI_LOAD_ONE_COPY) {
+  const bool one_copy = g->opts.load_mode == FI_LOAD_ONE_COPY && g->image;
+  if (one_copy) {
     // the pinned image stays the exact image of the arena; copies out of it must have finished
     if (g->copy_done) (void)hipEventSynchronize(g->copy_done);
-    if (t.arena_bytes > g->image_bytes) {
+    if (t.arena_bytes > g->image_capacity) {
       uint8_t* bigger = static_cast<uint8_t*>(pin_alloc(g->opts, (size_t)t.arena_bytes));
       if (!bigger) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)t.arena_bytes); return FI_ENOMEM_HOST; }
-      parallel_copy(bigger, g->image, g->image_bytes);
+      parallel_copy(bigger, g->image, std::min(g->image_bytes, g->image_capacity));   // same contents, more room: the DAG is unchanged
       pin_free(g->opts, g->image);
       g->image = bigger;
-      g->image_bytes = t.arena_bytes;
+      g->image_capacity = t.arena_bytes;
     }
     if (placed.spec.weights_packed) parallel_copy(g->image + placed.arena_off, src, placed.plan.packed_bytes);
     else pack_model(placed.spec, placed.plan, g->image + placed.arena_off);
@@ -1165,10 +1194,20 @@ fi_status fi_swap_model(fi_dag* g, int32_t slot, const fi_model_spec* model, voi
   }
   if (g->state == 1) {
     const hipError_t e = hipMemcpyAsync(g->dev + placed.arena_off, src, (size_t)placed.plan.packed_bytes, hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) { set_error("hipMemcpyAsync: %s", hipGetErrorString(e)); return FI_EHIP; }
-    if (g->copy_done) (void)hipEventRecord(g->copy_done, s);
+    if (e != hipSuccess) {
+      set_error("hipMemcpyAsync: %s", hipGetErrorString(e));
+      if (one_copy) {   // the DAG stays as it was, so its image must too: the outgoing member goes back where the newcomer was written
+        const Member& old = g->members[(size_t)slot];
+        if (old.spec.weights_packed) parallel_copy(g->image + old.arena_off, static_cast<const uint8_t*>(old.spec.weights), old.plan.packed_bytes);
+        else pack_model(old.spec, old.plan, g->image + old.arena_off);
+      }
+      return FI_EHIP;
+    }
+    if (g->copy_done) { (void)hipEventRecord(g->copy_done, s); g->copy_pending.store(true); }
+    else (void)hipStreamSynchronize(s);
     g->last_h2d_bytes = placed.plan.packed_bytes; g->last_h2d_copies = 1;
   }
+  if (one_copy) g->image_bytes = t.arena_bytes;   // what the next load copies
   drop_graph(g);
   g->members = std::move(t.members);
   g->nodes = std::move(t.nodes);

@@ -315,6 +315,11 @@ fi_status fi_server_swap(fi_server* s, int32_t slot, const fi_model_spec* model)
     // DAG, lanes included.
     s->swapping = true; s->swap_slot = slot;
     s->cv_done.wait(lk, [&] { return (s->queue[(size_t)slot].empty() && s->in_flight[(size_t)slot] == 0) || s->failed != FI_OK; });
+    if (s->failed != FI_OK) {   // a worker failed while the slot drained: nothing is swapped, the failure is what the caller gets
+      s->swapping = false; s->swap_slot = -1;
+      set_error("server failed: %s", s->failure.c_str());
+      return s->failed;
+    }
     s->regroup = true;
   }
   s->join_workers();

@@ -20,6 +20,66 @@ def rel_l2(a, ref):
     return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-30))
 
 
+# Element-wise bar beside the relative-L2 one (a single wrong element weighs ~1e-3 in the L2 norm of a large
+# tensor and would pass it).  Per output row (image): max |y - ref| <= c * 2^-8 * max |ref|.
+#  * bf16-stored members against the oracle's storage-rounding mode S, c = 4.  Two executors that round at the
+#    same places and differ only in summation order end 0.5-0.75 such units apart on the ResNets and 1.7 on
+#    VGG-16 (the oracle's own fp32- against fp64-accumulation builds in mode S, measured on the CPU before any
+#    GPU comparison); c = 4 leaves a factor of two above that and is 1.6 % of the row's largest value.
+#  * fp32-stored members and fp32 models against mode F, c = 1/4 (1e-3 of the row's largest value; their
+#    relative-L2 bar is 1e-4).
+ELEM_C_BF16 = 4.0
+ELEM_C_F32 = 0.25
+
+
+def elem_excess(y, ref, c):
+    """Largest per-row ratio of max |y - ref| to the bound c * 2^-8 * max |ref| (<= 1 passes)."""
+    y = np.asarray(y, dtype=np.float64).reshape(len(y), -1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(len(ref), -1)
+    lim = c * 2.0 ** -8 * np.maximum(np.abs(ref).max(axis=1), 1e-30)
+    return float((np.abs(y - ref).max(axis=1) / lim).max())
+
+
+def check_member(name, y, ref_f, ref_s, wide, tol=None, quiet=False):
+    """The parity bar of one member's output y [rows, values]: relative L2 against the fp32-activation oracle
+    (mode F; 1e-2 for bf16-stored activations, 1e-4 for fp32-stored), the element-wise bar above, top-1 judged
+    against the oracle with the member's storage rounding (ref_s; = ref_f for fp32-stored members)."""
+    tol = tol if tol is not None else (1e-4 if wide else 1e-2)
+    e = rel_l2(y, ref_f)
+    per_image = max(rel_l2(y[i], ref_f[i]) for i in range(len(y)))
+    ex = elem_excess(y, ref_f if wide else ref_s, ELEM_C_F32 if wide else ELEM_C_BF16)
+    ident, ties = check_top1(y, ref_s)
+    if not quiet:
+        print(f"  {name}: relL2 {e:.3e} (worst image {per_image:.3e}), element-wise {ex:.2f} of its bound, "
+              f"top-1 identical {ident}/{len(y)}, near ties {ties}")
+    assert np.isfinite(y).all()
+    assert e <= tol, f"{name}: rel L2 {e} > {tol}"
+    assert ex <= 1.0, f"{name}: an element is {ex:.2f}x its bound away from the oracle"
+    return e
+
+
+def check_against_oracle(name, model, blob, act, x_nchw, y, rows=None, tol=None, quiet=False):
+    """Runs the oracle for `model` on the rows `rows` of x_nchw (all by default), image by image on CORES threads,
+    in modes F and S, and holds y[rows] to the parity bar."""
+    rows = list(range(len(x_nchw))) if rows is None else list(rows)
+    wide = act == "f32" or model.dtype == "f32"
+    units = []
+    for r in rows:
+        units.append((model, blob, x_nchw[r:r + 1], False))
+        if not wide:
+            units.append((model, blob, x_nchw[r:r + 1], True))
+    res = oracle_units(units)
+    step = 1 if wide else 2
+    ref_f = np.concatenate([res[step * i] for i in range(len(rows))])
+    ref_s = ref_f if wide else np.concatenate([res[step * i + 1] for i in range(len(rows))])
+    L = model.layers[model.output]
+    if L.out_h * L.out_w > 1:   # the library's output rows are NHWC
+        b = len(rows)
+        ref_f = ref_f.reshape(b, L.cout, L.out_h, L.out_w).transpose(0, 2, 3, 1).reshape(b, -1)
+        ref_s = ref_s.reshape(b, L.cout, L.out_h, L.out_w).transpose(0, 2, 3, 1).reshape(b, -1)
+    return check_member(name, np.asarray(y)[rows], ref_f, ref_s, wide, tol, quiet)
+
+
 class GpuDag:
     """Builds one fused DAG from (model, blob[, act_dtype]) members and runs it."""
 

@@ -25,12 +25,7 @@ def _member(fam, seed, **kw):
 
 def _check_member(name, y, ref_f, ref_s, tol):
     from tests import harness
-    e = harness.rel_l2(y, ref_f)
-    per_image = max(harness.rel_l2(y[i], ref_f[i]) for i in range(len(y)))
-    ident, ties = harness.check_top1(y, ref_s)
-    print(f"  {name}: relL2 {e:.3e} (worst image {per_image:.3e}), top-1 identical {ident}/{len(y)}, near ties {ties}")
-    assert np.isfinite(y).all()
-    assert e <= tol, f"{name}: rel L2 {e} > {tol}"
+    harness.check_member(name, y, ref_f, ref_s, wide=tol < 1e-3, tol=tol)
 
 
 def test_config1_two_tiny_cnns_fp32():
@@ -97,9 +92,11 @@ def test_config3_heterogeneous_batch8():
         _check_member(f, ys[i], ref_f, ref_s, 1e-4 if f in WIDE else 1e-2)
 
 
-def test_config4_eight_resnet50_batch32_sampled():
-    """Full size on the GPU; the oracle checks 4 sampled images per member (every image row is
-    independent of the rest of the batch), a different sample for each member."""
+def test_config4_eight_resnet50_batch32_every_row():
+    """Full size on the GPU, in the launch configuration the benchmark times.  Every one of the 32 image rows of
+    every one of the 8 members is compared with the oracle, in its fp32-activation mode (relative L2) and in its
+    storage-rounding mode (element-wise bound, top-1): Section III-A, C1 holds for every image, the ragged last
+    tile of the last stage (image 31) included."""
     from tests import harness
     mem = [_member("resnet50", 1000 + i) for i in range(8)]
     x = gen.make_input(7, 32, 3, 224, 224, "normal", "bf16")
@@ -108,21 +105,16 @@ def test_config4_eight_resnet50_batch32_sampled():
         ys = g.run(x)
     finally:
         g.close()
-    units, picks = [], []
-    for i, (m, b, _) in enumerate(mem):
-        imgs = [(5 * i + 9 * j) % 32 for j in range(4)]
-        picks.append(imgs)
-        for img in imgs:
+    units = []
+    for (m, b, _) in mem:
+        for img in range(32):
             units.append((m, b, x[img:img + 1], False))
             units.append((m, b, x[img:img + 1], True))
     res = harness.oracle_units(units)
     for i in range(8):
-        ref_f = np.concatenate([res[(i * 4 + j) * 2] for j in range(4)])
-        ref_s = np.concatenate([res[(i * 4 + j) * 2 + 1] for j in range(4)])
-        _check_member(f"resnet50[{i}]", ys[i][picks[i]], ref_f, ref_s, 1e-2)
-        assert np.isfinite(ys[i]).all()
-    # every unsampled row is still covered by a property that holds at any size: members differ,
-    # and rows of one member differ from each other
+        ref_f = np.concatenate([res[(i * 32 + j) * 2] for j in range(32)])
+        ref_s = np.concatenate([res[(i * 32 + j) * 2 + 1] for j in range(32)])
+        _check_member(f"resnet50[{i}]", ys[i], ref_f, ref_s, 1e-2)
     assert not np.array_equal(ys[0], ys[1])
 
 
@@ -131,7 +123,8 @@ def test_full_size_family_batch32_sampled(fam):
     """Two identical-architecture members at the family's full image size and batch 32, the launch configuration the
     per-family benchmark times (64-column group-walking tiles for ResNeXt; dense blocks written in place with the
     affine stage applied by the 1x1 convolutions for DenseNet; Inception modules and fire modules written in place,
-    four-output pooling strips); the oracle checks two sampled images per member."""
+    four-output pooling strips); the oracle checks four images per member, the first and the last of the batch
+    among them (the last owns the ragged tail tile of every layer)."""
     from tests import harness
     mem = [_member(fam, 2000 + i) for i in range(2)]
     hw = mem[0][0].in_h
@@ -143,15 +136,15 @@ def test_full_size_family_batch32_sampled(fam):
         g.close()
     units, picks = [], []
     for i, (m, b, _) in enumerate(mem):
-        imgs = [(3 + 11 * i) % 32, (30 - 7 * i) % 32]
+        imgs = [0, (3 + 11 * i) % 32, (30 - 7 * i) % 32, 31]
         picks.append(imgs)
         for img in imgs:
             units.append((m, b, x[img:img + 1], False))
             units.append((m, b, x[img:img + 1], True))
     res = harness.oracle_units(units)
     for i in range(2):
-        ref_f = np.concatenate([res[(i * 2 + j) * 2] for j in range(2)])
-        ref_s = np.concatenate([res[(i * 2 + j) * 2 + 1] for j in range(2)])
+        ref_f = np.concatenate([res[(i * 4 + j) * 2] for j in range(4)])
+        ref_s = np.concatenate([res[(i * 4 + j) * 2 + 1] for j in range(4)])
         _check_member(f"{fam}[{i}]", ys[i][picks[i]], ref_f, ref_s, 1e-2)
         assert np.isfinite(ys[i]).all()
     assert not np.array_equal(ys[0], ys[1])
@@ -184,14 +177,16 @@ def test_further_table3_families_fused():
     for i, f in enumerate(fams):
         tol = 1e-2
         if f in WIDE_HERE:
-            # fp32-stored activations enter the matrix cores as two bf16 terms (16 mantissa bits), so against an fp32
-            # oracle the error is a fixed multiple (8-11x measured) of what a change of summation order alone does to
-            # this graph with these weights.  That conditioning is the distance between the oracle's own fp32 and fp64
-            # accumulation (MnasNet 8e-7, MobileNetV3-Large 9e-6): the 1e-4 bar is widened by four times that distance.
+            # fp32-stored activations enter the matrix cores as two bf16 terms, hi = bf16(x) and lo = bf16(x - hi): 16
+            # mantissa bits where bf16 storage keeps 8.  Per layer that is 2^-8 of the perturbation bf16 storage makes
+            # (pinned on the CPU in tests/test_oracle_pins.py), and both travel through the same graph, so the member
+            # ends 2^-8 x (distance between the oracle's storage-rounding and fp32 modes) from the fp32 oracle.  The bar
+            # is twice that (summation order adds its own share), and never below the 1e-4 of the fp32 path.
             import oracle
             m, b, _ = mem[i]
-            y64 = oracle.run_model(m, b, x, round_storage=False, f64=True)
-            tol = 1e-4 + 4.0 * harness.rel_l2(oracle.run_model(m, b, x, round_storage=False), y64)
+            d_sf = harness.rel_l2(oracle.run_model(m, b, x, round_storage=True), res[2 * i])
+            tol = max(1e-4, 2.0 * 2.0 ** -8 * d_sf)
+            print(f"  {f}: oracle modes S and F differ by {d_sf:.3e}: bar {tol:.3e}")
         _check_member(f, ys[i], res[2 * i], res[2 * i + 1], tol)
 
 
@@ -249,11 +244,11 @@ def test_efficientnet_v2_prefix():
     assert e <= 1e-4
 
 
-def test_config5_swap_churn_sampled():
+def test_config5_swap_churn_all_requests():
     """Pool of 16 packed models, seeded Poisson request stream; per request build, load, run, unload.
     By the fused == alone invariant a member's correct output depends only on (model, input batch), so
-    the oracle's logits are memoised per (model, batch, sampled image) and every request is checked by
-    lookup.  120 of the 1000 requests are replayed here (the benchmark replays all)."""
+    the oracle's logits are memoised per (model, batch) -- all 8 images, both oracle modes -- and every one of
+    the 1000 requests is replayed and every row of every member checked by lookup."""
     from tests import harness
     import paper_2410_21120_amd as fi
     import torch
@@ -270,8 +265,9 @@ def test_config5_swap_churn_sampled():
         fi.fi_model_pack(spec, packed.data_ptr(), n)
         pool.append((m, blob, act, packed))
     batches = [gen.make_input(7 + j, 8, 3, 224, 224, "normal", "bf16") for j in range(2)]
-    sample = [1, 6]
-    reqs = gen.request_stream(2024, 1000, 16, 4, 50.0, 2)[:120]
+    sample = list(range(8))
+    reqs = gen.request_stream(2024, 1000, 16, 4, 50.0, 2)
+    assert len(reqs) == 1000
     used = sorted({(mi, bi) for _, mm, bi in reqs for mi in mm})
     units = []
     for mi, bi in used:
@@ -309,10 +305,7 @@ def test_config5_swap_churn_sampled():
         for slot, mi in enumerate(members):
             ref_f, ref_s = memo[(mi, bi)]
             y = got[slot][sample]
-            e = harness.rel_l2(y, ref_f)
-            worst = max(worst, e)
-            assert e <= (1e-4 if pool[mi][2] == "f32" else 1e-2), (mi, bi, e)
-            harness.check_top1(y, ref_s)
-            assert np.isfinite(got[slot]).all()
+            wide = pool[mi][2] == "f32"
+            worst = max(worst, harness.check_member(f"model {mi} batch {bi}", y, ref_f, ref_s, wide, quiet=True))
     assert not alloc.live or all(not t.is_cuda for t in alloc.live.values())  # nothing left on the device
-    print(f"  120 requests replayed, worst member relL2 {worst:.3e}")
+    print(f"  {len(reqs)} requests replayed, worst member relL2 {worst:.3e}")

@@ -327,6 +327,11 @@ def test_per_member_batches(members):
                 y = o.cpu().numpy()
                 assert np.array_equal(y[:b], full[i][:b]), (batches, i)
                 assert np.all(y[b:] == -7.0), (batches, i)   # rows past the member's batch stay as they were
+                # unequal batches, every member on an input of its own: against the oracle (all but the MobileNetV2
+                # that stores bf16 activations, which no executor holds to the bar with these weights)
+                if b and batches[0] == 5 and not (mem[i][0].name.startswith("mobilenetv2") and mem[i][2] is None):
+                    from tests import harness
+                    harness.check_against_oracle(f"member {i} on {b} of its own images", mem[i][0], mem[i][1], mem[i][2], xs[i][:b], y[:b])
         with pytest.raises(fi.FiError) as e:
             dag.run_batches([t.data_ptr() for t in dev_in], [B + 1, 1, 1, 1, 1], [o.data_ptr() for o in outs], stream)
         assert e.value.status == fi.FI_EINVAL

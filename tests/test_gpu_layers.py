@@ -34,6 +34,10 @@ def _run_case(model, seed, batch, act_dtype=None, tol=None, bias_std=0.1):
     if not wide:
         ref_s = harness.oracle_nhwc(model, blob, x, True)
         assert harness.rel_l2(y, ref_s) <= 2e-3
+        ex = harness.elem_excess(y, ref_s, harness.ELEM_C_BF16)
+    else:
+        ex = harness.elem_excess(y, ref_f, harness.ELEM_C_F32)
+    assert ex <= 1.0, f"an element is {ex:.2f}x its bound away from the oracle"
     return e
 
 

@@ -42,8 +42,7 @@ def test_three_random_graphs_fused(seed):
         ref_s = harness.oracle_nhwc(m, blob, x, True)
         d_sf = harness.rel_l2(ref_s, ref_f)
         e_s = harness.rel_l2(y, ref_s)
-        flip = 2.0 ** -8 / np.sqrt(ref_f.size)   # one bf16 rounding that falls the other way weighs this much in a small output
-        assert e_s <= max(2e-3, d_sf) + flip + floor, f"member {i}: rel L2 vs storage-rounding oracle {e_s}, modes differ by {d_sf}"
+        assert e_s <= max(2e-3, 0.5 * d_sf) + floor, f"member {i}: rel L2 vs storage-rounding oracle {e_s}, modes differ by {d_sf}"
         if d_sf <= 0.5 * BF16_TOL:   # graphs on which bf16 storage itself stays inside the bar
             assert e_f <= BF16_TOL + floor, f"member {i}: rel L2 {e_f}"
 
@@ -169,8 +168,7 @@ def test_large_random_graphs_fused(seed):
         assert ys[i].shape == ref_f.shape and np.isfinite(ys[i]).all()
         floor = 1e-5 * np.sqrt(ref_f.size) / max(float(np.linalg.norm(ref_f)), 1e-30)
         d_sf = harness.rel_l2(ref_s, ref_f)
-        flip = 2.0 ** -8 / np.sqrt(ref_f.size)
-        assert harness.rel_l2(ys[i], ref_s) <= max(2e-3, d_sf) + flip + floor, (i, harness.rel_l2(ys[i], ref_s), d_sf)
+        assert harness.rel_l2(ys[i], ref_s) <= max(2e-3, 0.5 * d_sf) + floor, (i, harness.rel_l2(ys[i], ref_s), d_sf)
         if d_sf <= 0.5 * BF16_TOL:
             assert harness.rel_l2(ys[i], ref_f) <= BF16_TOL + floor
     ref_w = nhwc(refs[4])
@@ -216,5 +214,4 @@ def test_random_graphs_with_concatenating_blocks(seed):
         floor = 1e-5 * np.sqrt(ref_f.size) / scale
         d_sf = harness.rel_l2(ref_s, ref_f)
         e_s = harness.rel_l2(y, ref_s)
-        flip = 2.0 ** -8 / np.sqrt(ref_f.size)
-        assert e_s <= max(2e-3, d_sf) + flip + floor, f"member {i}: rel L2 vs storage-rounding oracle {e_s}, modes differ by {d_sf}"
+        assert e_s <= max(2e-3, 0.5 * d_sf) + floor, f"member {i}: rel L2 vs storage-rounding oracle {e_s}, modes differ by {d_sf}"

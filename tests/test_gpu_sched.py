@@ -61,6 +61,9 @@ def test_round_robin_outputs_equal_each_model_alone():
         assert overlap or st.peak_device_bytes <= largest_pair
         for i, o in enumerate(outs):
             assert np.array_equal(o.cpu().numpy(), alone[i]), f"model {i}, overlap={overlap}"
+        if overlap:   # what the scheduler left in every model's buffer, against the oracle run on that model alone
+            for i, (m, blob, act) in enumerate(members):
+                harness.check_against_oracle(f"{FAMS[i][0]}[{i}] after round robin", m, blob, act, x, outs[i].cpu().numpy())
     # one batch holding everything stays resident: a single load
     everything = fi.fi_footprint(specs, opts).device_bytes
     g1, n1 = fi.fi_partition(specs, opts, everything)

@@ -28,8 +28,8 @@ def _dag(max_batch, hw=64, fams=None):
         keep.append((k, blob))
         models.append(m)
     dag = fi.Dag(specs, max_batch, fi.TorchAllocators("cuda:0"), keepalive=keep, per_member_inputs=True)
-    dag.load(torch.cuda.current_stream().cuda_stream)
-    torch.cuda.synchronize()
+    dag.load(torch.cuda.current_stream().cuda_stream)   # no synchronisation: passes order themselves after the weight copy
+    dag.members_for_oracle = [(m, kb[1], act) for m, kb, (_, act) in zip(models, keep, fams)]
     return dag, models
 
 
@@ -73,6 +73,14 @@ def test_every_request_gets_its_member_alone_output(fams):
                 srv.wait(tickets[r])
             for r, (m, j) in enumerate(reqs):
                 assert np.array_equal(outs[r].cpu().numpy(), expect[(m, j)]), (r, m, j)
+            # the first served request of every member, against the oracle run on that member and image alone
+            from tests import harness
+            for m in range(n):
+                r = next(r for r, (mm, _) in enumerate(reqs) if mm == m)
+                j = reqs[r][1]
+                model, blob, act = dag.members_for_oracle[m]
+                harness.check_against_oracle(f"served request {r}: member {m}, image {j}", model, blob, act,
+                                             gen.make_input(500 + j, 1, 3, hw, hw, "normal", "bf16"), outs[r].cpu().numpy()[None])
             st = srv.stats()
             assert st.requests == 60 and 60 / (n * B) <= st.passes < 60, (st.requests, st.passes)
             assert st.max_images_per_pass <= n * B and st.mean_images_per_pass > 1.0

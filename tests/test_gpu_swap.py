@@ -147,3 +147,58 @@ def test_swap_that_does_not_fit_is_refused_and_the_dag_still_runs():
         assert np.array_equal(got[0], base[0]) and not np.array_equal(got[1], base[1])
     finally:
         g.close()
+
+
+def test_load_after_a_shrinking_swap_copies_the_new_arena_only():
+    """A swap that leaves the weight arena smaller than it was (the last-placed large member replaced by a small
+    one), on a BUILT handle and again on a LOADED one followed by unload: the next load copies exactly the new
+    plan's arena, never the larger image the handle once had, and gives the bits of a fresh build."""
+    import torch
+    import paper_2410_21120_amd as fi
+    from tests import harness
+    x = gen.make_input(7, 2, 3, HW, HW, "normal", "bf16")
+    big, small, small2 = _member("vgg16", 1001), _member("mobilenetv2", 5001, "f32"), _member("resnet18", 5002)
+    first = _member("resnet18", 1000)
+    fresh = _fresh([first, small], x)
+    fresh2 = _fresh([first, small2], x)
+
+    def spec_of(member):
+        m, blob, act = member
+        s, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes, act_dtype=act)
+        return s, (k, blob)
+    specs, keep = zip(*(spec_of(mb) for mb in (first, big)))
+    dag = fi.Dag(list(specs), 2, fi.TorchAllocators("cuda:0"), keepalive=list(keep))
+    stream = torch.cuda.current_stream().cuda_stream
+    xin = torch.from_numpy(gen.to_nhwc_storage(x, "bf16").view(np.int16)).cuda()
+
+    def run():
+        outs = [torch.full((2, 1000), float("nan"), dtype=torch.float32, device="cuda:0") for _ in range(2)]
+        dag.run(xin.data_ptr(), 2, [o.data_ptr() for o in outs], stream)
+        torch.cuda.synchronize()
+        return [o.cpu().numpy() for o in outs]
+    try:
+        before = dag.query().arena_bytes
+        s, k = spec_of(small)
+        dag.swap_model(1, s, stream, keepalive=k)          # BUILT: host work only
+        q = dag.query()
+        assert q.arena_bytes < before // 2                  # VGG-16's weights gave way to a small member's
+        dag.load(stream)
+        q = dag.query()
+        assert (q.last_h2d_copies, q.last_h2d_bytes) == (1, q.arena_bytes)
+        assert q.device_capacity >= q.last_h2d_bytes
+        assert all(np.array_equal(a, b) for a, b in zip(run(), fresh))
+        # the same on a LOADED handle: grow again, shrink, unload, load
+        s, k = spec_of(big)
+        dag.unload()
+        dag.swap_model(1, s, stream, keepalive=k)
+        dag.load(stream)
+        s, k = spec_of(small2)
+        dag.swap_model(1, s, stream, keepalive=k)
+        assert all(np.array_equal(a, b) for a, b in zip(run(), fresh2))
+        dag.unload()
+        dag.load(stream)
+        q = dag.query()
+        assert (q.last_h2d_copies, q.last_h2d_bytes) == (1, q.arena_bytes) and q.arena_bytes < before // 2
+        assert all(np.array_equal(a, b) for a, b in zip(run(), fresh2))
+    finally:
+        dag.destroy()

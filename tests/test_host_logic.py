@@ -335,6 +335,24 @@ def test_swap_model_replans_without_moving_the_other_members():
     assert d.query().arena_bytes >= spans[-1][1]
 
 
+def test_shrinking_swap_on_a_built_handle_shrinks_the_arena_the_next_load_copies():
+    """The last-placed large member gives way to a small one: the plan's weight arena (what a one-copy load
+    moves) shrinks to the members that are left, and the device footprint with it."""
+    d, _, _ = _build(["resnet18", "vgg16"], 2)
+    q0 = d.query()
+    m_new = zoo.FAMILIES["mobilenetv2"](hw=64)
+    blob = gen.make_blob(m_new, 79)
+    spec, keep = fi.make_spec(m_new, blob.ctypes.data, blob.nbytes)
+    d.swap_model(1, spec, keepalive=(keep, blob))
+    q1 = d.query()
+    spans = sorted((m.arena_off, m.arena_off + m.packed_bytes) for m in d.members())
+    assert q1.arena_bytes < q0.arena_bytes // 2
+    assert spans[-1][1] <= q1.arena_bytes < spans[-1][1] + 256
+    assert q1.device_bytes == q1.arena_bytes + q1.act_bytes + q1.workspace_bytes < q0.device_bytes
+    fresh, _, _ = _build(["resnet18", "mobilenetv2"], 2)
+    assert fresh.query().arena_bytes == q1.arena_bytes
+
+
 def test_swap_model_errors_leave_the_dag_unchanged():
     d, _, _ = _build(["resnet18", "resnet18"], 2)
     q0 = d.query()

@@ -376,3 +376,21 @@ def test_bf16_rounding_is_nearest_even():
     ref = torch.from_numpy(x).to(torch.bfloat16).float().numpy()  # library rounding
     assert np.array_equal(r, ref)
     assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
+
+
+def test_two_bf16_terms_carry_two_to_the_minus_eight_of_bf16_storage_error(rng):
+    """Tolerance derivation for members that keep fp32 activations: an fp32 value entering a bf16 product as
+    hi = bf16(x) plus lo = bf16(x - hi) is perturbed by at most 2^-8 of what rounding it to one bf16 value does,
+    element by element and therefore in every weighted sum (the oracle's own rounding routine, a plain matmul)."""
+    x = rng.standard_normal((64, 4096)).astype(np.float32) * np.exp(rng.standard_normal((64, 4096))).astype(np.float32)
+    w = oracle.round_bf16(rng.standard_normal((4096, 32)).astype(np.float32))
+    hi = oracle.round_bf16(x)
+    lo = oracle.round_bf16((x - hi).astype(np.float32))
+    one = np.abs(hi.astype(np.float64) - x)
+    two = np.abs(hi.astype(np.float64) + lo - x)
+    assert np.all(two <= 2.0 ** -8 * np.abs(x) * 2.0 ** -8 * 1.0000001)          # two terms: 2^-17 relative at worst ...
+    assert np.all(one <= 2.0 ** -8 * np.abs(x))                                  # ... one term: 2^-9 at worst
+    y = x.astype(np.float64) @ w
+    e_one = np.linalg.norm(hi.astype(np.float64) @ w - y)
+    e_two = np.linalg.norm((hi.astype(np.float64) + lo) @ w - y)
+    assert 0 < e_two <= 2.0 ** -8 * e_one
