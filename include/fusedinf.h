@@ -261,6 +261,19 @@ fi_status fi_load(fi_dag* dag, void* hip_stream);
  * node is a softmax.  1 <= batch <= max_batch.  Allocates nothing. */
 fi_status fi_run(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream);
 
+/* For callers that cannot allocate device memory or let the library do it (code being
+ * recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc): the
+ * pass of fi_run, same arguments and same output bits, with the split-K partial sums
+ * kept in a static device array of the library (FI_STATIC_SCRATCH_BYTES per GPU, held
+ * until the process ends) instead of the workspace region of the loaded allocation.
+ * Calls no hipMalloc / hipFree and no allocating library routine; always launches
+ * eagerly (use_graph is ignored).  FI_EBUDGET when fi_dag_info.workspace_bytes exceeds
+ * FI_STATIC_SCRATCH_BYTES (fi_run still serves such a DAG).  Every call on a GPU shares
+ * that GPU's array: two calls that overlap in time on one GPU, from whichever handle,
+ * stream or thread, race on it.  Nothing in the array needs clearing between calls. */
+#define FI_STATIC_SCRATCH_BYTES (32u << 20)
+fi_status fi_run_static(fi_dag* dag, const void* d_input, int32_t batch, void* const* d_outputs, void* hip_stream);
+
 /* Algorithm 1 gives every member model m its own input x^m: the same pass with
  * d_inputs a HOST array of n_models DEVICE pointers, member m reading
  * d_inputs[m] ([batch, in_h, in_w, in_c] NHWC in the weight dtype, read-only; all

@@ -100,7 +100,7 @@ class fi_launch_info(C.Structure):
 
 LIB_PATH = _build.OUT
 EXPORTS = ["fi_model_packed_size", "fi_model_pack", "fi_build_dag", "fi_footprint", "fi_partition", "fi_round_robin", "fi_query", "fi_node", "fi_launch", "fi_member", "fi_load",
-           "fi_run", "fi_run_inputs", "fi_run_batches", "fi_run_lane", "fi_profile", "fi_timeline", "fi_swap_model", "fi_server_start", "fi_server_submit", "fi_server_wait", "fi_server_query", "fi_server_swap", "fi_server_stop",
+           "fi_run", "fi_run_static", "fi_run_inputs", "fi_run_batches", "fi_run_lane", "fi_profile", "fi_timeline", "fi_swap_model", "fi_server_start", "fi_server_submit", "fi_server_wait", "fi_server_query", "fi_server_swap", "fi_server_stop",
            "fi_unload", "fi_destroy", "fi_last_error", "fi_version"]
 _lib = None
 
@@ -125,6 +125,7 @@ def lib():
         L.fi_launch.argtypes = [vp, i32, C.POINTER(fi_launch_info)]
         L.fi_load.argtypes = [vp, vp]
         L.fi_run.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
+        L.fi_run_static.argtypes = [vp, vp, i32, C.POINTER(vp), vp]
         L.fi_run_inputs.argtypes = [vp, C.POINTER(vp), i32, C.POINTER(vp), vp]
         L.fi_run_batches.argtypes = [vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), vp]
         L.fi_run_lane.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), vp]
@@ -259,6 +260,11 @@ def fi_load(h, stream_ptr=0) -> None:
 def fi_run(h, d_input_ptr, batch, d_output_ptrs, stream_ptr=0) -> None:
     outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
     _check(lib().fi_run(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr)), "fi_run")
+
+
+def fi_run_static(h, d_input_ptr, batch, d_output_ptrs, stream_ptr=0) -> None:
+    outs = (C.c_void_p * len(d_output_ptrs))(*d_output_ptrs)
+    _check(lib().fi_run_static(h, C.c_void_p(d_input_ptr), batch, outs, C.c_void_p(stream_ptr)), "fi_run_static")
 
 
 def fi_run_inputs(h, d_input_ptrs, batch, d_output_ptrs, stream_ptr=0) -> None:
@@ -481,6 +487,9 @@ class Dag:
 
     def run(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
         fi_run(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr)
+
+    def run_static(self, d_input_ptr, batch, d_output_ptrs, stream_ptr=0):
+        fi_run_static(self.h, d_input_ptr, batch, d_output_ptrs, stream_ptr)
 
     def run_inputs(self, d_input_ptrs, batch, d_output_ptrs, stream_ptr=0):
         fi_run_inputs(self.h, d_input_ptrs, batch, d_output_ptrs, stream_ptr)

@@ -816,7 +816,7 @@ static fi_status plan_dag(fi_dag* g) {
         d.xs = (in && in->root >= 0) ? g->nodes[(size_t)in->root].Cop : d.Cp;
         d.ys = nd.root >= 0 ? g->nodes[(size_t)nd.root].Cop : d.Cop;
       }
-      d.ws_off = g->act_bytes + nd.ws_off;  // the workspace follows the activation arena
+      d.ws_off = nd.ws_off;  // relative to the workspace (which follows the activation arena in a loaded handle)
       if (L.kind == K_FC) d.tiles_n = (nd.Co + 31) / 32;
       if (L.kind == K_CONCAT) {
         const Node& second = g->nodes[(size_t)nd.residual];
@@ -988,6 +988,9 @@ fi_status fi_load(fi_dag* g, void* stream) {
 // that copy; once the copy is known to have finished the wait is skipped.
 static void order_after_copy(fi_dag* g, hipStream_t s) {
   if (!g->copy_done || !g->copy_pending.load(std::memory_order_acquire)) return;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &cs) != hipSuccess) (void)hipGetLastError();
+  if (cs != hipStreamCaptureStatusNone) return;   // a caller recording this stream has ordered it after the load itself
   if (hipEventQuery(g->copy_done) == hipSuccess) { g->copy_pending.store(false, std::memory_order_release); return; }
   (void)hipGetLastError();   // hipErrorNotReady is not an error here
   (void)hipStreamWaitEvent(s, g->copy_done, 0);
@@ -998,7 +1001,8 @@ static void order_after_copy(fi_dag* g, hipStream_t s) {
 // in milliseconds since the pass began.
 static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream,
                           float* ms, int32_t n_ms, float* tl_begin = nullptr, float* tl_end = nullptr,
-                          const void* const* d_inputs = nullptr, const int32_t* batches = nullptr, int32_t only_lane = -1) {
+                          const void* const* d_inputs = nullptr, const int32_t* batches = nullptr, int32_t only_lane = -1,
+                          uint8_t* workspace = nullptr) {
   if (!g || (!d_input && !d_inputs) || !d_outputs) { set_error("null argument"); return FI_EINVAL; }
   if (d_inputs && !g->opts.per_member_inputs) { set_error("per-member inputs need a DAG built with per_member_inputs"); return FI_ESTATE; }
   if (g->state != 1) { set_error("fi_run: handle is not loaded"); return FI_ESTATE; }
@@ -1018,9 +1022,11 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!g->capturing) order_after_copy(g, s);
   std::vector<hipEvent_t> ev;
-  std::vector<size_t> ev_before(nl, 0);                        // timeline: index of the event that precedes launch i on its stream
-  std::vector<size_t> last_on_lane((size_t)g->n_lanes, 0);
+  std::vector<size_t> ev_before;                               // timeline: index of the event that precedes launch i on its stream
+  std::vector<size_t> last_on_lane;
   if (ms || timeline) {
+    ev_before.assign(nl, 0);
+    last_on_lane.assign((size_t)g->n_lanes, 0);
     ev.resize(nl + 1);
     for (auto& e : ev) if (hipEventCreate(&e) != hipSuccess) { set_error("hipEventCreate failed"); return FI_EHIP; }
     (void)hipEventRecord(ev[0], s);
@@ -1028,6 +1034,7 @@ static fi_status run_impl(fi_dag* g, const void* d_input, int32_t batch, void* c
   KArgs a{};
   a.wbase = g->dev;
   a.abase = g->dev + g->arena_bytes;
+  a.wsbase = workspace ? workspace : a.abase + g->act_bytes;   // the workspace follows the activation arena
   fi_status rc = FI_OK;
   // Lanes: after the shared input is staged on the caller's stream the internal streams fork from
   // it, every launch goes to its lane's stream, and the caller's stream joins them at the end.
@@ -1123,6 +1130,25 @@ fi_status fi_run(fi_dag* g, const void* d_input, int32_t batch, void* const* d_o
   const hipError_t e = hipGraphLaunch(g->gexec, s);
   if (e != hipSuccess) { set_error("hipGraphLaunch: %s", hipGetErrorString(e)); return FI_EHIP; }
   return FI_OK;
+}
+
+fi_status fi_run_static(fi_dag* g, const void* d_input, int32_t batch, void* const* d_outputs, void* stream) {
+  if (!g) { set_error("null handle"); return FI_EINVAL; }
+  if (g->workspace_bytes > FI_STATIC_SCRATCH_BYTES) {
+    set_error("fi_run_static: the DAG's split-K workspace is %llu bytes, the static array holds %llu (use fi_run)",
+              (unsigned long long)g->workspace_bytes, (unsigned long long)FI_STATIC_SCRATCH_BYTES);
+    return FI_EBUDGET;
+  }
+  void* ws = nullptr;
+  uint64_t ws_bytes = 0;
+  const int e = static_scratch(&ws, &ws_bytes);
+  if (e != (int)hipSuccess || !ws || ws_bytes < g->workspace_bytes) {
+    set_error("fi_run_static: no static workspace on this device: %s", hipGetErrorString((hipError_t)e));
+    return FI_EHIP;
+  }
+  // Partial sums are written in full by the split launch before the reduce launch reads them: nothing in the array
+  // has to start at zero, whatever an earlier call left there.
+  return run_impl(g, d_input, batch, d_outputs, stream, nullptr, 0, nullptr, nullptr, nullptr, nullptr, -1, static_cast<uint8_t*>(ws));
 }
 
 fi_status fi_run_inputs(fi_dag* g, const void* const* d_inputs, int32_t batch, void* const* d_outputs, void* stream) {

@@ -66,7 +66,7 @@ struct Desc {
                                  // thread along a row; concatenation / interleaving shuffle: pixel stride of the second source
   int32_t vec;                   // 1: bf16 tensors with Cp % 8 == 0, kernels work on 8-channel vectors
   int32_t splits;                // reduction splits (>1: fp32 partials [splits][rows][Cop] at ws_off)
-  uint64_t ws_off;               // split-K partials, relative to the activation base
+  uint64_t ws_off;               // split-K partials, relative to the workspace base (KArgs::wsbase)
   int32_t kw, pad_w;             // dense conv: kernel width and horizontal padding (k, pad are the vertical ones)
   int32_t gin, gout;             // MFMA conv of a grouped convolution: input / output channels per group (0 = dense walk over all channels)
   int32_t xs, ys;                // elements between neighbouring pixels of the input / output: Cp / Cop, or the channel stride of the
@@ -132,6 +132,7 @@ struct ModelPlan {
 struct KArgs {
   const uint8_t* wbase;          // weight arena (device)
   uint8_t* abase;                // activation region (device)
+  uint8_t* wsbase;               // split-K workspace (device): the tail of the loaded allocation, or the library's static array
   int32_t n, reserved;
   int32_t batch[FI_MAX_GROUP];   // images per problem slot in this pass (members may bring batches of their own)
   int32_t first_block[FI_MAX_GROUP + 1];  // workgroup index where each problem starts (filled per launch)
@@ -160,6 +161,10 @@ int launch_copy_rows(const void* const* src, void* const* dst, int32_t n, uint64
 void set_error(const char* fmt, ...);
 fi_status analyze_model(const fi_model_spec& m, ModelPlan& out);
 void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst);
+
+// The library's static split-K workspace on the current device (fi_run_static): its device address and size.
+// Implemented in fi_kernels.hip; returns a hipError_t as int.  Allocates nothing.
+int static_scratch(void** ptr, uint64_t* bytes);
 
 // Implemented in fi_kernels.hip.  Returns a hipError_t as int; `stream` is a hipStream_t.
 int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);

@@ -13,6 +13,7 @@
 // affine, a squeeze-excite scaling, a concatenation that a shuffle interleaves) has no launch.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "fi_internal.h"
@@ -593,7 +594,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
         const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
         if (m >= M || !col_ok) continue;
         if (d.splits > 1) {  // raw partial sums; the reduce launch finishes the node
-          float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
+          float* ws = reinterpret_cast<float*>(a.wsbase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
           *reinterpret_cast<float4*>(ws) = v0;
           *reinterpret_cast<float4*>(ws + 4) = v1;
           continue;
@@ -693,7 +694,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
         const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
         const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
         if (d.splits > 1) {  // raw partial sums; the reduce launch finishes the node
-          float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
+          float* ws = reinterpret_cast<float*>(a.wsbase + d.ws_off) + ((int64_t)split * M + m) * d.Cop + o;
           *reinterpret_cast<float4*>(ws) = v0;
           *reinterpret_cast<float4*>(ws + 4) = v1;
           continue;
@@ -1441,7 +1442,7 @@ __global__ void __launch_bounds__(256) fc_kernel(KArgs a) {
     return;
   }
   if (nok) {
-    float* ws = reinterpret_cast<float*>(a.abase + d.ws_off) + ((int64_t)split * batch + n) * d.Cop + tile * 32;
+    float* ws = reinterpret_cast<float*>(a.wsbase + d.ws_off) + ((int64_t)split * batch + n) * d.Cop + tile * 32;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int fo = 8 * g + 4 * (lane >> 5);
@@ -1496,7 +1497,7 @@ __global__ void __launch_bounds__(256) reduce_kernel(KArgs a) {
   const int idx = bid * 256 + threadIdx.x;
   if (idx >= rows * q4) return;
   const int o = (idx % q4) * 4, n = idx / q4;
-  const float* ws = reinterpret_cast<const float*>(a.abase + d.ws_off) + (int64_t)n * d.Cop + o;
+  const float* ws = reinterpret_cast<const float*>(a.wsbase + d.ws_off) + (int64_t)n * d.Cop + o;
   float4 sum = make_float4(0, 0, 0, 0);
   const int64_t stride = (int64_t)rows * d.Cop;
   int s = 0;
@@ -1562,6 +1563,35 @@ static int go(F kernel, int blocks, int threads, const KArgs& a, hipStream_t s) 
   if (blocks <= 0) return (int)hipSuccess;
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3((unsigned)threads), 0, s, a);
   return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Split-K workspace of the entry point that allocates nothing (fi_run_static): one array per GPU, held from the
+// moment the library's code object is loaded on that GPU until the process ends.  In host code the array's name
+// is only a stand-in: its device address comes from hipGetSymbolAddress, once per device, and that address is
+// what the kernels receive as KArgs::wsbase (exactly as they receive the workspace of a loaded handle).
+// ---------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[FI_STATIC_SCRATCH_BYTES];
+
+int static_scratch(void** ptr, uint64_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* per_device[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!per_device[dev]) {   // every GPU holds its own copy of the array at its own address
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    per_device[dev] = p;
+  }
+  *ptr = per_device[dev];
+  *bytes = FI_STATIC_SCRATCH_BYTES;
+  return (int)hipSuccess;
 }
 
 int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::vector<Desc>& hd) {

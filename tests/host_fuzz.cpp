@@ -17,6 +17,7 @@
 
 namespace fi {
 int launch_kernel(const Launch&, const KArgs&, void*, const std::vector<Desc>&) { return 0; }  // never reached
+int static_scratch(void**, uint64_t*) { return 1; }                                                // never reached
 }  // namespace fi
 
 namespace {
