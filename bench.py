@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--swap-requests", type=int, default=1000, help="requests of the swap-churn stream that are replayed (the stream has 1000)")
     ap.add_argument("--launch-table", default=None, metavar="FILE",
                     help="also write the per-launch roofline table (every launch beside its own roofline ceiling) as markdown")
+    ap.add_argument("--member-chunks", type=int, default=0,
+                    help="fi_build_opts.member_chunks of the timed DAG: the early, activation-heavy levels run for one chunk of a lane's "
+                         "members after the other (smaller activation arena, more launches); 0 = every level for all members together")
     ap.add_argument("--no-extras", action="store_true", help="skip separate-DAG, swap and CPU legs")
     ap.add_argument("--serial-lanes", action="store_true",
                     help="issue every launch on the caller's stream (no concurrent lanes): the condition the per-kernel "
@@ -118,7 +121,7 @@ def main():
 
     # ---- fused DAG: timed region ------------------------------------------------------------
     t0 = time.perf_counter()
-    dag = make_dag(members, serial_lanes=a.serial_lanes)
+    dag = make_dag(members, serial_lanes=a.serial_lanes, member_chunks=a.member_chunks)
     t_build = time.perf_counter() - t0
     torch.cuda.empty_cache()
     free0 = torch.cuda.mem_get_info()[0]

@@ -160,6 +160,15 @@ typedef struct {
                               * squeeze-excite scaling (FI_MUL) read only by a 1x1 convolution is applied by that convolution
                               * while it loads its input and needs no launch; 1: it runs as a launch of its own.  The outputs
                               * are the same bits either way. */
+  int32_t separate_chains;   /* 0: a dense convolution whose only reader is a 1x1 convolution (and that one's 1x1 reader, if it has
+                              * one) runs with it in ONE launch per 128-pixel tile: the first output stays in registers, the second
+                              * is written once and not read back (a ResNet bottleneck: 3x3 -> 1x1 expand -> the next block's 1x1
+                              * reduce); 1: every convolution is a launch of its own.  The outputs are the same bits either way. */
+  int32_t member_chunks;     /* 0 / 1: every level runs all members of a lane together.  c >= 2: the early, activation-heavy levels
+                              * of a lane's members (up to the depth after which a member's live activations stay below two thirds
+                              * of their peak) run for one chunk of ceil(members / c) members after the other, the deeper levels for
+                              * all members together as ever: the chunks' early tensors share memory, so the activation arena shrinks,
+                              * at the price of more, smaller launches.  The outputs are the same bits either way. */
 } fi_build_opts;
 
 typedef struct {

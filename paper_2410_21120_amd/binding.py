@@ -47,7 +47,8 @@ class fi_build_opts(C.Structure):
                 ("use_graph", C.c_int32), ("serial_lanes", C.c_int32), ("per_member_inputs", C.c_int32),
                 ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
                 ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p),
-                ("swap_headroom_bytes", C.c_uint64), ("copy_concats", C.c_int32), ("separate_affine", C.c_int32)]
+                ("swap_headroom_bytes", C.c_uint64), ("copy_concats", C.c_int32), ("separate_affine", C.c_int32),
+                ("separate_chains", C.c_int32), ("member_chunks", C.c_int32)]
 
 
 class fi_dag_info(C.Structure):
@@ -221,7 +222,7 @@ def fi_round_robin(specs, opts: fi_build_opts, group_of, n_groups, iterations, r
 
 def make_opts(max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY, max_device_bytes=0,
               use_graph=False, serial_lanes=False, swap_headroom_bytes=0, per_member_inputs=False,
-              copy_concats=False, separate_affine=False) -> fi_build_opts:
+              copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0) -> fi_build_opts:
     opts = fi_build_opts()
     opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
     opts.use_graph = int(use_graph)
@@ -230,6 +231,8 @@ def make_opts(max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_O
     opts.per_member_inputs = int(per_member_inputs)
     opts.copy_concats = int(copy_concats)
     opts.separate_affine = int(separate_affine)
+    opts.separate_chains = int(separate_chains)
+    opts.member_chunks = int(member_chunks)
     if allocators is not None:
         allocators.apply(opts)
     return opts
@@ -457,10 +460,10 @@ class Dag:
 
     def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
                  max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False, swap_headroom_bytes=0,
-                 per_member_inputs=False, copy_concats=False, separate_affine=False):
+                 per_member_inputs=False, copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0):
         self.keepalive = [specs, keepalive, allocators]
         opts = make_opts(max_batch, allocators, group_levels, load_mode, max_device_bytes, use_graph, serial_lanes,
-                         swap_headroom_bytes, per_member_inputs, copy_concats, separate_affine)
+                         swap_headroom_bytes, per_member_inputs, copy_concats, separate_affine, separate_chains, member_chunks)
         self.opts = opts
         self.h = fi_build_dag(specs, opts)
         self.n_models = len(specs)

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfusedinf.so")
-SOURCES = ["fi_plan.cpp", "fi_api.cpp", "fi_sched.cpp", "fi_server.cpp", "fi_kernels.hip"]
+SOURCES = ["fi_plan.cpp", "fi_api.cpp", "fi_sched.cpp", "fi_server.cpp", "fi_kernels.hip", "fi_chain.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -19,7 +19,7 @@ def stale() -> bool:
     if not os.path.exists(OUT):
         return True
     t = os.path.getmtime(OUT)
-    deps = sources() + [os.path.join(CSRC, "fi_internal.h"), os.path.join(HERE, "..", "include", "fusedinf.h")]
+    deps = sources() + [os.path.join(CSRC, "fi_internal.h"), os.path.join(CSRC, "fi_device.h"), os.path.join(HERE, "..", "include", "fusedinf.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

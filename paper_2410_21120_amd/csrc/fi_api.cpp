@@ -52,6 +52,7 @@ struct fi_dag {
   std::vector<fi::Launch> launches;
   std::vector<fi::Desc> descs;
   int32_t n_levels = 0;
+  int32_t n_runs = 0;                 // positions in the launch order (= n_levels unless early levels run in member chunks)
   int32_t wdtype = FI_BF16;
   uint64_t desc_bytes = 0, arena_bytes = 0, act_bytes = 0, workspace_bytes = 0, device_bytes = 0;
   uint64_t image_bytes = 0;           // bytes of the pinned image that a load copies (whole arena, or header only)
@@ -163,6 +164,7 @@ const char* kind_name(int kind, int tile) {
     case K_AVGPOOL: return "avgpool";
     case K_MUL: return "channel_scale";
     case K_GATHER: return "channel_gather";
+    case K_CHAIN: return tile ? "conv_chain3" : "conv_chain2";
   }
   return "?";
 }
@@ -406,6 +408,59 @@ static void fold_nodes_into_readers(fi_dag* g) {
   }
 }
 
+// Planner pass, after fold_nodes_into_readers: chains of convolutions that one launch carries through.
+// A dense convolution A (bf16 in and out, 64 or 128 output channels, whole 64-element reduction tiles per filter tap)
+// whose ONLY reader is a pointwise convolution B (any multiple of 128 output channels, optional residual), and
+// optionally a pointwise convolution C that reads B (64 or 128 output channels, no residual): a workgroup that owns
+// 128 output pixels of A finishes the same pixels of B and C.  A's output is stored nowhere, B's and C's are written
+// as ever.  In a ResNet bottleneck stage: A = a block's 3x3, B = its 1x1 expansion with the shortcut added,
+// C = the next block's 1x1 reduction (or the next stage's first one).
+static void form_chains(fi_dag* g) {
+  const int32_t total = (int32_t)g->nodes.size();
+  for (Node& nd : g->nodes) { nd.chain = -1; nd.chain_pos = 0; }
+  if (g->opts.separate_chains || g->wdtype != FI_BF16) return;
+  std::vector<std::vector<int32_t>> readers((size_t)total);   // nodes reading a tensor as their first input
+  std::vector<int32_t> other_uses((size_t)total, 0);          // uses as a second operand, or by a node fused into its reader
+  for (int32_t i = 0; i < total; ++i) {
+    const Node& nd = g->nodes[(size_t)i];
+    if (nd.input >= 0) readers[(size_t)nd.input].push_back(i);
+    if (nd.residual >= 0) other_uses[(size_t)nd.residual]++;
+  }
+  auto plain_conv = [&](const Node& n) {   // a dense bf16 MFMA convolution with nothing folded into or around it
+    const int adt = g->members[(size_t)n.model].spec.act_dtype;
+    return n.kind == K_CONV_MFMA && n.op == FI_CONV2D && adt == FI_BF16 && n.out_dtype == FI_BF16 && n.groups == 1 && n.pre < 0 && n.root < 0 &&
+           !n.elided && !n.is_output && n.splits == 1 && n.Cp != 4 && n.chain < 0;
+  };
+  auto pointwise = [](const Node& n) { return n.k == 1 && n.kw == 1 && n.stride == 1 && n.pad == 0 && n.pad_w == 0; };
+  for (int32_t i = 0; i < total; ++i) {
+    Node& A = g->nodes[(size_t)i];
+    if (!plain_conv(A) || A.residual >= 0 || A.Cp % 64 || A.C != A.Cp || (A.Co != 64 && A.Co != 128) || A.Co != A.Cop) continue;
+    if (A.Kp != A.k * A.kw * A.Cp || A.input < 0) continue;
+    if (A.input >= 0 && g->nodes[(size_t)A.input].root >= 0) continue;   // an input inside a concatenation has a pixel stride of its own
+    if (readers[(size_t)i].size() != 1 || other_uses[(size_t)i] != 0) continue;
+    const int32_t bi = readers[(size_t)i][0];
+    Node& Bn = g->nodes[(size_t)bi];
+    if (!plain_conv(Bn) || !pointwise(Bn) || Bn.level != A.level + 1 || Bn.run != A.run + 1 || Bn.C != A.Co || Bn.Cp != A.Cop || Bn.Co % 128 || Bn.Co != Bn.Cop || Bn.Kp != Bn.Cp) continue;
+    if (Bn.residual >= 0) {
+      const Node& R = g->nodes[(size_t)Bn.residual];
+      if (R.root >= 0 || R.out_dtype != FI_BF16 || R.Cop != Bn.Cop || Bn.residual == i) continue;
+      if (R.run >= A.run) continue;   // the chain runs in A's place: everything it reads is complete by then
+    }
+    int32_t ci = -1;
+    for (int32_t r : readers[(size_t)bi]) {
+      const Node& Cn = g->nodes[(size_t)r];
+      if (!plain_conv(Cn) || !pointwise(Cn) || Cn.residual >= 0 || Cn.level != Bn.level + 1 || Cn.run != Bn.run + 1) continue;
+      if (Cn.C != Bn.Co || Cn.Cp != Bn.Cop || Cn.Kp != Cn.Cp || (Cn.Co != 64 && Cn.Co != 128) || Cn.Co != Cn.Cop) continue;
+      ci = r;
+      break;
+    }
+    A.chain = i; A.chain_pos = 0;
+    Bn.chain = i; Bn.chain_pos = 1; Bn.run = A.run;
+    if (ci >= 0) { g->nodes[(size_t)ci].chain = i; g->nodes[(size_t)ci].chain_pos = 2; g->nodes[(size_t)ci].run = A.run; }
+    A.tile = ci >= 0 ? 1 : 0;   // (the chained launch has no tile choice: the field tells chains of three from chains of two)
+  }
+}
+
 // Everything derived from the member list: union graph, levels, lanes, kernels and tiles, launch
 // schedule, activation plan, weight arena placement, workspace, descriptors.  Members whose
 // arena_off is already set keep their place in the weight arena (their bytes may be resident);
@@ -482,11 +537,59 @@ static fi_status plan_dag(fi_dag* g) {
     for (Node& nd : g->nodes) nd.lane = g->members[(size_t)nd.model].lane;
   }
 
-  // ---- kernel family per node ---------------------------------------------------------
+  // ---- launch order: by depth, except that the early levels of a lane may run in member chunks --------
   const int B = opts->max_batch;
+  for (Node& nd : g->nodes) nd.run = nd.level;
+  g->n_runs = g->n_levels;
+  if (opts->member_chunks >= 2) {
+    // Per lane (its members have one architecture): the depth S after which a member's live activations stay below
+    // two thirds of their peak.  Levels 1..S run chunk by chunk (chunk k shifted by k S), everything deeper after
+    // the last chunk.  A shift common to a whole lane changes nothing between lanes: they are not level-synchronous.
+    int32_t longest = g->n_levels;
+    for (int32_t lane = 0; lane < g->n_lanes; ++lane) {
+      std::vector<int32_t> mem;
+      for (int32_t m = 0; m < n; ++m) if (g->members[(size_t)m].lane == lane) mem.push_back(m);
+      const int32_t chunks = std::min<int32_t>(opts->member_chunks, (int32_t)mem.size());
+      if (chunks < 2) continue;
+      const Member& first = g->members[(size_t)mem[0]];
+      const int32_t nn = (int32_t)first.plan.nodes.size();
+      std::vector<int32_t> last((size_t)nn);
+      std::vector<uint64_t> live((size_t)g->n_levels + 2, 0);
+      for (int32_t i = 0; i < nn; ++i) last[(size_t)i] = g->nodes[(size_t)(first.node0 + i)].level;
+      for (int32_t i = 0; i < nn; ++i) {
+        const Node& nd = g->nodes[(size_t)(first.node0 + i)];
+        if (nd.input >= 0) last[(size_t)(nd.input - first.node0)] = std::max(last[(size_t)(nd.input - first.node0)], nd.level);
+        if (nd.residual >= 0) last[(size_t)(nd.residual - first.node0)] = std::max(last[(size_t)(nd.residual - first.node0)], nd.level);
+      }
+      for (int32_t i = 0; i < nn; ++i) {
+        const Node& nd = g->nodes[(size_t)(first.node0 + i)];
+        const uint64_t bytes = nd.is_output ? 0 : (uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype);
+        for (int32_t lv = nd.level; lv <= last[(size_t)i]; ++lv) live[(size_t)lv] += bytes;
+      }
+      uint64_t peak = 0;
+      for (uint64_t v : live) peak = std::max(peak, v);
+      int32_t S = 0;
+      for (int32_t lv = g->n_levels; lv >= 1; --lv)
+        if (live[(size_t)lv] * 3 > peak * 2) { S = lv; break; }
+      if (S <= 0 || S >= g->n_levels) continue;
+      const int32_t per = ((int32_t)mem.size() + chunks - 1) / chunks;
+      for (size_t j = 0; j < mem.size(); ++j) {
+        const Member& mb = g->members[(size_t)mem[j]];
+        const int32_t k = (int32_t)j / per;
+        for (size_t t = 0; t < mb.plan.nodes.size(); ++t) {
+          Node& nd = g->nodes[(size_t)mb.node0 + t];
+          nd.run = nd.level <= S ? nd.level + k * S : nd.level + (chunks - 1) * S;
+        }
+      }
+      longest = std::max(longest, g->n_levels + (chunks - 1) * S);
+    }
+    g->n_runs = longest;
+  }
+
+  // ---- kernel family per node ---------------------------------------------------------
   std::map<std::tuple<int, int, int, int, int, int>, int> same_shape;  // problems of one shape per level
   for (const Node& nd : g->nodes)
-    if (nd.op == FI_CONV2D || nd.op == FI_FC) same_shape[std::make_tuple(nd.level + 1000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)]++;
+    if (nd.op == FI_CONV2D || nd.op == FI_FC) same_shape[std::make_tuple(nd.run + 10000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)]++;
   for (Node& nd : g->nodes) {
     const int adt = g->members[(size_t)nd.model].spec.act_dtype;
     nd.tile = 0;
@@ -524,7 +627,7 @@ static fi_status plan_dag(fi_dag* g) {
                       nd.model, nd.index, (unsigned long long)((uint64_t)B * nd.H * nd.W * nd.Cp * esize(adt)));
             return FI_EUNSUPPORTED;
           }
-          const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.level + 1000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
+          const int grp = opts->group_levels ? same_shape[std::make_tuple(nd.run + 10000 * nd.lane, nd.Ho * nd.Wo, nd.Co, nd.Kp, nd.k, nd.stride)] : 1;
           // sibling lanes run the same level at about the same time: the chip is shared by all of them
           nd.tile = pick_tile(nd, B, std::min(grp * g->members[(size_t)nd.model].sibling_lanes, (int)FI_MAX_GROUP), adt == FI_F32);
           if (walks_groups(nd, adt)) {   // the reduction shrinks to the tile's own groups: short, never split
@@ -548,6 +651,7 @@ static fi_status plan_dag(fi_dag* g) {
   // ---- nodes that need no launch: concatenations written in place, nodes applied by their reader ----
   store_concat_sources_in_place(g);
   fold_nodes_into_readers(g);
+  form_chains(g);
 
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
   //      share a launch, FI_MAX_GROUP problems at most --------------------------------------
@@ -589,14 +693,41 @@ static fi_status plan_dag(fi_dag* g) {
       ++L.n;
     }
   }
-  for (int32_t lv = 1; lv <= g->n_levels; ++lv) {
+  for (int32_t lv = 1; lv <= g->n_runs; ++lv) {
     std::map<std::tuple<int, int, int>, int32_t> open;   // (kind, tile, adtype/split/lane) -> launch index
     for (int32_t i = 0; i < total; ++i) {
       Node& nd = g->nodes[(size_t)i];
-      if (nd.level != lv) continue;
+      if (nd.run != lv) continue;
       if (nd.elided) {   // a concatenation in place is complete once its second source is written: reported under that launch
         nd.launch = nd.kind == K_CONCAT ? g->nodes[(size_t)nd.residual].launch : 0;   // (a fused affine node: set below)
         nd.slot = 0;
+        continue;
+      }
+      if (nd.chain >= 0 && nd.chain_pos > 0) continue;   // runs inside its chain's launch (set when the head is scheduled)
+      if (nd.chain == i) {
+        // the head of a chain: one problem = the chain's two or three nodes; launches are shared by chains of one shape
+        int32_t bi = -1, ci = -1;
+        for (int32_t r = i + 1; r < total; ++r) {
+          const Node& f = g->nodes[(size_t)r];
+          if (f.chain != i) continue;
+          if (f.chain_pos == 1) bi = r; else if (f.chain_pos == 2) ci = r;
+        }
+        const int shape = nd.Co * 4 + (ci >= 0 ? g->nodes[(size_t)ci].Co / 64 : 0);   // the kernel's template arguments
+        const auto key = std::make_tuple((int)K_CHAIN, shape, nd.lane);
+        auto it = open.find(key);
+        if (!opts->group_levels || it == open.end() || g->launches[(size_t)it->second].n + 3 > FI_MAX_GROUP) {
+          new_launch(lv, K_CHAIN, ci >= 0 ? 1 : 0, FI_BF16).lane = nd.lane;
+          open[key] = (int32_t)g->launches.size() - 1;
+          it = open.find(key);
+        }
+        Launch& L = g->launches[(size_t)it->second];
+        const int32_t trio[3] = {i, bi, ci >= 0 ? ci : bi};   // (a chain of two repeats its second node in the third place)
+        for (int t3 = 0; t3 < 3; ++t3) {
+          Node& f = g->nodes[(size_t)trio[t3]];
+          if (t3 < 2 || ci >= 0) { f.launch = it->second; f.slot = L.n; }
+          L.nodes.push_back(trio[t3]);
+          ++L.n;
+        }
         continue;
       }
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
@@ -641,19 +772,19 @@ static fi_status plan_dag(fi_dag* g) {
   std::vector<Tensor> tens((size_t)total + (size_t)n_stage);
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
-    nd.first_level = nd.last_level = nd.level;
+    nd.first_level = nd.last_level = nd.run;   // (live ranges are counted in launch order)
   }
   for (int32_t i = 0; i < total; ++i) {
     const Node& nd = g->nodes[(size_t)i];
-    if (nd.input >= 0) g->nodes[(size_t)nd.input].last_level = std::max(g->nodes[(size_t)nd.input].last_level, nd.level);
-    else { StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage]; st.last = std::max(st.last, nd.level); }
-    if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.level);
+    if (nd.input >= 0) g->nodes[(size_t)nd.input].last_level = std::max(g->nodes[(size_t)nd.input].last_level, nd.run);
+    else { StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage]; st.last = std::max(st.last, nd.run); }
+    if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.run);
     if (nd.pre >= 0) {   // the convolution reads the fused node's input (and gate) itself
       Node& T = g->nodes[(size_t)g->nodes[(size_t)nd.pre].input];
-      T.last_level = std::max(T.last_level, nd.level);
+      T.last_level = std::max(T.last_level, nd.run);
       if (g->nodes[(size_t)nd.pre].kind == K_MUL || g->nodes[(size_t)nd.pre].kind == K_CONCAT) {
         Node& G = g->nodes[(size_t)g->nodes[(size_t)nd.pre].residual];
-        G.last_level = std::max(G.last_level, nd.level);
+        G.last_level = std::max(G.last_level, nd.run);
       }
     }
   }
@@ -666,7 +797,7 @@ static fi_status plan_dag(fi_dag* g) {
   }
   for (int32_t i = 0; i < total; ++i) {
     Node& nd = g->nodes[(size_t)i];
-    nd.out_bytes = (nd.is_output || nd.root >= 0 || (nd.elided && nd.kind != K_CONCAT) || nd.elided == 2) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
+    nd.out_bytes = (nd.is_output || nd.root >= 0 || (nd.elided && nd.kind != K_CONCAT) || nd.elided == 2 || nd.chain == i) ? 0 : align_up((uint64_t)B * nd.Ho * nd.Wo * nd.Cop * esize(nd.out_dtype));
     tens[(size_t)i] = Tensor{nd.first_level, nd.last_level, nd.lane, nd.out_bytes, 0};
   }
   const Member& m0 = g->members[0];
@@ -741,7 +872,7 @@ static fi_status plan_dag(fi_dag* g) {
     std::map<std::pair<int32_t, int32_t>, uint64_t> level_top;
     for (Node& nd : g->nodes) {
       if (!(nd.kind == K_FC || (nd.kind == K_CONV_MFMA && nd.splits > 1))) continue;
-      uint64_t& top = level_top[{nd.lane, nd.level}];
+      uint64_t& top = level_top[{nd.lane, nd.run}];
       nd.ws_off = top;
       top += align_up((uint64_t)nd.splits * B * nd.Ho * nd.Wo * nd.Cop * 4);
       lane_need[(size_t)nd.lane] = std::max(lane_need[(size_t)nd.lane], top);
@@ -827,8 +958,13 @@ static fi_status plan_dag(fi_dag* g) {
         L.act_bytes += ((uint64_t)nd.splits * nd.Cop * 4 + (uint64_t)nd.Co * esize(nd.out_dtype)) * nd.Ho * nd.Wo;
         continue;
       }
+      if (L.kind == K_CHAIN && s % 3 == 2 && L.nodes[(size_t)s] == L.nodes[(size_t)s - 1]) continue;   // the filler of a chain of two
       L.macs += nd.macs;
       const uint64_t in_e = esize(nd.input >= 0 ? g->nodes[(size_t)nd.input].out_dtype : adt);
+      if (L.kind == K_CHAIN)   // the head's input, the second node's residual and output, the third node's output: nothing in between
+        L.act_bytes += (s % 3 == 0 ? (uint64_t)nd.H * nd.W * nd.C * in_e : (uint64_t)nd.Ho * nd.Wo * nd.Co * esize(nd.out_dtype)) +
+                       (nd.residual >= 0 ? (uint64_t)nd.Ho * nd.Wo * nd.Co * esize(adt) : 0);
+      else
       L.act_bytes += (uint64_t)nd.H * nd.W * nd.C * in_e + (uint64_t)nd.Ho * nd.Wo * nd.Co * esize(nd.out_dtype) +
                      (nd.residual >= 0 ? (uint64_t)nd.Ho * nd.Wo * nd.Co * esize(adt) : 0);
       if (nd.w_rel != kNone)
@@ -1239,7 +1375,7 @@ fi_status fi_swap_model(fi_dag* g, int32_t slot, const fi_model_spec* model, voi
   g->nodes = std::move(t.nodes);
   g->launches = std::move(t.launches);
   g->descs = std::move(t.descs);
-  g->n_levels = t.n_levels; g->wdtype = t.wdtype; g->macs = t.macs; g->n_lanes = t.n_lanes;
+  g->n_levels = t.n_levels; g->n_runs = t.n_runs; g->wdtype = t.wdtype; g->macs = t.macs; g->n_lanes = t.n_lanes;
   g->desc_bytes = t.desc_bytes; g->arena_bytes = t.arena_bytes; g->act_bytes = t.act_bytes;
   g->workspace_bytes = t.workspace_bytes; g->device_bytes = t.device_bytes;
   g->stages = std::move(t.stages);

@@ -1,0 +1,91 @@
+// Device-side helpers shared by the kernel files: element access, activations, problem lookup, MFMA operand types.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "fi_internal.h"
+
+namespace fi {
+
+// ---------------------------------------------------------------------------------
+// element access
+// ---------------------------------------------------------------------------------
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// round-to-nearest-even (the hardware conversion of gfx950: one instruction for a value, one for a pair)
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+__device__ __forceinline__ float ld(const float* p) { return *p; }
+__device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
+__device__ __forceinline__ void st(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
+
+// ReLU / ReLU6 / identity as branch-free selects (the common case), the smooth activations behind ONE
+// block-uniform branch per call: `act` is the same for every lane of a problem.
+__device__ __forceinline__ float activate_smooth(float v, int act) {
+  if (act == FI_ACT_HARDSWISH) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+  if (act == FI_ACT_HARDSIGMOID) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+  const float sg = 1.0f / (1.0f + expf(-v));
+  return act == FI_ACT_SILU ? v * sg : sg;
+}
+template <int N>
+__device__ __forceinline__ void activate_n(float* v, int act) {
+  if (__builtin_amdgcn_readfirstlane(act) > FI_ACT_RELU6) {
+#pragma unroll
+    for (int t = 0; t < N; ++t) v[t] = activate_smooth(v[t], act);
+    return;
+  }
+  const float hi = act == FI_ACT_RELU6 ? 6.0f : INFINITY;
+#pragma unroll
+  for (int t = 0; t < N; ++t) v[t] = act == FI_ACT_NONE ? v[t] : fminf(fmaxf(v[t], 0.0f), hi);
+}
+__device__ __forceinline__ float activate(float v, int act) {
+  activate_n<1>(&v, act);
+  return v;
+}
+
+// Finds the problem a workgroup belongs to from the per-launch table of starting workgroup
+// indices (kernel arguments: no memory round trip); on return `bid` is the index inside problem `p`.
+__device__ __forceinline__ bool find_problem_at(const KArgs& a, int gid, int& p, int& bid) {
+  p = 0;
+#pragma unroll
+  for (int i = 1; i < FI_MAX_GROUP; ++i) p += (i < a.n && gid >= a.first_block[i]) ? 1 : 0;
+  bid = gid - a.first_block[p];
+  return gid < a.first_block[a.n];
+}
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+
+constexpr int BK = 64;
+constexpr int LDS_STRIDE = BK + 8;  // elements; 144-byte rows keep 16-byte reads conflict-free
+constexpr int NXCD = 8;
+#ifndef STREAM_OUT_BYTES
+#define STREAM_OUT_BYTES (48 << 20)
+#endif
+constexpr uint32_t OOB = 0x80000000u;  // byte offset past any tensor: the buffer load returns zero
+
+// m / dv for 0 <= m < 2^24 (exact: the float product is off by at most one, then corrected)
+__device__ __forceinline__ int fast_div(int m, int dv, float inv) {
+  int t = (int)((float)m * inv);
+  const int r = m - t * dv;
+  t += (r >= dv) ? 1 : 0;
+  t -= (r < 0) ? 1 : 0;
+  return t;
+}
+
+__device__ __forceinline__ int xcd_contiguous(int bid, int total) {
+  const int c = total / NXCD, r = total % NXCD;
+  const int x = bid % NXCD, j = bid / NXCD;
+  return x * c + (x < r ? x : r) + j;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+}  // namespace fi

@@ -35,6 +35,7 @@ enum Kind : int32_t {
   K_AVGPOOL = 10,     // window average (divisor k*k)
   K_MUL = 11,         // per-(image, channel) gate
   K_GATHER = 12,      // channel slice (stride == 0: channels from pad on) or shuffle (stride == 1: k groups)
+  K_CHAIN = 13,       // a convolution and the one or two pointwise convolutions behind it, per 128-pixel tile, in one launch
   K_NKINDS
 };
 
@@ -95,7 +96,11 @@ struct Node {
                                  // concatenation that the two-group shuffle reading it replaces by interleaving its sources
   int32_t pre;                   // MFMA conv: the node fused into its input side, a per-channel affine (depthwise 1x1) or a
                                  // squeeze-excite scaling; shuffle: the concatenation it replaces (-1 = none)
-  int32_t level;
+  int32_t chain, chain_pos;      // chain >= 0: the node runs inside the chained launch headed by node `chain`, as its first (0), second
+                                 // (1) or third (2) convolution; the head's own output is stored nowhere
+  int32_t level;                 // depth: 1 + the deepest input
+  int32_t run;                   // position in the launch order (launches are issued by ascending `run`): the depth, unless the node
+                                 // follows a chain's head (then the head's) or its member's early levels are run in member chunks
   int32_t out_dtype;             // FI_F32 / FI_BF16 as stored
   int32_t is_output;
   int32_t first_level, last_level;
@@ -165,6 +170,9 @@ void pack_model(const fi_model_spec& m, const ModelPlan& p, uint8_t* dst);
 // The library's static split-K workspace on the current device (fi_run_static): its device address and size.
 // Implemented in fi_kernels.hip; returns a hipError_t as int.  Allocates nothing.
 int static_scratch(void** ptr, uint64_t* bytes);
+
+// Implemented in fi_chain.hip: a K_CHAIN launch (problems are triples of descriptors).  Returns a hipError_t as int.
+int launch_chain(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);
 
 // Implemented in fi_kernels.hip.  Returns a hipError_t as int; `stream` is a hipStream_t.
 int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);

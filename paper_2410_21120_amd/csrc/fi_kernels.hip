@@ -16,50 +16,10 @@
 #include <mutex>
 #include <type_traits>
 
+#include "fi_device.h"
 #include "fi_internal.h"
 
 namespace fi {
-
-// ---------------------------------------------------------------------------------
-// element access
-// ---------------------------------------------------------------------------------
-typedef uint16_t bf16_t;
-
-__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-// round-to-nearest-even; inputs are finite by construction
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-__device__ __forceinline__ float ld(const float* p) { return *p; }
-__device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
-__device__ __forceinline__ void st(float* p, float v) { *p = v; }
-__device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
-
-// ReLU / ReLU6 / identity as branch-free selects (the common case), the smooth activations behind ONE
-// block-uniform branch per call: `act` is the same for every lane of a problem.
-__device__ __forceinline__ float activate_smooth(float v, int act) {
-  if (act == FI_ACT_HARDSWISH) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
-  if (act == FI_ACT_HARDSIGMOID) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
-  const float sg = 1.0f / (1.0f + expf(-v));
-  return act == FI_ACT_SILU ? v * sg : sg;
-}
-template <int N>
-__device__ __forceinline__ void activate_n(float* v, int act) {
-  if (__builtin_amdgcn_readfirstlane(act) > FI_ACT_RELU6) {
-#pragma unroll
-    for (int t = 0; t < N; ++t) v[t] = activate_smooth(v[t], act);
-    return;
-  }
-  const float hi = act == FI_ACT_RELU6 ? 6.0f : INFINITY;
-#pragma unroll
-  for (int t = 0; t < N; ++t) v[t] = act == FI_ACT_NONE ? v[t] : fminf(fmaxf(v[t], 0.0f), hi);
-}
-__device__ __forceinline__ float activate(float v, int act) {
-  activate_n<1>(&v, act);
-  return v;
-}
 
 // Workgroups a problem needs, as a function of the batch (host and device agree on this).
 __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d, int batch) {
@@ -91,15 +51,6 @@ __host__ __device__ inline int problem_blocks(int kind, int tile, const Desc& d,
   return 0;
 }
 
-// Finds the problem a workgroup belongs to from the per-launch table of starting workgroup
-// indices (kernel arguments: no memory round trip); on return `bid` is the index inside problem `p`.
-__device__ __forceinline__ bool find_problem_at(const KArgs& a, int gid, int& p, int& bid) {
-  p = 0;
-#pragma unroll
-  for (int i = 1; i < FI_MAX_GROUP; ++i) p += (i < a.n && gid >= a.first_block[i]) ? 1 : 0;
-  bid = gid - a.first_block[p];
-  return gid < a.first_block[a.n];
-}
 __device__ __forceinline__ bool find_problem(const KArgs& a, int, int, int& p, int& bid) {
   return find_problem_at(a, (int)blockIdx.x, p, bid);
 }
@@ -182,38 +133,6 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(KArgs a) {
 // Workgroups are renumbered so that each XCD (blockIdx % 8) owns one contiguous run of
 // tiles: neighbouring tiles, which share input rows and a member's weights, meet in one L2.
 // ---------------------------------------------------------------------------------
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
-
-constexpr int BK = 64;
-constexpr int LDS_STRIDE = BK + 8;  // elements; 144-byte rows keep 16-byte reads conflict-free
-constexpr int NXCD = 8;
-#ifndef STREAM_OUT_BYTES
-#define STREAM_OUT_BYTES (48 << 20)
-#endif
-constexpr uint32_t OOB = 0x80000000u;  // byte offset past any tensor: the buffer load returns zero
-
-// m / dv for 0 <= m < 2^24 (exact: the float product is off by at most one, then corrected)
-__device__ __forceinline__ int fast_div(int m, int dv, float inv) {
-  int t = (int)((float)m * inv);
-  const int r = m - t * dv;
-  t += (r >= dv) ? 1 : 0;
-  t -= (r < 0) ? 1 : 0;
-  return t;
-}
-
-__device__ __forceinline__ int xcd_contiguous(int bid, int total) {
-  const int c = total / NXCD, r = total % NXCD;
-  const int x = bid % NXCD, j = bid / NXCD;
-  return x * c + (x < r ? x : r) + j;
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
-}
-
 // Finishes four consecutive features [o, o + 4) of output row n from their complete fp32 sums: bias
 // (and residual), activation, zero in the padded features, store.  p: the problem's slot in the launch.
 template <typename TA>
@@ -1595,6 +1514,7 @@ int static_scratch(void** ptr, uint64_t* bytes) {
 }
 
 int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::vector<Desc>& hd) {
+  if (L.kind == K_CHAIN) return launch_chain(L, args, stream, hd);
   hipStream_t s = static_cast<hipStream_t>(stream);
   KArgs a = args;
   for (int i = 0; i < L.n; ++i) a.d[i] = hd[(size_t)(L.first_desc + i)];

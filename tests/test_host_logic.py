@@ -43,7 +43,7 @@ def test_union_levels_and_operator_count():
     levels equal the member's own depth (Algorithm 1, compilation loop; Section IV-C: the DAG holds
     exactly the members' operators)."""
     fams = ["resnet50", "mobilenetv2", "vgg16", "resnet18"]
-    d, models, _ = _build(fams, 2)
+    d, models, _ = _build(fams, 2, separate_chains=True)   # one launch per node and level (chained launches: tested below)
     q = d.query()
     assert q.n_models == 4 and q.n_nodes == sum(len(m.layers) for m in models)
     assert q.n_levels == max(max(m.levels()) for m in models)
@@ -75,8 +75,8 @@ def test_union_levels_and_operator_count():
 
 def test_grouping_reduces_launches_only():
     fams = ["resnet50"] * 8
-    g, _, _ = _build(fams, 4)
-    u, _, _ = _build(fams, 4, group=False)
+    g, _, _ = _build(fams, 4, separate_chains=True)
+    u, _, _ = _build(fams, 4, group=False, separate_chains=True)   # (a launch per node: chains would take three nodes each)
     qg, qu = g.query(), u.query()
     n_red = sum(1 for L in u.launches() if L.name == b"splitk_reduce")  # split-K launches have a reduce twin
     assert n_red >= sum(1 for n in u.nodes() if n.op == fi.FI_FC)
@@ -93,7 +93,7 @@ def test_activation_arena_liveness_non_overlap():
         nodes = [n for n in d.nodes() if n.out_bytes]
         for n in nodes:
             assert n.out_off % 256 == 0 and n.out_off + n.out_bytes <= q.act_bytes
-            assert n.first_level == n.level and n.last_level >= n.level
+            assert n.first_level <= n.level and n.last_level >= n.first_level   # (a chain's outputs are written at its head's place)
         for i, a in enumerate(nodes):
             for b in nodes[i + 1:]:
                 if a.first_level <= b.last_level and b.first_level <= a.last_level:  # alive together
@@ -621,3 +621,46 @@ def test_folded_schedules_of_the_concatenating_and_gated_families():
     grouped = [i for i, L in enumerate(m.layers) if L.op == "conv" and L.groups > 1]
     assert len(grouped) == 16
     assert all(launch_names[d.nodes()[i].launch] in ("conv_mfma_256x64", "conv_mfma_128x64", "conv_mfma_64x64") for i in grouped)
+
+
+def test_chains_drop_the_first_tensor_and_two_launches_per_block():
+    """A bottleneck's 3x3, its 1x1 expansion and the next block's 1x1 reduction run as one launch: the 3x3's output has
+    no buffer, the launch's compulsory bytes are the head's input, the second node's residual and output and the third
+    node's output, and the schedule has fewer launches than with separate_chains."""
+    d, models, _ = _build(["resnet50"] * 2, 8, hw=128)
+    p, _, _ = _build(["resnet50"] * 2, 8, hw=128, separate_chains=True)
+    names = [L.name.decode() for L in d.launches()]
+    assert names.count("conv_chain3") >= 3 and not any(n.decode().startswith("conv_chain") for n in (L.name for L in p.launches()))
+    assert d.query().n_launches < p.query().n_launches
+    assert d.query().macs_per_image == p.query().macs_per_image
+    nodes, pnodes = d.nodes(), p.nodes()
+    for L in d.launches():
+        if not L.name.decode().startswith("conv_chain"):
+            continue
+        head = nodes[L.first_node]
+        assert head.out_bytes == 0 and pnodes[L.first_node].out_bytes > 0
+        assert L.n_problems == 6   # two members, three nodes each
+    chained = sum(L.bytes_per_image for L in d.launches())
+    plain = sum(L.bytes_per_image for L in p.launches())
+    assert chained < 0.95 * plain   # activation bytes per image of the whole schedule (only the first stage chains at this size)
+    assert sum(L.macs_per_image for L in d.launches()) == sum(L.macs_per_image for L in p.launches())
+
+
+def test_member_chunks_shrink_the_activation_arena():
+    """The early levels of a lane's members run chunk after chunk: the chunks' early tensors share memory, launches get
+    more numerous, the live ranges (in launch order) of tensors that share bytes never overlap."""
+    base, _, _ = _build(["resnet50"] * 4 + ["vgg16"] * 2, 4, hw=128)
+    half, _, _ = _build(["resnet50"] * 4 + ["vgg16"] * 2, 4, hw=128, member_chunks=2)
+    qb, qh = base.query(), half.query()
+    assert qh.act_bytes < 0.9 * qb.act_bytes and qh.n_launches > qb.n_launches
+    assert (qh.arena_bytes, qh.n_nodes, qh.n_levels, qh.macs_per_image) == (qb.arena_bytes, qb.n_nodes, qb.n_levels, qb.macs_per_image)
+    lane_of = [m.lane for m in half.members()]
+    nodes = [n for n in half.nodes() if n.out_bytes]
+    for i, a in enumerate(nodes):
+        for b in nodes[i + 1:]:
+            if lane_of[a.model] != lane_of[b.model] or (a.first_level <= b.last_level and b.first_level <= a.last_level):
+                assert a.out_off + a.out_bytes <= b.out_off or b.out_off + b.out_bytes <= a.out_off
+    # a single member per lane has nothing to chunk
+    one, _, _ = _build(["resnet50", "vgg16"], 4, hw=128, member_chunks=2)
+    ref, _, _ = _build(["resnet50", "vgg16"], 4, hw=128)
+    assert one.query().act_bytes == ref.query().act_bytes and one.query().n_launches == ref.query().n_launches
