@@ -133,7 +133,13 @@ typedef struct {
 
 typedef enum {
   FI_LOAD_ONE_COPY = 0,  /* gather members into one pinned image at build; fi_load = 1 H2D copy */
-  FI_LOAD_PER_MODEL = 1  /* no host gather; fi_load copies each member's packed blob (+1 for the schedule) */
+  FI_LOAD_PER_MODEL = 1, /* no host gather; fi_load copies each member's packed blob (+1 for the schedule) */
+  FI_LOAD_AUTO = 2       /* gather only when it pays: members that are all in device layout are copied one by one
+                          * straight out of the repository's blobs by the FIRST load of the handle (a set of models
+                          * that is loaded once, as when the subset changes with every request, never pays a host
+                          * gather); a handle that is loaded AGAIN gathers its image then, once, and from there on
+                          * every load is one copy.  With a canonical member the image has to be written at build
+                          * anyway and the mode is FI_LOAD_ONE_COPY. */
 } fi_load_mode;
 
 /* Allocator callbacks let the caller's memory pool (e.g. a tensor library's

@@ -18,7 +18,7 @@ FI_F32, FI_BF16 = 0, 1
 FI_CONV2D, FI_DWCONV2D, FI_MAXPOOL2D, FI_GLOBAL_AVGPOOL, FI_FC, FI_SOFTMAX, FI_CONCAT, FI_AVGPOOL2D, FI_MUL, FI_SLICE, FI_SHUFFLE = range(11)
 FI_ACT_NONE, FI_ACT_RELU, FI_ACT_RELU6, FI_ACT_HARDSWISH, FI_ACT_HARDSIGMOID, FI_ACT_SILU, FI_ACT_SIGMOID = range(7)
 FI_INPUT, FI_NO_RESIDUAL = -1, -2
-FI_LOAD_ONE_COPY, FI_LOAD_PER_MODEL = 0, 1
+FI_LOAD_ONE_COPY, FI_LOAD_PER_MODEL, FI_LOAD_AUTO = 0, 1, 2
 FI_MAX_GROUP = 16
 STATUS_NAMES = ["FI_OK", "FI_EINVAL", "FI_EUNSUPPORTED", "FI_ESTATE", "FI_ENOMEM_HOST", "FI_ENOMEM_DEVICE",
                 "FI_EBUDGET", "FI_EHIP"]

@@ -59,6 +59,8 @@ struct fi_dag {
   uint64_t image_capacity = 0;        // bytes the pinned allocation holds (a swap may shrink image_bytes, never this)
   std::vector<fi::StageTensor> stages;  // staged inputs: one per activation dtype, or one per member
   uint8_t* image = nullptr;           // pinned host image
+  bool gathered = false;              // the image is the whole arena (one copy per load); else the header only, members are copied from their blobs
+  int32_t n_loads = 0;                // loads so far (FI_LOAD_AUTO gathers before the second)
   uint8_t* dev = nullptr;             // the one device allocation (LOADED only)
   uint64_t dev_capacity = 0;          // its size: what the plan needed at load plus the swap headroom
   uint64_t last_h2d_bytes = 0;        // bytes and copies of the most recent load or member swap
@@ -240,7 +242,7 @@ fi_status fi_footprint(const fi_model_spec* models, int32_t n, const fi_build_op
 static fi_status build_core(const fi_model_spec* models, int32_t n, const fi_build_opts* opts, bool with_image, fi_dag** out) {
   if (!models || n < 1 || !opts || !out) { set_error("null argument or no models"); return FI_EINVAL; }
   if (opts->max_batch < 1 || opts->max_batch > kMaxBatch) { set_error("max_batch must be in [1, %d]", kMaxBatch); return FI_EINVAL; }
-  if (opts->load_mode != FI_LOAD_ONE_COPY && opts->load_mode != FI_LOAD_PER_MODEL) { set_error("bad load_mode"); return FI_EINVAL; }
+  if (opts->load_mode != FI_LOAD_ONE_COPY && opts->load_mode != FI_LOAD_PER_MODEL && opts->load_mode != FI_LOAD_AUTO) { set_error("bad load_mode"); return FI_EINVAL; }
   if ((opts->pin_alloc == nullptr) != (opts->pin_free == nullptr) || (opts->dev_alloc == nullptr) != (opts->dev_free == nullptr)) {
     set_error("allocator callbacks come in alloc/free pairs"); return FI_EINVAL; }
   std::unique_ptr<fi_dag> g(new (std::nothrow) fi_dag);
@@ -261,13 +263,17 @@ static fi_status build_core(const fi_model_spec* models, int32_t n, const fi_bui
   if (!with_image) { *out = g.release(); return FI_OK; }
 
   // ---- pinned image: the bytes fi_load copies ----------------------------------------------
-  g->image_bytes = opts->load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;
+  // FI_LOAD_AUTO: members already in device layout need no image until the handle is loaded a second time
+  bool all_packed = true;
+  for (const Member& mb : g->members) all_packed = all_packed && mb.spec.weights_packed;
+  g->gathered = opts->load_mode == FI_LOAD_ONE_COPY || (opts->load_mode == FI_LOAD_AUTO && !all_packed);
+  g->image_bytes = g->gathered ? g->arena_bytes : g->desc_bytes;
   g->image_capacity = g->image_bytes;
   g->image = static_cast<uint8_t*>(pin_alloc(*opts, (size_t)g->image_bytes));
   if (!g->image) { set_error("pinned allocation of %llu bytes failed", (unsigned long long)g->image_bytes); return FI_ENOMEM_HOST; }
   std::memset(g->image, 0, (size_t)g->desc_bytes);
   std::memcpy(g->image, "fusedinf-arena-1", 16);
-  if (opts->load_mode == FI_LOAD_ONE_COPY) {
+  if (g->gathered) {
     for (const Member& mb : g->members) {
       if (mb.spec.weights_packed) parallel_copy(g->image + mb.arena_off, static_cast<const uint8_t*>(mb.spec.weights), mb.plan.packed_bytes);
       else pack_model(mb.spec, mb.plan, g->image + mb.arena_off);
@@ -440,7 +446,7 @@ static void form_chains(fi_dag* g) {
     if (readers[(size_t)i].size() != 1 || other_uses[(size_t)i] != 0) continue;
     const int32_t bi = readers[(size_t)i][0];
     Node& Bn = g->nodes[(size_t)bi];
-    if (!plain_conv(Bn) || !pointwise(Bn) || Bn.level != A.level + 1 || Bn.run != A.run + 1 || Bn.C != A.Co || Bn.Cp != A.Cop || Bn.Co % 128 || Bn.Co != Bn.Cop || Bn.Kp != Bn.Cp) continue;
+    if (!plain_conv(Bn) || !pointwise(Bn) || Bn.level != A.level + 1 || Bn.run != A.run + 1 || Bn.C != A.Co || Bn.Cp != A.Cop || Bn.Co % 128 || Bn.Co > 1024 || Bn.Co != Bn.Cop || Bn.Kp != Bn.Cp) continue;
     if (Bn.residual >= 0) {
       const Node& R = g->nodes[(size_t)Bn.residual];
       if (R.root >= 0 || R.out_dtype != FI_BF16 || R.Cop != Bn.Cop || Bn.residual == i) continue;
@@ -1018,7 +1024,7 @@ fi_status fi_query(const fi_dag* g, fi_dag_info* info) {
   info->n_models = (int32_t)g->members.size(); info->n_nodes = (int32_t)g->nodes.size();
   info->n_levels = g->n_levels; info->n_launches = (int32_t)g->launches.size();
   info->n_device_allocs = 1;
-  info->n_h2d_copies = g->opts.load_mode == FI_LOAD_ONE_COPY ? 1 : 1 + (int32_t)g->members.size();
+  info->n_h2d_copies = g->gathered ? 1 : 1 + (int32_t)g->members.size();
   info->state = g->state;
   info->n_lanes = g->n_lanes;
   info->device_capacity = g->dev_capacity;
@@ -1079,13 +1085,30 @@ static void ensure_lanes(fi_dag* g) {
   }
 }
 
+// The whole arena image in pinned memory, from a handle that so far held the header only (all members are in device
+// layout).  On failure the handle keeps copying member by member.
+static bool gather_image(fi_dag* g) {
+  uint8_t* whole = static_cast<uint8_t*>(pin_alloc(g->opts, (size_t)g->arena_bytes));
+  if (!whole) return false;
+  if (g->copy_done) (void)hipEventSynchronize(g->copy_done);   // (the header may still be on its way out of the old image)
+  std::memset(whole, 0, (size_t)g->desc_bytes);
+  std::memcpy(whole, g->image, (size_t)std::min(g->desc_bytes, g->image_capacity));
+  for (const Member& mb : g->members) parallel_copy(whole + mb.arena_off, static_cast<const uint8_t*>(mb.spec.weights), mb.plan.packed_bytes);
+  pin_free(g->opts, g->image);
+  g->image = whole;
+  g->image_capacity = g->image_bytes = g->arena_bytes;
+  g->gathered = true;
+  return true;
+}
+
 fi_status fi_load(fi_dag* g, void* stream) {
   if (!g) { set_error("null handle"); return FI_EINVAL; }
   if (g->state != 0) { set_error("fi_load: handle is already loaded"); return FI_ESTATE; }
+  if (g->opts.load_mode == FI_LOAD_AUTO && !g->gathered && g->n_loads > 0) (void)gather_image(g);   // loaded again: worth one image from now on
   const uint64_t want = g->device_bytes + g->opts.swap_headroom_bytes;
   // what the load copies is the plan's arena (or its header), not whatever the pinned allocation can hold:
   // a member swap may have left the plan smaller than the image once was
-  const uint64_t copy_bytes = g->opts.load_mode == FI_LOAD_ONE_COPY ? g->arena_bytes : g->desc_bytes;
+  const uint64_t copy_bytes = g->gathered ? g->arena_bytes : g->desc_bytes;
   if (copy_bytes > want || copy_bytes > g->image_capacity) {
     set_error("fi_load: the arena image (%llu bytes) does not fit the pinned image (%llu) or the device allocation (%llu)",
               (unsigned long long)copy_bytes, (unsigned long long)g->image_capacity, (unsigned long long)want);
@@ -1098,7 +1121,7 @@ fi_status fi_load(fi_dag* g, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipMemcpyAsync(d, g->image, (size_t)copy_bytes, hipMemcpyHostToDevice, s);
   g->last_h2d_bytes = copy_bytes; g->last_h2d_copies = 1;
-  if (e == hipSuccess && g->opts.load_mode == FI_LOAD_PER_MODEL)
+  if (e == hipSuccess && !g->gathered)
     for (const Member& mb : g->members) {
       e = hipMemcpyAsync(d + mb.arena_off, mb.spec.weights, (size_t)mb.plan.packed_bytes, hipMemcpyHostToDevice, s);
       if (e != hipSuccess) break;
@@ -1116,6 +1139,7 @@ fi_status fi_load(fi_dag* g, void* stream) {
   g->dev = d;
   g->dev_capacity = want;
   g->state = 1;
+  ++g->n_loads;
   return FI_OK;
 }
 
@@ -1338,7 +1362,10 @@ fi_status fi_swap_model(fi_dag* g, int32_t slot, const fi_model_spec* model, voi
   hipStream_t s = static_cast<hipStream_t>(stream);
   const Member& placed = t.members[(size_t)slot];
   const uint8_t* src = static_cast<const uint8_t*>(placed.spec.weights);
-  const bool one_copy = g->opts.load_mode == FI_LOAD_ONE_COPY && g->image;
+  if (!g->gathered && g->image && !placed.spec.weights_packed) {   // a canonical newcomer has to be packed somewhere: from now on the handle keeps an image
+    if (g->opts.load_mode != FI_LOAD_AUTO || !gather_image(g)) { set_error("a member in canonical layout needs the handle's pinned image"); return FI_ENOMEM_HOST; }
+  }
+  const bool one_copy = g->gathered && g->image;
   if (one_copy) {
     // the pinned image stays the exact image of the arena; copies out of it must have finished
     if (g->copy_done) (void)hipEventSynchronize(g->copy_done);

@@ -61,9 +61,15 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   constexpr int PATCHES = 4 * 32 * PS * 2;
   constexpr int REGION0 = STAGE_A > PATCHES ? STAGE_A : PATCHES;   // A tiles during the first GEMM, the waves' patches afterwards
   constexpr int STAGE_B = 128 * LDS_STRIDE * 2;
-  __shared__ __attribute__((aligned(16))) uint8_t smem[REGION0 + STAGE_B];
+  constexpr int MAXN2 = 1024;                  // widest B the bias table holds (the host checks)
+  constexpr int BIAS = (W1 + MAXN2 + (N3 > 0 ? N3 : 0)) * 4;   // the three bias vectors, read by every lane in every epilogue
+  constexpr bool EARLY = W1 == 64 && N3 == 64;  // registers to spare: every weight tile a chunk needs is requested before the epilogue before it
+  __shared__ __attribute__((aligned(16))) uint8_t smem[REGION0 + STAGE_B + BIAS];
   bf16_t* const As = reinterpret_cast<bf16_t*>(smem);
   bf16_t* const Bs = reinterpret_cast<bf16_t*>(smem + REGION0);
+  float* const bias1 = reinterpret_cast<float*>(smem + REGION0 + STAGE_B);
+  float* const bias2 = bias1 + W1;
+  float* const bias3 = bias2 + MAXN2;
 
   int p, bid;
   if (!find_problem_at(a, xcd_contiguous((int)blockIdx.x, (int)gridDim.x), p, bid)) return;
@@ -138,6 +144,16 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
     }                                                                                                        \
   }
   FI_FETCH_B(w2, W1, 0, 0, 4)
+  {   // the bias vectors into LDS (visible after the first barrier of the first GEMM, long before their first reader)
+    const float* g1 = reinterpret_cast<const float*>(a.wbase + d1.b_off);
+    const float* g2 = reinterpret_cast<const float*>(a.wbase + d2.b_off);
+    for (int i = tid; i < W1; i += 256) bias1[i] = g1[i];
+    for (int i = tid; i < d2.Co; i += 256) bias2[i] = g2[i];
+    if constexpr (N3 > 0) {
+      const float* g3 = reinterpret_cast<const float*>(a.wbase + d3.b_off);
+      for (int i = tid; i < N3; i += 256) bias3[i] = g3[i];
+    }
+  }
   if constexpr (W1 == 64) { if (res) FI_FETCH_RES(0) }   // (the wider chains have no registers to spare for it this early)
 
   f32x16 acc1[NI1];
@@ -204,7 +220,7 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   // ---- A's epilogue in registers: bias, activation, one rounding; then into B's operand slots -------------
   uint32_t t1f[W1 / 16][4];
   {
-    const float* bias = reinterpret_cast<const float*>(a.wbase + d1.b_off);
+    const float* bias = bias1;
 #pragma unroll
     for (int j = 0; j < NI1; ++j) {
       uint32_t pk[4][2];
@@ -233,6 +249,8 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   for (int j = 0; j < NI3; ++j)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc3[j][e] = 0.0f;
+  u32x4 b3v[2][NI3];   // (EARLY) the two tiles of C's weights that a chunk multiplies
+  constexpr int WS = 2 * BK + 8;   // (EARLY) row stride of the two tiles parked side by side: 272-byte rows
 
   for (int c = 0; c < nchunks; ++c) {
     if constexpr (W1 != 64) { if (res) FI_FETCH_RES(c) }   // requested before this chunk's multiplies
@@ -245,7 +263,12 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
     for (int kt = 0; kt < KT2; ++kt) {
       FI_PARK_B(4)
       __syncthreads();
-      if (kt + 1 < KT2) FI_FETCH_B(w2, W1, c * 128, (kt + 1) * BK, 4)
+      if constexpr (EARLY) {   // both tiles of C's weights for this chunk and B's tile for the next: in flight through the epilogue
+        _Pragma("unroll") for (int t = 0; t < 2; ++t)
+        _Pragma("unroll") for (int i = 0; i < NI3; ++i)
+            b3v[t][i] = *reinterpret_cast<const u32x4*>(w3 + (int64_t)(srow + 32 * i) * Kp3 + c * 128 + t * BK + kvec);
+        if (c + 1 < nchunks) FI_FETCH_B(w2, W1, (c + 1) * 128, 0, 4)
+      } else if (kt + 1 < KT2) FI_FETCH_B(w2, W1, c * 128, (kt + 1) * BK, 4)
       else if (N3 > 0) FI_FETCH_B(w3, Kp3, 0, c * 128, NI3)
       else if (c + 1 < nchunks) FI_FETCH_B(w2, W1, (c + 1) * 128, 0, 4)
 #pragma unroll
@@ -277,7 +300,7 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
     }
     uint32_t t2f[8][4];
     {
-      const float* bias = reinterpret_cast<const float*>(a.wbase + d2.b_off) + c * 128;
+      const float* bias = bias2 + c * 128;
       uint32_t pk[4][4][2];
 #pragma unroll
       for (int j = 0; j < 4; ++j)
@@ -330,7 +353,28 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
     }
 
     // C: this chunk's 128 channels are reduction elements 128 c .. 128 c + 127 of C
-    if (N3 > 0) {
+    if constexpr (EARLY) {
+      // both tiles side by side in one [N3 x 128] block: one barrier pair, eight reduction steps
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < NI3; ++i) *reinterpret_cast<u32x4*>(&Bs[(srow + 32 * i) * WS + t * BK + kvec]) = b3v[t][i];
+      __syncthreads();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const int kof = ks * 16 + lh * 8;
+        u32x4 au;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) au[e] = t2f[ks][e];
+        const bf16x8 af = __builtin_bit_cast(bf16x8, au);
+#pragma unroll
+        for (int j = 0; j < NI3; ++j) {
+          const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(&Bs[(j * 32 + lp) * WS + kof]);
+          acc3[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af, acc3[j], 0, 0, 0);
+        }
+      }
+      __syncthreads();
+    } else if (N3 > 0) {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
         FI_PARK_B(NI3)
@@ -360,7 +404,7 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
 
   // ---- C's epilogue ---------------------------------------------------------------------------------------
   if (N3 > 0) {
-    const float* bias = reinterpret_cast<const float*>(a.wbase + d3.b_off);
+    const float* bias = bias3;
 #pragma unroll
     for (int j = 0; j < NI3; ++j)
 #pragma unroll
@@ -420,7 +464,7 @@ int launch_chain(const Launch& L, const KArgs& args, void* stream, const std::ve
       return (int)hipErrorInvalidValue;
     // B: pointwise on A's pixels, W1 -> a multiple of 128 channels
     if (d2.k != 1 || d2.kw != 1 || d2.stride != 1 || d2.pad != 0 || d2.pad_w != 0 || d2.C != W1 || d2.Cp != W1 || d2.Kp != W1 || d2.Co != d2.Cop || d2.Co % 128 ||
-        d2.Co < 128 || d2.splits != 1 || d2.ext || d2.out_f32 || d2.pre_kind != 0 || d2.gin > 0 || d2.Ho != d1.Ho || d2.Wo != d1.Wo || d2.ys < d2.Cop || d2.y_off == kNone)
+        d2.Co < 128 || d2.Co > 1024 || d2.splits != 1 || d2.ext || d2.out_f32 || d2.pre_kind != 0 || d2.gin > 0 || d2.Ho != d1.Ho || d2.Wo != d1.Wo || d2.ys < d2.Cop || d2.y_off == kNone)
       return (int)hipErrorInvalidValue;
     if (has_c) {   // C: pointwise on the same pixels, B's channels -> N3
       if (d3.k != 1 || d3.kw != 1 || d3.stride != 1 || d3.pad != 0 || d3.pad_w != 0 || d3.C != d2.Co || d3.Cp != d2.Co || d3.Kp != d2.Co || d3.Co != N3 ||

@@ -74,9 +74,40 @@ def test_grouped_equals_ungrouped_and_load_modes():
         t = torch.empty(n, dtype=torch.uint8, pin_memory=True)
         fi.fi_model_pack(spec, t.data_ptr(), n)
         packed.append((m, t.numpy(), act))
-    for mode in (fi.FI_LOAD_ONE_COPY, fi.FI_LOAD_PER_MODEL):
+    for mode in (fi.FI_LOAD_ONE_COPY, fi.FI_LOAD_PER_MODEL, fi.FI_LOAD_AUTO):
         c = _run(packed, x, load_mode=mode, packed=True)
         assert all(np.array_equal(u, v) for u, v in zip(a, c))
+    # FI_LOAD_AUTO gathers only when it pays: members in device layout travel one by one on the first load of the handle,
+    # as one image from the second load on; canonical members are packed at build, so their handle is one-copy from the start
+    from tests import harness
+    g = harness.GpuDag(packed, 2, load_mode=fi.FI_LOAD_AUTO, packed=True, swap_headroom_bytes=64 << 20)
+    try:
+        q = g.dag.query()
+        assert (q.n_h2d_copies, q.last_h2d_copies) == (1 + len(packed), 1 + len(packed)) and q.last_h2d_bytes >= q.arena_bytes - 256 * len(packed)
+        assert all(np.array_equal(u, v) for u, v in zip(a, g.run(x)))
+        g.dag.unload()
+        g.dag.load(g.stream)
+        q = g.dag.query()
+        assert (q.n_h2d_copies, q.last_h2d_copies, q.last_h2d_bytes) == (1, 1, q.arena_bytes)
+        assert all(np.array_equal(u, v) for u, v in zip(a, g.run(x)))
+        # a member swap on the gathered handle keeps the image exact: unload, load, same bits
+        newcomer = (mem[1][0], gen.make_blob(mem[1][0], 4321), mem[1][2])
+        g.packed = False
+        g.swap(1, newcomer)
+        after = g.run(x)
+        g.dag.unload()
+        g.dag.load(g.stream)
+        assert all(np.array_equal(u, v) for u, v in zip(after, g.run(x)))
+        assert np.array_equal(after[0], a[0]) and not np.array_equal(after[1], a[1])
+    finally:
+        g.close()
+    g = harness.GpuDag(mem, 2, load_mode=fi.FI_LOAD_AUTO)
+    try:
+        q = g.dag.query()
+        assert (q.n_h2d_copies, q.last_h2d_copies, q.last_h2d_bytes) == (1, 1, q.arena_bytes)
+        assert all(np.array_equal(u, v) for u, v in zip(a, g.run(x)))
+    finally:
+        g.close()
 
 
 def test_launch_counts_and_single_allocation():
