@@ -254,12 +254,16 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     for (int r = 0; r < d.kw; ++r) rc |= ((unsigned)(iw0 + r) < (unsigned)d.W) ? (65536 << r) : 0;
     a_rc[i] = ok ? rc : 0;  // rows past M read as zero
   }
-  const uint4* b_ptr[BR];
+  // Weights through a buffer resource as well: a vector that must read as zero (the half tile that ends a row padded
+  // to 32 elements, every vector of the fetch that follows the last tile) takes an out-of-range offset, so the fetch
+  // needs no branch and sits in one basic block with the multiply it overlaps.
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, (int)((int64_t)d.Co * d.Kp * 2), 0x00020000);
+  int b_row[BR];
 #pragma unroll
   for (int i = 0; i < BR; ++i) {
     int o = n0 + srow + RPP * i;
     o = o < d.Co ? o : d.Co - 1;  // clamped rows are computed and discarded
-    b_ptr[i] = reinterpret_cast<const uint4*>(w + (int64_t)o * d.Kp + kvec);
+    b_row[i] = (o * d.Kp + kvec) * 2;
   }
   // this thread's reduction position (r, s, c) for the tile being fetched
   int c_lo = 0, c_hi = d.Cp;   // channels walked per filter tap
@@ -303,14 +307,17 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   float4 pre_t[1][2];
   uint4 pre_g[1][PRE == 2 ? AR : 1][AV];   // PRE == 2: the gate vectors of this thread's rows
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
+  const bool one_wrap = c_len >= BK;     // (block-uniform)
 
-#define FI_FETCH(KT, S)                                                                           \
+#define FI_FETCH(KT, S, LIVE)                                                                     \
   {                                                                                               \
+    /* a fetch past the last tile: the top bit puts every offset out of range (plain arithmetic, so no branch on it) */ \
+    const uint32_t dead = (LIVE) ? 0u : OOB;                                                      \
     if constexpr (!C4) {                                                                          \
       const int tvar = ((kr * d.W + ks) * d.Cp + kc) * AE;                                        \
       _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                            \
         const bool ok = ((a_rc[i] >> kr) & (a_rc[i] >> (16 + ks)) & 1) != 0;                       \
-        const uint32_t off = ok ? (uint32_t)(a_row[i] + tvar) : OOB;                              \
+        const uint32_t off = (ok ? (uint32_t)(a_row[i] + tvar) : OOB) | dead;                     \
         _Pragma("unroll") for (int h = 0; h < AV; ++h)                                            \
             av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off + 16 * h, 0, 0);        \
       }                                                                                           \
@@ -325,7 +332,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                            \
         _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                           \
           const bool ok = tr[h] < d.k && ((a_rc[i] >> tr[h]) & (a_rc[i] >> (16 + tc[h])) & 1) != 0; \
-          const uint32_t off = ok ? (uint32_t)(a_row[i] + tv[h]) : OOB;                           \
+          const uint32_t off = (ok ? (uint32_t)(a_row[i] + tv[h]) : OOB) | dead;                  \
           if constexpr (WIDE) {                                                                   \
             av[S][i][h] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);                 \
           } else {                                                                                \
@@ -339,12 +346,12 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     if constexpr (PRE == 2) {                                                                     \
       _Pragma("unroll") for (int i = 0; i < AR; ++i)                                              \
       _Pragma("unroll") for (int h = 0; h < AV; ++h) {                                            \
-        if constexpr (WIDE) pre_g[S][i][h] = kr == 0 ? *reinterpret_cast<const uint4*>(pre_b + a_gate[i] + kc + 4 * h) : make_uint4(0, 0, 0, 0); \
-        else pre_g[S][i][h] = kr == 0 ? *reinterpret_cast<const uint4*>(pre_w + a_gate[i] + kc) : make_uint4(0, 0, 0, 0); \
+        if constexpr (WIDE) pre_g[S][i][h] = ((LIVE) && kr == 0) ? *reinterpret_cast<const uint4*>(pre_b + a_gate[i] + kc + 4 * h) : make_uint4(0, 0, 0, 0); \
+        else pre_g[S][i][h] = ((LIVE) && kr == 0) ? *reinterpret_cast<const uint4*>(pre_w + a_gate[i] + kc) : make_uint4(0, 0, 0, 0); \
       }                                                                                           \
     }                                                                                             \
     if constexpr (PRE == 1) { /* channels past Cp (the tile tail) have walked on to filter row 1: no stage, the input reads as zero */ \
-      const bool pok = kr == 0;                                                                   \
+      const bool pok = (LIVE) && kr == 0;                                                                 \
       pre_s[S] = pok ? *reinterpret_cast<const uint4*>(pre_w + kc) : make_uint4(0, 0, 0, 0);      \
       pre_t[S][0] = pok ? *reinterpret_cast<const float4*>(pre_b + kc) : make_float4(0, 0, 0, 0); \
       pre_t[S][1] = pok ? *reinterpret_cast<const float4*>(pre_b + kc + 4) : make_float4(0, 0, 0, 0); \
@@ -353,15 +360,24 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     /* position of this tile in a weight row, in 8-element vectors past the thread's own kvec */  \
     const int wt = GROUPED ? ((kr * d.kw + ks) * d.Cp + kc - kvec) >> 3 : (KT) * (BK / 8);        \
     _Pragma("unroll") for (int i = 0; i < BR; ++i)                                                \
-        bv[S][i] = bok ? b_ptr[i][wt] : make_uint4(0, 0, 0, 0);                                   \
+        bv[S][i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wres, (bok ? (uint32_t)(b_row[i] + wt * 16) : OOB) | dead, 0, 0)); \
     kc += BK;                                                                                     \
-    _Pragma("unroll") for (int t = 0; t < (GROUPED ? 1 : 8); ++t) {                               \
+    if (GROUPED || one_wrap) { /* at least 64 channels per tap: the walk leaves a tap at most once per tile */ \
       const bool wrap = kc >= c_hi;                                                               \
       kc -= wrap ? c_len : 0;                                                                     \
       ks += wrap ? 1 : 0;                                                                         \
       const bool wrap2 = ks == d.kw;                                                              \
       ks = wrap2 ? 0 : ks;                                                                        \
       kr += wrap2 ? 1 : 0;                                                                        \
+    } else {                                                                                      \
+      _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                             \
+        const bool wrap = kc >= c_hi;                                                             \
+        kc -= wrap ? c_len : 0;                                                                   \
+        ks += wrap ? 1 : 0;                                                                       \
+        const bool wrap2 = ks == d.kw;                                                            \
+        ks = wrap2 ? 0 : ks;                                                                      \
+        kr += wrap2 ? 1 : 0;                                                                      \
+      }                                                                                           \
     }                                                                                             \
   }
 
@@ -442,11 +458,12 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     }                                                                                             \
   }
 
-  if (kt0 < ntiles) FI_FETCH(kt0, 0)
+  FI_FETCH(kt0, 0, kt0 < ntiles)
   for (int kt = kt0; kt < ntiles; ++kt) {
     FI_PARK(0)
     __syncthreads();
-    if (kt + 1 < ntiles) FI_FETCH(kt + 1, 0)  // in flight while this tile is multiplied
+    const bool more = kt + 1 < ntiles;
+    FI_FETCH(kt + 1, 0, more)  // in flight while this tile is multiplied (after the last tile: nothing but out-of-range offsets)
     FI_MULTIPLY(0)
     __syncthreads();  // every wave is done with this tile before it is overwritten
   }
