@@ -181,10 +181,10 @@ def main():
                     busy += e - max(b, hi)
                     hi = e
             per_kernel[n]["busy_ms"] += busy / prof_iters
-    dom_name = max((n for n in per_kernel if n.startswith("conv_mfma")), key=lambda n: per_kernel[n]["busy_ms"],
+    dom_name = max((n for n in per_kernel if n.startswith("conv_")), key=lambda n: per_kernel[n]["busy_ms"],
                    default=max(per_kernel, key=lambda n: per_kernel[n]["busy_ms"]))
     dom = per_kernel[dom_name]
-    mfma = [v for n, v in per_kernel.items() if n.startswith("conv_mfma")]
+    mfma = [v for n, v in per_kernel.items() if n.startswith("conv_")]
     mfma_flops = sum(v["flops"] for v in mfma)
     # the roofline that binds this kernel's algorithmic work: matrix cores or HBM
     t_mfma = dom["flops"] / (PEAK_MFMA_BF16 * 1e12)
@@ -321,11 +321,11 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "a822641a28c7af84c49dc2541f622c1ffb2ff41b46e0c4a0246963ab1fc8e828",
+    "sources_sha256": "500cd9d931f8e96156d545a15b5a5dca3f552476cd8aeb87fb6101045c5f500b",
     "workload": "cfg4",
-    "kernel": "conv_mfma_128x128",
-    "launches_per_step": 54,
-    "fetch_kib_per_step": 2891765.2, "write_kib_per_step": 3976448.0,
+    "kernel": "conv_chain3",
+    "launches_per_step": 18,
+    "fetch_kib_per_step": 1338284.1, "write_kib_per_step": 2386496.0,
     "fetch_scale": 2.0, "write_scale": 1.0,
 }
 
@@ -334,7 +334,7 @@ def sources_sha256():
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2410_21120_amd", "csrc")
-    for f in ("fi_internal.h", "fi_plan.cpp", "fi_api.cpp", "fi_kernels.hip"):
+    for f in ("fi_internal.h", "fi_device.h", "fi_plan.cpp", "fi_api.cpp", "fi_kernels.hip", "fi_chain.hip"):
         with open(os.path.join(csrc, f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()
