@@ -467,18 +467,9 @@ static void form_chains(fi_dag* g) {
   }
 }
 
-// Everything derived from the member list: union graph, levels, lanes, kernels and tiles, launch
-// schedule, activation plan, weight arena placement, workspace, descriptors.  Members whose
-// arena_off is already set keep their place in the weight arena (their bytes may be resident);
-// the others go to the lowest gap that holds them.
-static fi_status plan_dag(fi_dag* g) {
-  const fi_build_opts* opts = &g->opts;
+// Planner pass: the disjoint union of the member graphs and every node's depth.
+static void union_member_graphs(fi_dag* g) {
   const int32_t n = (int32_t)g->members.size();
-  g->nodes.clear(); g->launches.clear(); g->descs.clear();
-  g->n_levels = 0; g->macs = 0; g->n_lanes = 1;
-  g->stages.clear();
-  g->wdtype = g->members[0].spec.dtype;
-
   // ---- union of the member graphs (no edge between members) and depth levels --------
   int32_t total = 0;
   for (auto& mb : g->members) { mb.node0 = total; total += (int32_t)mb.plan.nodes.size(); }
@@ -499,6 +490,15 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
+}
+
+// Planner pass: members of one architecture share a lane; large families are halved.
+static void assign_lanes(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  const int32_t total = (int32_t)g->nodes.size();
+  const int B = opts->max_batch;
+  (void)opts; (void)n; (void)total; (void)B;
   // ---- lanes: members whose graphs are identical node for node share launches level by level;
   //      members of different architecture rarely do, so each architecture gets a lane of its
   //      own that runs concurrently with the others (no edge joins two members).  A large family
@@ -543,8 +543,16 @@ static fi_status plan_dag(fi_dag* g) {
     for (Node& nd : g->nodes) nd.lane = g->members[(size_t)nd.model].lane;
   }
 
-  // ---- launch order: by depth, except that the early levels of a lane may run in member chunks --------
+}
+
+// Planner pass: the position of every node in the launch order (its depth, or shifted when early levels run in member chunks).
+static void assign_run_positions(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  const int32_t total = (int32_t)g->nodes.size();
   const int B = opts->max_batch;
+  (void)opts; (void)n; (void)total; (void)B;
+  // ---- launch order: by depth, except that the early levels of a lane may run in member chunks --------
   for (Node& nd : g->nodes) nd.run = nd.level;
   g->n_runs = g->n_levels;
   if (opts->member_chunks >= 2) {
@@ -592,6 +600,15 @@ static fi_status plan_dag(fi_dag* g) {
     g->n_runs = longest;
   }
 
+}
+
+// Planner pass: kernel family, tile and reduction split of every node.
+static fi_status choose_kernels(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  const int32_t total = (int32_t)g->nodes.size();
+  const int B = opts->max_batch;
+  (void)opts; (void)n; (void)total; (void)B;
   // ---- kernel family per node ---------------------------------------------------------
   std::map<std::tuple<int, int, int, int, int, int>, int> same_shape;  // problems of one shape per level
   for (const Node& nd : g->nodes)
@@ -654,11 +671,16 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
-  // ---- nodes that need no launch: concatenations written in place, nodes applied by their reader ----
-  store_concat_sources_in_place(g);
-  fold_nodes_into_readers(g);
-  form_chains(g);
+  return FI_OK;
+}
 
+// Planner pass: staged inputs and the launch list: per position, nodes of one family, tile and storage dtypes share a launch.
+static void build_schedule(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  const int32_t total = (int32_t)g->nodes.size();
+  const int B = opts->max_batch;
+  (void)opts; (void)n; (void)total; (void)B;
   // ---- launch schedule: per level, nodes of one family (and tile, and storage dtypes)
   //      share a launch, FI_MAX_GROUP problems at most --------------------------------------
   // staged inputs: the shared input once per activation dtype, or every member's own input
@@ -773,6 +795,15 @@ static fi_status plan_dag(fi_dag* g) {
   for (const Node& nd : g->nodes)
     if (nd.pre >= 0) { g->nodes[(size_t)nd.pre].launch = nd.launch; g->nodes[(size_t)nd.pre].slot = nd.slot; }
 
+}
+
+// Planner pass: live range of every stored tensor (in launch-order positions), then first fit by size.
+static void plan_activation_arena(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  const int32_t total = (int32_t)g->nodes.size();
+  const int B = opts->max_batch;
+  (void)opts; (void)n; (void)total; (void)B;
   // ---- activation arena: live range of every stored tensor, then first-fit by size -----
   const int32_t n_stage = (int32_t)g->stages.size();
   std::vector<Tensor> tens((size_t)total + (size_t)n_stage);
@@ -844,6 +875,15 @@ static fi_status plan_dag(fi_dag* g) {
   }
   for (int32_t t = 0; t < n_stage; ++t) g->stages[(size_t)t].off = tens[(size_t)(total + t)].off;
 
+}
+
+// Planner pass: members in the weight arena, split-K partials in the workspace, the budget check.
+static fi_status place_weights_and_workspace(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  const int32_t total = (int32_t)g->nodes.size();
+  const int B = opts->max_batch;
+  (void)opts; (void)n; (void)total; (void)B;
   // ---- weight arena: [descriptor table][member 0][member 1]... --------------------------
   size_t n_desc = 0;
   for (Launch& L : g->launches) { L.first_desc = (int32_t)n_desc; n_desc += (size_t)L.n; }
@@ -894,6 +934,17 @@ static fi_status plan_dag(fi_dag* g) {
     return FI_EBUDGET;
   }
 
+  return FI_OK;
+}
+
+// Planner pass: one problem descriptor per launch slot, and the per-launch work accounting.
+static void fill_descriptors(fi_dag* g) {
+  const fi_build_opts* opts = &g->opts;
+  const int32_t n = (int32_t)g->members.size();
+  const int32_t total = (int32_t)g->nodes.size();
+  const int B = opts->max_batch;
+  (void)opts; (void)n; (void)total; (void)B;
+  const Member& m0 = g->members[0];
   // ---- descriptors ---------------------------------------------------------------------
   for (Launch& L : g->launches) {
     if (L.kind == K_STAGE) {
@@ -1013,6 +1064,31 @@ static fi_status plan_dag(fi_dag* g) {
     }
   }
 
+}
+
+// Everything derived from the member list: union graph, levels, lanes, kernels and tiles, launch
+// schedule, activation plan, weight arena placement, workspace, descriptors.  Members whose
+// arena_off is already set keep their place in the weight arena (their bytes may be resident);
+// the others go to the lowest gap that holds them.
+static fi_status plan_dag(fi_dag* g) {
+  g->nodes.clear(); g->launches.clear(); g->descs.clear();
+  g->n_levels = 0; g->macs = 0; g->n_lanes = 1;
+  g->stages.clear();
+  g->wdtype = g->members[0].spec.dtype;
+  union_member_graphs(g);
+  assign_lanes(g);
+  assign_run_positions(g);
+  fi_status st = choose_kernels(g);
+  if (st != FI_OK) return st;
+  // nodes that need no launch of their own: concatenations written in place, nodes applied by their reader, chains
+  store_concat_sources_in_place(g);
+  fold_nodes_into_readers(g);
+  form_chains(g);
+  build_schedule(g);
+  plan_activation_arena(g);
+  st = place_weights_and_workspace(g);
+  if (st != FI_OK) return st;
+  fill_descriptors(g);
   return FI_OK;
 }
 
