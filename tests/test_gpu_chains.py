@@ -96,3 +96,63 @@ def test_member_chunks_keep_every_bit(chunks):
     for i, (a, b) in enumerate(zip(base, serial)):
         assert np.array_equal(a, b), i
     harness.check_against_oracle("resnet50[4] in the last chunk", mem[4][0], mem[4][1], None, x, got[4])
+
+
+def random_chain_model(seed):
+    """A seeded random chain outside the bottleneck pattern (see the test below).  Returns (model, batch, description)."""
+    import random
+    rng = random.Random(9100 + seed)
+    acts = [zoo.NONE, zoo.RELU, zoo.RELU6, zoo.HARDSWISH, zoo.SILU]
+    cin = rng.choice([64, 128, 192, 256])
+    w1 = rng.choice([64, 128])
+    n2 = rng.choice([128, 256, 384, 512])
+    n3 = rng.choice([0, 64, 128])
+    kh, kw_ = rng.choice([(1, 1), (3, 3), (3, 3), (5, 5), (1, 3), (3, 1)])
+    stride = rng.choice([1, 1, 2])
+    same = max(kh, kw_) // 2
+    pad = rng.choice([0, same])
+    h, w = rng.randint(9, 23), rng.randint(9, 23)
+    batch = rng.randint(1, 5)
+    if kh * kw_ * cin >= 1024:   # a long reduction over few pixels would be split over K, and a split convolution heads no chain
+        h, w = rng.randint(33, 47), rng.randint(33, 47)
+        ho, wo = (h + 2 * pad * (kh > 1) - kh) // stride + 1, (w + 2 * pad * (kw_ > 1) - kw_) // stride + 1
+        batch = -(-(130 * 64 // (w1 // 64)) // (ho * wo))
+    m = zoo.Model(f"chain{seed}", "bf16", 16, h, w)
+    x0 = m.add(zoo.CONV, -1, cin=16, cout=cin, k=3, stride=1, pad=1, act=zoo.RELU)
+    x1 = m.add(zoo.CONV, x0, cin=cin, cout=cin, k=1, stride=1, pad=0, act=zoo.RELU)   # the chain's input: an intermediate tensor
+    res = None
+    if pad == same and rng.random() < 0.7:   # a residual of B's shape, one level above the chain: a strided 1x1 projection
+        res = m.add(zoo.CONV, x0, cin=cin, cout=n2, k=1, stride=stride, pad=0, act=zoo.NONE)
+    a = m.add(zoo.CONV, x1, cin=cin, cout=w1, k=kh, kw=(kw_ if kw_ != kh else 0), stride=stride, pad=pad, act=rng.choice(acts))
+    b = m.add(zoo.CONV, a, cin=w1, cout=n2, k=1, stride=1, pad=0, act=rng.choice(acts), **({"residual": res} if res is not None else {}))
+    tail = b
+    if n3:
+        tail = m.add(zoo.CONV, b, cin=n2, cout=n3, k=1, stride=1, pad=0, act=rng.choice(acts))
+    both = m.add(zoo.CONV, tail, cin=(n3 or n2), cout=24, k=3, stride=1, pad=1, act=zoo.NONE)
+    if n3:   # B's output has a second reader, as a block output has in a residual network
+        m.add(zoo.CONV, b, cin=n2, cout=24, k=1, stride=1, pad=0, act=zoo.NONE, residual=both)
+    m.shapes()
+    return m, batch, f"{cin}->{w1} {kh}x{kw_}/{stride} pad {pad}, ->{n2} (residual {res is not None}), ->{n3}, image {h}x{w}, batch {batch}"
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_chains_equal_separate_launches_and_meet_the_oracle(seed):
+    """Seeded random chains outside the bottleneck pattern: first convolutions of every kernel shape (1x1, 3x3, 5x5,
+    rectangular, stride 2, with and without padding), 64 or 128 channels, second convolutions of 128 to 512 channels with
+    and without a residual, with and without a third convolution, every activation, non-square images and batches
+    whose pixel count leaves ragged tiles.  The model output is taken behind further convolutions so that every
+    chained tensor is an intermediate one.  Chained = separate launches, bit for bit; both meet the oracle."""
+    from tests import harness
+    m, batch, what = random_chain_model(seed)
+    blob = gen.make_blob(m, 9200 + seed)
+    x = gen.make_input(9300 + seed, batch, 16, m.in_h, m.in_w, "normal", "bf16")
+    print(f"seed {seed}: {what}", flush=True)
+    fast, names, _ = _run([(m, blob, None)], x)
+    plain, pnames, _ = _run([(m, blob, None)], x, separate_chains=True)
+    assert any(n.startswith("conv_chain") for n in names), names
+    assert not any(n.startswith("conv_chain") for n in pnames)
+    assert np.isfinite(fast[0]).all() and np.array_equal(fast[0], plain[0])
+    ref_f = harness.oracle_nhwc(m, blob, x, False)
+    ref_s = harness.oracle_nhwc(m, blob, x, True)
+    assert harness.rel_l2(fast[0], ref_f) <= 1e-2
+    assert harness.elem_excess(fast[0], ref_s, harness.ELEM_C_BF16) <= 1.0
