@@ -447,6 +447,8 @@ static void form_chains(fi_dag* g) {
     const int32_t bi = readers[(size_t)i][0];
     Node& Bn = g->nodes[(size_t)bi];
     if (!plain_conv(Bn) || !pointwise(Bn) || Bn.level != A.level + 1 || Bn.run != A.run + 1 || Bn.C != A.Co || Bn.Cp != A.Cop || Bn.Co % 128 || Bn.Co > 1024 || Bn.Co != Bn.Cop || Bn.Kp != Bn.Cp) continue;
+    // the chained launch addresses B's rows (and 127 past the last) with 32-bit byte offsets
+    if (((uint64_t)g->opts.max_batch * A.Ho * A.Wo + 128) * (uint64_t)Bn.Cop * 2 >= (1ull << 31)) continue;
     if (Bn.residual >= 0) {
       const Node& R = g->nodes[(size_t)Bn.residual];
       if (R.root >= 0 || R.out_dtype != FI_BF16 || R.Cop != Bn.Cop || Bn.residual == i) continue;

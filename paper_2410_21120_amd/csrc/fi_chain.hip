@@ -50,8 +50,10 @@ __device__ __forceinline__ void runs_to_fragments(const uint32_t (&pk)[4][2], ui
 }
 
 // W1: output channels of A = reduction length of B (64 or 128).  N3: output channels of C (64 or 128), 0 = no C.
+// SMOOTH: some node of the launch has an activation beyond identity / ReLU / ReLU6 (the variant without them keeps
+// its epilogues free of branches).
 // The launch's problems are triples of descriptors: a.d[3p] = A, a.d[3p + 1] = B, a.d[3p + 2] = C.
-template <int W1, int N3>
+template <int W1, int N3, bool SMOOTH>
 __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   constexpr int BM = 128;
   constexpr int NI1 = W1 / 32, NI3 = N3 > 0 ? N3 / 32 : 1;
@@ -132,29 +134,41 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   }
   // What the later phases wait for first is requested before anything else: the first tile of B's weights and the
   // residual rows of B's first chunk (32 rows x 256 bytes per wave, 16 bytes per lane and pass).
-  const uint8_t* __restrict__ res = d2.r_off != kNone ? a.abase + d2.r_off : nullptr;
+  // Residual rows in and output rows out go through buffer resources that end with the tensor's last row: a row past
+  // M reads as zero and is not written, without a branch (the epilogues stay in one basic block each, so that their
+  // LDS reads, loads and stores are issued in batches instead of one wait apiece).
+  const bool has_res = d2.r_off != kNone;
   const int mw = m0 + wave * 32;                                         // first row of this wave
+  const int cop2 = d2.Cop, ys2 = d2.ys;
+  const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(a.abase + (has_res ? d2.r_off : 0)), 0, has_res && M > 0 ? (int)((int64_t)M * cop2 * 2) : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t y2res = __builtin_amdgcn_make_buffer_rsrc(
+      a.abase + d2.y_off, 0, M > 0 ? (int)((((int64_t)M - 1) * ys2 + cop2) * 2) : 0, 0x00020000);
+  // this lane's 16-byte piece of a 128-channel row block: rows (lane >> 4) + 4 it, channels 8 (lane & 15) ..
+  const int prow = lane >> 4, pcol = (lane & 15) * 8;
+  const uint32_t r_off0 = (uint32_t)(((mw + prow) * cop2 + pcol) * 2), r_step = (uint32_t)(4 * cop2 * 2);
+  const uint32_t y_off0 = (uint32_t)(((mw + prow) * ys2 + pcol) * 2), y_step = (uint32_t)(4 * ys2 * 2);
   u32x4 rv[8];
 #define FI_FETCH_RES(CH)                                                                                     \
   {                                                                                                          \
-    _Pragma("unroll") for (int it = 0; it < 8; ++it) {                                                       \
-      const int item = it * 64 + lane, row = item >> 4, col = (item & 15) * 8;                               \
-      rv[it] = u32x4{0, 0, 0, 0};                                                                            \
-      if (mw + row < M) rv[it] = *reinterpret_cast<const u32x4*>(res + ((int64_t)(mw + row) * d2.Cop + (CH) * 128 + col) * 2); \
-    }                                                                                                        \
+    _Pragma("unroll") for (int it = 0; it < 8; ++it)                                                         \
+        rv[it] = __builtin_amdgcn_raw_buffer_load_b128(rres, r_off0 + it * r_step + (CH) * 256, 0, 0);       \
   }
   FI_FETCH_B(w2, W1, 0, 0, 4)
-  {   // the bias vectors into LDS (visible after the first barrier of the first GEMM, long before their first reader)
+  // The bias vectors travel to LDS through registers: every load is requested here, in one batch, and parked after the
+  // first GEMM (one round trip hidden behind it instead of three in a row in front of it).
+  constexpr int NB2 = MAXN2 / 256;
+  float bq1, bq2[NB2], bq3 = 0.0f;
+  {
     const float* g1 = reinterpret_cast<const float*>(a.wbase + d1.b_off);
     const float* g2 = reinterpret_cast<const float*>(a.wbase + d2.b_off);
-    for (int i = tid; i < W1; i += 256) bias1[i] = g1[i];
-    for (int i = tid; i < d2.Co; i += 256) bias2[i] = g2[i];
-    if constexpr (N3 > 0) {
-      const float* g3 = reinterpret_cast<const float*>(a.wbase + d3.b_off);
-      for (int i = tid; i < N3; i += 256) bias3[i] = g3[i];
-    }
+    const int n2 = d2.Co;
+    bq1 = g1[tid < W1 ? tid : 0];
+#pragma unroll
+    for (int i = 0; i < NB2; ++i) bq2[i] = g2[tid + 256 * i < n2 ? tid + 256 * i : 0];
+    if constexpr (N3 > 0) bq3 = reinterpret_cast<const float*>(a.wbase + d3.b_off)[tid < N3 ? tid : 0];
   }
-  if constexpr (W1 == 64) { if (res) FI_FETCH_RES(0) }   // (the wider chains have no registers to spare for it this early)
+  if constexpr (W1 == 64) { if (has_res) FI_FETCH_RES(0) }   // (the wider chains have no registers to spare for it this early)
 
   f32x16 acc1[NI1];
 #pragma unroll
@@ -217,18 +231,24 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
 #undef FI_FETCH_1
   }
 
+  if (tid < W1) bias1[tid] = bq1;
+#pragma unroll
+  for (int i = 0; i < NB2; ++i) bias2[tid + 256 * i] = bq2[i];   // (the table holds MAXN2 entries: rows past B's width are never read)
+  if constexpr (N3 > 0) { if (tid < N3) bias3[tid] = bq3; }
+  __syncthreads();
+
   // ---- A's epilogue in registers: bias, activation, one rounding; then into B's operand slots -------------
   uint32_t t1f[W1 / 16][4];
   {
-    const float* bias = bias1;
+    const Activation<SMOOTH> act1(d1.act);
 #pragma unroll
     for (int j = 0; j < NI1; ++j) {
       uint32_t pk[4][2];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const float4 b = *reinterpret_cast<const float4*>(bias + j * 32 + 8 * g + 4 * lh);
+        const float4 b = *reinterpret_cast<const float4*>(bias1 + j * 32 + 8 * g + 4 * lh);
         float v[4] = {acc1[j][4 * g] + b.x, acc1[j][4 * g + 1] + b.y, acc1[j][4 * g + 2] + b.z, acc1[j][4 * g + 3] + b.w};
-        activate_n<4>(v, d1.act);
+        act1.apply(v);
         pk[g][0] = pack_bf16x2(v[0], v[1]);
         pk[g][1] = pack_bf16x2(v[2], v[3]);
       }
@@ -253,7 +273,7 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   constexpr int WS = 2 * BK + 8;   // (EARLY) row stride of the two tiles parked side by side: 272-byte rows
 
   for (int c = 0; c < nchunks; ++c) {
-    if constexpr (W1 != 64) { if (res) FI_FETCH_RES(c) }   // requested before this chunk's multiplies
+    if constexpr (W1 != 64) { if (has_res) FI_FETCH_RES(c) }   // requested before this chunk's multiplies
     f32x16 acc2[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -289,36 +309,39 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
 
     // B's epilogue.  The residual rows go through the patch to reach the accumulators' layout; the finished rows go
     // through it the other way to leave as contiguous 16-byte pieces.  The patch belongs to this wave alone.
-    if (res) {
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int item = it * 64 + lane, row = item >> 4, col = (item & 15) * 8;
-        *reinterpret_cast<u32x4_a*>(&pt[row * PS + col]) = rv[it];
-      }
-      if constexpr (W1 == 64) { if (c + 1 < nchunks) FI_FETCH_RES(c + 1) }   // the next chunk's rows travel while this chunk is finished
-      wave_lds_fence();
-    }
+    const Activation<SMOOTH> act2(d2.act);
     uint32_t t2f[8][4];
     {
-      const float* bias = bias2 + c * 128;
       uint32_t pk[4][4][2];
+      if (has_res) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) *reinterpret_cast<u32x4_a*>(&pt[(prow + 4 * it) * PS + pcol]) = rv[it];
+        if constexpr (W1 == 64) { if (c + 1 < nchunks) FI_FETCH_RES(c + 1) }   // the next chunk's rows travel while this chunk is finished
+      }
+      wave_lds_fence();
+      // Bias, then the residual, then the activation, then the one rounding: the order of the stand-alone kernel.
+      // One loop for both cases (two copies of it would meet again with every value of the tile alive twice).  Without a
+      // residual the patch holds stale rows: they are read and replaced by -0.0, the one addend that leaves every
+      // value, either zero included, as it is.
+      uint32_t res_and = has_res ? 0xFFFFFFFFu : 0u, res_or = has_res ? 0u : 0x80008000u;
+      asm volatile("" : "+v"(res_and), "+v"(res_or));   // (kept from being turned back into a select per value)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int c0 = j * 32 + 8 * g + 4 * lh;
-          const float4 b = *reinterpret_cast<const float4*>(bias + c0);
+          const float4 b = *reinterpret_cast<const float4*>(bias2 + c * 128 + c0);
+          u32x2 r = *reinterpret_cast<const u32x2_a*>(&pt[lp * PS + c0]);
+          r[0] = (r[0] & res_and) | res_or;
+          r[1] = (r[1] & res_and) | res_or;
           float v[4] = {acc2[j][4 * g] + b.x, acc2[j][4 * g + 1] + b.y, acc2[j][4 * g + 2] + b.z, acc2[j][4 * g + 3] + b.w};
-          if (res) {
-            const u32x2 r = *reinterpret_cast<const u32x2_a*>(&pt[lp * PS + c0]);
-            v[0] += __uint_as_float(r[0] << 16); v[1] += __uint_as_float(r[0] & 0xFFFF0000u);
-            v[2] += __uint_as_float(r[1] << 16); v[3] += __uint_as_float(r[1] & 0xFFFF0000u);
-          }
-          activate_n<4>(v, d2.act);
+          v[0] += __uint_as_float(r[0] << 16); v[1] += __uint_as_float(r[0] & 0xFFFF0000u);
+          v[2] += __uint_as_float(r[1] << 16); v[3] += __uint_as_float(r[1] & 0xFFFF0000u);
+          act2.apply(v);
           pk[j][g][0] = pack_bf16x2(v[0], v[1]);
           pk[j][g][1] = pack_bf16x2(v[2], v[3]);
         }
-      if (res) wave_lds_fence();   // every residual value has been read before the patch is overwritten
+      wave_lds_fence();   // every residual value has been read before the patch is overwritten
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -328,18 +351,22 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
           *reinterpret_cast<u32x2_a*>(&pt[lp * PS + j * 32 + 8 * g + 4 * lh]) = o;
         }
       wave_lds_fence();
-      bf16_t* const y2 = reinterpret_cast<bf16_t*>(a.abase + d2.y_off);
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int item = it * 64 + lane, row = item >> 4, col = (item & 15) * 8;
-        const u32x4 o = *reinterpret_cast<const u32x4_a*>(&pt[row * PS + col]);
-        if (mw + row < M) {
-          u32x4* const yp = reinterpret_cast<u32x4*>(y2 + (int64_t)(mw + row) * d2.ys + c * 128 + col);
-          if (stream_out) __builtin_nontemporal_store(o, yp); else *yp = o;
+      for (int half = 0; half < 2; ++half) {   // four rows' pieces at a time
+        u32x4 orow[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) orow[it] = *reinterpret_cast<const u32x4_a*>(&pt[(prow + 4 * (4 * half + it)) * PS + pcol]);
+        if (stream_out) {
+#pragma unroll
+          for (int it = 0; it < 4; ++it) __builtin_amdgcn_raw_buffer_store_b128(orow[it], y2res, y_off0 + (4 * half + it) * y_step + c * 256, 0, 2);
+        } else {
+#pragma unroll
+          for (int it = 0; it < 4; ++it) __builtin_amdgcn_raw_buffer_store_b128(orow[it], y2res, y_off0 + (4 * half + it) * y_step + c * 256, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
       wave_lds_fence();   // the rows have been read before the next chunk's residual lands in the patch
-      if (N3 > 0) {
+      if constexpr (N3 > 0) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           uint32_t fr[2][4];
@@ -403,28 +430,36 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
 #undef FI_FETCH_RES
 
   // ---- C's epilogue ---------------------------------------------------------------------------------------
-  if (N3 > 0) {
-    const float* bias = bias3;
+  if constexpr (N3 > 0) {
+    const int ys3 = d3.ys;
+    const __amdgpu_buffer_rsrc_t y3res = __builtin_amdgcn_make_buffer_rsrc(
+        a.abase + d3.y_off, 0, M > 0 ? (int)((((int64_t)M - 1) * ys3 + N3) * 2) : 0, 0x00020000);
+    const Activation<SMOOTH> act3(d3.act);
 #pragma unroll
     for (int j = 0; j < NI3; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int c0 = j * 32 + 8 * g + 4 * lh;
-        const float4 b = *reinterpret_cast<const float4*>(bias + c0);
+        const float4 b = *reinterpret_cast<const float4*>(bias3 + c0);
         float v[4] = {acc3[j][4 * g] + b.x, acc3[j][4 * g + 1] + b.y, acc3[j][4 * g + 2] + b.z, acc3[j][4 * g + 3] + b.w};
-        activate_n<4>(v, d3.act);
+        act3.apply(v);
         u32x2 o;
         o[0] = pack_bf16x2(v[0], v[1]); o[1] = pack_bf16x2(v[2], v[3]);
         *reinterpret_cast<u32x2_a*>(&pt[lp * PS + c0]) = o;
       }
     wave_lds_fence();
-    bf16_t* const y3 = reinterpret_cast<bf16_t*>(a.abase + d3.y_off);
-    constexpr int CPR = NI3 * 4;   // 16-byte pieces per row
+    constexpr int CPR = NI3 * 4;          // 16-byte pieces per row
+    constexpr int NIT = 32 * CPR / 64;    // pieces per lane
+    u32x4 orow[NIT];
 #pragma unroll
-    for (int it = 0; it < 32 * CPR / 64; ++it) {
-      const int item = it * 64 + lane, row = item / CPR, col = (item % CPR) * 8;
-      const u32x4 o = *reinterpret_cast<const u32x4_a*>(&pt[row * PS + col]);
-      if (mw + row < M) *reinterpret_cast<u32x4*>(y3 + (int64_t)(mw + row) * d3.ys + col) = o;
+    for (int it = 0; it < NIT; ++it) {
+      const int item = it * 64 + lane;
+      orow[it] = *reinterpret_cast<const u32x4_a*>(&pt[(item / CPR) * PS + (item % CPR) * 8]);
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int item = it * 64 + lane;
+      __builtin_amdgcn_raw_buffer_store_b128(orow[it], y3res, (uint32_t)(((mw + item / CPR) * ys3 + (item % CPR) * 8) * 2), 0, 0);
     }
   }
 }
@@ -466,6 +501,10 @@ int launch_chain(const Launch& L, const KArgs& args, void* stream, const std::ve
     if (d2.k != 1 || d2.kw != 1 || d2.stride != 1 || d2.pad != 0 || d2.pad_w != 0 || d2.C != W1 || d2.Cp != W1 || d2.Kp != W1 || d2.Co != d2.Cop || d2.Co % 128 ||
         d2.Co < 128 || d2.Co > 1024 || d2.splits != 1 || d2.ext || d2.out_f32 || d2.pre_kind != 0 || d2.gin > 0 || d2.Ho != d1.Ho || d2.Wo != d1.Wo || d2.ys < d2.Cop || d2.y_off == kNone)
       return (int)hipErrorInvalidValue;
+    // rows are addressed with 32-bit byte offsets through buffer resources, 127 rows past the last one included
+    const uint64_t rows = (uint64_t)b * d1.Ho * d1.Wo + 128;
+    if (rows * (uint64_t)d2.ys * 2 >= (1ull << 31) || rows * (uint64_t)d2.Cop * 2 >= (1ull << 31) || (has_c && rows * (uint64_t)d3.ys * 2 >= (1ull << 31)))
+      return (int)hipErrorInvalidValue;
     if (has_c) {   // C: pointwise on the same pixels, B's channels -> N3
       if (d3.k != 1 || d3.kw != 1 || d3.stride != 1 || d3.pad != 0 || d3.pad_w != 0 || d3.C != d2.Co || d3.Cp != d2.Co || d3.Kp != d2.Co || d3.Co != N3 ||
           d3.Cop != N3 || (N3 != 64 && N3 != 128) || d3.splits != 1 || d3.ext || d3.out_f32 || d3.pre_kind != 0 || d3.gin > 0 || d3.r_off != kNone ||
@@ -479,12 +518,19 @@ int launch_chain(const Launch& L, const KArgs& args, void* stream, const std::ve
   for (int p = P; p <= FI_MAX_GROUP; ++p) a.first_block[p] = (int32_t)blocks;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int nb = (int)blocks;
-  if (W1 == 64 && N3 == 0) return go_chain(chain_mfma_kernel<64, 0>, nb, a, s);
-  if (W1 == 64 && N3 == 64) return go_chain(chain_mfma_kernel<64, 64>, nb, a, s);
-  if (W1 == 64 && N3 == 128) return go_chain(chain_mfma_kernel<64, 128>, nb, a, s);
-  if (W1 == 128 && N3 == 0) return go_chain(chain_mfma_kernel<128, 0>, nb, a, s);
-  if (W1 == 128 && N3 == 64) return go_chain(chain_mfma_kernel<128, 64>, nb, a, s);
-  if (W1 == 128 && N3 == 128) return go_chain(chain_mfma_kernel<128, 128>, nb, a, s);
+  bool smooth = false;
+  for (int p = 0; p < P; ++p)
+    for (int t = 0; t < (has_c ? 3 : 2); ++t) smooth = smooth || a.d[3 * p + t].act > FI_ACT_RELU6;
+#define FI_CHAIN_CASE(A, C)                                                                          \
+  if (W1 == (A) && N3 == (C))                                                                        \
+    return smooth ? go_chain(chain_mfma_kernel<A, C, true>, nb, a, s) : go_chain(chain_mfma_kernel<A, C, false>, nb, a, s);
+  FI_CHAIN_CASE(64, 0)
+  FI_CHAIN_CASE(64, 64)
+  FI_CHAIN_CASE(64, 128)
+  FI_CHAIN_CASE(128, 0)
+  FI_CHAIN_CASE(128, 64)
+  FI_CHAIN_CASE(128, 128)
+#undef FI_CHAIN_CASE
   return (int)hipErrorInvalidValue;
 }
 

@@ -21,23 +21,33 @@ __device__ __forceinline__ void st(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
 
 // ReLU / ReLU6 / identity as branch-free selects (the common case), the smooth activations behind ONE
-// block-uniform branch per call: `act` is the same for every lane of a problem.
-__device__ __forceinline__ float activate_smooth(float v, int act) {
-  if (act == FI_ACT_HARDSWISH) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
-  if (act == FI_ACT_HARDSIGMOID) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
-  const float sg = 1.0f / (1.0f + expf(-v));
-  return act == FI_ACT_SILU ? v * sg : sg;
-}
+// block-uniform branch per call, taken around the whole run of values: `act` is the same for every lane of a
+// problem, and a caller that hands over everything it holds in one call keeps its epilogue in one basic block.
+__device__ __forceinline__ float act_hardswish(float v) { return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f; }
+__device__ __forceinline__ float act_hardsigmoid(float v) { return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f; }
+__device__ __forceinline__ float act_sigmoid(float v) { return 1.0f / (1.0f + expf(-v)); }
 template <int N>
 __device__ __forceinline__ void activate_n(float* v, int act) {
-  if (__builtin_amdgcn_readfirstlane(act) > FI_ACT_RELU6) {
+  const int a = __builtin_amdgcn_readfirstlane(act);
+  if (a > FI_ACT_RELU6) {
+    if (a == FI_ACT_HARDSWISH) {
 #pragma unroll
-    for (int t = 0; t < N; ++t) v[t] = activate_smooth(v[t], act);
+      for (int t = 0; t < N; ++t) v[t] = act_hardswish(v[t]);
+    } else if (a == FI_ACT_HARDSIGMOID) {
+#pragma unroll
+      for (int t = 0; t < N; ++t) v[t] = act_hardsigmoid(v[t]);
+    } else if (a == FI_ACT_SILU) {
+#pragma unroll
+      for (int t = 0; t < N; ++t) v[t] = v[t] * act_sigmoid(v[t]);
+    } else {
+#pragma unroll
+      for (int t = 0; t < N; ++t) v[t] = act_sigmoid(v[t]);
+    }
     return;
   }
-  const float hi = act == FI_ACT_RELU6 ? 6.0f : INFINITY;
+  const float hi = a == FI_ACT_RELU6 ? 6.0f : INFINITY;
 #pragma unroll
-  for (int t = 0; t < N; ++t) v[t] = act == FI_ACT_NONE ? v[t] : fminf(fmaxf(v[t], 0.0f), hi);
+  for (int t = 0; t < N; ++t) v[t] = a == FI_ACT_NONE ? v[t] : fminf(fmaxf(v[t], 0.0f), hi);
 }
 __device__ __forceinline__ float activate(float v, int act) {
   activate_n<1>(&v, act);
@@ -57,6 +67,34 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+
+// The activation of one node, set up once per epilogue and applied to four values at a time.  A kernel variant whose
+// launches hold no smooth activation (SMOOTH = false) applies identity / ReLU / ReLU6 in two instructions a value and
+// has no branch: a bound that is NaN drops out of max / min (they return the other operand), so identity is
+// max(v, NaN), min(., NaN) and ReLU is max(v, 0), min(., NaN): the values activate_n selects, bit for bit.  (The
+// bounds pass through an empty asm so that the optimiser, which knows max(v, NaN) = v, does not turn the two
+// instructions back into selects.)  The general variant branches once per call.
+template <bool SMOOTH>
+struct Activation {
+  int act;
+  float lo, hi;
+  __device__ __forceinline__ explicit Activation(int a) : act(a), lo(0.0f), hi(0.0f) {
+    if constexpr (!SMOOTH) {
+      uint32_t lo_b = a == FI_ACT_NONE ? 0x7FC00000u : 0u, hi_b = a == FI_ACT_RELU6 ? 0x40C00000u : 0x7FC00000u;
+      asm volatile("" : "+v"(lo_b), "+v"(hi_b));
+      lo = __uint_as_float(lo_b);
+      hi = __uint_as_float(hi_b);
+    }
+  }
+  __device__ __forceinline__ void apply(float (&v)[4]) const {
+    if constexpr (SMOOTH) {
+      activate_n<4>(v, act);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] = fminf(fmaxf(v[t], lo), hi);
+    }
+  }
+};
 
 constexpr int BK = 64;
 constexpr int LDS_STRIDE = BK + 8;  // elements; 144-byte rows keep 16-byte reads conflict-free

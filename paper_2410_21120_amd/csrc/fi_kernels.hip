@@ -474,6 +474,39 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // Two epilogues.  Long reductions (the 256-row tile) drain wave by wave without workgroup
   // barriers; streaming tiles go through one workgroup-wide fp32 tile so that a row of BN
   // channels leaves as one contiguous run (wider HBM bursts matter more there).
+  // The common case has a path of its own, chosen once: bf16 output into the arena, every stored channel a real one,
+  // no split, identity / ReLU / ReLU6.  Residual rows come in and output rows leave through buffer resources that end
+  // with the tensor's last row, so a row past M or a column past Cop takes an out-of-range offset instead of a
+  // branch, the activation is two instructions a value, and each block of rows is finished in one basic block (its
+  // LDS reads, loads and stores issued in batches).  Everything else takes the general path below it.
+  bool fast = false;
+  if constexpr (!WIDE)
+    fast = d.splits == 1 && !d.ext && !d.out_f32 && d.Co == d.Cop && d.act <= FI_ACT_RELU6 &&
+           ((int64_t)M + BM) * d.ys * 2 < (1ll << 31) && ((int64_t)M + BM) * d.Cop * 2 < (1ll << 31);
+  const bool has_res = d.r_off != kNone;
+  const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(a.abase + (fast && has_res ? d.r_off : 0)), 0, fast && has_res && M > 0 ? (int)((int64_t)M * d.Cop * 2) : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
+      a.abase + (fast ? d.y_off : 0), 0, fast && M > 0 ? (int)((((int64_t)M - 1) * d.ys + d.Cop) * 2) : 0, 0x00020000);
+  // without a residual the loads return zero and the addend becomes -0.0, which leaves every value as it is
+  uint32_t res_and = has_res ? 0xFFFFFFFFu : 0u, res_or = has_res ? 0u : 0x80008000u;
+  asm volatile("" : "+v"(res_and), "+v"(res_or));   // (kept from being turned into a select per value)
+  // bias + residual + activation + the one rounding for 8 consecutive channels of one row
+#define FI_FINISH_8(V0, V1, R, PK)                                                                \
+  {                                                                                               \
+    float va[4] = {(V0).x + bias8[0], (V0).y + bias8[1], (V0).z + bias8[2], (V0).w + bias8[3]};   \
+    float vb[4] = {(V1).x + bias8[4], (V1).y + bias8[5], (V1).z + bias8[6], (V1).w + bias8[7]};   \
+    const uint32_t r0 = ((R)[0] & res_and) | res_or, r1 = ((R)[1] & res_and) | res_or;            \
+    const uint32_t r2 = ((R)[2] & res_and) | res_or, r3 = ((R)[3] & res_and) | res_or;            \
+    va[0] += __uint_as_float(r0 << 16); va[1] += __uint_as_float(r0 & 0xFFFF0000u);               \
+    va[2] += __uint_as_float(r1 << 16); va[3] += __uint_as_float(r1 & 0xFFFF0000u);               \
+    vb[0] += __uint_as_float(r2 << 16); vb[1] += __uint_as_float(r2 & 0xFFFF0000u);               \
+    vb[2] += __uint_as_float(r3 << 16); vb[3] += __uint_as_float(r3 & 0xFFFF0000u);               \
+    clamp.apply(va);                                                                              \
+    clamp.apply(vb);                                                                              \
+    (PK)[0] = pack_bf16x2(va[0], va[1]); (PK)[1] = pack_bf16x2(va[2], va[3]);                     \
+    (PK)[2] = pack_bf16x2(vb[0], vb[1]); (PK)[3] = pack_bf16x2(vb[2], vb[3]);                     \
+  }
   if constexpr (BM == 256) {
     // ---- epilogue: every wave transposes its own sub-tile through a private LDS patch -----------
     // (no workgroup barrier: waves drain independently, one 32-row MFMA block at a time).  With the
@@ -500,6 +533,43 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
     }
     const uint8_t* __restrict__ res = d.r_off != kNone ? a.abase + d.r_off : nullptr;
+    if (fast) {
+      const Activation<false> clamp(d.act);
+      const uint32_t col_dead = col_ok ? 0u : OOB;
+  #pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const int mb = m0 + wm * WTM + i * 32;
+        u32x4 rq[CH], pk[CH];
+  #pragma unroll
+        for (int ch = 0; ch < CH; ++ch)
+          rq[ch] = __builtin_amdgcn_raw_buffer_load_b128(rres, (uint32_t)(((mb + lr0 + ch * RSTEP) * d.Cop + o) * 2) | col_dead, 0, 0);
+  #pragma unroll
+        for (int j = 0; j < NI; ++j)
+  #pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<float4*>(&ep[(lane & 31) * EPS + j * 32 + 8 * g + 4 * (lane >> 5)]) =
+                make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  #pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+          const int lr = lr0 + ch * RSTEP;
+          const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
+          const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
+          FI_FINISH_8(v0, v1, rq[ch], pk[ch])
+        }
+        if (stream_out) {
+  #pragma unroll
+          for (int ch = 0; ch < CH; ++ch)
+            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mb + lr0 + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 2);
+        } else {
+  #pragma unroll
+          for (int ch = 0; ch < CH; ++ch)
+            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mb + lr0 + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+      return;
+    }
   #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int mb = m0 + wm * WTM + i * 32;  // first output row of this MFMA block
@@ -593,6 +663,49 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
     }
     const uint8_t* __restrict__ res = d.r_off != kNone ? a.abase + d.r_off : nullptr;
+    if (fast) {
+      const Activation<false> clamp(d.act);
+      const uint32_t col_dead = col_ok ? 0u : OOB;
+  #pragma unroll
+      for (int pass = 0; pass < BM / 64; ++pass) {
+        const int mp = m0 + pass * 64 + lr0;
+        u32x4 rq[CH], pk[CH];
+  #pragma unroll
+        for (int ch = 0; ch < CH; ++ch)
+          rq[ch] = __builtin_amdgcn_raw_buffer_load_b128(rres, (uint32_t)(((mp + ch * RSTEP) * d.Cop + o) * 2) | col_dead, 0, 0);
+        if (pass > 0) __syncthreads();
+  #pragma unroll
+        for (int i = 0; i < MI; ++i) {
+          const int rb = wm * WTM + i * 32;
+          if (rb / 64 != pass) continue;
+          const int lr = rb - pass * 64 + (lane & 31);
+  #pragma unroll
+          for (int j = 0; j < NI; ++j)
+  #pragma unroll
+            for (int g = 0; g < 4; ++g)
+              *reinterpret_cast<float4*>(&ep[lr * EPS + wn * WTN + j * 32 + 8 * g + 4 * (lane >> 5)]) =
+                  make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        }
+        __syncthreads();
+  #pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+          const int lr = lr0 + ch * RSTEP;
+          const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
+          const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
+          FI_FINISH_8(v0, v1, rq[ch], pk[ch])
+        }
+        if (stream_out) {
+  #pragma unroll
+          for (int ch = 0; ch < CH; ++ch)
+            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mp + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 2);
+        } else {
+  #pragma unroll
+          for (int ch = 0; ch < CH; ++ch)
+            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mp + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 0);
+        }
+      }
+      return;
+    }
   #pragma unroll
     for (int pass = 0; pass < BM / 64; ++pass) {
       uint4 rv[CH][AV];
@@ -670,6 +783,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       }
     }
   }
+#undef FI_FINISH_8
 }
 
 // ---------------------------------------------------------------------------------
