@@ -106,9 +106,7 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
       const int pp = t - n * d1.Ho;
       const int ih0 = pp * d1.stride - d1.pad, iw0 = q * d1.stride - d1.pad_w;
       a_row[i] = ((n * d1.H + ih0) * Wd + iw0) * Cp * 2;
-      int rc = 0;
-      for (int r = 0; r < d1.k; ++r) rc |= ((unsigned)(ih0 + r) < (unsigned)d1.H) ? (1 << r) : 0;
-      for (int r = 0; r < kw; ++r) rc |= ((unsigned)(iw0 + r) < (unsigned)Wd) ? (65536 << r) : 0;
+      const int rc = (int)(taps_inside(ih0, d1.k, d1.H) | (taps_inside(iw0, kw, Wd) << 16));
       a_rc[i] = ok ? rc : 0;   // rows past M read as zero
     }
   }
@@ -149,11 +147,17 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   const uint32_t r_off0 = (uint32_t)(((mw + prow) * cop2 + pcol) * 2), r_step = (uint32_t)(4 * cop2 * 2);
   const uint32_t y_off0 = (uint32_t)(((mw + prow) * ys2 + pcol) * 2), y_step = (uint32_t)(4 * ys2 * 2);
   u32x4 rv[8];
-#define FI_FETCH_RES(CH)                                                                                     \
+#define FI_FETCH_RES_PART(CH, IT0, IT1)                                                                      \
   {                                                                                                          \
-    _Pragma("unroll") for (int it = 0; it < 8; ++it)                                                         \
+    _Pragma("unroll") for (int it = (IT0); it < (IT1); ++it)                                                 \
         rv[it] = __builtin_amdgcn_raw_buffer_load_b128(rres, r_off0 + it * r_step + (CH) * 256, 0, 0);       \
   }
+#define FI_FETCH_RES(CH) FI_FETCH_RES_PART(CH, 0, 8)
+  // The chains whose third convolution has 128 channels have no registers for a whole residual block next to B's
+  // accumulators: RV_EARLY of its eight vectors travel ahead (during B's multiplies, or from the chunk before), the rest
+  // is requested when the multiplies are done.  (A request for all eight the register allocator answers with spills,
+  // and a spilled load is waited for on the spot, one after the other.)
+  constexpr int RV_EARLY = N3 == 128 ? (W1 == 128 ? 4 : 7) : 8;
   FI_FETCH_B(w2, W1, 0, 0, 4)
   // The bias vectors travel to LDS through registers: every load is requested here, in one batch, and parked after the
   // first GEMM (one round trip hidden behind it instead of three in a row in front of it).
@@ -168,7 +172,8 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
     for (int i = 0; i < NB2; ++i) bq2[i] = g2[tid + 256 * i < n2 ? tid + 256 * i : 0];
     if constexpr (N3 > 0) bq3 = reinterpret_cast<const float*>(a.wbase + d3.b_off)[tid < N3 ? tid : 0];
   }
-  if constexpr (W1 == 64) { if (has_res) FI_FETCH_RES(0) }   // (the wider chains have no registers to spare for it this early)
+  constexpr bool AHEAD = W1 == 64 || N3 == 0;   // the next chunk's residual is requested while this chunk is finished
+  if constexpr (AHEAD) { if (has_res) FI_FETCH_RES_PART(0, 0, RV_EARLY) }   // (the wider chains have no registers to spare for it this early)
 
   f32x16 acc1[NI1];
 #pragma unroll
@@ -273,7 +278,6 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
   constexpr int WS = 2 * BK + 8;   // (EARLY) row stride of the two tiles parked side by side: 272-byte rows
 
   for (int c = 0; c < nchunks; ++c) {
-    if constexpr (W1 != 64) { if (has_res) FI_FETCH_RES(c) }   // requested before this chunk's multiplies
     f32x16 acc2[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -291,6 +295,9 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
       } else if (kt + 1 < KT2) FI_FETCH_B(w2, W1, c * 128, (kt + 1) * BK, 4)
       else if (N3 > 0) FI_FETCH_B(w3, Kp3, 0, c * 128, NI3)
       else if (c + 1 < nchunks) FI_FETCH_B(w2, W1, (c + 1) * 128, 0, 4)
+      // (memory answers a wave in the order of its requests: the residual rows are asked for after the last weight
+      // tile that is parked before they are needed, so that no wait for weights stands behind them)
+      if constexpr (!AHEAD) { if (kt == KT2 - 1 && has_res) FI_FETCH_RES_PART(c, 0, RV_EARLY) }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const int kof = ks * 16 + lh * 8;
@@ -313,10 +320,11 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
     uint32_t t2f[8][4];
     {
       uint32_t pk[4][4][2];
+      if constexpr (RV_EARLY < 8) { if (has_res) FI_FETCH_RES_PART(c, RV_EARLY, 8) }
       if (has_res) {
 #pragma unroll
         for (int it = 0; it < 8; ++it) *reinterpret_cast<u32x4_a*>(&pt[(prow + 4 * it) * PS + pcol]) = rv[it];
-        if constexpr (W1 == 64) { if (c + 1 < nchunks) FI_FETCH_RES(c + 1) }   // the next chunk's rows travel while this chunk is finished
+        if constexpr (AHEAD) { if (c + 1 < nchunks) FI_FETCH_RES_PART(c + 1, 0, RV_EARLY) }   // the next chunk's rows travel while this chunk is finished
       }
       wave_lds_fence();
       // Bias, then the residual, then the activation, then the one rounding: the order of the stand-alone kernel.
@@ -428,6 +436,7 @@ __global__ void __launch_bounds__(256, 2) chain_mfma_kernel(KArgs a) {
 #undef FI_FETCH_B
 #undef FI_PARK_B
 #undef FI_FETCH_RES
+#undef FI_FETCH_RES_PART
 
   // ---- C's epilogue ---------------------------------------------------------------------------------------
   if constexpr (N3 > 0) {

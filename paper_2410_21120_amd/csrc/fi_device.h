@@ -113,6 +113,14 @@ __device__ __forceinline__ int fast_div(int m, int dv, float inv) {
   return t;
 }
 
+// Which taps of a filter row / column land inside the image, as a bit mask: bit r is set iff 0 <= origin + r < extent
+// (r < taps <= 15).  The valid taps are a run, so two shifts replace a loop over the taps.
+__device__ __forceinline__ uint32_t taps_inside(int origin, int taps, int extent) {
+  const int lo = origin < 0 ? -origin : 0;
+  const int hi = extent - origin < taps ? extent - origin : taps;
+  return hi > lo ? ((1u << hi) - 1u) & ~((1u << lo) - 1u) : 0u;
+}
+
 __device__ __forceinline__ int xcd_contiguous(int bid, int total) {
   const int c = total / NXCD, r = total % NXCD;
   const int x = bid % NXCD, j = bid / NXCD;

@@ -249,9 +249,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     const int pp = t - n * d.Ho;
     const int ih0 = pp * d.stride - d.pad, iw0 = q * d.stride - d.pad_w;
     a_row[i] = ((n * d.H + ih0) * d.W + iw0) * d.Cp * AE;
-    int rc = 0;
-    for (int r = 0; r < d.k; ++r) rc |= ((unsigned)(ih0 + r) < (unsigned)d.H) ? (1 << r) : 0;
-    for (int r = 0; r < d.kw; ++r) rc |= ((unsigned)(iw0 + r) < (unsigned)d.W) ? (65536 << r) : 0;
+    const int rc = (int)(taps_inside(ih0, d.k, d.H) | (taps_inside(iw0, d.kw, d.W) << 16));
     a_rc[i] = ok ? rc : 0;  // rows past M read as zero
   }
   // Weights through a buffer resource as well: a vector that must read as zero (the half tile that ends a row padded
