@@ -160,8 +160,11 @@ def main():
     launches = dag.launches()
     prof_iters = max(3, min(10, a.steps))
     per_kernel = {}
+    def kname(L):   # one name per kernel template: the chains of two and of three are one kernel (chain_mfma_kernel)
+        n = L.name.decode()
+        return "conv_chain" if n.startswith("conv_chain") else n
     for L in launches:
-        k = per_kernel.setdefault(L.name.decode(), dict(launches=0, ms=0.0, busy_ms=0.0, flops=0.0, bytes=0.0))
+        k = per_kernel.setdefault(kname(L), dict(launches=0, ms=0.0, busy_ms=0.0, flops=0.0, bytes=0.0))
         k["launches"] += 1
         k["flops"] += 2.0 * L.macs_per_image * B
         k["bytes"] += float(L.bytes_per_image) * B + L.weight_bytes
@@ -171,8 +174,8 @@ def main():
         spans = {}
         for i, (L, b, e) in enumerate(zip(launches, tb, te)):
             per_launch_span[i] += (e - b) / prof_iters
-            per_kernel[L.name.decode()]["ms"] += (e - b) / prof_iters
-            spans.setdefault(L.name.decode(), []).append((b, e))
+            per_kernel[kname(L)]["ms"] += (e - b) / prof_iters
+            spans.setdefault(kname(L), []).append((b, e))
         for n, iv in spans.items():
             iv.sort()
             busy, hi = 0.0, -1.0
@@ -321,12 +324,15 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "cefa98bf6dd0678f00932654556d356c01f86d358e0ad3f97d149e038328fe14",
+    "sources_sha256": "ac49af41b704dc7824daa47ef1c810337fb430ccb353733d11ff1a2304d81581",
     "workload": "cfg4",
-    "kernel": "conv_chain3",
-    "launches_per_step": 18,
-    "fetch_kib_per_step": 1338284.1, "write_kib_per_step": 2386496.0,
     "fetch_scale": 2.0, "write_scale": 1.0,
+    "kernels": {   # kernel name -> launches and KiB per step
+        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454401.6, "write_kib_per_step": 2579458.8},
+        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1091708.4, "write_kib_per_step": 1618210.6},
+        "conv_mfma_128x64": {"launches_per_step": 8, "fetch_kib_per_step": 101594.9, "write_kib_per_step": 501760.0},
+        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613625.0, "write_kib_per_step": 376320.0},
+    },
 }
 
 
@@ -342,11 +348,12 @@ def sources_sha256():
 
 def counter_traffic(kernel, workload):
     c = COUNTERS
-    if not c["sources_sha256"] or c["kernel"] != kernel or c["workload"] != workload or c["sources_sha256"] != sources_sha256():
+    k = c["kernels"].get(kernel)
+    if not c["sources_sha256"] or k is None or c["workload"] != workload or c["sources_sha256"] != sources_sha256():
         return None
-    per_launch = (c["fetch_kib_per_step"] * c["fetch_scale"] + c["write_kib_per_step"] * c["write_scale"]) * 1024.0 / c["launches_per_step"]
-    return dict(bytes_per_launch=per_launch, fetch_bytes_per_launch=c["fetch_kib_per_step"] * c["fetch_scale"] * 1024.0 / c["launches_per_step"],
-                write_bytes_per_launch=c["write_kib_per_step"] * c["write_scale"] * 1024.0 / c["launches_per_step"],
+    n = k["launches_per_step"]
+    fetch, write = k["fetch_kib_per_step"] * c["fetch_scale"] * 1024.0 / n, k["write_kib_per_step"] * c["write_scale"] * 1024.0 / n
+    return dict(bytes_per_launch=fetch + write, fetch_bytes_per_launch=fetch, write_bytes_per_launch=write,
                 source="a stored rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of these exact sources (not measured in this run), "
                        "scaled by a 1 GiB copy probe")
 
