@@ -477,34 +477,76 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   // with the tensor's last row, so a row past M or a column past Cop takes an out-of-range offset instead of a
   // branch, the activation is two instructions a value, and each block of rows is finished in one basic block (its
   // LDS reads, loads and stores issued in batches).  Everything else takes the general path below it.
-  bool fast = false;
-  if constexpr (!WIDE)
-    fast = d.splits == 1 && !d.ext && !d.out_f32 && d.Co == d.Cop && d.act <= FI_ACT_RELU6 &&
-           ((int64_t)M + BM) * d.ys * 2 < (1ll << 31) && ((int64_t)M + BM) * d.Cop * 2 < (1ll << 31);
+  // (members with fp32-stored activations take it too: fp32 residual rows in, fp32 rows out, two 16-byte pieces per 8 channels)
+  const bool fast = d.splits == 1 && !d.ext && (WIDE || !d.out_f32) && d.Co == d.Cop &&
+                    ((int64_t)M + BM) * d.ys * AE < (1ll << 31) && ((int64_t)M + BM) * d.Cop * AE < (1ll << 31);
   const bool has_res = d.r_off != kNone;
   const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(a.abase + (fast && has_res ? d.r_off : 0)), 0, fast && has_res && M > 0 ? (int)((int64_t)M * d.Cop * 2) : 0, 0x00020000);
+      const_cast<uint8_t*>(a.abase + (fast && has_res ? d.r_off : 0)), 0, fast && has_res && M > 0 ? (int)((int64_t)M * d.Cop * AE) : 0, 0x00020000);
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
-      a.abase + (fast ? d.y_off : 0), 0, fast && M > 0 ? (int)((((int64_t)M - 1) * d.ys + d.Cop) * 2) : 0, 0x00020000);
+      a.abase + (fast ? d.y_off : 0), 0, fast && M > 0 ? (int)((((int64_t)M - 1) * d.ys + d.Cop) * AE) : 0, 0x00020000);
   // without a residual the loads return zero and the addend becomes -0.0, which leaves every value as it is
   uint32_t res_and = has_res ? 0xFFFFFFFFu : 0u, res_or = has_res ? 0u : 0x80008000u;
   asm volatile("" : "+v"(res_and), "+v"(res_or));   // (kept from being turned into a select per value)
   // bias + residual + activation + the one rounding for 8 consecutive channels of one row
-#define FI_FINISH_8(V0, V1, R, PK)                                                                \
+#define FI_SUM_8(V0, V1, R, VA, VB)                                                               \
   {                                                                                               \
-    float va[4] = {(V0).x + bias8[0], (V0).y + bias8[1], (V0).z + bias8[2], (V0).w + bias8[3]};   \
-    float vb[4] = {(V1).x + bias8[4], (V1).y + bias8[5], (V1).z + bias8[6], (V1).w + bias8[7]};   \
-    const uint32_t r0 = ((R)[0] & res_and) | res_or, r1 = ((R)[1] & res_and) | res_or;            \
-    const uint32_t r2 = ((R)[2] & res_and) | res_or, r3 = ((R)[3] & res_and) | res_or;            \
-    va[0] += __uint_as_float(r0 << 16); va[1] += __uint_as_float(r0 & 0xFFFF0000u);               \
-    va[2] += __uint_as_float(r1 << 16); va[3] += __uint_as_float(r1 & 0xFFFF0000u);               \
-    vb[0] += __uint_as_float(r2 << 16); vb[1] += __uint_as_float(r2 & 0xFFFF0000u);               \
-    vb[2] += __uint_as_float(r3 << 16); vb[3] += __uint_as_float(r3 & 0xFFFF0000u);               \
-    clamp.apply(va);                                                                              \
-    clamp.apply(vb);                                                                              \
-    (PK)[0] = pack_bf16x2(va[0], va[1]); (PK)[1] = pack_bf16x2(va[2], va[3]);                     \
-    (PK)[2] = pack_bf16x2(vb[0], vb[1]); (PK)[3] = pack_bf16x2(vb[2], vb[3]);                     \
+    (VA)[0] = (V0).x + bias8[0]; (VA)[1] = (V0).y + bias8[1]; (VA)[2] = (V0).z + bias8[2]; (VA)[3] = (V0).w + bias8[3]; \
+    (VB)[0] = (V1).x + bias8[4]; (VB)[1] = (V1).y + bias8[5]; (VB)[2] = (V1).z + bias8[6]; (VB)[3] = (V1).w + bias8[7]; \
+    if constexpr (WIDE) { /* fp32 residual; none reads as +0.0, as on the general path */          \
+      _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+        (VA)[t] += __uint_as_float((R)[0][t]);                                                    \
+        (VB)[t] += __uint_as_float((R)[AV - 1][t]);                                               \
+      }                                                                                           \
+    } else {                                                                                      \
+      const uint32_t r0 = ((R)[0][0] & res_and) | res_or, r1 = ((R)[0][1] & res_and) | res_or;    \
+      const uint32_t r2 = ((R)[0][2] & res_and) | res_or, r3 = ((R)[0][3] & res_and) | res_or;    \
+      (VA)[0] += __uint_as_float(r0 << 16); (VA)[1] += __uint_as_float(r0 & 0xFFFF0000u);         \
+      (VA)[2] += __uint_as_float(r1 << 16); (VA)[3] += __uint_as_float(r1 & 0xFFFF0000u);         \
+      (VB)[0] += __uint_as_float(r2 << 16); (VB)[1] += __uint_as_float(r2 & 0xFFFF0000u);         \
+      (VB)[2] += __uint_as_float(r3 << 16); (VB)[3] += __uint_as_float(r3 & 0xFFFF0000u);         \
+    }                                                                                             \
   }
+#define FI_PACK_8(VA, VB, PK)                                                                     \
+  {                                                                                               \
+    if constexpr (WIDE) {                                                                         \
+      _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+        (PK)[0][t] = __float_as_uint((VA)[t]);                                                    \
+        (PK)[AV - 1][t] = __float_as_uint((VB)[t]);                                               \
+      }                                                                                           \
+    } else {                                                                                      \
+      (PK)[0][0] = pack_bf16x2((VA)[0], (VA)[1]); (PK)[0][1] = pack_bf16x2((VA)[2], (VA)[3]);     \
+      (PK)[0][2] = pack_bf16x2((VB)[0], (VB)[1]); (PK)[0][3] = pack_bf16x2((VB)[2], (VB)[3]);     \
+    }                                                                                             \
+  }
+  // a row's 8 channels: residual pieces in, finished pieces out (one 16-byte piece for bf16, two for fp32)
+#define FI_LOAD_RES(RQ, ROW)                                                                      \
+  _Pragma("unroll") for (int h = 0; h < AV; ++h)                                                  \
+      (RQ)[h] = __builtin_amdgcn_raw_buffer_load_b128(rres, ((uint32_t)(((ROW) * d.Cop + o) * AE) + 16 * h) | col_dead, 0, 0);
+#define FI_STORE_ROW(PK, ROW, AUX)                                                                \
+  _Pragma("unroll") for (int h = 0; h < AV; ++h)                                                  \
+      __builtin_amdgcn_raw_buffer_store_b128((PK)[h], yres, ((uint32_t)(((ROW) * d.ys + o) * AE) + 16 * h) | col_dead, 0, AUX);
+  // The rows of one block: sums for every chunk, the activation (identity / ReLU / ReLU6 as two instructions a value;
+  // a smooth one behind ONE branch for everything the thread holds of the block), the one rounding.  READ(ch, v0, v1)
+  // fetches chunk ch of the block from the LDS tile.
+#define FI_FINISH_BLOCK(RQ, PK, READ)                                                             \
+  {                                                                                               \
+    float vs[CH][8];                                                                              \
+    _Pragma("unroll") for (int ch = 0; ch < CH; ++ch) {                                           \
+      float4 v0, v1;                                                                              \
+      READ(ch, v0, v1)                                                                            \
+      float va[4], vb[4];                                                                         \
+      FI_SUM_8(v0, v1, (RQ)[ch], va, vb)                                                          \
+      if (!smooth) { clamp.apply(va); clamp.apply(vb); }                                          \
+      _Pragma("unroll") for (int t = 0; t < 4; ++t) { vs[ch][t] = va[t]; vs[ch][4 + t] = vb[t]; } \
+    }                                                                                             \
+    if (smooth) activate_n<CH * 8>(&vs[0][0], d.act);                                             \
+    _Pragma("unroll") for (int ch = 0; ch < CH; ++ch) {                                           \
+      float va[4] = {vs[ch][0], vs[ch][1], vs[ch][2], vs[ch][3]}, vb[4] = {vs[ch][4], vs[ch][5], vs[ch][6], vs[ch][7]}; \
+      FI_PACK_8(va, vb, (PK)[ch])                                                                 \
+    }                                                                                             \
+  }
+  const bool smooth = d.act > FI_ACT_RELU6;
   if constexpr (BM == 256) {
     // ---- epilogue: every wave transposes its own sub-tile through a private LDS patch -----------
     // (no workgroup barrier: waves drain independently, one 32-row MFMA block at a time).  With the
@@ -537,10 +579,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   #pragma unroll
       for (int i = 0; i < MI; ++i) {
         const int mb = m0 + wm * WTM + i * 32;
-        u32x4 rq[CH], pk[CH];
+        u32x4 rq[CH][AV], pk[CH][AV];
   #pragma unroll
-        for (int ch = 0; ch < CH; ++ch)
-          rq[ch] = __builtin_amdgcn_raw_buffer_load_b128(rres, (uint32_t)(((mb + lr0 + ch * RSTEP) * d.Cop + o) * 2) | col_dead, 0, 0);
+        for (int ch = 0; ch < CH; ++ch) { FI_LOAD_RES(rq[ch], mb + lr0 + ch * RSTEP) }
   #pragma unroll
         for (int j = 0; j < NI; ++j)
   #pragma unroll
@@ -548,21 +589,17 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
             *reinterpret_cast<float4*>(&ep[(lane & 31) * EPS + j * 32 + 8 * g + 4 * (lane >> 5)]) =
                 make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  #pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-          const int lr = lr0 + ch * RSTEP;
-          const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
-          const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
-          FI_FINISH_8(v0, v1, rq[ch], pk[ch])
-        }
+#define FI_READ_CHUNK(ch, v0, v1)                                                                 \
+          v0 = *reinterpret_cast<const float4*>(&ep[(lr0 + (ch) * RSTEP) * EPS + cc]);            \
+          v1 = *reinterpret_cast<const float4*>(&ep[(lr0 + (ch) * RSTEP) * EPS + cc + 4]);
+        FI_FINISH_BLOCK(rq, pk, FI_READ_CHUNK)
+#undef FI_READ_CHUNK
         if (stream_out) {
   #pragma unroll
-          for (int ch = 0; ch < CH; ++ch)
-            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mb + lr0 + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 2);
+          for (int ch = 0; ch < CH; ++ch) { FI_STORE_ROW(pk[ch], mb + lr0 + ch * RSTEP, 2) }
         } else {
   #pragma unroll
-          for (int ch = 0; ch < CH; ++ch)
-            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mb + lr0 + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 0);
+          for (int ch = 0; ch < CH; ++ch) { FI_STORE_ROW(pk[ch], mb + lr0 + ch * RSTEP, 0) }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
@@ -667,10 +704,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   #pragma unroll
       for (int pass = 0; pass < BM / 64; ++pass) {
         const int mp = m0 + pass * 64 + lr0;
-        u32x4 rq[CH], pk[CH];
+        u32x4 rq[CH][AV], pk[CH][AV];
   #pragma unroll
-        for (int ch = 0; ch < CH; ++ch)
-          rq[ch] = __builtin_amdgcn_raw_buffer_load_b128(rres, (uint32_t)(((mp + ch * RSTEP) * d.Cop + o) * 2) | col_dead, 0, 0);
+        for (int ch = 0; ch < CH; ++ch) { FI_LOAD_RES(rq[ch], mp + ch * RSTEP) }
         if (pass > 0) __syncthreads();
   #pragma unroll
         for (int i = 0; i < MI; ++i) {
@@ -685,21 +721,17 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
                   make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
         }
         __syncthreads();
-  #pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-          const int lr = lr0 + ch * RSTEP;
-          const float4 v0 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc]);
-          const float4 v1 = *reinterpret_cast<const float4*>(&ep[lr * EPS + cc + 4]);
-          FI_FINISH_8(v0, v1, rq[ch], pk[ch])
-        }
+#define FI_READ_CHUNK(ch, v0, v1)                                                                 \
+          v0 = *reinterpret_cast<const float4*>(&ep[(lr0 + (ch) * RSTEP) * EPS + cc]);            \
+          v1 = *reinterpret_cast<const float4*>(&ep[(lr0 + (ch) * RSTEP) * EPS + cc + 4]);
+        FI_FINISH_BLOCK(rq, pk, FI_READ_CHUNK)
+#undef FI_READ_CHUNK
         if (stream_out) {
   #pragma unroll
-          for (int ch = 0; ch < CH; ++ch)
-            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mp + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 2);
+          for (int ch = 0; ch < CH; ++ch) { FI_STORE_ROW(pk[ch], mp + ch * RSTEP, 2) }
         } else {
   #pragma unroll
-          for (int ch = 0; ch < CH; ++ch)
-            __builtin_amdgcn_raw_buffer_store_b128(pk[ch], yres, (uint32_t)(((mp + ch * RSTEP) * d.ys + o) * 2) | col_dead, 0, 0);
+          for (int ch = 0; ch < CH; ++ch) { FI_STORE_ROW(pk[ch], mp + ch * RSTEP, 0) }
         }
       }
       return;
@@ -781,7 +813,11 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
       }
     }
   }
-#undef FI_FINISH_8
+#undef FI_SUM_8
+#undef FI_PACK_8
+#undef FI_LOAD_RES
+#undef FI_STORE_ROW
+#undef FI_FINISH_BLOCK
 }
 
 // ---------------------------------------------------------------------------------
