@@ -324,14 +324,14 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "ac49af41b704dc7824daa47ef1c810337fb430ccb353733d11ff1a2304d81581",
+    "sources_sha256": "a85c2db3d5641d894851894a5a1f963ac18bea4949a7e33554f60dcea377b679",
     "workload": "cfg4",
     "fetch_scale": 2.0, "write_scale": 1.0,
     "kernels": {   # kernel name -> launches and KiB per step
-        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454401.6, "write_kib_per_step": 2579458.8},
-        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1091708.4, "write_kib_per_step": 1618210.6},
-        "conv_mfma_128x64": {"launches_per_step": 8, "fetch_kib_per_step": 101594.9, "write_kib_per_step": 501760.0},
-        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613625.0, "write_kib_per_step": 376320.0},
+        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454738.6, "write_kib_per_step": 2579431.2},
+        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098362.6, "write_kib_per_step": 1618232.7},
+        "conv_mfma_128x64": {"launches_per_step": 8, "fetch_kib_per_step": 101668.2, "write_kib_per_step": 501760.0},
+        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613355.8, "write_kib_per_step": 376320.0},
     },
 }
 
