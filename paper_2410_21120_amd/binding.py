@@ -48,7 +48,8 @@ class fi_build_opts(C.Structure):
                 ("max_device_bytes", C.c_uint64), ("dev_alloc", ALLOC_FN),
                 ("dev_free", FREE_FN), ("pin_alloc", ALLOC_FN), ("pin_free", FREE_FN), ("user", C.c_void_p),
                 ("swap_headroom_bytes", C.c_uint64), ("copy_concats", C.c_int32), ("separate_affine", C.c_int32),
-                ("separate_chains", C.c_int32), ("member_chunks", C.c_int32)]
+                ("separate_chains", C.c_int32), ("member_chunks", C.c_int32), ("separate_stem", C.c_int32),
+                ("reserved0", C.c_int32)]
 
 
 class fi_dag_info(C.Structure):
@@ -222,7 +223,7 @@ def fi_round_robin(specs, opts: fi_build_opts, group_of, n_groups, iterations, r
 
 def make_opts(max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY, max_device_bytes=0,
               use_graph=False, serial_lanes=False, swap_headroom_bytes=0, per_member_inputs=False,
-              copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0) -> fi_build_opts:
+              copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0, separate_stem=False) -> fi_build_opts:
     opts = fi_build_opts()
     opts.max_batch, opts.group_levels, opts.load_mode, opts.max_device_bytes = max_batch, int(group_levels), load_mode, max_device_bytes
     opts.use_graph = int(use_graph)
@@ -233,6 +234,7 @@ def make_opts(max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_O
     opts.separate_affine = int(separate_affine)
     opts.separate_chains = int(separate_chains)
     opts.member_chunks = int(member_chunks)
+    opts.separate_stem = int(separate_stem)
     if allocators is not None:
         allocators.apply(opts)
     return opts
@@ -460,10 +462,11 @@ class Dag:
 
     def __init__(self, specs, max_batch, allocators=None, group_levels=True, load_mode=FI_LOAD_ONE_COPY,
                  max_device_bytes=0, keepalive=None, use_graph=False, serial_lanes=False, swap_headroom_bytes=0,
-                 per_member_inputs=False, copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0):
+                 per_member_inputs=False, copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0,
+                 separate_stem=False):
         self.keepalive = [specs, keepalive, allocators]
         opts = make_opts(max_batch, allocators, group_levels, load_mode, max_device_bytes, use_graph, serial_lanes,
-                         swap_headroom_bytes, per_member_inputs, copy_concats, separate_affine, separate_chains, member_chunks)
+                         swap_headroom_bytes, per_member_inputs, copy_concats, separate_affine, separate_chains, member_chunks, separate_stem)
         self.opts = opts
         self.h = fi_build_dag(specs, opts)
         self.n_models = len(specs)

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfusedinf.so")
-SOURCES = ["fi_plan.cpp", "fi_api.cpp", "fi_sched.cpp", "fi_server.cpp", "fi_kernels.hip", "fi_chain.hip"]
+SOURCES = ["fi_plan.cpp", "fi_api.cpp", "fi_sched.cpp", "fi_server.cpp", "fi_kernels.hip", "fi_chain.hip", "fi_stem.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

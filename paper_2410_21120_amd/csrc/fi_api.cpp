@@ -167,6 +167,7 @@ const char* kind_name(int kind, int tile) {
     case K_MUL: return "channel_scale";
     case K_GATHER: return "channel_gather";
     case K_CHAIN: return tile ? "conv_chain3" : "conv_chain2";
+    case K_STEM: return tile ? "conv_stem_pool" : "conv_stem";
   }
   return "?";
 }
@@ -469,6 +470,44 @@ static void form_chains(fi_dag* g) {
   }
 }
 
+// Planner pass, after form_chains: the first convolution of an ImageNet-style member.  A 7x7 stride-2 convolution over the
+// 4-channel model input with 64 output channels (bf16 in and out, identity / ReLU / ReLU6) takes the stem kernel, which
+// multiplies from an input patch in LDS instead of gathering reduction vectors from memory.  When its ONLY reader is a
+// 3x3 stride-2 padding-1 max-pool (floor mode), that pool is part of the same launch: the pool node carries the launch,
+// the convolution gets none and its output is stored nowhere.  Same bits as the general kernels either way.
+static void take_stem_launches(fi_dag* g) {
+  if (g->opts.separate_stem || g->wdtype != FI_BF16) return;
+  const int32_t total = (int32_t)g->nodes.size();
+  const uint64_t B = (uint64_t)g->opts.max_batch;
+  std::vector<int32_t> uses((size_t)total, 0);   // readers of a tensor, as first or second operand
+  for (const Node& nd : g->nodes) {
+    if (nd.input >= 0) uses[(size_t)nd.input]++;
+    if (nd.residual >= 0) uses[(size_t)nd.residual]++;
+  }
+  for (Node& A : g->nodes) {
+    const int adt = g->members[(size_t)A.model].spec.act_dtype;
+    if (A.kind != K_CONV_MFMA || A.op != FI_CONV2D || adt != FI_BF16 || A.out_dtype != FI_BF16 || A.input >= 0 || A.residual >= 0) continue;
+    if (A.Cp != 4 || A.k != 7 || A.kw != 7 || A.stride != 2 || A.pad < 0 || A.pad > 3 || A.pad_w < 0 || A.pad_w > 3) continue;
+    if (A.Co != 64 || A.Cop != 64 || A.Kp != 224 || A.groups != 1 || A.act > FI_ACT_RELU6) continue;
+    if (A.is_output || A.root >= 0 || A.elided || A.pre >= 0 || A.chain >= 0 || A.splits != 1) continue;
+    if (B * A.Ho * A.Wo * 64 * 2 >= (1ull << 31)) continue;   // the kernel's 32-bit output offsets
+    A.kind = K_STEM;
+    A.tile = 0;
+  }
+  for (int32_t i = 0; i < total; ++i) {
+    Node& P = g->nodes[(size_t)i];
+    if (P.kind != K_MAXPOOL || P.input < 0 || P.k != 3 || P.stride != 2 || P.pad != 1) continue;
+    Node& A = g->nodes[(size_t)P.input];
+    if (A.kind != K_STEM || uses[(size_t)P.input] != 1) continue;
+    if (P.is_output || P.root >= 0 || P.elided || P.out_dtype != FI_BF16 || P.Cp != 64 || P.Cop != 64 || P.run != A.run + 1) continue;
+    if (P.Ho != (A.Ho + 2 - 3) / 2 + 1 || P.Wo != (A.Wo + 2 - 3) / 2 + 1) continue;   // (a ceil-mode pool keeps its own launch)
+    P.pre = P.input;
+    P.kind = K_STEM;
+    P.tile = 1;
+    A.elided = 1;
+  }
+}
+
 // Planner pass: the disjoint union of the member graphs and every node's depth.
 static void union_member_graphs(fi_dag* g) {
   const int32_t n = (int32_t)g->members.size();
@@ -761,7 +800,7 @@ static void build_schedule(fi_dag* g) {
         continue;
       }
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
-      const int pre_kind = nd.pre < 0 ? 0 : g->nodes[(size_t)nd.pre].kind == K_MUL ? 2 : 1;
+      const int pre_kind = (nd.pre < 0 || nd.kind == K_STEM) ? 0 : g->nodes[(size_t)nd.pre].kind == K_MUL ? 2 : 1;
       const auto key = std::make_tuple(nd.kind, nd.tile, nd.lane * 64 + pre_kind * 16 + (walks_groups(nd, adt) ? 8 : 0) + (nd.kind == K_CONV_MFMA && nd.Cp == 4 ? 4 : 0) + adt * 2 +
                                        ((nd.kind == K_CONV_MFMA || nd.kind == K_FC) && nd.splits > 1 ? 1 : 0));
       auto it = open.find(key);
@@ -818,7 +857,10 @@ static void plan_activation_arena(fi_dag* g) {
     if (nd.input >= 0) g->nodes[(size_t)nd.input].last_level = std::max(g->nodes[(size_t)nd.input].last_level, nd.run);
     else { StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage]; st.last = std::max(st.last, nd.run); }
     if (nd.residual >= 0) g->nodes[(size_t)nd.residual].last_level = std::max(g->nodes[(size_t)nd.residual].last_level, nd.run);
-    if (nd.pre >= 0) {   // the convolution reads the fused node's input (and gate) itself
+    if (nd.pre >= 0 && g->nodes[(size_t)nd.pre].input < 0) {   // a stem launch with its pool reads the staged model input
+      StageTensor& st = g->stages[(size_t)g->members[(size_t)nd.model].stage];
+      st.last = std::max(st.last, nd.run);
+    } else if (nd.pre >= 0) {   // the convolution reads the fused node's input (and gate) itself
       Node& T = g->nodes[(size_t)g->nodes[(size_t)nd.pre].input];
       T.last_level = std::max(T.last_level, nd.run);
       if (g->nodes[(size_t)nd.pre].kind == K_MUL || g->nodes[(size_t)nd.pre].kind == K_CONCAT) {
@@ -962,6 +1004,26 @@ static void fill_descriptors(fi_dag* g) {
       const Node& nd = g->nodes[(size_t)L.nodes[(size_t)s]];
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
       Desc& d = g->descs[(size_t)(L.first_desc + s)];
+      if (L.kind == K_STEM) {   // the convolution's fields (the node itself, or the one in front of the pool that carries the launch)
+        const Node& cv = L.tile == 1 ? g->nodes[(size_t)nd.pre] : nd;
+        d.x_off = g->stages[(size_t)g->members[(size_t)nd.model].stage].off;
+        d.y_off = nd.out_off;
+        d.r_off = d.pw_off = d.pb_off = kNone;
+        d.w_off = cv.w_off; d.b_off = cv.b_off;
+        d.H = cv.H; d.W = cv.W; d.C = cv.C; d.Cp = cv.Cp; d.xs = cv.Cp;
+        d.k = cv.k; d.kw = cv.kw; d.stride = cv.stride; d.pad = cv.pad; d.pad_w = cv.pad_w; d.act = cv.act; d.Kp = cv.Kp;
+        d.gin = cv.Ho; d.gout = cv.Wo;
+        d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop; d.ys = nd.Cop;
+        d.splits = 1;
+        d.ws_off = kNone;
+        // workgroups walk several pixel blocks: as many as stay resident together (two per compute unit), over the launch's
+        // problems and the lanes that run the same level at about the same time
+        d.tiles_n = std::max(16, 512 / std::max(1, L.n * g->members[(size_t)nd.model].sibling_lanes));
+        L.macs += cv.macs;
+        L.act_bytes += (uint64_t)cv.H * cv.W * cv.C * 2 + (uint64_t)nd.Ho * nd.Wo * nd.Co * 2;
+        L.weight_bytes += (uint64_t)cv.Co * cv.k * cv.kw * cv.C * 2 + (uint64_t)cv.Co * 4;
+        continue;
+      }
       d.x_off = nd.input >= 0 ? g->nodes[(size_t)nd.input].out_off : g->stages[(size_t)g->members[(size_t)nd.model].stage].off;
       d.y_off = nd.is_output ? kNone : nd.out_off;
       d.r_off = nd.residual >= 0 ? g->nodes[(size_t)nd.residual].out_off : kNone;
@@ -1086,6 +1148,7 @@ static fi_status plan_dag(fi_dag* g) {
   store_concat_sources_in_place(g);
   fold_nodes_into_readers(g);
   form_chains(g);
+  take_stem_launches(g);
   build_schedule(g);
   plan_activation_arena(g);
   st = place_weights_and_workspace(g);

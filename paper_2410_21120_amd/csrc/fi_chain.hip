@@ -33,22 +33,6 @@ typedef u32x2 __attribute__((may_alias)) u32x2_a;
 
 __device__ __forceinline__ void wave_lds_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
-// From the packed outputs of one 32-channel block (pk[g] = channels 8g + 4h .. + 3 of this lane's pixel, h = lane >> 5,
-// as two dwords of bf16 pairs) to the operand fragments of the two 16-element reduction steps the block covers:
-// frag[half] = channels 16 half + 8h .. + 7.
-__device__ __forceinline__ void runs_to_fragments(const uint32_t (&pk)[4][2], uint32_t (&frag)[2][4]) {
-#pragma unroll
-  for (int half = 0; half < 2; ++half)
-#pragma unroll
-    for (int dw = 0; dw < 2; ++dw) {
-      // lower half keeps its own run g0 and receives the upper half's run g0; the upper half receives the lower
-      // half's run g0 + 1 and keeps its own
-      const auto r = __builtin_amdgcn_permlane32_swap(pk[2 * half][dw], pk[2 * half + 1][dw], false, false);
-      frag[half][dw] = r[0];
-      frag[half][2 + dw] = r[1];
-    }
-}
-
 // W1: output channels of A = reduction length of B (64 or 128).  N3: output channels of C (64 or 128), 0 = no C.
 // SMOOTH: some node of the launch has an activation beyond identity / ReLU / ReLU6 (the variant without them keeps
 // its epilogues free of branches).

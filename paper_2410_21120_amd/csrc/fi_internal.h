@@ -36,6 +36,8 @@ enum Kind : int32_t {
   K_MUL = 11,         // per-(image, channel) gate
   K_GATHER = 12,      // channel slice (stride == 0: channels from pad on) or shuffle (stride == 1: k groups)
   K_CHAIN = 13,       // a convolution and the one or two pointwise convolutions behind it, per 128-pixel tile, in one launch
+  K_STEM = 14,        // the 7x7 stride-2 convolution over the 4-channel model input, from an input patch in LDS (tile 0), or that
+                      // convolution and the 3x3 stride-2 max-pool that alone reads it (tile 1: the pool node carries the launch)
   K_NKINDS
 };
 
@@ -64,12 +66,15 @@ struct Desc {
   int32_t ext;                   // 1: output is the caller's fp32 buffer of this problem
   int32_t out_f32;               // 1: output stored as fp32 whatever the activation dtype
   int32_t tiles_n;               // MFMA conv: column tiles; FC: 32-feature tiles; depthwise / pooling strip kernels: outputs per
-                                 // thread along a row; concatenation / interleaving shuffle: pixel stride of the second source
+                                 // thread along a row; concatenation / interleaving shuffle: pixel stride of the second source;
+                                 // stem launch: workgroups that share the problem
   int32_t vec;                   // 1: bf16 tensors with Cp % 8 == 0, kernels work on 8-channel vectors
   int32_t splits;                // reduction splits (>1: fp32 partials [splits][rows][Cop] at ws_off)
   uint64_t ws_off;               // split-K partials, relative to the workspace base (KArgs::wsbase)
   int32_t kw, pad_w;             // dense conv: kernel width and horizontal padding (k, pad are the vertical ones)
-  int32_t gin, gout;             // MFMA conv of a grouped convolution: input / output channels per group (0 = dense walk over all channels)
+  int32_t gin, gout;             // MFMA conv of a grouped convolution: input / output channels per group (0 = dense walk over all channels);
+                                 // stem launch: height / width of the convolution's output (Ho, Wo are the stored tensor's: the pooled size
+                                 // when the pool is part of the launch)
   int32_t xs, ys;                // elements between neighbouring pixels of the input / output: Cp / Cop, or the channel stride of the
                                  // concatenation the tensor is stored inside (read by the depthwise kernels and by MFMA convolutions
                                  // with an input-side stage, written by the bf16 vector kernels and the MFMA convolution; every other
@@ -95,7 +100,8 @@ struct Node {
                                  // scaling node that the convolution reading it applies while loading its input, or (2) a
                                  // concatenation that the two-group shuffle reading it replaces by interleaving its sources
   int32_t pre;                   // MFMA conv: the node fused into its input side, a per-channel affine (depthwise 1x1) or a
-                                 // squeeze-excite scaling; shuffle: the concatenation it replaces (-1 = none)
+                                 // squeeze-excite scaling; shuffle: the concatenation it replaces; max-pool run by a stem launch: the
+                                 // convolution in front of it (-1 = none)
   int32_t chain, chain_pos;      // chain >= 0: the node runs inside the chained launch headed by node `chain`, as its first (0), second
                                  // (1) or third (2) convolution; the head's own output is stored nowhere
   int32_t level;                 // depth: 1 + the deepest input
@@ -173,6 +179,10 @@ int static_scratch(void** ptr, uint64_t* bytes);
 
 // Implemented in fi_chain.hip: a K_CHAIN launch (problems are triples of descriptors).  Returns a hipError_t as int.
 int launch_chain(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);
+
+// Implemented in fi_stem.hip: a K_STEM launch, and the workgroups one of its problems takes.  Returns a hipError_t as int.
+int launch_stem(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);
+int stem_blocks(int tile, const Desc& d, int batch);
 
 // Implemented in fi_kernels.hip.  Returns a hipError_t as int; `stream` is a hipStream_t.
 int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);

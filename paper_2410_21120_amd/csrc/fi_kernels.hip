@@ -1680,6 +1680,7 @@ int static_scratch(void** ptr, uint64_t* bytes) {
 
 int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::vector<Desc>& hd) {
   if (L.kind == K_CHAIN) return launch_chain(L, args, stream, hd);
+  if (L.kind == K_STEM) return launch_stem(L, args, stream, hd);
   hipStream_t s = static_cast<hipStream_t>(stream);
   KArgs a = args;
   for (int i = 0; i < L.n; ++i) a.d[i] = hd[(size_t)(L.first_desc + i)];

@@ -1,0 +1,404 @@
+// The first convolution of an ImageNet-style member: 7x7, stride 2, over the 4-channel model input, 64 output
+// channels (Section V, Table III: the ResNet, Wide ResNet, ResNeXt, DenseNet and GoogLeNet stems), optionally with
+// the 3x3 stride-2 padding-1 max-pool that alone reads it, in one launch.
+//
+// The general implicit-GEMM kernel gathers this layer's reduction vectors pixel by pixel from HBM (a 4-channel
+// pixel is 8 bytes, a reduction vector two filter taps) and is bound by that address work.  Here a workgroup owns a
+// two-dimensional block of output pixels, brings the input patch under it into LDS once (rows of contiguous pixels,
+// even and odd columns in planes of their own so that the stride-2 reads of neighbouring output pixels are
+// contiguous), and feeds the matrix cores straight from the patch: no im2col tile exists anywhere.  The 64 x 196
+// weights stay in registers as MFMA operands for as long as the workgroup lives, and a workgroup walks several
+// pixel blocks (the next block's patch is requested before the current block is multiplied).
+//
+// The reduction order is the general kernel's (taps row-major, 4 channels per tap, 16 elements per MFMA, ascending),
+// bias, activation and the one rounding to bf16 are its operations, and the max-pool combines its taps with the pooling
+// kernel's operation in the pooling kernel's order: the outputs are the same bits as the separate launches'.
+#include <hip/hip_runtime.h>
+
+#include "fi_device.h"
+
+namespace fi {
+namespace {
+
+constexpr int SK = 7;            // filter side
+constexpr int SS = 2;            // stride
+constexpr int STEM_KP = 224;     // packed weight row: 49 taps x 4 channels, rounded up to 32 elements
+constexpr int KSTEPS = 13;       // 16-element reduction steps that hold a real tap (the last real element is 195)
+constexpr int KREG = 12;         // steps whose weight fragments stay in registers; the others wait in LDS (the registers they
+                                 // would take are the ones the tile loop is short of)
+constexpr int CO = 64;           // output channels
+constexpr int OS = 72;           // bf16 elements per pixel row of the LDS output tile (144 bytes: 16-byte reads hit all banks)
+
+template <bool POOL>
+struct Geo {
+  // convolution outputs one block covers: with the pool, 15 x 17 of them are what 7 x 8 pooled pixels read
+  static constexpr int CH = POOL ? 15 : 16, CW = POOL ? 17 : 16;
+  static constexpr int NPX = CH * CW;                                   // <= 256: eight 32-pixel MFMA column blocks
+  static constexpr int PH = (CH - 1) * SS + SK, PW = (CW - 1) * SS + SK;  // the input patch under them
+  static constexpr int HALF = 20;                                       // pixels per plane row (>= (PW + 1) / 2)
+  // bytes per patch row: even-column plane, odd-column plane.  With the pool 8 bytes more: the lanes that take the block's
+  // 17th column read one pixel per row, and rows 656 instead of 640 bytes apart spread them over the banks.
+  static constexpr int ROWB = 2 * HALF * 8 + (POOL ? 8 : 0);
+  static constexpr int NPATCH = PH * PW;
+  static constexpr int SLOTS = (NPATCH + 255) / 256;                    // patch pixels a thread brings in
+  static constexpr int PATCH_BYTES = PH * ROWB;
+  static constexpr int ZERO_AT = PATCH_BYTES;                           // 16 zero bytes: taps past the filter, patch slots past the patch
+  static constexpr int BIAS_AT = ZERO_AT + 16;
+  static constexpr int WLDS_AT = BIAS_AT + CO * 4;                      // weight fragments of steps KREG.., [step][32-channel block][lane]
+  static constexpr int OUT_AT = WLDS_AT + (KSTEPS - KREG) * 2 * 64 * 16;
+  static constexpr int LDS_BYTES = OUT_AT + 256 * OS * 2;
+  static constexpr int TPH = 7, TPW = 8;                                // pooled pixels per block
+  static_assert((PW + 1) / 2 <= HALF, "a patch row fits its two planes");
+  static_assert(NPX <= 256, "eight 32-pixel blocks");
+  static_assert(KSTEPS - KREG <= 4, "one wave parks one step's fragments");
+  static_assert(PW < 255, "patch columns fit 8 bits");
+};
+
+// Byte offset of filter tap `tap` (row-major) from an output pixel's window origin in the LDS patch, -1 for the
+// taps that pad the reduction to a multiple of 16 elements (their weights are zero; they must read zero).
+template <bool POOL>
+__device__ __forceinline__ constexpr int tap_offset(int tap) {
+  if (tap >= SK * SK) return -1;
+  const int r = tap / SK, t = tap % SK;
+  return r * Geo<POOL>::ROWB + (t & 1) * Geo<POOL>::HALF * 8 + (t >> 1) * 8;
+}
+
+// One descriptor per problem.  Convolution fields as for any convolution (H, W, Cp = 4, k = kw = 7, stride 2, pad,
+// pad_w, act, w_off, b_off, Kp = 224); gin x gout is the convolution's output (height x width); Ho x Wo is what is
+// stored at y_off: the same without the pool, the pooled size with it; tiles_n = workgroups that share the problem.
+// CLAMP6: the launch holds a ReLU6 (otherwise the upper clamp is not applied at all).
+template <bool POOL, bool CLAMP6>
+__global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
+  using G = Geo<POOL>;
+  __shared__ __attribute__((aligned(16))) uint8_t smem[G::LDS_BYTES];
+  int p, bid;
+  if (!find_problem_at(a, (int)blockIdx.x, p, bid)) return;
+  const Desc d = a.d[p];
+  const int batch = a.batch[p];
+  const int Hc = d.gin, Wc = d.gout;
+  const int ty = POOL ? (d.Ho + G::TPH - 1) / G::TPH : (Hc + G::CH - 1) / G::CH;
+  const int tx = POOL ? (d.Wo + G::TPW - 1) / G::TPW : (Wc + G::CW - 1) / G::CW;
+  const int ntiles = batch * ty * tx;
+  const int nwg = min(d.tiles_n, ntiles);     // workgroups of this problem (the launch counted them the same way)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool upper = lane >= 32;              // lanes 32-63 hold reduction elements 8-15 of a step
+
+  const uint8_t* const xbase = a.abase + d.x_off;
+  const int image_bytes = d.H * d.W * 8;
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(a.wbase + d.w_off), 0, CO * STEM_KP * 2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
+      a.abase + d.y_off, 0, batch > 0 ? (int)((int64_t)batch * d.Ho * d.Wo * CO * 2) : 0, 0x00020000);
+  const bool stream_out = (int64_t)batch * d.Ho * d.Wo * CO * 2 > (int64_t)STREAM_OUT_BYTES;
+
+  // the weights: the MFMA operand fragments of every reduction step, for both 32-channel blocks
+  bf16x8 bw[KREG][2];
+#pragma unroll
+  for (int ks = 0; ks < KREG; ++ks)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      bw[ks][j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+          wres, (uint32_t)(((j * 32 + (lane & 31)) * STEM_KP + ks * 16 + (upper ? 8 : 0)) * 2), 0, 0));
+  if (wave < KSTEPS - KREG) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      *reinterpret_cast<u32x4*>(smem + G::WLDS_AT + ((wave * 2 + j) * 64 + lane) * 16) = __builtin_amdgcn_raw_buffer_load_b128(
+          wres, (uint32_t)(((j * 32 + (lane & 31)) * STEM_KP + (KREG + wave) * 16 + (upper ? 8 : 0)) * 2), 0, 0);
+  }
+  if (tid < CO / 4)
+    *reinterpret_cast<float4*>(smem + G::BIAS_AT + tid * 16) = *reinterpret_cast<const float4*>(a.wbase + d.b_off + tid * 16);
+  if (tid == 0) *reinterpret_cast<uint4*>(smem + G::ZERO_AT) = make_uint4(0, 0, 0, 0);
+
+  // This thread's patch pixels: slot j is pixel tid + 256 j of the patch, row-major.  Per slot: the pixel's byte offset from
+  // the patch origin in the image, and (one register) its column in the patch and where it goes in LDS (a slot past the
+  // patch reads zeros and writes them to the zero slot).
+  int slot_rel[G::SLOTS], slot_at[G::SLOTS];   // slot_at: LDS byte offset << 8 | patch column (255: a column no image has)
+#pragma unroll
+  for (int j = 0; j < G::SLOTS; ++j) {
+    const int i = tid + 256 * j;
+    const int pr = i / G::PW, pc = i - pr * G::PW;
+    const bool in_patch = i < G::NPATCH;
+    slot_rel[j] = (pr * d.W + pc) * 8;
+    slot_at[j] = in_patch ? ((pr * G::ROWB + (pc & 1) * G::HALF * 8 + (pc >> 1) * 8) << 8) | pc : (G::ZERO_AT << 8) | 255;
+  }
+  // Window origins in the LDS patch of the two 32-pixel blocks this wave multiplies.  Lanes 32-63 read the tap two
+  // places after the one lanes 0-31 read; seen from a tap at column t of the filter that is 8 bytes on (t <= 4), or
+  // wraps to the next filter row (t = 5 and t = 6: two other distances).  One base per case with the lane half's
+  // distance already in it leaves every read as base + a constant the instruction carries.  The fourth base sends
+  // lanes 32-63 to the zero slot: the last step's upper half lies past the filter.
+  // Which pixels: 16 neighbouring lanes take 16 neighbouring pixels of one row of the block (their reads are 128
+  // contiguous bytes of a plane: every bank once).  Without the pool that is all 16 x 16 pixels; with it, rows of 17:
+  // fifteen half-groups take columns 0-15 of the fifteen rows, the sixteenth takes column 16 of all of them.
+  constexpr int LAST_TAP = SK * SK - 1;
+  int win[2][4], out_at[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int hg = wave * 4 + i * 2 + ((lane & 31) >> 4), l16 = lane & 15;
+    int cy = hg, cx = l16;
+    bool real = true;
+    if constexpr (POOL) {
+      if (hg == G::CH) { cy = l16; cx = G::CW - 1; real = l16 < G::CH; }
+      cy = real ? cy : 0;
+    }
+    out_at[i] = (real ? cy * G::CW + cx : 255) * OS * 2;   // the pixel's row in the LDS output tile (row 255: nobody reads it)
+    const int w0 = (SS * cy) * G::ROWB + cx * 8;   // (stride 2: output column cx starts at patch column 2 cx, element cx of the even plane)
+    win[i][0] = w0 + (upper ? tap_offset<POOL>(2) - tap_offset<POOL>(0) : 0);
+    win[i][1] = w0 + (upper ? tap_offset<POOL>(7) - tap_offset<POOL>(5) : 0);
+    win[i][2] = w0 + (upper ? tap_offset<POOL>(8) - tap_offset<POOL>(6) : 0);
+    win[i][3] = upper ? G::ZERO_AT - tap_offset<POOL>(LAST_TAP) : w0;
+  }
+  // identity / ReLU / ReLU6 as max and min against bounds that are NaN where there is none (max / min return the other
+  // operand): the general kernel's two instructions, with the min left out where no problem of the launch has a ReLU6
+  uint32_t lo_b = d.act == FI_ACT_NONE ? 0x7FC00000u : 0u, hi_b = d.act == FI_ACT_RELU6 ? 0x40C00000u : 0x7FC00000u;
+  asm volatile("" : "+v"(lo_b), "+v"(hi_b));
+  const float act_lo = __uint_as_float(lo_b), act_hi = __uint_as_float(hi_b);
+
+  u32x2 pv[G::SLOTS];
+  // With the pool, a tile's two output vectors per thread leave one iteration late, just before the next patch is
+  // requested: a store issued after those loads would have to complete before the loads' data may be used (one
+  // in-order counter covers both), and the wait for the patch would be a wait for the store's acknowledgement.
+  u32x4 late[2] = {};
+  uint32_t late_off[2] = {OOB, OOB};          // (nothing to store yet: out of range, dropped)
+  int n, by, bx;   // image and block position of the tile whose patch is in flight
+#define FI_TILE_POS(T)                                                                            \
+  {                                                                                               \
+    const int per = ty * tx;                                                                      \
+    n = (T) / per;                                                                                \
+    const int rem = (T) - n * per;                                                                \
+    by = rem / tx;                                                                                \
+    bx = rem - by * tx;                                                                           \
+  }
+  // first convolution output of block (by, bx)
+#define FI_ORIGIN(CY0, CX0)                                                                       \
+  const int CY0 = POOL ? by * G::TPH * 2 - 1 : by * G::CH, CX0 = POOL ? bx * G::TPW * 2 - 1 : bx * G::CW;
+  // The patch of block (n, by, bx) through a buffer resource that covers image n alone: a row above or below the image
+  // is out of its range and reads zero by itself; a column left or right of the image would land in a neighbouring row
+  // and takes the out-of-range offset.  (LIVE false: an empty resource, everything reads zero.)
+#define FI_FETCH_PATCH(LIVE)                                                                      \
+  {                                                                                               \
+    FI_ORIGIN(cy0, cx0)                                                                           \
+    const int iy0 = cy0 * SS - d.pad, ix0 = cx0 * SS - d.pad_w;                                   \
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(                        \
+        const_cast<uint8_t*>(xbase + (int64_t)n * image_bytes), 0, (LIVE) ? image_bytes : 0, 0x00020000); \
+    const int origin = (iy0 * d.W + ix0) * 8;                                                     \
+    _Pragma("unroll") for (int j = 0; j < G::SLOTS; ++j) {                                        \
+      const int pc = slot_at[j] & 255;                                                            \
+      const bool col_ok = pc != 255 && (uint32_t)(ix0 + pc) < (uint32_t)d.W;                      \
+      pv[j] = __builtin_amdgcn_raw_buffer_load_b64(xres, col_ok ? (uint32_t)(origin + slot_rel[j]) : OOB, 0, 0); \
+    }                                                                                             \
+  }
+
+  int t = bid;
+  FI_TILE_POS(t)
+  FI_FETCH_PATCH(t < ntiles)
+  for (; t < ntiles; t += nwg) {
+    const int cn = n, cby = by, cbx = bx;     // the tile being multiplied
+#pragma unroll
+    for (int j = 0; j < G::SLOTS; ++j) *reinterpret_cast<u32x2*>(smem + (slot_at[j] >> 8)) = pv[j];
+    __syncthreads();
+    if constexpr (POOL) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) __builtin_amdgcn_raw_buffer_store_b128(late[j], yres, late_off[j], 0, 0);
+    }
+    {
+      const int tn = t + nwg;
+      FI_TILE_POS(tn < ntiles ? tn : t)
+      FI_FETCH_PATCH(tn < ntiles)             // in flight while this tile is multiplied
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    // operand fragments straight from the patch, one step ahead of the multiplies that use them (the scheduling
+    // barriers keep the compiler from hoisting every step's reads to the top, which costs more registers than there are)
+#define FI_READ_A(KS, AF)                                                                         \
+  _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                 \
+    u32x4 v;                                                                                      \
+    _Pragma("unroll") for (int h = 0; h < 2; ++h) { /* elements 0-3: one tap, elements 4-7: the next */ \
+      const int tap = 4 * (KS) + h;           /* what lanes 0-31 read; lanes 32-63: tap + 2 */    \
+      if (tap > LAST_TAP) {                                                                       \
+        v[2 * h] = v[2 * h + 1] = 0u;                                                             \
+      } else {                                                                                    \
+        const int col = tap % SK;                                                                 \
+        const int base = tap + 2 > LAST_TAP ? 3 : col <= 4 ? 0 : col == 5 ? 1 : 2;                \
+        const u32x2 half = *reinterpret_cast<const u32x2*>(smem + win[i][base] + tap_offset<POOL>(tap)); \
+        v[2 * h] = half[0];                                                                       \
+        v[2 * h + 1] = half[1];                                                                   \
+      }                                                                                           \
+    }                                                                                             \
+    (AF)[i] = __builtin_bit_cast(bf16x8, v);                                                      \
+  }
+    bf16x8 af[2][2], wl[2];
+    FI_READ_A(0, af[0])
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      if (ks + 1 < KSTEPS) { FI_READ_A(ks + 1, af[(ks + 1) & 1]) }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ks < KREG ? bw[ks < KREG ? ks : 0][j] : wl[j], af[ks & 1][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 >= KREG && ks + 1 < KSTEPS) {   // the next step's weights from LDS, into registers this step's multiplies have read
+#pragma unroll
+        for (int j = 0; j < 2; ++j) wl[j] = *reinterpret_cast<const bf16x8*>(smem + G::WLDS_AT + (((ks + 1 - KREG) * 2 + j) * 64 + lane) * 16);
+      }
+    }
+#undef FI_READ_A
+
+    // Bias, activation, the one rounding.  A lane holds, for one pixel, runs of 4 consecutive channels; the two halves of
+    // the wave exchange runs so that each ends with 8 consecutive channels, parked with one 16-byte write.
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      float4 b[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) b[g] = *reinterpret_cast<const float4*>(smem + G::BIAS_AT + (j * 32 + 8 * g + (upper ? 4 : 0)) * 4);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        uint32_t pk[4][2], frag[2][4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v[4] = {acc[i][j][4 * g] + b[g].x, acc[i][j][4 * g + 1] + b[g].y, acc[i][j][4 * g + 2] + b[g].z, acc[i][j][4 * g + 3] + b[g].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[e] = fmaxf(v[e], act_lo);
+            if constexpr (CLAMP6) v[e] = fminf(v[e], act_hi);
+          }
+          pk[g][0] = pack_bf16x2(v[0], v[1]);
+          pk[g][1] = pack_bf16x2(v[2], v[3]);
+        }
+        runs_to_fragments(pk, frag);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const u32x4 q = {frag[half][0], frag[half][1], frag[half][2], frag[half][3]};
+          *reinterpret_cast<u32x4*>(smem + G::OUT_AT + out_at[i] + (j * 32 + 16 * half + (upper ? 8 : 0)) * 2) = q;
+        }
+      }
+    }
+    __syncthreads();
+
+    {
+      const int n = cn, by = cby, bx = cbx;
+      FI_ORIGIN(cy0, cx0)
+      if constexpr (!POOL) {
+        // every pixel row (64 channels, 128 bytes) leaves as eight 16-byte pieces of neighbouring threads
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int v = tid + 256 * j;
+          const int px = v >> 3, c8 = (v & 7) * 8;
+          const int cy = cy0 + px / G::CW, cx = cx0 + px % G::CW;
+          const bool ok = cy < Hc && cx < Wc;
+          const u32x4 q = *reinterpret_cast<const u32x4*>(smem + G::OUT_AT + (px * OS + c8) * 2);
+          const uint32_t off = ok ? (uint32_t)((((n * Hc + cy) * Wc + cx) * CO + c8) * 2) : OOB;
+          if (stream_out) __builtin_amdgcn_raw_buffer_store_b128(q, yres, off, 0, 2);
+          else __builtin_amdgcn_raw_buffer_store_b128(q, yres, off, 0, 0);
+        }
+      } else {
+        // 7 x 8 pooled pixels x eight 8-channel vectors.  The taps of a window in (row, column) order, combined with the
+        // pooling kernel's operation.  A tap outside the convolution's output (the pool's padding) is not skipped but
+        // moved onto the nearest row / column inside it, which lies in the same window: the maximum sees one of its
+        // values twice and is the same.  (Positions relative to the block: rows ly_lo..ly_hi, columns lx_lo..lx_hi exist.)
+        const int ly_lo = cy0 < 0 ? -cy0 : 0, ly_hi = min(G::CH - 1, Hc - 1 - cy0);
+        const int lx_lo = cx0 < 0 ? -cx0 : 0, lx_hi = min(G::CW - 1, Wc - 1 - cx0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int v = tid + 256 * j;
+          const int pp = v >> 3, c8 = (v & 7) * 8;
+          const bool live = pp < G::TPH * G::TPW;
+          const int ph = live ? pp >> 3 : 0, pw = pp & 7;
+          int row_at[3], col_at[3];
+#pragma unroll
+          for (int r = 0; r < 3; ++r) {
+            row_at[r] = min(max(2 * ph + r, ly_lo), ly_hi) * (G::CW * OS * 2);
+            col_at[r] = min(max(2 * pw + r, lx_lo), lx_hi) * (OS * 2) + c8 * 2;
+          }
+          float best[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+#pragma unroll
+          for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+              const u32x4 q = *reinterpret_cast<const u32x4*>(smem + G::OUT_AT + row_at[r] + col_at[s]);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                best[2 * e] = fmaxf(best[2 * e], __uint_as_float(q[e] << 16));
+                best[2 * e + 1] = fmaxf(best[2 * e + 1], __uint_as_float(q[e] & 0xFFFF0000u));
+              }
+            }
+          u32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)   // the maxima are bf16 values already: packing is exact
+            o[e] = (__float_as_uint(best[2 * e]) >> 16) | (__float_as_uint(best[2 * e + 1]) & 0xFFFF0000u);
+          const int oy = by * G::TPH + ph, ox = bx * G::TPW + pw;
+          const bool st_ok = live && oy < d.Ho && ox < d.Wo;
+          late[j] = o;
+          late_off[j] = st_ok ? (uint32_t)((((n * d.Ho + oy) * d.Wo + ox) * CO + c8) * 2) : OOB;
+        }
+      }
+    }
+    __syncthreads();   // the output tile and the patch are free again
+  }
+  if constexpr (POOL) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) __builtin_amdgcn_raw_buffer_store_b128(late[j], yres, late_off[j], 0, 0);
+  }
+#undef FI_TILE_POS
+#undef FI_ORIGIN
+#undef FI_FETCH_PATCH
+}
+
+}  // namespace
+
+// Workgroups of one problem of a stem launch: every block of output pixels at most once, `share` at most.
+int stem_blocks(int tile, const Desc& d, int batch) {
+  const bool pool = tile == 1;
+  const int ty = pool ? (d.Ho + 6) / 7 : (d.gin + 15) / 16;
+  const int tx = pool ? (d.Wo + 7) / 8 : (d.gout + 15) / 16;
+  const int64_t tiles = (int64_t)batch * ty * tx;
+  return (int)std::min<int64_t>(tiles, d.tiles_n);
+}
+
+int launch_stem(const Launch& L, const KArgs& args, void* stream, const std::vector<Desc>& hd) {
+  if (L.wdtype != FI_BF16 || L.adtype != FI_BF16 || (L.tile != 0 && L.tile != 1) || L.n < 1 || L.n > FI_MAX_GROUP) return (int)hipErrorInvalidValue;
+  KArgs a = args;
+  int64_t blocks = 0;
+  for (int i = 0; i < FI_MAX_GROUP + 1; ++i) {
+    a.first_block[i] = (int32_t)blocks;
+    if (i >= L.n) continue;
+    const Desc& t = hd[(size_t)(L.first_desc + i)];
+    a.d[i] = t;
+    // what the kernel takes for granted
+    if (t.k != SK || t.kw != SK || t.stride != SS || t.Cp != 4 || t.Kp != STEM_KP || t.Co != CO || t.Cop != CO || t.ys != CO || t.xs != 4 ||
+        t.act < 0 || t.act > FI_ACT_RELU6 || t.ext || t.out_f32 || t.splits != 1 || t.r_off != kNone || t.tiles_n < 1 ||
+        t.pad < 0 || t.pad > 3 || t.pad_w < 0 || t.pad_w > 3 || t.x_off == kNone || t.y_off == kNone || t.w_off == kNone || t.b_off == kNone)
+      return (int)hipErrorInvalidValue;
+    if (t.gin != (t.H + 2 * t.pad - SK) / SS + 1 || t.gout != (t.W + 2 * t.pad_w - SK) / SS + 1 || t.gin < 1 || t.gout < 1) return (int)hipErrorInvalidValue;
+    if (L.tile == 1 ? (t.Ho != (t.gin + 2 - 3) / 2 + 1 || t.Wo != (t.gout + 2 - 3) / 2 + 1) : (t.Ho != t.gin || t.Wo != t.gout)) return (int)hipErrorInvalidValue;
+    // 32-bit byte offsets through buffer resources
+    if ((uint64_t)a.batch[i] * t.H * t.W * 8 >= (1ull << 31) || (uint64_t)a.batch[i] * t.Ho * t.Wo * CO * 2 >= (1ull << 31)) return (int)hipErrorInvalidValue;
+    blocks += stem_blocks(L.tile, t, a.batch[i]);
+    if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+  }
+  if (blocks == 0) return (int)hipSuccess;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  bool clamp6 = false;
+  for (int i = 0; i < L.n; ++i) clamp6 = clamp6 || hd[(size_t)(L.first_desc + i)].act == FI_ACT_RELU6;
+  const dim3 grid((unsigned)blocks), wg(256);
+  if (L.tile == 1) {
+    if (clamp6) hipLaunchKernelGGL((stem_kernel<true, true>), grid, wg, 0, s, a);
+    else hipLaunchKernelGGL((stem_kernel<true, false>), grid, wg, 0, s, a);
+  } else {
+    if (clamp6) hipLaunchKernelGGL((stem_kernel<false, true>), grid, wg, 0, s, a);
+    else hipLaunchKernelGGL((stem_kernel<false, false>), grid, wg, 0, s, a);
+  }
+  return (int)hipGetLastError();
+}
+
+}  // namespace fi

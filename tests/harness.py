@@ -84,7 +84,7 @@ class GpuDag:
     """Builds one fused DAG from (model, blob[, act_dtype]) members and runs it."""
 
     def __init__(self, members, max_batch, group_levels=True, load_mode=fi.FI_LOAD_ONE_COPY, packed=False, use_graph=False, serial_lanes=False,
-                 swap_headroom_bytes=0, copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0):
+                 swap_headroom_bytes=0, copy_concats=False, separate_affine=False, separate_chains=False, member_chunks=0, separate_stem=False):
         import torch
         self.torch = torch
         self.alloc = fi.TorchAllocators("cuda:0")
@@ -98,7 +98,7 @@ class GpuDag:
             keep.append((k, blob))
         self.dag = fi.Dag(specs, max_batch, self.alloc, group_levels=group_levels, load_mode=load_mode, keepalive=keep,
                           use_graph=use_graph, serial_lanes=serial_lanes, swap_headroom_bytes=swap_headroom_bytes, copy_concats=copy_concats, separate_affine=separate_affine,
-                          separate_chains=separate_chains, member_chunks=member_chunks)
+                          separate_chains=separate_chains, member_chunks=member_chunks, separate_stem=separate_stem)
         self.packed = packed
         self.side = torch.cuda.Stream() if use_graph else None  # graph capture needs a non-default stream
         self.stream = self.side.cuda_stream if use_graph else torch.cuda.current_stream().cuda_stream

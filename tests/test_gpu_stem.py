@@ -1,0 +1,117 @@
+"""The stem launch: a 7x7 stride-2 convolution over the model input computed from an input patch held on chip, with
+the 3x3 stride-2 max-pool that alone reads it in the same launch (Section V, Table III: the first two layers of the
+ResNet-style families).  It must equal, bit for bit, the general convolution kernel followed by a pooling launch
+(Section III-A, C1: the output of each model remains the same), and meet the oracle like them."""
+import numpy as np
+import pytest
+
+from workloads import gen, zoo
+
+pytestmark = pytest.mark.gpu
+
+
+def stem_model(h, w, pad=3, pool="3x3/2", act=zoo.RELU, cout_tail=16):
+    """conv 7x7/2 -> [max-pool] -> 1x1 convolution whose fp32 output is the member's output: every pixel of the stem's
+    tensor reaches the caller."""
+    m = zoo.Model(f"stem{h}x{w}p{pad}{pool}", "bf16", 3, h, w)
+    a = m.add(zoo.CONV, zoo.MODEL_INPUT, cin=3, cout=64, k=7, stride=2, pad=pad, act=act)
+    if pool == "3x3/2":
+        a = m.add(zoo.MAXPOOL, a, k=3, stride=2, pad=1)
+    elif pool == "ceil":
+        a = m.add(zoo.MAXPOOL, a, k=3, stride=2, pad=0, ceil=True)
+    elif pool == "2x2/2":
+        a = m.add(zoo.MAXPOOL, a, k=2, stride=2, pad=0)
+    m.add(zoo.CONV, a, cin=64, cout=cout_tail, k=1, stride=1, pad=0, act=zoo.NONE)
+    return m.shapes()
+
+
+def _run(mem, x, **kw):
+    from tests import harness
+    g = harness.GpuDag(mem, x.shape[0], **kw)
+    try:
+        names = [L.name.decode() for L in g.dag.launches()]
+        return g.run(x), names
+    finally:
+        g.close()
+
+
+CASES = [
+    # h, w, pad, pool, act, batch
+    (224, 224, 3, "3x3/2", zoo.RELU, 2),     # the ImageNet stem: 56 x 56 pooled pixels are whole 7 x 8 blocks
+    (64, 64, 3, "3x3/2", zoo.RELU, 5),
+    (97, 131, 3, "3x3/2", zoo.RELU, 3),      # odd sizes: ragged blocks on both edges, a pool window hanging over the last row
+    (33, 50, 3, "3x3/2", zoo.NONE, 4),       # no activation: negative values through the pool
+    (17, 23, 3, "3x3/2", zoo.RELU6, 7),      # smaller than one block
+    (230, 38, 0, "3x3/2", zoo.RELU, 2),      # no padding
+    (75, 75, 1, "3x3/2", zoo.RELU, 3),
+    (224, 224, 3, None, zoo.RELU, 2),        # no pool behind the convolution: the stem kernel alone
+    (97, 131, 3, None, zoo.NONE, 3),
+    (40, 29, 2, None, zoo.RELU6, 6),
+    (112, 112, 3, "ceil", zoo.RELU, 3),      # a pool the launch does not take (ceil mode, no padding): stem kernel + pooling launch
+    (90, 90, 3, "2x2/2", zoo.RELU, 3),
+]
+
+
+@pytest.mark.parametrize("h,w,pad,pool,act,batch", CASES)
+def test_stem_launch_equals_general_kernels_bitwise_and_meets_the_oracle(h, w, pad, pool, act, batch):
+    from tests import harness
+    print(f"stem case {h}x{w} pad {pad} pool {pool} act {act} batch {batch}", flush=True)
+    models = [stem_model(h, w, pad, pool, act) for _ in range(3)]
+    mem = [(m, gen.make_blob(m, 5100 + i), None) for i, m in enumerate(models)]
+    x = gen.make_input(51 + h, batch, 3, h, w, "normal", "bf16")
+    fast, names = _run(mem, x)
+    plain, pnames = _run(mem, x, separate_stem=True)
+    want = "conv_stem_pool" if pool == "3x3/2" else "conv_stem"
+    assert want in names and not any(n.startswith("conv_stem") for n in pnames), (names, pnames)
+    if pool == "3x3/2":
+        assert "maxpool" not in names and "maxpool" in pnames
+    for i, (a, b) in enumerate(zip(fast, plain)):
+        assert np.isfinite(a).all()
+        assert np.array_equal(a, b), f"member {i}: the stem launch differs from the general kernels"
+    harness.check_against_oracle(f"stem {h}x{w} {pool}", mem[1][0], mem[1][1], None, x, fast[1])
+
+
+def test_stem_launch_under_every_build_option_and_beside_other_members():
+    """ResNets (stem + pool in one launch) beside a VGG and an fp32-activation MobileNetV2 (general kernels), ungrouped,
+    on one stream, as a HIP graph, in member chunks, alone, with fewer images than max_batch: the same bits."""
+    from tests import harness
+    hw = 64
+    fams = [("resnet18", None), ("vgg11", None), ("mobilenetv2", "f32"), ("resnet50", None), ("resnet18", None)]
+    mem = []
+    for i, (f, act) in enumerate(fams):
+        m = zoo.FAMILIES[f](hw=hw)
+        mem.append((m, gen.make_blob(m, 5200 + i), act))
+    x = gen.make_input(53, 4, 3, hw, hw, "normal", "bf16")
+    base, names = _run(mem, x)
+    assert "conv_stem_pool" in names
+    for kw in (dict(separate_stem=True), dict(group_levels=False), dict(serial_lanes=True), dict(use_graph=True), dict(member_chunks=2),
+               dict(separate_stem=True, separate_chains=True)):
+        got, _ = _run(mem, x, **kw)
+        for i, (a, b) in enumerate(zip(base, got)):
+            assert np.array_equal(a, b), (kw, i)
+    alone, _ = _run([mem[0]], x)
+    assert np.array_equal(alone[0], base[0])
+    g = harness.GpuDag(mem, 9)   # room for 9 images: 9 given, then 4; an image's bits do not depend on its batch
+    try:
+        x9 = np.concatenate([x, gen.make_input(54, 5, 3, hw, hw, "normal", "bf16")])
+        full = g.run(x9)
+        few = g.run(x)
+    finally:
+        g.close()
+    for a, b in zip(few, full):
+        assert np.array_equal(a, b[:4])
+    for i in (0, 3):
+        harness.check_against_oracle(f"{fams[i][0]} with the stem launch", mem[i][0], mem[i][1], None, x, base[i])
+
+
+def test_stem_launch_full_size_batch32_equals_general_kernels():
+    """The launch configuration the benchmark times: ResNet-50 stems at 224 x 224, batch 32, two members."""
+    hw, batch = 224, 32
+    models = [stem_model(hw, hw) for _ in range(2)]
+    mem = [(m, gen.make_blob(m, 5300 + i), None) for i, m in enumerate(models)]
+    x = gen.make_input(55, batch, 3, hw, hw, "normal", "bf16")
+    fast, names = _run(mem, x)
+    plain, _ = _run(mem, x, separate_stem=True)
+    assert "conv_stem_pool" in names
+    for a, b in zip(fast, plain):
+        assert np.array_equal(a, b)

@@ -43,7 +43,7 @@ def test_union_levels_and_operator_count():
     levels equal the member's own depth (Algorithm 1, compilation loop; Section IV-C: the DAG holds
     exactly the members' operators)."""
     fams = ["resnet50", "mobilenetv2", "vgg16", "resnet18"]
-    d, models, _ = _build(fams, 2, separate_chains=True)   # one launch per node and level (chained launches: tested below)
+    d, models, _ = _build(fams, 2, separate_chains=True, separate_stem=True)   # one launch per node and level (chained and stem launches: tested below)
     q = d.query()
     assert q.n_models == 4 and q.n_nodes == sum(len(m.layers) for m in models)
     assert q.n_levels == max(max(m.levels()) for m in models)
@@ -75,8 +75,8 @@ def test_union_levels_and_operator_count():
 
 def test_grouping_reduces_launches_only():
     fams = ["resnet50"] * 8
-    g, _, _ = _build(fams, 4, separate_chains=True)
-    u, _, _ = _build(fams, 4, group=False, separate_chains=True)   # (a launch per node: chains would take three nodes each)
+    g, _, _ = _build(fams, 4, separate_chains=True, separate_stem=True)
+    u, _, _ = _build(fams, 4, group=False, separate_chains=True, separate_stem=True)   # (a launch per node: chains would take three nodes each, a stem launch two)
     qg, qu = g.query(), u.query()
     n_red = sum(1 for L in u.launches() if L.name == b"splitk_reduce")  # split-K launches have a reduce twin
     assert n_red >= sum(1 for n in u.nodes() if n.op == fi.FI_FC)
@@ -644,6 +644,53 @@ def test_chains_drop_the_first_tensor_and_two_launches_per_block():
     plain = sum(L.bytes_per_image for L in p.launches())
     assert chained < 0.95 * plain   # activation bytes per image of the whole schedule (only the first stage chains at this size)
     assert sum(L.macs_per_image for L in d.launches()) == sum(L.macs_per_image for L in p.launches())
+
+
+def test_stem_launch_takes_the_pool_and_drops_the_first_tensor():
+    """The 7x7 stride-2 first convolution and the 3x3 stride-2 max-pool behind it run as one launch carried by the pool
+    node: the convolution's output has no buffer, its work is counted under that launch, the compulsory bytes are the
+    input image and the pooled tensor, and the staged input stays alive until that launch."""
+    d, models, _ = _build(["resnet50", "resnet18", "vgg11"], 4, hw=96)
+    p, _, _ = _build(["resnet50", "resnet18", "vgg11"], 4, hw=96, separate_stem=True)
+    names = [L.name.decode() for L in d.launches()]
+    pnames = [L.name.decode() for L in p.launches()]
+    assert "conv_stem_pool" in names and not any(n.startswith("conv_stem") for n in pnames)
+    qd, qp = d.query(), p.query()
+    assert (qd.n_nodes, qd.n_levels, qd.macs_per_image, qd.arena_bytes) == (qp.n_nodes, qp.n_levels, qp.macs_per_image, qp.arena_bytes)
+    assert qd.n_launches < qp.n_launches
+    nodes, pnodes = d.nodes(), p.nodes()
+    members = d.members()
+    for mi in (0, 1):   # the two ResNets
+        conv, pool = nodes[members[mi].first_node], nodes[members[mi].first_node + 1]
+        assert conv.out_bytes == 0 and pnodes[members[mi].first_node].out_bytes > 0
+        assert conv.launch == pool.launch and names[pool.launch] == "conv_stem_pool"
+        assert pool.out_bytes == pnodes[members[mi].first_node + 1].out_bytes
+    vgg_first = nodes[members[2].first_node]
+    assert names[vgg_first.launch].startswith("conv_mfma")   # a 3x3 first layer keeps the general kernel
+    for L in d.launches():
+        if L.name.decode() != "conv_stem_pool":
+            continue
+        pool = nodes[L.first_node]
+        conv = nodes[L.first_node - 1]
+        assert L.macs_per_image >= conv.macs and L.level == pool.level
+        # the input image (3 channels) and the pooled tensor (64 channels), bf16, for every problem of the launch
+        assert L.bytes_per_image == L.n_problems * 2 * (96 * 96 * 3 + pool.out_h * pool.out_w * 64)
+    assert sum(L.macs_per_image for L in d.launches()) == sum(L.macs_per_image for L in p.launches())
+    assert sum(L.bytes_per_image for L in d.launches()) < sum(L.bytes_per_image for L in p.launches())
+    # a stem whose reader is not that pool keeps a launch of its own, with the stem kernel
+    from workloads import zoo
+    m = zoo.Model("stem_only", "bf16", 3, 64, 64)
+    a = m.add(zoo.CONV, zoo.MODEL_INPUT, cin=3, cout=64, k=7, stride=2, pad=3, act=zoo.RELU)
+    a = m.add(zoo.MAXPOOL, a, k=3, stride=2, pad=0, ceil=True)
+    m.add(zoo.CONV, a, cin=64, cout=16, k=1, stride=1, pad=0, act=zoo.NONE)
+    m.shapes()
+    blob = gen.make_blob(m, 77)
+    spec, k = fi.make_spec(m, blob.ctypes.data, blob.nbytes)
+    alloc = fi.HostAllocators()
+    lone = fi.Dag([spec], 2, alloc, keepalive=[(k, blob)])
+    lnames = [L.name.decode() for L in lone.launches()]
+    assert "conv_stem" in lnames and "maxpool" in lnames and "conv_stem_pool" not in lnames
+    assert lone.nodes()[0].out_bytes > 0
 
 
 def test_member_chunks_shrink_the_activation_arena():
