@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--serial-lanes", action="store_true",
                     help="issue every launch on the caller's stream (no concurrent lanes): the condition the per-kernel "
                          "roofline is measured in, for profiler runs that should show the same durations")
+    ap.add_argument("--separate-stem", action="store_true",
+                    help="fi_build_opts.separate_stem of the timed DAG: the first convolution with the general kernel and the max-pool "
+                         "behind it as a launch of its own (the same bits; for an A/B timing of the stem launch on one box)")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to calibrate rocprofv3 counters)")
     a = ap.parse_args()
@@ -121,7 +124,7 @@ def main():
 
     # ---- fused DAG: timed region ------------------------------------------------------------
     t0 = time.perf_counter()
-    dag = make_dag(members, serial_lanes=a.serial_lanes, member_chunks=a.member_chunks)
+    dag = make_dag(members, serial_lanes=a.serial_lanes, member_chunks=a.member_chunks, separate_stem=a.separate_stem)
     t_build = time.perf_counter() - t0
     torch.cuda.empty_cache()
     free0 = torch.cuda.mem_get_info()[0]
@@ -324,14 +327,15 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "a85c2db3d5641d894851894a5a1f963ac18bea4949a7e33554f60dcea377b679",
+    "sources_sha256": "87ca7deb6b99b49160497fa0d8ff2291f23737900ff16cb98eb99d72d0513626",
     "workload": "cfg4",
     "fetch_scale": 2.0, "write_scale": 1.0,
     "kernels": {   # kernel name -> launches and KiB per step
-        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454738.6, "write_kib_per_step": 2579431.2},
-        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098362.6, "write_kib_per_step": 1618232.7},
-        "conv_mfma_128x64": {"launches_per_step": 8, "fetch_kib_per_step": 101668.2, "write_kib_per_step": 501760.0},
-        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613355.8, "write_kib_per_step": 376320.0},
+        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454863.8, "write_kib_per_step": 2579432.1},
+        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098442.9, "write_kib_per_step": 1618214.3},
+        "conv_mfma_128x64": {"launches_per_step": 4, "fetch_kib_per_step": 50684.2, "write_kib_per_step": 100352.0},
+        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613184.2, "write_kib_per_step": 376320.0},
+        "conv_stem_pool": {"launches_per_step": 4, "fetch_kib_per_step": 53303.1, "write_kib_per_step": 100352.0},
     },
 }
 
@@ -340,7 +344,7 @@ def sources_sha256():
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2410_21120_amd", "csrc")
-    for f in ("fi_internal.h", "fi_device.h", "fi_plan.cpp", "fi_api.cpp", "fi_kernels.hip", "fi_chain.hip"):
+    for f in ("fi_internal.h", "fi_device.h", "fi_plan.cpp", "fi_api.cpp", "fi_kernels.hip", "fi_chain.hip", "fi_stem.hip"):
         with open(os.path.join(csrc, f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()

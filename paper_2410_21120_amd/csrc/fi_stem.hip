@@ -42,7 +42,7 @@ struct Geo {
   static constexpr int NPATCH = PH * PW;
   static constexpr int SLOTS = (NPATCH + 255) / 256;                    // patch pixels a thread brings in
   static constexpr int PATCH_BYTES = PH * ROWB;
-  static constexpr int ZERO_AT = PATCH_BYTES;                           // 16 zero bytes: taps past the filter, patch slots past the patch
+  static constexpr int ZERO_AT = (PATCH_BYTES + 15) / 16 * 16;          // 16 zero bytes: taps past the filter, patch slots past the patch
   static constexpr int BIAS_AT = ZERO_AT + 16;
   static constexpr int WLDS_AT = BIAS_AT + CO * 4;                      // weight fragments of steps KREG.., [step][32-channel block][lane]
   static constexpr int OUT_AT = WLDS_AT + (KSTEPS - KREG) * 2 * 64 * 16;
@@ -50,6 +50,7 @@ struct Geo {
   static constexpr int TPH = 7, TPW = 8;                                // pooled pixels per block
   static_assert((PW + 1) / 2 <= HALF, "a patch row fits its two planes");
   static_assert(NPX <= 256, "eight 32-pixel blocks");
+  static_assert(OUT_AT % 16 == 0 && WLDS_AT % 16 == 0 && BIAS_AT % 16 == 0, "16-byte LDS accesses are aligned");
   static_assert(KSTEPS - KREG <= 4, "one wave parks one step's fragments");
   static_assert(PW < 255, "patch columns fit 8 bits");
 };
@@ -141,7 +142,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
       if (hg == G::CH) { cy = l16; cx = G::CW - 1; real = l16 < G::CH; }
       cy = real ? cy : 0;
     }
-    out_at[i] = (real ? cy * G::CW + cx : 255) * OS * 2;   // the pixel's row in the LDS output tile (row 255: nobody reads it)
+    out_at[i] = (real ? cy * G::CW + cx : 255) * (OS / 8); // the pixel's row in the LDS output tile, in 16-byte pieces (row 255: nobody reads it)
     const int w0 = (SS * cy) * G::ROWB + cx * 8;   // (stride 2: output column cx starts at patch column 2 cx, element cx of the even plane)
     win[i][0] = w0 + (upper ? tap_offset<POOL>(2) - tap_offset<POOL>(0) : 0);
     win[i][1] = w0 + (upper ? tap_offset<POOL>(7) - tap_offset<POOL>(5) : 0);
@@ -277,7 +278,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           const u32x4 q = {frag[half][0], frag[half][1], frag[half][2], frag[half][3]};
-          *reinterpret_cast<u32x4*>(smem + G::OUT_AT + out_at[i] + (j * 32 + 16 * half + (upper ? 8 : 0)) * 2) = q;
+          reinterpret_cast<u32x4*>(smem + G::OUT_AT)[out_at[i] + j * 4 + 2 * half + (upper ? 1 : 0)] = q;
         }
       }
     }
@@ -294,7 +295,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
           const int px = v >> 3, c8 = (v & 7) * 8;
           const int cy = cy0 + px / G::CW, cx = cx0 + px % G::CW;
           const bool ok = cy < Hc && cx < Wc;
-          const u32x4 q = *reinterpret_cast<const u32x4*>(smem + G::OUT_AT + (px * OS + c8) * 2);
+          const u32x4 q = reinterpret_cast<const u32x4*>(smem + G::OUT_AT)[px * (OS / 8) + (v & 7)];
           const uint32_t off = ok ? (uint32_t)((((n * Hc + cy) * Wc + cx) * CO + c8) * 2) : OOB;
           if (stream_out) __builtin_amdgcn_raw_buffer_store_b128(q, yres, off, 0, 2);
           else __builtin_amdgcn_raw_buffer_store_b128(q, yres, off, 0, 0);
@@ -315,8 +316,8 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
           int row_at[3], col_at[3];
 #pragma unroll
           for (int r = 0; r < 3; ++r) {
-            row_at[r] = min(max(2 * ph + r, ly_lo), ly_hi) * (G::CW * OS * 2);
-            col_at[r] = min(max(2 * pw + r, lx_lo), lx_hi) * (OS * 2) + c8 * 2;
+            row_at[r] = min(max(2 * ph + r, ly_lo), ly_hi) * (G::CW * OS / 8);   // (16-byte pieces)
+            col_at[r] = min(max(2 * pw + r, lx_lo), lx_hi) * (OS / 8) + (v & 7);
           }
           float best[8];
 #pragma unroll
@@ -325,7 +326,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
           for (int r = 0; r < 3; ++r)
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-              const u32x4 q = *reinterpret_cast<const u32x4*>(smem + G::OUT_AT + row_at[r] + col_at[s]);
+              const u32x4 q = reinterpret_cast<const u32x4*>(smem + G::OUT_AT)[row_at[r] + col_at[s]];
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
                 best[2 * e] = fmaxf(best[2 * e], __uint_as_float(q[e] << 16));
