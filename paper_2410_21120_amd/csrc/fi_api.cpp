@@ -473,7 +473,7 @@ static void form_chains(fi_dag* g) {
 // Planner pass, after form_chains: the first convolution of an ImageNet-style member.  A 7x7 stride-2 convolution over the
 // 4-channel model input with 64 output channels (bf16 in and out, identity / ReLU / ReLU6) takes the stem kernel, which
 // multiplies from an input patch in LDS instead of gathering reduction vectors from memory.  When its ONLY reader is a
-// 3x3 stride-2 padding-1 max-pool (floor mode), that pool is part of the same launch: the pool node carries the launch,
+// 3x3 stride-2 max-pool (padding 0 or 1, floor or ceil mode), that pool is part of the same launch: the pool node carries the launch,
 // the convolution gets none and its output is stored nowhere.  Same bits as the general kernels either way.
 static void take_stem_launches(fi_dag* g) {
   if (g->opts.separate_stem || g->wdtype != FI_BF16) return;
@@ -496,11 +496,15 @@ static void take_stem_launches(fi_dag* g) {
   }
   for (int32_t i = 0; i < total; ++i) {
     Node& P = g->nodes[(size_t)i];
-    if (P.kind != K_MAXPOOL || P.input < 0 || P.k != 3 || P.stride != 2 || P.pad != 1) continue;
+    if (P.kind != K_MAXPOOL || P.input < 0 || P.k != 3 || P.stride != 2 || P.pad < 0 || P.pad > 1) continue;
     Node& A = g->nodes[(size_t)P.input];
     if (A.kind != K_STEM || uses[(size_t)P.input] != 1) continue;
-    if (P.is_output || P.root >= 0 || P.elided || P.out_dtype != FI_BF16 || P.Cp != 64 || P.Cop != 64 || P.run != A.run + 1) continue;
-    if (P.Ho != (A.Ho + 2 - 3) / 2 + 1 || P.Wo != (A.Wo + 2 - 3) / 2 + 1) continue;   // (a ceil-mode pool keeps its own launch)
+    if (P.is_output || P.elided || P.out_dtype != FI_BF16 || P.Cp != 64 || P.Cop != 64 || P.run != A.run + 1) continue;
+    // (the pooled tensor may be stored inside a concatenation's, as the first tensor of a DenseNet block is: the launch writes
+    // it at that tensor's pixel stride, which has to stay within the kernel's 32-bit offsets)
+    if (P.root >= 0 && B * P.Ho * P.Wo * (uint64_t)g->nodes[(size_t)P.root].Cop * 2 >= (1ull << 31)) continue;
+    // floor or ceil mode: all the kernel needs is that every window starts inside the convolution's output
+    if ((P.Ho - 1) * 2 - P.pad >= A.Ho || (P.Wo - 1) * 2 - P.pad >= A.Wo) continue;
     P.pre = P.input;
     P.kind = K_STEM;
     P.tile = 1;
@@ -1013,7 +1017,9 @@ static void fill_descriptors(fi_dag* g) {
         d.H = cv.H; d.W = cv.W; d.C = cv.C; d.Cp = cv.Cp; d.xs = cv.Cp;
         d.k = cv.k; d.kw = cv.kw; d.stride = cv.stride; d.pad = cv.pad; d.pad_w = cv.pad_w; d.act = cv.act; d.Kp = cv.Kp;
         d.gin = cv.Ho; d.gout = cv.Wo;
-        d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop; d.ys = nd.Cop;
+        d.pre_act = L.tile == 1 ? nd.pad : 0;   // (with the pool: its padding)
+        d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop;
+        d.ys = nd.root >= 0 ? g->nodes[(size_t)nd.root].Cop : nd.Cop;
         d.splits = 1;
         d.ws_off = kNone;
         // workgroups walk several pixel blocks: as many as stay resident together (two per compute unit), over the launch's

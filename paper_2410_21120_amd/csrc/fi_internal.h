@@ -82,7 +82,7 @@ struct Desc {
   uint64_t pw_off, pb_off;       // MFMA conv with a stage on its input side.  pre_kind 1, per-channel affine: scale (bf16 [Cp]) and
                                  // shift (fp32 [Cp]) in the weight arena.  pre_kind 2, per-(image, channel) gate: pw_off is the gate
                                  // tensor [batch][Cp] (bf16) in the activation region.  kNone where unused
-  int32_t pre_act, pre_kind;     // activation of the affine stage; 0 = no stage
+  int32_t pre_act, pre_kind;     // activation of the affine stage; 0 = no stage.  Stem launch with the pool: pre_act is the pool's padding
 };
 static_assert(sizeof(Desc) == 168, "Desc is 168 bytes");
 

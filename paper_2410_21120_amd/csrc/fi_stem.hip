@@ -66,7 +66,8 @@ __device__ __forceinline__ constexpr int tap_offset(int tap) {
 
 // One descriptor per problem.  Convolution fields as for any convolution (H, W, Cp = 4, k = kw = 7, stride 2, pad,
 // pad_w, act, w_off, b_off, Kp = 224); gin x gout is the convolution's output (height x width); Ho x Wo is what is
-// stored at y_off: the same without the pool, the pooled size with it; tiles_n = workgroups that share the problem.
+// stored at y_off: the same without the pool, the pooled size with it (3x3 windows, stride 2, padding pre_act = 0 or 1,
+// every window starting inside the convolution's output: floor or ceil mode); tiles_n = workgroups that share the problem.
 // CLAMP6: the launch holds a ReLU6 (otherwise the upper clamp is not applied at all).
 template <bool POOL, bool CLAMP6>
 __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
@@ -77,6 +78,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
   const Desc d = a.d[p];
   const int batch = a.batch[p];
   const int Hc = d.gin, Wc = d.gout;
+  const int pool_pad = d.pre_act;             // (with the pool: its padding, 0 or 1)
   const int ty = POOL ? (d.Ho + G::TPH - 1) / G::TPH : (Hc + G::CH - 1) / G::CH;
   const int tx = POOL ? (d.Wo + G::TPW - 1) / G::TPW : (Wc + G::CW - 1) / G::CW;
   const int ntiles = batch * ty * tx;
@@ -89,8 +91,9 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
   const int image_bytes = d.H * d.W * 8;
   const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(a.wbase + d.w_off), 0, CO * STEM_KP * 2, 0x00020000);
+  // (the stored tensor may sit inside a concatenation's: its pixels are then ys, not 64, channels apart)
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
-      a.abase + d.y_off, 0, batch > 0 ? (int)((int64_t)batch * d.Ho * d.Wo * CO * 2) : 0, 0x00020000);
+      a.abase + d.y_off, 0, batch > 0 ? (int)((((int64_t)batch * d.Ho * d.Wo - 1) * d.ys + CO) * 2) : 0, 0x00020000);
   const bool stream_out = (int64_t)batch * d.Ho * d.Wo * CO * 2 > (int64_t)STREAM_OUT_BYTES;
 
   // the weights: the MFMA operand fragments of every reduction step, for both 32-channel blocks
@@ -172,7 +175,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
   }
   // first convolution output of block (by, bx)
 #define FI_ORIGIN(CY0, CX0)                                                                       \
-  const int CY0 = POOL ? by * G::TPH * 2 - 1 : by * G::CH, CX0 = POOL ? bx * G::TPW * 2 - 1 : bx * G::CW;
+  const int CY0 = POOL ? by * G::TPH * 2 - pool_pad : by * G::CH, CX0 = POOL ? bx * G::TPW * 2 - pool_pad : bx * G::CW;
   // The patch of block (n, by, bx) through a buffer resource that covers image n alone: a row above or below the image
   // is out of its range and reads zero by itself; a column left or right of the image would land in a neighbouring row
   // and takes the out-of-range offset.  (LIVE false: an empty resource, everything reads zero.)
@@ -296,7 +299,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
           const int cy = cy0 + px / G::CW, cx = cx0 + px % G::CW;
           const bool ok = cy < Hc && cx < Wc;
           const u32x4 q = reinterpret_cast<const u32x4*>(smem + G::OUT_AT)[px * (OS / 8) + (v & 7)];
-          const uint32_t off = ok ? (uint32_t)((((n * Hc + cy) * Wc + cx) * CO + c8) * 2) : OOB;
+          const uint32_t off = ok ? (uint32_t)((((n * Hc + cy) * Wc + cx) * d.ys + c8) * 2) : OOB;
           if (stream_out) __builtin_amdgcn_raw_buffer_store_b128(q, yres, off, 0, 2);
           else __builtin_amdgcn_raw_buffer_store_b128(q, yres, off, 0, 0);
         }
@@ -304,7 +307,8 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
         // 7 x 8 pooled pixels x eight 8-channel vectors.  The taps of a window in (row, column) order, combined with the
         // pooling kernel's operation.  A tap outside the convolution's output (the pool's padding) is not skipped but
         // moved onto the nearest row / column inside it, which lies in the same window: the maximum sees one of its
-        // values twice and is the same.  (Positions relative to the block: rows ly_lo..ly_hi, columns lx_lo..lx_hi exist.)
+        // values twice and is the same; so is a tap that hangs over the far border in ceil mode.  (Positions relative to
+        // the block: rows ly_lo..ly_hi, columns lx_lo..lx_hi exist.)
         const int ly_lo = cy0 < 0 ? -cy0 : 0, ly_hi = min(G::CH - 1, Hc - 1 - cy0);
         const int lx_lo = cx0 < 0 ? -cx0 : 0, lx_hi = min(G::CW - 1, Wc - 1 - cx0);
 #pragma unroll
@@ -340,7 +344,7 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
           const int oy = by * G::TPH + ph, ox = bx * G::TPW + pw;
           const bool st_ok = live && oy < d.Ho && ox < d.Wo;
           late[j] = o;
-          late_off[j] = st_ok ? (uint32_t)((((n * d.Ho + oy) * d.Wo + ox) * CO + c8) * 2) : OOB;
+          late_off[j] = st_ok ? (uint32_t)((((n * d.Ho + oy) * d.Wo + ox) * d.ys + c8) * 2) : OOB;
         }
       }
     }
@@ -376,14 +380,17 @@ int launch_stem(const Launch& L, const KArgs& args, void* stream, const std::vec
     const Desc& t = hd[(size_t)(L.first_desc + i)];
     a.d[i] = t;
     // what the kernel takes for granted
-    if (t.k != SK || t.kw != SK || t.stride != SS || t.Cp != 4 || t.Kp != STEM_KP || t.Co != CO || t.Cop != CO || t.ys != CO || t.xs != 4 ||
+    if (t.k != SK || t.kw != SK || t.stride != SS || t.Cp != 4 || t.Kp != STEM_KP || t.Co != CO || t.Cop != CO || t.ys < CO || t.ys % 8 || t.xs != 4 ||
         t.act < 0 || t.act > FI_ACT_RELU6 || t.ext || t.out_f32 || t.splits != 1 || t.r_off != kNone || t.tiles_n < 1 ||
         t.pad < 0 || t.pad > 3 || t.pad_w < 0 || t.pad_w > 3 || t.x_off == kNone || t.y_off == kNone || t.w_off == kNone || t.b_off == kNone)
       return (int)hipErrorInvalidValue;
     if (t.gin != (t.H + 2 * t.pad - SK) / SS + 1 || t.gout != (t.W + 2 * t.pad_w - SK) / SS + 1 || t.gin < 1 || t.gout < 1) return (int)hipErrorInvalidValue;
-    if (L.tile == 1 ? (t.Ho != (t.gin + 2 - 3) / 2 + 1 || t.Wo != (t.gout + 2 - 3) / 2 + 1) : (t.Ho != t.gin || t.Wo != t.gout)) return (int)hipErrorInvalidValue;
+    if (L.tile == 1) {   // every pooling window starts inside the convolution's output
+      if (t.pre_act < 0 || t.pre_act > 1 || t.Ho < 1 || t.Wo < 1 || (t.Ho - 1) * 2 - t.pre_act >= t.gin || (t.Wo - 1) * 2 - t.pre_act >= t.gout)
+        return (int)hipErrorInvalidValue;
+    } else if (t.Ho != t.gin || t.Wo != t.gout) return (int)hipErrorInvalidValue;
     // 32-bit byte offsets through buffer resources
-    if ((uint64_t)a.batch[i] * t.H * t.W * 8 >= (1ull << 31) || (uint64_t)a.batch[i] * t.Ho * t.Wo * CO * 2 >= (1ull << 31)) return (int)hipErrorInvalidValue;
+    if ((uint64_t)a.batch[i] * t.H * t.W * 8 >= (1ull << 31) || (uint64_t)a.batch[i] * t.Ho * t.Wo * t.ys * 2 >= (1ull << 31)) return (int)hipErrorInvalidValue;
     blocks += stem_blocks(L.tile, t, a.batch[i]);
     if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
   }

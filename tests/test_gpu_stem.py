@@ -47,8 +47,10 @@ CASES = [
     (224, 224, 3, None, zoo.RELU, 2),        # no pool behind the convolution: the stem kernel alone
     (97, 131, 3, None, zoo.NONE, 3),
     (40, 29, 2, None, zoo.RELU6, 6),
-    (112, 112, 3, "ceil", zoo.RELU, 3),      # a pool the launch does not take (ceil mode, no padding): stem kernel + pooling launch
-    (90, 90, 3, "2x2/2", zoo.RELU, 3),
+    (112, 112, 3, "ceil", zoo.RELU, 3),      # ceil mode without padding (GoogLeNet): the last window hangs over the border
+    (99, 61, 3, "ceil", zoo.NONE, 4),
+    (224, 224, 3, "ceil", zoo.RELU, 2),
+    (90, 90, 3, "2x2/2", zoo.RELU, 3),       # a pool the launch does not take: stem kernel + pooling launch
 ]
 
 
@@ -61,9 +63,9 @@ def test_stem_launch_equals_general_kernels_bitwise_and_meets_the_oracle(h, w, p
     x = gen.make_input(51 + h, batch, 3, h, w, "normal", "bf16")
     fast, names = _run(mem, x)
     plain, pnames = _run(mem, x, separate_stem=True)
-    want = "conv_stem_pool" if pool == "3x3/2" else "conv_stem"
+    want = "conv_stem_pool" if pool in ("3x3/2", "ceil") else "conv_stem"
     assert want in names and not any(n.startswith("conv_stem") for n in pnames), (names, pnames)
-    if pool == "3x3/2":
+    if pool in ("3x3/2", "ceil"):
         assert "maxpool" not in names and "maxpool" in pnames
     for i, (a, b) in enumerate(zip(fast, plain)):
         assert np.isfinite(a).all()
@@ -102,6 +104,40 @@ def test_stem_launch_under_every_build_option_and_beside_other_members():
         assert np.array_equal(a, b[:4])
     for i in (0, 3):
         harness.check_against_oracle(f"{fams[i][0]} with the stem launch", mem[i][0], mem[i][1], None, x, base[i])
+
+
+def test_stem_launch_writes_its_pooled_tensor_inside_a_concatenation():
+    """The first tensor of a DenseNet block is stored inside the block's concatenation (no concat launch): the stem launch
+    then writes its pooled pixels at that tensor's channel stride."""
+    from tests import harness
+    h, w, batch = 70, 52, 3
+    m = zoo.Model("stem_concat", "bf16", 3, h, w)
+    a = m.add(zoo.CONV, zoo.MODEL_INPUT, cin=3, cout=64, k=7, stride=2, pad=3, act=zoo.RELU)
+    pool = m.add(zoo.MAXPOOL, a, k=3, stride=2, pad=1)
+    b = m.add(zoo.DWCONV, pool, cin=64, cout=64, k=1, stride=1, pad=0, act=zoo.RELU, bn=False)   # (a dense layer: per-channel affine,
+    b = m.add(zoo.CONV, b, cin=64, cout=128, k=1, stride=1, pad=0, act=zoo.RELU)                  # 1x1 squeeze, 3x3 with the new channels)
+    b = m.add(zoo.CONV, b, cin=128, cout=32, k=3, stride=1, pad=1, act=zoo.NONE, bias=False, bn=False)
+    c = m.add(zoo.CONCAT, pool, residual=b)
+    m.add(zoo.CONV, c, cin=96, cout=24, k=1, stride=1, pad=0, act=zoo.NONE)
+    m.shapes()
+    mem = [(m, gen.make_blob(m, 5400 + i), None) for i in range(2)]
+    x = gen.make_input(57, batch, 3, h, w, "normal", "bf16")
+    fast, names = _run(mem, x)
+    plain, pnames = _run(mem, x, separate_stem=True)
+    copied, cnames = _run(mem, x, copy_concats=True)
+    assert "conv_stem_pool" in names and "concat" not in names and "concat" in cnames and "conv_stem_pool" in cnames
+    for a1, b1, c1 in zip(fast, plain, copied):
+        assert np.isfinite(a1).all() and np.array_equal(a1, b1) and np.array_equal(a1, c1)
+    harness.check_against_oracle("stem into a concatenation", m, mem[0][1], None, x, fast[0])
+    # DenseNet-121: the same layout in a whole model
+    dm = zoo.FAMILIES["densenet121"](hw=64)
+    dmem = [(dm, gen.make_blob(dm, 5410 + i), None) for i in range(2)]
+    dx = gen.make_input(58, 2, 3, 64, 64, "normal", "bf16")
+    dfast, dnames = _run(dmem, dx)
+    dplain, _ = _run(dmem, dx, separate_stem=True)
+    assert "conv_stem_pool" in dnames
+    for a1, b1 in zip(dfast, dplain):
+        assert np.array_equal(a1, b1)
 
 
 def test_stem_launch_full_size_batch32_equals_general_kernels():

@@ -681,7 +681,7 @@ def test_stem_launch_takes_the_pool_and_drops_the_first_tensor():
     from workloads import zoo
     m = zoo.Model("stem_only", "bf16", 3, 64, 64)
     a = m.add(zoo.CONV, zoo.MODEL_INPUT, cin=3, cout=64, k=7, stride=2, pad=3, act=zoo.RELU)
-    a = m.add(zoo.MAXPOOL, a, k=3, stride=2, pad=0, ceil=True)
+    a = m.add(zoo.MAXPOOL, a, k=2, stride=2, pad=0)
     m.add(zoo.CONV, a, cin=64, cout=16, k=1, stride=1, pad=0, act=zoo.NONE)
     m.shapes()
     blob = gen.make_blob(m, 77)
