@@ -327,15 +327,15 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "5491a8ee54b02258a9bdacb9e285dc7c88b26dca37f80855758af476748aaaef",
+    "sources_sha256": "685dd29346a878a2d1c6f994a70939e36904f6c66ac7ae89f46e9b2e9cc61ed3",
     "workload": "cfg4",
     "fetch_scale": 2.0, "write_scale": 1.0,
     "kernels": {   # kernel name -> launches and KiB per step
-        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454689.2, "write_kib_per_step": 2579478.1},
-        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098432.9, "write_kib_per_step": 1618223.4},
-        "conv_mfma_128x64": {"launches_per_step": 4, "fetch_kib_per_step": 50683.5, "write_kib_per_step": 100352.0},
-        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613223.4, "write_kib_per_step": 376320.0},
-        "conv_stem_pool": {"launches_per_step": 4, "fetch_kib_per_step": 53305.4, "write_kib_per_step": 100352.0},
+        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454692.3, "write_kib_per_step": 2579447.3},
+        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098647.6, "write_kib_per_step": 1618226.4},
+        "conv_mfma_128x64": {"launches_per_step": 4, "fetch_kib_per_step": 50684.7, "write_kib_per_step": 100352.0},
+        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613000.1, "write_kib_per_step": 376320.0},
+        "conv_stem_pool": {"launches_per_step": 4, "fetch_kib_per_step": 53305.5, "write_kib_per_step": 100352.0},
     },
 }
 

@@ -1,6 +1,6 @@
 // The first convolution of an ImageNet-style member: 7x7, stride 2, over the 4-channel model input, 64 output
 // channels (Section V, Table III: the ResNet, Wide ResNet, ResNeXt, DenseNet and GoogLeNet stems), optionally with
-// the 3x3 stride-2 padding-1 max-pool that alone reads it, in one launch.
+// the 3x3 stride-2 max-pool (padding 0 or 1) that alone reads it, in one launch.
 //
 // The general implicit-GEMM kernel gathers this layer's reduction vectors pixel by pixel from HBM (a 4-channel
 // pixel is 8 bytes, a reduction vector two filter taps) and is bound by that address work.  Here a workgroup owns a

@@ -73,6 +73,32 @@ def test_stem_launch_equals_general_kernels_bitwise_and_meets_the_oracle(h, w, p
     harness.check_against_oracle(f"stem {h}x{w} {pool}", mem[1][0], mem[1][1], None, x, fast[1])
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_stems_equal_general_kernels(seed):
+    """Seeded random image sizes (1 to 5 blocks a side, every remainder), paddings, pools, activations and batches."""
+    rng = np.random.default_rng(9000 + seed)
+    h, w = int(rng.integers(7, 150)), int(rng.integers(7, 150))
+    pad = int(rng.integers(0, 4))
+    pool = [None, "3x3/2", "ceil", "3x3/2"][int(rng.integers(0, 4))]
+    act = [zoo.NONE, zoo.RELU, zoo.RELU6][int(rng.integers(0, 3))]
+    batch = int(rng.integers(1, 6))
+    if pool is not None and (h + 2 * pad - 7) // 2 + 1 < 3:
+        pool = None   # (a pooling window larger than the tensor)
+    if pool is not None and (w + 2 * pad - 7) // 2 + 1 < 3:
+        pool = None
+    print(f"random stem {seed}: {h}x{w} pad {pad} pool {pool} act {act} batch {batch}", flush=True)
+    models = [stem_model(h, w, pad, pool, act) for _ in range(2)]
+    mem = [(m, gen.make_blob(m, 5600 + 2 * seed + i), None) for i, m in enumerate(models)]
+    x = gen.make_input(5700 + seed, batch, 3, h, w, "normal", "bf16")
+    fast, names = _run(mem, x)
+    plain, pnames = _run(mem, x, separate_stem=True)
+    assert any(n.startswith("conv_stem") for n in names) and not any(n.startswith("conv_stem") for n in pnames)
+    for a, b in zip(fast, plain):
+        assert np.isfinite(a).all() and np.array_equal(a, b)
+    from tests import harness
+    harness.check_against_oracle(f"random stem {seed}", mem[0][0], mem[0][1], None, x, fast[0])
+
+
 def test_stem_launch_under_every_build_option_and_beside_other_members():
     """ResNets (stem + pool in one launch) beside a VGG and an fp32-activation MobileNetV2 (general kernels), ungrouped,
     on one stream, as a HIP graph, in member chunks, alone, with fewer images than max_batch: the same bits."""
