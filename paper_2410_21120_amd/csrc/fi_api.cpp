@@ -155,7 +155,7 @@ const char* kind_name(int kind, int tile) {
   switch (kind) {
     case K_STAGE: return "stage_input";
     case K_CONV_DIRECT: return "conv_direct";
-    case K_CONV_MFMA: return tile == T_256x128 ? "conv_mfma_256x128" : tile == T_256x64 ? "conv_mfma_256x64" : tile == T_128x128 ? "conv_mfma_128x128" : tile == T_128x64 ? "conv_mfma_128x64" : "conv_mfma_64x64";
+    case K_CONV_MFMA: return tile == T_256x128 ? "conv_mfma_256x128" : tile == T_256x64 ? "conv_mfma_256x64" : (tile == T_128x128 || tile == T_128x128_DEEP) ? "conv_mfma_128x128" : tile == T_128x64 ? "conv_mfma_128x64" : "conv_mfma_64x64";
     case K_DWCONV: return "dwconv";
     case K_MAXPOOL: return "maxpool";
     case K_GAP: return "global_avgpool";
@@ -509,6 +509,23 @@ static void take_stem_launches(fi_dag* g) {
     P.kind = K_STEM;
     P.tile = 1;
     A.elided = 1;
+  }
+}
+
+// Planner pass, after the passes that fold nodes into convolutions: a plain bf16 convolution on the 128x128 tile whose
+// reduction is long (32 tiles or more) and whose member brings few workgroups (64 at most: with eight members a launch
+// still has at most two per compute unit) keeps three reduction tiles in flight in registers instead of one.  Such a
+// launch has nothing else to hide a load behind; the deeper prefetch costs registers that launches of many workgroups
+// need for residency, so they keep the plain tile.  (The summation order, hence every bit, is the same.)
+static void deepen_long_reductions(fi_dag* g) {
+  if (g->wdtype != FI_BF16) return;
+  const int64_t B = g->opts.max_batch;
+  for (Node& nd : g->nodes) {
+    const int adt = g->members[(size_t)nd.model].spec.act_dtype;
+    if (nd.kind != K_CONV_MFMA || nd.tile != T_128x128 || adt != FI_BF16 || nd.out_dtype != FI_BF16) continue;
+    if (nd.pre >= 0 || nd.elided || nd.chain >= 0 || nd.splits != 1 || nd.Cp == 4 || walks_groups(nd, adt)) continue;
+    const int64_t blocks = ((B * nd.Ho * nd.Wo + 127) / 128) * ((nd.Co + 127) / 128);
+    if (nd.Kp >= 32 * 64 && blocks <= 64) nd.tile = T_128x128_DEEP;
   }
 }
 
@@ -1155,6 +1172,7 @@ static fi_status plan_dag(fi_dag* g) {
   fold_nodes_into_readers(g);
   form_chains(g);
   take_stem_launches(g);
+  deepen_long_reductions(g);
   build_schedule(g);
   plan_activation_arena(g);
   st = place_weights_and_workspace(g);

@@ -42,14 +42,16 @@ enum Kind : int32_t {
 };
 
 // Tile shapes of the MFMA implicit GEMM (rows = output pixels, cols = output channels).
-enum Tile : int32_t { T_128x128 = 0, T_128x64 = 1, T_64x64 = 2, T_256x128 = 3, T_256x64 = 4, T_NTILES };
+// T_128x128_DEEP: the 128x128 tile with three reduction tiles in flight in registers instead of one (long reductions in
+// launches of few workgroups).
+enum Tile : int32_t { T_128x128 = 0, T_128x64 = 1, T_64x64 = 2, T_256x128 = 3, T_256x64 = 4, T_128x128_DEEP = 5, T_NTILES };
 #ifdef __HIPCC__
 #define FI_HD __host__ __device__
 #else
 #define FI_HD
 #endif
 FI_HD inline int tile_bm(int t) { return (t == T_256x128 || t == T_256x64) ? 256 : t == T_64x64 ? 64 : 128; }
-FI_HD inline int tile_bn(int t) { return (t == T_128x128 || t == T_256x128) ? 128 : 64; }
+FI_HD inline int tile_bn(int t) { return (t == T_128x128 || t == T_256x128 || t == T_128x128_DEEP) ? 128 : 64; }
 
 // Problem descriptor: one node of the fused DAG, batch independent, handed to the kernels
 // as launch arguments.  Tensor offsets are relative to the activation region, weight offsets

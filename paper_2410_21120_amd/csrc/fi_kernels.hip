@@ -177,9 +177,13 @@ __device__ __forceinline__ void finish_row4(const KArgs& a, const Desc& d, int p
 // concatenation's tensor, so its pixel stride is Desc.xs.
 // PRE == 2: the input is scaled by a per-(image, channel) gate instead, x' = x * gate[n][c] rounded to bf16 (the
 // scaling node that ends a squeeze-excite block; fp32 product, one rounding: the scaling kernel's operation).
-template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false, int PRE = 0>
+// DEPTH: reduction tiles in flight in registers.  One (a tile's loads overlap the multiply of the tile before) is enough
+// where several workgroups share a compute unit; a launch of few workgroups with a long reduction (one or two per
+// compute unit, nothing else to hide a load behind) takes three, at the price of 64 registers.
+template <int TILE, int BM, int BN, int WGM, int WGN, bool WIDE, bool C4 = false, bool GROUPED = false, int PRE = 0, int DEPTH = 1>
 __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   static_assert(!GROUPED || (!WIDE && !C4), "the group walk exists for bf16 activations with 8-channel vectors");
+  static_assert(DEPTH == 1 || (!WIDE && !C4 && !GROUPED && PRE == 0), "deeper prefetch exists for the plain bf16 convolution");
   static_assert(!PRE || (!C4 && !GROUPED && (!WIDE || PRE == 2)),
                 "input-side stages exist for dense pointwise convolutions: the affine one on bf16 activations, the gate on either");
   constexpr int NT = WGM * WGN * 64;     // threads per workgroup
@@ -298,12 +302,12 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  // One register stage feeds one LDS buffer: fetch one tile ahead, two barriers per tile.
-  u32x4 av[1][AR][AV];
-  uint4 bv[1][BR];
-  uint4 pre_s[1];        // PRE == 1: scale (8 bf16) and shift (8 fp32) of this thread's channels in the tile being fetched
-  float4 pre_t[1][2];
-  uint4 pre_g[1][PRE == 2 ? AR : 1][AV];   // PRE == 2: the gate vectors of this thread's rows
+  // DEPTH register stages feed one LDS buffer: fetch DEPTH tiles ahead, two barriers per tile.
+  u32x4 av[DEPTH][AR][AV];
+  uint4 bv[DEPTH][BR];
+  uint4 pre_s[DEPTH];    // PRE == 1: scale (8 bf16) and shift (8 fp32) of this thread's channels in the tile being fetched
+  float4 pre_t[DEPTH][2];
+  uint4 pre_g[DEPTH][PRE == 2 ? AR : 1][AV];   // PRE == 2: the gate vectors of this thread's rows
   const bool b_tail = (d.Kp % BK) != 0;  // weight rows are padded to 32: the last tile may be half
   const bool one_wrap = c_len >= BK;     // (block-uniform)
 
@@ -379,10 +383,10 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     }                                                                                             \
   }
 
-#define FI_PARK(S)                                                                                \
+#define FI_PARK(S) /* register stage S into the LDS buffer */                                      \
   {                                                                                               \
-    bf16_t* const Ap = As + (S) * STAGE;                                                          \
-    bf16_t* const Bp = Bs + (S) * STAGE;                                                          \
+    bf16_t* const Ap = As;                                                                        \
+    bf16_t* const Bp = Bs;                                                                        \
     _Pragma("unroll") for (int i = 0; i < AR; ++i) {                                              \
       if constexpr (PRE == 2 && !WIDE) {                                                          \
         const uint32_t gw[4] = {pre_g[S][i][0].x, pre_g[S][i][0].y, pre_g[S][i][0].z, pre_g[S][i][0].w}; \
@@ -436,10 +440,10 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
   }
 
   // weights are the first MFMA operand: a lane then holds, for ONE pixel, runs of 4 consecutive channels
-#define FI_MULTIPLY(S)                                                                            \
+#define FI_MULTIPLY()                                                                             \
   {                                                                                               \
-    const bf16_t* const Ap = As + (S) * STAGE;                                                    \
-    const bf16_t* const Bp = Bs + (S) * STAGE;                                                    \
+    const bf16_t* const Ap = As;                                                                  \
+    const bf16_t* const Bp = Bs;                                                                  \
     _Pragma("unroll") for (int kk = 0; kk < BK; kk += 16) {                                       \
       bf16x8 af[AT][MI], bfr[NI];                                                                 \
       const int kof = kk + (lane >> 5) * 8;                                                       \
@@ -456,14 +460,32 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv_mfma_kernel(KArgs a) {
     }                                                                                             \
   }
 
-  FI_FETCH(kt0, 0, kt0 < ntiles)
-  for (int kt = kt0; kt < ntiles; ++kt) {
-    FI_PARK(0)
-    __syncthreads();
-    const bool more = kt + 1 < ntiles;
-    FI_FETCH(kt + 1, 0, more)  // in flight while this tile is multiplied (after the last tile: nothing but out-of-range offsets)
-    FI_MULTIPLY(0)
-    __syncthreads();  // every wave is done with this tile before it is overwritten
+  if constexpr (DEPTH == 1) {
+    FI_FETCH(kt0, 0, kt0 < ntiles)
+    for (int kt = kt0; kt < ntiles; ++kt) {
+      FI_PARK(0)
+      __syncthreads();
+      const bool more = kt + 1 < ntiles;
+      FI_FETCH(kt + 1, 0, more)  // in flight while this tile is multiplied (after the last tile: nothing but out-of-range offsets)
+      FI_MULTIPLY()
+      __syncthreads();  // every wave is done with this tile before it is overwritten
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) { FI_FETCH(kt0 + u, u, kt0 + u < ntiles) }
+    for (int kt = kt0; kt < ntiles; kt += DEPTH) {
+#pragma unroll
+      for (int u = 0; u < DEPTH; ++u) {
+        const int t = kt + u;
+        if (t < ntiles) {   // (block-uniform)
+          FI_PARK(u)
+          __syncthreads();
+          FI_FETCH(t + DEPTH, u, t + DEPTH < ntiles)   // DEPTH tiles ahead: in flight through DEPTH multiplies
+          FI_MULTIPLY()
+          __syncthreads();
+        }
+      }
+    }
   }
 #undef FI_FETCH
 #undef FI_PARK
@@ -1774,7 +1796,9 @@ int launch_kernel(const Launch& L, const KArgs& args, void* stream, const std::v
       if (L.tile == T_256x128) return go(conv_mfma_kernel<T_256x128, 256, 128, 2, 2, false>, nb, 256, a, s);
       if (L.tile == T_256x64) return go(conv_mfma_kernel<T_256x64, 256, 64, 4, 1, false>, nb, 256, a, s);
       if (L.tile == T_128x128) return go(conv_mfma_kernel<T_128x128, 128, 128, 2, 2, false>, nb, 256, a, s);
+      if (L.tile == T_128x128_DEEP) return go(conv_mfma_kernel<T_128x128_DEEP, 128, 128, 2, 2, false, false, false, 0, 3>, nb, 256, a, s);
       if (L.tile == T_128x64) return go(conv_mfma_kernel<T_128x64, 128, 64, 2, 2, false>, nb, 256, a, s);
+      if (L.tile != T_64x64) return (int)hipErrorInvalidValue;
       return go(conv_mfma_kernel<T_64x64, 64, 64, 2, 2, false>, nb, 256, a, s);
     case K_DWCONV: {
       const bool vec = hd[(size_t)L.first_desc].vec != 0;

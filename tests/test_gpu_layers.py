@@ -59,6 +59,32 @@ def test_conv_relu(case, mode):
     _run_case(m, 100 + cin + cout, b, act_dtype="f32" if mode == "bf16_wide" else None)
 
 
+def test_long_reductions_in_small_launches_keep_their_bits():
+    """ResNet-50's last stage in isolation: a 3x3 over 512 channels and a 1x1 over 2048 at 7x7, batch 32, bring 52
+    workgroups each and take the 128x128 tile with three reduction tiles in flight.  At batch 96 the same layers bring
+    148 workgroups and take the plain tile: the first 32 images must come out with the same bits (the reduction order
+    does not depend on the prefetch depth), and meet the oracle."""
+    from tests import harness
+    m = zoo.Model("stage4", "bf16", 512, 7, 7)
+    a = m.add(zoo.CONV, -1, cin=512, cout=512, k=3, stride=1, pad=1, act=zoo.RELU)
+    a = m.add(zoo.CONV, a, cin=512, cout=2048, k=1, stride=1, pad=0, act=zoo.RELU)
+    a = m.add(zoo.CONV, a, cin=2048, cout=512, k=1, stride=1, pad=0, act=zoo.RELU)
+    m.add(zoo.CONV, a, cin=512, cout=24, k=1, stride=1, pad=0, act=zoo.NONE)
+    m.shapes()
+    blob = gen.make_blob(m, 777)
+    x = gen.make_input(778, 96, 512, 7, 7, "normal", "bf16")
+    outs = {}
+    for batch in (32, 96, 31):   # (31: a ragged last tile under the deep prefetch)
+        g = harness.GpuDag([(m, blob, None)], batch)
+        try:
+            outs[batch] = g.run(x[:batch])[0]
+        finally:
+            g.close()
+    assert np.isfinite(outs[32]).all()
+    assert np.array_equal(outs[32], outs[96][:32]) and np.array_equal(outs[31], outs[96][:31])
+    harness.check_against_oracle("last-stage layers, deep prefetch", m, blob, None, x[:32], outs[32], rows=[0, 7, 31])
+
+
 @pytest.mark.parametrize("case", [(128, 128, 3, 1, 1, 127, 129, 4),   # 256x128 tile: long reduction, ragged last tile
                                   (64, 64, 3, 1, 1, 127, 129, 4),     # 256x64 tile: narrow, long reduction
                                   (256, 128, 1, 1, 0, 127, 129, 4)])  # 128x128 tile, pointwise prologue
