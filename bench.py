@@ -327,15 +327,15 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "685dd29346a878a2d1c6f994a70939e36904f6c66ac7ae89f46e9b2e9cc61ed3",
+    "sources_sha256": "2397886b7785f01fa8f8c9a3d7367fc7eda9c420280a492f56fbf514e6395a23",
     "workload": "cfg4",
     "fetch_scale": 2.0, "write_scale": 1.0,
     "kernels": {   # kernel name -> launches and KiB per step
-        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454692.3, "write_kib_per_step": 2579447.3},
-        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098647.6, "write_kib_per_step": 1618226.4},
-        "conv_mfma_128x64": {"launches_per_step": 4, "fetch_kib_per_step": 50684.7, "write_kib_per_step": 100352.0},
-        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613000.1, "write_kib_per_step": 376320.0},
-        "conv_stem_pool": {"launches_per_step": 4, "fetch_kib_per_step": 53305.5, "write_kib_per_step": 100352.0},
+        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454786.0, "write_kib_per_step": 2579434.9},
+        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098419.3, "write_kib_per_step": 1618221.1},
+        "conv_mfma_128x64": {"launches_per_step": 4, "fetch_kib_per_step": 50695.0, "write_kib_per_step": 100352.0},
+        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 614266.5, "write_kib_per_step": 376320.0},
+        "conv_stem_pool": {"launches_per_step": 4, "fetch_kib_per_step": 53305.2, "write_kib_per_step": 100352.0},
     },
 }
 
