@@ -175,9 +175,10 @@ typedef struct {
                               * of their peak) run for one chunk of ceil(members / c) members after the other, the deeper levels for
                               * all members together as ever: the chunks' early tensors share memory, so the activation arena shrinks,
                               * at the price of more, smaller launches.  The outputs are the same bits either way. */
-  int32_t separate_stem;     /* 0: a 7x7 stride-2 convolution over the model input with 64 output channels (the first layer of the
-                              * ResNet-style families) runs from an input patch held on chip, and a 3x3 stride-2 max-pool (padding 0
-                              * or 1) that alone reads it runs in the same launch (the convolution's output is stored nowhere); 1: the
+  int32_t separate_stem;     /* 0: a 7x7 stride-2, 3x3 stride-1 or 3x3 stride-2 convolution over the model input with 64 output channels
+                              * (the first layer of the ResNet-style families, of VGG, of SqueezeNet 1.1) runs from an input patch held on
+                              * chip, and a 3x3 stride-2 max-pool (padding 0 or 1) that alone reads a stride-2 one runs in the same launch
+                              * (the convolution's output is stored nowhere); 1: the
                               * general convolution kernel and a pooling launch of its own.  The outputs are the same bits either way. */
   int32_t reserved0;
 } fi_build_opts;

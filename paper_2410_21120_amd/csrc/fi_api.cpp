@@ -167,7 +167,7 @@ const char* kind_name(int kind, int tile) {
     case K_MUL: return "channel_scale";
     case K_GATHER: return "channel_gather";
     case K_CHAIN: return tile ? "conv_chain3" : "conv_chain2";
-    case K_STEM: return tile ? "conv_stem_pool" : "conv_stem";
+    case K_STEM: return (tile & 1) ? "conv_stem_pool" : "conv_stem";
   }
   return "?";
 }
@@ -470,8 +470,8 @@ static void form_chains(fi_dag* g) {
   }
 }
 
-// Planner pass, after form_chains: the first convolution of an ImageNet-style member.  A 7x7 stride-2 convolution over the
-// 4-channel model input with 64 output channels (bf16 in and out, identity / ReLU / ReLU6) takes the stem kernel, which
+// Planner pass, after form_chains: the first convolution of an ImageNet-style member.  A 7x7 stride-2, 3x3 stride-1 or 3x3
+// stride-2 convolution over the 4-channel model input with 64 output channels (bf16 in and out, identity / ReLU / ReLU6) takes the stem kernel, which
 // multiplies from an input patch in LDS instead of gathering reduction vectors from memory.  When its ONLY reader is a
 // 3x3 stride-2 max-pool (padding 0 or 1, floor or ceil mode), that pool is part of the same launch: the pool node carries the launch,
 // the convolution gets none and its output is stored nowhere.  Same bits as the general kernels either way.
@@ -487,18 +487,20 @@ static void take_stem_launches(fi_dag* g) {
   for (Node& A : g->nodes) {
     const int adt = g->members[(size_t)A.model].spec.act_dtype;
     if (A.kind != K_CONV_MFMA || A.op != FI_CONV2D || adt != FI_BF16 || A.out_dtype != FI_BF16 || A.input >= 0 || A.residual >= 0) continue;
-    if (A.Cp != 4 || A.k != 7 || A.kw != 7 || A.stride != 2 || A.pad < 0 || A.pad > 3 || A.pad_w < 0 || A.pad_w > 3) continue;
-    if (A.Co != 64 || A.Cop != 64 || A.Kp != 224 || A.groups != 1 || A.act > FI_ACT_RELU6) continue;
+    const int geom = stem_geometry(A.k, A.kw, A.stride);
+    if (A.Cp != 4 || geom < 0 || A.pad < 0 || A.pad > A.k / 2 || A.pad_w < 0 || A.pad_w > A.k / 2) continue;
+    if (A.H + 2 * A.pad < A.k || A.W + 2 * A.pad_w < A.k) continue;
+    if (A.Co != 64 || A.Cop != 64 || A.Kp != (A.k * A.k * 4 + 31) / 32 * 32 || A.groups != 1 || A.act > FI_ACT_RELU6) continue;
     if (A.is_output || A.root >= 0 || A.elided || A.pre >= 0 || A.chain >= 0 || A.splits != 1) continue;
     if (B * A.Ho * A.Wo * 64 * 2 >= (1ull << 31)) continue;   // the kernel's 32-bit output offsets
     A.kind = K_STEM;
-    A.tile = 0;
+    A.tile = 2 * geom;
   }
   for (int32_t i = 0; i < total; ++i) {
     Node& P = g->nodes[(size_t)i];
     if (P.kind != K_MAXPOOL || P.input < 0 || P.k != 3 || P.stride != 2 || P.pad < 0 || P.pad > 1) continue;
     Node& A = g->nodes[(size_t)P.input];
-    if (A.kind != K_STEM || uses[(size_t)P.input] != 1) continue;
+    if (A.kind != K_STEM || A.stride != 2 || uses[(size_t)P.input] != 1) continue;
     if (P.is_output || P.elided || P.out_dtype != FI_BF16 || P.Cp != 64 || P.Cop != 64 || P.run != A.run + 1) continue;
     // (the pooled tensor may be stored inside a concatenation's, as the first tensor of a DenseNet block is: the launch writes
     // it at that tensor's pixel stride, which has to stay within the kernel's 32-bit offsets)
@@ -507,7 +509,7 @@ static void take_stem_launches(fi_dag* g) {
     if ((P.Ho - 1) * 2 - P.pad >= A.Ho || (P.Wo - 1) * 2 - P.pad >= A.Wo) continue;
     P.pre = P.input;
     P.kind = K_STEM;
-    P.tile = 1;
+    P.tile = A.tile | 1;
     A.elided = 1;
   }
 }
@@ -1026,7 +1028,7 @@ static void fill_descriptors(fi_dag* g) {
       const int adt = g->members[(size_t)nd.model].spec.act_dtype;
       Desc& d = g->descs[(size_t)(L.first_desc + s)];
       if (L.kind == K_STEM) {   // the convolution's fields (the node itself, or the one in front of the pool that carries the launch)
-        const Node& cv = L.tile == 1 ? g->nodes[(size_t)nd.pre] : nd;
+        const Node& cv = (L.tile & 1) ? g->nodes[(size_t)nd.pre] : nd;
         d.x_off = g->stages[(size_t)g->members[(size_t)nd.model].stage].off;
         d.y_off = nd.out_off;
         d.r_off = d.pw_off = d.pb_off = kNone;
@@ -1034,7 +1036,7 @@ static void fill_descriptors(fi_dag* g) {
         d.H = cv.H; d.W = cv.W; d.C = cv.C; d.Cp = cv.Cp; d.xs = cv.Cp;
         d.k = cv.k; d.kw = cv.kw; d.stride = cv.stride; d.pad = cv.pad; d.pad_w = cv.pad_w; d.act = cv.act; d.Kp = cv.Kp;
         d.gin = cv.Ho; d.gout = cv.Wo;
-        d.pre_act = L.tile == 1 ? nd.pad : 0;   // (with the pool: its padding)
+        d.pre_act = (L.tile & 1) ? nd.pad : 0;   // (with the pool: its padding)
         d.Ho = nd.Ho; d.Wo = nd.Wo; d.Co = nd.Co; d.Cop = nd.Cop;
         d.ys = nd.root >= 0 ? g->nodes[(size_t)nd.root].Cop : nd.Cop;
         d.splits = 1;

@@ -36,8 +36,9 @@ enum Kind : int32_t {
   K_MUL = 11,         // per-(image, channel) gate
   K_GATHER = 12,      // channel slice (stride == 0: channels from pad on) or shuffle (stride == 1: k groups)
   K_CHAIN = 13,       // a convolution and the one or two pointwise convolutions behind it, per 128-pixel tile, in one launch
-  K_STEM = 14,        // the 7x7 stride-2 convolution over the 4-channel model input, from an input patch in LDS (tile 0), or that
-                      // convolution and the 3x3 stride-2 max-pool that alone reads it (tile 1: the pool node carries the launch)
+  K_STEM = 14,        // a 7x7 stride-2, 3x3 stride-1 or 3x3 stride-2 convolution over the 4-channel model input, from an input patch
+                      // in LDS (tile bit 0 clear), or a stride-2 one and the 3x3 stride-2 max-pool that alone reads it (tile bit 0
+                      // set: the pool node carries the launch); tile bits 1.. = which convolution
   K_NKINDS
 };
 
@@ -185,6 +186,7 @@ int launch_chain(const Launch& L, const KArgs& a, void* stream, const std::vecto
 // Implemented in fi_stem.hip: a K_STEM launch, and the workgroups one of its problems takes.  Returns a hipError_t as int.
 int launch_stem(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);
 int stem_blocks(int tile, const Desc& d, int batch);
+int stem_geometry(int k, int kw, int stride);   // the geometry bits of a stem launch's tile field (tile = 2 * geometry + pool), -1 = none
 
 // Implemented in fi_kernels.hip.  Returns a hipError_t as int; `stream` is a hipStream_t.
 int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);

@@ -1,13 +1,14 @@
-// The first convolution of an ImageNet-style member: 7x7, stride 2, over the 4-channel model input, 64 output
-// channels (Section V, Table III: the ResNet, Wide ResNet, ResNeXt, DenseNet and GoogLeNet stems), optionally with
-// the 3x3 stride-2 max-pool (padding 0 or 1) that alone reads it, in one launch.
+// The first convolution of an ImageNet-style member, over the 4-channel model input, 64 output channels (Section V,
+// Table III): 7x7 stride 2 (the ResNet, Wide ResNet, ResNeXt, DenseNet and GoogLeNet stems), 3x3 stride 1 (VGG) or
+// 3x3 stride 2 (SqueezeNet 1.1); a stride-2 one optionally with the 3x3 stride-2 max-pool (padding 0 or 1) that alone
+// reads it, in one launch.
 //
 // The general implicit-GEMM kernel gathers this layer's reduction vectors pixel by pixel from HBM (a 4-channel
 // pixel is 8 bytes, a reduction vector two filter taps) and is bound by that address work.  Here a workgroup owns a
 // two-dimensional block of output pixels, brings the input patch under it into LDS once (rows of contiguous pixels,
-// even and odd columns in planes of their own so that the stride-2 reads of neighbouring output pixels are
+// for stride 2 even and odd columns in planes of their own so that the reads of neighbouring output pixels are
 // contiguous), and feeds the matrix cores straight from the patch: no im2col tile exists anywhere.  The 64 x 196
-// weights stay in registers as MFMA operands for as long as the workgroup lives, and a workgroup walks several
+// (or 64 x 36) weights stay in registers as MFMA operands for as long as the workgroup lives, and a workgroup walks several
 // pixel blocks (the next block's patch is requested before the current block is multiplied).
 //
 // The reduction order is the general kernel's (taps row-major, 4 channels per tap, 16 elements per MFMA, ascending),
@@ -20,25 +21,27 @@
 namespace fi {
 namespace {
 
-constexpr int SK = 7;            // filter side
-constexpr int SS = 2;            // stride
-constexpr int STEM_KP = 224;     // packed weight row: 49 taps x 4 channels, rounded up to 32 elements
-constexpr int KSTEPS = 13;       // 16-element reduction steps that hold a real tap (the last real element is 195)
-constexpr int KREG = 12;         // steps whose weight fragments stay in registers; the others wait in LDS (the registers they
-                                 // would take are the ones the tile loop is short of)
 constexpr int CO = 64;           // output channels
 constexpr int OS = 72;           // bf16 elements per pixel row of the LDS output tile (144 bytes: 16-byte reads hit all banks)
 
-template <bool POOL>
+// SK: filter side, SS: stride.
+template <int SK, int SS, bool POOL>
 struct Geo {
+  static constexpr int LAST_TAP = SK * SK - 1;
+  static constexpr int KP = (SK * SK * 4 + 31) / 32 * 32;               // packed weight row: 4 channels per tap, rounded up to 32 elements
+  static constexpr int KSTEPS = (SK * SK * 4 + 15) / 16;                // 16-element reduction steps that hold a real tap
+  // steps whose weight fragments stay in registers; the others wait in LDS (the registers they would take are the ones
+  // the tile loop is short of)
+  static constexpr int KREG = KSTEPS < 12 ? KSTEPS : 12;
   // convolution outputs one block covers: with the pool, 15 x 17 of them are what 7 x 8 pooled pixels read
   static constexpr int CH = POOL ? 15 : 16, CW = POOL ? 17 : 16;
   static constexpr int NPX = CH * CW;                                   // <= 256: eight 32-pixel MFMA column blocks
   static constexpr int PH = (CH - 1) * SS + SK, PW = (CW - 1) * SS + SK;  // the input patch under them
-  static constexpr int HALF = 20;                                       // pixels per plane row (>= (PW + 1) / 2)
-  // bytes per patch row: even-column plane, odd-column plane.  With the pool 8 bytes more: the lanes that take the block's
-  // 17th column read one pixel per row, and rows 656 instead of 640 bytes apart spread them over the banks.
-  static constexpr int ROWB = 2 * HALF * 8 + (POOL ? 8 : 0);
+  // Stride 2: a patch row is an even-column plane and an odd-column plane of HALF pixels each.  With the pool 8 bytes more:
+  // the lanes that take the block's 17th column read one pixel per row, and rows 656 instead of 640 bytes apart spread
+  // them over the banks.  Stride 1: the pixels of a row in their order.
+  static constexpr int HALF = ((PW + 1) / 2 + 3) / 4 * 4;
+  static constexpr int ROWB = SS == 2 ? 2 * HALF * 8 + (POOL ? 8 : 0) : (PW * 8 + 15) / 16 * 16;
   static constexpr int NPATCH = PH * PW;
   static constexpr int SLOTS = (NPATCH + 255) / 256;                    // patch pixels a thread brings in
   static constexpr int PATCH_BYTES = PH * ROWB;
@@ -46,8 +49,12 @@ struct Geo {
   static constexpr int BIAS_AT = ZERO_AT + 16;
   static constexpr int WLDS_AT = BIAS_AT + CO * 4;                      // weight fragments of steps KREG.., [step][32-channel block][lane]
   static constexpr int OUT_AT = WLDS_AT + (KSTEPS - KREG) * 2 * 64 * 16;
+  // where pixel (pr, pc) of the patch sits in LDS
+  static constexpr int at(int pr, int pc) { return SS == 2 ? pr * ROWB + (pc & 1) * HALF * 8 + (pc >> 1) * 8 : pr * ROWB + pc * 8; }
   static constexpr int LDS_BYTES = OUT_AT + 256 * OS * 2;
   static constexpr int TPH = 7, TPW = 8;                                // pooled pixels per block
+  static_assert(SS == 1 || SS == 2, "strides 1 and 2");
+  static_assert(!POOL || SS == 2, "the pool's block geometry is the stride-2 one");
   static_assert((PW + 1) / 2 <= HALF, "a patch row fits its two planes");
   static_assert(NPX <= 256, "eight 32-pixel blocks");
   static_assert(OUT_AT % 16 == 0 && WLDS_AT % 16 == 0 && BIAS_AT % 16 == 0, "16-byte LDS accesses are aligned");
@@ -55,23 +62,19 @@ struct Geo {
   static_assert(PW < 255, "patch columns fit 8 bits");
 };
 
-// Byte offset of filter tap `tap` (row-major) from an output pixel's window origin in the LDS patch, -1 for the
-// taps that pad the reduction to a multiple of 16 elements (their weights are zero; they must read zero).
-template <bool POOL>
-__device__ __forceinline__ constexpr int tap_offset(int tap) {
-  if (tap >= SK * SK) return -1;
-  const int r = tap / SK, t = tap % SK;
-  return r * Geo<POOL>::ROWB + (t & 1) * Geo<POOL>::HALF * 8 + (t >> 1) * 8;
-}
+// Byte offset of filter tap `tap` (row-major) from an output pixel's window origin in the LDS patch.
+template <int SK, int SS, bool POOL>
+__device__ __forceinline__ constexpr int tap_offset(int tap) { return Geo<SK, SS, POOL>::at(tap / SK, tap % SK); }
 
-// One descriptor per problem.  Convolution fields as for any convolution (H, W, Cp = 4, k = kw = 7, stride 2, pad,
-// pad_w, act, w_off, b_off, Kp = 224); gin x gout is the convolution's output (height x width); Ho x Wo is what is
+// One descriptor per problem.  Convolution fields as for any convolution (H, W, Cp = 4, k = kw = SK, stride SS, pad,
+// pad_w, act, w_off, b_off, Kp = 224 or 64); gin x gout is the convolution's output (height x width); Ho x Wo is what is
 // stored at y_off: the same without the pool, the pooled size with it (3x3 windows, stride 2, padding pre_act = 0 or 1,
 // every window starting inside the convolution's output: floor or ceil mode); tiles_n = workgroups that share the problem.
 // CLAMP6: the launch holds a ReLU6 (otherwise the upper clamp is not applied at all).
-template <bool POOL, bool CLAMP6>
+template <int SK, int SS, bool POOL, bool CLAMP6>
 __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
-  using G = Geo<POOL>;
+  using G = Geo<SK, SS, POOL>;
+  constexpr int KSTEPS = G::KSTEPS, KREG = G::KREG, STEM_KP = G::KP, LAST_TAP = G::LAST_TAP;
   __shared__ __attribute__((aligned(16))) uint8_t smem[G::LDS_BYTES];
   int p, bid;
   if (!find_problem_at(a, (int)blockIdx.x, p, bid)) return;
@@ -124,17 +127,16 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
     const int pr = i / G::PW, pc = i - pr * G::PW;
     const bool in_patch = i < G::NPATCH;
     slot_rel[j] = (pr * d.W + pc) * 8;
-    slot_at[j] = in_patch ? ((pr * G::ROWB + (pc & 1) * G::HALF * 8 + (pc >> 1) * 8) << 8) | pc : (G::ZERO_AT << 8) | 255;
+    slot_at[j] = in_patch ? (G::at(pr, pc) << 8) | pc : (G::ZERO_AT << 8) | 255;
   }
   // Window origins in the LDS patch of the two 32-pixel blocks this wave multiplies.  Lanes 32-63 read the tap two
-  // places after the one lanes 0-31 read; seen from a tap at column t of the filter that is 8 bytes on (t <= 4), or
-  // wraps to the next filter row (t = 5 and t = 6: two other distances).  One base per case with the lane half's
+  // places after the one lanes 0-31 read; seen from a tap at column t of the filter that is a fixed distance on in the
+  // same filter row (t <= SK - 3), or wraps to the next row (t = SK - 2 and t = SK - 1: two other distances).  One base per case with the lane half's
   // distance already in it leaves every read as base + a constant the instruction carries.  The fourth base sends
   // lanes 32-63 to the zero slot: the last step's upper half lies past the filter.
   // Which pixels: 16 neighbouring lanes take 16 neighbouring pixels of one row of the block (their reads are 128
   // contiguous bytes of a plane: every bank once).  Without the pool that is all 16 x 16 pixels; with it, rows of 17:
   // fifteen half-groups take columns 0-15 of the fifteen rows, the sixteenth takes column 16 of all of them.
-  constexpr int LAST_TAP = SK * SK - 1;
   int win[2][4], out_at[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
@@ -147,10 +149,10 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
     }
     out_at[i] = (real ? cy * G::CW + cx : 255) * (OS / 8); // the pixel's row in the LDS output tile, in 16-byte pieces (row 255: nobody reads it)
     const int w0 = (SS * cy) * G::ROWB + cx * 8;   // (stride 2: output column cx starts at patch column 2 cx, element cx of the even plane)
-    win[i][0] = w0 + (upper ? tap_offset<POOL>(2) - tap_offset<POOL>(0) : 0);
-    win[i][1] = w0 + (upper ? tap_offset<POOL>(7) - tap_offset<POOL>(5) : 0);
-    win[i][2] = w0 + (upper ? tap_offset<POOL>(8) - tap_offset<POOL>(6) : 0);
-    win[i][3] = upper ? G::ZERO_AT - tap_offset<POOL>(LAST_TAP) : w0;
+    win[i][0] = w0 + (upper ? tap_offset<SK, SS, POOL>(2) - tap_offset<SK, SS, POOL>(0) : 0);
+    win[i][1] = w0 + (upper ? tap_offset<SK, SS, POOL>(SK) - tap_offset<SK, SS, POOL>(SK - 2) : 0);
+    win[i][2] = w0 + (upper ? tap_offset<SK, SS, POOL>(SK + 1) - tap_offset<SK, SS, POOL>(SK - 1) : 0);
+    win[i][3] = upper ? G::ZERO_AT - tap_offset<SK, SS, POOL>(LAST_TAP) : w0;
   }
   // identity / ReLU / ReLU6 as max and min against bounds that are NaN where there is none (max / min return the other
   // operand): the general kernel's two instructions, with the min left out where no problem of the launch has a ReLU6
@@ -229,8 +231,8 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
         v[2 * h] = v[2 * h + 1] = 0u;                                                             \
       } else {                                                                                    \
         const int col = tap % SK;                                                                 \
-        const int base = tap + 2 > LAST_TAP ? 3 : col <= 4 ? 0 : col == 5 ? 1 : 2;                \
-        const u32x2 half = *reinterpret_cast<const u32x2*>(smem + win[i][base] + tap_offset<POOL>(tap)); \
+        const int base = tap + 2 > LAST_TAP ? 3 : col <= SK - 3 ? 0 : col == SK - 2 ? 1 : 2;      \
+        const u32x2 half = *reinterpret_cast<const u32x2*>(smem + win[i][base] + tap_offset<SK, SS, POOL>(tap)); \
         v[2 * h] = half[0];                                                                       \
         v[2 * h + 1] = half[1];                                                                   \
       }                                                                                           \
@@ -361,9 +363,19 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
 
 }  // namespace
 
-// Workgroups of one problem of a stem launch: every block of output pixels at most once, `share` at most.
+// A stem launch's tile field: bit 0 = the pool is part of the launch, bits 1.. = the convolution's geometry.
+//   geometry 0: 7x7 stride 2, 1: 3x3 stride 1, 2: 3x3 stride 2
+int stem_geometry(int k, int kw, int stride) {
+  if (k != kw) return -1;
+  if (k == 7 && stride == 2) return 0;
+  if (k == 3 && stride == 1) return 1;
+  if (k == 3 && stride == 2) return 2;
+  return -1;
+}
+
+// Workgroups of one problem of a stem launch: every block of output pixels at most once, Desc.tiles_n at most.
 int stem_blocks(int tile, const Desc& d, int batch) {
-  const bool pool = tile == 1;
+  const bool pool = (tile & 1) != 0;
   const int ty = pool ? (d.Ho + 6) / 7 : (d.gin + 15) / 16;
   const int tx = pool ? (d.Wo + 7) / 8 : (d.gout + 15) / 16;
   const int64_t tiles = (int64_t)batch * ty * tx;
@@ -371,7 +383,11 @@ int stem_blocks(int tile, const Desc& d, int batch) {
 }
 
 int launch_stem(const Launch& L, const KArgs& args, void* stream, const std::vector<Desc>& hd) {
-  if (L.wdtype != FI_BF16 || L.adtype != FI_BF16 || (L.tile != 0 && L.tile != 1) || L.n < 1 || L.n > FI_MAX_GROUP) return (int)hipErrorInvalidValue;
+  const bool pool = (L.tile & 1) != 0;
+  const int geom = L.tile >> 1;
+  if (L.wdtype != FI_BF16 || L.adtype != FI_BF16 || L.tile < 0 || geom > 2 || (pool && geom == 1) || L.n < 1 || L.n > FI_MAX_GROUP) return (int)hipErrorInvalidValue;
+  const int sk = geom == 0 ? 7 : 3, ss = geom == 1 ? 1 : 2;
+  const int kp = (sk * sk * 4 + 31) / 32 * 32;
   KArgs a = args;
   int64_t blocks = 0;
   for (int i = 0; i < FI_MAX_GROUP + 1; ++i) {
@@ -380,12 +396,13 @@ int launch_stem(const Launch& L, const KArgs& args, void* stream, const std::vec
     const Desc& t = hd[(size_t)(L.first_desc + i)];
     a.d[i] = t;
     // what the kernel takes for granted
-    if (t.k != SK || t.kw != SK || t.stride != SS || t.Cp != 4 || t.Kp != STEM_KP || t.Co != CO || t.Cop != CO || t.ys < CO || t.ys % 8 || t.xs != 4 ||
+    if (t.k != sk || t.kw != sk || t.stride != ss || t.Cp != 4 || t.Kp != kp || t.Co != CO || t.Cop != CO || t.ys < CO || t.ys % 8 || t.xs != 4 ||
         t.act < 0 || t.act > FI_ACT_RELU6 || t.ext || t.out_f32 || t.splits != 1 || t.r_off != kNone || t.tiles_n < 1 ||
-        t.pad < 0 || t.pad > 3 || t.pad_w < 0 || t.pad_w > 3 || t.x_off == kNone || t.y_off == kNone || t.w_off == kNone || t.b_off == kNone)
+        t.pad < 0 || t.pad > sk / 2 || t.pad_w < 0 || t.pad_w > sk / 2 || t.x_off == kNone || t.y_off == kNone || t.w_off == kNone || t.b_off == kNone)
       return (int)hipErrorInvalidValue;
-    if (t.gin != (t.H + 2 * t.pad - SK) / SS + 1 || t.gout != (t.W + 2 * t.pad_w - SK) / SS + 1 || t.gin < 1 || t.gout < 1) return (int)hipErrorInvalidValue;
-    if (L.tile == 1) {   // every pooling window starts inside the convolution's output
+    if (t.H + 2 * t.pad < sk || t.W + 2 * t.pad_w < sk) return (int)hipErrorInvalidValue;
+    if (t.gin != (t.H + 2 * t.pad - sk) / ss + 1 || t.gout != (t.W + 2 * t.pad_w - sk) / ss + 1 || t.gin < 1 || t.gout < 1) return (int)hipErrorInvalidValue;
+    if (pool) {   // every pooling window starts inside the convolution's output
       if (t.pre_act < 0 || t.pre_act > 1 || t.Ho < 1 || t.Wo < 1 || (t.Ho - 1) * 2 - t.pre_act >= t.gin || (t.Wo - 1) * 2 - t.pre_act >= t.gout)
         return (int)hipErrorInvalidValue;
     } else if (t.Ho != t.gin || t.Wo != t.gout) return (int)hipErrorInvalidValue;
@@ -399,13 +416,17 @@ int launch_stem(const Launch& L, const KArgs& args, void* stream, const std::vec
   bool clamp6 = false;
   for (int i = 0; i < L.n; ++i) clamp6 = clamp6 || hd[(size_t)(L.first_desc + i)].act == FI_ACT_RELU6;
   const dim3 grid((unsigned)blocks), wg(256);
-  if (L.tile == 1) {
-    if (clamp6) hipLaunchKernelGGL((stem_kernel<true, true>), grid, wg, 0, s, a);
-    else hipLaunchKernelGGL((stem_kernel<true, false>), grid, wg, 0, s, a);
-  } else {
-    if (clamp6) hipLaunchKernelGGL((stem_kernel<false, true>), grid, wg, 0, s, a);
-    else hipLaunchKernelGGL((stem_kernel<false, false>), grid, wg, 0, s, a);
+#define FI_STEM_GO(SK_, SS_, POOL_)                                                               \
+  {                                                                                               \
+    if (clamp6) hipLaunchKernelGGL((stem_kernel<SK_, SS_, POOL_, true>), grid, wg, 0, s, a);      \
+    else hipLaunchKernelGGL((stem_kernel<SK_, SS_, POOL_, false>), grid, wg, 0, s, a);            \
   }
+  if (geom == 0 && pool) FI_STEM_GO(7, 2, true)
+  else if (geom == 0) FI_STEM_GO(7, 2, false)
+  else if (geom == 1) FI_STEM_GO(3, 1, false)
+  else if (pool) FI_STEM_GO(3, 2, true)
+  else FI_STEM_GO(3, 2, false)
+#undef FI_STEM_GO
   return (int)hipGetLastError();
 }
 

@@ -1,6 +1,6 @@
-"""The stem launch: a 7x7 stride-2 convolution over the model input computed from an input patch held on chip, with
-the 3x3 stride-2 max-pool that alone reads it in the same launch (Section V, Table III: the first two layers of the
-ResNet-style families).  It must equal, bit for bit, the general convolution kernel followed by a pooling launch
+"""The stem launch: a 7x7 stride-2 (3x3 stride-1, 3x3 stride-2) convolution over the model input computed from an input
+patch held on chip, a stride-2 one with the 3x3 stride-2 max-pool that alone reads it in the same launch (Section V,
+Table III: the first layers of the ResNet-style families, of VGG, of SqueezeNet 1.1).  It must equal, bit for bit, the general convolution kernel followed by a pooling launch
 (Section III-A, C1: the output of each model remains the same), and meet the oracle like them."""
 import numpy as np
 import pytest
@@ -10,11 +10,11 @@ from workloads import gen, zoo
 pytestmark = pytest.mark.gpu
 
 
-def stem_model(h, w, pad=3, pool="3x3/2", act=zoo.RELU, cout_tail=16):
+def stem_model(h, w, pad=3, pool="3x3/2", act=zoo.RELU, cout_tail=16, k=7, stride=2):
     """conv 7x7/2 -> [max-pool] -> 1x1 convolution whose fp32 output is the member's output: every pixel of the stem's
     tensor reaches the caller."""
-    m = zoo.Model(f"stem{h}x{w}p{pad}{pool}", "bf16", 3, h, w)
-    a = m.add(zoo.CONV, zoo.MODEL_INPUT, cin=3, cout=64, k=7, stride=2, pad=pad, act=act)
+    m = zoo.Model(f"stem{k}s{stride}_{h}x{w}p{pad}{pool}", "bf16", 3, h, w)
+    a = m.add(zoo.CONV, zoo.MODEL_INPUT, cin=3, cout=64, k=k, stride=stride, pad=pad, act=act)
     if pool == "3x3/2":
         a = m.add(zoo.MAXPOOL, a, k=3, stride=2, pad=1)
     elif pool == "ceil":
@@ -73,21 +73,51 @@ def test_stem_launch_equals_general_kernels_bitwise_and_meets_the_oracle(h, w, p
     harness.check_against_oracle(f"stem {h}x{w} {pool}", mem[1][0], mem[1][1], None, x, fast[1])
 
 
-@pytest.mark.parametrize("seed", range(16))
+SMALL_FILTER_CASES = [
+    # k, stride, h, w, pad, pool, act, batch
+    (3, 1, 224, 224, 1, None, zoo.RELU, 2),     # VGG's first layer
+    (3, 1, 37, 53, 1, None, zoo.NONE, 3),       # ragged blocks
+    (3, 1, 16, 16, 0, None, zoo.RELU6, 5),      # no padding, 14 x 14 outputs: less than a block
+    (3, 1, 50, 21, 1, "2x2/2", zoo.RELU, 2),    # a pool behind a stride-1 layer keeps its launch
+    (3, 2, 224, 224, 0, "ceil", zoo.RELU, 2),   # SqueezeNet 1.1's first two layers
+    (3, 2, 95, 64, 1, "3x3/2", zoo.RELU, 3),
+    (3, 2, 61, 77, 0, None, zoo.NONE, 4),
+    (3, 2, 33, 20, 1, "ceil", zoo.RELU6, 6),
+]
+
+
+@pytest.mark.parametrize("k,stride,h,w,pad,pool,act,batch", SMALL_FILTER_CASES)
+def test_small_filter_stems_equal_general_kernels_bitwise_and_meet_the_oracle(k, stride, h, w, pad, pool, act, batch):
+    from tests import harness
+    print(f"stem case {k}x{k}/{stride} {h}x{w} pad {pad} pool {pool} act {act} batch {batch}", flush=True)
+    models = [stem_model(h, w, pad, pool, act, k=k, stride=stride) for _ in range(3)]
+    mem = [(m, gen.make_blob(m, 5800 + i), None) for i, m in enumerate(models)]
+    x = gen.make_input(59 + h, batch, 3, h, w, "normal", "bf16")
+    fast, names = _run(mem, x)
+    plain, pnames = _run(mem, x, separate_stem=True)
+    fused = stride == 2 and pool in ("3x3/2", "ceil")
+    assert ("conv_stem_pool" if fused else "conv_stem") in names and not any(n.startswith("conv_stem") for n in pnames), (names, pnames)
+    assert ("maxpool" in names) == (pool is not None and not fused)
+    for i, (a, b) in enumerate(zip(fast, plain)):
+        assert np.isfinite(a).all()
+        assert np.array_equal(a, b), f"member {i}: the stem launch differs from the general kernels"
+    harness.check_against_oracle(f"stem {k}x{k}/{stride} {h}x{w} {pool}", mem[1][0], mem[1][1], None, x, fast[1])
+
+
+@pytest.mark.parametrize("seed", range(24))
 def test_random_stems_equal_general_kernels(seed):
     """Seeded random image sizes (1 to 5 blocks a side, every remainder), paddings, pools, activations and batches."""
     rng = np.random.default_rng(9000 + seed)
+    k, stride = [(7, 2), (3, 1), (3, 2)][seed % 3]
     h, w = int(rng.integers(7, 150)), int(rng.integers(7, 150))
-    pad = int(rng.integers(0, 4))
+    pad = int(rng.integers(0, k // 2 + 1))
     pool = [None, "3x3/2", "ceil", "3x3/2"][int(rng.integers(0, 4))]
     act = [zoo.NONE, zoo.RELU, zoo.RELU6][int(rng.integers(0, 3))]
     batch = int(rng.integers(1, 6))
-    if pool is not None and (h + 2 * pad - 7) // 2 + 1 < 3:
+    if pool is not None and min((h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1) < 3:
         pool = None   # (a pooling window larger than the tensor)
-    if pool is not None and (w + 2 * pad - 7) // 2 + 1 < 3:
-        pool = None
-    print(f"random stem {seed}: {h}x{w} pad {pad} pool {pool} act {act} batch {batch}", flush=True)
-    models = [stem_model(h, w, pad, pool, act) for _ in range(2)]
+    print(f"random stem {seed}: {k}x{k}/{stride} {h}x{w} pad {pad} pool {pool} act {act} batch {batch}", flush=True)
+    models = [stem_model(h, w, pad, pool, act, k=k, stride=stride) for _ in range(2)]
     mem = [(m, gen.make_blob(m, 5600 + 2 * seed + i), None) for i, m in enumerate(models)]
     x = gen.make_input(5700 + seed, batch, 3, h, w, "normal", "bf16")
     fast, names = _run(mem, x)

@@ -666,7 +666,8 @@ def test_stem_launch_takes_the_pool_and_drops_the_first_tensor():
         assert conv.launch == pool.launch and names[pool.launch] == "conv_stem_pool"
         assert pool.out_bytes == pnodes[members[mi].first_node + 1].out_bytes
     vgg_first = nodes[members[2].first_node]
-    assert names[vgg_first.launch].startswith("conv_mfma")   # a 3x3 first layer keeps the general kernel
+    assert names[vgg_first.launch] == "conv_stem" and vgg_first.out_bytes > 0   # a 3x3 stride-1 first layer: the stem kernel, no pool to take
+    assert pnames[pnodes[members[2].first_node].launch].startswith("conv_mfma")
     for L in d.launches():
         if L.name.decode() != "conv_stem_pool":
             continue
