@@ -327,14 +327,14 @@ def main():
 # 1 GiB device-to-device copy).  The figures belong to one exact set of sources: when any of them
 # has changed since the counters were taken the entry no longer applies and traffic is null.
 COUNTERS = {
-    "sources_sha256": "6909587e3a3a659012de585673869bd0d834144e91d382c1f871289343301062",
+    "sources_sha256": "9b606115b84689c62433e6363bdfe3f1430ba51e1bd7c0343ffe29c13a4932da",
     "workload": "cfg4",
     "fetch_scale": 2.0, "write_scale": 1.0,
     "kernels": {   # kernel name -> launches and KiB per step
-        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454769.8, "write_kib_per_step": 2579440.7},
-        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1097954.9, "write_kib_per_step": 1618213.3},
-        "conv_mfma_128x64": {"launches_per_step": 4, "fetch_kib_per_step": 50695.4, "write_kib_per_step": 100352.0},
-        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613784.0, "write_kib_per_step": 376320.0},
+        "conv_chain": {"launches_per_step": 20, "fetch_kib_per_step": 1454594.1, "write_kib_per_step": 2579447.5},
+        "conv_mfma_128x128": {"launches_per_step": 38, "fetch_kib_per_step": 1098184.7, "write_kib_per_step": 1618214.0},
+        "conv_mfma_128x64": {"launches_per_step": 4, "fetch_kib_per_step": 50694.5, "write_kib_per_step": 100352.0},
+        "conv_mfma_256x128": {"launches_per_step": 24, "fetch_kib_per_step": 613750.8, "write_kib_per_step": 376320.0},
     },
 }
 

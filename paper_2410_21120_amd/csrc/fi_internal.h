@@ -186,7 +186,15 @@ int launch_chain(const Launch& L, const KArgs& a, void* stream, const std::vecto
 // Implemented in fi_stem.hip: a K_STEM launch, and the workgroups one of its problems takes.  Returns a hipError_t as int.
 int launch_stem(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);
 int stem_blocks(int tile, const Desc& d, int batch);
-int stem_geometry(int k, int kw, int stride);   // the geometry bits of a stem launch's tile field (tile = 2 * geometry + pool), -1 = none
+// A stem launch's tile field: bit 0 = the pool is part of the launch, bits 1.. = the convolution's geometry
+// (0: 7x7 stride 2, 1: 3x3 stride 1, 2: 3x3 stride 2; -1: none of them).
+inline int stem_geometry(int k, int kw, int stride) {
+  if (k != kw) return -1;
+  if (k == 7 && stride == 2) return 0;
+  if (k == 3 && stride == 1) return 1;
+  if (k == 3 && stride == 2) return 2;
+  return -1;
+}
 
 // Implemented in fi_kernels.hip.  Returns a hipError_t as int; `stream` is a hipStream_t.
 int launch_kernel(const Launch& L, const KArgs& a, void* stream, const std::vector<Desc>& host_descs);

@@ -363,16 +363,6 @@ __global__ void __launch_bounds__(256, 2) stem_kernel(KArgs a) {
 
 }  // namespace
 
-// A stem launch's tile field: bit 0 = the pool is part of the launch, bits 1.. = the convolution's geometry.
-//   geometry 0: 7x7 stride 2, 1: 3x3 stride 1, 2: 3x3 stride 2
-int stem_geometry(int k, int kw, int stride) {
-  if (k != kw) return -1;
-  if (k == 7 && stride == 2) return 0;
-  if (k == 3 && stride == 1) return 1;
-  if (k == 3 && stride == 2) return 2;
-  return -1;
-}
-
 // Workgroups of one problem of a stem launch: every block of output pixels at most once, Desc.tiles_n at most.
 int stem_blocks(int tile, const Desc& d, int batch) {
   const bool pool = (tile & 1) != 0;
